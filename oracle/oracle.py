@@ -1,0 +1,204 @@
+"""ctypes wrapper around the plain-C CPU oracle (oracle/a2ats_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg.  Nothing under the product package imports it,
+and it imports nothing from the product package.
+
+All wrappers take torch CPU tensors (or anything np.asarray accepts), widen
+float inputs to float32 exactly (bf16 -> f32 is exact) and return numpy arrays
+in float64 / int32 / uint8.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "a2ats_oracle.c")
+_LIB = os.path.join(_HERE, "liba2ats_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no fast-math) into oracle/liba2ats_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+               "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB)
+    return _lib
+
+
+def threads() -> int:
+    return int(_load().a2ats_oracle_threads())
+
+
+def _f32(x) -> np.ndarray:
+    if hasattr(x, "detach"):
+        import torch
+        x = x.detach().to("cpu").to(torch.float32).numpy()
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+def _f64(x) -> np.ndarray:
+    if hasattr(x, "detach"):
+        import torch
+        x = x.detach().to("cpu").to(torch.float64).numpy()
+    return np.ascontiguousarray(x, dtype=np.float64)
+
+
+def _u8(x) -> np.ndarray:
+    if hasattr(x, "detach"):
+        x = x.detach().to("cpu").numpy()
+    return np.ascontiguousarray(x, dtype=np.uint8)
+
+
+def _i32(x) -> Optional[np.ndarray]:
+    if x is None:
+        return None
+    if hasattr(x, "detach"):
+        x = x.detach().to("cpu").numpy()
+    return np.ascontiguousarray(x, dtype=np.int32)
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+_I = ctypes.c_int
+_L = ctypes.c_int64
+_D = ctypes.c_double
+
+
+def rope(x, inv_freq, pos: float) -> np.ndarray:
+    """x R_pos for every row of x [..., D] (section 2.1)."""
+    x = _f32(x)
+    D = x.shape[-1]
+    out = np.empty(x.shape, dtype=np.float64)
+    inv = _f64(inv_freq)
+    _load().a2ats_oracle_rope(_p(x), _L(x.size // D), _I(D), _p(inv), _D(float(pos)), _p(out))
+    return out
+
+
+def lut(q_rot, codebook, n_q_heads: int) -> np.ndarray:
+    """[B,Hq,M,L] float64 table of q~ . centroid per subspace."""
+    q_rot = _f64(q_rot)
+    cb = _f32(codebook)
+    B, Hq, D = q_rot.shape
+    Hkv, M, L, ds = cb.shape
+    assert Hq == n_q_heads and M * ds == D
+    out = np.empty((B, Hq, M, L), dtype=np.float64)
+    _load().a2ats_oracle_lut(_p(q_rot), _p(cb), _I(B), _I(Hq), _I(Hkv), _I(M), _I(L), _I(ds), _p(out))
+    return out
+
+
+def scores_explicit(q_rot, codebook, codes, n_ctx: int) -> np.ndarray:
+    """[B,Hq,N] approximate scores q~ . k^_j by explicit reconstruction."""
+    q_rot = _f64(q_rot)
+    cb = _f32(codebook)
+    codes = _u8(codes)
+    B, Hq, D = q_rot.shape
+    Hkv, M, L, ds = cb.shape
+    S = codes.shape[2]
+    assert codes.shape == (B, Hkv, S, M) and n_ctx <= S
+    out = np.empty((B, Hq, n_ctx), dtype=np.float64)
+    _load().a2ats_oracle_scores_explicit(_p(q_rot), _p(cb), _p(codes), _I(B), _I(Hq), _I(Hkv), _I(M),
+                                         _I(L), _I(ds), _L(n_ctx), _L(S), _p(out))
+    return out
+
+
+def scores_lut(lut_, codes, n_kv_heads: int, n_ctx: int) -> np.ndarray:
+    lut_ = _f64(lut_)
+    codes = _u8(codes)
+    B, Hq, M, L = lut_.shape
+    S = codes.shape[2]
+    out = np.empty((B, Hq, n_ctx), dtype=np.float64)
+    _load().a2ats_oracle_scores_lut(_p(lut_), _p(codes), _I(B), _I(Hq), _I(n_kv_heads), _I(M), _I(L),
+                                    _L(n_ctx), _L(S), _p(out))
+    return out
+
+
+def topk(scores, top_k: int, window: int, n_sink: int = 0, seq_lens=None
+         ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Full-sort top-K: (idx [B,Hq,K] ascending / -1 padded, count [B,Hq], kth score [B,Hq])."""
+    scores = _f64(scores)
+    B, Hq, N = scores.shape
+    sl = _i32(seq_lens)
+    idx = np.empty((B, Hq, max(top_k, 0)), dtype=np.int32)
+    cnt = np.empty((B, Hq), dtype=np.int32)
+    kth = np.empty((B, Hq), dtype=np.float64)
+    _load().a2ats_oracle_topk(_p(scores), _I(B), _I(Hq), _L(N), _I(top_k), _I(window), _I(n_sink),
+                              _p(sl), _p(idx), _p(cnt), _p(kth))
+    return idx, cnt, kth
+
+
+def sparse_attn(q, k, v, topk_idx, topk_count, n_ctx: int, window: int, n_sink: int, inv_freq,
+                b_off: float, seq_lens=None) -> np.ndarray:
+    """[B,Hq,D] float64 selective attention over sinks U top-K U window under WRoPE."""
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    idx, cnt = _i32(topk_idx), _i32(topk_count)
+    B, Hq, D = q.shape
+    _, Hkv, S, _ = k.shape
+    K = idx.shape[2]
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    rc = _load().a2ats_oracle_sparse_attn(_p(q), _p(k), _p(v), _p(idx), _p(cnt), _I(B), _I(Hq), _I(Hkv),
+                                          _I(D), _L(n_ctx), _L(S), _I(K), _I(window), _I(n_sink),
+                                          _p(_f64(inv_freq)), _D(float(b_off)), _p(_i32(seq_lens)), _p(out))
+    if rc != 0:
+        raise ValueError("top-K index outside the candidate range")
+    return out
+
+
+def dense_wrope_attn(q, k, v, n_ctx: int, window: int, inv_freq, b_off: float, seq_lens=None
+                     ) -> np.ndarray:
+    q, k, v = _f32(q), _f32(k), _f32(v)
+    B, Hq, D = q.shape
+    _, Hkv, S, _ = k.shape
+    out = np.empty((B, Hq, D), dtype=np.float64)
+    _load().a2ats_oracle_dense_wrope_attn(_p(q), _p(k), _p(v), _I(B), _I(Hq), _I(Hkv), _I(D), _L(n_ctx),
+                                          _L(S), _I(window), _p(_f64(inv_freq)), _D(float(b_off)),
+                                          _p(_i32(seq_lens)), _p(out))
+    return out
+
+
+W_NONE, W_DIAG, W_BLOCK = 0, 1, 2
+
+
+def encode(keys, codebook, weights=None, mode: int = W_NONE, want_margins: bool = False):
+    """codes [B,Hkv,n,M] uint8 (and, if asked, the best / second-best distortions)."""
+    keys, cb = _f32(keys), _f32(codebook)
+    B, Hkv, n, D = keys.shape
+    _, M, L, ds = cb.shape
+    w = None if weights is None else _f32(weights)
+    assert mode == W_NONE or w is not None
+    codes = np.empty((B, Hkv, n, M), dtype=np.uint8)
+    best = np.empty((B, Hkv, n, M), dtype=np.float64) if want_margins else None
+    second = np.empty((B, Hkv, n, M), dtype=np.float64) if want_margins else None
+    _load().a2ats_oracle_encode(_p(keys), _p(cb), _p(w), _I(mode), _I(B), _I(Hkv), _L(n), _I(M), _I(L),
+                                _I(ds), _p(codes), _p(best), _p(second))
+    if want_margins:
+        return codes, best, second
+    return codes
+
+
+def encode_cholesky(keys, codebook, h_block) -> np.ndarray:
+    keys, cb, w = _f32(keys), _f32(codebook), _f32(h_block)
+    B, Hkv, n, D = keys.shape
+    _, M, L, ds = cb.shape
+    codes = np.empty((B, Hkv, n, M), dtype=np.uint8)
+    rc = _load().a2ats_oracle_encode_cholesky(_p(keys), _p(cb), _p(w), _I(B), _I(Hkv), _L(n), _I(M),
+                                              _I(L), _I(ds), _p(codes))
+    if rc != 0:
+        raise ValueError("weight block is not positive definite")
+    return codes

@@ -1,0 +1,392 @@
+"""Pins for the CPU oracle: every routine is checked against something other than itself --
+hand-derived fixtures, closed forms, algebraic identities of the paper, special cases that
+reduce to a numpy / torch library routine, and brute force on tiny inputs.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_12665_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                out.append([float(t) for t in line.split()])
+    return out
+
+
+def rope_matrix(D, inv_freq, pos):
+    """R_pos as an explicit D x D matrix for the row-vector convention x -> x R."""
+    h = D // 2
+    R = np.zeros((D, D))
+    for t in range(h):
+        a = pos * inv_freq[t]
+        R[t, t] = math.cos(a)
+        R[t + h, t] = -math.sin(a)
+        R[t, t + h] = math.sin(a)
+        R[t + h, t + h] = math.cos(a)
+    return R
+
+
+def rotate_half_rope(x, inv_freq, pos):
+    """The x*cos + rotate_half(x)*sin formulation used by the model families' reference code."""
+    D = x.shape[-1]
+    ang = pos * np.concatenate([inv_freq, inv_freq])
+    x1, x2 = x[..., :D // 2], x[..., D // 2:]
+    rot = np.concatenate([-x2, x1], axis=-1)
+    return x * np.cos(ang) + rot * np.sin(ang)
+
+
+# ------------------------------------------------------------------ O1 rotation
+def test_rope_golden_quarter_turn(oracle):
+    inv = np.array([math.pi / 2, math.pi])
+    for row in _rows("rope_quarter_turn.txt"):
+        x, want = np.array(row[:4], dtype=np.float32), np.array(row[4:])
+        got = oracle.rope(x[None], inv, 1.0)[0]
+        np.testing.assert_allclose(got, want, atol=1e-12)
+
+
+def test_rope_matches_rotate_half_and_matrix(oracle):
+    rng = np.random.default_rng(1)
+    D = 128
+    inv = synth.inv_freq(D, 500000.0).numpy()
+    x = rng.standard_normal((5, D)).astype(np.float32)
+    for pos in (0.0, 1.0, 63.0, 2048.0):
+        got = oracle.rope(x, inv, pos)
+        np.testing.assert_allclose(got, rotate_half_rope(x.astype(np.float64), inv, pos), atol=1e-12)
+        np.testing.assert_allclose(got, x.astype(np.float64) @ rope_matrix(D, inv, pos), atol=1e-12)
+    np.testing.assert_array_equal(oracle.rope(x, inv, 0.0), x.astype(np.float64))
+
+
+def test_rope_relative_position_identity(oracle):
+    """R_i R_j^T = R_{i-j} (section 2.1): rope(q,b).k == rope(q,p).rope(k,p-b) for any p."""
+    rng = np.random.default_rng(2)
+    D, b = 128, 2048
+    inv = synth.inv_freq(D, 10000.0).numpy()
+    q = rng.standard_normal((3, D)).astype(np.float32)
+    k = rng.standard_normal((3, D)).astype(np.float32)
+    ref = np.sum(oracle.rope(q, inv, b) * k.astype(np.float64), axis=-1)
+    for p in (b, b + 1, 5000, 131071):
+        alt = np.sum(oracle.rope(q, inv, p) * oracle.rope(k, inv, p - b), axis=-1)
+        np.testing.assert_allclose(alt, ref, rtol=0, atol=1e-10)
+    Ri, Rj = rope_matrix(D, inv, 77), rope_matrix(D, inv, 30)
+    np.testing.assert_allclose(Ri @ Rj.T, rope_matrix(D, inv, 47), atol=1e-12)
+    # norm preserving, and composition rope(rope(x,a),c) == rope(x,a+c)
+    np.testing.assert_allclose(np.linalg.norm(oracle.rope(q, inv, b), axis=-1),
+                               np.linalg.norm(q.astype(np.float64), axis=-1), rtol=1e-13)
+    once = oracle.rope(q, inv, 700.0)
+    twice = oracle.rope(oracle.rope(q, inv, 300.0).astype(np.float32), inv, 400.0)
+    np.testing.assert_allclose(twice, once, atol=1e-5)   # float32 round trip in between
+
+
+# ------------------------------------------------------------------ O2 scores
+def _small_problem(seed=0, B=2, Hq=4, Hkv=2, M=4, ds=4, N=50):
+    wl = synth.Workload("t", B, Hq, Hkv, M * ds, M, N, 8, 4, kv_dtype="f32", rope_base=10000.0, seed=seed)
+    return wl, synth.make_decode_inputs(wl)
+
+
+def test_scores_lut_equals_explicit_and_numpy(oracle):
+    wl, x = _small_problem()
+    qrot = oracle.rope(x["q"], x["inv_freq"], wl.wrope_b)
+    s_exp = oracle.scores_explicit(qrot, x["codebook"], x["codes"], wl.ctx_len)
+    lut = oracle.lut(qrot, x["codebook"], wl.n_q_heads)
+    s_lut = oracle.scores_lut(lut, x["codes"], wl.n_kv_heads, wl.ctx_len)
+    np.testing.assert_allclose(s_lut, s_exp, rtol=1e-12, atol=1e-12)
+    # library formulation: reconstructed keys (pure gather) times q~, via numpy matmul
+    khat = synth.reconstruct(x["codebook"], x["codes"]).double().numpy()
+    G = wl.group
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            np.testing.assert_allclose(s_exp[b, h], khat[b, h // G] @ qrot[b, h], rtol=1e-12, atol=1e-12)
+    # LUT entries themselves: einsum over the subspace slice
+    cb = x["codebook"].double().numpy()
+    for h in range(wl.n_q_heads):
+        want = np.einsum("mt,mct->mc", qrot[0, h].reshape(wl.n_sub, wl.sub_dim), cb[h // G])
+        np.testing.assert_allclose(lut[0, h], want, rtol=1e-12, atol=1e-12)
+
+
+def test_scores_single_codebook_case(oracle):
+    """M = 1 is the paper's own geometry: u^_j = q~ . c_{s_j} (eq. attention weights approximation)."""
+    wl, x = _small_problem(seed=3, M=1, ds=16, Hq=2, Hkv=2)
+    qrot = oracle.rope(x["q"], x["inv_freq"], wl.wrope_b)
+    s = oracle.scores_explicit(qrot, x["codebook"], x["codes"], wl.ctx_len)
+    cb = x["codebook"].double().numpy()
+    codes = x["codes"].numpy()
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            want = cb[h, 0][codes[b, h, :, 0]] @ qrot[b, h]
+            np.testing.assert_allclose(s[b, h], want, rtol=1e-12, atol=1e-12)
+
+
+def test_scores_exact_when_keys_are_centroids_and_permutation(oracle):
+    wl, x = _small_problem(seed=4)
+    qrot = oracle.rope(x["q"], x["inv_freq"], wl.wrope_b)
+    keys = synth.reconstruct(x["codebook"], x["codes"]).double().numpy()   # keys == centroids
+    s = oracle.scores_explicit(qrot, x["codebook"], x["codes"], wl.ctx_len)
+    # exact WRoPE score of a non-local token: q R_b k^T with an explicit rotation matrix
+    R = rope_matrix(wl.head_dim, x["inv_freq"].numpy(), wl.wrope_b)
+    q = x["q"].double().numpy()
+    for h in range(wl.n_q_heads):
+        np.testing.assert_allclose(s[1, h], keys[1, h // wl.group] @ (q[1, h] @ R), rtol=1e-11, atol=1e-11)
+    perm = torch.randperm(wl.ctx_len, generator=torch.Generator().manual_seed(0))
+    s_p = oracle.scores_explicit(qrot, x["codebook"], x["codes"][:, :, perm].contiguous(), wl.ctx_len)
+    np.testing.assert_array_equal(s_p, s[:, :, perm.numpy()])
+
+
+# ------------------------------------------------------------------ O3 top-K
+def _topk_numpy(s, K, w, n_sink, n=None):
+    n = s.shape[0] if n is None else n
+    win = max(0, n - w)
+    lo = min(n_sink, win)
+    cand = np.arange(lo, win)
+    order = np.lexsort((cand, -s[lo:win]))           # primary: score desc, secondary: index asc
+    return np.sort(cand[order[:min(K, len(cand))]])
+
+
+@pytest.mark.parametrize("N,K,w,n_sink", [(50, 8, 4, 0), (50, 8, 4, 4), (33, 1, 32, 0), (40, 64, 8, 2),
+                                          (16, 4, 16, 0), (10, 3, 32, 4), (257, 7, 64, 4)])
+def test_topk_matches_lexsort(oracle, N, K, w, n_sink):
+    rng = np.random.default_rng(N + K)
+    s = np.round(rng.standard_normal((2, 3, N)) * 4) / 4      # many exact ties
+    idx, cnt, kth = oracle.topk(s, K, w, n_sink)
+    for b in range(2):
+        for h in range(3):
+            want = _topk_numpy(s[b, h], K, w, n_sink)
+            assert cnt[b, h] == len(want)
+            np.testing.assert_array_equal(idx[b, h, :len(want)], want)
+            assert np.all(idx[b, h, len(want):] == -1)
+            if len(want):
+                assert kth[b, h] == np.min(s[b, h][want])
+                # threshold consistency: nothing unselected beats the K-th score; equal ones have higher index
+                lo, win = min(n_sink, max(0, N - w)), max(0, N - w)
+                rest = np.setdiff1d(np.arange(lo, win), want)
+                assert np.all(s[b, h][rest] <= kth[b, h])
+                eq_rest = rest[s[b, h][rest] == kth[b, h]]
+                eq_sel = want[s[b, h][want] == kth[b, h]]
+                if len(eq_rest):
+                    assert eq_rest.min() > eq_sel.max()
+
+
+def test_topk_degenerate_and_shift_invariance(oracle):
+    s = np.zeros((1, 1, 100))
+    idx, cnt, _ = oracle.topk(s, 10, 16, 4)
+    np.testing.assert_array_equal(idx[0, 0], np.arange(4, 14))      # all equal -> lowest indices
+    idx, cnt, _ = oracle.topk(s, 500, 16, 4)
+    assert cnt[0, 0] == 80 and np.array_equal(idx[0, 0, :80], np.arange(4, 84))
+    rng = np.random.default_rng(0)
+    s = rng.standard_normal((1, 2, 300))
+    a, _, _ = oracle.topk(s, 20, 32, 0)
+    b, _, _ = oracle.topk(s + 3.5, 20, 32, 0)
+    np.testing.assert_array_equal(a, b)
+    sl = np.array([120], dtype=np.int32)
+    c, cc, _ = oracle.topk(s, 20, 32, 0, seq_lens=sl)
+    np.testing.assert_array_equal(c[0, 1], _topk_numpy(s[0, 1], 20, 32, 0, n=120))
+
+
+# ------------------------------------------------------------------ O4 attention
+def _attn_problem(seed, N=40, w=8, B=2, Hq=4, Hkv=2, D=16):
+    wl = synth.Workload("t", B, Hq, Hkv, D, 4, N, 8, w, kv_dtype="f32", rope_base=10000.0, seed=seed)
+    return wl, synth.make_decode_inputs(wl)
+
+
+def _dense_wrope_numpy(q, k, v, inv, w, b_off):
+    """eq. WRoPE with explicit rotation matrices, one head."""
+    n, D = k.shape
+    i = n - 1
+    logits = np.empty(n)
+    for j in range(n):
+        R = rope_matrix(D, inv, (i - j) if (i - j) < w else b_off)
+        logits[j] = (q @ R) @ k[j] / math.sqrt(D)
+    p = np.exp(logits - logits.max())
+    p /= p.sum()
+    return p @ v
+
+
+def test_attention_golden_two_tokens(oracle):
+    want = np.array(_rows("wrope_two_token.txt")[0])
+    e = math.exp(-math.sqrt(2.0))
+    np.testing.assert_allclose(want, [e / (1 + e), 1 / (1 + e)], atol=1e-8)
+    q = np.array([[[2.0, 0.0]]], dtype=np.float32)
+    k = np.array([[[[1.0, 0.0], [0.0, 1.0]]]], dtype=np.float32)
+    v = k.copy()
+    idx = np.array([[[0]]], dtype=np.int32)
+    cnt = np.array([[1]], dtype=np.int32)
+    out = oracle.sparse_attn(q, k, v, idx, cnt, 2, 1, 0, np.array([1.0]), math.pi)
+    np.testing.assert_allclose(out[0, 0], want, atol=1e-8)
+    dense = oracle.dense_wrope_attn(q, k, v, 2, 1, np.array([1.0]), math.pi)
+    np.testing.assert_allclose(dense[0, 0], want, atol=1e-8)
+
+
+def test_dense_wrope_matches_matrix_form(oracle):
+    wl, x = _attn_problem(5)
+    inv = x["inv_freq"].numpy()
+    got = oracle.dense_wrope_attn(x["q"], x["k"], x["v"], wl.ctx_len, wl.window, inv, 100.0)
+    q, k, v = (x[n].double().numpy() for n in ("q", "k", "v"))
+    for b in range(wl.batch):
+        for h in range(wl.n_q_heads):
+            want = _dense_wrope_numpy(q[b, h], k[b, h // wl.group], v[b, h // wl.group], inv, wl.window, 100.0)
+            np.testing.assert_allclose(got[b, h], want, rtol=1e-10, atol=1e-12)
+
+
+def test_sparse_with_all_candidates_equals_dense(oracle):
+    """K >= n - w: the attended set is every token, so selective attention is dense WRoPE attention."""
+    for n_sink in (0, 3):
+        wl, x = _attn_problem(6)
+        N, w = wl.ctx_len, wl.window
+        ncand = N - w - n_sink
+        idx = np.tile(np.arange(n_sink, N - w, dtype=np.int32), (wl.batch, wl.n_q_heads, 1))
+        cnt = np.full((wl.batch, wl.n_q_heads), ncand, dtype=np.int32)
+        sp = oracle.sparse_attn(x["q"], x["k"], x["v"], idx, cnt, N, w, n_sink, x["inv_freq"], 2048.0)
+        de = oracle.dense_wrope_attn(x["q"], x["k"], x["v"], N, w, x["inv_freq"], 2048.0)
+        np.testing.assert_allclose(sp, de, rtol=1e-12, atol=1e-13)
+        # order of the retrieved indices does not matter
+        sp2 = oracle.sparse_attn(x["q"], x["k"], x["v"], idx[:, :, ::-1].copy(), cnt, N, w, n_sink,
+                                 x["inv_freq"], 2048.0)
+        np.testing.assert_allclose(sp2, sp, rtol=1e-12, atol=1e-13)
+
+
+def test_full_window_is_standard_rope_sdpa(oracle):
+    """w >= n: WRoPE is standard RoPE (section 4.1) -> library SDPA over rotated q and keys."""
+    wl, x = _attn_problem(7, N=24, w=64)
+    inv = x["inv_freq"].numpy()
+    got = oracle.dense_wrope_attn(x["q"], x["k"], x["v"], wl.ctx_len, wl.window, inv, 2048.0)
+    i = wl.ctx_len - 1
+    q, k, v = (x[n].double() for n in ("q", "k", "v"))
+    qr = torch.from_numpy(rotate_half_rope(q.numpy(), inv, i))[:, :, None, :]             # [B,Hq,1,D]
+    kr = torch.stack([torch.from_numpy(rotate_half_rope(k[:, :, j].numpy(), inv, j)) for j in range(wl.ctx_len)], 2)
+    kr = kr.repeat_interleave(wl.group, dim=1)
+    vv = v.repeat_interleave(wl.group, dim=1)
+    want = torch.nn.functional.scaled_dot_product_attention(qr, kr, vv)[:, :, 0].numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-9, atol=1e-11)
+    # and the selective routine with no candidates at all (n <= w) is the same thing
+    idx = np.full((wl.batch, wl.n_q_heads, 4), -1, dtype=np.int32)
+    cnt = np.zeros((wl.batch, wl.n_q_heads), dtype=np.int32)
+    sp = oracle.sparse_attn(x["q"], x["k"], x["v"], idx, cnt, wl.ctx_len, wl.window, 4, inv, 2048.0)
+    np.testing.assert_allclose(sp, want, rtol=1e-9, atol=1e-11)
+
+
+def test_attention_constant_values_and_subset(oracle):
+    wl, x = _attn_problem(8)
+    v = torch.ones_like(x["v"]) * torch.arange(wl.head_dim, dtype=torch.float32)
+    idx = np.tile(np.array([1, 5, 9, 20], dtype=np.int32), (wl.batch, wl.n_q_heads, 1))
+    cnt = np.full((wl.batch, wl.n_q_heads), 4, dtype=np.int32)
+    out = oracle.sparse_attn(x["q"], x["k"], v, idx, cnt, wl.ctx_len, wl.window, 0, x["inv_freq"], 2048.0)
+    np.testing.assert_allclose(out, np.broadcast_to(np.arange(wl.head_dim), out.shape), rtol=1e-12)
+    # subset semantics: compare with a numpy softmax over exactly {1,5,9,20} U window, one head
+    inv = x["inv_freq"].numpy()
+    q, k, vv = (x[n].double().numpy() for n in ("q", "k", "v"))
+    b, h = 1, 3
+    kv = h // wl.group
+    N, w = wl.ctx_len, wl.window
+    S = [1, 5, 9, 20] + list(range(N - w, N))
+    lg = []
+    for j in S:
+        pos = (N - 1 - j) if (N - 1 - j) < w else 2048.0
+        lg.append(rotate_half_rope(q[b, h], inv, pos) @ k[b, kv, j] / math.sqrt(wl.head_dim))
+    p = np.exp(np.array(lg) - max(lg))
+    p /= p.sum()
+    got = oracle.sparse_attn(x["q"], x["k"], x["v"], idx, cnt, N, w, 0, inv, 2048.0)
+    np.testing.assert_allclose(got[b, h], p @ vv[b, kv][S], rtol=1e-10, atol=1e-12)
+    with pytest.raises(ValueError):      # an index inside the window is not a legal retrieved token
+        bad = idx.copy()
+        bad[0, 0, 0] = N - 1
+        oracle.sparse_attn(x["q"], x["k"], x["v"], bad, cnt, N, w, 0, inv, 2048.0)
+
+
+# ------------------------------------------------------------------ O5 encode
+def _enc_problem(seed, M=4, ds=4, n=64, stress=True):
+    wl = synth.Workload("t", 2, 4, 2, M * ds, M, 128, 8, 4, kv_dtype="f32", seed=seed)
+    keys = synth.make_encode_keys(wl, n, stress=stress)
+    cb = synth.make_codebook(wl)
+    hm = synth.make_query_second_moment(wl)
+    return wl, keys, cb, hm
+
+
+def test_encode_identity_is_nearest_centroid(oracle):
+    wl, keys, cb, _ = _enc_problem(1, M=4, ds=8)
+    codes = oracle.encode(keys, cb)
+    kk = keys.double().reshape(2, 2, -1, wl.n_sub, wl.sub_dim)
+    for kv in range(2):
+        for m in range(wl.n_sub):
+            d = torch.cdist(kk[:, kv, :, m].reshape(-1, wl.sub_dim), cb[kv, m].double())   # library routine
+            want = d.argmin(dim=1).reshape(2, -1).numpy()
+            np.testing.assert_array_equal(codes[:, kv, :, m], want)
+    # keys that are centroids map to themselves
+    wl2 = wl.replace(seed=9)
+    cz = torch.randint(0, 256, (1, 2, 32, wl.n_sub), dtype=torch.int32).to(torch.uint8)
+    rec = synth.reconstruct(cb, cz)
+    hm = synth.make_query_second_moment(wl2)
+    np.testing.assert_array_equal(oracle.encode(rec, cb), cz.numpy())
+    np.testing.assert_array_equal(oracle.encode(rec, cb, hm["h_diag"], oracle.W_DIAG), cz.numpy())
+    np.testing.assert_array_equal(oracle.encode(rec, cb, hm["h_block"], oracle.W_BLOCK), cz.numpy())
+
+
+def test_encode_weighted_forms_agree(oracle):
+    wl, keys, cb, hm = _enc_problem(2)
+    blk, b1, b2 = oracle.encode(keys, cb, hm["h_block"], oracle.W_BLOCK, want_margins=True)
+    # numpy statement of the quadratic form (section 4.2, f')
+    kk = keys.double().numpy().reshape(2, 2, -1, wl.n_sub, wl.sub_dim)
+    cbd = cb.double().numpy()
+    Hb = hm["h_block"].double().numpy()
+    for kv in range(2):
+        for m in range(wl.n_sub):
+            d = kk[:, kv, :, m][:, :, None, :] - cbd[kv, m][None, None]          # [B,n,L,ds]
+            dist = np.einsum("bnlr,rc,bnlc->bnl", d, Hb[kv, m], d)
+            np.testing.assert_array_equal(blk[:, kv, :, m], dist.argmin(-1))
+            np.testing.assert_allclose(b1[:, kv, :, m], dist.min(-1), rtol=1e-12)
+            np.testing.assert_allclose(b2[:, kv, :, m], np.sort(dist, -1)[..., 1], rtol=1e-12)
+    # Cholesky reformulation: f'(k; C) = f(kL; CL)
+    np.testing.assert_array_equal(oracle.encode_cholesky(keys, cb, hm["h_block"]), blk)
+    for kv in range(2):
+        for m in range(wl.n_sub):
+            Lc = np.linalg.cholesky(Hb[kv, m])                                    # library routine
+            z = kk[:, kv, :, m] @ Lc
+            cz = cbd[kv, m] @ Lc
+            d = ((z[:, :, None, :] - cz[None, None]) ** 2).sum(-1)
+            np.testing.assert_array_equal(blk[:, kv, :, m], d.argmin(-1))
+    # a block-diagonal H with only its diagonal kept is the per-dimension form
+    diag_blocks = torch.diag_embed(torch.diagonal(hm["h_block"], dim1=-2, dim2=-1))
+    hd = torch.diagonal(hm["h_block"], dim1=-2, dim2=-1).reshape(2, -1).contiguous()
+    np.testing.assert_array_equal(oracle.encode(keys, cb, diag_blocks, oracle.W_BLOCK),
+                                  oracle.encode(keys, cb, hd, oracle.W_DIAG))
+    np.testing.assert_array_equal(hd.numpy(), hm["h_diag"].numpy())
+    # scaling H leaves the assignment unchanged; H = I in block form is the Euclidean one
+    np.testing.assert_array_equal(oracle.encode(keys, cb, hm["h_block"] * 4.0, oracle.W_BLOCK), blk)
+    eye = torch.eye(wl.sub_dim).expand(2, wl.n_sub, -1, -1).contiguous()
+    np.testing.assert_array_equal(oracle.encode(keys, cb, eye, oracle.W_BLOCK), oracle.encode(keys, cb))
+    assert (blk != oracle.encode(keys, cb)).mean() > 0.02     # the weighting matters on this input
+
+
+def test_query_aware_assignment_lowers_weighted_distortion(oracle):
+    """For a fixed codebook, J' under f' <= J' under f (section 3.2 / 4.2), term by term."""
+    wl, keys, cb, hm = _enc_problem(3)
+    Hb = hm["h_block"].double().numpy()
+    cbd = cb.double().numpy()
+    kk = keys.double().numpy().reshape(2, 2, -1, wl.n_sub, wl.sub_dim)
+
+    def jprime(codes):
+        tot = 0.0
+        for kv in range(2):
+            for m in range(wl.n_sub):
+                d = kk[:, kv, :, m] - cbd[kv, m][codes[:, kv, :, m]]
+                tot += np.einsum("bnr,rc,bnc->", d, Hb[kv, m], d)
+        return tot
+
+    aware = oracle.encode(keys, cb, hm["h_block"], oracle.W_BLOCK)
+    plain = oracle.encode(keys, cb)
+    assert jprime(aware) < jprime(plain)
+    # and it is the expected squared score error for queries with second moment H_m:
+    # E[(q.(k - k^))^2] = (k - k^) H (k - k^)^T, checked by Monte Carlo on one subvector
+    rng = np.random.default_rng(0)
+    Lc = np.linalg.cholesky(Hb[0, 0])
+    qs = rng.standard_normal((200000, wl.sub_dim)) @ Lc.T            # E[q^T q] = H
+    d = kk[0, 0, 0, 0] - cbd[0, 0][aware[0, 0, 0, 0]]
+    np.testing.assert_allclose(np.mean((qs @ d) ** 2), d @ Hb[0, 0] @ d, rtol=0.02)
