@@ -1,0 +1,180 @@
+/*
+ * a2ats.h -- C ABI of the MI355X (gfx950) implementation of the A2ATS decode-time
+ * retrieval path (arXiv 2502.12665): windowed-RoPE query, per-subspace lookup tables,
+ * code gather-sum scoring with exact top-K, selective attention over the retrieved
+ * tokens plus the recent window, and the prefill-side key encoder.
+ *
+ * General contract
+ *   - Every pointer marked [dev] is a device pointer owned by the caller; [host] is a
+ *     host pointer.  The library never allocates, frees or retains memory and never
+ *     synchronises: all work is enqueued on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream).  Scratch memory comes from the caller (`ws`), sized by
+ *     a2ats_workspace_bytes(); its contents are undefined on entry and on return.
+ *   - All arguments are validated on the host before anything is launched; on error
+ *     nothing has been enqueued.  Return value: A2ATS_OK (0) or a negative a2ats_status.
+ *   - Row-major layouts, last index fastest.  Query head h reads KV head h / G,
+ *     G = n_q_heads / n_kv_heads.  Positions are 0-based; a sequence of n tokens has its
+ *     current (query) token at position n - 1 with its key/value/code already cached.
+ *   - seq_lens ([dev], nullable, int32 [B]): tokens per sequence, 0 <= seq_lens[b] <=
+ *     ctx_len; NULL means every sequence has ctx_len tokens.
+ *   - Supported shapes: head_dim == 128, n_centroids == 256, sub_dim in {4, 8}
+ *     (n_sub * sub_dim == head_dim), G <= 8, ctx_len <= 2^20, top_k <= 4096.  Anything
+ *     else returns A2ATS_ERR_UNSUPPORTED.
+ *
+ * Lookup-table format (shared by a2ats_build_lut and a2ats_score_topk)
+ *   The table holds, for every query head and subspace m, the 256 inner products of
+ *   the rotated query slice with the centroids, in 32-bit fixed point:
+ *       lut[b, kv, g4, c, m, r]  (int32, dims [B, Hkv, ceil(G/4), 256, M, 4])
+ *         = round( 2^e * <q_rot[b, h, m*ds : (m+1)*ds], codebook[kv, m, c, :]> ),
+ *       h = kv*G + 4*g4 + r   (entries of heads past G are 0),
+ *       lut_scale[b, h] = 2^-e (float32; the power of two is chosen per head so that a
+ *       sum of M entries cannot overflow).
+ *   A token's approximate score is lut_scale * sum_m lut[.., codes[j, m], m, ..]; integer
+ *   accumulation makes it independent of summation order, so equal code rows score
+ *   exactly equal and ties resolve by token index.
+ */
+#ifndef A2ATS_H_
+#define A2ATS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct a2ats_dims {
+  int32_t batch;        /* B                                        */
+  int32_t n_q_heads;    /* Hq                                       */
+  int32_t n_kv_heads;   /* Hkv, divides Hq                          */
+  int32_t head_dim;     /* D                                        */
+  int32_t n_sub;        /* M   subspaces                            */
+  int32_t sub_dim;      /* ds  (M * ds == D)                        */
+  int32_t n_centroids;  /* L   (256: one uint8 code per subspace)   */
+  int32_t ctx_len;      /* N   tokens in the cache incl. the current one */
+  int64_t ctx_stride;   /* token-axis capacity of codes / k / v, >= N    */
+} a2ats_dims;
+
+typedef enum a2ats_status {
+  A2ATS_OK = 0,
+  A2ATS_ERR_INVALID_ARG = -1, /* NULL required pointer, inconsistent dims, negative sizes */
+  A2ATS_ERR_UNSUPPORTED = -2, /* shape outside the compiled kernel set                    */
+  A2ATS_ERR_WORKSPACE = -3,   /* ws_bytes smaller than a2ats_workspace_bytes()            */
+  A2ATS_ERR_HIP = -4          /* a launch failed (hipGetLastError after the launch)       */
+} a2ats_status;
+
+enum { A2ATS_F32 = 0, A2ATS_BF16 = 1 };                       /* element types of q / k / v / out */
+enum { A2ATS_W_NONE = 0, A2ATS_W_DIAG = 1, A2ATS_W_BLOCK = 2 }; /* encoder distortion              */
+enum { A2ATS_OP_ENCODE = 0, A2ATS_OP_LUT = 1, A2ATS_OP_SCORE_TOPK = 2, A2ATS_OP_ATTN = 3 };
+
+int a2ats_version(void);
+const char* a2ats_status_string(int status);
+
+/* Number of int32 elements of the lookup table for these dims: B*Hkv*ceil(G/4)*256*M*4. */
+size_t a2ats_lut_elems(const a2ats_dims* dims);
+
+/* Scratch bytes `op` needs for these dims (0 if it needs none; (size_t)-1 on bad dims). */
+size_t a2ats_workspace_bytes(const a2ats_dims* dims, int op, int32_t top_k, int32_t window);
+
+/*
+ * Host helper: rotation tables for WRoPE (paper section 4.1, eq. "WRoPE"; section 2.1).
+ * Dimension t is paired with t + D/2; the pair turns by position * inv_freq[t].
+ *   cos_b, sin_b     [host, out, float32 D/2]          angle b * inv_freq[t]   (fixed offset b)
+ *   cos_win, sin_win [host, out, float32 window * D/2] angle delta * inv_freq[t], delta = 0..window-1
+ * Angles are formed and evaluated in float64 and rounded once to float32.  cos_win/sin_win
+ * may be NULL when window == 0.  The caller copies the tables to the device.
+ */
+int a2ats_rope_tables(int32_t head_dim, const double* inv_freq, int32_t b, int32_t window,
+                      float* cos_b, float* sin_b, float* cos_win, float* sin_win);
+
+/*
+ * Prefill / append-side key encoder (paper section 4.2, query-aware quantisation function
+ * f'; section 2.2, f).  For every new key row and subspace m:
+ *     codes[b, kv, pos0 + j, m] = argmin_c (k_m - C[kv,m,c]) H_m (k_m - C[kv,m,c])^T ,
+ * lowest c on exact ties.  weight_mode selects H_m:
+ *     A2ATS_W_NONE   H_m = I (plain nearest centroid), weights ignored (may be NULL)
+ *     A2ATS_W_DIAG   H_m = diag(weights[kv, m*ds .. m*ds+ds-1]),  weights [dev, f32 Hkv*D], > 0
+ *     A2ATS_W_BLOCK  H_m = weights[kv, m, :, :],  weights [dev, f32 Hkv*M*ds*ds], symmetric
+ *                    positive definite (the ds x ds diagonal blocks of E[q^T q])
+ *   keys     [dev, f32  B*Hkv*n_new*D]     pre-RoPE keys, dense (no stride)
+ *   codebook [dev, f32  Hkv*M*256*ds]
+ *   codes    [dev, u8   B*Hkv*ctx_stride*M] rows pos0 .. pos0+n_new-1 are written
+ * Distances are evaluated in float32 and re-evaluated in float64 from the definition
+ * whenever the two smallest are closer than 1e-4 relative, so codes equal the float64
+ * argmin.  Needs no workspace.  n_new == 0 is a no-op.
+ */
+int a2ats_encode_keys(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
+                      const float* codebook, const float* weights, int weight_mode,
+                      uint8_t* codes, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Steps 1-2 of a decode step (paper section 4.1: q~ = q R_b; section 4.2 last equation /
+ * section 2.2 eq. "attention weights approximation": u^_j = q~ . c_{s_j}, tabulated per
+ * subspace).
+ *   q         [dev, q_dtype B*Hq*D]   pre-RoPE query of the current token
+ *   cos_b/sin_b [dev, f32 D/2]        from a2ats_rope_tables
+ *   codebook  [dev, f32 Hkv*M*256*ds]
+ *   q_rot     [dev, out, f32 B*Hq*D]  q R_b, rotated in float64, rounded once
+ *   lut       [dev, out, int32 a2ats_lut_elems()]   see "Lookup-table format"
+ *   lut_scale [dev, out, f32 B*Hq]
+ * Inner products are accumulated in float64.  Needs no workspace.
+ */
+int a2ats_build_lut(const a2ats_dims* dims, const void* q, int q_dtype, const float* cos_b,
+                    const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
+                    float* lut_scale, void* stream);
+
+/*
+ * Steps 3 of a decode step: approximate scores for every cached token by gather-summing
+ * table entries through its codes, then exact top-K (paper section 4: "retrieves the
+ * top-K tokens with the highest attention scores").  For sequence b with n tokens the
+ * candidates are positions [sink_end, n - window), sink_end = min(n_sink, max(0, n - window)):
+ * sinks and the recent window are always attended and never compete.  Selection is per
+ * query head; equal scores go to the lower position.
+ *   codes      [dev, u8 B*Hkv*ctx_stride*M]
+ *   lut, lut_scale   from a2ats_build_lut
+ *   topk_idx   [dev, out, int32 B*Hq*top_k]  selected positions in ascending order;
+ *                                            slots past topk_count are -1
+ *   topk_count [dev, out, int32 B*Hq]        K' = min(top_k, #candidates)
+ *   topk_score [dev, out, nullable, f32 B*Hq*top_k] score of each selected position
+ *   scores_out [dev, out, nullable, f32 B*Hq*ctx_stride] debug: every token's score
+ *              (positions >= n are not written)
+ * top_k == 0 is allowed.  window >= 0, n_sink >= 0.
+ */
+int a2ats_score_topk(const a2ats_dims* dims, const uint8_t* codes, const int32_t* lut,
+                     const float* lut_scale, int32_t top_k, int32_t window, int32_t n_sink,
+                     const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
+                     float* topk_score, float* scores_out, void* ws, size_t ws_bytes,
+                     void* stream);
+
+/*
+ * Step 4: exact attention over S = sinks U top-K U window (paper section 2.1 eq. "output
+ * state" restricted to S; section 4.1 eq. "WRoPE").  With i = n - 1:
+ *     logit_j = q R_{i-j} k_j^T / sqrt(D)   for i - j <  window
+ *     logit_j = q R_b     k_j^T / sqrt(D)   otherwise (q R_b = q_rot)
+ *     out     = sum_{j in S} softmax(logit)_j v_j
+ * Keys are the exact pre-RoPE keys.  float32 accumulation; out is rounded once to kv_dtype.
+ *   q        [dev, kv_dtype B*Hq*D]      q_rot [dev, f32 B*Hq*D]
+ *   k_cache, v_cache [dev, kv_dtype B*Hkv*ctx_stride*D]
+ *   topk_idx [dev, int32 B*Hq*top_k], topk_count [dev, int32 B*Hq]  (every index must be a
+ *            candidate position of its sequence; the kernels do not re-check)
+ *   cos_win/sin_win [dev, f32 window*D/2] from a2ats_rope_tables (may be NULL if window == 0)
+ *   out      [dev, out, kv_dtype B*Hq*D]  (zeros for an empty sequence)
+ */
+int a2ats_sparse_attn(const a2ats_dims* dims, const void* q, const float* q_rot,
+                      const void* k_cache, const void* v_cache, int kv_dtype,
+                      const int32_t* topk_idx, const int32_t* topk_count, int32_t top_k,
+                      int32_t window, int32_t n_sink, const float* cos_win, const float* sin_win,
+                      const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Profiling aid (not part of the method): when both events are non-NULL, the next
+ * a2ats_score_topk calls record ev_start / ev_stop (hipEvent_t passed as void*) on their
+ * stream immediately around the code-streaming kernel, so a caller can time that kernel
+ * alone.  Pass NULLs to switch it off.  Process-global, not thread-safe.
+ */
+void a2ats_profile_stream_kernel(void* ev_start, void* ev_stop);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A2ATS_H_ */

@@ -1,0 +1,204 @@
+"""Thin ctypes binding over liba2ats.so (the C ABI in include/a2ats.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch is
+used for device memory and for the current HIP stream.  There is no CPU fallback: if
+the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liba2ats.so")
+
+F32, BF16 = 0, 1
+W_NONE, W_DIAG, W_BLOCK = 0, 1, 2
+OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN = 0, 1, 2, 3
+EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes",
+           "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
+           "a2ats_sparse_attn", "a2ats_profile_stream_kernel"]
+
+
+class A2atsError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+
+
+class Dims(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("n_sub", ctypes.c_int32), ("sub_dim", ctypes.c_int32),
+                ("n_centroids", ctypes.c_int32), ("ctx_len", ctypes.c_int32), ("ctx_stride", ctypes.c_int64)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library (build it with paper_2502_12665_amd.build.build() first)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run __graft_entry__.build() "
+                                    "or `python -m paper_2502_12665_amd.build`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        dp = ctypes.POINTER(Dims)
+        L.a2ats_version.restype = ctypes.c_int
+        L.a2ats_status_string.restype = ctypes.c_char_p
+        L.a2ats_status_string.argtypes = [ctypes.c_int]
+        L.a2ats_lut_elems.restype = sz
+        L.a2ats_lut_elems.argtypes = [dp]
+        L.a2ats_workspace_bytes.restype = sz
+        L.a2ats_workspace_bytes.argtypes = [dp, ctypes.c_int, i32, i32]
+        L.a2ats_rope_tables.restype = ctypes.c_int
+        L.a2ats_rope_tables.argtypes = [i32, vp, i32, i32, vp, vp, vp, vp]
+        L.a2ats_encode_keys.restype = ctypes.c_int
+        L.a2ats_encode_keys.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, sz, vp]
+        L.a2ats_build_lut.restype = ctypes.c_int
+        L.a2ats_build_lut.argtypes = [dp, vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
+        L.a2ats_score_topk.restype = ctypes.c_int
+        L.a2ats_score_topk.argtypes = [dp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.a2ats_sparse_attn.restype = ctypes.c_int
+        L.a2ats_sparse_attn.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, vp,
+                                        vp, vp, vp, sz, vp]
+        L.a2ats_profile_stream_kernel.restype = None
+        L.a2ats_profile_stream_kernel.argtypes = [vp, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().a2ats_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(lib().a2ats_version())
+
+
+def make_dims(batch, n_q_heads, n_kv_heads, head_dim, n_sub, ctx_len, ctx_stride=None,
+              n_centroids=256, sub_dim=None) -> Dims:
+    return Dims(batch, n_q_heads, n_kv_heads, head_dim, n_sub,
+                head_dim // n_sub if sub_dim is None else sub_dim, n_centroids, ctx_len,
+                ctx_len if ctx_stride is None else ctx_stride)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_contiguous(), "tensors crossing the C ABI must be contiguous"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise A2atsError(rc, what)
+
+
+def lut_elems(dims: Dims) -> int:
+    return int(lib().a2ats_lut_elems(ctypes.byref(dims)))
+
+
+def workspace_bytes(dims: Dims, op: int, top_k: int = 0, window: int = 0) -> int:
+    n = int(lib().a2ats_workspace_bytes(ctypes.byref(dims), op, top_k, window))
+    if n == ctypes.c_size_t(-1).value:
+        raise A2atsError(-1, "a2ats_workspace_bytes")
+    return n
+
+
+def rope_tables(head_dim: int, inv_freq: torch.Tensor, b: int, window: int, device=None):
+    """Host helper -> (cos_b, sin_b [D/2], cos_win, sin_win [window, D/2]) float32, moved to `device`."""
+    inv = inv_freq.detach().to("cpu", torch.float64).contiguous()
+    half = head_dim // 2
+    cb, sb = torch.empty(half, dtype=torch.float32), torch.empty(half, dtype=torch.float32)
+    cw = torch.empty(max(window, 1), half, dtype=torch.float32)
+    sw = torch.empty(max(window, 1), half, dtype=torch.float32)
+    rc = lib().a2ats_rope_tables(head_dim, _ptr(inv), int(b), int(window), _ptr(cb), _ptr(sb), _ptr(cw), _ptr(sw))
+    _check(rc, "a2ats_rope_tables")
+    outs = (cb, sb, cw, sw)
+    return tuple(t.to(device) for t in outs) if device is not None else outs
+
+
+def encode_keys(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, weight_mode: int, codes,
+                ws: Optional[torch.Tensor] = None):
+    rc = lib().a2ats_encode_keys(ctypes.byref(dims), _ptr(keys), n_new, pos0, _ptr(codebook), _ptr(weights),
+                                 weight_mode, _ptr(codes), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                 _stream())
+    _check(rc, "a2ats_encode_keys")
+
+
+def build_lut(dims: Dims, q, cos_b, sin_b, codebook, q_rot, lut, lut_scale):
+    rc = lib().a2ats_build_lut(ctypes.byref(dims), _ptr(q), _dtype_code(q), _ptr(cos_b), _ptr(sin_b),
+                               _ptr(codebook), _ptr(q_rot), _ptr(lut), _ptr(lut_scale), _stream())
+    _check(rc, "a2ats_build_lut")
+
+
+def score_topk(dims: Dims, codes, lut, lut_scale, top_k: int, window: int, n_sink: int, seq_lens,
+               topk_idx, topk_count, topk_score=None, scores_out=None, ws: Optional[torch.Tensor] = None):
+    rc = lib().a2ats_score_topk(ctypes.byref(dims), _ptr(codes), _ptr(lut), _ptr(lut_scale), top_k, window,
+                                n_sink, _ptr(seq_lens), _ptr(topk_idx), _ptr(topk_count), _ptr(topk_score),
+                                _ptr(scores_out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                                _stream())
+    _check(rc, "a2ats_score_topk")
+
+
+def sparse_attn(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k: int, window: int,
+                n_sink: int, cos_win, sin_win, seq_lens, out, ws: Optional[torch.Tensor] = None):
+    rc = lib().a2ats_sparse_attn(ctypes.byref(dims), _ptr(q), _ptr(q_rot), _ptr(k_cache), _ptr(v_cache),
+                                 _dtype_code(k_cache), _ptr(topk_idx), _ptr(topk_count), top_k, window, n_sink,
+                                 _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _ptr(ws),
+                                 0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_sparse_attn")
+
+
+def profile_stream_kernel(ev_start: Optional[int], ev_stop: Optional[int]):
+    lib().a2ats_profile_stream_kernel(ctypes.c_void_p(ev_start or 0), ctypes.c_void_p(ev_stop or 0))
+
+
+class DecodeState:
+    """Device buffers for one decode step of a fixed shape (allocation only; no arithmetic)."""
+
+    def __init__(self, dims: Dims, top_k: int, window: int, n_sink: int, kv_dtype: torch.dtype,
+                 inv_freq: torch.Tensor, wrope_b: int, device="cuda", want_scores=False):
+        self.dims, self.top_k, self.window, self.n_sink = dims, top_k, window, n_sink
+        B, Hq, D = dims.batch, dims.n_q_heads, dims.head_dim
+        dev = torch.device(device)
+        self.cos_b, self.sin_b, self.cos_win, self.sin_win = rope_tables(D, inv_freq, wrope_b, window, dev)
+        self.q_rot = torch.empty(B, Hq, D, dtype=torch.float32, device=dev)
+        self.lut = torch.empty(max(lut_elems(dims), 4), dtype=torch.int32, device=dev)
+        self.lut_scale = torch.empty(B, Hq, dtype=torch.float32, device=dev)
+        self.topk_idx = torch.empty(B, Hq, top_k, dtype=torch.int32, device=dev)
+        self.topk_count = torch.empty(B, Hq, dtype=torch.int32, device=dev)
+        self.topk_score = torch.empty(B, Hq, max(top_k, 1), dtype=torch.float32, device=dev)
+        self.scores = torch.empty(B, Hq, dims.ctx_stride, dtype=torch.float32, device=dev) if want_scores else None
+        self.out = torch.empty(B, Hq, D, dtype=kv_dtype, device=dev)
+        n_ws = max(workspace_bytes(dims, OP_SCORE_TOPK, top_k, window),
+                   workspace_bytes(dims, OP_ATTN, top_k, window),
+                   workspace_bytes(dims, OP_ENCODE), 256)
+        self.ws = torch.empty(n_ws, dtype=torch.uint8, device=dev)
+
+    def step(self, q, codes, k_cache, v_cache, codebook, seq_lens=None, with_scores=False):
+        """build_lut -> score_topk -> sparse_attn on the current stream; returns self.out."""
+        build_lut(self.dims, q, self.cos_b, self.sin_b, codebook, self.q_rot, self.lut, self.lut_scale)
+        score_topk(self.dims, codes, self.lut, self.lut_scale, self.top_k, self.window, self.n_sink, seq_lens,
+                   self.topk_idx, self.topk_count, self.topk_score,
+                   self.scores if with_scores else None, self.ws)
+        sparse_attn(self.dims, q, self.q_rot, k_cache, v_cache, self.topk_idx, self.topk_count, self.top_k,
+                    self.window, self.n_sink, self.cos_win, self.sin_win, seq_lens, self.out, self.ws)
+        return self.out

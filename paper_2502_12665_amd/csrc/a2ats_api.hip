@@ -1,0 +1,172 @@
+// C ABI of the library: host-side argument validation, workspace planning and launches.
+// Everything is checked before the first launch, so every error path is reachable without
+// a GPU.
+#include <math.h>
+
+#include "common.hpp"
+#include "internal.hpp"
+
+
+namespace {
+
+int check_dims(const a2ats_dims* d) {
+  if (!d) return A2ATS_ERR_INVALID_ARG;
+  if (d->batch < 0 || d->n_q_heads <= 0 || d->n_kv_heads <= 0 || d->head_dim <= 0 || d->n_sub <= 0 ||
+      d->sub_dim <= 0 || d->n_centroids <= 0 || d->ctx_len < 0)
+    return A2ATS_ERR_INVALID_ARG;
+  if (d->n_q_heads % d->n_kv_heads != 0) return A2ATS_ERR_INVALID_ARG;
+  if ((int64_t)d->n_sub * d->sub_dim != d->head_dim) return A2ATS_ERR_INVALID_ARG;
+  if (d->ctx_stride < d->ctx_len) return A2ATS_ERR_INVALID_ARG;
+  if (d->head_dim != 128 || d->n_centroids != 256) return A2ATS_ERR_UNSUPPORTED;
+  if (d->sub_dim != 4 && d->sub_dim != 8) return A2ATS_ERR_UNSUPPORTED;
+  if (d->n_q_heads / d->n_kv_heads > 8) return A2ATS_ERR_UNSUPPORTED;
+  if (d->ctx_len > (1 << 20)) return A2ATS_ERR_UNSUPPORTED;
+  return A2ATS_OK;
+}
+
+bool misaligned16(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int a2ats_version(void) { return 100; }
+
+const char* a2ats_status_string(int status) {
+  switch (status) {
+    case A2ATS_OK: return "ok";
+    case A2ATS_ERR_INVALID_ARG: return "invalid argument";
+    case A2ATS_ERR_UNSUPPORTED: return "unsupported shape";
+    case A2ATS_ERR_WORKSPACE: return "workspace too small";
+    case A2ATS_ERR_HIP: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+size_t a2ats_lut_elems(const a2ats_dims* d) {
+  if (check_dims(d) != A2ATS_OK) return 0;
+  const int G = d->n_q_heads / d->n_kv_heads;
+  const size_t NG = (size_t)(G + 3) / 4;
+  return (size_t)d->batch * d->n_kv_heads * NG * 256 * d->n_sub * 4;
+}
+
+size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t window) {
+  if (check_dims(d) != A2ATS_OK) return (size_t)-1;
+  switch (op) {
+    case A2ATS_OP_ENCODE: return a2ats::encode_ws_bytes(*d);
+    case A2ATS_OP_LUT: return 0;
+    case A2ATS_OP_SCORE_TOPK: {
+      if (top_k < 0 || window < 0) return (size_t)-1;
+      // the plan does not depend on n_sink except through the candidate count; size for 0 sinks
+      const a2ats::TopkPlan p = a2ats::make_topk_plan(*d, top_k, window, 0);
+      return p.fast ? p.bytes : 0;
+    }
+    case A2ATS_OP_ATTN: {
+      if (top_k < 0 || window < 0) return (size_t)-1;
+      // sized for the largest split the planner can pick (n_sink only adds rows)
+      const size_t heads = (size_t)d->batch * d->n_q_heads;
+      return heads * 32 * (128 + 2) * sizeof(float);
+    }
+    default: return (size_t)-1;
+  }
+}
+
+int a2ats_rope_tables(int32_t head_dim, const double* inv_freq, int32_t b, int32_t window, float* cos_b,
+                      float* sin_b, float* cos_win, float* sin_win) {
+  if (head_dim <= 0 || (head_dim & 1) || !inv_freq || !cos_b || !sin_b || window < 0)
+    return A2ATS_ERR_INVALID_ARG;
+  if (window > 0 && (!cos_win || !sin_win)) return A2ATS_ERR_INVALID_ARG;
+  const int half = head_dim / 2;
+  for (int t = 0; t < half; ++t) {
+    const double a = (double)b * inv_freq[t];
+    cos_b[t] = (float)cos(a);
+    sin_b[t] = (float)sin(a);
+  }
+  for (int dlt = 0; dlt < window; ++dlt)
+    for (int t = 0; t < half; ++t) {
+      const double a = (double)dlt * inv_freq[t];
+      cos_win[(size_t)dlt * half + t] = (float)cos(a);
+      sin_win[(size_t)dlt * half + t] = (float)sin(a);
+    }
+  return A2ATS_OK;
+}
+
+int a2ats_encode_keys(const a2ats_dims* d, const float* keys, int32_t n_new, int32_t pos0,
+                      const float* codebook, const float* weights, int weight_mode, uint8_t* codes,
+                      void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE && weight_mode != A2ATS_W_DIAG && weight_mode != A2ATS_W_BLOCK)
+    return A2ATS_ERR_INVALID_ARG;
+  if (!keys || !codebook || !codes) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE && !weights) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(keys) || misaligned16(codebook)) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE) {
+    if (!ws || misaligned16(ws)) return A2ATS_ERR_WORKSPACE;
+    if (ws_bytes < a2ats::encode_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
+  }
+  if ((int64_t)n_new > 65535LL * 256) return A2ATS_ERR_UNSUPPORTED;
+  const hipError_t e = a2ats::launch_encode(*d, keys, n_new, pos0, codebook, weights, weight_mode, codes,
+                                            weight_mode != A2ATS_W_NONE ? ws : nullptr, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_build_lut(const a2ats_dims* d, const void* q, int q_dtype, const float* cos_b, const float* sin_b,
+                    const float* codebook, float* q_rot, int32_t* lut, float* lut_scale, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
+  if (!q || !cos_b || !sin_b || !codebook || !q_rot || !lut || !lut_scale) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(codebook) || misaligned16(lut)) return A2ATS_ERR_INVALID_ARG;
+  const hipError_t e = a2ats::launch_build_lut(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut,
+                                               lut_scale, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut, const float* lut_scale,
+                     int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
+                     int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,
+                     size_t ws_bytes, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
+  if (!codes || !lut || !lut_scale || !topk_count) return A2ATS_ERR_INVALID_ARG;
+  if (top_k > 0 && !topk_idx) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(codes) || misaligned16(lut)) return A2ATS_ERR_INVALID_ARG;
+  if (top_k > 4096) return A2ATS_ERR_UNSUPPORTED;
+  const a2ats::TopkPlan plan = a2ats::make_topk_plan(*d, top_k, window, n_sink);
+  if (plan.fast) {
+    if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
+  }
+  const hipError_t e = a2ats::launch_score_topk(*d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
+                                                topk_idx, topk_count, topk_score, scores_out, ws,
+                                                (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
+                      const void* v_cache, int kv_dtype, const int32_t* topk_idx, const int32_t* topk_count,
+                      int32_t top_k, int32_t window, int32_t n_sink, const float* cos_win,
+                      const float* sin_win, const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes,
+                      void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (kv_dtype != A2ATS_F32 && kv_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
+  if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
+  if (!q || !q_rot || !k_cache || !v_cache || !topk_count || !out) return A2ATS_ERR_INVALID_ARG;
+  if (top_k > 0 && !topk_idx) return A2ATS_ERR_INVALID_ARG;
+  if (window > 0 && (!cos_win || !sin_win)) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(k_cache) || misaligned16(v_cache) || misaligned16(cos_win) || misaligned16(sin_win))
+    return A2ATS_ERR_INVALID_ARG;
+  const a2ats::AttnPlan plan = a2ats::make_attn_plan(*d, top_k, window, n_sink);
+  if (plan.n_split > 1 && (!ws || ws_bytes < plan.bytes)) return A2ATS_ERR_WORKSPACE;
+  const hipError_t e = a2ats::launch_sparse_attn(*d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx,
+                                                 topk_count, top_k, window, n_sink, cos_win, sin_win,
+                                                 seq_lens, out, ws, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+void a2ats_profile_stream_kernel(void* ev_start, void* ev_stop) { a2ats::set_profile_events(ev_start, ev_stop); }
+
+}  // extern "C"

@@ -1,0 +1,134 @@
+// Shared device helpers for the gfx950 kernels: wave64 lane utilities, block scans and the
+// rank search over an LDS histogram used by every selection stage.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "a2ats.h"
+
+namespace a2ats {
+
+constexpr int kWave = 64;          // CDNA wavefront width
+constexpr int kCentroids = 256;    // one uint8 code per subspace
+constexpr int kHeadsPerGroup = 4;  // query heads served by one 16-byte table entry
+constexpr int kHistBins = 2048;
+
+__device__ __forceinline__ int lane_id() {
+  return __builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+}
+
+// Number of set bits of `mask` below the calling lane.
+__device__ __forceinline__ int lanes_below(uint64_t mask) {
+  return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                   __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Integer score -> unsigned key with the same order.
+__device__ __forceinline__ uint32_t score_key(int32_t s) { return (uint32_t)s ^ 0x80000000u; }
+__device__ __forceinline__ int32_t key_score(uint32_t k) { return (int32_t)(k ^ 0x80000000u); }
+
+// Exclusive prefix sum of `v` over the block (NT threads, NT a multiple of 64).  `s_wave` is an
+// LDS array of NT/64 words owned by this call site.  Returns the exclusive prefix and the
+// block total.  One barrier; callers alternate between two `s_wave` arrays when they scan
+// repeatedly so that a second barrier is not needed.
+template <int NT>
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave,
+                                                         uint32_t& total) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  uint32_t inc = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    uint32_t o = __shfl_up(inc, off);
+    if (lane >= off) inc += o;
+  }
+  if (lane == 63) s_wave[wv] = inc;
+  __syncthreads();
+  uint32_t base = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < NT / 64; ++i) {
+    uint32_t w = s_wave[i];
+    if (i < wv) base += w;
+    tot += w;
+  }
+  total = tot;
+  return base + inc - v;
+}
+
+// Rank search over a histogram of NB bins, scanning from the highest bin down: finds the bin
+// T with  sum_{bin > T} count < k <= sum_{bin >= T} count  (1 <= k <= sum of all bins).
+// `count(bin)` reads one bin (normally from LDS).  s_res[0] = T, s_res[1] = sum_{bin > T}.
+// Two barriers; every thread of the block must call it.  s_wave: NT/64 words of LDS,
+// s_res: 2 words of LDS.
+template <int NT, int NB, typename Count>
+__device__ __forceinline__ void block_find_rank_desc(Count count, uint32_t k, uint32_t* s_wave,
+                                                     uint32_t* s_res) {
+  static_assert(NB % NT == 0, "bins must divide evenly over the block");
+  constexpr int PER = NB / NT;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int top = NB - 1 - (int)threadIdx.x * PER;
+  uint32_t loc[PER];
+  uint32_t sum = 0;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    loc[i] = count(top - i);
+    sum += loc[i];
+  }
+  uint32_t inc = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    uint32_t o = __shfl_up(inc, off);
+    if (lane >= off) inc += o;
+  }
+  if (lane == 63) s_wave[wv] = inc;
+  __syncthreads();
+  uint32_t base = 0;
+  for (int i = 0; i < wv; ++i) base += s_wave[i];
+  inc += base;
+  uint32_t run = inc - sum;
+  if (run < k && k <= inc) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      if (run + loc[i] >= k) {
+        s_res[0] = (uint32_t)(top - i);
+        s_res[1] = run;
+        break;
+      }
+      run += loc[i];
+    }
+  }
+  __syncthreads();
+}
+
+// Per-sequence geometry of the candidate range (sinks and window never compete).
+struct SeqRange {
+  int n;          // tokens in the sequence
+  int win_start;  // first window position
+  int sink_end;   // one past the last sink
+  int ncand;      // win_start - sink_end
+  int kk;         // min(top_k, ncand)
+};
+
+__device__ __forceinline__ SeqRange seq_range(int ctx_len, const int32_t* seq_lens, int b,
+                                              int window, int n_sink, int top_k) {
+  SeqRange r;
+  r.n = seq_lens ? seq_lens[b] : ctx_len;
+  r.n = r.n < 0 ? 0 : (r.n > ctx_len ? ctx_len : r.n);
+  r.win_start = r.n - window > 0 ? r.n - window : 0;
+  r.sink_end = n_sink < r.win_start ? n_sink : r.win_start;
+  r.ncand = r.win_start - r.sink_end;
+  r.kk = top_k < r.ncand ? top_k : r.ncand;
+  return r;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+// Round-to-nearest-even float -> bf16 (finite inputs; NaN is kept a NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+}  // namespace a2ats

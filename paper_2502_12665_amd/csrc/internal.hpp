@@ -1,0 +1,49 @@
+// Host-side declarations shared by the translation units of the library: launch plans and
+// the launch functions the C ABI layer calls.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "a2ats.h"
+
+namespace a2ats {
+
+// How a2ats_score_topk runs for a shape, and how it carves its workspace.
+struct TopkPlan {
+  bool fast;            // sampled threshold + one streaming pass (else: exact route only)
+  int NG;               // head groups of 4 per KV head
+  int P0;               // sampling workgroups per (sequence, KV head, head group)
+  int chunks;           // streaming workgroups per (sequence, KV head, head group)
+  int rows_per_chunk;
+  int cap;              // candidate-list capacity per head
+  size_t off_thr, off_count, off_cand, bytes;
+};
+
+struct AttnPlan {
+  int n_split;          // workgroups sharing the rows of one head
+  size_t bytes;
+};
+
+TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink);
+AttnPlan make_attn_plan(const a2ats_dims& d, int top_k, int window, int n_sink);
+size_t encode_ws_bytes(const a2ats_dims& d);
+void set_profile_events(void* ev_start, void* ev_stop);
+
+hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
+                            const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
+                            float* lut_scale, hipStream_t stream);
+hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const int32_t* lut,
+                             const float* lut_scale, int top_k, int window, int n_sink,
+                             const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
+                             float* topk_score, float* scores_out, void* ws, hipStream_t stream);
+hipError_t launch_sparse_attn(const a2ats_dims& d, const void* q, const float* q_rot, const void* k_cache,
+                              const void* v_cache, int kv_dtype, const int32_t* topk_idx,
+                              const int32_t* topk_count, int top_k, int window, int n_sink,
+                              const float* cos_win, const float* sin_win, const int32_t* seq_lens,
+                              void* out, void* ws, hipStream_t stream);
+hipError_t launch_encode(const a2ats_dims& d, const float* keys, int n_new, int pos0, const float* codebook,
+                         const float* weights, int mode, uint8_t* codes, void* ws, hipStream_t stream);
+
+}  // namespace a2ats

@@ -1,0 +1,688 @@
+// Step 3 of a decode step: approximate scores by gather-summing fixed-point table entries
+// through the uint8 codes (section 4.2 last equation), and exact per-head top-K (section 4).
+//
+// Two routes, chosen on the host from the shape:
+//
+//  exact route (short contexts, very large K, ragged corner cases; also the in-kernel fallback
+//  of the fast route): one workgroup per query head runs an MSB-first radix select over the
+//  32-bit score keys by re-streaming its sequence (3 histogram passes), then one ordered pass
+//  that emits the winners in ascending position, equal scores going to the lower position.
+//
+//  fast route (long contexts): the code matrix is streamed from HBM once.
+//    1. sample_threshold_kernel scores a strided sample of each sequence (about 1/16 of it) and
+//       derives, per head, an integer threshold below the K-th score with a 5-sigma margin
+//       (distribution-free: it only uses ranks of the sample).
+//    2. stream_select_kernel streams all code rows, one 16-byte table read per code byte
+//       serving the four heads of a group, and appends every (position, score) at or above
+//       the threshold to a per-head candidate list (about 2K entries) through wave-private
+//       LDS staging.
+//    3. final_select_kernel (one workgroup per head) radix-selects the exact K-th key among
+//       the candidates in LDS, resolves ties by position, and orders the winners by position
+//       with an LDS bitmap.  If the candidate list is too short or overflowed -- possible only
+//       when the sample misled (probability ~1e-6 per head) or for degenerate inputs -- the
+//       workgroup runs the exact route for its head instead, so the result is always exact.
+#include <math.h>
+
+#include "common.hpp"
+#include "internal.hpp"
+
+namespace a2ats {
+
+constexpr int kExactThreads = 1024;
+constexpr int kStreamThreads = 512;
+constexpr int kSampleThreads = 512;
+constexpr int kStageCap = 64;        // wave-private staging entries per head
+constexpr int kSampleRows = 1024;    // rows scored by one sampling workgroup
+constexpr float kSigma = 5.0f;
+
+TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) {
+  TopkPlan p{};
+  const int G = d.n_q_heads / d.n_kv_heads;
+  p.NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
+  long ncand = (long)d.ctx_len - window - n_sink;
+  if (ncand < 0) ncand = 0;
+  p.cap = 8192;
+  p.fast = ncand >= 16384 && d.ctx_len <= (1 << 18) && top_k >= 1 && top_k <= 2048 &&
+           4L * top_k <= ncand;
+  if (p.fast) {
+    long s_tot = ncand / 16 / kSampleRows * kSampleRows;
+    if (s_tot < kSampleRows) s_tot = kSampleRows;
+    if (s_tot > 8 * kSampleRows) s_tot = 8 * kSampleRows;
+    p.P0 = (int)(s_tot / kSampleRows);
+    const long problems = (long)d.batch * d.n_kv_heads * p.NG;
+    long chunks = (512 + problems - 1) / problems;
+    const long max_chunks = (ncand + 2047) / 2048;
+    if (chunks > max_chunks) chunks = max_chunks;
+    if (chunks < 1) chunks = 1;
+    long rpc = (ncand + chunks - 1) / chunks;
+    rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
+    p.chunks = (int)((ncand + rpc - 1) / rpc);
+    p.rows_per_chunk = (int)rpc;
+    const size_t heads = (size_t)d.batch * d.n_q_heads;
+    p.off_thr = 0;
+    p.off_count = p.off_thr + heads * p.P0 * sizeof(int32_t);
+    p.off_cand = (p.off_count + heads * sizeof(uint32_t) + 255) / 256 * 256;
+    p.bytes = p.off_cand + heads * (size_t)p.cap * sizeof(uint2);
+  }
+  return p;
+}
+
+// ------------------------------------------------------------------------------------------
+// Scoring primitives
+// ------------------------------------------------------------------------------------------
+
+// Score of one token for one head from a [c][m] single-head table in LDS.
+template <int M>
+__device__ __forceinline__ int32_t score_one_head(const uint8_t* row, const int32_t* lut1) {
+  int32_t s = 0;
+#pragma unroll
+  for (int qd = 0; qd < M / 16; ++qd) {
+    const uint4 w = *(const uint4*)(row + qd * 16);
+    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t byte = (ww[i >> 2] >> (8 * (i & 3))) & 0xffu;
+      s += lut1[byte * M + qd * 16 + i];
+    }
+  }
+  return s;
+}
+
+// Scores of one token for the four heads of a group from the [c][m][4] table in LDS.
+template <int M>
+__device__ __forceinline__ void score_four_heads(const uint4 (&w)[M / 16], const int4* lutv,
+                                                 int32_t (&acc)[4]) {
+  acc[0] = acc[1] = acc[2] = acc[3] = 0;
+#pragma unroll
+  for (int qd = 0; qd < M / 16; ++qd) {
+    const uint32_t ww[4] = {w[qd].x, w[qd].y, w[qd].z, w[qd].w};
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const uint32_t byte = (ww[i >> 2] >> (8 * (i & 3))) & 0xffu;
+      const int4 e = lutv[byte * M + qd * 16 + i];
+      acc[0] += e.x; acc[1] += e.y; acc[2] += e.z; acc[3] += e.w;
+    }
+  }
+}
+
+template <int M, int NT>
+__device__ __forceinline__ void load_group_lut(const int32_t* __restrict__ lut_grp, int4* lutv) {
+  const int4* src = (const int4*)lut_grp;
+#pragma unroll 4
+  for (int e = threadIdx.x; e < kCentroids * M; e += NT) lutv[e] = src[e];
+}
+
+// ------------------------------------------------------------------------------------------
+// Exact route (also the fallback of the fast route)
+// ------------------------------------------------------------------------------------------
+struct ExactLds {
+  uint32_t hist[kHistBins];
+  uint32_t wave_a[kExactThreads / 64];
+  uint32_t wave_b[kExactThreads / 64];
+  uint32_t res[2];
+};
+
+// Exact top-K for one head by the whole workgroup.  `lut1` is kCentroids*M words of LDS.
+// Writes out_idx[0..kk) ascending (and out_score) ; the caller has written the count and the
+// -1 padding.  Requires sr.kk >= 1.
+template <int M>
+__device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
+                                   const int32_t* __restrict__ lut_grp, int r, float scale,
+                                   const SeqRange& sr, int32_t* __restrict__ out_idx,
+                                   float* __restrict__ out_score, int32_t* lut1, ExactLds& L) {
+  constexpr int NT = kExactThreads;
+  const int tid = threadIdx.x;
+  for (int e = tid; e < kCentroids * M; e += NT) lut1[e] = lut_grp[e * kHeadsPerGroup + r];
+  __syncthreads();
+
+  const int lo = sr.sink_end, hi = sr.win_start;
+  uint32_t kth = 0, k_rem = (uint32_t)sr.kk;
+  if (sr.kk < sr.ncand) {
+    uint32_t prefix = 0, mask = 0;
+#pragma unroll 1
+    for (int lvl = 0; lvl < 3; ++lvl) {
+      const int shift = lvl == 0 ? 21 : (lvl == 1 ? 10 : 0);
+      const uint32_t dmask = lvl == 2 ? 1023u : 2047u;
+      for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
+      __syncthreads();
+      for (int j = lo + tid; j < hi; j += NT) {
+        const uint32_t key = score_key(score_one_head<M>(seq_codes + (size_t)j * M, lut1));
+        if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
+      }
+      __syncthreads();
+      block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
+      const uint32_t bin = L.res[0], above = L.res[1];
+      k_rem -= above;
+      prefix |= bin << shift;
+      mask |= dmask << shift;
+      __syncthreads();
+    }
+    kth = prefix;
+  } else {
+    kth = 0;  // every candidate is taken: all keys >= 0
+    k_rem = (uint32_t)sr.kk;
+  }
+
+  // Ordered emission: keys above the K-th, plus the first k_rem positions that equal it.
+  uint32_t eq_seen = 0, out_n = 0;
+  const bool take_all = sr.kk >= sr.ncand;
+#pragma unroll 1
+  for (int base = lo; base < hi; base += NT) {
+    const int j = base + tid;
+    int32_t s = 0;
+    uint32_t gt = 0, eq = 0;
+    if (j < hi) {
+      s = score_one_head<M>(seq_codes + (size_t)j * M, lut1);
+      const uint32_t key = score_key(s);
+      gt = take_all ? 1u : (key > kth ? 1u : 0u);
+      eq = take_all ? 0u : (key == kth ? 1u : 0u);
+    }
+    uint32_t tot_eq, tot_sel;
+    const uint32_t ex_eq = block_exclusive_scan<NT>(eq, L.wave_a, tot_eq);
+    const uint32_t sel = gt | ((eq && (eq_seen + ex_eq < k_rem)) ? 1u : 0u);
+    const uint32_t ex_sel = block_exclusive_scan<NT>(sel, L.wave_b, tot_sel);
+    if (sel) {
+      const uint32_t pos = out_n + ex_sel;
+      out_idx[pos] = j;
+      if (out_score) out_score[pos] = (float)s * scale;
+    }
+    eq_seen += tot_eq;
+    out_n += tot_sel;
+    if (out_n >= (uint32_t)sr.kk) break;
+  }
+}
+
+template <int M>
+__global__ __launch_bounds__(kExactThreads) void select_exact_kernel(
+    const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
+    const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
+    int32_t* __restrict__ topk_idx, int32_t* __restrict__ topk_count,
+    float* __restrict__ topk_score, int Hq, int Hkv, int NG, int ctx_len, int64_t ctx_stride,
+    int top_k, int window, int n_sink) {
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  __shared__ ExactLds L;
+  const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq;
+  const int G = Hq / Hkv, kv = h / G, hg = h % G;
+  const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
+  int32_t* oi = topk_idx + (size_t)bh * top_k;
+  float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
+  if (threadIdx.x == 0) topk_count[bh] = sr.kk;
+  for (int t = sr.kk + threadIdx.x; t < top_k; t += kExactThreads) {
+    oi[t] = -1;
+    if (os) os[t] = 0.f;
+  }
+  if (sr.kk == 0) return;
+  const int32_t* lut_grp =
+      lut + (((size_t)b * Hkv + kv) * NG + hg / kHeadsPerGroup) * (kCentroids * M * kHeadsPerGroup);
+  exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M, lut_grp,
+                        hg % kHeadsPerGroup, lut_scale[bh], sr, oi, os, (int32_t*)dyn_lds, L);
+}
+
+// ------------------------------------------------------------------------------------------
+// Debug: dense scores for every token (not on the fast path; used by parity tests)
+// ------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
+    const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
+    const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
+    float* __restrict__ scores_out, int Hq, int Hkv, int NG, int ctx_len, int64_t ctx_stride) {
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  int4* lutv = (int4*)dyn_lds;
+  const int prob = blockIdx.y;  // (b, kv, g4)
+  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
+  const int G = Hq / Hkv;
+  load_group_lut<M, kStreamThreads>(lut + (size_t)prob * (kCentroids * M * kHeadsPerGroup), lutv);
+  __syncthreads();
+  int n = seq_lens ? seq_lens[b] : ctx_len;
+  n = n < 0 ? 0 : (n > ctx_len ? ctx_len : n);
+  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  float sc[4];
+  for (int r = 0; r < 4; ++r) {
+    const int hg = g4 * kHeadsPerGroup + r;
+    sc[r] = hg < G ? lut_scale[(size_t)b * Hq + kv * G + hg] : 0.f;
+  }
+  for (int j = blockIdx.x * kStreamThreads + threadIdx.x; j < n; j += gridDim.x * kStreamThreads) {
+    uint4 w[M / 16];
+#pragma unroll
+    for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
+    int32_t acc[4];
+    score_four_heads<M>(w, lutv, acc);
+    for (int r = 0; r < 4; ++r) {
+      const int hg = g4 * kHeadsPerGroup + r;
+      if (hg < G) scores_out[((size_t)b * Hq + kv * G + hg) * ctx_stride + j] = (float)acc[r] * sc[r];
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fast route, stage 1: sampled thresholds
+// ------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
+    const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
+    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr,
+    uint32_t* __restrict__ cand_count, int Hq, int Hkv, int NG, int P0, int ctx_len,
+    int64_t ctx_stride, int top_k, int window, int n_sink) {
+  constexpr int NT = kSampleThreads;
+  constexpr int NW = NT / 64;
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  int4* lutv = (int4*)dyn_lds;
+  __shared__ uint32_t s_hist[2][kHistBins];   // two heads per word, 16-bit counts (<= 1024 each)
+  __shared__ int32_t s_mm[NW][M][8];
+  __shared__ int32_t s_red[M][8];
+  __shared__ int32_t s_lo[kHeadsPerGroup];
+  __shared__ int32_t s_shift[kHeadsPerGroup];
+  __shared__ uint32_t s_wave[NW];
+  __shared__ uint32_t s_res[2];
+
+  const int p = blockIdx.x, prob = blockIdx.y;
+  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
+  const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
+
+  // sampling plan for this sequence
+  const int s_p = min(kSampleRows, sr.ncand / P0);
+  const long s_all = (long)s_p * P0;
+  int r_p = 0;
+  bool take_all = sr.ncand <= top_k || s_p == 0;
+  if (!take_all) {
+    const float r0 = (float)top_k * (float)s_all / (float)sr.ncand;
+    const float x = 0.5f * (kSigma + sqrtf(kSigma * kSigma + 4.f * r0));
+    r_p = (int)ceilf(x * x / (float)P0) + 1;
+    if (r_p > s_p) take_all = true;
+  }
+  if (p == 0 && tid < kHeadsPerGroup) {
+    const int hg = g4 * kHeadsPerGroup + tid;
+    if (hg < G) cand_count[(size_t)b * Hq + kv * G + hg] = 0;
+  }
+  if (take_all) {
+    if (tid < kHeadsPerGroup) {
+      const int hg = g4 * kHeadsPerGroup + tid;
+      if (hg < G) thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = INT32_MIN;
+    }
+    return;
+  }
+
+  // table -> LDS, with per-(subspace, head) min / max of the entries this thread copies
+  const int4* src = (const int4*)(lut + (size_t)prob * (kCentroids * M * kHeadsPerGroup));
+  int32_t mn[4] = {INT32_MAX, INT32_MAX, INT32_MAX, INT32_MAX};
+  int32_t mxv[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
+  for (int e = tid; e < kCentroids * M; e += NT) {   // e % M == tid % M for every e of a thread
+    const int4 v = src[e];
+    lutv[e] = v;
+    mn[0] = min(mn[0], v.x); mn[1] = min(mn[1], v.y); mn[2] = min(mn[2], v.z); mn[3] = min(mn[3], v.w);
+    mxv[0] = max(mxv[0], v.x); mxv[1] = max(mxv[1], v.y); mxv[2] = max(mxv[2], v.z); mxv[3] = max(mxv[3], v.w);
+  }
+  for (int i = tid; i < 2 * kHistBins; i += NT) (&s_hist[0][0])[i] = 0;
+#pragma unroll
+  for (int off = M; off < 64; off <<= 1) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      mn[r] = min(mn[r], __shfl_xor(mn[r], off));
+      mxv[r] = max(mxv[r], __shfl_xor(mxv[r], off));
+    }
+  }
+  if (lane < M) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      s_mm[wv][lane][r] = mn[r];
+      s_mm[wv][lane][4 + r] = mxv[r];
+    }
+  }
+  __syncthreads();
+  if (tid < M * 8) {
+    const int m = tid / 8, c = tid % 8;
+    int32_t v = s_mm[0][m][c];
+    for (int w = 1; w < NW; ++w) v = c < 4 ? min(v, s_mm[w][m][c]) : max(v, s_mm[w][m][c]);
+    s_red[m][c] = v;
+  }
+  __syncthreads();
+  if (tid < kHeadsPerGroup) {
+    int32_t lo = 0, hi = 0;
+    for (int m = 0; m < M; ++m) {
+      lo += s_red[m][tid];
+      hi += s_red[m][4 + tid];
+    }
+    const uint32_t range = (uint32_t)(hi - lo);
+    int sh = 32 - __clz(range) - 11;   // smallest shift with (range >> shift) < 2048
+    s_lo[tid] = lo;
+    s_shift[tid] = sh < 0 ? 0 : sh;
+  }
+  __syncthreads();
+
+  // score this workgroup's share of the strided sample
+  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  const int lo0 = s_lo[0], lo1 = s_lo[1], lo2 = s_lo[2], lo3 = s_lo[3];
+  const int sh0 = s_shift[0], sh1 = s_shift[1], sh2 = s_shift[2], sh3 = s_shift[3];
+  for (int i = tid; i < s_p; i += NT) {
+    const long g = (long)p * s_p + i;
+    const int j = sr.sink_end + (int)((g * sr.ncand) / s_all);
+    uint4 w[M / 16];
+#pragma unroll
+    for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
+    int32_t acc[4];
+    score_four_heads<M>(w, lutv, acc);
+    atomicAdd(&s_hist[0][(uint32_t)(acc[0] - lo0) >> sh0], 1u);
+    atomicAdd(&s_hist[0][(uint32_t)(acc[1] - lo1) >> sh1], 1u << 16);
+    atomicAdd(&s_hist[1][(uint32_t)(acc[2] - lo2) >> sh2], 1u);
+    atomicAdd(&s_hist[1][(uint32_t)(acc[3] - lo3) >> sh3], 1u << 16);
+  }
+  __syncthreads();
+#pragma unroll 1
+  for (int r = 0; r < kHeadsPerGroup; ++r) {
+    block_find_rank_desc<NT, kHistBins>(
+        [&](int i) { return (s_hist[r >> 1][i] >> (16 * (r & 1))) & 0xffffu; }, (uint32_t)r_p, s_wave, s_res);
+    if (tid == 0) {
+      const int hg = g4 * kHeadsPerGroup + r;
+      // lower edge of the bin holding the r_p-th largest sample: at least r_p samples are >= it
+      if (hg < G)
+        thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = s_lo[r] + (int32_t)(s_res[0] << s_shift[r]);
+    }
+    __syncthreads();
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Fast route, stage 2: one pass over the code matrix
+// ------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(kStreamThreads) void stream_select_kernel(
+    const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
+    const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
+    uint32_t* __restrict__ cand_count, uint2* __restrict__ cand, int Hq, int Hkv, int NG, int P0,
+    int rows_per_chunk, int cap, int ctx_len, int64_t ctx_stride, int top_k, int window,
+    int n_sink) {
+  constexpr int NT = kStreamThreads;
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  int4* lutv = (int4*)dyn_lds;
+  uint2* stage_all = (uint2*)(dyn_lds + (size_t)kCentroids * M * sizeof(int4));
+
+  const int chunk = blockIdx.x, prob = blockIdx.y;
+  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
+  const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
+  const long begin = (long)sr.sink_end + (long)chunk * rows_per_chunk;
+  if (begin >= sr.win_start) return;
+  const int end = (int)min((long)sr.win_start, begin + rows_per_chunk);
+
+  load_group_lut<M, NT>(lut + (size_t)prob * (kCentroids * M * kHeadsPerGroup), lutv);
+
+  int32_t T[4];
+  size_t head[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int hg = g4 * kHeadsPerGroup + r;
+    head[r] = (size_t)b * Hq + kv * G + (hg < G ? hg : 0);
+    int32_t t = INT32_MAX;   // padded heads never produce candidates
+    if (hg < G) {
+      t = thr[head[r] * P0];
+      for (int pp = 1; pp < P0; ++pp) t = min(t, thr[head[r] * P0 + pp]);
+    }
+    T[r] = t;
+  }
+  __syncthreads();
+
+  uint2* stage = stage_all + (size_t)wv * kHeadsPerGroup * kStageCap;
+  int cnt[4] = {0, 0, 0, 0};
+
+  auto flush = [&](int r) {
+    const int n = cnt[r];
+    if (n == 0) return;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    uint32_t base = 0;
+    if (lane == 0) base = atomicAdd(&cand_count[head[r]], (uint32_t)n);
+    base = __shfl(base, 0);
+    for (int i = lane; i < n; i += 64)
+      if (base + i < (uint32_t)cap) cand[head[r] * cap + base + i] = stage[r * kStageCap + i];
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    cnt[r] = 0;
+  };
+
+  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  constexpr int U = 2;
+#pragma unroll 1
+  for (int base = (int)begin; base < end; base += NT * U) {
+    uint4 w[U][M / 16];
+    int jj[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      jj[u] = base + u * NT + tid;
+      const int jl = jj[u] < end ? jj[u] : end - 1;
+#pragma unroll
+      for (int qd = 0; qd < M / 16; ++qd)
+        w[u][qd] = *(const uint4*)(seq_codes + (size_t)jl * M + qd * 16);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int32_t acc[4];
+      score_four_heads<M>(w[u], lutv, acc);
+      const bool valid = jj[u] < end;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const bool pred = valid && acc[r] >= T[r];
+        const uint64_t mask = __ballot(pred);
+        if (mask) {
+          const int n = __popcll(mask);
+          if (cnt[r] + n > kStageCap) flush(r);
+          if (pred) stage[r * kStageCap + cnt[r] + lanes_below(mask)] = make_uint2((uint32_t)jj[u], (uint32_t)acc[r]);
+          cnt[r] += n;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) flush(r);
+}
+
+// ------------------------------------------------------------------------------------------
+// Fast route, stage 3: exact selection among the candidates, ordered output
+// ------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(kExactThreads) void final_select_kernel(
+    const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
+    const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
+    const uint32_t* __restrict__ cand_count, const uint2* __restrict__ cand,
+    int32_t* __restrict__ topk_idx, int32_t* __restrict__ topk_count,
+    float* __restrict__ topk_score, int Hq, int Hkv, int NG, int cap, int ctx_len,
+    int64_t ctx_stride, int top_k, int window, int n_sink) {
+  constexpr int NT = kExactThreads;
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  __shared__ ExactLds L;
+  const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq;
+  const int G = Hq / Hkv, kv = h / G, hg = h % G, tid = threadIdx.x;
+  const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
+  int32_t* oi = topk_idx + (size_t)bh * top_k;
+  float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
+  if (tid == 0) topk_count[bh] = sr.kk;
+  for (int t = sr.kk + tid; t < top_k; t += NT) {
+    oi[t] = -1;
+    if (os) os[t] = 0.f;
+  }
+  if (sr.kk == 0) return;
+  const float scale = lut_scale[bh];
+  const uint32_t n_c = cand_count[bh];
+  if (n_c > (uint32_t)cap || n_c < (uint32_t)sr.kk) {
+    const int32_t* lut_grp = lut + (((size_t)b * Hkv + kv) * NG + hg / kHeadsPerGroup) *
+                                       (kCentroids * M * kHeadsPerGroup);
+    exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M, lut_grp,
+                          hg % kHeadsPerGroup, scale, sr, oi, os, (int32_t*)dyn_lds, L);
+    return;
+  }
+
+  // LDS carve-up: candidate positions and keys, position bitmap, per-word prefix counts
+  const int n_words = (ctx_len + 31) / 32;
+  uint32_t* c_idx = (uint32_t*)dyn_lds;
+  uint32_t* c_key = c_idx + cap;
+  uint32_t* bitmap = c_key + cap;
+  uint16_t* wpre = (uint16_t*)(bitmap + n_words);
+  constexpr uint32_t kDropped = 0x80000000u;
+
+  for (uint32_t i = tid; i < n_c; i += NT) {
+    const uint2 e = cand[(size_t)bh * cap + i];
+    c_idx[i] = e.x;
+    c_key[i] = score_key((int32_t)e.y);
+  }
+  // K-th largest key among the candidates (MSB-first radix select, 11 + 11 + 10 bits)
+  uint32_t prefix = 0, mask = 0, k_rem = (uint32_t)sr.kk, n_eq = 0;
+#pragma unroll 1
+  for (int lvl = 0; lvl < 3; ++lvl) {
+    const int shift = lvl == 0 ? 21 : (lvl == 1 ? 10 : 0);
+    const uint32_t dmask = lvl == 2 ? 1023u : 2047u;
+    for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < n_c; i += NT) {
+      const uint32_t key = c_key[i];
+      if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
+    }
+    __syncthreads();
+    block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
+    const uint32_t bin = L.res[0], above = L.res[1];
+    n_eq = L.hist[bin];
+    k_rem -= above;
+    prefix |= bin << shift;
+    mask |= dmask << shift;
+    __syncthreads();
+  }
+  const uint32_t kth = prefix;
+
+  // Rank of a position among the set bits of the bitmap: prefix popcounts per 32-bit word.
+  const int wpt = (n_words + NT - 1) / NT;
+  auto build_word_prefix = [&](uint32_t* s_wave) {
+    uint32_t loc = 0;
+    for (int i = 0; i < wpt; ++i) {
+      const int w = tid * wpt + i;
+      if (w < n_words) loc += __popc(bitmap[w]);
+    }
+    uint32_t tot;
+    uint32_t run = block_exclusive_scan<NT>(loc, s_wave, tot);
+    for (int i = 0; i < wpt; ++i) {
+      const int w = tid * wpt + i;
+      if (w < n_words) {
+        wpre[w] = (uint16_t)run;
+        run += __popc(bitmap[w]);
+      }
+    }
+    __syncthreads();
+  };
+  auto rank_of = [&](uint32_t pos) -> uint32_t {
+    return (uint32_t)wpre[pos >> 5] + __popc(bitmap[pos >> 5] & ((1u << (pos & 31)) - 1u));
+  };
+
+  if (n_eq > k_rem) {   // more candidates tie with the K-th key than fit: lowest positions win
+    for (int w = tid; w < n_words; w += NT) bitmap[w] = 0;
+    __syncthreads();
+    for (uint32_t i = tid; i < n_c; i += NT)
+      if (c_key[i] == kth) atomicOr(&bitmap[c_idx[i] >> 5], 1u << (c_idx[i] & 31));
+    __syncthreads();
+    build_word_prefix(L.wave_a);
+    for (uint32_t i = tid; i < n_c; i += NT)
+      if (c_key[i] == kth && rank_of(c_idx[i]) >= k_rem) c_idx[i] |= kDropped;
+    __syncthreads();
+  }
+  for (int w = tid; w < n_words; w += NT) bitmap[w] = 0;
+  __syncthreads();
+  for (uint32_t i = tid; i < n_c; i += NT)
+    if (c_key[i] >= kth && !(c_idx[i] & kDropped)) atomicOr(&bitmap[c_idx[i] >> 5], 1u << (c_idx[i] & 31));
+  __syncthreads();
+  build_word_prefix(L.wave_b);
+  for (uint32_t i = tid; i < n_c; i += NT) {
+    if (c_key[i] >= kth && !(c_idx[i] & kDropped)) {
+      const uint32_t pos = rank_of(c_idx[i]);
+      oi[pos] = (int32_t)c_idx[i];
+      if (os) os[pos] = (float)key_score(c_key[i]) * scale;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------------
+static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+
+void set_profile_events(void* a, void* b) {
+  g_ev_start = (hipEvent_t)a;
+  g_ev_stop = (hipEvent_t)b;
+}
+
+template <typename K>
+static hipError_t allow_lds(K kernel, size_t bytes) {
+  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int M>
+static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan, const uint8_t* codes,
+                                      const int32_t* lut, const float* lut_scale, int top_k, int window,
+                                      int n_sink, const int32_t* seq_lens, int32_t* topk_idx,
+                                      int32_t* topk_count, float* topk_score, float* scores_out,
+                                      void* ws, hipStream_t stream) {
+  const int Hq = d.n_q_heads, Hkv = d.n_kv_heads, NG = plan.NG;
+  const int heads = d.batch * Hq, problems = d.batch * Hkv * NG;
+  const size_t lut4_bytes = (size_t)kCentroids * M * sizeof(int4);
+  const size_t lut1_bytes = (size_t)kCentroids * M * sizeof(int32_t);
+  hipError_t err;
+  if (heads == 0) return hipSuccess;
+
+  if (scores_out) {
+    if ((err = allow_lds(score_dense_kernel<M>, lut4_bytes)) != hipSuccess) return err;
+    int gx = (d.ctx_len + kStreamThreads * 8 - 1) / (kStreamThreads * 8);
+    gx = gx < 1 ? 1 : gx;
+    hipLaunchKernelGGL((score_dense_kernel<M>), dim3(gx, problems), dim3(kStreamThreads), lut4_bytes,
+                       stream, codes, lut, lut_scale, seq_lens, scores_out, Hq, Hkv, NG, d.ctx_len,
+                       d.ctx_stride);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+  }
+
+  if (!plan.fast) {
+    if ((err = allow_lds(select_exact_kernel<M>, lut1_bytes)) != hipSuccess) return err;
+    hipLaunchKernelGGL((select_exact_kernel<M>), dim3(heads), dim3(kExactThreads), lut1_bytes, stream,
+                       codes, lut, lut_scale, seq_lens, topk_idx, topk_count, topk_score, Hq, Hkv, NG,
+                       d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+    return hipGetLastError();
+  }
+
+  unsigned char* wsb = (unsigned char*)ws;
+  int32_t* thr = (int32_t*)(wsb + plan.off_thr);
+  uint32_t* cand_count = (uint32_t*)(wsb + plan.off_count);
+  uint2* cand = (uint2*)(wsb + plan.off_cand);
+
+  if ((err = allow_lds(sample_threshold_kernel<M>, lut4_bytes)) != hipSuccess) return err;
+  hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0, problems), dim3(kSampleThreads),
+                     lut4_bytes, stream, codes, lut, seq_lens, thr, cand_count, Hq, Hkv, NG, plan.P0,
+                     d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+  if ((err = hipGetLastError()) != hipSuccess) return err;
+
+  const size_t stream_lds =
+      lut4_bytes + (size_t)(kStreamThreads / 64) * kHeadsPerGroup * kStageCap * sizeof(uint2);
+  if ((err = allow_lds(stream_select_kernel<M>, stream_lds)) != hipSuccess) return err;
+  if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_start, stream);
+  hipLaunchKernelGGL((stream_select_kernel<M>), dim3(plan.chunks, problems), dim3(kStreamThreads),
+                     stream_lds, stream, codes, lut, seq_lens, thr, cand_count, cand, Hq, Hkv, NG,
+                     plan.P0, plan.rows_per_chunk, plan.cap, d.ctx_len, d.ctx_stride, top_k, window,
+                     n_sink);
+  if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_stop, stream);
+  if ((err = hipGetLastError()) != hipSuccess) return err;
+
+  const int n_words = (d.ctx_len + 31) / 32;
+  size_t final_lds = (size_t)plan.cap * 8 + (size_t)n_words * 4 + (size_t)n_words * 2;
+  if (final_lds < lut1_bytes) final_lds = lut1_bytes;
+  final_lds = (final_lds + 15) / 16 * 16;
+  if ((err = allow_lds(final_select_kernel<M>, final_lds)) != hipSuccess) return err;
+  hipLaunchKernelGGL((final_select_kernel<M>), dim3(heads), dim3(kExactThreads), final_lds, stream,
+                     codes, lut, lut_scale, seq_lens, cand_count, cand, topk_idx, topk_count,
+                     topk_score, Hq, Hkv, NG, plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const int32_t* lut,
+                             const float* lut_scale, int top_k, int window, int n_sink,
+                             const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
+                             float* topk_score, float* scores_out, void* ws, hipStream_t stream) {
+  const TopkPlan plan = make_topk_plan(d, top_k, window, n_sink);
+  if (d.n_sub == 16)
+    return launch_score_topk_m<16>(d, plan, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
+                                   topk_idx, topk_count, topk_score, scores_out, ws, stream);
+  return launch_score_topk_m<32>(d, plan, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
+                                 topk_idx, topk_count, topk_score, scores_out, ws, stream);
+}
+
+}  // namespace a2ats

@@ -1,0 +1,112 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+plans workspaces, builds rotation tables, and rejects bad arguments before touching a GPU."""
+import ctypes
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2502_12665_amd import binding as b
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2502_12665_amd import build
+        build.build()
+    return b
+
+
+def test_every_declared_symbol_is_exported(binding):
+    header = open(os.path.join(ROOT, "include", "a2ats.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(a2ats_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    L = binding.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert binding.version() >= 100
+    assert binding.status_string(0) == "ok" and "workspace" in binding.status_string(-3)
+
+
+def test_dims_validation_and_plans(binding):
+    good = binding.make_dims(4, 32, 8, 128, 16, 131072)
+    assert binding.lut_elems(good) == 4 * 8 * 1 * 256 * 16 * 4
+    g7 = binding.make_dims(2, 28, 4, 128, 32, 65536)
+    assert binding.lut_elems(g7) == 2 * 4 * 2 * 256 * 32 * 4
+    assert binding.workspace_bytes(good, binding.OP_LUT) == 0
+    assert binding.workspace_bytes(good, binding.OP_SCORE_TOPK, 2048, 256) > 128 * 8192 * 8
+    small = binding.make_dims(1, 4, 1, 128, 16, 4096)
+    assert binding.workspace_bytes(small, binding.OP_SCORE_TOPK, 128, 64) == 0
+    assert binding.workspace_bytes(good, binding.OP_ENCODE) == 8 * 16 * (64 + 256 * 8) * 4
+    L = binding.lib()
+    null = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(16)      # non-NULL, aligned, never dereferenced: validation fails first
+
+    def topk(d, top_k=8, window=4, n_sink=0, codes=one, ws=null, ws_bytes=0):
+        return L.a2ats_score_topk(ctypes.byref(d), codes, one, one, top_k, window, n_sink, null, one, one,
+                                  null, null, ws, ws_bytes, null)
+
+    bad = binding.make_dims(1, 4, 3, 128, 16, 64)              # Hq % Hkv != 0
+    assert topk(bad) == -1
+    bad = binding.make_dims(1, 4, 1, 128, 16, 64, sub_dim=4)   # M * ds != D
+    assert topk(bad) == -1
+    bad = binding.make_dims(1, 4, 1, 128, 16, 64, ctx_stride=32)
+    assert topk(bad) == -1
+    assert topk(binding.make_dims(1, 4, 1, 64, 8, 64)) == -2           # head_dim 64 not compiled
+    assert topk(binding.make_dims(1, 4, 1, 128, 16, 64, n_centroids=128, sub_dim=8)) == -2
+    assert topk(binding.make_dims(1, 16, 1, 128, 16, 64)) == -2        # group of 16
+    assert topk(small, top_k=-1) == -1
+    assert topk(small, window=-1) == -1
+    assert topk(small, codes=null) == -1
+    assert topk(small, codes=ctypes.c_void_p(8)) == -1                 # misaligned code matrix
+    assert topk(small, top_k=5000) == -2
+    assert topk(good, top_k=2048, window=256) == -3                    # fast route needs a workspace
+    assert topk(good, top_k=2048, window=256, ws=one, ws_bytes=1024) == -3
+    rc = L.a2ats_build_lut(ctypes.byref(small), one, 7, one, one, one, one, one, one, null)
+    assert rc == -1
+    rc = L.a2ats_encode_keys(ctypes.byref(small), one, 4, 4094, one, null, 0, one, null, 0, null)
+    assert rc == -1                                                     # pos0 + n_new > ctx_stride
+    rc = L.a2ats_encode_keys(ctypes.byref(small), one, 4, 0, one, null, 1, one, null, 0, null)
+    assert rc == -1                                                     # weighted mode without weights
+    rc = L.a2ats_encode_keys(ctypes.byref(small), one, 4, 0, one, one, 2, one, null, 0, null)
+    assert rc == -3
+    rc = L.a2ats_sparse_attn(ctypes.byref(small), one, one, one, one, 3, one, one, 8, 4, 0, one, one, null,
+                             one, null, 0, null)
+    assert rc == -1                                                     # unknown dtype
+    rc = L.a2ats_sparse_attn(ctypes.byref(good), one, one, one, one, 1, one, one, 2048, 256, 0, one, one,
+                             null, one, null, 0, null)
+    assert rc == -3                                                     # split attention needs a workspace
+    with pytest.raises(binding.A2atsError):
+        binding.workspace_bytes(bad, binding.OP_LUT)
+
+
+def test_rope_tables_against_numpy(binding):
+    from paper_2502_12665_amd import synth
+    inv = synth.inv_freq(128, 500000.0)
+    cb, sb, cw, sw = binding.rope_tables(128, inv, 2048, 64)
+    ang = 2048.0 * inv.numpy()
+    np.testing.assert_array_equal(cb.numpy(), np.cos(ang).astype(np.float32))
+    np.testing.assert_array_equal(sb.numpy(), np.sin(ang).astype(np.float32))
+    d = np.arange(64, dtype=np.float64)[:, None] * inv.numpy()[None, :]
+    np.testing.assert_array_equal(cw.numpy(), np.cos(d).astype(np.float32))
+    np.testing.assert_array_equal(sw.numpy(), np.sin(d).astype(np.float32))
+    assert cw[0].eq(1).all() and sw[0].eq(0).all()
+
+
+def test_product_path_does_not_touch_the_oracle():
+    """The package must not import or reference anything under oracle/ (no CPU fallback)."""
+    pkg = os.path.join(ROOT, "paper_2502_12665_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".cpp", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower() or f == "synth.py", f
+    text = open(os.path.join(pkg, "synth.py")).read()
+    assert "import oracle" not in text and "from oracle" not in text

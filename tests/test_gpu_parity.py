@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path, called through the C ABI binding, against the CPU oracle on the
+same seeded inputs.  Tolerances are stated in tests/helpers.py."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2502_12665_amd import binding as B
+from paper_2502_12665_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    B.lib()   # fails loudly if the library is not built
+
+
+def _run_and_check(oracle, wl, seq_lens=None, n_sink=None, ctx_stride=None, x=None, mutate=None):
+    x = synth.make_decode_inputs(wl, ctx_stride=ctx_stride) if x is None else x
+    if mutate is not None:
+        mutate(x)
+    xd = H.to_dev(x)
+    st = H.gpu_decode(wl, xd, seq_lens=seq_lens, n_sink=n_sink)
+    return st, H.check_step_against_oracle(oracle, wl, st, x, seq_lens=seq_lens, n_sink=n_sink)
+
+
+def test_tiny_shape_sweep_exact_route(oracle):
+    w = 16
+    n_cases = 0
+    for G, (N, K), n_sink in itertools.product((1, 4, 7), [(1, 1), (w, 7), (w + 1, 1), (w + 7, 7), (257, 0),
+                                                           (257, 7), (257, 257), (1000, 1), (1000, 7),
+                                                           (1000, 1000)], (0, 4)):
+        M = 32 if G == 7 else 16
+        wl = synth.Workload(f"sweep_G{G}_N{N}_K{K}_s{n_sink}", 2, 2 * G, 2, 128, M, N, K, w, n_sink=n_sink,
+                            kv_dtype="f32" if G == 1 else "bf16", rope_base=10000.0, seed=N + K + G)
+        H.log(wl.name)
+        _run_and_check(oracle, wl, ctx_stride=N + 5)
+        n_cases += 1
+    # ragged lengths, including an empty sequence and one shorter than the window
+    wl = synth.Workload("sweep_ragged", 4, 8, 2, 128, 16, 600, 9, w, n_sink=4, seed=3)
+    H.log(wl.name)
+    _run_and_check(oracle, wl, seq_lens=[600, 0, 11, 333], ctx_stride=640)
+    assert n_cases == 60
+
+
+def test_config1_tiny(oracle):
+    wl = synth.WORKLOADS["c1_tiny"]
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl)
+    H.log(f"{wl.name}: {res}")
+    # table parity (1e-4 relative) against the oracle's float64 table
+    x = synth.make_decode_inputs(wl)
+    lut = oracle.lut(oracle.rope(x["q"], x["inv_freq"], wl.wrope_b), x["codebook"], wl.n_q_heads)
+    H.check_scores(H.lut_as_float(st, wl), lut, "table")
+
+
+@pytest.mark.parametrize("name,G,M,N,K,w,n_sink,seq_lens,stride", [
+    ("fast_m16_g4", 4, 16, 20000, 600, 128, 0, None, None),
+    ("fast_m16_g4_ragged", 4, 16, 24000, 512, 64, 4, [24000, 17001, 300, 0], 24064),
+    ("fast_m32_g7", 7, 32, 18000, 500, 100, 4, [18000, 16500], 18016),
+    ("fast_m16_g1_k1", 1, 16, 40000, 1, 64, 0, None, None),
+    ("fast_m16_g8", 8, 16, 17000, 2048, 256, 0, None, None),
+])
+def test_fast_route_medium(oracle, name, G, M, N, K, w, n_sink, seq_lens, stride):
+    Bn = len(seq_lens) if seq_lens else 2
+    wl = synth.Workload(name, Bn, 2 * G, 2, 128, M, N, K, w, n_sink=n_sink, seed=11)
+    H.log(wl.name)
+    dims = H.dims_of(wl, stride)
+    assert B.workspace_bytes(dims, B.OP_SCORE_TOPK, K, w) > 0, "expected the fast route"
+    st, res = _run_and_check(oracle, wl, seq_lens=seq_lens, ctx_stride=stride)
+    H.log(f"{name}: {res}")
+
+
+def test_config2_llama8b_32k(oracle):
+    wl = synth.WORKLOADS["c2_llama8b_32k"]
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl)
+    H.log(f"{wl.name}: {res}")
+    x = synth.make_decode_inputs(wl, with_kv=False)
+    lut = oracle.lut(oracle.rope(x["q"], x["inv_freq"], wl.wrope_b), x["codebook"], wl.n_q_heads)
+    H.check_scores(H.lut_as_float(st, wl), lut, "table")
+
+
+def test_exact_ties_go_to_the_lowest_position(oracle):
+    # (a) every code row identical: all scores equal, the fast route's candidate list overflows
+    #     and the in-kernel exact fallback must return the first K candidates
+    wl = synth.Workload("ties_all_equal", 1, 4, 1, 128, 16, 20000, 300, 64, n_sink=4, seed=5)
+
+    def all_same(x):
+        x["codes"][:] = x["codes"][:, :, :1]
+    H.log(wl.name)
+    st, _ = _run_and_check(oracle, wl, mutate=all_same)
+    want = np.arange(4, 304, dtype=np.int32)
+    for h in range(4):
+        np.testing.assert_array_equal(st.topk_idx.cpu().numpy()[0, h], want)
+    # (b) rows drawn from 40 distinct patterns: ~500 exact copies of each score, so the K-th key is
+    #     shared by many candidates and the position tie-break inside the candidate list decides
+    wl = synth.Workload("ties_few_patterns", 2, 8, 2, 128, 16, 20000, 700, 64, seed=6)
+
+    def few_patterns(x):
+        g = torch.Generator().manual_seed(1)
+        pick = torch.randint(0, 40, (wl.batch, wl.n_kv_heads, wl.ctx_len), generator=g)
+        pat = x["codes"][:, :, :40].clone()
+        x["codes"][:, :, :wl.ctx_len] = torch.gather(pat, 2, pick[..., None].expand(-1, -1, -1, wl.n_sub))
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl, mutate=few_patterns)
+    assert res["excluded"] == 0
+    # (c) same on the exact route
+    wl = synth.Workload("ties_few_patterns_exact", 1, 4, 1, 128, 16, 3000, 100, 64, seed=7)
+
+    def few_patterns_small(x):
+        g = torch.Generator().manual_seed(2)
+        pick = torch.randint(0, 7, (1, 1, wl.ctx_len), generator=g)
+        pat = x["codes"][:, :, :7].clone()
+        x["codes"][:, :, :wl.ctx_len] = torch.gather(pat, 2, pick[..., None].expand(-1, -1, -1, wl.n_sub))
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl, mutate=few_patterns_small)
+    assert res["excluded"] == 0
+
+
+def test_attention_with_oracle_indices_and_full_retrieval(oracle):
+    """a5 alone: feed the oracle's own top-K to the GPU attention; and K >= n - w gives dense WRoPE."""
+    wl = synth.Workload("attn_only", 2, 8, 2, 128, 16, 3000, 200, 64, n_sink=4, seed=9)
+    x = synth.make_decode_inputs(wl)
+    ref = H.oracle_decode(oracle, wl, x)
+    xd = H.to_dev(x)
+    st = H.gpu_decode(wl, xd)
+    st.topk_idx.copy_(torch.from_numpy(ref["idx"]))
+    st.topk_count.copy_(torch.from_numpy(ref["cnt"]))
+    B.sparse_attn(st.dims, xd["q"], st.q_rot, xd["k"], xd["v"], st.topk_idx, st.topk_count, wl.top_k,
+                  wl.window, wl.n_sink, st.cos_win, st.sin_win, None, st.out, st.ws)
+    torch.cuda.synchronize()
+    err = np.abs(st.out.float().cpu().numpy() - ref["out"]).max()
+    H.log(f"attention with oracle indices: err {err:.3e}")
+    assert err <= 2e-2
+    for dt, tol in (("f32", 2e-4), ("bf16", 2e-2)):
+        wl2 = synth.Workload("attn_dense", 2, 8, 2, 128, 16, 700, 700, 64, n_sink=0, kv_dtype=dt, seed=10)
+        x2 = synth.make_decode_inputs(wl2)
+        st2 = H.gpu_decode(wl2, H.to_dev(x2))
+        dense = oracle.dense_wrope_attn(x2["q"], x2["k"], x2["v"], wl2.ctx_len, wl2.window, x2["inv_freq"],
+                                        float(wl2.wrope_b))
+        err = np.abs(st2.out.float().cpu().numpy() - dense).max()
+        H.log(f"K = n - w, {dt}: err vs dense WRoPE {err:.3e}")
+        assert err <= tol
+
+
+@pytest.mark.parametrize("M,mode", [(16, "none"), (16, "diag"), (16, "block"), (32, "none"), (32, "diag"),
+                                    (32, "block")])
+def test_encode_keys(oracle, M, mode):
+    wl = synth.Workload(f"enc_m{M}_{mode}", 2, 8, 2, 128, M, 2048, 16, 16, seed=21)
+    hm = synth.make_query_second_moment(wl)
+    cb = synth.make_codebook(wl)
+    code = {"none": B.W_NONE, "diag": B.W_DIAG, "block": B.W_BLOCK}[mode]
+    weights = {"none": None, "diag": hm["h_diag"], "block": hm["h_block"]}[mode]
+    dims = H.dims_of(wl, 2100)
+    ws = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+    for n_new, pos0, stress in ((1000, 37, False), (777, 0, True), (1, 2099, False)):
+        H.log(f"{wl.name} n_new={n_new} stress={stress}")
+        keys = synth.make_encode_keys(wl, n_new, stress=stress)
+        codes = torch.full((wl.batch, wl.n_kv_heads, 2100, M), 0xEE, dtype=torch.uint8, device="cuda")
+        B.encode_keys(dims, keys.cuda(), n_new, pos0, cb.cuda(), None if weights is None else weights.cuda(),
+                      code, codes, ws)
+        torch.cuda.synchronize()
+        got = codes.cpu().numpy()
+        want, b1, b2 = oracle.encode(keys, cb, weights, code, want_margins=True)
+        n_near = H.compare_codes(got[:, :, pos0:pos0 + n_new], want, b1, b2)
+        assert (got[:, :, :pos0] == 0xEE).all() and (got[:, :, pos0 + n_new:] == 0xEE).all()
+        if mode != "none" and stress:
+            plain = oracle.encode(keys, cb)
+            assert (want != plain).mean() > 0.02, "weighting should matter on the stress keys"
+        H.log(f"  near-tie exclusions: {n_near}")
+
+
+def test_run_to_run_determinism():
+    wl = synth.Workload("determinism", 2, 8, 2, 128, 16, 30000, 900, 128, seed=4)
+    xd = H.to_dev(synth.make_decode_inputs(wl))
+    outs = []
+    for _ in range(3):
+        st = H.gpu_decode(wl, xd, want_scores=False)
+        outs.append((st.topk_idx.cpu().clone(), st.topk_score.cpu().clone(), st.out.cpu().clone()))
+    for o in outs[1:]:
+        assert torch.equal(o[0], outs[0][0]) and torch.equal(o[1], outs[0][1])
+        assert torch.equal(o[2].view(torch.int16), outs[0][2].view(torch.int16))
