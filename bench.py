@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the A2ATS decode-time retrieval path on one MI355X.
+
+A step is one pass of the whole hot path for one transformer layer over one batch:
+encode the current token's key (query-aware distortion, one key per sequence and KV head),
+rotate the query and build the lookup tables, score every cached token and select the top-K,
+run selective attention.  Inputs are synthetic (seeded) and resident in HBM before the timed
+region.  To keep the 256 MB Infinity Cache from serving the code matrix, the step rotates
+over R independent replicas of every input (R "layers"), so consecutive touches of one
+replica are separated by the other replicas' traffic.
+
+Prints ONE JSON line (see the keys below); `value` is scored key rows per second over whole
+steps.  The `roofline` object is for the code-streaming kernel, timed with HIP events
+recorded by the library immediately around that launch.
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs (the library records them on the stream it launches on)."""
+
+    def __init__(self, n):
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.ev = []
+        for _ in range(2 * n):
+            e = ctypes.c_void_p()
+            rc = self.hip.hipEventCreate(ctypes.byref(e))
+            assert rc == 0, rc
+            self.ev.append(e)
+
+    def pair(self, i):
+        return self.ev[2 * i].value, self.ev[2 * i + 1].value
+
+    def elapsed_ms(self, i):
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.ev[2 * i], self.ev[2 * i + 1])
+        assert rc == 0, rc
+        return ms.value
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="c4_long_128k")
+    ap.add_argument("--replicas", type=int, default=8, help="independent input sets cycled through (cold cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_12665_amd import binding as B
+    from paper_2502_12665_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    R = max(1, args.replicas)
+    dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)
+    N, Bn, Hq, Hkv, M, D, K, w = wl.ctx_len, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.n_sub, wl.head_dim, \
+        wl.top_k, wl.window
+
+    # ---- inputs, resident in HBM
+    reps = []
+    for r in range(R):
+        x = synth.make_decode_inputs(wl.replace(seed=wl.seed + r), device="cuda")
+        x["new_key"] = x["k"][:, :, N - 1:N, :].float().contiguous()
+        reps.append(x)
+    hm = synth.make_query_second_moment(wl)
+    h_diag = hm["h_diag"].cuda()
+    st = B.DecodeState(dims, K, w, wl.n_sink, reps[0]["q"].dtype, reps[0]["inv_freq"], wl.wrope_b)
+    cand_counts = torch.empty(Bn, Hq, dtype=torch.int32, device="cuda")
+
+    n_ev = args.steps
+    kev = HipEvents(n_ev)
+    phase_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+
+    def step(i, timed):
+        x = reps[i % R]
+        if timed:
+            phase_ev[i][0].record()
+        B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
+        if timed:
+            phase_ev[i][1].record()
+        B.build_lut(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, st.lut, st.lut_scale)
+        if timed:
+            phase_ev[i][2].record()
+            B.profile_stream_kernel(*kev.pair(i))
+        B.score_topk(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx, st.topk_count,
+                     None, None, st.ws)
+        if timed:
+            phase_ev[i][3].record()
+        elif i == 0:   # candidate-list sizes, read before the attention reuses the workspace
+            B.score_topk_stats(dims, K, w, wl.n_sink, st.ws, cand_counts)
+        B.sparse_attn(dims, x["q"], st.q_rot, x["k"], x["v"], st.topk_idx, st.topk_count, K, w, wl.n_sink,
+                      st.cos_win, st.sin_win, None, st.out, st.ws)
+        if timed:
+            phase_ev[i][4].record()
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    B.profile_stream_kernel(None, None)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ph = [[phase_ev[i][p].elapsed_time(phase_ev[i][p + 1]) * 1e3 for i in range(args.steps)] for p in range(4)]
+    med = lambda v: float(sorted(v)[len(v) // 2])
+    mean = lambda v: float(sum(v) / len(v))
+    cc = cand_counts.cpu().numpy().astype("int64")
+    fast_route = bool((cc >= 0).all())   # the exact-only route reports 0xFFFFFFFF (-1 as int32)
+    kern_us = [kev.elapsed_ms(i) * 1e3 for i in range(args.steps)] if fast_route else [float("nan")]
+
+    rows = Bn * Hkv * N
+    code_bytes = rows * M
+    lut_bytes = Bn * Hq * M * 256 * 4
+    idx_bytes = Bn * Hq * K * 4
+    phase_bytes = code_bytes + lut_bytes + idx_bytes          # score + top-K phase
+    kernel_bytes = code_bytes + lut_bytes                      # what the streaming kernel must read
+    e = 2 if wl.kv_dtype == "bf16" else 4
+    attn_bytes = Bn * Hq * min(K, N - w) * 2 * D * e + Bn * Hkv * w * 2 * D * e
+    k_us = mean(kern_us)
+    achieved = kernel_bytes / (k_us * 1e-6) / 1e9 if k_us == k_us else None
+
+    out = {
+        "metric": "scored keys/s (whole decode step: encode 1 key + WRoPE/LUT + score/top-K + sparse attention)",
+        "value": rows / (ms_per_step * 1e-3),
+        "unit": "keys/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 fixed-point scores; bf16 K/V with f32 accumulate" if wl.kv_dtype == "bf16" else
+                 "int32 fixed-point scores; f32 K/V",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": Bn, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D,
+                   "n_sub": M, "ctx_len": N, "top_k": K, "window": w, "replicas_cycled": R},
+        "us_per_decode_step": ms_per_step * 1e3,
+        "phase_us_median": {"encode_1key": med(ph[0]), "wrope_lut": med(ph[1]), "score_topk": med(ph[2]),
+                            "sparse_attn": med(ph[3])},
+        "score_topk_phase": {"scored_keys_per_s": rows / (med(ph[2]) * 1e-6),
+                             "query_head_scores_per_s": Bn * Hq * N / (med(ph[2]) * 1e-6),
+                             "algorithmic_bytes": phase_bytes,
+                             "GBps": phase_bytes / (med(ph[2]) * 1e-6) / 1e9,
+                             "frac_of_hbm_peak": phase_bytes / (med(ph[2]) * 1e-6) / 1e9 / HBM_PEAK_GBS},
+        "sparse_attn_phase": {"algorithmic_bytes": attn_bytes,
+                              "GBps": attn_bytes / (med(ph[3]) * 1e-6) / 1e9,
+                              "frac_of_hbm_peak": attn_bytes / (med(ph[3]) * 1e-6) / 1e9 / HBM_PEAK_GBS},
+        "candidates_per_head": {"mean": float(cc.mean()), "max": int(cc.max()), "min": int(cc.min())}
+        if fast_route else None,
+        "roofline": {"kernel": "stream_select_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                     "traffic": None, "algorithmic_bytes_per_launch": kernel_bytes,
+                     "avg_launch_us": k_us if k_us == k_us else None},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        nb = min(2, Bn)
+        x = reps[0]
+        xc = {k: x[k][:nb].cpu() for k in ("q", "codes", "k", "v")}
+        cb = x["codebook"].cpu()
+        inv = x["inv_freq"]
+        nk = x["new_key"][:nb].cpu()
+        t0 = time.perf_counter()
+        orc.encode(nk, cb, hm["h_diag"], orc.W_DIAG)
+        qrot = orc.rope(xc["q"], inv, wl.wrope_b)
+        sc = orc.scores_explicit(qrot, cb, xc["codes"], N)
+        idx, cnt, kth = orc.topk(sc, K, w, wl.n_sink)
+        orc.sparse_attn(xc["q"], xc["k"], xc["v"], idx, cnt, N, w, wl.n_sink, inv, float(wl.wrope_b))
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": nb * Hkv * N / dt, "unit": "keys/s", "cores": orc.threads(),
+                               "kind": "oracle",
+                               "sample": f"one whole decode step for batch elements 0..{nb - 1} of {Bn} "
+                                         f"({nb * Hkv} of {Bn * Hkv} (sequence, KV head) problems), {dt:.2f} s"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

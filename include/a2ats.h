@@ -101,7 +101,8 @@ int a2ats_rope_tables(int32_t head_dim, const double* inv_freq, int32_t b, int32
  *   codes    [dev, u8   B*Hkv*ctx_stride*M] rows pos0 .. pos0+n_new-1 are written
  * Distances are evaluated in float32 and re-evaluated in float64 from the definition
  * whenever the two smallest are closer than 1e-4 relative, so codes equal the float64
- * argmin.  Needs no workspace.  n_new == 0 is a no-op.
+ * argmin.  The weighted modes need a2ats_workspace_bytes(dims, A2ATS_OP_ENCODE, 0, 0) bytes
+ * of workspace (transformed centroids); A2ATS_W_NONE needs none.  n_new == 0 is a no-op.
  */
 int a2ats_encode_keys(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
                       const float* codebook, const float* weights, int weight_mode,
@@ -124,7 +125,7 @@ int a2ats_build_lut(const a2ats_dims* dims, const void* q, int q_dtype, const fl
                     float* lut_scale, void* stream);
 
 /*
- * Steps 3 of a decode step: approximate scores for every cached token by gather-summing
+ * Step 3 of a decode step: approximate scores for every cached token by gather-summing
  * table entries through its codes, then exact top-K (paper section 4: "retrieves the
  * top-K tokens with the highest attention scores").  For sequence b with n tokens the
  * candidates are positions [sink_end, n - window), sink_end = min(n_sink, max(0, n - window)):
@@ -165,6 +166,16 @@ int a2ats_sparse_attn(const a2ats_dims* dims, const void* q, const float* q_rot,
                       const int32_t* topk_idx, const int32_t* topk_count, int32_t top_k,
                       int32_t window, int32_t n_sink, const float* cos_win, const float* sin_win,
                       const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Diagnostics (not part of the method): after an a2ats_score_topk call with the same dims /
+ * top_k / window / n_sink and the same `ws`, copy the per-head size of the candidate list the
+ * streaming pass produced into cand_counts [dev, out, uint32 B*Hq] (asynchronously, on
+ * `stream`).  A head took the in-kernel exact fallback iff its count is below its K' or above
+ * 8192.  For shapes served by the exact route alone every entry is set to 0xFFFFFFFF.
+ */
+int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink,
+                           const void* ws, uint32_t* cand_counts, void* stream);
 
 /*
  * Profiling aid (not part of the method): when both events are non-NULL, the next

@@ -20,7 +20,7 @@ W_NONE, W_DIAG, W_BLOCK = 0, 1, 2
 OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN = 0, 1, 2, 3
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
-           "a2ats_sparse_attn", "a2ats_profile_stream_kernel"]
+           "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel"]
 
 
 class A2atsError(RuntimeError):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.a2ats_sparse_attn.restype = ctypes.c_int
         L.a2ats_sparse_attn.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, vp,
                                         vp, vp, vp, sz, vp]
+        L.a2ats_score_topk_stats.restype = ctypes.c_int
+        L.a2ats_score_topk_stats.argtypes = [dp, i32, i32, i32, vp, vp, vp]
         L.a2ats_profile_stream_kernel.restype = None
         L.a2ats_profile_stream_kernel.argtypes = [vp, vp]
         _lib = L
@@ -165,6 +167,12 @@ def sparse_attn(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_count, to
                                  _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _ptr(ws),
                                  0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_sparse_attn")
+
+
+def score_topk_stats(dims: Dims, top_k: int, window: int, n_sink: int, ws, cand_counts):
+    rc = lib().a2ats_score_topk_stats(ctypes.byref(dims), top_k, window, n_sink, _ptr(ws), _ptr(cand_counts),
+                                      _stream())
+    _check(rc, "a2ats_score_topk_stats")
 
 
 def profile_stream_kernel(ev_start: Optional[int], ev_stop: Optional[int]):

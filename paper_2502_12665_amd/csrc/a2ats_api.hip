@@ -167,6 +167,17 @@ int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, co
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
+int a2ats_score_topk_stats(const a2ats_dims* d, int32_t top_k, int32_t window, int32_t n_sink, const void* ws,
+                           uint32_t* cand_counts, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (top_k < 0 || window < 0 || n_sink < 0 || !cand_counts) return A2ATS_ERR_INVALID_ARG;
+  const a2ats::TopkPlan plan = a2ats::make_topk_plan(*d, top_k, window, n_sink);
+  if (plan.fast && !ws) return A2ATS_ERR_WORKSPACE;
+  const hipError_t e = a2ats::copy_topk_stats(*d, top_k, window, n_sink, ws, cand_counts, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
 void a2ats_profile_stream_kernel(void* ev_start, void* ev_stop) { a2ats::set_profile_events(ev_start, ev_stop); }
 
 }  // extern "C"

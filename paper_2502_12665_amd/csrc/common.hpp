@@ -121,6 +121,13 @@ __device__ __forceinline__ SeqRange seq_range(int ctx_len, const int32_t* seq_le
   return r;
 }
 
+// 16-byte load that tells the caches the line will not be reused (streamed data).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream_u4(const void* p) {
+  const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // Round-to-nearest-even float -> bf16 (finite inputs; NaN is kept a NaN).

@@ -30,6 +30,8 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink);
 AttnPlan make_attn_plan(const a2ats_dims& d, int top_k, int window, int n_sink);
 size_t encode_ws_bytes(const a2ats_dims& d);
 void set_profile_events(void* ev_start, void* ev_stop);
+hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sink, const void* ws,
+                           uint32_t* cand_counts, hipStream_t stream);
 
 hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                             const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,

@@ -31,7 +31,9 @@ namespace a2ats {
 constexpr int kExactThreads = 1024;
 constexpr int kStreamThreads = 512;
 constexpr int kSampleThreads = 512;
-constexpr int kStageCap = 64;        // wave-private staging entries per head
+constexpr int kStageCap = 64;        // wave-private LDS staging entries per head (>= one ballot)
+constexpr int kSubCap = 128;         // candidate slots a wave owns in HBM, per head
+constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kSampleRows = 1024;    // rows scored by one sampling workgroup
 constexpr float kSigma = 5.0f;
 
@@ -54,15 +56,18 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     const long max_chunks = (ncand + 2047) / 2048;
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
+    if (chunks > 64) chunks = 64;
     long rpc = (ncand + chunks - 1) / chunks;
     rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
     p.chunks = (int)((ncand + rpc - 1) / rpc);
     p.rows_per_chunk = (int)rpc;
     const size_t heads = (size_t)d.batch * d.n_q_heads;
     p.off_thr = 0;
+    // one candidate segment (count + kSubCap slots) per head, chunk and wave of the streaming pass
+    const size_t segs = heads * p.chunks * kStreamWaves;
     p.off_count = p.off_thr + heads * p.P0 * sizeof(int32_t);
-    p.off_cand = (p.off_count + heads * sizeof(uint32_t) + 255) / 256 * 256;
-    p.bytes = p.off_cand + heads * (size_t)p.cap * sizeof(uint2);
+    p.off_cand = (p.off_count + segs * sizeof(uint32_t) + 255) / 256 * 256;
+    p.bytes = p.off_cand + segs * (size_t)kSubCap * sizeof(uint2);
   }
   return p;
 }
@@ -71,7 +76,8 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
 // Scoring primitives
 // ------------------------------------------------------------------------------------------
 
-// Score of one token for one head from a [c][m] single-head table in LDS.
+// Score of one token for one head from an [m][c] single-head table in LDS (random c -> random
+// banks; a [c][m] order would put every lane of a read on the same two banks).
 template <int M>
 __device__ __forceinline__ int32_t score_one_head(const uint8_t* row, const int32_t* lut1) {
   int32_t s = 0;
@@ -82,34 +88,77 @@ __device__ __forceinline__ int32_t score_one_head(const uint8_t* row, const int3
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const uint32_t byte = (ww[i >> 2] >> (8 * (i & 3))) & 0xffu;
-      s += lut1[byte * M + qd * 16 + i];
+      s += lut1[(qd * 16 + i) * kCentroids + byte];
     }
   }
   return s;
 }
 
-// Scores of one token for the four heads of a group from the [c][m][4] table in LDS.
+// Scores of one token for the four heads of a group from the table in LDS, which is held as
+// [M/16 halves][256 c][16 m][4 heads] (for M = 16 this is the global [c][m][4] order).
+//
+// LDS serves a 16-byte read 8 lanes at a time (128 B per clock); lanes whose addresses agree
+// modulo 128 B collide.  With the table stored [c][m][4] (256 B per centroid row, subspace m
+// at byte 16*m of the row) the bank group of a read is m mod 8, whatever the code byte is.
+// Lane L therefore visits the subspaces of its row in the order m = t ^ (L & 15), t = 0..15
+// (per 16-byte half row): in every read the 8 lanes served together touch 8 different bank
+// groups, so random codes cause no conflicts.  The order does not matter for the result
+// because scores are integer sums.
+template <int M>
+struct LaneSwizzle {
+  uint32_t mc[M / 4];   // byte t&3 of mc[t>>2]: (m & 15) << 4 for step t of this lane
+  uint32_t sel[4];      // v_perm selectors: address byte 1 <- code byte (k ^ b), byte 0 <- mc byte k
+  bool swap1, swap2;    // dword index of the row is XORed with (rho >> 2)
+  __device__ __forceinline__ void init(int lane) {
+    const uint32_t rho = lane & 15, b = rho & 3;
+#pragma unroll
+    for (int d = 0; d < M / 4; ++d) {
+      uint32_t v = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) v |= ((((uint32_t)(4 * d + k) ^ rho) & 15u) << 4) << (8 * k);
+      mc[d] = v;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) sel[k] = 0x0c0c0000u | ((4u + ((uint32_t)k ^ b)) << 8) | (uint32_t)k;
+    swap1 = (rho >> 2) & 1;
+    swap2 = (rho >> 3) & 1;
+  }
+};
+
 template <int M>
 __device__ __forceinline__ void score_four_heads(const uint4 (&w)[M / 16], const int4* lutv,
-                                                 int32_t (&acc)[4]) {
+                                                 const LaneSwizzle<M>& sw, int32_t (&acc)[4]) {
   acc[0] = acc[1] = acc[2] = acc[3] = 0;
+  const unsigned char* base = (const unsigned char*)lutv;
 #pragma unroll
   for (int qd = 0; qd < M / 16; ++qd) {
-    const uint32_t ww[4] = {w[qd].x, w[qd].y, w[qd].z, w[qd].w};
+    // z[d] = row dword (d ^ (rho >> 2))
+    const uint32_t x0 = sw.swap1 ? w[qd].y : w[qd].x, x1 = sw.swap1 ? w[qd].x : w[qd].y;
+    const uint32_t x2 = sw.swap1 ? w[qd].w : w[qd].z, x3 = sw.swap1 ? w[qd].z : w[qd].w;
+    const uint32_t z[4] = {sw.swap2 ? x2 : x0, sw.swap2 ? x3 : x1, sw.swap2 ? x0 : x2, sw.swap2 ? x1 : x3};
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const uint32_t byte = (ww[i >> 2] >> (8 * (i & 3))) & 0xffu;
-      const int4 e = lutv[byte * M + qd * 16 + i];
+    for (int t = 0; t < 16; ++t) {
+      // (code byte << 8) | (m << 4): byte offset of entry [c][m] inside this half's 64 KB table
+      const uint32_t off = __builtin_amdgcn_perm(z[t >> 2], sw.mc[qd * 4 + (t >> 2)], sw.sel[t & 3]);
+      const int4 e = *(const int4*)(base + qd * 65536 + off);
       acc[0] += e.x; acc[1] += e.y; acc[2] += e.z; acc[3] += e.w;
     }
   }
+}
+
+// LDS slot of global table entry e = c * M + m.
+template <int M>
+__device__ __forceinline__ int lds_slot(int e) {
+  if (M == 16) return e;
+  const int c = e / M, m = e % M;
+  return (m >> 4) * (kCentroids * 16) + c * 16 + (m & 15);
 }
 
 template <int M, int NT>
 __device__ __forceinline__ void load_group_lut(const int32_t* __restrict__ lut_grp, int4* lutv) {
   const int4* src = (const int4*)lut_grp;
 #pragma unroll 4
-  for (int e = threadIdx.x; e < kCentroids * M; e += NT) lutv[e] = src[e];
+  for (int e = threadIdx.x; e < kCentroids * M; e += NT) lutv[lds_slot<M>(e)] = src[e];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -120,6 +169,7 @@ struct ExactLds {
   uint32_t wave_a[kExactThreads / 64];
   uint32_t wave_b[kExactThreads / 64];
   uint32_t res[2];
+  int32_t sub_min[32], sub_max[32];
 };
 
 // Exact top-K for one head by the whole workgroup.  `lut1` is kCentroids*M words of LDS.
@@ -132,21 +182,51 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
                                    float* __restrict__ out_score, int32_t* lut1, ExactLds& L) {
   constexpr int NT = kExactThreads;
   const int tid = threadIdx.x;
-  for (int e = tid; e < kCentroids * M; e += NT) lut1[e] = lut_grp[e * kHeadsPerGroup + r];
+  for (int e = tid; e < kCentroids * M; e += NT)   // e = c * M + m in the global order
+    lut1[(e % M) * kCentroids + e / M] = lut_grp[e * kHeadsPerGroup + r];
   __syncthreads();
 
   const int lo = sr.sink_end, hi = sr.win_start;
   uint32_t kth = 0, k_rem = (uint32_t)sr.kk;
   if (sr.kk < sr.ncand) {
+    // Bounds of any score (sum of per-subspace minima / maxima): radix digits are taken from
+    // key - key(lower bound), so that the histogram bins spread over the occupied range
+    // instead of all keys sharing their leading bits.
+    if (tid < 32) {
+      L.sub_min[tid] = INT32_MAX;
+      L.sub_max[tid] = INT32_MIN;
+    }
+    __syncthreads();
+    for (int e = tid; e < kCentroids * M; e += NT) {   // e = m * 256 + c: a wave covers one m
+      int32_t mn = lut1[e], mx = mn;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) {
+        mn = min(mn, __shfl_xor(mn, off));
+        mx = max(mx, __shfl_xor(mx, off));
+      }
+      if ((tid & 63) == 0) {
+        atomicMin(&L.sub_min[e / kCentroids], mn);
+        atomicMax(&L.sub_max[e / kCentroids], mx);
+      }
+    }
+    __syncthreads();
+    int32_t s_lo = 0, s_hi = 0;
+    for (int m = 0; m < M; ++m) {
+      s_lo += L.sub_min[m];
+      s_hi += L.sub_max[m];
+    }
+    const uint32_t k_lo = score_key(s_lo);
+    int remaining = 32 - __clz(score_key(s_hi) - k_lo);   // significant bits of a relative key
     uint32_t prefix = 0, mask = 0;
 #pragma unroll 1
-    for (int lvl = 0; lvl < 3; ++lvl) {
-      const int shift = lvl == 0 ? 21 : (lvl == 1 ? 10 : 0);
-      const uint32_t dmask = lvl == 2 ? 1023u : 2047u;
+    while (remaining > 0) {
+      const int bits = remaining < 11 ? remaining : 11;
+      const int shift = remaining - bits;
+      const uint32_t dmask = (1u << bits) - 1u;
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       __syncthreads();
       for (int j = lo + tid; j < hi; j += NT) {
-        const uint32_t key = score_key(score_one_head<M>(seq_codes + (size_t)j * M, lut1));
+        const uint32_t key = score_key(score_one_head<M>(seq_codes + (size_t)j * M, lut1)) - k_lo;
         if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
       }
       __syncthreads();
@@ -155,11 +235,12 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
       k_rem -= above;
       prefix |= bin << shift;
       mask |= dmask << shift;
+      remaining = shift;
       __syncthreads();
     }
-    kth = prefix;
+    kth = prefix + k_lo;
   } else {
-    kth = 0;  // every candidate is taken: all keys >= 0
+    kth = 0;  // every candidate is taken
     k_rem = (uint32_t)sr.kk;
   }
 
@@ -236,6 +317,8 @@ __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
   int n = seq_lens ? seq_lens[b] : ctx_len;
   n = n < 0 ? 0 : (n > ctx_len ? ctx_len : n);
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  LaneSwizzle<M> sw;
+  sw.init(threadIdx.x & 63);
   float sc[4];
   for (int r = 0; r < 4; ++r) {
     const int hg = g4 * kHeadsPerGroup + r;
@@ -246,7 +329,7 @@ __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
 #pragma unroll
     for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
     int32_t acc[4];
-    score_four_heads<M>(w, lutv, acc);
+    score_four_heads<M>(w, lutv, sw, acc);
     for (int r = 0; r < 4; ++r) {
       const int hg = g4 * kHeadsPerGroup + r;
       if (hg < G) scores_out[((size_t)b * Hq + kv * G + hg) * ctx_stride + j] = (float)acc[r] * sc[r];
@@ -260,8 +343,8 @@ __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
 template <int M>
 __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
-    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr,
-    uint32_t* __restrict__ cand_count, int Hq, int Hkv, int NG, int P0, int ctx_len,
+    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int Hq, int Hkv, int NG,
+    int P0, int ctx_len,
     int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kSampleThreads;
   constexpr int NW = NT / 64;
@@ -291,10 +374,6 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
     r_p = (int)ceilf(x * x / (float)P0) + 1;
     if (r_p > s_p) take_all = true;
   }
-  if (p == 0 && tid < kHeadsPerGroup) {
-    const int hg = g4 * kHeadsPerGroup + tid;
-    if (hg < G) cand_count[(size_t)b * Hq + kv * G + hg] = 0;
-  }
   if (take_all) {
     if (tid < kHeadsPerGroup) {
       const int hg = g4 * kHeadsPerGroup + tid;
@@ -309,7 +388,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
   int32_t mxv[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
   for (int e = tid; e < kCentroids * M; e += NT) {   // e % M == tid % M for every e of a thread
     const int4 v = src[e];
-    lutv[e] = v;
+    lutv[lds_slot<M>(e)] = v;
     mn[0] = min(mn[0], v.x); mn[1] = min(mn[1], v.y); mn[2] = min(mn[2], v.z); mn[3] = min(mn[3], v.w);
     mxv[0] = max(mxv[0], v.x); mxv[1] = max(mxv[1], v.y); mxv[2] = max(mxv[2], v.z); mxv[3] = max(mxv[3], v.w);
   }
@@ -351,6 +430,8 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
   __syncthreads();
 
   // score this workgroup's share of the strided sample
+  LaneSwizzle<M> sw;
+  sw.init(lane);
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
   const int lo0 = s_lo[0], lo1 = s_lo[1], lo2 = s_lo[2], lo3 = s_lo[3];
   const int sh0 = s_shift[0], sh1 = s_shift[1], sh2 = s_shift[2], sh3 = s_shift[3];
@@ -361,7 +442,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
 #pragma unroll
     for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
     int32_t acc[4];
-    score_four_heads<M>(w, lutv, acc);
+    score_four_heads<M>(w, lutv, sw, acc);
     atomicAdd(&s_hist[0][(uint32_t)(acc[0] - lo0) >> sh0], 1u);
     atomicAdd(&s_hist[0][(uint32_t)(acc[1] - lo1) >> sh1], 1u << 16);
     atomicAdd(&s_hist[1][(uint32_t)(acc[2] - lo2) >> sh2], 1u);
@@ -386,93 +467,152 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
 // Fast route, stage 2: one pass over the code matrix
 // ------------------------------------------------------------------------------------------
 template <int M>
-__global__ __launch_bounds__(kStreamThreads) void stream_select_kernel(
+__device__ __forceinline__ void stream_select_body(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
-    uint32_t* __restrict__ cand_count, uint2* __restrict__ cand, int Hq, int Hkv, int NG, int P0,
-    int rows_per_chunk, int cap, int ctx_len, int64_t ctx_stride, int top_k, int window,
-    int n_sink) {
+    uint32_t* __restrict__ seg_count, uint2* __restrict__ cand, int Hq, int Hkv, int NG, int P0,
+    int rows_per_chunk, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   int4* lutv = (int4*)dyn_lds;
   uint2* stage_all = (uint2*)(dyn_lds + (size_t)kCentroids * M * sizeof(int4));
 
-  const int chunk = blockIdx.x, prob = blockIdx.y;
+  const int chunk = blockIdx.x, n_chunks = gridDim.x, prob = blockIdx.y;
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   const long begin = (long)sr.sink_end + (long)chunk * rows_per_chunk;
-  if (begin >= sr.win_start) return;
   const int end = (int)min((long)sr.win_start, begin + rows_per_chunk);
+
+  // Every (head, chunk, wave) owns one candidate segment in HBM: no atomics, no contention.
+  size_t seg[4];
+  bool live[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int hg = g4 * kHeadsPerGroup + r;
+    live[r] = hg < G;
+    const size_t head = (size_t)b * Hq + kv * G + (live[r] ? hg : 0);
+    seg[r] = (head * n_chunks + chunk) * kStreamWaves + wv;
+  }
+  if (begin >= sr.win_start) {   // nothing to score: publish empty segments
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (live[r] && lane == 0) seg_count[seg[r]] = 0;
+    return;
+  }
 
   load_group_lut<M, NT>(lut + (size_t)prob * (kCentroids * M * kHeadsPerGroup), lutv);
 
   int32_t T[4];
-  size_t head[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const int hg = g4 * kHeadsPerGroup + r;
-    head[r] = (size_t)b * Hq + kv * G + (hg < G ? hg : 0);
     int32_t t = INT32_MAX;   // padded heads never produce candidates
-    if (hg < G) {
-      t = thr[head[r] * P0];
-      for (int pp = 1; pp < P0; ++pp) t = min(t, thr[head[r] * P0 + pp]);
+    if (live[r]) {
+      const size_t head = seg[r] / ((size_t)n_chunks * kStreamWaves);
+      t = thr[head * P0];
+      for (int pp = 1; pp < P0; ++pp) t = min(t, thr[head * P0 + pp]);
     }
     T[r] = t;
   }
   __syncthreads();
 
   uint2* stage = stage_all + (size_t)wv * kHeadsPerGroup * kStageCap;
-  int cnt[4] = {0, 0, 0, 0};
+  LaneSwizzle<M> sw;
+  sw.init(lane);
+  int cnt[4] = {0, 0, 0, 0};   // staged in LDS, per head (wave-uniform)
+  int done[4] = {0, 0, 0, 0};  // already copied to this wave's HBM segment
 
+  // Copy the staged entries of head r to the wave's segment.  Entries past the segment capacity
+  // are dropped but still counted, which the final kernel recognises as an overflow.
   auto flush = [&](int r) {
     const int n = cnt[r];
     if (n == 0) return;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    uint32_t base = 0;
-    if (lane == 0) base = atomicAdd(&cand_count[head[r]], (uint32_t)n);
-    base = __shfl(base, 0);
     for (int i = lane; i < n; i += 64)
-      if (base + i < (uint32_t)cap) cand[head[r] * cap + base + i] = stage[r * kStageCap + i];
+      if (done[r] + i < kSubCap) cand[seg[r] * kSubCap + done[r] + i] = stage[r * kStageCap + i];
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    done[r] += n;
     cnt[r] = 0;
   };
 
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
-  constexpr int U = 2;
-#pragma unroll 1
-  for (int base = (int)begin; base < end; base += NT * U) {
-    uint4 w[U][M / 16];
-    int jj[U];
+  // Rows are read U at a time per thread, one full step ahead of their use (two register sets
+  // used alternately), so every wave keeps up to 2*U 16-byte loads in flight while it gathers.
+  constexpr int U = 4;
+  constexpr int STEP = NT * U;
+  uint4 rows_a[U][M / 16], rows_b[U][M / 16];
+  // Loads are unconditional (row index clamped into the chunk) so that the wait before the
+  // gathers only covers the older of the two row sets in flight.
+  auto load_rows = [&](int base, uint4 (&dst)[U][M / 16]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      jj[u] = base + u * NT + tid;
-      const int jl = jj[u] < end ? jj[u] : end - 1;
+      const int j = base + u * NT + tid;
+      const int jl = j < end ? j : end - 1;
 #pragma unroll
       for (int qd = 0; qd < M / 16; ++qd)
-        w[u][qd] = *(const uint4*)(seq_codes + (size_t)jl * M + qd * 16);
+        dst[u][qd] = load_stream_u4(seq_codes + (size_t)jl * M + qd * 16);
+    }
+  };
+  auto process = [&](int base, const uint4 (&rows)[U][M / 16]) {
+    // Scores and the per-head "at or above threshold" wave masks are formed together, so the
+    // gathered table entries die inside this straight-line block.
+    int32_t acc[U][4];
+    uint64_t hit[U][4];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      score_four_heads<M>(rows[u], lutv, sw, acc[u]);
+      const bool valid = base + u * NT + tid < end;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) hit[u][r] = __ballot(valid && acc[u][r] >= T[r]);
+      __builtin_amdgcn_sched_barrier(0);   // one row's gathers at a time: bounds live registers
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      int32_t acc[4];
-      score_four_heads<M>(w[u], lutv, acc);
-      const bool valid = jj[u] < end;
+      const int j = base + u * NT + tid;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const bool pred = valid && acc[r] >= T[r];
-        const uint64_t mask = __ballot(pred);
+        const uint64_t mask = hit[u][r];
         if (mask) {
           const int n = __popcll(mask);
           if (cnt[r] + n > kStageCap) flush(r);
-          if (pred) stage[r * kStageCap + cnt[r] + lanes_below(mask)] = make_uint2((uint32_t)jj[u], (uint32_t)acc[r]);
+          if ((mask >> lane) & 1)
+            stage[r * kStageCap + cnt[r] + lanes_below(mask)] = make_uint2((uint32_t)j, (uint32_t)acc[u][r]);
           cnt[r] += n;
         }
       }
     }
+  };
+  load_rows((int)begin, rows_a);
+#pragma unroll 1
+  for (int base = (int)begin; base < end; base += 2 * STEP) {
+    load_rows(base + STEP, rows_b);
+    process(base, rows_a);
+    load_rows(base + 2 * STEP, rows_a);
+    process(base + STEP, rows_b);
   }
 #pragma unroll
-  for (int r = 0; r < 4; ++r) flush(r);
+  for (int r = 0; r < 4; ++r) {
+    flush(r);
+    if (live[r] && lane == 0) seg_count[seg[r]] = (uint32_t)done[r];
+  }
 }
+
+#define A2ATS_STREAM_ARGS                                                                          \
+  const uint8_t *__restrict__ codes, const int32_t *__restrict__ lut,                             \
+      const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ thr,                      \
+      uint32_t *__restrict__ seg_count, uint2 *__restrict__ cand, int Hq, int Hkv, int NG, int P0, \
+      int rows_per_chunk, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink
+#define A2ATS_STREAM_PASS                                                                          \
+  codes, lut, seq_lens, thr, seg_count, cand, Hq, Hkv, NG, P0, rows_per_chunk, ctx_len,            \
+      ctx_stride, top_k, window, n_sink
+
+// M = 16: 80 KB of LDS per workgroup, two workgroups per CU -> 4 waves per SIMD, 128 VGPRs.
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void stream_select_kernel16(A2ATS_STREAM_ARGS) { stream_select_body<16>(A2ATS_STREAM_PASS); }
+// M = 32: 144 KB of LDS, one workgroup per CU -> 2 waves per SIMD.
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void stream_select_kernel32(A2ATS_STREAM_ARGS) { stream_select_body<32>(A2ATS_STREAM_PASS); }
+
 
 // ------------------------------------------------------------------------------------------
 // Fast route, stage 3: exact selection among the candidates, ordered output
@@ -481,9 +621,9 @@ template <int M>
 __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
-    const uint32_t* __restrict__ cand_count, const uint2* __restrict__ cand,
+    const uint32_t* __restrict__ seg_count, const uint2* __restrict__ cand,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ topk_count,
-    float* __restrict__ topk_score, int Hq, int Hkv, int NG, int cap, int ctx_len,
+    float* __restrict__ topk_score, int Hq, int Hkv, int NG, int n_seg, int cap, int ctx_len,
     int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kExactThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
@@ -500,8 +640,23 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   }
   if (sr.kk == 0) return;
   const float scale = lut_scale[bh];
-  const uint32_t n_c = cand_count[bh];
-  if (n_c > (uint32_t)cap || n_c < (uint32_t)sr.kk) {
+  // Candidate segments of this head (one per chunk and wave of the streaming pass): exclusive
+  // prefix of their sizes.  n_seg <= 512 <= NT.
+  __shared__ uint32_t s_seg_off[513];
+  __shared__ uint32_t s_overflow;
+  if (tid == 0) s_overflow = 0;
+  __syncthreads();
+  uint32_t my_cnt = 0;
+  if (tid < n_seg) {
+    my_cnt = seg_count[(size_t)bh * n_seg + tid];
+    if (my_cnt > (uint32_t)kSubCap) s_overflow = 1;
+  }
+  uint32_t n_c;
+  const uint32_t my_off = block_exclusive_scan<NT>(my_cnt, L.wave_a, n_c);
+  if (tid < n_seg) s_seg_off[tid] = my_off;
+  if (tid == 0) s_seg_off[n_seg] = n_c;
+  __syncthreads();
+  if (s_overflow || n_c > (uint32_t)cap || n_c < (uint32_t)sr.kk) {
     const int32_t* lut_grp = lut + (((size_t)b * Hkv + kv) * NG + hg / kHeadsPerGroup) *
                                        (kCentroids * M * kHeadsPerGroup);
     exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M, lut_grp,
@@ -517,17 +672,48 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   uint16_t* wpre = (uint16_t*)(bitmap + n_words);
   constexpr uint32_t kDropped = 0x80000000u;
 
+  // Candidate keys are stored relative to the smallest one, so that the radix digits spread
+  // over the occupied range (all candidates share the leading bits of their absolute keys).
+  uint32_t kmin = 0xffffffffu, kmax = 0;
   for (uint32_t i = tid; i < n_c; i += NT) {
-    const uint2 e = cand[(size_t)bh * cap + i];
+    int lo_s = 0, hi_s = n_seg;   // segment holding flat candidate i: last s with off[s] <= i
+    while (hi_s - lo_s > 1) {
+      const int mid = (lo_s + hi_s) >> 1;
+      if (s_seg_off[mid] <= i) lo_s = mid; else hi_s = mid;
+    }
+    const uint2 e = cand[((size_t)bh * n_seg + lo_s) * kSubCap + (i - s_seg_off[lo_s])];
+    const uint32_t key = score_key((int32_t)e.y);
     c_idx[i] = e.x;
-    c_key[i] = score_key((int32_t)e.y);
+    c_key[i] = key;
+    kmin = min(kmin, key);
+    kmax = max(kmax, key);
   }
-  // K-th largest key among the candidates (MSB-first radix select, 11 + 11 + 10 bits)
-  uint32_t prefix = 0, mask = 0, k_rem = (uint32_t)sr.kk, n_eq = 0;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    kmin = min(kmin, __shfl_xor(kmin, off));
+    kmax = max(kmax, __shfl_xor(kmax, off));
+  }
+  if ((tid & 63) == 0) {
+    L.wave_a[tid >> 6] = kmin;
+    L.wave_b[tid >> 6] = kmax;
+  }
+  __syncthreads();
+  kmin = L.wave_a[0];
+  kmax = L.wave_b[0];
+  for (int w = 1; w < NT / 64; ++w) {
+    kmin = min(kmin, L.wave_a[w]);
+    kmax = max(kmax, L.wave_b[w]);
+  }
+  __syncthreads();
+  for (uint32_t i = tid; i < n_c; i += NT) c_key[i] -= kmin;
+  // K-th largest key among the candidates: MSB-first radix select over the significant bits
+  uint32_t prefix = 0, mask = 0, k_rem = (uint32_t)sr.kk, n_eq = n_c;
+  int remaining = 32 - __clz(kmax - kmin);
 #pragma unroll 1
-  for (int lvl = 0; lvl < 3; ++lvl) {
-    const int shift = lvl == 0 ? 21 : (lvl == 1 ? 10 : 0);
-    const uint32_t dmask = lvl == 2 ? 1023u : 2047u;
+  while (remaining > 0) {
+    const int bits = remaining < 11 ? remaining : 11;
+    const int shift = remaining - bits;
+    const uint32_t dmask = (1u << bits) - 1u;
     for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
     __syncthreads();
     for (uint32_t i = tid; i < n_c; i += NT) {
@@ -541,9 +727,10 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     k_rem -= above;
     prefix |= bin << shift;
     mask |= dmask << shift;
+    remaining = shift;
     __syncthreads();
   }
-  const uint32_t kth = prefix;
+  const uint32_t kth = prefix;   // relative to kmin, like c_key[]
 
   // Rank of a position among the set bits of the bitmap: prefix popcounts per 32-bit word.
   const int wpt = (n_words + NT - 1) / NT;
@@ -589,7 +776,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     if (c_key[i] >= kth && !(c_idx[i] & kDropped)) {
       const uint32_t pos = rank_of(c_idx[i]);
       oi[pos] = (int32_t)c_idx[i];
-      if (os) os[pos] = (float)key_score(c_key[i]) * scale;
+      if (os) os[pos] = (float)key_score(c_key[i] + kmin) * scale;
     }
   }
 }
@@ -602,6 +789,27 @@ static hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 void set_profile_events(void* a, void* b) {
   g_ev_start = (hipEvent_t)a;
   g_ev_stop = (hipEvent_t)b;
+}
+
+__global__ void sum_segments_kernel(const uint32_t* __restrict__ seg_count, uint32_t* __restrict__ out,
+                                    int heads, int n_seg) {
+  const int h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h >= heads) return;
+  uint32_t tot = 0;
+  for (int s = 0; s < n_seg; ++s) tot += seg_count[(size_t)h * n_seg + s];
+  out[h] = tot;
+}
+
+hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sink, const void* ws,
+                           uint32_t* cand_counts, hipStream_t stream) {
+  const TopkPlan plan = make_topk_plan(d, top_k, window, n_sink);
+  const int heads = d.batch * d.n_q_heads;
+  if (heads == 0) return hipSuccess;
+  if (!plan.fast) return hipMemsetAsync(cand_counts, 0xff, (size_t)heads * sizeof(uint32_t), stream);
+  hipLaunchKernelGGL(sum_segments_kernel, dim3((heads + 255) / 256), dim3(256), 0, stream,
+                     (const uint32_t*)((const unsigned char*)ws + plan.off_count), cand_counts, heads,
+                     plan.chunks * kStreamWaves);
+  return hipGetLastError();
 }
 
 template <typename K>
@@ -642,23 +850,23 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
 
   unsigned char* wsb = (unsigned char*)ws;
   int32_t* thr = (int32_t*)(wsb + plan.off_thr);
-  uint32_t* cand_count = (uint32_t*)(wsb + plan.off_count);
+  uint32_t* seg_count = (uint32_t*)(wsb + plan.off_count);
   uint2* cand = (uint2*)(wsb + plan.off_cand);
 
   if ((err = allow_lds(sample_threshold_kernel<M>, lut4_bytes)) != hipSuccess) return err;
   hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0, problems), dim3(kSampleThreads),
-                     lut4_bytes, stream, codes, lut, seq_lens, thr, cand_count, Hq, Hkv, NG, plan.P0,
+                     lut4_bytes, stream, codes, lut, seq_lens, thr, Hq, Hkv, NG, plan.P0,
                      d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
   const size_t stream_lds =
       lut4_bytes + (size_t)(kStreamThreads / 64) * kHeadsPerGroup * kStageCap * sizeof(uint2);
-  if ((err = allow_lds(stream_select_kernel<M>, stream_lds)) != hipSuccess) return err;
+  auto stream_kernel = M == 16 ? stream_select_kernel16 : stream_select_kernel32;
+  if ((err = allow_lds(stream_kernel, stream_lds)) != hipSuccess) return err;
   if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_start, stream);
-  hipLaunchKernelGGL((stream_select_kernel<M>), dim3(plan.chunks, problems), dim3(kStreamThreads),
-                     stream_lds, stream, codes, lut, seq_lens, thr, cand_count, cand, Hq, Hkv, NG,
-                     plan.P0, plan.rows_per_chunk, plan.cap, d.ctx_len, d.ctx_stride, top_k, window,
-                     n_sink);
+  hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks, problems), dim3(kStreamThreads),
+                     stream_lds, stream, codes, lut, seq_lens, thr, seg_count, cand, Hq, Hkv, NG,
+                     plan.P0, plan.rows_per_chunk, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_stop, stream);
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
@@ -668,8 +876,9 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   final_lds = (final_lds + 15) / 16 * 16;
   if ((err = allow_lds(final_select_kernel<M>, final_lds)) != hipSuccess) return err;
   hipLaunchKernelGGL((final_select_kernel<M>), dim3(heads), dim3(kExactThreads), final_lds, stream,
-                     codes, lut, lut_scale, seq_lens, cand_count, cand, topk_idx, topk_count,
-                     topk_score, Hq, Hkv, NG, plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                     codes, lut, lut_scale, seq_lens, seg_count, cand, topk_idx, topk_count,
+                     topk_score, Hq, Hkv, NG, plan.chunks * kStreamWaves, plan.cap, d.ctx_len,
+                     d.ctx_stride, top_k, window, n_sink);
   return hipGetLastError();
 }
 
