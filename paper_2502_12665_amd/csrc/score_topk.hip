@@ -812,9 +812,17 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
   return hipGetLastError();
 }
 
+// Raise a kernel's dynamic-LDS limit (needed above 64 KB).  The attribute is sticky, so it is set
+// once per kernel and device; `slot` is a per-call-site cache of the largest size set so far.
 template <typename K>
-static hipError_t allow_lds(K kernel, size_t bytes) {
-  return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+static hipError_t allow_lds(K kernel, size_t bytes, size_t* slot) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
+  if (slot[dev] >= bytes) return hipSuccess;
+  const hipError_t e =
+      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) slot[dev] = bytes;
+  return e;
 }
 
 template <int M>
@@ -828,10 +836,11 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   const size_t lut4_bytes = (size_t)kCentroids * M * sizeof(int4);
   const size_t lut1_bytes = (size_t)kCentroids * M * sizeof(int32_t);
   hipError_t err;
+  static size_t s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_final[16];
   if (heads == 0) return hipSuccess;
 
   if (scores_out) {
-    if ((err = allow_lds(score_dense_kernel<M>, lut4_bytes)) != hipSuccess) return err;
+    if ((err = allow_lds(score_dense_kernel<M>, lut4_bytes, s_dense)) != hipSuccess) return err;
     int gx = (d.ctx_len + kStreamThreads * 8 - 1) / (kStreamThreads * 8);
     gx = gx < 1 ? 1 : gx;
     hipLaunchKernelGGL((score_dense_kernel<M>), dim3(gx, problems), dim3(kStreamThreads), lut4_bytes,
@@ -841,7 +850,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   }
 
   if (!plan.fast) {
-    if ((err = allow_lds(select_exact_kernel<M>, lut1_bytes)) != hipSuccess) return err;
+    if ((err = allow_lds(select_exact_kernel<M>, lut1_bytes, s_exact)) != hipSuccess) return err;
     hipLaunchKernelGGL((select_exact_kernel<M>), dim3(heads), dim3(kExactThreads), lut1_bytes, stream,
                        codes, lut, lut_scale, seq_lens, topk_idx, topk_count, topk_score, Hq, Hkv, NG,
                        d.ctx_len, d.ctx_stride, top_k, window, n_sink);
@@ -853,7 +862,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   uint32_t* seg_count = (uint32_t*)(wsb + plan.off_count);
   uint2* cand = (uint2*)(wsb + plan.off_cand);
 
-  if ((err = allow_lds(sample_threshold_kernel<M>, lut4_bytes)) != hipSuccess) return err;
+  if ((err = allow_lds(sample_threshold_kernel<M>, lut4_bytes, s_sample)) != hipSuccess) return err;
   hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0, problems), dim3(kSampleThreads),
                      lut4_bytes, stream, codes, lut, seq_lens, thr, Hq, Hkv, NG, plan.P0,
                      d.ctx_len, d.ctx_stride, top_k, window, n_sink);
@@ -862,7 +871,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   const size_t stream_lds =
       lut4_bytes + (size_t)(kStreamThreads / 64) * kHeadsPerGroup * kStageCap * sizeof(uint2);
   auto stream_kernel = M == 16 ? stream_select_kernel16 : stream_select_kernel32;
-  if ((err = allow_lds(stream_kernel, stream_lds)) != hipSuccess) return err;
+  if ((err = allow_lds(stream_kernel, stream_lds, s_stream)) != hipSuccess) return err;
   if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_start, stream);
   hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks, problems), dim3(kStreamThreads),
                      stream_lds, stream, codes, lut, seq_lens, thr, seg_count, cand, Hq, Hkv, NG,
@@ -874,7 +883,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   size_t final_lds = (size_t)plan.cap * 8 + (size_t)n_words * 4 + (size_t)n_words * 2;
   if (final_lds < lut1_bytes) final_lds = lut1_bytes;
   final_lds = (final_lds + 15) / 16 * 16;
-  if ((err = allow_lds(final_select_kernel<M>, final_lds)) != hipSuccess) return err;
+  if ((err = allow_lds(final_select_kernel<M>, final_lds, s_final)) != hipSuccess) return err;
   hipLaunchKernelGGL((final_select_kernel<M>), dim3(heads), dim3(kExactThreads), final_lds, stream,
                      codes, lut, lut_scale, seq_lens, seg_count, cand, topk_idx, topk_count,
                      topk_score, Hq, Hkv, NG, plan.chunks * kStreamWaves, plan.cap, d.ctx_len,

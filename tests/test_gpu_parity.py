@@ -185,3 +185,121 @@ def test_run_to_run_determinism():
     for o in outs[1:]:
         assert torch.equal(o[0], outs[0][0]) and torch.equal(o[1], outs[0][1])
         assert torch.equal(o[2].view(torch.int16), outs[0][2].view(torch.int16))
+
+
+# ------------------------------------------------------------------ full-size configurations
+def _full_size_check(oracle, wl, sample, plant=False, n_sink=0):
+    """Run one decode step at a benchmark configuration's full size (inputs generated on the GPU with
+    the seeded torch generator), then (a) compare sampled (sequence, KV head) problems element by
+    element with the oracle and (b) check properties that hold for every head at any size."""
+    H.log(f"{wl.name}: generating inputs on the GPU")
+    xd = synth.make_decode_inputs(wl, device="cuda")
+    if plant:
+        _plant_similar_keys(oracle, wl, xd)
+    H.log(f"{wl.name}: GPU step")
+    st = H.gpu_decode(wl, xd, want_scores=True, n_sink=n_sink)
+    # (b) properties over all heads, computed with torch library routines on the library's own scores
+    N, K, w = wl.ctx_len, wl.top_k, wl.window
+    cnt = st.topk_count
+    assert int(cnt.min()) == int(cnt.max()) == min(K, N - w - n_sink)
+    idx = st.topk_idx.long()
+    assert int(idx.min()) >= n_sink and int(idx.max()) < N - w
+    assert bool((idx[:, :, 1:] > idx[:, :, :-1]).all()), "indices not strictly ascending"
+    sc = st.scores[:, :, :N]
+    sel = torch.zeros_like(sc, dtype=torch.bool).scatter_(2, idx, True)
+    cand = torch.zeros(N, dtype=torch.bool, device="cuda")
+    cand[n_sink:N - w] = True
+    neg = torch.full_like(sc, float("-inf"))
+    min_sel = torch.where(sel, sc, -neg).amin(dim=2)
+    max_unsel = torch.where(~sel & cand, sc, neg).amax(dim=2)
+    assert bool((min_sel >= max_unsel).all()), "a rejected candidate outscores a selected one"
+    # ties at the threshold: among positions scoring exactly the K-th score, the selected ones come first
+    eq = (sc == min_sel[:, :, None]) & cand
+    pos = torch.arange(N, device="cuda")
+    last_sel_eq = torch.where(eq & sel, pos, torch.full_like(pos, -1)).amax(dim=2)
+    first_unsel_eq = torch.where(eq & ~sel, pos, torch.full_like(pos, N)).amin(dim=2)
+    assert bool((last_sel_eq < first_unsel_eq).all()), "a tie at the K-th score did not go to the lower position"
+    np.testing.assert_array_equal(st.topk_score.cpu().numpy(), torch.gather(sc, 2, idx).cpu().numpy())
+    cc = torch.empty(wl.batch, wl.n_q_heads, dtype=torch.int32, device="cuda")
+    # (a) sampled problems against the oracle
+    tot_exc = 0
+    for (b, kv) in sample:
+        H.log(f"{wl.name}: oracle on problem (b={b}, kv={kv})")
+        sub, x = H.slice_problem(wl, xd, b, kv)
+        res = H.check_step_against_oracle(oracle, wl, st, x, b_sel=b, kv_sel=kv, n_sink=n_sink)
+        tot_exc += res["excluded"]
+        H.log(f"  {res}")
+    return st, tot_exc
+
+
+def _plant_similar_keys(oracle, wl, xd):
+    """Give 1 % of the candidate tokens of every (sequence, KV head) a key pulled towards the rotated
+    query of the group's first head, and re-encode those keys (nearest centroid), so that the top-K
+    has structure.  Built with the oracle's own rotation and encoder; tests only."""
+    G, N, w = wl.group, wl.ctx_len, wl.window
+    g = torch.Generator().manual_seed(1234)
+    qrot = oracle.rope(xd["q"].cpu(), xd["inv_freq"], wl.wrope_b)           # [B,Hq,D]
+    cb = xd["codebook"].cpu()
+    n_pl = (N - w) // 100
+    for b in range(wl.batch):
+        for kv in range(wl.n_kv_heads):
+            d = torch.from_numpy(qrot[b, kv * G]).float()
+            d = d / d.norm()
+            pos = torch.randperm(N - w, generator=g)[:n_pl]
+            keys = xd["k"][b, kv, pos.cuda()].float().cpu() + 4.0 * d
+            codes = oracle.encode(keys[None, None], cb[kv:kv + 1])[0, 0]
+            xd["k"][b, kv, pos.cuda()] = keys.to(xd["k"].dtype).cuda()
+            xd["codes"][b, kv, pos.cuda()] = torch.from_numpy(codes).cuda()
+
+
+def test_config3_batched_32k_planted(oracle):
+    wl = synth.WORKLOADS["c3_batched_32k"]
+    _full_size_check(oracle, wl, sample=[(0, 0), (7, 3), (15, 7)], plant=True)
+
+
+def test_config4_long_128k(oracle):
+    wl = synth.WORKLOADS["c4_long_128k"]
+    _full_size_check(oracle, wl, sample=[(0, 0), (1, 5), (3, 7)])
+
+
+def test_config5_qwen7b_64k_decode(oracle):
+    wl = synth.WORKLOADS["c5_qwen7b_64k"]
+    _full_size_check(oracle, wl, sample=[(0, 0), (13, 2), (31, 3)])
+
+
+def test_config5_encode_then_decode(oracle):
+    """Configuration 5's prefill side: encode 65536 float32 pre-RoPE keys per KV head under the
+    per-dimension query-aware distortion (weights = diagonal of a seeded PSD query second moment),
+    here for 4 of the 32 sequences at full length, compare one whole sequence plus a 1 % sample of
+    the other three with the oracle, and check that a decode step over the produced codes agrees with
+    the oracle run on the same codes."""
+    wl = synth.WORKLOADS["c5_qwen7b_64k"].replace(batch=4)
+    N, M = wl.ctx_len, wl.n_sub
+    hm = synth.make_query_second_moment(wl)
+    cb = synth.make_codebook(wl, "cuda")
+    H.log("c5 encode: generating keys")
+    keys = synth.make_encode_keys(wl, N, device="cuda")
+    dims = H.dims_of(wl)
+    ws = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+    codes = torch.empty(wl.batch, wl.n_kv_heads, N, M, dtype=torch.uint8, device="cuda")
+    H.log("c5 encode: GPU")
+    B.encode_keys(dims, keys, N, 0, cb, hm["h_diag"].cuda(), B.W_DIAG, codes, ws)
+    torch.cuda.synchronize()
+    H.log("c5 encode: oracle on sequence 0 (all KV heads)")
+    want, b1, b2 = oracle.encode(keys[:1].cpu(), cb.cpu(), hm["h_diag"], oracle.W_DIAG, want_margins=True)
+    n0 = H.compare_codes(codes[:1].cpu().numpy(), want, b1, b2)
+    g = torch.Generator().manual_seed(5)
+    pick = torch.randperm(N, generator=g)[:N // 100]
+    sub_keys = keys[1:, :, pick.cuda()].cpu().contiguous()
+    want, b1, b2 = oracle.encode(sub_keys, cb.cpu(), hm["h_diag"], oracle.W_DIAG, want_margins=True)
+    n1 = H.compare_codes(codes[1:, :, pick.cuda()].cpu().numpy(), want, b1, b2)
+    H.log(f"c5 encode: near-tie exclusions {n0} + {n1}")
+    # decode over the encoder's codes
+    xd = synth.make_decode_inputs(wl, device="cuda")
+    xd["codes"] = codes
+    xd["k"] = keys.to(torch.bfloat16)
+    st = H.gpu_decode(wl, xd)
+    for (b, kv) in [(0, 0), (3, 2)]:
+        sub, x = H.slice_problem(wl, xd, b, kv)
+        res = H.check_step_against_oracle(oracle, wl, st, x, b_sel=b, kv_sel=kv)
+        H.log(f"  decode on encoded keys (b={b}, kv={kv}): {res}")
