@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--workload", default="c4_long_128k")
     ap.add_argument("--replicas", type=int, default=8, help="independent input sets cycled through (cold cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run 3 plain float32 copies (out = in + 0) of this many MiB, so that a "
+                         "rocprofv3 --pmc run of this command holds a kernel of known HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -111,6 +114,14 @@ def main():
         if timed:
             phase_ev[i][4].record()
 
+    if args.calibration_copy_mib > 0:
+        n = args.calibration_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i, False)
     torch.cuda.synchronize()
