@@ -22,16 +22,22 @@
  *     else returns A2ATS_ERR_UNSUPPORTED.
  *
  * Lookup-table format (shared by a2ats_build_lut and a2ats_score_topk)
- *   The table holds, for every query head and subspace m, the 256 inner products of
- *   the rotated query slice with the centroids, in 32-bit fixed point:
- *       lut[b, kv, g4, c, m, r]  (int32, dims [B, Hkv, ceil(G/4), 256, M, 4])
- *         = round( 2^e * <q_rot[b, h, m*ds : (m+1)*ds], codebook[kv, m, c, :]> ),
- *       h = kv*G + 4*g4 + r   (entries of heads past G are 0),
- *       lut_scale[b, h] = 2^-e (float32; the power of two is chosen per head so that a
- *       sum of M entries cannot overflow).
- *   A token's approximate score is lut_scale * sum_m lut[.., codes[j, m], m, ..]; integer
- *   accumulation makes it independent of summation order, so equal code rows score
- *   exactly equal and ties resolve by token index.
+ *   `lut` is one int32 array of a2ats_lut_elems() words produced by a2ats_build_lut and consumed
+ *   by a2ats_score_topk.  With NG = ceil(G/4) groups of four query heads per KV head it holds
+ *     exact  [B*Hq][M][256] int32            exact[b,h,m,c] = round(2^e * <q_rot[b,h,m*ds:(m+1)*ds],
+ *                                            codebook[kv,m,c,:]>), inner product in float64; the
+ *                                            power of two 2^e is chosen per head so that a sum of
+ *                                            M entries stays below 2^30; lut_scale[b,h] = 2^-e
+ *     coarse [B*Hkv*NG][M/16][256][16][4] uint16   coarse[.., c, m, r] = (exact[b,h,m,c] - min_c'
+ *                                            exact[b,h,m,c']) >> s for head h = kv*G + 4*g4 + r
+ *                                            (0 for heads past G); s is the smallest shift for
+ *                                            which every coarse entry is <= floor(65535 / M)
+ *     meta   [B*Hq][4] int32                 {sum_m min_c exact[b,h,m,c], s, 0, 0}
+ *   in this order.  A token's approximate score is lut_scale * sum_m exact[.., m, codes[j,m]]:
+ *   integer accumulation makes it independent of summation order, so equal code rows score
+ *   exactly equal and ties resolve by token index.  Its coarse score sum_m coarse[.., codes[j,m],
+ *   m, r] fits 16 bits and satisfies  exact = meta[0] + (coarse << s) + rem, 0 <= rem < M * 2^s,
+ *   which is what lets the streaming pass filter with 16-bit arithmetic and still be exact.
  */
 #ifndef A2ATS_H_
 #define A2ATS_H_
@@ -70,7 +76,7 @@ enum { A2ATS_OP_ENCODE = 0, A2ATS_OP_LUT = 1, A2ATS_OP_SCORE_TOPK = 2, A2ATS_OP_
 int a2ats_version(void);
 const char* a2ats_status_string(int status);
 
-/* Number of int32 elements of the lookup table for these dims: B*Hkv*ceil(G/4)*256*M*4. */
+/* Number of int32 elements of the lookup-table array for these dims (see the format above). */
 size_t a2ats_lut_elems(const a2ats_dims* dims);
 
 /* Scratch bytes `op` needs for these dims (0 if it needs none; (size_t)-1 on bad dims). */
@@ -116,7 +122,7 @@ int a2ats_encode_keys(const a2ats_dims* dims, const float* keys, int32_t n_new, 
  *   cos_b/sin_b [dev, f32 D/2]        from a2ats_rope_tables
  *   codebook  [dev, f32 Hkv*M*256*ds]
  *   q_rot     [dev, out, f32 B*Hq*D]  q R_b, rotated in float64, rounded once
- *   lut       [dev, out, int32 a2ats_lut_elems()]   see "Lookup-table format"
+ *   lut       [dev, out, int32 a2ats_lut_elems()]   see "Lookup-table format" (16-byte aligned)
  *   lut_scale [dev, out, f32 B*Hq]
  * Inner products are accumulated in float64.  Needs no workspace.
  */

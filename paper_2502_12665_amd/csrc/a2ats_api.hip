@@ -45,9 +45,7 @@ const char* a2ats_status_string(int status) {
 
 size_t a2ats_lut_elems(const a2ats_dims* d) {
   if (check_dims(d) != A2ATS_OK) return 0;
-  const int G = d->n_q_heads / d->n_kv_heads;
-  const size_t NG = (size_t)(G + 3) / 4;
-  return (size_t)d->batch * d->n_kv_heads * NG * 256 * d->n_sub * 4;
+  return a2ats::lut_layout(d->batch, d->n_q_heads, d->n_kv_heads, d->n_sub).total;
 }
 
 size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t window) {

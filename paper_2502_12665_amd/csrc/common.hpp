@@ -24,6 +24,24 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
                                    __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
 }
 
+// Word offsets (int32 units) of the three parts of the lookup-table blob, see a2ats.h.
+struct LutLayout {
+  size_t off_exact;   // [B*Hq][M][256] int32
+  size_t off_coarse;  // [B*Hkv*NG][M/16][256][16] x 4 uint16
+  size_t off_meta;    // [B*Hq][4] int32: {sum of subspace minima, shift, 0, 0}
+  size_t total;
+};
+__host__ __device__ inline LutLayout lut_layout(int B, int Hq, int Hkv, int M) {
+  const int G = Hq / Hkv, NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
+  const size_t heads = (size_t)B * Hq, probs = (size_t)B * Hkv * NG;
+  LutLayout l;
+  l.off_exact = 0;
+  l.off_coarse = heads * M * kCentroids;
+  l.off_meta = l.off_coarse + probs * kCentroids * M * 2;
+  l.total = l.off_meta + heads * 4;
+  return l;
+}
+
 // Integer score -> unsigned key with the same order.
 __device__ __forceinline__ uint32_t score_key(int32_t s) { return (uint32_t)s ^ 0x80000000u; }
 __device__ __forceinline__ int32_t key_score(uint32_t k) { return (int32_t)(k ^ 0x80000000u); }
@@ -98,6 +116,22 @@ __device__ __forceinline__ void block_find_rank_desc(Count count, uint32_t k, ui
     }
   }
   __syncthreads();
+}
+
+// Workgroups are dealt to the 8 XCDs (each with its own L2) round-robin by linear workgroup id.
+// Map a linear id to (problem, part) so that every part of a problem runs on XCD (problem % 8):
+// the table that kernel k wrote or read for a problem is then in the L2 that kernel k+1's
+// workgroups for the same problem use.  Falls back to the plain order when the number of
+// problems is not a multiple of 8.
+__device__ __forceinline__ void xcd_map(int linear, int parts, int problems, int& problem, int& part) {
+  if ((problems & 7) == 0) {
+    const int xcd = linear & 7, slot = linear >> 3;
+    problem = (slot / parts) * 8 + xcd;
+    part = slot % parts;
+  } else {
+    problem = linear / parts;
+    part = linear % parts;
+  }
 }
 
 // Per-sequence geometry of the candidate range (sinks and window never compete).

@@ -33,6 +33,19 @@ void set_profile_events(void* ev_start, void* ev_stop);
 hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sink, const void* ws,
                            uint32_t* cand_counts, hipStream_t stream);
 
+// Raise a kernel's dynamic-LDS limit (needed above 64 KB).  The attribute is sticky, so it is set
+// once per kernel and device; `slot` (16 entries, one per device) caches the largest size set.
+template <typename K>
+inline hipError_t allow_dynamic_lds(K kernel, size_t bytes, size_t* slot) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
+  if (slot[dev] >= bytes) return hipSuccess;
+  const hipError_t e =
+      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) slot[dev] = bytes;
+  return e;
+}
+
 hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                             const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
                             float* lut_scale, hipStream_t stream);

@@ -3,24 +3,27 @@
 //
 // Two routes, chosen on the host from the shape:
 //
-//  exact route (short contexts, very large K, ragged corner cases; also the in-kernel fallback
-//  of the fast route): one workgroup per query head runs an MSB-first radix select over the
-//  32-bit score keys by re-streaming its sequence (3 histogram passes), then one ordered pass
-//  that emits the winners in ascending position, equal scores going to the lower position.
+//  exact route (short contexts, very large K; also the in-kernel fallback of the fast route):
+//  one workgroup per query head runs an MSB-first radix select over the 32-bit score keys by
+//  re-streaming its sequence (<= 3 histogram passes), then one ordered pass that emits the
+//  winners in ascending position, equal scores going to the lower position.
 //
-//  fast route (long contexts): the code matrix is streamed from HBM once.
-//    1. sample_threshold_kernel scores a strided sample of each sequence (about 1/16 of it) and
-//       derives, per head, an integer threshold below the K-th score with a 5-sigma margin
-//       (distribution-free: it only uses ranks of the sample).
-//    2. stream_select_kernel streams all code rows, one 16-byte table read per code byte
-//       serving the four heads of a group, and appends every (position, score) at or above
-//       the threshold to a per-head candidate list (about 2K entries) through wave-private
-//       LDS staging.
-//    3. final_select_kernel (one workgroup per head) radix-selects the exact K-th key among
-//       the candidates in LDS, resolves ties by position, and orders the winners by position
-//       with an LDS bitmap.  If the candidate list is too short or overflowed -- possible only
-//       when the sample misled (probability ~1e-6 per head) or for degenerate inputs -- the
-//       workgroup runs the exact route for its head instead, so the result is always exact.
+//  fast route (long contexts): the code matrix is streamed from HBM once, against a 16-bit
+//  coarse copy of the tables, and only the survivors are scored exactly.
+//    1. sample_threshold_kernel scores a strided sample of each sequence (about 1/16 of it) with
+//       the coarse tables and derives, per head, a coarse threshold below the K-th score with a
+//       5-sigma margin (distribution-free: it only uses ranks of the sample).
+//    2. stream_select_kernel streams all code rows: one 8-byte LDS read per code byte serves the
+//       four heads of a group (two heads per 32-bit word, 16 bits each, so one integer add
+//       accumulates two heads).  Rows whose coarse score reaches the threshold are written, with
+//       their code bytes, to a per-(head, chunk, wave) segment in HBM (about 2K per head).
+//    3. final_select_kernel (one workgroup per head) scores the survivors exactly from the
+//       head's 32-bit table, radix-selects the exact K-th key among them, proves that no row
+//       outside the survivor list can reach that key (coarse and exact scores differ by less
+//       than M coarse units), and writes the winners in ascending position.  If the proof fails
+//       or a list is too short / overflowed -- possible only when the sample misled (about 1e-6
+//       per head) or for degenerate inputs -- the workgroup runs the exact route for its head,
+//       so the result is always exact with respect to the 32-bit scores.
 #include <math.h>
 
 #include "common.hpp"
@@ -30,11 +33,11 @@ namespace a2ats {
 
 constexpr int kExactThreads = 1024;
 constexpr int kStreamThreads = 512;
-constexpr int kSampleThreads = 512;
-constexpr int kStageCap = 64;        // wave-private LDS staging entries per head (>= one ballot)
-constexpr int kSubCap = 128;         // candidate slots a wave owns in HBM, per head
 constexpr int kStreamWaves = kStreamThreads / 64;
+constexpr int kSampleThreads = 512;
+constexpr int kSubCap = 128;         // survivor slots a wave owns in HBM, per head
 constexpr int kSampleRows = 1024;    // rows scored by one sampling workgroup
+constexpr int kSmallList = 1024;     // members of the K-th key's bin ranked by brute force
 constexpr float kSigma = 5.0f;
 
 TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) {
@@ -44,8 +47,7 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
   long ncand = (long)d.ctx_len - window - n_sink;
   if (ncand < 0) ncand = 0;
   p.cap = 8192;
-  p.fast = ncand >= 16384 && d.ctx_len <= (1 << 18) && top_k >= 1 && top_k <= 2048 &&
-           4L * top_k <= ncand;
+  p.fast = ncand >= 16384 && top_k >= 1 && top_k <= 2048 && 4L * top_k <= ncand;
   if (p.fast) {
     long s_tot = ncand / 16 / kSampleRows * kSampleRows;
     if (s_tot < kSampleRows) s_tot = kSampleRows;
@@ -62,12 +64,13 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     p.chunks = (int)((ncand + rpc - 1) / rpc);
     p.rows_per_chunk = (int)rpc;
     const size_t heads = (size_t)d.batch * d.n_q_heads;
-    p.off_thr = 0;
-    // one candidate segment (count + kSubCap slots) per head, chunk and wave of the streaming pass
+    // one survivor segment (count + kSubCap entries) per head, chunk and wave of the streaming pass
     const size_t segs = heads * p.chunks * kStreamWaves;
+    const size_t entry_bytes = (2 + d.n_sub / 4) * sizeof(uint32_t);
+    p.off_thr = 0;
     p.off_count = p.off_thr + heads * p.P0 * sizeof(int32_t);
     p.off_cand = (p.off_count + segs * sizeof(uint32_t) + 255) / 256 * 256;
-    p.bytes = p.off_cand + segs * (size_t)kSubCap * sizeof(uint2);
+    p.bytes = p.off_cand + segs * (size_t)kSubCap * entry_bytes;
   }
   return p;
 }
@@ -76,34 +79,37 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
 // Scoring primitives
 // ------------------------------------------------------------------------------------------
 
-// Score of one token for one head from an [m][c] single-head table in LDS (random c -> random
+// Exact score of one token for one head from the head's [m][c] table in LDS (random c -> random
 // banks; a [c][m] order would put every lane of a read on the same two banks).
 template <int M>
-__device__ __forceinline__ int32_t score_one_head(const uint8_t* row, const int32_t* lut1) {
+__device__ __forceinline__ int32_t score_exact(const uint32_t (&w)[M / 4], const int32_t* lut1) {
   int32_t s = 0;
 #pragma unroll
-  for (int qd = 0; qd < M / 16; ++qd) {
-    const uint4 w = *(const uint4*)(row + qd * 16);
-    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const uint32_t byte = (ww[i >> 2] >> (8 * (i & 3))) & 0xffu;
-      s += lut1[(qd * 16 + i) * kCentroids + byte];
-    }
-  }
+  for (int i = 0; i < M; ++i) s += lut1[i * kCentroids + ((w[i >> 2] >> (8 * (i & 3))) & 0xffu)];
   return s;
 }
 
-// Scores of one token for the four heads of a group from the table in LDS, which is held as
-// [M/16 halves][256 c][16 m][4 heads] (for M = 16 this is the global [c][m][4] order).
+template <int M>
+__device__ __forceinline__ int32_t score_exact_row(const uint8_t* row, const int32_t* lut1) {
+  uint32_t w[M / 4];
+#pragma unroll
+  for (int qd = 0; qd < M / 16; ++qd) {
+    const uint4 v = *(const uint4*)(row + qd * 16);
+    w[4 * qd] = v.x; w[4 * qd + 1] = v.y; w[4 * qd + 2] = v.z; w[4 * qd + 3] = v.w;
+  }
+  return score_exact<M>(w, lut1);
+}
+
+// Coarse scores of one token for the four heads of a group.  The coarse table sits in LDS as
+// [M/16 halves][256 c][16 m] 8-byte entries (two 32-bit words, each holding two heads' 16-bit
+// values), i.e. 128 bytes = all 32 banks per centroid row, entry m on banks 2m and 2m+1.
 //
-// LDS serves a 16-byte read 8 lanes at a time (128 B per clock); lanes whose addresses agree
-// modulo 128 B collide.  With the table stored [c][m][4] (256 B per centroid row, subspace m
-// at byte 16*m of the row) the bank group of a read is m mod 8, whatever the code byte is.
-// Lane L therefore visits the subspaces of its row in the order m = t ^ (L & 15), t = 0..15
-// (per 16-byte half row): in every read the 8 lanes served together touch 8 different bank
-// groups, so random codes cause no conflicts.  The order does not matter for the result
-// because scores are integer sums.
+// LDS serves an 8-byte read 16 lanes at a time; lanes collide when they touch the same banks.
+// With this layout the banks of a read depend only on m, not on the (random) code byte, so lane
+// L visits the subspaces of its row in the order m = t ^ (L & 15), t = 0..15 (per 16-byte half
+// row): the 16 lanes served together always touch 16 different entries of their rows, and
+// random codes cause no conflicts.  The visiting order does not change the result because the
+// scores are integer sums.
 template <int M>
 struct LaneSwizzle {
   uint32_t mc[M / 4];   // byte t&3 of mc[t>>2]: (m & 15) << 4 for step t of this lane
@@ -126,10 +132,10 @@ struct LaneSwizzle {
 };
 
 template <int M>
-__device__ __forceinline__ void score_four_heads(const uint4 (&w)[M / 16], const int4* lutv,
-                                                 const LaneSwizzle<M>& sw, int32_t (&acc)[4]) {
-  acc[0] = acc[1] = acc[2] = acc[3] = 0;
-  const unsigned char* base = (const unsigned char*)lutv;
+__device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const unsigned char* tbl,
+                                             const LaneSwizzle<M>& sw, uint32_t& a01, uint32_t& a23) {
+  a01 = 0;
+  a23 = 0;
 #pragma unroll
   for (int qd = 0; qd < M / 16; ++qd) {
     // z[d] = row dword (d ^ (rho >> 2))
@@ -138,27 +144,23 @@ __device__ __forceinline__ void score_four_heads(const uint4 (&w)[M / 16], const
     const uint32_t z[4] = {sw.swap2 ? x2 : x0, sw.swap2 ? x3 : x1, sw.swap2 ? x0 : x2, sw.swap2 ? x1 : x3};
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
-      // (code byte << 8) | (m << 4): byte offset of entry [c][m] inside this half's 64 KB table
-      const uint32_t off = __builtin_amdgcn_perm(z[t >> 2], sw.mc[qd * 4 + (t >> 2)], sw.sel[t & 3]);
-      const int4 e = *(const int4*)(base + qd * 65536 + off);
-      acc[0] += e.x; acc[1] += e.y; acc[2] += e.z; acc[3] += e.w;
+      // v_perm builds (code byte << 8) | (m << 4); halved it is the byte offset (c << 7) | (m << 3)
+      const uint32_t off = __builtin_amdgcn_perm(z[t >> 2], sw.mc[qd * 4 + (t >> 2)], sw.sel[t & 3]) >> 1;
+      const uint2 e = *(const uint2*)(tbl + qd * (kCentroids * 128) + off);
+      a01 += e.x;
+      a23 += e.y;
     }
   }
 }
 
-// LDS slot of global table entry e = c * M + m.
-template <int M>
-__device__ __forceinline__ int lds_slot(int e) {
-  if (M == 16) return e;
-  const int c = e / M, m = e % M;
-  return (m >> 4) * (kCentroids * 16) + c * 16 + (m & 15);
-}
-
+// Copy a problem's coarse table (already in LDS order) to LDS.
 template <int M, int NT>
-__device__ __forceinline__ void load_group_lut(const int32_t* __restrict__ lut_grp, int4* lutv) {
-  const int4* src = (const int4*)lut_grp;
+__device__ __forceinline__ void load_coarse_table(const int32_t* __restrict__ lut, const LutLayout& lay,
+                                                  int prob, unsigned char* tbl) {
+  const int4* src = (const int4*)(lut + lay.off_coarse + (size_t)prob * (kCentroids * M * 2));
+  int4* dst = (int4*)tbl;
 #pragma unroll 4
-  for (int e = threadIdx.x; e < kCentroids * M; e += NT) lutv[lds_slot<M>(e)] = src[e];
+  for (int e = threadIdx.x; e < kCentroids * M / 2; e += NT) dst[e] = src[e];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -172,18 +174,22 @@ struct ExactLds {
   int32_t sub_min[32], sub_max[32];
 };
 
-// Exact top-K for one head by the whole workgroup.  `lut1` is kCentroids*M words of LDS.
-// Writes out_idx[0..kk) ascending (and out_score) ; the caller has written the count and the
-// -1 padding.  Requires sr.kk >= 1.
+// Exact top-K for one head by the whole workgroup.  `head_table` is the head's [m][c] table in
+// global memory, `lut1` kCentroids*M words of LDS.  Writes out_idx[0..kk) ascending (and
+// out_score); the caller has written the count and the -1 padding.  Requires sr.kk >= 1.
 template <int M>
 __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
-                                   const int32_t* __restrict__ lut_grp, int r, float scale,
+                                   const int32_t* __restrict__ head_table, float scale,
                                    const SeqRange& sr, int32_t* __restrict__ out_idx,
                                    float* __restrict__ out_score, int32_t* lut1, ExactLds& L) {
   constexpr int NT = kExactThreads;
   const int tid = threadIdx.x;
-  for (int e = tid; e < kCentroids * M; e += NT)   // e = c * M + m in the global order
-    lut1[(e % M) * kCentroids + e / M] = lut_grp[e * kHeadsPerGroup + r];
+  __syncthreads();   // lut1 may alias LDS the caller was still reading
+  for (int e = tid; e < kCentroids * M; e += NT) lut1[e] = head_table[e];
+  if (tid < 32) {
+    L.sub_min[tid] = INT32_MAX;
+    L.sub_max[tid] = INT32_MIN;
+  }
   __syncthreads();
 
   const int lo = sr.sink_end, hi = sr.win_start;
@@ -192,11 +198,6 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
     // Bounds of any score (sum of per-subspace minima / maxima): radix digits are taken from
     // key - key(lower bound), so that the histogram bins spread over the occupied range
     // instead of all keys sharing their leading bits.
-    if (tid < 32) {
-      L.sub_min[tid] = INT32_MAX;
-      L.sub_max[tid] = INT32_MIN;
-    }
-    __syncthreads();
     for (int e = tid; e < kCentroids * M; e += NT) {   // e = m * 256 + c: a wave covers one m
       int32_t mn = lut1[e], mx = mn;
 #pragma unroll
@@ -226,7 +227,7 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       __syncthreads();
       for (int j = lo + tid; j < hi; j += NT) {
-        const uint32_t key = score_key(score_one_head<M>(seq_codes + (size_t)j * M, lut1)) - k_lo;
+        const uint32_t key = score_key(score_exact_row<M>(seq_codes + (size_t)j * M, lut1)) - k_lo;
         if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
       }
       __syncthreads();
@@ -239,9 +240,6 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
       __syncthreads();
     }
     kth = prefix + k_lo;
-  } else {
-    kth = 0;  // every candidate is taken
-    k_rem = (uint32_t)sr.kk;
   }
 
   // Ordered emission: keys above the K-th, plus the first k_rem positions that equal it.
@@ -253,7 +251,7 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
     int32_t s = 0;
     uint32_t gt = 0, eq = 0;
     if (j < hi) {
-      s = score_one_head<M>(seq_codes + (size_t)j * M, lut1);
+      s = score_exact_row<M>(seq_codes + (size_t)j * M, lut1);
       const uint32_t key = score_key(s);
       gt = take_all ? 1u : (key > kth ? 1u : 0u);
       eq = take_all ? 0u : (key == kth ? 1u : 0u);
@@ -278,12 +276,12 @@ __global__ __launch_bounds__(kExactThreads) void select_exact_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ topk_count,
-    float* __restrict__ topk_score, int Hq, int Hkv, int NG, int ctx_len, int64_t ctx_stride,
+    float* __restrict__ topk_score, int B, int Hq, int Hkv, int ctx_len, int64_t ctx_stride,
     int top_k, int window, int n_sink) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ ExactLds L;
   const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq;
-  const int G = Hq / Hkv, kv = h / G, hg = h % G;
+  const int G = Hq / Hkv, kv = h / G;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   int32_t* oi = topk_idx + (size_t)bh * top_k;
   float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
@@ -293,72 +291,51 @@ __global__ __launch_bounds__(kExactThreads) void select_exact_kernel(
     if (os) os[t] = 0.f;
   }
   if (sr.kk == 0) return;
-  const int32_t* lut_grp =
-      lut + (((size_t)b * Hkv + kv) * NG + hg / kHeadsPerGroup) * (kCentroids * M * kHeadsPerGroup);
-  exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M, lut_grp,
-                        hg % kHeadsPerGroup, lut_scale[bh], sr, oi, os, (int32_t*)dyn_lds, L);
+  const LutLayout lay = lut_layout(B, Hq, Hkv, M);
+  exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M,
+                        lut + lay.off_exact + (size_t)bh * (kCentroids * M), lut_scale[bh], sr, oi, os,
+                        (int32_t*)dyn_lds, L);
 }
 
 // ------------------------------------------------------------------------------------------
-// Debug: dense scores for every token (not on the fast path; used by parity tests)
+// Debug: dense exact scores for every token (not on the fast path; used by parity tests)
 // ------------------------------------------------------------------------------------------
 template <int M>
 __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
-    float* __restrict__ scores_out, int Hq, int Hkv, int NG, int ctx_len, int64_t ctx_stride) {
+    float* __restrict__ scores_out, int B, int Hq, int Hkv, int ctx_len, int64_t ctx_stride) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  int4* lutv = (int4*)dyn_lds;
-  const int prob = blockIdx.y;  // (b, kv, g4)
-  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
-  const int G = Hq / Hkv;
-  load_group_lut<M, kStreamThreads>(lut + (size_t)prob * (kCentroids * M * kHeadsPerGroup), lutv);
+  int32_t* lut1 = (int32_t*)dyn_lds;
+  const int bh = blockIdx.y, b = bh / Hq, h = bh % Hq;
+  const int G = Hq / Hkv, kv = h / G;
+  const LutLayout lay = lut_layout(B, Hq, Hkv, M);
+  const int32_t* head_table = lut + lay.off_exact + (size_t)bh * (kCentroids * M);
+  for (int e = threadIdx.x; e < kCentroids * M; e += kStreamThreads) lut1[e] = head_table[e];
   __syncthreads();
   int n = seq_lens ? seq_lens[b] : ctx_len;
   n = n < 0 ? 0 : (n > ctx_len ? ctx_len : n);
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
-  LaneSwizzle<M> sw;
-  sw.init(threadIdx.x & 63);
-  float sc[4];
-  for (int r = 0; r < 4; ++r) {
-    const int hg = g4 * kHeadsPerGroup + r;
-    sc[r] = hg < G ? lut_scale[(size_t)b * Hq + kv * G + hg] : 0.f;
-  }
-  for (int j = blockIdx.x * kStreamThreads + threadIdx.x; j < n; j += gridDim.x * kStreamThreads) {
-    uint4 w[M / 16];
-#pragma unroll
-    for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
-    int32_t acc[4];
-    score_four_heads<M>(w, lutv, sw, acc);
-    for (int r = 0; r < 4; ++r) {
-      const int hg = g4 * kHeadsPerGroup + r;
-      if (hg < G) scores_out[((size_t)b * Hq + kv * G + hg) * ctx_stride + j] = (float)acc[r] * sc[r];
-    }
-  }
+  const float sc = lut_scale[bh];
+  for (int j = blockIdx.x * kStreamThreads + threadIdx.x; j < n; j += gridDim.x * kStreamThreads)
+    scores_out[(size_t)bh * ctx_stride + j] = (float)score_exact_row<M>(seq_codes + (size_t)j * M, lut1) * sc;
 }
 
 // ------------------------------------------------------------------------------------------
-// Fast route, stage 1: sampled thresholds
+// Fast route, stage 1: sampled coarse thresholds
 // ------------------------------------------------------------------------------------------
 template <int M>
 __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
-    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int Hq, int Hkv, int NG,
-    int P0, int ctx_len,
-    int64_t ctx_stride, int top_k, int window, int n_sink) {
+    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int B, int Hq, int Hkv, int NG,
+    int P0, int problems, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kSampleThreads;
-  constexpr int NW = NT / 64;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  int4* lutv = (int4*)dyn_lds;
+  unsigned char* tbl = dyn_lds;
   __shared__ uint32_t s_hist[2][kHistBins];   // two heads per word, 16-bit counts (<= 1024 each)
-  __shared__ int32_t s_mm[NW][M][8];
-  __shared__ int32_t s_red[M][8];
-  __shared__ int32_t s_lo[kHeadsPerGroup];
-  __shared__ int32_t s_shift[kHeadsPerGroup];
-  __shared__ uint32_t s_wave[NW];
-  __shared__ uint32_t s_res[2];
 
-  const int p = blockIdx.x, prob = blockIdx.y;
+  int p, prob;
+  xcd_map(blockIdx.x, P0, problems, prob, p);
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
@@ -382,84 +359,66 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
     return;
   }
 
-  // table -> LDS, with per-(subspace, head) min / max of the entries this thread copies
-  const int4* src = (const int4*)(lut + (size_t)prob * (kCentroids * M * kHeadsPerGroup));
-  int32_t mn[4] = {INT32_MAX, INT32_MAX, INT32_MAX, INT32_MAX};
-  int32_t mxv[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
-  for (int e = tid; e < kCentroids * M; e += NT) {   // e % M == tid % M for every e of a thread
-    const int4 v = src[e];
-    lutv[lds_slot<M>(e)] = v;
-    mn[0] = min(mn[0], v.x); mn[1] = min(mn[1], v.y); mn[2] = min(mn[2], v.z); mn[3] = min(mn[3], v.w);
-    mxv[0] = max(mxv[0], v.x); mxv[1] = max(mxv[1], v.y); mxv[2] = max(mxv[2], v.z); mxv[3] = max(mxv[3], v.w);
-  }
+  const LutLayout lay = lut_layout(B, Hq, Hkv, M);
+  load_coarse_table<M, NT>(lut, lay, prob, tbl);
   for (int i = tid; i < 2 * kHistBins; i += NT) (&s_hist[0][0])[i] = 0;
-#pragma unroll
-  for (int off = M; off < 64; off <<= 1) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      mn[r] = min(mn[r], __shfl_xor(mn[r], off));
-      mxv[r] = max(mxv[r], __shfl_xor(mxv[r], off));
-    }
-  }
-  if (lane < M) {
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      s_mm[wv][lane][r] = mn[r];
-      s_mm[wv][lane][4 + r] = mxv[r];
-    }
-  }
-  __syncthreads();
-  if (tid < M * 8) {
-    const int m = tid / 8, c = tid % 8;
-    int32_t v = s_mm[0][m][c];
-    for (int w = 1; w < NW; ++w) v = c < 4 ? min(v, s_mm[w][m][c]) : max(v, s_mm[w][m][c]);
-    s_red[m][c] = v;
-  }
-  __syncthreads();
-  if (tid < kHeadsPerGroup) {
-    int32_t lo = 0, hi = 0;
-    for (int m = 0; m < M; ++m) {
-      lo += s_red[m][tid];
-      hi += s_red[m][4 + tid];
-    }
-    const uint32_t range = (uint32_t)(hi - lo);
-    int sh = 32 - __clz(range) - 11;   // smallest shift with (range >> shift) < 2048
-    s_lo[tid] = lo;
-    s_shift[tid] = sh < 0 ? 0 : sh;
-  }
   __syncthreads();
 
-  // score this workgroup's share of the strided sample
+  // Score this workgroup's share of the strided sample.  A coarse score is below 2^16, so
+  // score >> 5 indexes a 2048-bin histogram directly.
   LaneSwizzle<M> sw;
   sw.init(lane);
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
-  const int lo0 = s_lo[0], lo1 = s_lo[1], lo2 = s_lo[2], lo3 = s_lo[3];
-  const int sh0 = s_shift[0], sh1 = s_shift[1], sh2 = s_shift[2], sh3 = s_shift[3];
   for (int i = tid; i < s_p; i += NT) {
     const long g = (long)p * s_p + i;
     const int j = sr.sink_end + (int)((g * sr.ncand) / s_all);
     uint4 w[M / 16];
 #pragma unroll
     for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
-    int32_t acc[4];
-    score_four_heads<M>(w, lutv, sw, acc);
-    atomicAdd(&s_hist[0][(uint32_t)(acc[0] - lo0) >> sh0], 1u);
-    atomicAdd(&s_hist[0][(uint32_t)(acc[1] - lo1) >> sh1], 1u << 16);
-    atomicAdd(&s_hist[1][(uint32_t)(acc[2] - lo2) >> sh2], 1u);
-    atomicAdd(&s_hist[1][(uint32_t)(acc[3] - lo3) >> sh3], 1u << 16);
+    uint32_t a01, a23;
+    score_coarse<M>(w, tbl, sw, a01, a23);
+    atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);
+    atomicAdd(&s_hist[0][a01 >> 21], 1u << 16);
+    atomicAdd(&s_hist[1][(a23 & 0xffffu) >> 5], 1u);
+    atomicAdd(&s_hist[1][a23 >> 21], 1u << 16);
   }
   __syncthreads();
-#pragma unroll 1
-  for (int r = 0; r < kHeadsPerGroup; ++r) {
-    block_find_rank_desc<NT, kHistBins>(
-        [&](int i) { return (s_hist[r >> 1][i] >> (16 * (r & 1))) & 0xffffu; }, (uint32_t)r_p, s_wave, s_res);
-    if (tid == 0) {
-      const int hg = g4 * kHeadsPerGroup + r;
-      // lower edge of the bin holding the r_p-th largest sample: at least r_p samples are >= it
-      if (hg < G)
-        thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = s_lo[r] + (int32_t)(s_res[0] << s_shift[r]);
+  // Rank search, one wave per head: lane l owns bins [32 l, 32 l + 32); a suffix scan over the
+  // lanes finds the one whose range holds the r_p-th largest sample, and that lane walks its bins.
+  if (wv < kHeadsPerGroup) {
+    const int r = wv;
+    const int hg = g4 * kHeadsPerGroup + r;
+    const uint32_t* hrow = s_hist[r >> 1];
+    const int fsh = 16 * (r & 1);
+    uint32_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+      const int ii = (i + lane) & 31;   // rotate the walk so the lanes of a read hit different banks
+      sum += (hrow[32 * lane + ii] >> fsh) & 0xffffu;
     }
-    __syncthreads();
+    uint32_t inc = sum;   // inclusive suffix sum over lanes (higher lanes hold higher bins)
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t o = __shfl_down(inc, off);
+      if (lane + off < 64) inc += o;
+    }
+    const uint32_t k = (uint32_t)r_p, above_lane = inc - sum;
+    if (above_lane < k && k <= inc && hg < G) {
+      uint32_t run = above_lane;
+      int bin = 32 * lane;
+      for (int i = 31; i >= 0; --i) {
+        const uint32_t c = (hrow[32 * lane + i] >> fsh) & 0xffffu;
+        if (run + c >= k) {
+          bin = 32 * lane + i;
+          break;
+        }
+        run += c;
+      }
+      // Lower edge of the bin holding the r_p-th largest sample (at least r_p samples reach it),
+      // lowered by M: a row's coarse score is below its exact score by less than M coarse units,
+      // and the final kernel needs that much slack to prove its result complete.
+      thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = max(0, (bin << 5) - M);
+    }
   }
 }
 
@@ -470,166 +429,176 @@ template <int M>
 __device__ __forceinline__ void stream_select_body(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
-    uint32_t* __restrict__ seg_count, uint2* __restrict__ cand, int Hq, int Hkv, int NG, int P0,
-    int rows_per_chunk, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink) {
+    uint32_t* __restrict__ seg_count, uint32_t* __restrict__ cand, int B, int Hq, int Hkv, int NG,
+    int P0, int n_chunks, int problems, int rows_per_chunk, int ctx_len, int64_t ctx_stride,
+    int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
+  constexpr int EW = 2 + M / 4;   // words per survivor entry: position, coarse score, code bytes
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  int4* lutv = (int4*)dyn_lds;
-  uint2* stage_all = (uint2*)(dyn_lds + (size_t)kCentroids * M * sizeof(int4));
+  unsigned char* tbl = dyn_lds;
 
-  const int chunk = blockIdx.x, n_chunks = gridDim.x, prob = blockIdx.y;
+  int chunk, prob;
+  xcd_map(blockIdx.x, n_chunks, problems, prob, chunk);
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   const long begin = (long)sr.sink_end + (long)chunk * rows_per_chunk;
   const int end = (int)min((long)sr.win_start, begin + rows_per_chunk);
+  // A wave owns a contiguous run of rows, so its survivors come out in ascending position and
+  // the segments of a head, taken in (chunk, wave) order, are sorted by position.
+  const int rows_per_wave = rows_per_chunk / kStreamWaves;
+  const long wbegin = begin + (long)wv * rows_per_wave;
+  const int wend = (int)min((long)end, wbegin + rows_per_wave);
 
-  // Every (head, chunk, wave) owns one candidate segment in HBM: no atomics, no contention.
+  // Every (head, chunk, wave) owns one survivor segment in HBM: no atomics, no contention.
   size_t seg[4];
   bool live[4];
+  int32_t T[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int hg = g4 * kHeadsPerGroup + r;
     live[r] = hg < G;
     const size_t head = (size_t)b * Hq + kv * G + (live[r] ? hg : 0);
     seg[r] = (head * n_chunks + chunk) * kStreamWaves + wv;
+    int32_t t = INT32_MAX;   // padded heads never produce survivors
+    if (live[r]) {
+      t = thr[head * P0];
+      for (int pp = 1; pp < P0; ++pp) t = min(t, thr[head * P0 + pp]);
+    }
+    T[r] = t;
   }
-  if (begin >= sr.win_start) {   // nothing to score: publish empty segments
+  if (begin >= sr.win_start) {   // nothing to score in this chunk: publish empty segments
 #pragma unroll
     for (int r = 0; r < 4; ++r)
       if (live[r] && lane == 0) seg_count[seg[r]] = 0;
     return;
   }
 
-  load_group_lut<M, NT>(lut + (size_t)prob * (kCentroids * M * kHeadsPerGroup), lutv);
-
-  int32_t T[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    int32_t t = INT32_MAX;   // padded heads never produce candidates
-    if (live[r]) {
-      const size_t head = seg[r] / ((size_t)n_chunks * kStreamWaves);
-      t = thr[head * P0];
-      for (int pp = 1; pp < P0; ++pp) t = min(t, thr[head * P0 + pp]);
-    }
-    T[r] = t;
-  }
+  const LutLayout lay = lut_layout(B, Hq, Hkv, M);
+  load_coarse_table<M, NT>(lut, lay, prob, tbl);
   __syncthreads();
 
-  uint2* stage = stage_all + (size_t)wv * kHeadsPerGroup * kStageCap;
   LaneSwizzle<M> sw;
   sw.init(lane);
-  int cnt[4] = {0, 0, 0, 0};   // staged in LDS, per head (wave-uniform)
-  int done[4] = {0, 0, 0, 0};  // already copied to this wave's HBM segment
+  int done[4] = {0, 0, 0, 0};   // survivors of this wave so far, per head (wave-uniform)
 
-  // Copy the staged entries of head r to the wave's segment.  Entries past the segment capacity
-  // are dropped but still counted, which the final kernel recognises as an overflow.
-  auto flush = [&](int r) {
-    const int n = cnt[r];
-    if (n == 0) return;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    for (int i = lane; i < n; i += 64)
-      if (done[r] + i < kSubCap) cand[seg[r] * kSubCap + done[r] + i] = stage[r * kStageCap + i];
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    done[r] += n;
-    cnt[r] = 0;
-  };
-
-  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
-  // Rows are read U at a time per thread, one full step ahead of their use (two register sets
-  // used alternately), so every wave keeps up to 2*U 16-byte loads in flight while it gathers.
-  constexpr int U = 4;
-  constexpr int STEP = NT * U;
-  uint4 rows_a[U][M / 16], rows_b[U][M / 16];
-  // Loads are unconditional (row index clamped into the chunk) so that the wait before the
-  // gathers only covers the older of the two row sets in flight.
-  auto load_rows = [&](int base, uint4 (&dst)[U][M / 16]) {
+  if (wbegin < wend) {
+    const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+    // Rows are read U at a time per lane, one full step ahead of their use (two register sets
+    // used alternately); loads are unconditional (row index clamped into the wave's range) so
+    // that the wait before the gathers only covers the older of the two sets in flight.
+    constexpr int U = 4;
+    constexpr int STEP = 64 * U;
+    uint4 rows_a[U][M / 16], rows_b[U][M / 16];
+    auto load_rows = [&](int base, uint4 (&dst)[U][M / 16]) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int j = base + u * NT + tid;
-      const int jl = j < end ? j : end - 1;
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * 64 + lane;
+        const int jl = j < wend ? j : wend - 1;
 #pragma unroll
-      for (int qd = 0; qd < M / 16; ++qd)
-        dst[u][qd] = load_stream_u4(seq_codes + (size_t)jl * M + qd * 16);
-    }
-  };
-  auto process = [&](int base, const uint4 (&rows)[U][M / 16]) {
-    // Scores and the per-head "at or above threshold" wave masks are formed together, so the
-    // gathered table entries die inside this straight-line block.
-    int32_t acc[U][4];
-    uint64_t hit[U][4];
+        for (int qd = 0; qd < M / 16; ++qd)
+          dst[u][qd] = load_stream_u4(seq_codes + (size_t)jl * M + qd * 16);
+      }
+    };
+    auto process = [&](int base, const uint4 (&rows)[U][M / 16]) {
+      // Scores and the per-head "reaches the threshold" wave masks are formed together, so the
+      // gathered table entries die inside this straight-line block.
+      uint32_t a01[U], a23[U];
+      uint64_t hit[U][4];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      score_four_heads<M>(rows[u], lutv, sw, acc[u]);
-      const bool valid = base + u * NT + tid < end;
+      for (int u = 0; u < U; ++u) {
+        score_coarse<M>(rows[u], tbl, sw, a01[u], a23[u]);
+        const bool valid = base + u * 64 + lane < wend;
+        hit[u][0] = __ballot(valid && (int32_t)(a01[u] & 0xffffu) >= T[0]);
+        hit[u][1] = __ballot(valid && (int32_t)(a01[u] >> 16) >= T[1]);
+        hit[u][2] = __ballot(valid && (int32_t)(a23[u] & 0xffffu) >= T[2]);
+        hit[u][3] = __ballot(valid && (int32_t)(a23[u] >> 16) >= T[3]);
+        __builtin_amdgcn_sched_barrier(0);   // one row's gathers at a time: bounds live registers
+      }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) hit[u][r] = __ballot(valid && acc[u][r] >= T[r]);
-      __builtin_amdgcn_sched_barrier(0);   // one row's gathers at a time: bounds live registers
-    }
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * 64 + lane;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int j = base + u * NT + tid;
+        for (int r = 0; r < 4; ++r) {
+          const uint64_t mask = hit[u][r];
+          if (mask) {
+            if ((mask >> lane) & 1) {
+              const int slot = done[r] + lanes_below(mask);
+              if (slot < kSubCap) {   // entries past the capacity are dropped but still counted
+                const uint32_t a = r < 2 ? a01[u] : a23[u];
+                uint2* e = (uint2*)(cand + (seg[r] * kSubCap + slot) * EW);
+                e[0] = make_uint2((uint32_t)j, (r & 1) ? (a >> 16) : (a & 0xffffu));
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const uint64_t mask = hit[u][r];
-        if (mask) {
-          const int n = __popcll(mask);
-          if (cnt[r] + n > kStageCap) flush(r);
-          if ((mask >> lane) & 1)
-            stage[r * kStageCap + cnt[r] + lanes_below(mask)] = make_uint2((uint32_t)j, (uint32_t)acc[u][r]);
-          cnt[r] += n;
+                for (int qd = 0; qd < M / 16; ++qd) {
+                  e[1 + 2 * qd] = make_uint2(rows[u][qd].x, rows[u][qd].y);
+                  e[2 + 2 * qd] = make_uint2(rows[u][qd].z, rows[u][qd].w);
+                }
+              }
+            }
+            done[r] += __popcll(mask);
+          }
         }
       }
-    }
-  };
-  load_rows((int)begin, rows_a);
+    };
+    load_rows((int)wbegin, rows_a);
 #pragma unroll 1
-  for (int base = (int)begin; base < end; base += 2 * STEP) {
-    load_rows(base + STEP, rows_b);
-    process(base, rows_a);
-    load_rows(base + 2 * STEP, rows_a);
-    process(base + STEP, rows_b);
+    for (int base = (int)wbegin; base < wend; base += 2 * STEP) {
+      load_rows(base + STEP, rows_b);
+      process(base, rows_a);
+      load_rows(base + 2 * STEP, rows_a);
+      process(base + STEP, rows_b);
+    }
   }
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    flush(r);
+  for (int r = 0; r < 4; ++r)
     if (live[r] && lane == 0) seg_count[seg[r]] = (uint32_t)done[r];
-  }
 }
 
 #define A2ATS_STREAM_ARGS                                                                          \
   const uint8_t *__restrict__ codes, const int32_t *__restrict__ lut,                             \
       const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ thr,                      \
-      uint32_t *__restrict__ seg_count, uint2 *__restrict__ cand, int Hq, int Hkv, int NG, int P0, \
-      int rows_per_chunk, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink
+      uint32_t *__restrict__ seg_count, uint32_t *__restrict__ cand, int B, int Hq, int Hkv, int NG, \
+      int P0, int n_chunks, int problems, int rows_per_chunk, int ctx_len, int64_t ctx_stride,     \
+      int top_k, int window, int n_sink
 #define A2ATS_STREAM_PASS                                                                          \
-  codes, lut, seq_lens, thr, seg_count, cand, Hq, Hkv, NG, P0, rows_per_chunk, ctx_len,            \
-      ctx_stride, top_k, window, n_sink
+  codes, lut, seq_lens, thr, seg_count, cand, B, Hq, Hkv, NG, P0, n_chunks, problems,              \
+      rows_per_chunk, ctx_len, ctx_stride, top_k, window, n_sink
 
-// M = 16: 80 KB of LDS per workgroup, two workgroups per CU -> 4 waves per SIMD, 128 VGPRs.
+// M = 16: 32 KB of LDS per workgroup; 128 VGPRs -> 4 waves per SIMD (two workgroups per CU).
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void stream_select_kernel16(A2ATS_STREAM_ARGS) { stream_select_body<16>(A2ATS_STREAM_PASS); }
-// M = 32: 144 KB of LDS, one workgroup per CU -> 2 waves per SIMD.
-__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// M = 32: 64 KB of LDS per workgroup, twice the row registers.
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
 void stream_select_kernel32(A2ATS_STREAM_ARGS) { stream_select_body<32>(A2ATS_STREAM_PASS); }
 
-
 // ------------------------------------------------------------------------------------------
-// Fast route, stage 3: exact selection among the candidates, ordered output
+// Fast route, stage 3: exact scores of the survivors, exact selection, ordered output
 // ------------------------------------------------------------------------------------------
 template <int M>
 __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
-    const uint32_t* __restrict__ seg_count, const uint2* __restrict__ cand,
-    int32_t* __restrict__ topk_idx, int32_t* __restrict__ topk_count,
-    float* __restrict__ topk_score, int Hq, int Hkv, int NG, int n_seg, int cap, int ctx_len,
-    int64_t ctx_stride, int top_k, int window, int n_sink) {
+    const int32_t* __restrict__ thr, const uint32_t* __restrict__ seg_count,
+    const uint32_t* __restrict__ cand, int32_t* __restrict__ topk_idx,
+    int32_t* __restrict__ topk_count, float* __restrict__ topk_score, int B, int Hq, int Hkv, int NG,
+    int P0, int problems, int n_seg, int cap, int ctx_len, int64_t ctx_stride, int top_k,
+    int window, int n_sink) {
   constexpr int NT = kExactThreads;
+  constexpr int EW = 2 + M / 4;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ ExactLds L;
-  const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq;
-  const int G = Hq / Hkv, kv = h / G, hg = h % G, tid = threadIdx.x;
+  __shared__ uint32_t s_seg_off[513];
+  __shared__ uint32_t s_overflow, s_small_n, s_kth;
+  __shared__ uint32_t s_small_key[kSmallList];
+
+  // one workgroup per (problem, head slot), on the XCD that streamed the problem
+  int prob, r;
+  xcd_map(blockIdx.x, kHeadsPerGroup, problems, prob, r);
+  const int G = Hq / Hkv;
+  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
+  const int hg = g4 * kHeadsPerGroup + r;
+  if (hg >= G) return;
+  const int bh = b * Hq + kv * G + hg, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   int32_t* oi = topk_idx + (size_t)bh * top_k;
   float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
@@ -640,12 +609,25 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   }
   if (sr.kk == 0) return;
   const float scale = lut_scale[bh];
-  // Candidate segments of this head (one per chunk and wave of the streaming pass): exclusive
-  // prefix of their sizes.  n_seg <= 512 <= NT.
-  __shared__ uint32_t s_seg_off[513];
-  __shared__ uint32_t s_overflow;
-  if (tid == 0) s_overflow = 0;
+  const LutLayout lay = lut_layout(B, Hq, Hkv, M);
+  const int32_t* head_table = lut + lay.off_exact + (size_t)bh * (kCentroids * M);
+  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+
+  // LDS carve-up: the head's exact table, survivor keys and positions
+  int32_t* lut1 = (int32_t*)dyn_lds;
+  uint32_t* c_key = (uint32_t*)(lut1 + kCentroids * M);
+  uint32_t* c_pos = c_key + cap;
+
+  for (int e = tid; e < kCentroids * M; e += NT) lut1[e] = head_table[e];
+  for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
+  if (tid == 0) {
+    s_overflow = 0;
+    s_small_n = 0;
+    s_kth = 0;
+  }
   __syncthreads();
+  // Survivor segments of this head (one per chunk and wave of the streaming pass, sorted by
+  // position when taken in order): exclusive prefix of their sizes.  n_seg <= 512 <= NT.
   uint32_t my_cnt = 0;
   if (tid < n_seg) {
     my_cnt = seg_count[(size_t)bh * n_seg + tid];
@@ -657,45 +639,42 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   if (tid == 0) s_seg_off[n_seg] = n_c;
   __syncthreads();
   if (s_overflow || n_c > (uint32_t)cap || n_c < (uint32_t)sr.kk) {
-    const int32_t* lut_grp = lut + (((size_t)b * Hkv + kv) * NG + hg / kHeadsPerGroup) *
-                                       (kCentroids * M * kHeadsPerGroup);
-    exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M, lut_grp,
-                          hg % kHeadsPerGroup, scale, sr, oi, os, (int32_t*)dyn_lds, L);
+    exact_select_block<M>(seq_codes, head_table, scale, sr, oi, os, lut1, L);
     return;
   }
 
-  // LDS carve-up: candidate positions and keys, position bitmap, per-word prefix counts
-  const int n_words = (ctx_len + 31) / 32;
-  uint32_t* c_idx = (uint32_t*)dyn_lds;
-  uint32_t* c_key = c_idx + cap;
-  uint32_t* bitmap = c_key + cap;
-  uint16_t* wpre = (uint16_t*)(bitmap + n_words);
-  constexpr uint32_t kDropped = 0x80000000u;
-
-  // Candidate keys are stored relative to the smallest one, so that the radix digits spread
-  // over the occupied range (all candidates share the leading bits of their absolute keys).
+  // Exact keys of the survivors (a wave per segment, a lane per entry) and their range.  Keys
+  // are then taken relative to the smallest one, so that radix digits spread over the occupied
+  // range instead of all survivors sharing the leading bits of their absolute keys.
   uint32_t kmin = 0xffffffffu, kmax = 0;
-  for (uint32_t i = tid; i < n_c; i += NT) {
-    int lo_s = 0, hi_s = n_seg;   // segment holding flat candidate i: last s with off[s] <= i
-    while (hi_s - lo_s > 1) {
-      const int mid = (lo_s + hi_s) >> 1;
-      if (s_seg_off[mid] <= i) lo_s = mid; else hi_s = mid;
+  for (int s_ = wv; s_ < n_seg; s_ += NT / 64) {
+    const uint32_t base = s_seg_off[s_], n = s_seg_off[s_ + 1] - base;
+    const uint32_t* src = cand + ((size_t)bh * n_seg + s_) * kSubCap * EW;
+    for (uint32_t i = lane; i < n; i += 64) {
+      const uint2* e = (const uint2*)(src + (size_t)i * EW);
+      uint32_t w[M / 4];
+      const uint32_t pos = e[0].x;
+#pragma unroll
+      for (int q2 = 0; q2 < M / 8; ++q2) {
+        const uint2 v = e[1 + q2];
+        w[2 * q2] = v.x;
+        w[2 * q2 + 1] = v.y;
+      }
+      const uint32_t key = score_key(score_exact<M>(w, lut1));
+      c_pos[base + i] = pos;
+      c_key[base + i] = key;
+      kmin = min(kmin, key);
+      kmax = max(kmax, key);
     }
-    const uint2 e = cand[((size_t)bh * n_seg + lo_s) * kSubCap + (i - s_seg_off[lo_s])];
-    const uint32_t key = score_key((int32_t)e.y);
-    c_idx[i] = e.x;
-    c_key[i] = key;
-    kmin = min(kmin, key);
-    kmax = max(kmax, key);
   }
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     kmin = min(kmin, __shfl_xor(kmin, off));
     kmax = max(kmax, __shfl_xor(kmax, off));
   }
-  if ((tid & 63) == 0) {
-    L.wave_a[tid >> 6] = kmin;
-    L.wave_b[tid >> 6] = kmax;
+  if (lane == 0) {
+    L.wave_a[wv] = kmin;
+    L.wave_b[wv] = kmax;
   }
   __syncthreads();
   kmin = L.wave_a[0];
@@ -704,80 +683,104 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     kmin = min(kmin, L.wave_a[w]);
     kmax = max(kmax, L.wave_b[w]);
   }
-  __syncthreads();
-  for (uint32_t i = tid; i < n_c; i += NT) c_key[i] -= kmin;
-  // K-th largest key among the candidates: MSB-first radix select over the significant bits
-  uint32_t prefix = 0, mask = 0, k_rem = (uint32_t)sr.kk, n_eq = n_c;
-  int remaining = 32 - __clz(kmax - kmin);
-#pragma unroll 1
-  while (remaining > 0) {
-    const int bits = remaining < 11 ? remaining : 11;
-    const int shift = remaining - bits;
-    const uint32_t dmask = (1u << bits) - 1u;
-    for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
-    __syncthreads();
-    for (uint32_t i = tid; i < n_c; i += NT) {
-      const uint32_t key = c_key[i];
-      if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
-    }
-    __syncthreads();
-    block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
-    const uint32_t bin = L.res[0], above = L.res[1];
-    n_eq = L.hist[bin];
-    k_rem -= above;
-    prefix |= bin << shift;
-    mask |= dmask << shift;
-    remaining = shift;
-    __syncthreads();
-  }
-  const uint32_t kth = prefix;   // relative to kmin, like c_key[]
 
-  // Rank of a position among the set bits of the bitmap: prefix popcounts per 32-bit word.
-  const int wpt = (n_words + NT - 1) / NT;
-  auto build_word_prefix = [&](uint32_t* s_wave) {
-    uint32_t loc = 0;
-    for (int i = 0; i < wpt; ++i) {
-      const int w = tid * wpt + i;
-      if (w < n_words) loc += __popc(bitmap[w]);
-    }
-    uint32_t tot;
-    uint32_t run = block_exclusive_scan<NT>(loc, s_wave, tot);
-    for (int i = 0; i < wpt; ++i) {
-      const int w = tid * wpt + i;
-      if (w < n_words) {
-        wpre[w] = (uint16_t)run;
-        run += __popc(bitmap[w]);
-      }
-    }
-    __syncthreads();
-  };
-  auto rank_of = [&](uint32_t pos) -> uint32_t {
-    return (uint32_t)wpre[pos >> 5] + __popc(bitmap[pos >> 5] & ((1u << (pos & 31)) - 1u));
-  };
-
-  if (n_eq > k_rem) {   // more candidates tie with the K-th key than fit: lowest positions win
-    for (int w = tid; w < n_words; w += NT) bitmap[w] = 0;
-    __syncthreads();
-    for (uint32_t i = tid; i < n_c; i += NT)
-      if (c_key[i] == kth) atomicOr(&bitmap[c_idx[i] >> 5], 1u << (c_idx[i] & 31));
-    __syncthreads();
-    build_word_prefix(L.wave_a);
-    for (uint32_t i = tid; i < n_c; i += NT)
-      if (c_key[i] == kth && rank_of(c_idx[i]) >= k_rem) c_idx[i] |= kDropped;
-    __syncthreads();
-  }
-  for (int w = tid; w < n_words; w += NT) bitmap[w] = 0;
-  __syncthreads();
-  for (uint32_t i = tid; i < n_c; i += NT)
-    if (c_key[i] >= kth && !(c_idx[i] & kDropped)) atomicOr(&bitmap[c_idx[i] >> 5], 1u << (c_idx[i] & 31));
-  __syncthreads();
-  build_word_prefix(L.wave_b);
+  // First radix level over the significant bits of the relative keys.
+  const int nbits = 32 - __clz(kmax - kmin);
+  const int bits1 = nbits < 11 ? nbits : 11, shift1 = nbits - bits1;
   for (uint32_t i = tid; i < n_c; i += NT) {
-    if (c_key[i] >= kth && !(c_idx[i] & kDropped)) {
-      const uint32_t pos = rank_of(c_idx[i]);
-      oi[pos] = (int32_t)c_idx[i];
-      if (os) os[pos] = (float)key_score(c_key[i] + kmin) * scale;
+    const uint32_t key = c_key[i] - kmin;
+    c_key[i] = key;
+    atomicAdd(&L.hist[key >> shift1], 1u);
+  }
+  __syncthreads();   // also orders the reads of wave_a / wave_b above before their reuse below
+  block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, (uint32_t)sr.kk, L.wave_a, L.res);
+  const uint32_t bin1 = L.res[0], above1 = L.res[1], m_bin = L.hist[bin1];
+  uint32_t k_rem = (uint32_t)sr.kk - above1;   // winners still to pick inside bin1
+  uint32_t kth;                                // K-th largest relative key
+  if (m_bin <= (uint32_t)kSmallList) {
+    // Usual case: the bin of the K-th key holds a handful of survivors; the k_rem-th largest of
+    // them is found by counting, for each member, the members above it.
+    for (uint32_t i = tid; i < n_c; i += NT)
+      if ((c_key[i] >> shift1) == bin1) s_small_key[atomicAdd(&s_small_n, 1u)] = c_key[i];
+    __syncthreads();
+    if ((uint32_t)tid < m_bin) {
+      const uint32_t key = s_small_key[tid];
+      uint32_t gt = 0, eq = 0;
+      for (uint32_t u = 0; u < m_bin; ++u) {
+        const uint32_t ku = s_small_key[u];
+        gt += ku > key ? 1u : 0u;
+        eq += ku == key ? 1u : 0u;
+      }
+      if (gt < k_rem && k_rem <= gt + eq) s_kth = key;   // every thread that qualifies holds this key
     }
+    __syncthreads();
+    kth = s_kth;
+  } else {
+    // Heavy ties: finish the radix select level by level.
+    uint32_t prefix = bin1 << shift1, mask = ((1u << bits1) - 1u) << shift1;
+    int remaining = shift1;
+    __syncthreads();
+#pragma unroll 1
+    while (remaining > 0) {
+      const int bits = remaining < 11 ? remaining : 11;
+      const int shift = remaining - bits;
+      const uint32_t dmask = (1u << bits) - 1u;
+      for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
+      __syncthreads();
+      for (uint32_t i = tid; i < n_c; i += NT) {
+        const uint32_t key = c_key[i];
+        if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
+      }
+      __syncthreads();
+      block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
+      const uint32_t bin = L.res[0], above = L.res[1];
+      k_rem -= above;
+      prefix |= bin << shift;
+      mask |= dmask << shift;
+      remaining = shift;
+      __syncthreads();
+    }
+    kth = prefix;
+  }
+
+  // Completeness: a row that is not a survivor has coarse score <= Tc - 1, hence exact score
+  // below base + ((Tc - 1 + M) << shift).  If the K-th survivor key reaches that bound, no such
+  // row can displace (or tie with) a winner.  Otherwise redo this head by the exact route.
+  {
+    int32_t tc = thr[(size_t)bh * P0];
+    for (int pp = 1; pp < P0; ++pp) tc = min(tc, thr[(size_t)bh * P0 + pp]);
+    const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
+    const long bound = (long)meta[0] + (((long)tc - 1 + M) << meta[1]);
+    const long kth_score = (long)key_score(kth + kmin);
+    if (tc != INT32_MIN && kth_score < bound) {
+      exact_select_block<M>(seq_codes, head_table, scale, sr, oi, os, lut1, L);
+      return;
+    }
+  }
+
+  // Winners: keys above the K-th, plus the first (K - #above) survivors equal to it.  Survivors
+  // are in ascending position, so a winner's output slot is the number of winners before it:
+  // one block scan over (above, equal) counts packed in a word.
+  const uint32_t per = (n_c + NT - 1) / NT;
+  const uint32_t i0 = min(n_c, (uint32_t)tid * per), i1 = min(n_c, i0 + per);
+  uint32_t loc = 0;
+  for (uint32_t i = i0; i < i1; ++i) {
+    const uint32_t key = c_key[i];
+    loc += (key > kth ? 1u : 0u) + (key == kth ? 0x10000u : 0u);
+  }
+  uint32_t tot;
+  uint32_t pre = block_exclusive_scan<NT>(loc, L.wave_b, tot);
+  const uint32_t k_eq = (uint32_t)sr.kk - (tot & 0xffffu);   // equal keys that still fit
+  for (uint32_t i = i0; i < i1; ++i) {
+    const uint32_t key = c_key[i];
+    const uint32_t gt_before = pre & 0xffffu, eq_before = pre >> 16;
+    const bool win = key > kth || (key == kth && eq_before < k_eq);
+    if (win) {
+      const uint32_t slot = gt_before + min(eq_before, k_eq);
+      oi[slot] = (int32_t)c_pos[i];
+      if (os) os[slot] = (float)key_score(key + kmin) * scale;
+    }
+    pre += (key > kth ? 1u : 0u) + (key == kth ? 0x10000u : 0u);
   }
 }
 
@@ -812,47 +815,33 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
   return hipGetLastError();
 }
 
-// Raise a kernel's dynamic-LDS limit (needed above 64 KB).  The attribute is sticky, so it is set
-// once per kernel and device; `slot` is a per-call-site cache of the largest size set so far.
-template <typename K>
-static hipError_t allow_lds(K kernel, size_t bytes, size_t* slot) {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  if (slot[dev] >= bytes) return hipSuccess;
-  const hipError_t e =
-      hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e == hipSuccess) slot[dev] = bytes;
-  return e;
-}
-
 template <int M>
 static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan, const uint8_t* codes,
                                       const int32_t* lut, const float* lut_scale, int top_k, int window,
                                       int n_sink, const int32_t* seq_lens, int32_t* topk_idx,
                                       int32_t* topk_count, float* topk_score, float* scores_out,
                                       void* ws, hipStream_t stream) {
-  const int Hq = d.n_q_heads, Hkv = d.n_kv_heads, NG = plan.NG;
-  const int heads = d.batch * Hq, problems = d.batch * Hkv * NG;
-  const size_t lut4_bytes = (size_t)kCentroids * M * sizeof(int4);
+  const int B = d.batch, Hq = d.n_q_heads, Hkv = d.n_kv_heads, NG = plan.NG;
+  const int heads = B * Hq, problems = B * Hkv * NG;
+  const size_t coarse_bytes = (size_t)kCentroids * M * 8;
   const size_t lut1_bytes = (size_t)kCentroids * M * sizeof(int32_t);
   hipError_t err;
   static size_t s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_final[16];
   if (heads == 0) return hipSuccess;
 
   if (scores_out) {
-    if ((err = allow_lds(score_dense_kernel<M>, lut4_bytes, s_dense)) != hipSuccess) return err;
+    if ((err = allow_dynamic_lds(score_dense_kernel<M>, lut1_bytes, s_dense)) != hipSuccess) return err;
     int gx = (d.ctx_len + kStreamThreads * 8 - 1) / (kStreamThreads * 8);
     gx = gx < 1 ? 1 : gx;
-    hipLaunchKernelGGL((score_dense_kernel<M>), dim3(gx, problems), dim3(kStreamThreads), lut4_bytes,
-                       stream, codes, lut, lut_scale, seq_lens, scores_out, Hq, Hkv, NG, d.ctx_len,
-                       d.ctx_stride);
+    hipLaunchKernelGGL((score_dense_kernel<M>), dim3(gx, heads), dim3(kStreamThreads), lut1_bytes, stream,
+                       codes, lut, lut_scale, seq_lens, scores_out, B, Hq, Hkv, d.ctx_len, d.ctx_stride);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
 
   if (!plan.fast) {
-    if ((err = allow_lds(select_exact_kernel<M>, lut1_bytes, s_exact)) != hipSuccess) return err;
+    if ((err = allow_dynamic_lds(select_exact_kernel<M>, lut1_bytes, s_exact)) != hipSuccess) return err;
     hipLaunchKernelGGL((select_exact_kernel<M>), dim3(heads), dim3(kExactThreads), lut1_bytes, stream,
-                       codes, lut, lut_scale, seq_lens, topk_idx, topk_count, topk_score, Hq, Hkv, NG,
+                       codes, lut, lut_scale, seq_lens, topk_idx, topk_count, topk_score, B, Hq, Hkv,
                        d.ctx_len, d.ctx_stride, top_k, window, n_sink);
     return hipGetLastError();
   }
@@ -860,34 +849,30 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   unsigned char* wsb = (unsigned char*)ws;
   int32_t* thr = (int32_t*)(wsb + plan.off_thr);
   uint32_t* seg_count = (uint32_t*)(wsb + plan.off_count);
-  uint2* cand = (uint2*)(wsb + plan.off_cand);
+  uint32_t* cand = (uint32_t*)(wsb + plan.off_cand);
 
-  if ((err = allow_lds(sample_threshold_kernel<M>, lut4_bytes, s_sample)) != hipSuccess) return err;
-  hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0, problems), dim3(kSampleThreads),
-                     lut4_bytes, stream, codes, lut, seq_lens, thr, Hq, Hkv, NG, plan.P0,
+  if ((err = allow_dynamic_lds(sample_threshold_kernel<M>, coarse_bytes, s_sample)) != hipSuccess) return err;
+  hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0 * problems), dim3(kSampleThreads),
+                     coarse_bytes, stream, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, plan.P0, problems,
                      d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
-  const size_t stream_lds =
-      lut4_bytes + (size_t)(kStreamThreads / 64) * kHeadsPerGroup * kStageCap * sizeof(uint2);
   auto stream_kernel = M == 16 ? stream_select_kernel16 : stream_select_kernel32;
-  if ((err = allow_lds(stream_kernel, stream_lds, s_stream)) != hipSuccess) return err;
+  if ((err = allow_dynamic_lds(stream_kernel, coarse_bytes, s_stream)) != hipSuccess) return err;
   if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_start, stream);
-  hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks, problems), dim3(kStreamThreads),
-                     stream_lds, stream, codes, lut, seq_lens, thr, seg_count, cand, Hq, Hkv, NG,
-                     plan.P0, plan.rows_per_chunk, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+  hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
+                     stream, codes, lut, seq_lens, thr, seg_count, cand, B, Hq, Hkv, NG, plan.P0,
+                     plan.chunks, problems, plan.rows_per_chunk, d.ctx_len, d.ctx_stride, top_k, window,
+                     n_sink);
   if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_stop, stream);
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
-  const int n_words = (d.ctx_len + 31) / 32;
-  size_t final_lds = (size_t)plan.cap * 8 + (size_t)n_words * 4 + (size_t)n_words * 2;
-  if (final_lds < lut1_bytes) final_lds = lut1_bytes;
-  final_lds = (final_lds + 15) / 16 * 16;
-  if ((err = allow_lds(final_select_kernel<M>, final_lds, s_final)) != hipSuccess) return err;
-  hipLaunchKernelGGL((final_select_kernel<M>), dim3(heads), dim3(kExactThreads), final_lds, stream,
-                     codes, lut, lut_scale, seq_lens, seg_count, cand, topk_idx, topk_count,
-                     topk_score, Hq, Hkv, NG, plan.chunks * kStreamWaves, plan.cap, d.ctx_len,
-                     d.ctx_stride, top_k, window, n_sink);
+  const size_t final_lds = lut1_bytes + (size_t)plan.cap * 8;
+  if ((err = allow_dynamic_lds(final_select_kernel<M>, final_lds, s_final)) != hipSuccess) return err;
+  hipLaunchKernelGGL((final_select_kernel<M>), dim3(problems * kHeadsPerGroup), dim3(kExactThreads),
+                     final_lds, stream, codes, lut, lut_scale, seq_lens, thr, seg_count, cand, topk_idx,
+                     topk_count, topk_score, B, Hq, Hkv, NG, plan.P0, problems, plan.chunks * kStreamWaves,
+                     plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   return hipGetLastError();
 }
 

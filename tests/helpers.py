@@ -54,16 +54,36 @@ def gpu_decode(wl: synth.Workload, xd: dict, seq_lens=None, n_sink=None, want_sc
 
 
 def lut_as_float(st, wl: synth.Workload) -> np.ndarray:
-    """Library table -> [B,Hq,M,L] float64 (dequantised), for comparison with the oracle's table."""
-    G = wl.group
+    """Exact part of the library table -> [B,Hq,M,L] float64 (dequantised), for comparison with the
+    oracle's table."""
+    n = wl.batch * wl.n_q_heads * wl.n_sub * 256
+    t = st.lut[:n].cpu().numpy().reshape(wl.batch, wl.n_q_heads, wl.n_sub, 256).astype(np.float64)
+    return t * st.lut_scale.cpu().numpy().astype(np.float64)[:, :, None, None]
+
+
+def coarse_table_consistent(st, wl: synth.Workload) -> bool:
+    """The 16-bit coarse copy of the table must obey exact = base + (coarse << s) + rem with
+    0 <= rem < 2^s per entry (summed over subspaces: rem < M * 2^s), for every head."""
+    Bn, Hq, Hkv, M, G = wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.n_sub, wl.group
     NG = (G + 3) // 4
-    t = st.lut.cpu().numpy().reshape(wl.batch, wl.n_kv_heads, NG, 256, wl.n_sub, 4).astype(np.float64)
-    sc = st.lut_scale.cpu().numpy().astype(np.float64)
-    out = np.empty((wl.batch, wl.n_q_heads, wl.n_sub, 256))
-    for h in range(wl.n_q_heads):
+    lut = st.lut.cpu().numpy()
+    n_exact = Bn * Hq * M * 256
+    n_coarse = Bn * Hkv * NG * 256 * M * 2
+    exact = lut[:n_exact].reshape(Bn, Hq, M, 256).astype(np.int64)
+    coarse = lut[n_exact:n_exact + n_coarse].view(np.uint16).reshape(Bn, Hkv, NG, M // 16, 256, 16, 4).astype(np.int64)
+    meta = lut[n_exact + n_coarse:n_exact + n_coarse + Bn * Hq * 4].reshape(Bn, Hq, 4).astype(np.int64)
+    for h in range(Hq):
         kv, hg = divmod(h, G)
-        out[:, h] = np.transpose(t[:, kv, hg // 4, :, :, hg % 4], (0, 2, 1)) * sc[:, h, None, None]
-    return out
+        c = coarse[:, kv, hg // 4, :, :, :, hg % 4]                      # [B, half, 256 c, 16 m]
+        c = np.transpose(c, (0, 1, 3, 2)).reshape(Bn, M, 256)            # [B, m, c]
+        mins = exact[:, h].min(axis=2)                                   # [B, M]
+        s = meta[:, h, 1]
+        if not np.array_equal(meta[:, h, 0], mins.sum(axis=1)):
+            return False
+        rem = exact[:, h] - mins[:, :, None] - (c << s[:, None, None])
+        if (rem < 0).any() or (rem >= (1 << s)[:, None, None]).any() or c.max() > 65535 // M:
+            return False
+    return True
 
 
 def check_scores(got: np.ndarray, want: np.ndarray, what="scores"):

@@ -35,11 +35,11 @@ def test_every_declared_symbol_is_exported(binding):
 
 def test_dims_validation_and_plans(binding):
     good = binding.make_dims(4, 32, 8, 128, 16, 131072)
-    assert binding.lut_elems(good) == 4 * 8 * 1 * 256 * 16 * 4
+    assert binding.lut_elems(good) == 4 * 32 * 16 * 256 + 4 * 8 * 1 * 256 * 16 * 2 + 4 * 32 * 4
     g7 = binding.make_dims(2, 28, 4, 128, 32, 65536)
-    assert binding.lut_elems(g7) == 2 * 4 * 2 * 256 * 32 * 4
+    assert binding.lut_elems(g7) == 2 * 28 * 32 * 256 + 2 * 4 * 2 * 256 * 32 * 2 + 2 * 28 * 4
     assert binding.workspace_bytes(good, binding.OP_LUT) == 0
-    assert binding.workspace_bytes(good, binding.OP_SCORE_TOPK, 2048, 256) > 128 * 8192 * 8
+    assert binding.workspace_bytes(good, binding.OP_SCORE_TOPK, 2048, 256) > 128 * 2048 * 24
     small = binding.make_dims(1, 4, 1, 128, 16, 4096)
     assert binding.workspace_bytes(small, binding.OP_SCORE_TOPK, 128, 64) == 0
     assert binding.workspace_bytes(good, binding.OP_ENCODE) == 8 * 16 * (64 + 256 * 8) * 4

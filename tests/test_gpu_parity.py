@@ -56,6 +56,7 @@ def test_config1_tiny(oracle):
     x = synth.make_decode_inputs(wl)
     lut = oracle.lut(oracle.rope(x["q"], x["inv_freq"], wl.wrope_b), x["codebook"], wl.n_q_heads)
     H.check_scores(H.lut_as_float(st, wl), lut, "table")
+    assert H.coarse_table_consistent(st, wl)
 
 
 @pytest.mark.parametrize("name,G,M,N,K,w,n_sink,seq_lens,stride", [
@@ -72,6 +73,7 @@ def test_fast_route_medium(oracle, name, G, M, N, K, w, n_sink, seq_lens, stride
     dims = H.dims_of(wl, stride)
     assert B.workspace_bytes(dims, B.OP_SCORE_TOPK, K, w) > 0, "expected the fast route"
     st, res = _run_and_check(oracle, wl, seq_lens=seq_lens, ctx_stride=stride)
+    assert H.coarse_table_consistent(st, wl)
     H.log(f"{name}: {res}")
 
 
