@@ -136,8 +136,9 @@ def main():
     ph = [[phase_ev[i][p].elapsed_time(phase_ev[i][p + 1]) * 1e3 for i in range(args.steps)] for p in range(4)]
     med = lambda v: float(sorted(v)[len(v) // 2])
     mean = lambda v: float(sum(v) / len(v))
-    cc = cand_counts.cpu().numpy().astype("int64")
-    fast_route = bool((cc >= 0).all())   # the exact-only route reports 0xFFFFFFFF (-1 as int32)
+    raw = cand_counts.cpu().numpy().astype("int64") & 0xFFFFFFFF
+    fast_route = bool((raw != 0xFFFFFFFF).all())   # the exact-only route reports 0xFFFFFFFF
+    cc, routes = raw & 0x0FFFFFFF, raw >> 28
     kern_us = [kev.elapsed_ms(i) * 1e3 for i in range(args.steps)] if fast_route else [float("nan")]
 
     rows = Bn * Hkv * N
@@ -173,7 +174,8 @@ def main():
         "sparse_attn_phase": {"algorithmic_bytes": attn_bytes,
                               "GBps": attn_bytes / (med(ph[3]) * 1e-6) / 1e9,
                               "frac_of_hbm_peak": attn_bytes / (med(ph[3]) * 1e-6) / 1e9 / HBM_PEAK_GBS},
-        "candidates_per_head": {"mean": float(cc.mean()), "max": int(cc.max()), "min": int(cc.min())}
+        "survivors_per_head": {"mean": float(cc.mean()), "max": int(cc.max()), "min": int(cc.min()),
+                               "heads_on_exact_fallback": int((routes != 0).sum())}
         if fast_route else None,
         "roofline": {"kernel": "stream_select_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,

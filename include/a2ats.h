@@ -175,10 +175,11 @@ int a2ats_sparse_attn(const a2ats_dims* dims, const void* q, const float* q_rot,
 
 /*
  * Diagnostics (not part of the method): after an a2ats_score_topk call with the same dims /
- * top_k / window / n_sink and the same `ws`, copy the per-head size of the candidate list the
- * streaming pass produced into cand_counts [dev, out, uint32 B*Hq] (asynchronously, on
- * `stream`).  A head took the in-kernel exact fallback iff its count is below its K' or above
- * 8192.  For shapes served by the exact route alone every entry is set to 0xFFFFFFFF.
+ * top_k / window / n_sink and the same `ws`, write per head into cand_counts [dev, out, uint32
+ * B*Hq] (asynchronously, on `stream`): bits 0-27 the number of rows the streaming pass kept
+ * for that head, bits 28-31 the route the final kernel took (0 = fast; 1 = too few survivors,
+ * 2 = too many, 3 = a segment overflowed, 4 = completeness proof failed: exact fallback).  For
+ * shapes served by the exact route alone every entry is 0xFFFFFFFF.
  */
 int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink,
                            const void* ws, uint32_t* cand_counts, void* stream);

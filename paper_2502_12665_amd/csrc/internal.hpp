@@ -17,8 +17,9 @@ struct TopkPlan {
   int P0;               // sampling workgroups per (sequence, KV head, head group)
   int chunks;           // streaming workgroups per (sequence, KV head, head group)
   int rows_per_chunk;
-  int cap;              // candidate-list capacity per head
-  size_t off_thr, off_count, off_cand, bytes;
+  int cap;              // survivor capacity per head in the final kernel's LDS
+  int row_cap;          // row entries a wave of the streaming pass owns in HBM
+  size_t off_thr, off_route, off_count, off_cand, bytes;
 };
 
 struct AttnPlan {

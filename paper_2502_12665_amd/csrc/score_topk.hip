@@ -35,7 +35,7 @@ constexpr int kExactThreads = 1024;
 constexpr int kStreamThreads = 512;
 constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kSampleThreads = 512;
-constexpr int kSubCap = 128;         // survivor slots a wave owns in HBM, per head
+constexpr int kSegMeta = 8;          // words of a segment header: rows, 4 per-head counts, padding
 constexpr int kSampleRows = 1024;    // rows scored by one sampling workgroup
 constexpr int kSmallList = 1024;     // members of the K-th key's bin ranked by brute force
 constexpr float kSigma = 5.0f;
@@ -64,13 +64,23 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     p.chunks = (int)((ncand + rpc - 1) / rpc);
     p.rows_per_chunk = (int)rpc;
     const size_t heads = (size_t)d.batch * d.n_q_heads;
-    // one survivor segment (count + kSubCap entries) per head, chunk and wave of the streaming pass
-    const size_t segs = heads * p.chunks * kStreamWaves;
-    const size_t entry_bytes = (2 + d.n_sub / 4) * sizeof(uint32_t);
+    // One survivor segment per (problem, chunk, wave) of the streaming pass: a header and row_cap
+    // row entries.  A row survives if any of the (up to) four heads wants it; with a threshold
+    // that lets about 2.2 K rows per head through that is at most 4 * 2.2 * K / ncand of the rows.
+    const long rows_per_wave = rpc / kStreamWaves;
+    long cap_rows = (long)(rows_per_wave * (4.0 * 2.5 * top_k / (double)ncand) * 1.5) + 32;
+    cap_rows = (cap_rows + 31) / 32 * 32;
+    if (cap_rows < 64) cap_rows = 64;
+    if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;
+    if (cap_rows > 32768) cap_rows = 32768;   // ranks inside a segment are stored in 16 bits
+    p.row_cap = (int)cap_rows;
+    const size_t segs = (size_t)problems * p.chunks * kStreamWaves;
+    const size_t entry_bytes = (4 + d.n_sub / 4) * sizeof(uint32_t);
     p.off_thr = 0;
-    p.off_count = p.off_thr + heads * p.P0 * sizeof(int32_t);
-    p.off_cand = (p.off_count + segs * sizeof(uint32_t) + 255) / 256 * 256;
-    p.bytes = p.off_cand + segs * (size_t)kSubCap * entry_bytes;
+    p.off_route = (p.off_thr + heads * p.P0 * sizeof(int32_t) + 255) / 256 * 256;
+    p.off_count = (p.off_route + heads * sizeof(uint32_t) + 255) / 256 * 256;
+    p.off_cand = (p.off_count + segs * kSegMeta * sizeof(uint32_t) + 255) / 256 * 256;
+    p.bytes = p.off_cand + segs * (size_t)p.row_cap * entry_bytes;
   }
   return p;
 }
@@ -100,19 +110,23 @@ __device__ __forceinline__ int32_t score_exact_row(const uint8_t* row, const int
   return score_exact<M>(w, lut1);
 }
 
-// Coarse scores of one token for the four heads of a group.  The coarse table sits in LDS as
-// [M/16 halves][256 c][16 m] 8-byte entries (two 32-bit words, each holding two heads' 16-bit
-// values), i.e. 128 bytes = all 32 banks per centroid row, entry m on banks 2m and 2m+1.
+// Coarse scores of one token for the four heads of a group.  The coarse table sits in LDS with
+// one 256-byte row per centroid id c: the 8-byte entry (two 32-bit words, each holding two heads'
+// 16-bit values) of subspace m is at byte (c << 8) | ((m >> 4) << 7) | ((m & 15) << 3).  (For
+// M = 16 the upper half of each row is unused.)
 //
 // LDS serves an 8-byte read 16 lanes at a time; lanes collide when they touch the same banks.
 // With this layout the banks of a read depend only on m, not on the (random) code byte, so lane
 // L visits the subspaces of its row in the order m = t ^ (L & 15), t = 0..15 (per 16-byte half
 // row): the 16 lanes served together always touch 16 different entries of their rows, and
 // random codes cause no conflicts.  The visiting order does not change the result because the
-// scores are integer sums.
+// scores are integer sums.  One v_perm_b32 assembles the whole LDS address of a read from the
+// code byte and a per-lane constant.
+constexpr int kCoarseLdsBytes = kCentroids * 256;
+
 template <int M>
 struct LaneSwizzle {
-  uint32_t mc[M / 4];   // byte t&3 of mc[t>>2]: (m & 15) << 4 for step t of this lane
+  uint32_t mc[M / 4];   // byte t&3 of mc[t>>2]: low address byte for step t of this lane
   uint32_t sel[4];      // v_perm selectors: address byte 1 <- code byte (k ^ b), byte 0 <- mc byte k
   bool swap1, swap2;    // dword index of the row is XORed with (rho >> 2)
   __device__ __forceinline__ void init(int lane) {
@@ -121,7 +135,11 @@ struct LaneSwizzle {
     for (int d = 0; d < M / 4; ++d) {
       uint32_t v = 0;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) v |= ((((uint32_t)(4 * d + k) ^ rho) & 15u) << 4) << (8 * k);
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t t = 4 * d + k;                       // step within the whole row
+        const uint32_t m_low = (t ^ rho) & 15u, half = t >> 4;
+        v |= ((half << 7) | (m_low << 3)) << (8 * k);
+      }
       mc[d] = v;
     }
 #pragma unroll
@@ -131,7 +149,12 @@ struct LaneSwizzle {
   }
 };
 
-template <int M>
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) const u32x2_t* lds_u2_ptr;
+
+// kBaseZero: the table starts at LDS address 0 (kernel without static LDS), so the v_perm result
+// is the address itself; otherwise it is an offset from `tbl`.
+template <int M, bool kBaseZero>
 __device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const unsigned char* tbl,
                                              const LaneSwizzle<M>& sw, uint32_t& a01, uint32_t& a23) {
   a01 = 0;
@@ -144,23 +167,43 @@ __device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const uns
     const uint32_t z[4] = {sw.swap2 ? x2 : x0, sw.swap2 ? x3 : x1, sw.swap2 ? x0 : x2, sw.swap2 ? x1 : x3};
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
-      // v_perm builds (code byte << 8) | (m << 4); halved it is the byte offset (c << 7) | (m << 3)
-      const uint32_t off = __builtin_amdgcn_perm(z[t >> 2], sw.mc[qd * 4 + (t >> 2)], sw.sel[t & 3]) >> 1;
-      const uint2 e = *(const uint2*)(tbl + qd * (kCentroids * 128) + off);
+      const uint32_t off = __builtin_amdgcn_perm(z[t >> 2], sw.mc[qd * 4 + (t >> 2)], sw.sel[t & 3]);
+      u32x2_t e;
+      if (kBaseZero) e = *(lds_u2_ptr)(uintptr_t)off;
+      else e = *(const u32x2_t*)(tbl + off);
       a01 += e.x;
       a23 += e.y;
     }
   }
 }
 
-// Copy a problem's coarse table (already in LDS order) to LDS.
+// The P0 sampling workgroups of a problem each estimate a head's threshold from their share of the
+// sample; the streaming and final kernels use the mean of the estimates (rounded down), which is
+// close to what one rank search over the merged sample would give.  INT32_MIN ("take every row")
+// from any of them wins.  Exactness never depends on this value: the final kernel proves its
+// result complete against whatever threshold was used, or redoes the head exactly.
+__device__ __forceinline__ int32_t combined_threshold(const int32_t* __restrict__ t, int P0) {
+  long sum = 0;
+  bool all_rows = false;
+  for (int p = 0; p < P0; ++p) {
+    const int32_t v = t[p];
+    all_rows |= v == INT32_MIN;
+    sum += v;
+  }
+  if (all_rows) return INT32_MIN;
+  return (int32_t)(sum / P0);   // thresholds are >= 0
+}
+
+// Copy a problem's coarse table from its global order [half][c][16 m] to the LDS layout above.
 template <int M, int NT>
 __device__ __forceinline__ void load_coarse_table(const int32_t* __restrict__ lut, const LutLayout& lay,
                                                   int prob, unsigned char* tbl) {
   const int4* src = (const int4*)(lut + lay.off_coarse + (size_t)prob * (kCentroids * M * 2));
-  int4* dst = (int4*)tbl;
 #pragma unroll 4
-  for (int e = threadIdx.x; e < kCentroids * M / 2; e += NT) dst[e] = src[e];
+  for (int e = threadIdx.x; e < kCentroids * M / 2; e += NT) {   // e: pair of entries (2 * e, 2 * e + 1)
+    const int half = e / (kCentroids * 8), c = (e / 8) % kCentroids, mp = e % 8;
+    *(int4*)(tbl + (c << 8) + (half << 7) + (mp << 4)) = src[e];
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -185,7 +228,7 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
   constexpr int NT = kExactThreads;
   const int tid = threadIdx.x;
   __syncthreads();   // lut1 may alias LDS the caller was still reading
-  for (int e = tid; e < kCentroids * M; e += NT) lut1[e] = head_table[e];
+  for (int e = tid; e < kCentroids * M / 4; e += NT) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
   if (tid < 32) {
     L.sub_min[tid] = INT32_MAX;
     L.sub_max[tid] = INT32_MIN;
@@ -311,7 +354,7 @@ __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
   const int G = Hq / Hkv, kv = h / G;
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
   const int32_t* head_table = lut + lay.off_exact + (size_t)bh * (kCentroids * M);
-  for (int e = threadIdx.x; e < kCentroids * M; e += kStreamThreads) lut1[e] = head_table[e];
+  for (int e = threadIdx.x; e < kCentroids * M / 4; e += kStreamThreads) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
   __syncthreads();
   int n = seq_lens ? seq_lens[b] : ctx_len;
   n = n < 0 ? 0 : (n > ctx_len ? ctx_len : n);
@@ -346,6 +389,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
   int r_p = 0;
   bool take_all = sr.ncand <= top_k || s_p == 0;
   if (!take_all) {
+    // rank r in the merged sample with r - sigma * sqrt(r) >= K * S / N, shared out over the P0 parts
     const float r0 = (float)top_k * (float)s_all / (float)sr.ncand;
     const float x = 0.5f * (kSigma + sqrtf(kSigma * kSigma + 4.f * r0));
     r_p = (int)ceilf(x * x / (float)P0) + 1;
@@ -376,7 +420,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
 #pragma unroll
     for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
     uint32_t a01, a23;
-    score_coarse<M>(w, tbl, sw, a01, a23);
+    score_coarse<M, false>(w, tbl, sw, a01, a23);
     atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);
     atomicAdd(&s_hist[0][a01 >> 21], 1u << 16);
     atomicAdd(&s_hist[1][(a23 & 0xffffu) >> 5], 1u);
@@ -429,11 +473,11 @@ template <int M>
 __device__ __forceinline__ void stream_select_body(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
-    uint32_t* __restrict__ seg_count, uint32_t* __restrict__ cand, int B, int Hq, int Hkv, int NG,
-    int P0, int n_chunks, int problems, int rows_per_chunk, int ctx_len, int64_t ctx_stride,
-    int top_k, int window, int n_sink) {
+    uint32_t* __restrict__ seg_meta, uint32_t* __restrict__ cand, int B, int Hq, int Hkv, int NG,
+    int P0, int n_chunks, int problems, int rows_per_chunk, int row_cap, int ctx_len,
+    int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
-  constexpr int EW = 2 + M / 4;   // words per survivor entry: position, coarse score, code bytes
+  constexpr int EW = 4 + M / 4;   // words per row entry: position, head mask, 4 ranks, code bytes
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   unsigned char* tbl = dyn_lds;
 
@@ -445,32 +489,31 @@ __device__ __forceinline__ void stream_select_body(
   const long begin = (long)sr.sink_end + (long)chunk * rows_per_chunk;
   const int end = (int)min((long)sr.win_start, begin + rows_per_chunk);
   // A wave owns a contiguous run of rows, so its survivors come out in ascending position and
-  // the segments of a head, taken in (chunk, wave) order, are sorted by position.
+  // the segments of a problem, taken in (chunk, wave) order, are sorted by position.
   const int rows_per_wave = rows_per_chunk / kStreamWaves;
   const long wbegin = begin + (long)wv * rows_per_wave;
   const int wend = (int)min((long)end, wbegin + rows_per_wave);
 
-  // Every (head, chunk, wave) owns one survivor segment in HBM: no atomics, no contention.
-  size_t seg[4];
-  bool live[4];
+  // Every (problem, chunk, wave) owns one survivor segment in HBM: no atomics, no contention.
+  const size_t seg = ((size_t)prob * n_chunks + chunk) * kStreamWaves + wv;
+  uint32_t* my_meta = seg_meta + seg * kSegMeta;
   int32_t T[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int hg = g4 * kHeadsPerGroup + r;
-    live[r] = hg < G;
-    const size_t head = (size_t)b * Hq + kv * G + (live[r] ? hg : 0);
-    seg[r] = (head * n_chunks + chunk) * kStreamWaves + wv;
-    int32_t t = INT32_MAX;   // padded heads never produce survivors
-    if (live[r]) {
-      t = thr[head * P0];
-      for (int pp = 1; pp < P0; ++pp) t = min(t, thr[head * P0 + pp]);
+    int32_t t = 65536;   // padded heads never want a row (a coarse score is below 2^16)
+    if (hg < G) {
+      const size_t head = (size_t)b * Hq + kv * G + hg;
+      t = combined_threshold(thr + head * P0, P0);
     }
     T[r] = t;
   }
-  if (begin >= sr.win_start) {   // nothing to score in this chunk: publish empty segments
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (live[r] && lane == 0) seg_count[seg[r]] = 0;
+  // The scoring loop addresses the table by absolute LDS address (it must start at 0, which holds
+  // because this kernel has no static LDS).  Should a toolchain ever place it elsewhere, publish
+  // an overflowing segment instead: the final kernel then takes the exact route.
+  const bool misplaced = (uint32_t)(uintptr_t)tbl != 0u;
+  if (begin >= sr.win_start || misplaced) {   // nothing to score in this chunk: empty segments
+    if (lane < kSegMeta) my_meta[lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
     return;
   }
 
@@ -480,7 +523,9 @@ __device__ __forceinline__ void stream_select_body(
 
   LaneSwizzle<M> sw;
   sw.init(lane);
-  int done[4] = {0, 0, 0, 0};   // survivors of this wave so far, per head (wave-uniform)
+  int n_rows = 0;                  // row entries written by this wave (wave-uniform)
+  int n_head[4] = {0, 0, 0, 0};    // of which wanted by each head
+  uint32_t* my_rows = cand + seg * (size_t)row_cap * EW;
 
   if (wbegin < wend) {
     const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
@@ -507,7 +552,7 @@ __device__ __forceinline__ void stream_select_body(
       uint64_t hit[U][4];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        score_coarse<M>(rows[u], tbl, sw, a01[u], a23[u]);
+        score_coarse<M, true>(rows[u], tbl, sw, a01[u], a23[u]);
         const bool valid = base + u * 64 + lane < wend;
         hit[u][0] = __ballot(valid && (int32_t)(a01[u] & 0xffffu) >= T[0]);
         hit[u][1] = __ballot(valid && (int32_t)(a01[u] >> 16) >= T[1]);
@@ -515,28 +560,31 @@ __device__ __forceinline__ void stream_select_body(
         hit[u][3] = __ballot(valid && (int32_t)(a23[u] >> 16) >= T[3]);
         __builtin_amdgcn_sched_barrier(0);   // one row's gathers at a time: bounds live registers
       }
+      // A surviving row is written once, with the mask of the heads that want it and, for each
+      // of them, its rank among the rows of this segment that the head wants (so the final kernel
+      // can place every entry without looking at the others).
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int j = base + u * 64 + lane;
+        const uint64_t any = hit[u][0] | hit[u][1] | hit[u][2] | hit[u][3];
+        if (any) {
+          if ((any >> lane) & 1) {
+            const int slot = n_rows + lanes_below(any);
+            if (slot < row_cap) {   // rows past the capacity are dropped but still counted
+              uint32_t hm = 0, rk[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const uint64_t mask = hit[u][r];
-          if (mask) {
-            if ((mask >> lane) & 1) {
-              const int slot = done[r] + lanes_below(mask);
-              if (slot < kSubCap) {   // entries past the capacity are dropped but still counted
-                const uint32_t a = r < 2 ? a01[u] : a23[u];
-                uint2* e = (uint2*)(cand + (seg[r] * kSubCap + slot) * EW);
-                e[0] = make_uint2((uint32_t)j, (r & 1) ? (a >> 16) : (a & 0xffffu));
-#pragma unroll
-                for (int qd = 0; qd < M / 16; ++qd) {
-                  e[1 + 2 * qd] = make_uint2(rows[u][qd].x, rows[u][qd].y);
-                  e[2 + 2 * qd] = make_uint2(rows[u][qd].z, rows[u][qd].w);
-                }
+              for (int r = 0; r < 4; ++r) {
+                hm |= (uint32_t)((hit[u][r] >> lane) & 1) << r;
+                rk[r] = (uint32_t)(n_head[r] + lanes_below(hit[u][r])) & 0xffffu;
               }
+              uint4* e = (uint4*)(my_rows + (size_t)slot * EW);
+              e[0] = make_uint4((uint32_t)(base + u * 64 + lane), hm, rk[0] | (rk[1] << 16), rk[2] | (rk[3] << 16));
+#pragma unroll
+              for (int qd = 0; qd < M / 16; ++qd) e[1 + qd] = rows[u][qd];
             }
-            done[r] += __popcll(mask);
           }
+          n_rows += __popcll(any);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) n_head[r] += __popcll(hit[u][r]);
         }
       }
     };
@@ -549,25 +597,30 @@ __device__ __forceinline__ void stream_select_body(
       process(base + STEP, rows_b);
     }
   }
+  if (lane < kSegMeta) {
+    uint32_t v = 0;
+    if (lane == 0) v = (uint32_t)n_rows;
 #pragma unroll
-  for (int r = 0; r < 4; ++r)
-    if (live[r] && lane == 0) seg_count[seg[r]] = (uint32_t)done[r];
+    for (int r = 0; r < 4; ++r)
+      if (lane == 1 + r) v = (uint32_t)n_head[r];
+    my_meta[lane] = v;
+  }
 }
 
 #define A2ATS_STREAM_ARGS                                                                          \
   const uint8_t *__restrict__ codes, const int32_t *__restrict__ lut,                             \
       const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ thr,                      \
-      uint32_t *__restrict__ seg_count, uint32_t *__restrict__ cand, int B, int Hq, int Hkv, int NG, \
-      int P0, int n_chunks, int problems, int rows_per_chunk, int ctx_len, int64_t ctx_stride,     \
-      int top_k, int window, int n_sink
+      uint32_t *__restrict__ seg_meta, uint32_t *__restrict__ cand, int B, int Hq, int Hkv, int NG,  \
+      int P0, int n_chunks, int problems, int rows_per_chunk, int row_cap, int ctx_len,            \
+      int64_t ctx_stride, int top_k, int window, int n_sink
 #define A2ATS_STREAM_PASS                                                                          \
-  codes, lut, seq_lens, thr, seg_count, cand, B, Hq, Hkv, NG, P0, n_chunks, problems,              \
-      rows_per_chunk, ctx_len, ctx_stride, top_k, window, n_sink
+  codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, P0, n_chunks, problems,               \
+      rows_per_chunk, row_cap, ctx_len, ctx_stride, top_k, window, n_sink
 
-// M = 16: 32 KB of LDS per workgroup; 128 VGPRs -> 4 waves per SIMD (two workgroups per CU).
+// 64 KB of LDS per workgroup.  M = 16: 128 VGPRs -> 4 waves per SIMD (two workgroups per CU).
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 void stream_select_kernel16(A2ATS_STREAM_ARGS) { stream_select_body<16>(A2ATS_STREAM_PASS); }
-// M = 32: 64 KB of LDS per workgroup, twice the row registers.
+// M = 32: twice the row registers.
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
 void stream_select_kernel32(A2ATS_STREAM_ARGS) { stream_select_body<32>(A2ATS_STREAM_PASS); }
 
@@ -578,13 +631,13 @@ template <int M>
 __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
-    const int32_t* __restrict__ thr, const uint32_t* __restrict__ seg_count,
-    const uint32_t* __restrict__ cand, int32_t* __restrict__ topk_idx,
+    const int32_t* __restrict__ thr, const uint32_t* __restrict__ seg_meta,
+    const uint32_t* __restrict__ cand, uint32_t* __restrict__ route, int32_t* __restrict__ topk_idx,
     int32_t* __restrict__ topk_count, float* __restrict__ topk_score, int B, int Hq, int Hkv, int NG,
-    int P0, int problems, int n_seg, int cap, int ctx_len, int64_t ctx_stride, int top_k,
+    int P0, int problems, int n_seg, int row_cap, int cap, int ctx_len, int64_t ctx_stride, int top_k,
     int window, int n_sink) {
   constexpr int NT = kExactThreads;
-  constexpr int EW = 2 + M / 4;
+  constexpr int EW = 4 + M / 4;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ ExactLds L;
   __shared__ uint32_t s_seg_off[513];
@@ -607,7 +660,10 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     oi[t] = -1;
     if (os) os[t] = 0.f;
   }
-  if (sr.kk == 0) return;
+  if (sr.kk == 0) {
+    if (tid == 0) route[bh] = 0u;
+    return;
+  }
   const float scale = lut_scale[bh];
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
   const int32_t* head_table = lut + lay.off_exact + (size_t)bh * (kCentroids * M);
@@ -618,7 +674,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   uint32_t* c_key = (uint32_t*)(lut1 + kCentroids * M);
   uint32_t* c_pos = c_key + cap;
 
-  for (int e = tid; e < kCentroids * M; e += NT) lut1[e] = head_table[e];
+  for (int e = tid; e < kCentroids * M / 4; e += NT) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
   for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
   if (tid == 0) {
     s_overflow = 0;
@@ -626,12 +682,17 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     s_kth = 0;
   }
   __syncthreads();
-  // Survivor segments of this head (one per chunk and wave of the streaming pass, sorted by
-  // position when taken in order): exclusive prefix of their sizes.  n_seg <= 512 <= NT.
+  // Survivor segments of this head's problem (one per chunk and wave of the streaming pass,
+  // sorted by position when taken in order): exclusive prefix of the number of rows this head
+  // wants in each.  n_seg <= 512 <= NT.
+  __shared__ uint16_t s_seg_rows[512];
   uint32_t my_cnt = 0;
   if (tid < n_seg) {
-    my_cnt = seg_count[(size_t)bh * n_seg + tid];
-    if (my_cnt > (uint32_t)kSubCap) s_overflow = 1;
+    const uint32_t* mt = seg_meta + ((size_t)prob * n_seg + tid) * kSegMeta;
+    const uint32_t rows = mt[0];
+    my_cnt = mt[1 + r];
+    if (rows > (uint32_t)row_cap) s_overflow = 1;
+    s_seg_rows[tid] = (uint16_t)min(rows, 65535u);
   }
   uint32_t n_c;
   const uint32_t my_off = block_exclusive_scan<NT>(my_cnt, L.wave_a, n_c);
@@ -639,6 +700,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   if (tid == 0) s_seg_off[n_seg] = n_c;
   __syncthreads();
   if (s_overflow || n_c > (uint32_t)cap || n_c < (uint32_t)sr.kk) {
+    if (tid == 0) route[bh] = s_overflow ? 3u : (n_c > (uint32_t)cap ? 2u : 1u);   // diagnostics only
     exact_select_block<M>(seq_codes, head_table, scale, sr, oi, os, lut1, L);
     return;
   }
@@ -647,22 +709,50 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   // are then taken relative to the smallest one, so that radix digits spread over the occupied
   // range instead of all survivors sharing the leading bits of their absolute keys.
   uint32_t kmin = 0xffffffffu, kmax = 0;
-  for (int s_ = wv; s_ < n_seg; s_ += NT / 64) {
-    const uint32_t base = s_seg_off[s_], n = s_seg_off[s_ + 1] - base;
-    const uint32_t* src = cand + ((size_t)bh * n_seg + s_) * kSubCap * EW;
-    for (uint32_t i = lane; i < n; i += 64) {
-      const uint2* e = (const uint2*)(src + (size_t)i * EW);
-      uint32_t w[M / 4];
-      const uint32_t pos = e[0].x;
+  {
+    // Pass 1: pick this head's rows out of the problem's row entries.  tps threads share a
+    // segment; every entry carries its own destination (segment offset + rank), so all loads
+    // are independent and no thread waits for another.  c_key temporarily holds the entry index.
+    const int tps = NT / n_seg > 0 ? NT / n_seg : 1;
+    const uint32_t* rows0 = cand + (size_t)prob * n_seg * (size_t)row_cap * EW;
+    for (int s_ = tid / tps; s_ < n_seg; s_ += NT / tps) {
+      const uint32_t n_rows = s_seg_rows[s_], dst0 = s_seg_off[s_];
+      // Four entry headers are fetched whole and together before any of them is looked at (the
+      // empty asm keeps the compiler from splitting a header load and sinking parts of it behind
+      // the "does this head want the row" branch, which would serialise two latencies per entry).
+      for (uint32_t i0 = tid % tps; i0 < n_rows; i0 += 4 * tps) {
+        u32x4_t hd[4];
 #pragma unroll
-      for (int q2 = 0; q2 < M / 8; ++q2) {
-        const uint2 v = e[1 + q2];
-        w[2 * q2] = v.x;
-        w[2 * q2 + 1] = v.y;
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t i = min(i0 + k * tps, n_rows - 1);
+          hd[k] = *(const u32x4_t*)(rows0 + ((size_t)s_ * row_cap + i) * EW);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(hd[k]));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const uint32_t i = i0 + k * tps;
+          if (i < n_rows && ((hd[k].y >> r) & 1u)) {
+            const uint32_t rk = ((r < 2 ? hd[k].z : hd[k].w) >> (16 * (r & 1))) & 0xffffu;
+            c_pos[dst0 + rk] = hd[k].x;
+            c_key[dst0 + rk] = (uint32_t)s_ * (uint32_t)row_cap + i;
+          }
+        }
+      }
+    }
+    __syncthreads();
+    // Pass 2: exact keys of this head's survivors, densely (no divergence).
+#pragma unroll 2
+    for (uint32_t i = tid; i < n_c; i += NT) {
+      const uint4* e = (const uint4*)(rows0 + (size_t)c_key[i] * EW);
+      uint32_t w[M / 4];
+#pragma unroll
+      for (int qd = 0; qd < M / 16; ++qd) {
+        const uint4 v = e[1 + qd];
+        w[4 * qd] = v.x; w[4 * qd + 1] = v.y; w[4 * qd + 2] = v.z; w[4 * qd + 3] = v.w;
       }
       const uint32_t key = score_key(score_exact<M>(w, lut1));
-      c_pos[base + i] = pos;
-      c_key[base + i] = key;
+      c_key[i] = key;
       kmin = min(kmin, key);
       kmax = max(kmax, key);
     }
@@ -747,15 +837,16 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   // below base + ((Tc - 1 + M) << shift).  If the K-th survivor key reaches that bound, no such
   // row can displace (or tie with) a winner.  Otherwise redo this head by the exact route.
   {
-    int32_t tc = thr[(size_t)bh * P0];
-    for (int pp = 1; pp < P0; ++pp) tc = min(tc, thr[(size_t)bh * P0 + pp]);
+    const int32_t tc = combined_threshold(thr + (size_t)bh * P0, P0);
     const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
     const long bound = (long)meta[0] + (((long)tc - 1 + M) << meta[1]);
     const long kth_score = (long)key_score(kth + kmin);
     if (tc != INT32_MIN && kth_score < bound) {
+      if (tid == 0) route[bh] = 4u;
       exact_select_block<M>(seq_codes, head_table, scale, sr, oi, os, lut1, L);
       return;
     }
+    if (tid == 0) route[bh] = 0u;
   }
 
   // Winners: keys above the K-th, plus the first (K - #above) survivors equal to it.  Survivors
@@ -794,13 +885,15 @@ void set_profile_events(void* a, void* b) {
   g_ev_stop = (hipEvent_t)b;
 }
 
-__global__ void sum_segments_kernel(const uint32_t* __restrict__ seg_count, uint32_t* __restrict__ out,
-                                    int heads, int n_seg) {
-  const int h = blockIdx.x * blockDim.x + threadIdx.x;
-  if (h >= heads) return;
+__global__ void sum_segments_kernel(const uint32_t* __restrict__ seg_meta, const uint32_t* __restrict__ route,
+                                    uint32_t* __restrict__ out, int B, int Hq, int Hkv, int NG, int n_seg) {
+  const int bh = blockIdx.x * blockDim.x + threadIdx.x;
+  if (bh >= B * Hq) return;
+  const int G = Hq / Hkv, b = bh / Hq, h = bh % Hq, kv = h / G, hg = h % G;
+  const size_t prob = ((size_t)b * Hkv + kv) * NG + hg / kHeadsPerGroup;
   uint32_t tot = 0;
-  for (int s = 0; s < n_seg; ++s) tot += seg_count[(size_t)h * n_seg + s];
-  out[h] = tot;
+  for (int s = 0; s < n_seg; ++s) tot += seg_meta[(prob * n_seg + s) * kSegMeta + 1 + (hg % kHeadsPerGroup)];
+  out[bh] = min(tot, 0x0fffffffu) | (route[bh] << 28);
 }
 
 hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sink, const void* ws,
@@ -810,8 +903,9 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
   if (heads == 0) return hipSuccess;
   if (!plan.fast) return hipMemsetAsync(cand_counts, 0xff, (size_t)heads * sizeof(uint32_t), stream);
   hipLaunchKernelGGL(sum_segments_kernel, dim3((heads + 255) / 256), dim3(256), 0, stream,
-                     (const uint32_t*)((const unsigned char*)ws + plan.off_count), cand_counts, heads,
-                     plan.chunks * kStreamWaves);
+                     (const uint32_t*)((const unsigned char*)ws + plan.off_count),
+                     (const uint32_t*)((const unsigned char*)ws + plan.off_route), cand_counts, d.batch,
+                     d.n_q_heads, d.n_kv_heads, plan.NG, plan.chunks * kStreamWaves);
   return hipGetLastError();
 }
 
@@ -823,7 +917,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
                                       void* ws, hipStream_t stream) {
   const int B = d.batch, Hq = d.n_q_heads, Hkv = d.n_kv_heads, NG = plan.NG;
   const int heads = B * Hq, problems = B * Hkv * NG;
-  const size_t coarse_bytes = (size_t)kCentroids * M * 8;
+  const size_t coarse_bytes = (size_t)kCoarseLdsBytes;
   const size_t lut1_bytes = (size_t)kCentroids * M * sizeof(int32_t);
   hipError_t err;
   static size_t s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_final[16];
@@ -848,7 +942,8 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
 
   unsigned char* wsb = (unsigned char*)ws;
   int32_t* thr = (int32_t*)(wsb + plan.off_thr);
-  uint32_t* seg_count = (uint32_t*)(wsb + plan.off_count);
+  uint32_t* seg_meta = (uint32_t*)(wsb + plan.off_count);
+  uint32_t* route = (uint32_t*)(wsb + plan.off_route);
   uint32_t* cand = (uint32_t*)(wsb + plan.off_cand);
 
   if ((err = allow_dynamic_lds(sample_threshold_kernel<M>, coarse_bytes, s_sample)) != hipSuccess) return err;
@@ -861,18 +956,18 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   if ((err = allow_dynamic_lds(stream_kernel, coarse_bytes, s_stream)) != hipSuccess) return err;
   if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_start, stream);
   hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
-                     stream, codes, lut, seq_lens, thr, seg_count, cand, B, Hq, Hkv, NG, plan.P0,
-                     plan.chunks, problems, plan.rows_per_chunk, d.ctx_len, d.ctx_stride, top_k, window,
-                     n_sink);
+                     stream, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, plan.P0,
+                     plan.chunks, problems, plan.rows_per_chunk, plan.row_cap, d.ctx_len, d.ctx_stride,
+                     top_k, window, n_sink);
   if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_stop, stream);
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
   const size_t final_lds = lut1_bytes + (size_t)plan.cap * 8;
   if ((err = allow_dynamic_lds(final_select_kernel<M>, final_lds, s_final)) != hipSuccess) return err;
   hipLaunchKernelGGL((final_select_kernel<M>), dim3(problems * kHeadsPerGroup), dim3(kExactThreads),
-                     final_lds, stream, codes, lut, lut_scale, seq_lens, thr, seg_count, cand, topk_idx,
+                     final_lds, stream, codes, lut, lut_scale, seq_lens, thr, seg_meta, cand, route, topk_idx,
                      topk_count, topk_score, B, Hq, Hkv, NG, plan.P0, problems, plan.chunks * kStreamWaves,
-                     plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                     plan.row_cap, plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   return hipGetLastError();
 }
 

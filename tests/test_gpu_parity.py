@@ -305,3 +305,35 @@ def test_config5_encode_then_decode(oracle):
         sub, x = H.slice_problem(wl, xd, b, kv)
         res = H.check_step_against_oracle(oracle, wl, st, x, b_sel=b, kv_sel=kv)
         H.log(f"  decode on encoded keys (b={b}, kv={kv}): {res}")
+
+
+def _routes(wl, xd, n_sink=0):
+    """Run tables + score/top-K alone and return (survivors per head, route per head)."""
+    dims = H.dims_of(wl, xd["codes"].shape[2])
+    st = B.DecodeState(dims, wl.top_k, wl.window, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+    B.build_lut(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, st.lut, st.lut_scale)
+    B.score_topk(dims, xd["codes"], st.lut, st.lut_scale, wl.top_k, wl.window, n_sink, None, st.topk_idx,
+                 st.topk_count, None, None, st.ws)
+    out = torch.empty(wl.batch, wl.n_q_heads, dtype=torch.int32, device="cuda")
+    B.score_topk_stats(dims, wl.top_k, wl.window, n_sink, st.ws, out)
+    torch.cuda.synchronize()
+    raw = out.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+    return raw & 0x0FFFFFFF, raw >> 28
+
+
+def test_fast_route_is_taken_and_fallback_triggers():
+    """Ordinary inputs must be served by the streaming route for every head (no silent exact
+    fallback), with a survivor list of modest size; degenerate inputs must fall back."""
+    for name in ("c2_llama8b_32k", "c4_long_128k"):
+        wl = synth.WORKLOADS[name]
+        xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+        surv, route = _routes(wl, xd)
+        H.log(f"{name}: survivors per head mean {surv.mean():.0f} min {surv.min()} max {surv.max()}; "
+              f"fallback heads {(route != 0).sum()}")
+        assert (route == 0).all()
+        assert surv.min() >= wl.top_k and surv.max() <= 4 * wl.top_k
+    wl = synth.Workload("ties_all_equal", 1, 4, 1, 128, 16, 20000, 300, 64, seed=5)
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    xd["codes"][:] = xd["codes"][:, :, :1]
+    surv, route = _routes(wl, xd)
+    assert (route != 0).all(), route
