@@ -547,18 +547,19 @@ __device__ __forceinline__ void stream_select_body(
     };
     auto process = [&](int base, const uint4 (&rows)[U][M / 16]) {
       // Scores and the per-head "reaches the threshold" wave masks are formed together, so the
-      // gathered table entries die inside this straight-line block.
-      uint32_t a01[U], a23[U];
+      // gathered table entries die inside this straight-line block.  The masks live in scalar
+      // registers; their popcounts cost no vector instructions.
       uint64_t hit[U][4];
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        score_coarse<M, true>(rows[u], tbl, sw, a01[u], a23[u]);
-        const bool valid = base + u * 64 + lane < wend;
-        hit[u][0] = __ballot(valid && (int32_t)(a01[u] & 0xffffu) >= T[0]);
-        hit[u][1] = __ballot(valid && (int32_t)(a01[u] >> 16) >= T[1]);
-        hit[u][2] = __ballot(valid && (int32_t)(a23[u] & 0xffffu) >= T[2]);
-        hit[u][3] = __ballot(valid && (int32_t)(a23[u] >> 16) >= T[3]);
-        __builtin_amdgcn_sched_barrier(0);   // one row's gathers at a time: bounds live registers
+        uint32_t a01, a23;
+        score_coarse<M, true>(rows[u], tbl, sw, a01, a23);
+        const uint64_t valid = __builtin_amdgcn_ballot_w64(base + u * 64 + lane < wend);
+        hit[u][0] = __builtin_amdgcn_ballot_w64((int32_t)(a01 & 0xffffu) >= T[0]) & valid;
+        hit[u][1] = __builtin_amdgcn_ballot_w64((int32_t)(a01 >> 16) >= T[1]) & valid;
+        hit[u][2] = __builtin_amdgcn_ballot_w64((int32_t)(a23 & 0xffffu) >= T[2]) & valid;
+        hit[u][3] = __builtin_amdgcn_ballot_w64((int32_t)(a23 >> 16) >= T[3]) & valid;
+        if (u & 1) __builtin_amdgcn_sched_barrier(0);   // two rows' gathers at a time: bounds live registers
       }
       // A surviving row is written once, with the mask of the heads that want it and, for each
       // of them, its rank among the rows of this segment that the head wants (so the final kernel
@@ -567,16 +568,18 @@ __device__ __forceinline__ void stream_select_body(
       for (int u = 0; u < U; ++u) {
         const uint64_t any = hit[u][0] | hit[u][1] | hit[u][2] | hit[u][3];
         if (any) {
-          if ((any >> lane) & 1) {
-            const int slot = n_rows + lanes_below(any);
+          if (__builtin_amdgcn_inverse_ballot_w64(any)) {
+            const int slot = (int)__builtin_amdgcn_mbcnt_hi(
+                (uint32_t)(any >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)any, (uint32_t)n_rows));
             if (slot < row_cap) {   // rows past the capacity are dropped but still counted
               uint32_t hm = 0, rk[4];
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
-                hm |= (uint32_t)((hit[u][r] >> lane) & 1) << r;
-                rk[r] = (uint32_t)(n_head[r] + lanes_below(hit[u][r])) & 0xffffu;
+                hm |= __builtin_amdgcn_inverse_ballot_w64(hit[u][r]) ? (1u << r) : 0u;
+                rk[r] = __builtin_amdgcn_mbcnt_hi(
+                    (uint32_t)(hit[u][r] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit[u][r], (uint32_t)n_head[r]));
               }
-              uint4* e = (uint4*)(my_rows + (size_t)slot * EW);
+              uint4* e = (uint4*)(my_rows + (uint32_t)slot * (uint32_t)EW);
               e[0] = make_uint4((uint32_t)(base + u * 64 + lane), hm, rk[0] | (rk[1] << 16), rk[2] | (rk[3] << 16));
 #pragma unroll
               for (int qd = 0; qd < M / 16; ++qd) e[1 + qd] = rows[u][qd];

@@ -160,7 +160,7 @@ def test_encode_keys(oracle, M, mode):
     weights = {"none": None, "diag": hm["h_diag"], "block": hm["h_block"]}[mode]
     dims = H.dims_of(wl, 2100)
     ws = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
-    for n_new, pos0, stress in ((1000, 37, False), (777, 0, True), (1, 2099, False)):
+    for n_new, pos0, stress in ((1000, 37, False), (777, 0, True), (1, 2099, False), (17, 5, True)):
         H.log(f"{wl.name} n_new={n_new} stress={stress}")
         keys = synth.make_encode_keys(wl, n_new, stress=stress)
         codes = torch.full((wl.batch, wl.n_kv_heads, 2100, M), 0xEE, dtype=torch.uint8, device="cuda")
@@ -337,3 +337,32 @@ def test_fast_route_is_taken_and_fallback_triggers():
     xd["codes"][:] = xd["codes"][:, :, :1]
     surv, route = _routes(wl, xd)
     assert (route != 0).all(), route
+
+
+def test_decode_step_in_a_hip_graph():
+    """A captured decode step must replay to the eager result every time, with eager work and
+    synchronisations between the replays."""
+    wl = synth.Workload("graph", 2, 8, 2, 128, 16, 30000, 900, 128, seed=8)
+    xd = H.to_dev(synth.make_decode_inputs(wl))
+    st = H.gpu_decode(wl, xd, want_scores=False)           # eager reference (also warms the library)
+    ref = (st.topk_idx.clone(), st.out.clone())
+    new_key = xd["k"][:, :, -1:, :].float().contiguous()
+
+    def step():
+        B.encode_keys(st.dims, new_key, 1, wl.ctx_len - 1, xd["codebook"], None, B.W_NONE, xd["codes"], st.ws)
+        st.step(xd["q"], xd["codes"], xd["k"], xd["v"], xd["codebook"])
+    step()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for it in range(4):
+        st.topk_idx.fill_(-3)
+        st.out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(st.topk_idx, ref[0]), f"replay {it}: top-K differs"
+        assert torch.equal(st.out.view(torch.int16), ref[1].view(torch.int16)), f"replay {it}: output differs"
+        junk = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
+        assert junk == junk
