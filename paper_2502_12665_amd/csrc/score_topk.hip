@@ -413,9 +413,19 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
   LaneSwizzle<M> sw;
   sw.init(lane);
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  // The sample is taken in runs of kRun consecutive rows (one 128-byte line of the code matrix),
+  // the runs evenly spread over the candidates: HBM delivers whole lines, so a row-strided sample
+  // would fetch eight times the bytes it uses.  (For rows drawn independently, as in the synthetic
+  // workloads, this changes nothing statistically; if neighbouring tokens' scores are correlated
+  // the estimate is noisier, which costs at most a detour over the exact route.)
+  constexpr int kRun = 128 / M;
+  const long n_runs = (s_all + kRun - 1) / kRun;
   for (int i = tid; i < s_p; i += NT) {
     const long g = (long)p * s_p + i;
-    const int j = sr.sink_end + (int)((g * sr.ncand) / s_all);
+    const long run = g / kRun;
+    int j = sr.sink_end + (int)((run * sr.ncand) / n_runs);
+    j = max(sr.sink_end, j & ~(kRun - 1)) + (int)(g % kRun);
+    j = min(j, sr.win_start - 1);
     uint4 w[M / 16];
 #pragma unroll
     for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
@@ -677,6 +687,18 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   uint32_t* c_key = (uint32_t*)(lut1 + kCentroids * M);
   uint32_t* c_pos = c_key + cap;
 
+  // Everything this workgroup needs from global memory before it can look at a survivor is
+  // requested here in one go, so the latencies overlap: the segment headers, the threshold and
+  // table constants of the completeness check (used at the very end), and the head's table.
+  uint32_t seg_rows = 0, my_cnt = 0;
+  if (tid < n_seg) {
+    const uint32_t* mt = seg_meta + ((size_t)prob * n_seg + tid) * kSegMeta;
+    seg_rows = mt[0];
+    my_cnt = mt[1 + r];
+  }
+  const int32_t tc = combined_threshold(thr + (size_t)bh * P0, P0);
+  const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
+  const long proof_bound = (long)meta[0] + (((long)tc - 1 + M) << meta[1]);
   for (int e = tid; e < kCentroids * M / 4; e += NT) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
   for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
   if (tid == 0) {
@@ -689,13 +711,9 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   // sorted by position when taken in order): exclusive prefix of the number of rows this head
   // wants in each.  n_seg <= 512 <= NT.
   __shared__ uint16_t s_seg_rows[512];
-  uint32_t my_cnt = 0;
   if (tid < n_seg) {
-    const uint32_t* mt = seg_meta + ((size_t)prob * n_seg + tid) * kSegMeta;
-    const uint32_t rows = mt[0];
-    my_cnt = mt[1 + r];
-    if (rows > (uint32_t)row_cap) s_overflow = 1;
-    s_seg_rows[tid] = (uint16_t)min(rows, 65535u);
+    if (seg_rows > (uint32_t)row_cap) s_overflow = 1;
+    s_seg_rows[tid] = (uint16_t)min(seg_rows, 65535u);
   }
   uint32_t n_c;
   const uint32_t my_off = block_exclusive_scan<NT>(my_cnt, L.wave_a, n_c);
@@ -737,17 +755,21 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
           const uint32_t i = i0 + k * tps;
           if (i < n_rows && ((hd[k].y >> r) & 1u)) {
             const uint32_t rk = ((r < 2 ? hd[k].z : hd[k].w) >> (16 * (r & 1))) & 0xffffu;
-            c_pos[dst0 + rk] = hd[k].x;
-            c_key[dst0 + rk] = (uint32_t)s_ * (uint32_t)row_cap + i;
+            if (dst0 + rk < n_c) {   // always true for entries the streaming pass wrote; keeps LDS writes in range whatever the workspace holds
+              c_pos[dst0 + rk] = hd[k].x;
+              c_key[dst0 + rk] = (uint32_t)s_ * (uint32_t)row_cap + i;
+            }
           }
         }
       }
     }
     __syncthreads();
     // Pass 2: exact keys of this head's survivors, densely (no divergence).
+    const uint32_t last_entry = (uint32_t)n_seg * (uint32_t)row_cap - 1u;
 #pragma unroll 2
     for (uint32_t i = tid; i < n_c; i += NT) {
-      const uint4* e = (const uint4*)(rows0 + (size_t)c_key[i] * EW);
+      // the clamp is a no-op for a consistent workspace; it keeps the read inside this problem's entries
+      const uint4* e = (const uint4*)(rows0 + (size_t)min(c_key[i], last_entry) * EW);
       uint32_t w[M / 4];
 #pragma unroll
       for (int qd = 0; qd < M / 16; ++qd) {
@@ -840,11 +862,8 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   // below base + ((Tc - 1 + M) << shift).  If the K-th survivor key reaches that bound, no such
   // row can displace (or tie with) a winner.  Otherwise redo this head by the exact route.
   {
-    const int32_t tc = combined_threshold(thr + (size_t)bh * P0, P0);
-    const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
-    const long bound = (long)meta[0] + (((long)tc - 1 + M) << meta[1]);
     const long kth_score = (long)key_score(kth + kmin);
-    if (tc != INT32_MIN && kth_score < bound) {
+    if (tc != INT32_MIN && kth_score < proof_bound) {
       if (tid == 0) route[bh] = 4u;
       exact_select_block<M>(seq_codes, head_table, scale, sr, oi, os, lut1, L);
       return;
