@@ -23,7 +23,8 @@ struct TopkPlan {
 };
 
 struct AttnPlan {
-  int n_split;          // workgroups sharing the rows of one head
+  int n_far;            // workgroups sharing the sinks and retrieved rows of one head
+  int n_win;            // workgroups sharing its window rows
   size_t bytes;
 };
 

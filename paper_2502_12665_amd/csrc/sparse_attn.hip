@@ -6,9 +6,9 @@
 // head has its own retrieved set, so the "matrix" on the query side has one row; the
 // products are therefore done on the vector ALU and all effort goes into keeping many row
 // loads in flight: a row is read by 16 (bf16) or 32 (float32) lanes with one 16-byte load
-// each, a wave works on 4 (2) rows at a time, and the rows of one head are split over
-// several workgroups whose partial (max, sum, accumulator) triples a second small kernel
-// merges.
+// each, a wave works on 4 (2) rows at a time with a second set of rows already requested, and
+// the rows of one head are split over several workgroups whose partial (max, sum, accumulator)
+// triples a second small kernel merges.
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -19,32 +19,41 @@ constexpr int kAttnTile = 512;   // positions staged in LDS at a time
 constexpr int kD = 128;
 
 AttnPlan make_attn_plan(const a2ats_dims& d, int top_k, int window, int n_sink) {
+  // Workgroups of a head: n_far share the sinks and the retrieved rows, n_win the window rows
+  // (which need the per-row rotation and are kept apart so that the common path has no branch).
   AttnPlan p;
   const long heads = (long)d.batch * d.n_q_heads;
-  long rows = (long)n_sink + top_k + window;
-  if (rows > d.ctx_len) rows = d.ctx_len;
-  long ns = heads > 0 ? (1024 + heads - 1) / heads : 1;
-  const long by_rows = rows / 64 > 1 ? rows / 64 : 1;
-  if (ns > by_rows) ns = by_rows;
-  if (ns > 32) ns = 32;
-  if (ns < 1) ns = 1;
-  p.n_split = (int)ns;
-  p.bytes = ns > 1 ? (size_t)heads * ns * (kD + 2) * sizeof(float) : 0;
+  long far_rows = (long)n_sink + top_k;
+  if (far_rows > d.ctx_len) far_rows = d.ctx_len;
+  long nf = heads > 0 ? (1024 + heads - 1) / heads : 1;
+  const long by_rows = far_rows / 64 > 1 ? far_rows / 64 : 1;
+  if (nf > by_rows) nf = by_rows;
+  if (nf > 32) nf = 32;
+  if (nf < 1) nf = 1;
+  long nw = ((long)window + 127) / 128;
+  if (nw > 8) nw = 8;
+  if (nw < 1) nw = 1;
+  p.n_far = (int)nf;
+  p.n_win = (int)nw;
+  p.bytes = (size_t)heads * (nf + nw) * (kD + 2) * sizeof(float);
   return p;
 }
 
+// A lane's 16-byte piece of a row, kept as loaded (so that rows in flight cost four registers
+// each) and widened to float only when it is used.
 template <typename T> struct RowVec;
 template <> struct RowVec<float> {
   static constexpr int LPR = 32, VEC = 4;
-  static __device__ __forceinline__ void load(const float* p, float (&o)[4]) {
-    const float4 v = *(const float4*)p;
-    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  static __device__ __forceinline__ uint4 load(const float* p) { return *(const uint4*)p; }
+  static __device__ __forceinline__ void widen(const uint4& v, float (&o)[4]) {
+    o[0] = __uint_as_float(v.x); o[1] = __uint_as_float(v.y);
+    o[2] = __uint_as_float(v.z); o[3] = __uint_as_float(v.w);
   }
 };
 template <> struct RowVec<uint16_t> {
   static constexpr int LPR = 16, VEC = 8;
-  static __device__ __forceinline__ void load(const uint16_t* p, float (&o)[8]) {
-    const uint4 v = *(const uint4*)p;
+  static __device__ __forceinline__ uint4 load(const uint16_t* p) { return *(const uint4*)p; }
+  static __device__ __forceinline__ void widen(const uint4& v, float (&o)[8]) {
     const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -77,9 +86,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     const T* __restrict__ q, const float* __restrict__ q_rot, const T* __restrict__ k_cache,
     const T* __restrict__ v_cache, const int32_t* __restrict__ topk_idx,
     const int32_t* __restrict__ topk_count, const float* __restrict__ cos_win,
-    const float* __restrict__ sin_win, const int32_t* __restrict__ seq_lens, T* __restrict__ out,
+    const float* __restrict__ sin_win, const int32_t* __restrict__ seq_lens,
     float* __restrict__ partial, int Hq, int Hkv, int ctx_len, int64_t ctx_stride, int top_k,
-    int window, int n_sink, int n_split) {
+    int window, int n_sink, int n_far, int n_win) {
   constexpr int LPR = RowVec<T>::LPR, VEC = RowVec<T>::VEC;
   constexpr int SLOTS = 64 / LPR;            // rows a wave reads at once
   constexpr int NWV = kAttnThreads / 64;
@@ -88,88 +97,132 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   __shared__ int32_t s_pos[kAttnTile];
   __shared__ float s_m[NWV], s_l[NWV], s_acc[NWV][kD];
 
-  const int split = blockIdx.x, bh = blockIdx.y, b = bh / Hq, h = bh % Hq;
+  const int part = blockIdx.x, bh = blockIdx.y, b = bh / Hq, h = bh % Hq;
   const int G = Hq / Hkv, kv = h / G;
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, slot = lane / LPR, sub = lane % LPR;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   const int cnt = max(0, min(min(topk_count[bh], top_k), sr.ncand));
-  const int n_att = sr.sink_end + cnt + (sr.n - sr.win_start);
-  const int per = (n_att + n_split - 1) / n_split;
-  const int t0 = split * per, t1 = min(n_att, t0 + per);
+  // Far rows (sinks, then the retrieved rows) are dealt out round-robin to the first n_far
+  // workgroups of the head, window rows to the other n_win.
+  const bool win_part = part >= n_far;
+  const int n_rows = win_part ? sr.n - sr.win_start : sr.sink_end + cnt;
+  const int stride = win_part ? n_win : n_far, first = win_part ? part - n_far : part;
+  const int n_mine = n_rows > first ? (n_rows - first + stride - 1) / stride : 0;
 
-  // this lane's slice of the query: own dims d0..d0+VEC-1 and the dims paired with them
   const int d0 = sub * VEC;
-  const bool low_half = d0 < HALF;
-  const int dp = low_half ? d0 + HALF : d0 - HALF;
-  const float sgn = low_half ? -1.f : 1.f;
-  float q_own[VEC], q_par[VEC], q_far[VEC];
-  {
-    const size_t qb = (size_t)bh * kD;
-#pragma unroll
-    for (int v = 0; v < VEC; ++v) {
-      q_own[v] = load_elem(q + qb + d0 + v);
-      q_par[v] = load_elem(q + qb + dp + v) * sgn;
-      q_far[v] = q_rot[qb + d0 + v];
-    }
-  }
   const float scale = 0.08838834764831845f;   // 1/sqrt(128)
   const T* kb = k_cache + ((size_t)b * Hkv + kv) * ctx_stride * kD + d0;
   const T* vb = v_cache + ((size_t)b * Hkv + kv) * ctx_stride * kD + d0;
   const int32_t* idx = topk_idx + (size_t)bh * top_k;
+  const size_t qb = (size_t)bh * kD;
 
   float m_run = -INFINITY, l_run = 0.f, acc[VEC];
 #pragma unroll
   for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
 
-  for (int tb = t0; tb < t1; tb += kAttnTile) {
-    const int tn = min(kAttnTile, t1 - tb);
+  // One row's contribution, given this lane's part of q . k
+  auto absorb = [&](float dot, const uint4& vraw) {
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
+    float vr[VEC];
+    RowVec<T>::widen(vraw, vr);
+    const float logit = dot * scale;
+    const float mn = fmaxf(m_run, logit);
+    const float alpha = __expf(m_run - mn), pr = __expf(logit - mn);
+    l_run = l_run * alpha + pr;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = acc[v] * alpha + pr * vr[v];
+    m_run = mn;
+  };
+
+  for (int tb = 0; tb < n_mine; tb += kAttnTile) {
+    const int tn = min(kAttnTile, n_mine - tb);
     __syncthreads();
     for (int i = tid; i < tn; i += kAttnThreads) {
-      const int t = tb + i;
+      const int t = first + (tb + i) * stride;
       int j;
-      if (t < sr.sink_end) j = t;
-      else if (t < sr.sink_end + cnt) j = idx[t - sr.sink_end];
-      else j = sr.win_start + (t - sr.sink_end - cnt);
+      if (win_part) j = sr.win_start + t;
+      else j = t < sr.sink_end ? t : idx[t - sr.sink_end];
       s_pos[i] = min(max(j, 0), sr.n - 1);   // a bad caller index must not leave the cache
     }
     __syncthreads();
-    constexpr int U = 2;
-    for (int i0 = wv * SLOTS + slot; i0 < tn; i0 += RB * U) {
-      float kr[U][VEC], vr[U][VEC], qv[U][VEC];
-      bool valid[U];
+
+    if (!win_part) {
+      // Far rows: logit = q~ . k.  Two register sets of U rows are used alternately: the loads of
+      // one are issued (unconditionally, row index clamped) before the other is consumed, so a
+      // wave always has 2 U key and value rows in flight.
+      constexpr int U = 2;
+      constexpr int STEP = RB * U;
+      float q_far[VEC];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        const int i = i0 + u * RB;
-        valid[u] = i < tn;
-        const int j = s_pos[valid[u] ? i : i0];
-        RowVec<T>::load(kb + (size_t)j * kD, kr[u]);
-        RowVec<T>::load(vb + (size_t)j * kD, vr[u]);
-        const int delta = sr.n - 1 - j;
-        if (delta < window) {   // window token: standard RoPE at relative position delta
-          const float* cw = cos_win + (size_t)delta * HALF + (d0 & (HALF - 1));
-          const float* sw = sin_win + (size_t)delta * HALF + (d0 & (HALF - 1));
+      for (int v = 0; v < VEC; ++v) q_far[v] = q_rot[qb + d0 + v];
+      uint4 ka[U], va[U], kc[U], vc[U];
+      auto load_set = [&](int i0, uint4 (&kr)[U], uint4 (&vr)[U]) {
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) qv[u][v] = q_own[v] * cw[v] + q_par[v] * sw[v];
-        } else {
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) qv[u][v] = q_far[v];
+        for (int u = 0; u < U; ++u) {
+          const int j = s_pos[min(i0 + u * RB, tn - 1)];
+          kr[u] = RowVec<T>::load(kb + (size_t)j * kD);
+          vr[u] = RowVec<T>::load(vb + (size_t)j * kD);
         }
+      };
+      auto use_set = [&](int i0, const uint4 (&kr)[U], const uint4 (&vr)[U]) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          float kf[VEC];
+          RowVec<T>::widen(kr[u], kf);
+          float dot = 0.f;
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) dot += q_far[v] * kf[v];
+          if (i0 + u * RB < tn) absorb(dot, vr[u]);
+        }
+      };
+      const int lane_row = wv * SLOTS + slot;
+      load_set(lane_row, ka, va);
+#pragma unroll 1
+      for (int base = 0; base < tn; base += 2 * STEP) {
+        load_set(base + STEP + lane_row, kc, vc);
+        use_set(base + lane_row, ka, va);
+        load_set(base + 2 * STEP + lane_row, ka, va);
+        use_set(base + STEP + lane_row, kc, vc);
       }
+    } else {
+      // Window rows: logit = (q R_delta) . k with the standard rotation at the relative position
+      // delta = n - 1 - j, built from the cos/sin tables of the row.
+      constexpr int U = 2;
+      const bool low_half = d0 < HALF;
+      const int dp = low_half ? d0 + HALF : d0 - HALF;
+      const float sgn = low_half ? -1.f : 1.f;
+      float q_own[VEC], q_par[VEC];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        float dot = 0.f;
+      for (int v = 0; v < VEC; ++v) {
+        q_own[v] = load_elem(q + qb + d0 + v);
+        q_par[v] = load_elem(q + qb + dp + v) * sgn;
+      }
+      for (int i0 = wv * SLOTS + slot; i0 < tn; i0 += RB * U) {
+        uint4 kr[U], vr[U];
+        float cw[U][VEC], sw[U][VEC];
 #pragma unroll
-        for (int v = 0; v < VEC; ++v) dot += qv[u][v] * kr[u][v];
+        for (int u = 0; u < U; ++u) {
+          const int j = s_pos[min(i0 + u * RB, tn - 1)];
+          kr[u] = RowVec<T>::load(kb + (size_t)j * kD);
+          vr[u] = RowVec<T>::load(vb + (size_t)j * kD);
+          const int delta = min(max(sr.n - 1 - j, 0), window - 1);
+          const float* cp = cos_win + (size_t)delta * HALF + (d0 & (HALF - 1));
+          const float* sp = sin_win + (size_t)delta * HALF + (d0 & (HALF - 1));
 #pragma unroll
-        for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
-        if (valid[u]) {
-          const float logit = dot * scale;
-          const float mn = fmaxf(m_run, logit);
-          const float alpha = __expf(m_run - mn), p = __expf(logit - mn);
-          l_run = l_run * alpha + p;
+          for (int v = 0; v < VEC; ++v) {
+            cw[u][v] = cp[v];
+            sw[u][v] = sp[v];
+          }
+        }
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) acc[v] = acc[v] * alpha + p * vr[u][v];
-          m_run = mn;
+        for (int u = 0; u < U; ++u) {
+          float kf[VEC];
+          RowVec<T>::widen(kr[u], kf);
+          float dot = 0.f;
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) dot += (q_own[v] * cw[u][v] + q_par[v] * sw[u][v]) * kf[v];
+          if (i0 + u * RB < tn) absorb(dot, vr[u]);
         }
       }
     }
@@ -196,13 +249,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
       const float a2[1] = {s_acc[w][tid]};
       merge_state<1>(m, l, a, s_m[w], s_l[w], a2);
     }
-    if (n_split == 1) {
-      store_elem(out + (size_t)bh * kD + tid, l > 0.f ? a[0] / l : 0.f);
-    } else {
-      float* pp = partial + ((size_t)bh * n_split + split) * (kD + 2);
-      pp[tid] = a[0];
-      if (tid == 0) { pp[kD] = m; pp[kD + 1] = l; }
-    }
+    float* pp = partial + ((size_t)bh * (n_far + n_win) + part) * (kD + 2);
+    pp[tid] = a[0];
+    if (tid == 0) { pp[kD] = m; pp[kD + 1] = l; }
   }
 }
 
@@ -232,14 +281,15 @@ static hipError_t launch_attn_t(const a2ats_dims& d, const AttnPlan& plan, const
                                 void* out, void* ws, hipStream_t stream) {
   const int heads = d.batch * d.n_q_heads;
   if (heads == 0) return hipSuccess;
-  hipLaunchKernelGGL((attn_partial_kernel<T>), dim3(plan.n_split, heads), dim3(kAttnThreads), 0, stream,
+  const int parts = plan.n_far + plan.n_win;
+  hipLaunchKernelGGL((attn_partial_kernel<T>), dim3(parts, heads), dim3(kAttnThreads), 0, stream,
                      (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
-                     cos_win, sin_win, seq_lens, (T*)out, (float*)ws, d.n_q_heads, d.n_kv_heads,
-                     d.ctx_len, d.ctx_stride, top_k, window, n_sink, plan.n_split);
+                     cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
+                     d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win);
   hipError_t err = hipGetLastError();
-  if (err != hipSuccess || plan.n_split == 1) return err;
+  if (err != hipSuccess) return err;
   hipLaunchKernelGGL((attn_combine_kernel<T>), dim3(heads), dim3(kD), 0, stream, (const float*)ws,
-                     (T*)out, plan.n_split);
+                     (T*)out, parts);
   return hipGetLastError();
 }
 
