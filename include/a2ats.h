@@ -32,7 +32,7 @@
  *                                            exact[b,h,m,c']) >> s for head h = kv*G + 4*g4 + r
  *                                            (0 for heads past G); s is the smallest shift for
  *                                            which every coarse entry is <= floor(65535 / M)
- *     meta   [B*Hq][4] int32                 {sum_m min_c exact[b,h,m,c], s, 0, 0}
+ *     meta   [B*Hq][4] int32                 {sum_m min_c exact[b,h,m,c], s, sum_m max_c exact[b,h,m,c], 0}
  *   in this order.  A token's approximate score is lut_scale * sum_m exact[.., m, codes[j,m]]:
  *   integer accumulation makes it independent of summation order, so equal code rows score
  *   exactly equal and ties resolve by token index.  Its coarse score sum_m coarse[.., codes[j,m],

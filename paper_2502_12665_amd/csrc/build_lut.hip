@@ -161,10 +161,11 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
   if (tid < kHeadsPerGroup) {
     const int r = tid;
     uint32_t range = 0;
-    int32_t base = 0;
+    int32_t base = 0, top = 0;
     for (int mm = 0; mm < M; ++mm) {
       range = max(range, (uint32_t)(s_mm[0][mm][4 + r] - s_min[mm][r]));
       base += s_min[mm][r];
+      top += s_mm[0][mm][4 + r];
     }
     int sh = 0;
     while ((range >> sh) > (uint32_t)MAXQ) ++sh;
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
       int32_t* meta = lut + lay.off_meta + ((size_t)b * Hq + kv * G + hg) * 4;
       meta[0] = base;   // sum over subspaces of the smallest entry
       meta[1] = sh;     // coarse entry = (exact entry - subspace minimum) >> sh
-      meta[2] = 0;
+      meta[2] = top;    // sum over subspaces of the largest entry: no score exceeds it
       meta[3] = 0;
     }
   }

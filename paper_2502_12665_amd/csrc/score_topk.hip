@@ -72,10 +72,10 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     cap_rows = (cap_rows + 31) / 32 * 32;
     if (cap_rows < 64) cap_rows = 64;
     if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;
-    if (cap_rows > 32768) cap_rows = 32768;   // ranks inside a segment are stored in 16 bits
-    p.row_cap = (int)cap_rows;
+    if (cap_rows > 1024) cap_rows = 1024;   // ranks inside a segment are stored in 10 bits
+    p.row_cap = (int)cap_rows;                // a multiple of 32
     const size_t segs = (size_t)problems * p.chunks * kStreamWaves;
-    const size_t entry_bytes = (4 + d.n_sub / 4) * sizeof(uint32_t);
+    const size_t entry_bytes = 8 + d.n_sub;   // header + code bytes
     p.off_thr = 0;
     p.off_route = (p.off_thr + heads * p.P0 * sizeof(int32_t) + 255) / 256 * 256;
     p.off_count = (p.off_route + heads * sizeof(uint32_t) + 255) / 256 * 256;
@@ -192,6 +192,26 @@ __device__ __forceinline__ int32_t combined_threshold(const int32_t* __restrict_
   }
   if (all_rows) return INT32_MIN;
   return (int32_t)(sum / P0);   // thresholds are >= 0
+}
+
+// Survivor entries.  The streaming pass writes, per (problem, chunk, wave) segment, row_cap
+// 8-byte headers followed by row_cap rows of code bytes.  A header packs the token position (20
+// bits: contexts are at most 2^20 tokens), the mask of the heads that want the row (4 bits) and,
+// for each head, the row's rank among the rows of its segment that the head wants (10 bits each:
+// a segment holds at most 1024 rows).
+template <int M>
+__host__ __device__ __forceinline__ size_t segment_words(int row_cap) {
+  return (size_t)row_cap * (2 + M / 4);
+}
+// `hm20`: the head mask already shifted to bits 20..23
+__device__ __forceinline__ uint2 pack_entry_header(uint32_t pos, uint32_t hm20, const uint32_t (&rk)[4]) {
+  return make_uint2(pos | hm20 | (rk[0] << 24), (rk[0] >> 8) | (rk[1] << 2) | (rk[2] << 12) | (rk[3] << 22));
+}
+__device__ __forceinline__ uint32_t entry_pos(uint32_t w0) { return w0 & 0xfffffu; }
+__device__ __forceinline__ bool entry_wanted(uint32_t w0, int r) { return (w0 >> (20 + r)) & 1u; }
+__device__ __forceinline__ uint32_t entry_rank(uint32_t w0, uint32_t w1, int r) {
+  if (r == 0) return (w0 >> 24) | ((w1 & 3u) << 8);
+  return (w1 >> (10 * r - 8)) & 1023u;
 }
 
 // Copy a problem's coarse table from its global order [half][c][16 m] to the LDS layout above.
@@ -487,7 +507,6 @@ __device__ __forceinline__ void stream_select_body(
     int P0, int n_chunks, int problems, int rows_per_chunk, int row_cap, int ctx_len,
     int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
-  constexpr int EW = 4 + M / 4;   // words per row entry: position, head mask, 4 ranks, code bytes
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   unsigned char* tbl = dyn_lds;
 
@@ -535,7 +554,10 @@ __device__ __forceinline__ void stream_select_body(
   sw.init(lane);
   int n_rows = 0;                  // row entries written by this wave (wave-uniform)
   int n_head[4] = {0, 0, 0, 0};    // of which wanted by each head
-  uint32_t* my_rows = cand + seg * (size_t)row_cap * EW;
+  // A segment is row_cap 8-byte entry headers followed by row_cap rows of code bytes.
+  uint32_t* my_seg = cand + seg * segment_words<M>(row_cap);
+  uint2* my_hdr = (uint2*)my_seg;
+  uint4* my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
 
   if (wbegin < wend) {
     const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
@@ -585,14 +607,13 @@ __device__ __forceinline__ void stream_select_body(
               uint32_t hm = 0, rk[4];
 #pragma unroll
               for (int r = 0; r < 4; ++r) {
-                hm |= __builtin_amdgcn_inverse_ballot_w64(hit[u][r]) ? (1u << r) : 0u;
+                hm |= __builtin_amdgcn_inverse_ballot_w64(hit[u][r]) ? (1u << (20 + r)) : 0u;
                 rk[r] = __builtin_amdgcn_mbcnt_hi(
                     (uint32_t)(hit[u][r] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit[u][r], (uint32_t)n_head[r]));
               }
-              uint4* e = (uint4*)(my_rows + (uint32_t)slot * (uint32_t)EW);
-              e[0] = make_uint4((uint32_t)(base + u * 64 + lane), hm, rk[0] | (rk[1] << 16), rk[2] | (rk[3] << 16));
+              my_hdr[slot] = pack_entry_header((uint32_t)(base + u * 64 + lane), hm, rk);
 #pragma unroll
-              for (int qd = 0; qd < M / 16; ++qd) e[1 + qd] = rows[u][qd];
+              for (int qd = 0; qd < M / 16; ++qd) my_codes[slot * (M / 16) + qd] = rows[u][qd];
             }
           }
           n_rows += __popcll(any);
@@ -650,7 +671,6 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     int P0, int problems, int n_seg, int row_cap, int cap, int ctx_len, int64_t ctx_stride, int top_k,
     int window, int n_sink) {
   constexpr int NT = kExactThreads;
-  constexpr int EW = 4 + M / 4;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ ExactLds L;
   __shared__ uint32_t s_seg_off[513];
@@ -664,7 +684,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int hg = g4 * kHeadsPerGroup + r;
   if (hg >= G) return;
-  const int bh = b * Hq + kv * G + hg, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int bh = b * Hq + kv * G + hg, tid = threadIdx.x;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   int32_t* oi = topk_idx + (size_t)bh * top_k;
   float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
@@ -698,7 +718,8 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   }
   const int32_t tc = combined_threshold(thr + (size_t)bh * P0, P0);
   const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
-  const long proof_bound = (long)meta[0] + (((long)tc - 1 + M) << meta[1]);
+  const int32_t m_base = meta[0], m_shift = meta[1], m_top = meta[2];
+  const long proof_bound = (long)m_base + (((long)tc - 1 + M) << m_shift);
   for (int e = tid; e < kCentroids * M / 4; e += NT) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
   for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
   if (tid == 0) {
@@ -726,88 +747,71 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     return;
   }
 
-  // Exact keys of the survivors (a wave per segment, a lane per entry) and their range.  Keys
-  // are then taken relative to the smallest one, so that radix digits spread over the occupied
-  // range instead of all survivors sharing the leading bits of their absolute keys.
-  uint32_t kmin = 0xffffffffu, kmax = 0;
+  // Keys are taken relative to a lower bound of every survivor's exact key (a survivor's coarse
+  // score reaches the threshold, so its exact score is at least base + (Tc << s)), and the first
+  // radix level spreads the 2048 bins over the range up to the largest possible score.  Both
+  // bounds are known before any survivor is looked at, so the histogram is filled while the keys
+  // are computed.
+  const long lo_score = tc == INT32_MIN ? (long)m_base : (long)m_base + ((long)max(tc, 0) << m_shift);
+  const uint32_t klo = score_key((int32_t)max(lo_score, (long)INT32_MIN + 1));
+  const uint32_t khi = max(klo, score_key(m_top));
+  const int nbits = 32 - __clz(khi - klo);
+  const int bits1 = nbits < 11 ? nbits : 11, shift1 = nbits - bits1;
   {
-    // Pass 1: pick this head's rows out of the problem's row entries.  tps threads share a
-    // segment; every entry carries its own destination (segment offset + rank), so all loads
-    // are independent and no thread waits for another.  c_key temporarily holds the entry index.
+    // Pass 1: pick this head's rows out of the problem's entry headers.  tps threads share a
+    // segment; every header carries its own destination (segment offset + rank), so all loads
+    // are independent and no thread waits for another.  c_key temporarily holds where the entry's
+    // code bytes are (in 16-byte units from the start of the problem's segments).
+    constexpr int kInFlight = 8;
     const int tps = NT / n_seg > 0 ? NT / n_seg : 1;
-    const uint32_t* rows0 = cand + (size_t)prob * n_seg * (size_t)row_cap * EW;
+    const size_t seg_words = segment_words<M>(row_cap);
+    const uint32_t* seg0 = cand + (size_t)prob * n_seg * seg_words;
+    const uint32_t seg_q = (uint32_t)(seg_words / 4), codes_q = (uint32_t)row_cap / 2;   // in 16-byte units
     for (int s_ = tid / tps; s_ < n_seg; s_ += NT / tps) {
       const uint32_t n_rows = s_seg_rows[s_], dst0 = s_seg_off[s_];
-      // Four entry headers are fetched whole and together before any of them is looked at (the
-      // empty asm keeps the compiler from splitting a header load and sinking parts of it behind
-      // the "does this head want the row" branch, which would serialise two latencies per entry).
-      for (uint32_t i0 = tid % tps; i0 < n_rows; i0 += 4 * tps) {
-        u32x4_t hd[4];
+      const u32x2_t* hdr = (const u32x2_t*)(seg0 + (size_t)s_ * seg_words);
+      for (uint32_t i0 = tid % tps; i0 < n_rows; i0 += kInFlight * tps) {
+        // The headers are fetched together before any of them is looked at (the empty asm keeps the
+        // compiler from sinking a load behind the "does this head want the row" branch, which
+        // would serialise the latencies).
+        u32x2_t hd[kInFlight];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-          const uint32_t i = min(i0 + k * tps, n_rows - 1);
-          hd[k] = *(const u32x4_t*)(rows0 + ((size_t)s_ * row_cap + i) * EW);
-        }
+        for (int k = 0; k < kInFlight; ++k) hd[k] = hdr[min(i0 + k * tps, n_rows - 1)];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) asm volatile("" : "+v"(hd[k]));
+        for (int k = 0; k < kInFlight; ++k) asm volatile("" : "+v"(hd[k]));
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < kInFlight; ++k) {
           const uint32_t i = i0 + k * tps;
-          if (i < n_rows && ((hd[k].y >> r) & 1u)) {
-            const uint32_t rk = ((r < 2 ? hd[k].z : hd[k].w) >> (16 * (r & 1))) & 0xffffu;
-            if (dst0 + rk < n_c) {   // always true for entries the streaming pass wrote; keeps LDS writes in range whatever the workspace holds
-              c_pos[dst0 + rk] = hd[k].x;
-              c_key[dst0 + rk] = (uint32_t)s_ * (uint32_t)row_cap + i;
+          if (i < n_rows && entry_wanted(hd[k].x, r)) {
+            const uint32_t dst = dst0 + entry_rank(hd[k].x, hd[k].y, r);
+            if (dst < n_c) {   // always true for entries the streaming pass wrote; keeps LDS writes in range whatever the workspace holds
+              c_pos[dst] = entry_pos(hd[k].x);
+              c_key[dst] = (uint32_t)s_ * seg_q + codes_q + i * (M / 16);
             }
           }
         }
       }
     }
     __syncthreads();
-    // Pass 2: exact keys of this head's survivors, densely (no divergence).
-    const uint32_t last_entry = (uint32_t)n_seg * (uint32_t)row_cap - 1u;
+    // Pass 2: exact keys of this head's survivors, densely (no divergence), and their histogram.
+    const uint4* codes0 = (const uint4*)seg0;
+    const uint32_t last_q = (uint32_t)n_seg * seg_q - M / 16;   // the clamp below is a no-op for a consistent workspace
 #pragma unroll 2
     for (uint32_t i = tid; i < n_c; i += NT) {
-      // the clamp is a no-op for a consistent workspace; it keeps the read inside this problem's entries
-      const uint4* e = (const uint4*)(rows0 + (size_t)min(c_key[i], last_entry) * EW);
+      const uint4* e = codes0 + min(c_key[i], last_q);
       uint32_t w[M / 4];
 #pragma unroll
       for (int qd = 0; qd < M / 16; ++qd) {
-        const uint4 v = e[1 + qd];
+        const uint4 v = e[qd];
         w[4 * qd] = v.x; w[4 * qd + 1] = v.y; w[4 * qd + 2] = v.z; w[4 * qd + 3] = v.w;
       }
-      const uint32_t key = score_key(score_exact<M>(w, lut1));
+      const uint32_t key = max(score_key(score_exact<M>(w, lut1)), klo) - klo;
       c_key[i] = key;
-      kmin = min(kmin, key);
-      kmax = max(kmax, key);
+      atomicAdd(&L.hist[min(key >> shift1, (uint32_t)kHistBins - 1)], 1u);
     }
   }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    kmin = min(kmin, __shfl_xor(kmin, off));
-    kmax = max(kmax, __shfl_xor(kmax, off));
-  }
-  if (lane == 0) {
-    L.wave_a[wv] = kmin;
-    L.wave_b[wv] = kmax;
-  }
+  const uint32_t kmin = klo;
   __syncthreads();
-  kmin = L.wave_a[0];
-  kmax = L.wave_b[0];
-  for (int w = 1; w < NT / 64; ++w) {
-    kmin = min(kmin, L.wave_a[w]);
-    kmax = max(kmax, L.wave_b[w]);
-  }
-
-  // First radix level over the significant bits of the relative keys.
-  const int nbits = 32 - __clz(kmax - kmin);
-  const int bits1 = nbits < 11 ? nbits : 11, shift1 = nbits - bits1;
-  for (uint32_t i = tid; i < n_c; i += NT) {
-    const uint32_t key = c_key[i] - kmin;
-    c_key[i] = key;
-    atomicAdd(&L.hist[key >> shift1], 1u);
-  }
-  __syncthreads();   // also orders the reads of wave_a / wave_b above before their reuse below
   block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, (uint32_t)sr.kk, L.wave_a, L.res);
   const uint32_t bin1 = L.res[0], above1 = L.res[1], m_bin = L.hist[bin1];
   uint32_t k_rem = (uint32_t)sr.kk - above1;   // winners still to pick inside bin1

@@ -80,6 +80,8 @@ def coarse_table_consistent(st, wl: synth.Workload) -> bool:
         s = meta[:, h, 1]
         if not np.array_equal(meta[:, h, 0], mins.sum(axis=1)):
             return False
+        if not np.array_equal(meta[:, h, 2], exact[:, h].max(axis=2).sum(axis=1)):
+            return False
         rem = exact[:, h] - mins[:, :, None] - (c << s[:, None, None])
         if (rem < 0).any() or (rem >= (1 << s)[:, None, None]).any() or c.max() > 65535 // M:
             return False
