@@ -182,16 +182,28 @@ __device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const uns
 // close to what one rank search over the merged sample would give.  INT32_MIN ("take every row")
 // from any of them wins.  Exactness never depends on this value: the final kernel proves its
 // result complete against whatever threshold was used, or redoes the head exactly.
-__device__ __forceinline__ int32_t combined_threshold(const int32_t* __restrict__ t, int P0) {
-  long sum = 0;
-  bool all_rows = false;
-  for (int p = 0; p < P0; ++p) {
-    const int32_t v = t[p];
-    all_rows |= v == INT32_MIN;
-    sum += v;
+// Called by all lanes of a wave for NH consecutive heads starting at `head0` (heads at or past
+// `n_valid` get 65536, which no coarse score reaches): lane 8 r + p loads part p of head r, so
+// the P0 <= 8 values of all heads arrive with one load latency instead of one after another.
+template <int NH>
+__device__ __forceinline__ void combined_thresholds(const int32_t* __restrict__ thr, size_t head0,
+                                                    int n_valid, int P0, int32_t (&T)[NH]) {
+  static_assert(NH * 8 <= 64, "one lane per (head, part)");
+  const int lane = threadIdx.x & 63, r = lane >> 3, p = lane & 7;
+  int32_t v = 0;
+  if (r < NH && r < n_valid && p < P0) v = thr[(head0 + r) * P0 + p];
+  int32_t all_rows = v == INT32_MIN ? 1 : 0;
+  int32_t sum = all_rows ? 0 : v;   // thresholds are >= 0 and below 2^16
+#pragma unroll
+  for (int off = 1; off < 8; off <<= 1) {
+    sum += __shfl_xor(sum, off);
+    all_rows |= __shfl_xor(all_rows, off);
   }
-  if (all_rows) return INT32_MIN;
-  return (int32_t)(sum / P0);   // thresholds are >= 0
+#pragma unroll
+  for (int i = 0; i < NH; ++i) {
+    const int32_t s_i = __builtin_amdgcn_readlane(sum, 8 * i), a_i = __builtin_amdgcn_readlane(all_rows, 8 * i);
+    T[i] = i >= n_valid ? 65536 : (a_i ? INT32_MIN : s_i / P0);
+  }
 }
 
 // Survivor entries.  The streaming pass writes, per (problem, chunk, wave) segment, row_cap
@@ -526,17 +538,8 @@ __device__ __forceinline__ void stream_select_body(
   // Every (problem, chunk, wave) owns one survivor segment in HBM: no atomics, no contention.
   const size_t seg = ((size_t)prob * n_chunks + chunk) * kStreamWaves + wv;
   uint32_t* my_meta = seg_meta + seg * kSegMeta;
-  int32_t T[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int hg = g4 * kHeadsPerGroup + r;
-    int32_t t = 65536;   // padded heads never want a row (a coarse score is below 2^16)
-    if (hg < G) {
-      const size_t head = (size_t)b * Hq + kv * G + hg;
-      t = combined_threshold(thr + head * P0, P0);
-    }
-    T[r] = t;
-  }
+  int32_t T[4];   // padded heads never want a row
+  combined_thresholds<4>(thr, (size_t)b * Hq + kv * G + g4 * kHeadsPerGroup, G - g4 * kHeadsPerGroup, P0, T);
   // The scoring loop addresses the table by absolute LDS address (it must start at 0, which holds
   // because this kernel has no static LDS).  Should a toolchain ever place it elsewhere, publish
   // an overflowing segment instead: the final kernel then takes the exact route.
@@ -545,10 +548,6 @@ __device__ __forceinline__ void stream_select_body(
     if (lane < kSegMeta) my_meta[lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
     return;
   }
-
-  const LutLayout lay = lut_layout(B, Hq, Hkv, M);
-  load_coarse_table<M, NT>(lut, lay, prob, tbl);
-  __syncthreads();
 
   LaneSwizzle<M> sw;
   sw.init(lane);
@@ -559,7 +558,8 @@ __device__ __forceinline__ void stream_select_body(
   uint2* my_hdr = (uint2*)my_seg;
   uint4* my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
 
-  if (wbegin < wend) {
+  const bool has_rows = wbegin < wend;   // wave-uniform
+  {
     const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
     // Rows are read U at a time per lane, one full step ahead of their use (two register sets
     // used alternately); loads are unconditional (row index clamped into the wave's range) so
@@ -622,7 +622,11 @@ __device__ __forceinline__ void stream_select_body(
         }
       }
     };
-    load_rows((int)wbegin, rows_a);
+    // The first rows are requested before the table is copied to LDS, so both latencies overlap.
+    // (Every wave of the workgroup reaches the barrier, also one whose row range is empty.)
+    if (has_rows) load_rows((int)wbegin, rows_a);
+    load_coarse_table<M, NT>(lut, lut_layout(B, Hq, Hkv, M), prob, tbl);
+    __syncthreads();
 #pragma unroll 1
     for (int base = (int)wbegin; base < wend; base += 2 * STEP) {
       load_rows(base + STEP, rows_b);
@@ -716,7 +720,9 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     seg_rows = mt[0];
     my_cnt = mt[1 + r];
   }
-  const int32_t tc = combined_threshold(thr + (size_t)bh * P0, P0);
+  int32_t tc1[1];
+  combined_thresholds<1>(thr, (size_t)bh, 1, P0, tc1);
+  const int32_t tc = tc1[0];
   const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
   const int32_t m_base = meta[0], m_shift = meta[1], m_top = meta[2];
   const long proof_bound = (long)m_base + (((long)tc - 1 + M) << m_shift);
