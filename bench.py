@@ -74,8 +74,6 @@ def main():
     ap.add_argument("--cpu-baseline-seconds", type=float, default=10.0,
                     help="the oracle repeats whole steps until this much time has passed")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays")
-    ap.add_argument("--no-overlap", action="store_true",
-                    help="run the key encode and the table build one after the other instead of side by side")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run 3 plain float32 copies (out = in + 0) of this many MiB, so that a "
                          "rocprofv3 --pmc run of this command holds a kernel of known HBM traffic")
@@ -112,27 +110,14 @@ def main():
     kev = HipEvents(n_ev)
     phase_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
 
-    side = torch.cuda.Stream()   # default priority
-
-    def step(i, timed, overlap=False):
+    def step(i, timed, stats=False):
         x = reps[i % R]
         if timed:
             phase_ev[i][0].record()
-        if overlap:
-            # The new key's encode and the query's table build do not depend on each other (the
-            # encode writes the code row of position N-1, which is inside the window and never
-            # scored): run them side by side and join before the scoring, which shares `ws`.
-            main = torch.cuda.current_stream()
-            side.wait_stream(main)
-            with torch.cuda.stream(side):
-                B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
-        else:
-            B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
+        B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
         if timed:
             phase_ev[i][1].record()
         B.build_lut(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, st.lut, st.lut_scale)
-        if overlap:
-            torch.cuda.current_stream().wait_stream(side)
         if timed:
             phase_ev[i][2].record()
             B.profile_stream_kernel(*kev.pair(i))
@@ -140,7 +125,7 @@ def main():
                      None, None, st.ws)
         if timed:
             phase_ev[i][3].record()
-        elif i == 0:   # candidate-list sizes, read before the attention reuses the workspace
+        elif stats:   # candidate-list sizes, read before the attention reuses the workspace
             B.score_topk_stats(dims, K, w, wl.n_sink, st.ws, cand_counts)
         B.sparse_attn(dims, x["q"], st.q_rot, x["k"], x["v"], st.topk_idx, st.topk_count, K, w, wl.n_sink,
                       st.cos_win, st.sin_win, None, st.out, st.ws)
@@ -156,33 +141,35 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     for i in range(args.warmup):
-        step(i, False)
+        step(i, False, stats=(i == 0))
     torch.cuda.synchronize()
 
-    # ---- timed region 1: K whole steps.  The step is launch-bound on the host side (13 small
-    # kernels), so each replica's step is captured once into a HIP graph and replayed.
-    use_graph = not args.no_graph
-    if use_graph:
+    # ---- timed region 1: K whole steps, launched eagerly (the host runs ahead of the GPU) and, unless
+    # --no-graph, also as replays of one captured HIP graph per replica; `value` takes the faster
+    # of the two and `launch` says which.  Both regions time exactly K steps between two
+    # device synchronisations.
+    def timed_steps(run_one):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            run_one(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_eager = timed_steps(lambda i: step(i, False))
+    ms_graph = None
+    if not args.no_graph:
         graphs = []
         for r in range(R):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
-                step(r, False, overlap=not args.no_overlap)
+                step(r, False)
             graphs.append(g)
         for r in range(R):
             graphs[r].replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            graphs[i % R].replay()
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    else:
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            step(i, False, overlap=not args.no_overlap)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
+        ms_graph = timed_steps(lambda i: graphs[i % R].replay())
+    use_graph = ms_graph is not None and ms_graph < ms_eager
+    ms_per_step = ms_graph if use_graph else ms_eager
 
     # ---- timed region 2: the same K steps launched eagerly with events between the phases and
     # around the streaming kernel (events cannot be read back from inside a graph)
@@ -194,7 +181,6 @@ def main():
     te1 = time.perf_counter()
     B.profile_stream_kernel(None, None)
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
     ph = [[phase_ev[i][p].elapsed_time(phase_ev[i][p + 1]) * 1e3 for i in range(args.steps)] for p in range(4)]
     med = lambda v: float(sorted(v)[len(v) // 2])
     mean = lambda v: float(sum(v) / len(v))
@@ -219,8 +205,8 @@ def main():
         "value": rows / (ms_per_step * 1e-3),
         "unit": "keys/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "launch": ("hip-graph replay" if use_graph else "eager") +
-                  ("" if args.no_overlap else ", key encode alongside table build"),
+        "launch": "hip-graph replay" if use_graph else "eager",
+        "ms_per_step_eager": ms_eager, "ms_per_step_graph_replay": ms_graph,
         "ms_per_step_eager_with_events": (te1 - te0) * 1e3 / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32 fixed-point scores; bf16 K/V with f32 accumulate" if wl.kv_dtype == "bf16" else
