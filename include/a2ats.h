@@ -79,7 +79,9 @@ const char* a2ats_status_string(int status);
 /* Number of int32 elements of the lookup-table array for these dims (see the format above). */
 size_t a2ats_lut_elems(const a2ats_dims* dims);
 
-/* Scratch bytes `op` needs for these dims (0 if it needs none; (size_t)-1 on bad dims). */
+/* Scratch bytes `op` needs for these dims (0 if it needs none; (size_t)-1 on bad dims).  For
+ * A2ATS_OP_ATTN the figure covers up to 64 sink tokens; a call with more may need more and is
+ * refused with A2ATS_ERR_WORKSPACE if `ws` is too small. */
 size_t a2ats_workspace_bytes(const a2ats_dims* dims, int op, int32_t top_k, int32_t window);
 
 /*

@@ -61,9 +61,9 @@ size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t
     }
     case A2ATS_OP_ATTN: {
       if (top_k < 0 || window < 0) return (size_t)-1;
-      // sized for the largest split the planner can pick (n_sink only adds rows)
-      const size_t heads = (size_t)d->batch * d->n_q_heads;
-      return heads * 32 * (128 + 2) * sizeof(float);
+      // The number of workgroups per head grows with the attended rows; sized for up to 64 sinks
+      // (a call with more sinks than that may ask for more and is refused if `ws` is too small).
+      return a2ats::make_attn_plan(*d, top_k, window, 64).bytes;
     }
     default: return (size_t)-1;
   }
