@@ -26,6 +26,7 @@
 //       so the result is always exact with respect to the 32-bit scores.
 #include <math.h>
 
+#include <algorithm>
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -59,21 +60,28 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
     if (chunks > 64) chunks = 64;
-    long rpc = (ncand + chunks - 1) / chunks;
-    rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
-    p.chunks = (int)((ncand + rpc - 1) / rpc);
-    p.rows_per_chunk = (int)rpc;
-    const size_t heads = (size_t)d.batch * d.n_q_heads;
     // One survivor segment per (problem, chunk, wave) of the streaming pass: a header and row_cap
     // row entries.  A row survives if any of the (up to) four heads wants it; with a threshold
-    // that lets about 2.2 K rows per head through that is at most 4 * 2.2 * K / ncand of the rows.
-    const long rows_per_wave = rpc / kStreamWaves;
-    long cap_rows = (long)(rows_per_wave * (4.0 * 2.5 * top_k / (double)ncand) * 1.5) + 32;
-    cap_rows = (cap_rows + 31) / 32 * 32;
-    if (cap_rows < 64) cap_rows = 64;
-    if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;
-    if (cap_rows > 1024) cap_rows = 1024;   // ranks inside a segment are stored in 10 bits
+    // that lets about 2.5 K rows per head through that is at most 4 * 2.5 * K / ncand of the rows;
+    // row_cap is 1.5 times that share of a wave's rows.  Ranks inside a segment are stored in 10
+    // bits, so the context is cut into more chunks until row_cap fits 1024.
+    const double keep = std::min(1.0, 4.0 * 2.5 * top_k / (double)ncand);
+    long rpc, cap_rows;
+    for (;; ++chunks) {
+      rpc = (ncand + chunks - 1) / chunks;
+      rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
+      const long rows_per_wave = rpc / kStreamWaves;
+      cap_rows = (long)(rows_per_wave * keep * 1.5) + 32;
+      cap_rows = (cap_rows + 31) / 32 * 32;
+      if (cap_rows < 64) cap_rows = 64;
+      if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;   // rows_per_wave is a multiple of 64
+      if (cap_rows <= 1024 || chunks >= 64) break;
+    }
+    if (cap_rows > 1024) cap_rows = 1024;   // cannot happen for contexts up to 2^20 tokens (64 chunks of <= 2048 rows per wave)
+    p.chunks = (int)((ncand + rpc - 1) / rpc);
+    p.rows_per_chunk = (int)rpc;
     p.row_cap = (int)cap_rows;                // a multiple of 32
+    const size_t heads = (size_t)d.batch * d.n_q_heads;
     const size_t segs = (size_t)problems * p.chunks * kStreamWaves;
     const size_t entry_bytes = 8 + d.n_sub;   // header + code bytes
     p.off_thr = 0;

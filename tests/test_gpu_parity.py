@@ -324,7 +324,7 @@ def _routes(wl, xd, n_sink=0):
 def test_fast_route_is_taken_and_fallback_triggers():
     """Ordinary inputs must be served by the streaming route for every head (no silent exact
     fallback), with a survivor list of modest size; degenerate inputs must fall back."""
-    for name in ("c2_llama8b_32k", "c4_long_128k"):
+    for name in ("c2_llama8b_32k", "c3_batched_32k", "c4_long_128k", "c5_qwen7b_64k"):
         wl = synth.WORKLOADS[name]
         xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
         surv, route = _routes(wl, xd)
