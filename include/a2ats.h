@@ -24,16 +24,16 @@
  * Lookup-table format (shared by a2ats_build_lut and a2ats_score_topk)
  *   `lut` is one int32 array of a2ats_lut_elems() words produced by a2ats_build_lut and consumed
  *   by a2ats_score_topk.  With NG = ceil(G/4) groups of four query heads per KV head it holds
- *     exact  [B*Hq][M][256] int32            exact[b,h,m,c] = round(2^e * <q_rot[b,h,m*ds:(m+1)*ds],
+ *     exact  [B*Hq][256][M] int32            exact[b,h,c,m] = round(2^e * <q_rot[b,h,m*ds:(m+1)*ds],
  *                                            codebook[kv,m,c,:]>), inner product in float64; the
  *                                            power of two 2^e is chosen per head so that a sum of
  *                                            M entries stays below 2^30; lut_scale[b,h] = 2^-e
- *     coarse [B*Hkv*NG][M/16][256][16][4] uint16   coarse[.., c, m, r] = (exact[b,h,m,c] - min_c'
- *                                            exact[b,h,m,c']) >> s for head h = kv*G + 4*g4 + r
+ *     coarse [B*Hkv*NG][M/16][256][16][4] uint16   coarse[.., c, m, r] = (exact[b,h,c,m] - min_c'
+ *                                            exact[b,h,c',m]) >> s for head h = kv*G + 4*g4 + r
  *                                            (0 for heads past G); s is the smallest shift for
  *                                            which every coarse entry is <= floor(65535 / M)
- *     meta   [B*Hq][4] int32                 {sum_m min_c exact[b,h,m,c], s, sum_m max_c exact[b,h,m,c], 0}
- *   in this order.  A token's approximate score is lut_scale * sum_m exact[.., m, codes[j,m]]:
+ *     meta   [B*Hq][4] int32                 {sum_m min_c exact[b,h,c,m], s, sum_m max_c exact[b,h,c,m], 0}
+ *   in this order.  A token's approximate score is lut_scale * sum_m exact[.., codes[j,m], m]:
  *   integer accumulation makes it independent of summation order, so equal code rows score
  *   exactly equal and ties resolve by token index.  Its coarse score sum_m coarse[.., codes[j,m],
  *   m, r] fits 16 bits and satisfies  exact = meta[0] + (coarse << s) + rem, 0 <= rem < M * 2^s,

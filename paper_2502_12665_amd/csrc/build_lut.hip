@@ -6,16 +6,15 @@
 // anything a matrix core would help with, so it runs on the vector ALU in float64: products
 // of two float32 values are exact in float64, which makes every table entry the correctly
 // rounded inner product.  Three things are written per head (see "Lookup-table format" in
-// a2ats.h): the exact 32-bit fixed-point table [m][c], a 16-bit coarse copy of it interleaved
-// over the four heads of the group [c][m][4] for the streaming kernel, and the two numbers that
-// relate them (sum of the per-subspace minima, shift).
+// a2ats.h): the exact 32-bit fixed-point table [c][m], a 16-bit coarse copy of it interleaved
+// over the four heads of the group [c][m][4] for the streaming kernel, and the numbers that
+// relate them (sum of the per-subspace minima, shift, sum of the per-subspace maxima).
 #include "common.hpp"
 #include "internal.hpp"
 
 namespace a2ats {
 
 constexpr int kLutThreads = 1024;
-constexpr int kLutWaves = kLutThreads / 64;
 
 template <int DS, bool QBF16>
 __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
@@ -25,22 +24,33 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
   constexpr int D = 128, HALF = 64, M = D / DS;
   constexpr int ENTRIES = kCentroids * M;
   constexpr int EPT = ENTRIES / kLutThreads;
-  constexpr int ROW = kCentroids + 1;   // padded row of the LDS transpose buffer
   constexpr int MAXQ = 65535 / M;       // a sum of M coarse entries fits 16 bits
-  extern __shared__ __align__(16) unsigned char dyn_lds[];
-  int32_t* s_t = (int32_t*)dyn_lds;     // [4][M][ROW]
   __shared__ float s_q[kHeadsPerGroup][D];
-  __shared__ double s_max[kLutWaves][kHeadsPerGroup];
+  __shared__ uint32_t s_maxbits[kHeadsPerGroup];   // largest |entry| per head, as float bits
   __shared__ int s_exp[kHeadsPerGroup];
-  __shared__ int32_t s_mm[kLutWaves][M][8];
-  __shared__ int32_t s_min[M][kHeadsPerGroup];
+  __shared__ int32_t s_min[M][kHeadsPerGroup], s_max[M][kHeadsPerGroup];
   __shared__ int32_t s_shift[kHeadsPerGroup];
 
   const int G = Hq / Hkv;
   const int prob = blockIdx.x;
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
-  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tid = threadIdx.x;
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
+
+  // The codebook rows of this thread's entries (e = c * M + m, so its entries share m = tid % M)
+  // are requested first: their latency overlaps the query rotation.
+  const int m = tid % M;
+  float cv[EPT][DS];
+#pragma unroll
+  for (int k = 0; k < EPT; ++k) {
+    const int c = (tid + k * kLutThreads) / M;
+    const float* cw = codebook + (((size_t)kv * M + m) * kCentroids + c) * DS;
+#pragma unroll
+    for (int t = 0; t < DS; t += 4) {
+      const float4 f = *(const float4*)(cw + t);
+      cv[k][t] = f.x; cv[k][t + 1] = f.y; cv[k][t + 2] = f.z; cv[k][t + 3] = f.w;
+    }
+  }
 
   // --- q~ = q R_b for the (up to) four heads of this group
   if (tid < kHeadsPerGroup * HALF) {
@@ -69,44 +79,42 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
     s_q[r][t] = o1;
     s_q[r][t + HALF] = o2;
   }
+  if (tid < kHeadsPerGroup) s_maxbits[tid] = 0u;
+  if (tid < M * kHeadsPerGroup) {
+    s_min[tid / kHeadsPerGroup][tid % kHeadsPerGroup] = INT32_MAX;
+    s_max[tid / kHeadsPerGroup][tid % kHeadsPerGroup] = INT32_MIN;
+  }
   __syncthreads();
 
-  // --- table entries in float64; entry e = c * M + m, so a thread's entries share m = tid % M
+  // --- table entries in float64
   double val[EPT][kHeadsPerGroup];
-  double mx[kHeadsPerGroup] = {0.0, 0.0, 0.0, 0.0};
-  const int m = tid % M;
+  float mx[kHeadsPerGroup] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int k = 0; k < EPT; ++k) {
-    const int c = (tid + k * kLutThreads) / M;
-    const float* cw = codebook + (((size_t)kv * M + m) * kCentroids + c) * DS;
-    float cv[DS];
-#pragma unroll
-    for (int t = 0; t < DS; t += 4) {
-      const float4 f = *(const float4*)(cw + t);
-      cv[t] = f.x; cv[t + 1] = f.y; cv[t + 2] = f.z; cv[t + 3] = f.w;
-    }
 #pragma unroll
     for (int r = 0; r < kHeadsPerGroup; ++r) {
       double acc = 0.0;
 #pragma unroll
-      for (int t = 0; t < DS; ++t) acc += (double)s_q[r][m * DS + t] * (double)cv[t];
+      for (int t = 0; t < DS; ++t) acc += (double)s_q[r][m * DS + t] * (double)cv[k][t];
       val[k][r] = acc;
-      mx[r] = fmax(mx[r], fabs(acc));
+      // rounded away from zero, so the float maximum is never below the true one
+      mx[r] = fmaxf(mx[r], __double2float_ru(fabs(acc)));
     }
   }
 
-  // --- per-head power-of-two scale: M * max|entry| * 2^e < 2^30
+  // --- per-head power-of-two scale: M * max|entry| * 2^e < 2^30.  Non-negative floats order like
+  // their bit patterns, so the block maximum is an integer atomic max in LDS (one per wave and head
+  // after a butterfly over the wave).
 #pragma unroll
   for (int r = 0; r < kHeadsPerGroup; ++r) {
-    double v = mx[r];
+    float v = mx[r];
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmax(v, __shfl_xor(v, off));
-    if (lane == 0) s_max[wv][r] = v;
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    if ((tid & 63) == 0) atomicMax(&s_maxbits[r], __float_as_uint(v));
   }
   __syncthreads();
   if (tid < kHeadsPerGroup) {
-    double v = 0.0;
-    for (int w = 0; w < kLutWaves; ++w) v = fmax(v, s_max[w][tid]);
+    const double v = (double)__uint_as_float(s_maxbits[tid]);
     int e = 0;
     if (v > 0.0) {
       int x;
@@ -121,41 +129,25 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
   __syncthreads();
 
   // --- exact fixed-point entries; per-(subspace, head) minimum and maximum over the centroids
+  // (LDS atomics: the four lanes of a wave that share a subspace collide, nothing else does)
   int32_t iv[EPT][kHeadsPerGroup];
-  int32_t mn[4] = {INT32_MAX, INT32_MAX, INT32_MAX, INT32_MAX};
-  int32_t mxv[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
+  {
+    int32_t mn[4] = {INT32_MAX, INT32_MAX, INT32_MAX, INT32_MAX};
+    int32_t mxv[4] = {INT32_MIN, INT32_MIN, INT32_MIN, INT32_MIN};
 #pragma unroll
-  for (int k = 0; k < EPT; ++k)
+    for (int k = 0; k < EPT; ++k)
+#pragma unroll
+      for (int r = 0; r < kHeadsPerGroup; ++r) {
+        const int32_t v = (int32_t)rint(ldexp(val[k][r], s_exp[r]));
+        iv[k][r] = v;
+        mn[r] = min(mn[r], v);
+        mxv[r] = max(mxv[r], v);
+      }
 #pragma unroll
     for (int r = 0; r < kHeadsPerGroup; ++r) {
-      const int32_t v = (int32_t)rint(ldexp(val[k][r], s_exp[r]));
-      iv[k][r] = v;
-      mn[r] = min(mn[r], v);
-      mxv[r] = max(mxv[r], v);
+      atomicMin(&s_min[m][r], mn[r]);
+      atomicMax(&s_max[m][r], mxv[r]);
     }
-#pragma unroll
-  for (int off = M; off < 64; off <<= 1)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      mn[r] = min(mn[r], __shfl_xor(mn[r], off));
-      mxv[r] = max(mxv[r], __shfl_xor(mxv[r], off));
-    }
-  if (lane < M)
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      s_mm[wv][lane][r] = mn[r];
-      s_mm[wv][lane][4 + r] = mxv[r];
-    }
-  __syncthreads();
-  if (tid < M * 4) {   // thread (mm, r): min over waves, and the range max - min of this subspace
-    const int mm = tid / 4, r = tid % 4;
-    int32_t lo = s_mm[0][mm][r], hi = s_mm[0][mm][4 + r];
-    for (int w = 1; w < kLutWaves; ++w) {
-      lo = min(lo, s_mm[w][mm][r]);
-      hi = max(hi, s_mm[w][mm][4 + r]);
-    }
-    s_min[mm][r] = lo;
-    s_mm[0][mm][4 + r] = hi;   // only this thread reads or writes this slot from here on
   }
   __syncthreads();
   if (tid < kHeadsPerGroup) {
@@ -163,9 +155,9 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
     uint32_t range = 0;
     int32_t base = 0, top = 0;
     for (int mm = 0; mm < M; ++mm) {
-      range = max(range, (uint32_t)(s_mm[0][mm][4 + r] - s_min[mm][r]));
+      range = max(range, (uint32_t)(s_max[mm][r] - s_min[mm][r]));
       base += s_min[mm][r];
-      top += s_mm[0][mm][4 + r];
+      top += s_max[mm][r];
     }
     int sh = 0;
     while ((range >> sh) > (uint32_t)MAXQ) ++sh;
@@ -177,6 +169,16 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
       meta[1] = sh;     // coarse entry = (exact entry - subspace minimum) >> sh
       meta[2] = top;    // sum over subspaces of the largest entry: no score exceeds it
       meta[3] = 0;
+    }
+  }
+  // --- exact tables, one per head as [c][m]: entry e of a thread is word e of the head's table
+#pragma unroll
+  for (int r = 0; r < kHeadsPerGroup; ++r) {
+    const int hg = g4 * kHeadsPerGroup + r;
+    if (hg < G) {
+      int32_t* ex = lut + lay.off_exact + ((size_t)b * Hq + kv * G + hg) * ENTRIES;
+#pragma unroll
+      for (int k = 0; k < EPT; ++k) ex[tid + k * kLutThreads] = iv[k][r];
     }
   }
   __syncthreads();
@@ -194,22 +196,6 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
       coarse[(m >> 4) * (kCentroids * 16) + c * 16 + (m & 15)] = make_uint2(q0 | (q1 << 16), q2 | (q3 << 16));
     }
   }
-
-  // --- exact tables, one per head as [m][c]: transposed through LDS so the writes are coalesced
-#pragma unroll
-  for (int k = 0; k < EPT; ++k) {
-    const int c = (tid + k * kLutThreads) / M;
-#pragma unroll
-    for (int r = 0; r < kHeadsPerGroup; ++r) s_t[(r * M + m) * ROW + c] = iv[k][r];
-  }
-  __syncthreads();
-  for (int i = tid; i < kHeadsPerGroup * ENTRIES; i += kLutThreads) {
-    const int r = i / ENTRIES, mc = i % ENTRIES;   // mc = mm * 256 + c
-    const int hg = g4 * kHeadsPerGroup + r;
-    if (hg < G)
-      lut[lay.off_exact + ((size_t)b * Hq + kv * G + hg) * ENTRIES + mc] =
-          s_t[(r * M + mc / kCentroids) * ROW + (mc % kCentroids)];
-  }
 }
 
 hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
@@ -219,19 +205,13 @@ hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, con
   const int NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
   const dim3 grid(d.batch * d.n_kv_heads * NG), block(kLutThreads);
   if (grid.x == 0) return hipSuccess;
-  const size_t lds = (size_t)kHeadsPerGroup * d.n_sub * (kCentroids + 1) * sizeof(int32_t);
-  static size_t s_slot[4][16];
-  hipError_t err;
-#define A2ATS_LAUNCH_LUT(DS, BF, SLOT)                                                              \
-  do {                                                                                               \
-    if ((err = allow_dynamic_lds(build_lut_kernel<DS, BF>, lds, s_slot[SLOT])) != hipSuccess) return err; \
-    hipLaunchKernelGGL((build_lut_kernel<DS, BF>), grid, block, lds, stream, q, cos_b, sin_b, codebook, \
-                       q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG);               \
-  } while (0)
+#define A2ATS_LAUNCH_LUT(DS, BF)                                                                    \
+  hipLaunchKernelGGL((build_lut_kernel<DS, BF>), grid, block, 0, stream, q, cos_b, sin_b, codebook, \
+                     q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG)
   if (d.sub_dim == 8) {
-    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUT(8, true, 0); else A2ATS_LAUNCH_LUT(8, false, 1);
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUT(8, true); else A2ATS_LAUNCH_LUT(8, false);
   } else {
-    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUT(4, true, 2); else A2ATS_LAUNCH_LUT(4, false, 3);
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUT(4, true); else A2ATS_LAUNCH_LUT(4, false);
   }
 #undef A2ATS_LAUNCH_LUT
   return hipGetLastError();

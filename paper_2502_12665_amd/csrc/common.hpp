@@ -26,9 +26,9 @@ __device__ __forceinline__ int lanes_below(uint64_t mask) {
 
 // Word offsets (int32 units) of the three parts of the lookup-table blob, see a2ats.h.
 struct LutLayout {
-  size_t off_exact;   // [B*Hq][M][256] int32
+  size_t off_exact;   // [B*Hq][256][M] int32
   size_t off_coarse;  // [B*Hkv*NG][M/16][256][16] x 4 uint16
-  size_t off_meta;    // [B*Hq][4] int32: {sum of subspace minima, shift, 0, 0}
+  size_t off_meta;    // [B*Hq][4] int32: {sum of subspace minima, shift, sum of subspace maxima, 0}
   size_t total;
 };
 __host__ __device__ inline LutLayout lut_layout(int B, int Hq, int Hkv, int M) {

@@ -97,25 +97,86 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
 // Scoring primitives
 // ------------------------------------------------------------------------------------------
 
-// Exact score of one token for one head from the head's [m][c] table in LDS (random c -> random
-// banks; a [c][m] order would put every lane of a read on the same two banks).
+// Exact score of one token for one head.  The head's table sits in LDS with one 256-byte row per
+// centroid id c; the 4-byte entry of subspace m is at byte m << 2 of the row (M = 32), or, for
+// M = 16, twice: at m << 2 and at 64 + (m << 2).  LDS serves a 4-byte read 32 lanes at a time.
+// Lane L visits the subspaces of its row in the order m = t ^ (L & 15) within a 16-byte half row,
+// and lanes 16..31 of each half-wave use the second copy (M = 16) or take the two half rows in the
+// other order (M = 32): the 32 lanes served together then touch 32 different banks whatever the
+// code bytes are (a [m][c] table would spread them at random: ~3.5 lanes on the busiest bank).
+// The visiting order does not change the result because the scores are integer sums.
+constexpr int kExactLdsBytes = kCentroids * 256;
+
+template <int M, int NT>
+__device__ __forceinline__ void load_exact_table(const int32_t* __restrict__ head_table, unsigned char* tbl) {
+  const int4* src = (const int4*)head_table;   // [256 c][M] int32
+#pragma unroll 4
+  for (int e = threadIdx.x; e < kCentroids * M / 4; e += NT) {
+    const int c = e / (M / 4), mq = e % (M / 4);
+    const int4 v = src[e];
+    *(int4*)(tbl + (c << 8) + (mq << 4)) = v;
+    if (M == 16) *(int4*)(tbl + (c << 8) + 64 + (mq << 4)) = v;
+  }
+}
+
 template <int M>
-__device__ __forceinline__ int32_t score_exact(const uint32_t (&w)[M / 4], const int32_t* lut1) {
+struct ExactSwizzle {
+  uint32_t mc[M / 4];   // byte t&3 of mc[t>>2]: low address byte for step t of this lane
+  uint32_t sel[4];      // v_perm selectors: address byte 1 <- code byte (k ^ b), byte 0 <- mc byte k
+  bool swap1, swap2;    // dword index inside a half row is XORed with (rho >> 2)
+  bool swaph;           // M = 32: this lane takes the two half rows in the other order
+  __device__ __forceinline__ void init(int lane) {
+    const uint32_t rho = lane & 15, b = rho & 3, hi = (lane >> 4) & 1;
+#pragma unroll
+    for (int d = 0; d < M / 4; ++d) {
+      uint32_t v = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t t = 4 * d + k;
+        const uint32_t m_low = (t ^ rho) & 15u, half = t >> 4;
+        const uint32_t byte = M == 16 ? ((hi << 6) | (m_low << 2)) : ((((half ^ hi) << 4) | m_low) << 2);
+        v |= byte << (8 * k);
+      }
+      mc[d] = v;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) sel[k] = 0x0c0c0000u | ((4u + ((uint32_t)k ^ b)) << 8) | (uint32_t)k;
+    swap1 = (rho >> 2) & 1;
+    swap2 = (rho >> 3) & 1;
+    swaph = M == 32 && hi;
+  }
+};
+
+template <int M>
+__device__ __forceinline__ int32_t score_exact(const uint4 (&w)[M / 16], const unsigned char* tbl,
+                                               const ExactSwizzle<M>& sw) {
   int32_t s = 0;
 #pragma unroll
-  for (int i = 0; i < M; ++i) s += lut1[i * kCentroids + ((w[i >> 2] >> (8 * (i & 3))) & 0xffu)];
+  for (int qd = 0; qd < M / 16; ++qd) {
+    uint4 h = w[qd];
+    if (M == 32) {
+      const uint4 o = w[(M / 16 - 1) - qd];
+      h = make_uint4(sw.swaph ? o.x : h.x, sw.swaph ? o.y : h.y, sw.swaph ? o.z : h.z, sw.swaph ? o.w : h.w);
+    }
+    const uint32_t x0 = sw.swap1 ? h.y : h.x, x1 = sw.swap1 ? h.x : h.y;
+    const uint32_t x2 = sw.swap1 ? h.w : h.z, x3 = sw.swap1 ? h.z : h.w;
+    const uint32_t z[4] = {sw.swap2 ? x2 : x0, sw.swap2 ? x3 : x1, sw.swap2 ? x0 : x2, sw.swap2 ? x1 : x3};
+#pragma unroll
+    for (int t = 0; t < 16; ++t) {
+      const uint32_t off = __builtin_amdgcn_perm(z[t >> 2], sw.mc[qd * 4 + (t >> 2)], sw.sel[t & 3]);
+      s += *(const int32_t*)(tbl + off);
+    }
+  }
   return s;
 }
 
 template <int M>
-__device__ __forceinline__ int32_t score_exact_row(const uint8_t* row, const int32_t* lut1) {
-  uint32_t w[M / 4];
+__device__ __forceinline__ int32_t score_exact_row(const uint8_t* row, const unsigned char* tbl,
+                                                   const ExactSwizzle<M>& sw) {
+  uint4 w[M / 16];
 #pragma unroll
-  for (int qd = 0; qd < M / 16; ++qd) {
-    const uint4 v = *(const uint4*)(row + qd * 16);
-    w[4 * qd] = v.x; w[4 * qd + 1] = v.y; w[4 * qd + 2] = v.z; w[4 * qd + 3] = v.w;
-  }
-  return score_exact<M>(w, lut1);
+  for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(row + qd * 16);
+  return score_exact<M>(w, tbl, sw);
 }
 
 // Coarse scores of one token for the four heads of a group.  The coarse table sits in LDS with
@@ -254,51 +315,32 @@ struct ExactLds {
   uint32_t wave_a[kExactThreads / 64];
   uint32_t wave_b[kExactThreads / 64];
   uint32_t res[2];
-  int32_t sub_min[32], sub_max[32];
 };
 
-// Exact top-K for one head by the whole workgroup.  `head_table` is the head's [m][c] table in
-// global memory, `lut1` kCentroids*M words of LDS.  Writes out_idx[0..kk) ascending (and
-// out_score); the caller has written the count and the -1 padding.  Requires sr.kk >= 1.
+// Exact top-K for one head by the whole workgroup.  `head_table` is the head's [c][m] table in
+// global memory, `meta` its four table constants, `tbl` kExactLdsBytes of LDS.  Writes
+// out_idx[0..kk) ascending (and out_score); the caller has written the count and the -1 padding.
+// Requires sr.kk >= 1.
 template <int M>
 __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
-                                   const int32_t* __restrict__ head_table, float scale,
+                                   const int32_t* __restrict__ head_table,
+                                   const int32_t* __restrict__ meta, float scale,
                                    const SeqRange& sr, int32_t* __restrict__ out_idx,
-                                   float* __restrict__ out_score, int32_t* lut1, ExactLds& L) {
+                                   float* __restrict__ out_score, unsigned char* tbl, ExactLds& L) {
   constexpr int NT = kExactThreads;
   const int tid = threadIdx.x;
-  __syncthreads();   // lut1 may alias LDS the caller was still reading
-  for (int e = tid; e < kCentroids * M / 4; e += NT) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
-  if (tid < 32) {
-    L.sub_min[tid] = INT32_MAX;
-    L.sub_max[tid] = INT32_MIN;
-  }
+  const int32_t s_lo = meta[0], s_hi = meta[2];   // bounds of any score
+  ExactSwizzle<M> sw;
+  sw.init(tid & 63);
+  __syncthreads();   // tbl may alias LDS the caller was still reading
+  load_exact_table<M, NT>(head_table, tbl);
   __syncthreads();
 
   const int lo = sr.sink_end, hi = sr.win_start;
   uint32_t kth = 0, k_rem = (uint32_t)sr.kk;
   if (sr.kk < sr.ncand) {
-    // Bounds of any score (sum of per-subspace minima / maxima): radix digits are taken from
-    // key - key(lower bound), so that the histogram bins spread over the occupied range
-    // instead of all keys sharing their leading bits.
-    for (int e = tid; e < kCentroids * M; e += NT) {   // e = m * 256 + c: a wave covers one m
-      int32_t mn = lut1[e], mx = mn;
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) {
-        mn = min(mn, __shfl_xor(mn, off));
-        mx = max(mx, __shfl_xor(mx, off));
-      }
-      if ((tid & 63) == 0) {
-        atomicMin(&L.sub_min[e / kCentroids], mn);
-        atomicMax(&L.sub_max[e / kCentroids], mx);
-      }
-    }
-    __syncthreads();
-    int32_t s_lo = 0, s_hi = 0;
-    for (int m = 0; m < M; ++m) {
-      s_lo += L.sub_min[m];
-      s_hi += L.sub_max[m];
-    }
+    // Radix digits are taken from key - key(lower bound of any score), so that the histogram bins
+    // spread over the occupied range instead of all keys sharing their leading bits.
     const uint32_t k_lo = score_key(s_lo);
     int remaining = 32 - __clz(score_key(s_hi) - k_lo);   // significant bits of a relative key
     uint32_t prefix = 0, mask = 0;
@@ -310,7 +352,7 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       __syncthreads();
       for (int j = lo + tid; j < hi; j += NT) {
-        const uint32_t key = score_key(score_exact_row<M>(seq_codes + (size_t)j * M, lut1)) - k_lo;
+        const uint32_t key = score_key(score_exact_row<M>(seq_codes + (size_t)j * M, tbl, sw)) - k_lo;
         if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
       }
       __syncthreads();
@@ -334,7 +376,7 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
     int32_t s = 0;
     uint32_t gt = 0, eq = 0;
     if (j < hi) {
-      s = score_exact_row<M>(seq_codes + (size_t)j * M, lut1);
+      s = score_exact_row<M>(seq_codes + (size_t)j * M, tbl, sw);
       const uint32_t key = score_key(s);
       gt = take_all ? 1u : (key > kth ? 1u : 0u);
       eq = take_all ? 0u : (key == kth ? 1u : 0u);
@@ -376,8 +418,8 @@ __global__ __launch_bounds__(kExactThreads) void select_exact_kernel(
   if (sr.kk == 0) return;
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
   exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M,
-                        lut + lay.off_exact + (size_t)bh * (kCentroids * M), lut_scale[bh], sr, oi, os,
-                        (int32_t*)dyn_lds, L);
+                        lut + lay.off_exact + (size_t)bh * (kCentroids * M), lut + lay.off_meta + (size_t)bh * 4,
+                        lut_scale[bh], sr, oi, os, dyn_lds, L);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -389,19 +431,20 @@ __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
     float* __restrict__ scores_out, int B, int Hq, int Hkv, int ctx_len, int64_t ctx_stride) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  int32_t* lut1 = (int32_t*)dyn_lds;
+  unsigned char* tbl = dyn_lds;
   const int bh = blockIdx.y, b = bh / Hq, h = bh % Hq;
   const int G = Hq / Hkv, kv = h / G;
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
-  const int32_t* head_table = lut + lay.off_exact + (size_t)bh * (kCentroids * M);
-  for (int e = threadIdx.x; e < kCentroids * M / 4; e += kStreamThreads) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
+  load_exact_table<M, kStreamThreads>(lut + lay.off_exact + (size_t)bh * (kCentroids * M), tbl);
+  ExactSwizzle<M> sw;
+  sw.init(threadIdx.x & 63);
   __syncthreads();
   int n = seq_lens ? seq_lens[b] : ctx_len;
   n = n < 0 ? 0 : (n > ctx_len ? ctx_len : n);
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
   const float sc = lut_scale[bh];
   for (int j = blockIdx.x * kStreamThreads + threadIdx.x; j < n; j += gridDim.x * kStreamThreads)
-    scores_out[(size_t)bh * ctx_stride + j] = (float)score_exact_row<M>(seq_codes + (size_t)j * M, lut1) * sc;
+    scores_out[(size_t)bh * ctx_stride + j] = (float)score_exact_row<M>(seq_codes + (size_t)j * M, tbl, sw) * sc;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -715,8 +758,8 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
 
   // LDS carve-up: the head's exact table, survivor keys and positions
-  int32_t* lut1 = (int32_t*)dyn_lds;
-  uint32_t* c_key = (uint32_t*)(lut1 + kCentroids * M);
+  unsigned char* tbl = dyn_lds;
+  uint32_t* c_key = (uint32_t*)(dyn_lds + kExactLdsBytes);
   uint32_t* c_pos = c_key + cap;
 
   // Everything this workgroup needs from global memory before it can look at a survivor is
@@ -734,7 +777,9 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
   const int32_t m_base = meta[0], m_shift = meta[1], m_top = meta[2];
   const long proof_bound = (long)m_base + (((long)tc - 1 + M) << m_shift);
-  for (int e = tid; e < kCentroids * M / 4; e += NT) ((int4*)lut1)[e] = ((const int4*)head_table)[e];
+  load_exact_table<M, NT>(head_table, tbl);
+  ExactSwizzle<M> sw;
+  sw.init(tid & 63);
   for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
   if (tid == 0) {
     s_overflow = 0;
@@ -757,7 +802,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   __syncthreads();
   if (s_overflow || n_c > (uint32_t)cap || n_c < (uint32_t)sr.kk) {
     if (tid == 0) route[bh] = s_overflow ? 3u : (n_c > (uint32_t)cap ? 2u : 1u);   // diagnostics only
-    exact_select_block<M>(seq_codes, head_table, scale, sr, oi, os, lut1, L);
+    exact_select_block<M>(seq_codes, head_table, meta, scale, sr, oi, os, tbl, L);
     return;
   }
 
@@ -813,13 +858,10 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
 #pragma unroll 2
     for (uint32_t i = tid; i < n_c; i += NT) {
       const uint4* e = codes0 + min(c_key[i], last_q);
-      uint32_t w[M / 4];
+      uint4 w[M / 16];
 #pragma unroll
-      for (int qd = 0; qd < M / 16; ++qd) {
-        const uint4 v = e[qd];
-        w[4 * qd] = v.x; w[4 * qd + 1] = v.y; w[4 * qd + 2] = v.z; w[4 * qd + 3] = v.w;
-      }
-      const uint32_t key = max(score_key(score_exact<M>(w, lut1)), klo) - klo;
+      for (int qd = 0; qd < M / 16; ++qd) w[qd] = e[qd];
+      const uint32_t key = max(score_key(score_exact<M>(w, tbl, sw)), klo) - klo;
       c_key[i] = key;
       atomicAdd(&L.hist[min(key >> shift1, (uint32_t)kHistBins - 1)], 1u);
     }
@@ -883,7 +925,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     const long kth_score = (long)key_score(kth + kmin);
     if (tc != INT32_MIN && kth_score < proof_bound) {
       if (tid == 0) route[bh] = 4u;
-      exact_select_block<M>(seq_codes, head_table, scale, sr, oi, os, lut1, L);
+      exact_select_block<M>(seq_codes, head_table, meta, scale, sr, oi, os, tbl, L);
       return;
     }
     if (tid == 0) route[bh] = 0u;
@@ -958,7 +1000,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   const int B = d.batch, Hq = d.n_q_heads, Hkv = d.n_kv_heads, NG = plan.NG;
   const int heads = B * Hq, problems = B * Hkv * NG;
   const size_t coarse_bytes = (size_t)kCoarseLdsBytes;
-  const size_t lut1_bytes = (size_t)kCentroids * M * sizeof(int32_t);
+  const size_t lut1_bytes = kExactLdsBytes;
   hipError_t err;
   static size_t s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_final[16];
   if (heads == 0) return hipSuccess;

@@ -57,7 +57,8 @@ def lut_as_float(st, wl: synth.Workload) -> np.ndarray:
     """Exact part of the library table -> [B,Hq,M,L] float64 (dequantised), for comparison with the
     oracle's table."""
     n = wl.batch * wl.n_q_heads * wl.n_sub * 256
-    t = st.lut[:n].cpu().numpy().reshape(wl.batch, wl.n_q_heads, wl.n_sub, 256).astype(np.float64)
+    t = st.lut[:n].cpu().numpy().reshape(wl.batch, wl.n_q_heads, 256, wl.n_sub).astype(np.float64)
+    t = np.ascontiguousarray(t.transpose(0, 1, 3, 2))   # library order is [c][m]
     return t * st.lut_scale.cpu().numpy().astype(np.float64)[:, :, None, None]
 
 
@@ -69,7 +70,7 @@ def coarse_table_consistent(st, wl: synth.Workload) -> bool:
     lut = st.lut.cpu().numpy()
     n_exact = Bn * Hq * M * 256
     n_coarse = Bn * Hkv * NG * 256 * M * 2
-    exact = lut[:n_exact].reshape(Bn, Hq, M, 256).astype(np.int64)
+    exact = lut[:n_exact].reshape(Bn, Hq, 256, M).astype(np.int64).transpose(0, 1, 3, 2)   # -> [B,Hq,m,c]
     coarse = lut[n_exact:n_exact + n_coarse].view(np.uint16).reshape(Bn, Hkv, NG, M // 16, 256, 16, 4).astype(np.int64)
     meta = lut[n_exact + n_coarse:n_exact + n_coarse + Bn * Hq * 4].reshape(Bn, Hq, 4).astype(np.int64)
     for h in range(Hq):
