@@ -521,7 +521,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
   }
   __syncthreads();
   // Rank search, one wave per head: lane l owns bins [32 l, 32 l + 32); a suffix scan over the
-  // lanes finds the one whose range holds the r_p-th largest sample, and that lane walks its bins.
+  // lanes finds the one whose range holds the r_p-th largest sample; the wave then searches that range.
   if (wv < kHeadsPerGroup) {
     const int r = wv;
     const int hg = g4 * kHeadsPerGroup + r;
@@ -540,21 +540,25 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
       if (lane + off < 64) inc += o;
     }
     const uint32_t k = (uint32_t)r_p, above_lane = inc - sum;
-    if (above_lane < k && k <= inc && hg < G) {
-      uint32_t run = above_lane;
-      int bin = 32 * lane;
-      for (int i = 31; i >= 0; --i) {
-        const uint32_t c = (hrow[32 * lane + i] >> fsh) & 0xffffu;
-        if (run + c >= k) {
-          bin = 32 * lane + i;
-          break;
-        }
-        run += c;
+    const uint64_t owner = __ballot(above_lane < k && k <= inc);   // the lane whose 32 bins hold the rank
+    if (owner != 0 && hg < G) {
+      // Second level, by the whole wave: lane i < 32 takes bin 31 - i of the owner's range (so
+      // bins descend with the lane index) and a prefix sum finds the first lane that reaches k.
+      const int src = __ffsll((unsigned long long)owner) - 1;
+      const uint32_t above = __shfl(above_lane, src);
+      const uint32_t c = lane < 32 ? (hrow[32 * src + 31 - lane] >> fsh) & 0xffffu : 0u;
+      uint32_t incl = c;
+#pragma unroll
+      for (int off = 1; off < 32; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
       }
+      const uint64_t reach = __ballot(lane < 32 && above + incl >= k);
+      const int bin = 32 * src + 31 - (__ffsll((unsigned long long)reach) - 1);
       // Lower edge of the bin holding the r_p-th largest sample (at least r_p samples reach it),
       // lowered by M: a row's coarse score is below its exact score by less than M coarse units,
       // and the final kernel needs that much slack to prove its result complete.
-      thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = max(0, (bin << 5) - M);
+      if (lane == 0) thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = max(0, (bin << 5) - M);
     }
   }
 }

@@ -255,22 +255,56 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   }
 }
 
+// Merge the partial states of a head: 4 groups of 128 threads (one thread per output dimension)
+// each fold every fourth state into a running one -- four states' loads are issued together, so a
+// head with up to 16 workgroups costs one load latency -- then the four are folded through LDS.
+constexpr int kCombineGroups = 4;
 template <typename T>
-__global__ __launch_bounds__(kD) void attn_combine_kernel(const float* __restrict__ partial,
-                                                          T* __restrict__ out, int n_split) {
-  const int bh = blockIdx.x, d = threadIdx.x;
-  const float* pp = partial + (size_t)bh * n_split * (kD + 2);
-  float m = -INFINITY;
-  for (int s = 0; s < n_split; ++s) m = fmaxf(m, pp[s * (kD + 2) + kD]);
-  float l = 0.f, o = 0.f;
-  if (m != -INFINITY) {
-    for (int s = 0; s < n_split; ++s) {
-      const float w = __expf(pp[s * (kD + 2) + kD] - m);
-      l += pp[s * (kD + 2) + kD + 1] * w;
-      o += pp[s * (kD + 2) + d] * w;
+__global__ __launch_bounds__(kCombineGroups* kD) void attn_combine_kernel(const float* __restrict__ partial,
+                                                                         T* __restrict__ out, int n_states) {
+  __shared__ float s_m[kCombineGroups], s_l[kCombineGroups], s_o[kCombineGroups][kD];
+  const int bh = blockIdx.x, d = threadIdx.x % kD, g = threadIdx.x / kD;
+  const float* pp = partial + (size_t)bh * n_states * (kD + 2);
+  float m = -INFINITY, l = 0.f, o = 0.f;
+  constexpr int UN = 4;
+  for (int s0 = g; s0 < n_states; s0 += kCombineGroups * UN) {
+    float pm[UN], pl[UN], po[UN];
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      const int s = min(s0 + u * kCombineGroups, n_states - 1);
+      pm[u] = pp[(size_t)s * (kD + 2) + kD];
+      pl[u] = pp[(size_t)s * (kD + 2) + kD + 1];
+      po[u] = pp[(size_t)s * (kD + 2) + d];
+    }
+#pragma unroll
+    for (int u = 0; u < UN; ++u) {
+      if (s0 + u * kCombineGroups < n_states && pm[u] != -INFINITY) {
+        const float mn = fmaxf(m, pm[u]);
+        const float a = __expf(m - mn), c = __expf(pm[u] - mn);
+        l = l * a + pl[u] * c;
+        o = o * a + po[u] * c;
+        m = mn;
+      }
     }
   }
-  store_elem(out + (size_t)bh * kD + d, l > 0.f ? o / l : 0.f);
+  if (d == 0) { s_m[g] = m; s_l[g] = l; }
+  s_o[g][d] = o;
+  __syncthreads();
+  if (g == 0) {
+    float mm = s_m[0];
+#pragma unroll
+    for (int i = 1; i < kCombineGroups; ++i) mm = fmaxf(mm, s_m[i]);
+    float lt = 0.f, ot = 0.f;
+    if (mm != -INFINITY) {
+#pragma unroll
+      for (int i = 0; i < kCombineGroups; ++i) {
+        const float w = __expf(s_m[i] - mm);   // exp(-inf) = 0 for an empty group
+        lt += s_l[i] * w;
+        ot += s_o[i][d] * w;
+      }
+    }
+    store_elem(out + (size_t)bh * kD + d, lt > 0.f ? ot / lt : 0.f);
+  }
 }
 
 template <typename T>
@@ -288,8 +322,8 @@ static hipError_t launch_attn_t(const a2ats_dims& d, const AttnPlan& plan, const
                      d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  hipLaunchKernelGGL((attn_combine_kernel<T>), dim3(heads), dim3(kD), 0, stream, (const float*)ws,
-                     (T*)out, parts);
+  hipLaunchKernelGGL((attn_combine_kernel<T>), dim3(heads), dim3(kCombineGroups * kD), 0, stream,
+                     (const float*)ws, (T*)out, parts);
   return hipGetLastError();
 }
 
