@@ -63,6 +63,20 @@ def measured_traffic(workload):
     return None
 
 
+def profiled_kernel_us(workload):
+    """Average duration of the streaming kernel in the committed rocprofv3 --kernel-trace summary of
+    this command (None if there is none): the event pair above also covers the dispatch between
+    two commands, which the profiler's kernel time does not."""
+    path = os.path.join(ROOT, "profiles", f"decode_step_{workload}_kernel_stats.txt")
+    try:
+        for line in open(path):
+            if line.startswith("a2ats::stream_select_kernel"):
+                return float(line.split()[2])
+    except (OSError, ValueError, IndexError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -198,6 +212,7 @@ def main():
     e = 2 if wl.kv_dtype == "bf16" else 4
     attn_bytes = Bn * Hq * min(K, N - w) * 2 * D * e + Bn * Hkv * w * 2 * D * e
     k_us = mean(kern_us)
+    prof_us = profiled_kernel_us(wl.name)
     achieved = kernel_bytes / (k_us * 1e-6) / 1e9 if k_us == k_us else None
 
     out = {
@@ -231,7 +246,9 @@ def main():
         "roofline": {"kernel": "stream_select_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
                      "traffic": measured_traffic(wl.name), "algorithmic_bytes_per_launch": kernel_bytes,
-                     "avg_launch_us": k_us if k_us == k_us else None},
+                     "avg_launch_us": k_us if k_us == k_us else None,
+                     "avg_launch_us_rocprofv3": prof_us,
+                     "frac_rocprofv3": (kernel_bytes / (prof_us * 1e-6) / 1e9 / HBM_PEAK_GBS) if prof_us else None},
     }
 
     if not args.no_cpu_baseline:
