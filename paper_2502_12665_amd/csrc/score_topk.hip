@@ -254,13 +254,18 @@ __device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const uns
 // Called by all lanes of a wave for NH consecutive heads starting at `head0` (heads at or past
 // `n_valid` get 65536, which no coarse score reaches): lane 8 r + p loads part p of head r, so
 // the P0 <= 8 values of all heads arrive with one load latency instead of one after another.
+// Split in two so that a caller can put its other loads between the request and the use.
 template <int NH>
-__device__ __forceinline__ void combined_thresholds(const int32_t* __restrict__ thr, size_t head0,
-                                                    int n_valid, int P0, int32_t (&T)[NH]) {
+__device__ __forceinline__ int32_t request_thresholds(const int32_t* __restrict__ thr, size_t head0,
+                                                      int n_valid, int P0) {
   static_assert(NH * 8 <= 64, "one lane per (head, part)");
   const int lane = threadIdx.x & 63, r = lane >> 3, p = lane & 7;
   int32_t v = 0;
   if (r < NH && r < n_valid && p < P0) v = thr[(head0 + r) * P0 + p];
+  return v;
+}
+template <int NH>
+__device__ __forceinline__ void combine_thresholds(int32_t v, int n_valid, int P0, int32_t (&T)[NH]) {
   int32_t all_rows = v == INT32_MIN ? 1 : 0;
   int32_t sum = all_rows ? 0 : v;   // thresholds are >= 0 and below 2^16
 #pragma unroll
@@ -593,8 +598,10 @@ __device__ __forceinline__ void stream_select_body(
   // Every (problem, chunk, wave) owns one survivor segment in HBM: no atomics, no contention.
   const size_t seg = ((size_t)prob * n_chunks + chunk) * kStreamWaves + wv;
   uint32_t* my_meta = seg_meta + seg * kSegMeta;
+  // thresholds of the group's heads: requested here, combined after the table copy has been issued
+  const int32_t thr_lane = request_thresholds<4>(thr, (size_t)b * Hq + kv * G + g4 * kHeadsPerGroup,
+                                                G - g4 * kHeadsPerGroup, P0);
   int32_t T[4];   // padded heads never want a row
-  combined_thresholds<4>(thr, (size_t)b * Hq + kv * G + g4 * kHeadsPerGroup, G - g4 * kHeadsPerGroup, P0, T);
   // The scoring loop addresses the table by absolute LDS address (it must start at 0, which holds
   // because this kernel has no static LDS).  Should a toolchain ever place it elsewhere, publish
   // an overflowing segment instead: the final kernel then takes the exact route.
@@ -681,6 +688,7 @@ __device__ __forceinline__ void stream_select_body(
     // (Every wave of the workgroup reaches the barrier, also one whose row range is empty.)
     if (has_rows) load_rows((int)wbegin, rows_a);
     load_coarse_table<M, NT>(lut, lut_layout(B, Hq, Hkv, M), prob, tbl);
+    combine_thresholds<4>(thr_lane, G - g4 * kHeadsPerGroup, P0, T);
     __syncthreads();
 #pragma unroll 1
     for (int base = (int)wbegin; base < wend; base += 2 * STEP) {
@@ -775,13 +783,14 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     seg_rows = mt[0];
     my_cnt = mt[1 + r];
   }
-  int32_t tc1[1];
-  combined_thresholds<1>(thr, (size_t)bh, 1, P0, tc1);
-  const int32_t tc = tc1[0];
+  const int32_t thr_lane = request_thresholds<1>(thr, (size_t)bh, 1, P0);
   const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
   const int32_t m_base = meta[0], m_shift = meta[1], m_top = meta[2];
-  const long proof_bound = (long)m_base + (((long)tc - 1 + M) << m_shift);
   load_exact_table<M, NT>(head_table, tbl);
+  int32_t tc1[1];
+  combine_thresholds<1>(thr_lane, 1, P0, tc1);
+  const int32_t tc = tc1[0];
+  const long proof_bound = (long)m_base + (((long)tc - 1 + M) << m_shift);
   ExactSwizzle<M> sw;
   sw.init(tid & 63);
   for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
