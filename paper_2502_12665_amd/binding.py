@@ -20,7 +20,8 @@ W_NONE, W_DIAG, W_BLOCK = 0, 1, 2
 OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN = 0, 1, 2, 3
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
-           "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel"]
+           "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel",
+           "a2ats_decode_prologue"]
 
 
 class A2atsError(RuntimeError):
@@ -61,6 +62,9 @@ def lib() -> ctypes.CDLL:
         L.a2ats_encode_keys.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, sz, vp]
         L.a2ats_build_lut.restype = ctypes.c_int
         L.a2ats_build_lut.argtypes = [dp, vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
+        L.a2ats_decode_prologue.restype = ctypes.c_int
+        L.a2ats_decode_prologue.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp,
+                                            vp, vp, vp, vp, vp]
         L.a2ats_score_topk.restype = ctypes.c_int
         L.a2ats_score_topk.argtypes = [dp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.a2ats_sparse_attn.restype = ctypes.c_int
@@ -149,6 +153,16 @@ def build_lut(dims: Dims, q, cos_b, sin_b, codebook, q_rot, lut, lut_scale):
     rc = lib().a2ats_build_lut(ctypes.byref(dims), _ptr(q), _dtype_code(q), _ptr(cos_b), _ptr(sin_b),
                                _ptr(codebook), _ptr(q_rot), _ptr(lut), _ptr(lut_scale), _stream())
     _check(rc, "a2ats_build_lut")
+
+
+def decode_prologue(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, weight_mode: int, codes,
+                    q, cos_b, sin_b, q_rot, lut, lut_scale):
+    """encode_keys (n_new <= 32) and build_lut in one launch."""
+    rc = lib().a2ats_decode_prologue(ctypes.byref(dims), _ptr(keys), n_new, pos0, _ptr(codebook),
+                                     _ptr(weights), weight_mode, _ptr(codes), _ptr(q), _dtype_code(q),
+                                     _ptr(cos_b), _ptr(sin_b), _ptr(q_rot), _ptr(lut), _ptr(lut_scale),
+                                     _stream())
+    _check(rc, "a2ats_decode_prologue")
 
 
 def score_topk(dims: Dims, codes, lut, lut_scale, top_k: int, window: int, n_sink: int, seq_lens,

@@ -122,6 +122,28 @@ int a2ats_build_lut(const a2ats_dims* d, const void* q, int q_dtype, const float
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
+int a2ats_decode_prologue(const a2ats_dims* d, const float* keys, int32_t n_new, int32_t pos0,
+                          const float* codebook, const float* weights, int weight_mode, uint8_t* codes,
+                          const void* q, int q_dtype, const float* cos_b, const float* sin_b, float* q_rot,
+                          int32_t* lut, float* lut_scale, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE && weight_mode != A2ATS_W_DIAG && weight_mode != A2ATS_W_BLOCK)
+    return A2ATS_ERR_INVALID_ARG;
+  if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
+  if (!codebook || !q || !cos_b || !sin_b || !q_rot || !lut || !lut_scale) return A2ATS_ERR_INVALID_ARG;
+  if (n_new > 0 && (!keys || !codes)) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE && !weights) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(codebook) || misaligned16(lut) || (n_new > 0 && misaligned16(keys)))
+    return A2ATS_ERR_INVALID_ARG;
+  if (n_new > 32) return A2ATS_ERR_UNSUPPORTED;   // prefill-sized batches go through a2ats_encode_keys
+  const hipError_t e = a2ats::launch_decode_prologue(*d, keys, n_new, pos0, codebook, weights, weight_mode,
+                                                     codes, q, q_dtype, cos_b, sin_b, q_rot, lut, lut_scale,
+                                                     (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
 int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut, const float* lut_scale,
                      int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
                      int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,

@@ -11,16 +11,17 @@
 // relate them (sum of the per-subspace minima, shift, sum of the per-subspace maxima).
 #include "common.hpp"
 #include "internal.hpp"
+#include "encode_few.hpp"
 
 namespace a2ats {
 
 constexpr int kLutThreads = 1024;
 
 template <int DS, bool QBF16>
-__global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
-    const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
-    const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
-    float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG) {
+__device__ __forceinline__ void build_lut_body(
+    int prob, const void* __restrict__ q_in, const float* __restrict__ cos_b,
+    const float* __restrict__ sin_b, const float* __restrict__ codebook, float* __restrict__ q_rot,
+    int32_t* __restrict__ lut, float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG) {
   constexpr int D = 128, HALF = 64, M = D / DS;
   constexpr int ENTRIES = kCentroids * M;
   constexpr int EPT = ENTRIES / kLutThreads;
@@ -32,7 +33,6 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
   __shared__ int32_t s_shift[kHeadsPerGroup];
 
   const int G = Hq / Hkv;
-  const int prob = blockIdx.x;
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int tid = threadIdx.x;
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
@@ -198,6 +198,39 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
   }
 }
 
+template <int DS, bool QBF16>
+__global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
+    const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
+    const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
+    float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG) {
+  build_lut_body<DS, QBF16>(blockIdx.x, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG);
+}
+
+// Decode prologue in one launch: the first n_lut workgroups build the tables of the current query,
+// the others encode the few keys appended this step, four (key, subspace) pairs per workgroup.
+// The two halves touch disjoint data.
+template <int DS, bool QBF16>
+__global__ __launch_bounds__(kLutThreads) void decode_prologue_kernel(
+    const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
+    const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
+    float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG, int n_lut,
+    const float* __restrict__ keys, const float* __restrict__ weights, int mode,
+    uint8_t* __restrict__ codes, int n_new, int pos0, int64_t ctx_stride) {
+  constexpr int M = 128 / DS;
+  if ((int)blockIdx.x < n_lut) {
+    build_lut_body<DS, QBF16>(blockIdx.x, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG);
+    return;
+  }
+  __shared__ double s_d[kLutThreads / 64];
+  __shared__ int s_i[kLutThreads / 64];
+  const int grp = threadIdx.x >> 8, c = threadIdx.x & 255;
+  const long pair = (long)(blockIdx.x - n_lut) * (kLutThreads / kCentroids) + grp;
+  const long n_pairs = (long)B * Hkv * n_new * M;
+  const int m = (int)(pair % M), j = (int)((pair / M) % n_new), bkv = (int)(pair / ((long)M * n_new));
+  encode_few_pair<DS>(keys, codebook, weights, mode, codes, Hkv, M, n_new, pos0, ctx_stride, m, j, bkv, c,
+                      grp, pair < n_pairs, s_d, s_i);
+}
+
 hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                             const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
                             float* lut_scale, hipStream_t stream) {
@@ -214,6 +247,30 @@ hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, con
     if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUT(4, true); else A2ATS_LAUNCH_LUT(4, false);
   }
 #undef A2ATS_LAUNCH_LUT
+  return hipGetLastError();
+}
+
+hipError_t launch_decode_prologue(const a2ats_dims& d, const float* keys, int n_new, int pos0,
+                                  const float* codebook, const float* weights, int mode, uint8_t* codes,
+                                  const void* q, int q_dtype, const float* cos_b, const float* sin_b,
+                                  float* q_rot, int32_t* lut, float* lut_scale, hipStream_t stream) {
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const int NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
+  const int n_lut = d.batch * d.n_kv_heads * NG;
+  const long n_pairs = (long)d.batch * d.n_kv_heads * n_new * d.n_sub;
+  const int per_wg = kLutThreads / kCentroids;
+  const dim3 grid(n_lut + (unsigned)((n_pairs + per_wg - 1) / per_wg)), block(kLutThreads);
+  if (grid.x == 0) return hipSuccess;
+#define A2ATS_LAUNCH_PRO(DS, BF)                                                                       \
+  hipLaunchKernelGGL((decode_prologue_kernel<DS, BF>), grid, block, 0, stream, q, cos_b, sin_b, codebook, \
+                     q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG, n_lut, keys, weights, \
+                     mode, codes, n_new, pos0, d.ctx_stride)
+  if (d.sub_dim == 8) {
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_PRO(8, true); else A2ATS_LAUNCH_PRO(8, false);
+  } else {
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_PRO(4, true); else A2ATS_LAUNCH_PRO(4, false);
+  }
+#undef A2ATS_LAUNCH_PRO
   return hipGetLastError();
 }
 

@@ -15,6 +15,7 @@
 // emitted code is the float64 argmin.
 #include "common.hpp"
 #include "internal.hpp"
+#include "encode_few.hpp"
 
 namespace a2ats {
 
@@ -156,65 +157,18 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(
 }
 
 // Append-time shape (a few new keys per sequence, e.g. one per decode step): the prefill kernel
-// would run one thread per key with 256 serial distance evaluations.  Here one workgroup takes a
-// (key, subspace) pair, one thread per centroid evaluates the distortion straight from the
-// definition in float64, and a block argmin picks the winner, lowest index on ties.
+// would run one thread per key with 256 serial distance evaluations; here a workgroup of 256
+// threads takes one (key, subspace) pair (see encode_few.hpp).
 template <int DS>
 __global__ __launch_bounds__(kCentroids) void encode_few_kernel(
     const float* __restrict__ keys, const float* __restrict__ codebook,
     const float* __restrict__ weights, int mode, uint8_t* __restrict__ codes, int Hkv, int M,
     int n_new, int pos0, int64_t ctx_stride) {
-  constexpr int D = 128;
-  __shared__ double s_d[kCentroids / 64];
-  __shared__ int s_i[kCentroids / 64];
-  const int m = blockIdx.x, j = blockIdx.y, bkv = blockIdx.z, kv = bkv % Hkv;
-  const int c = threadIdx.x, blk = kv * M + m;
-  const float* kp = keys + ((size_t)bkv * n_new + j) * D + m * DS;
-  const float* cw = codebook + ((size_t)blk * kCentroids + c) * DS;
-  double dv[DS];
-#pragma unroll
-  for (int t = 0; t < DS; ++t) dv[t] = (double)kp[t] - (double)cw[t];
-  double dist = 0.0;
-  if (mode == A2ATS_W_NONE) {
-#pragma unroll
-    for (int t = 0; t < DS; ++t) dist += dv[t] * dv[t];
-  } else if (mode == A2ATS_W_DIAG) {
-    const float* hw = weights + (size_t)kv * D + m * DS;
-#pragma unroll
-    for (int t = 0; t < DS; ++t) dist += dv[t] * (double)hw[t] * dv[t];
-  } else {
-    const float* H = weights + (size_t)blk * DS * DS;
-#pragma unroll
-    for (int r = 0; r < DS; ++r)
-#pragma unroll
-      for (int cc = 0; cc < DS; ++cc) dist += dv[r] * (double)H[r * DS + cc] * dv[cc];
-  }
-  int idx = c;
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const double od = __shfl_xor(dist, off);
-    const int oi = __shfl_xor(idx, off);
-    if (od < dist || (od == dist && oi < idx)) {
-      dist = od;
-      idx = oi;
-    }
-  }
-  if ((c & 63) == 0) {
-    s_d[c >> 6] = dist;
-    s_i[c >> 6] = idx;
-  }
-  __syncthreads();
-  if (c == 0) {
-    for (int w = 1; w < kCentroids / 64; ++w)
-      if (s_d[w] < dist || (s_d[w] == dist && s_i[w] < idx)) {
-        dist = s_d[w];
-        idx = s_i[w];
-      }
-    codes[((size_t)bkv * ctx_stride + pos0 + j) * M + m] = (uint8_t)idx;
-  }
+  __shared__ double s_d[4];
+  __shared__ int s_i[4];
+  encode_few_pair<DS>(keys, codebook, weights, mode, codes, Hkv, M, n_new, pos0, ctx_stride, blockIdx.x,
+                      blockIdx.y, blockIdx.z, threadIdx.x, 0, true, s_d, s_i);
 }
-
-constexpr int kFewKeys = 32;   // at or below this many new keys per sequence the append-time kernel runs
 
 template <int DS>
 static hipError_t launch_encode_ds(const a2ats_dims& d, const float* keys, int n_new, int pos0,

@@ -307,6 +307,38 @@ def test_config5_encode_then_decode(oracle):
         H.log(f"  decode on encoded keys (b={b}, kv={kv}): {res}")
 
 
+@pytest.mark.parametrize("name,n_new,mode", [("c1_tiny", 1, "none"), ("c2_llama8b_32k", 1, "diag"),
+                                             ("c5_qwen7b_64k", 3, "block")])
+def test_decode_prologue_equals_the_two_calls(name, n_new, mode):
+    """The fused prologue (append-time encode + table build in one launch) must write bit for bit
+    what a2ats_encode_keys and a2ats_build_lut write."""
+    wl = synth.WORKLOADS[name].replace(batch=min(synth.WORKLOADS[name].batch, 4), ctx_len=4096)
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    hm = synth.make_query_second_moment(wl)
+    wmode = {"none": B.W_NONE, "diag": B.W_DIAG, "block": B.W_BLOCK}[mode]
+    weights = None if mode == "none" else hm["h_diag" if mode == "diag" else "h_block"].cuda()
+    keys = synth.make_encode_keys(wl, n_new, device="cuda", stress=True)
+    dims = H.dims_of(wl)
+    pos0 = wl.ctx_len - n_new
+    res = []
+    for fused in (False, True):
+        st = B.DecodeState(dims, wl.top_k, wl.window, 0, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+        st.lut.fill_(-1)
+        codes = xd["codes"].clone()
+        if fused:
+            B.decode_prologue(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, xd["q"],
+                              st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale)
+        else:
+            ws = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+            B.encode_keys(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, ws)
+            B.build_lut(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, st.lut, st.lut_scale)
+        torch.cuda.synchronize()
+        res.append((codes.cpu(), st.lut.cpu(), st.lut_scale.cpu(), st.q_rot.cpu()))
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    assert not torch.equal(res[0][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the rows were rewritten
+
+
 def _routes(wl, xd, n_sink=0):
     """Run tables + score/top-K alone and return (survivors per head, route per head)."""
     dims = H.dims_of(wl, xd["codes"].shape[2])
