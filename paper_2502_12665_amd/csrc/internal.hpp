@@ -15,6 +15,7 @@ struct TopkPlan {
   bool fast;            // sampled threshold + one streaming pass (else: exact route only)
   int NG;               // head groups of 4 per KV head
   int P0;               // sampling workgroups per (sequence, KV head, head group)
+  int sample_rows;      // rows each of them scores
   int chunks;           // streaming workgroups per (sequence, KV head, head group)
   int rows_per_chunk;
   int cap;              // survivor capacity per head in the final kernel's LDS

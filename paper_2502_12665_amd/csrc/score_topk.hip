@@ -50,10 +50,15 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
   p.cap = 8192;
   p.fast = ncand >= 16384 && top_k >= 1 && top_k <= 2048 && 4L * top_k <= ncand;
   if (p.fast) {
+    // Sample a sixteenth of the candidates, in units of kSampleRows, shared by at most 8
+    // workgroups: up to 8 * kSampleRows each workgroup scores kSampleRows rows, beyond that (very
+    // long contexts, where a small sample would put the 5-sigma threshold far too low and the
+    // survivor lists would outgrow the final kernel's LDS) each takes an eighth of the sample.
     long s_tot = ncand / 16 / kSampleRows * kSampleRows;
     if (s_tot < kSampleRows) s_tot = kSampleRows;
-    if (s_tot > 8 * kSampleRows) s_tot = 8 * kSampleRows;
-    p.P0 = (int)(s_tot / kSampleRows);
+    if (s_tot > 64 * kSampleRows) s_tot = 64 * kSampleRows;
+    p.P0 = (int)std::min<long>(8, s_tot / kSampleRows);
+    p.sample_rows = (int)(s_tot / p.P0);   // at most 8192: the histogram counts are 16 bits wide
     const long problems = (long)d.batch * d.n_kv_heads * p.NG;
     long chunks = (512 + problems - 1) / problems;
     const long max_chunks = (ncand + 2047) / 2048;
@@ -459,11 +464,12 @@ template <int M>
 __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int B, int Hq, int Hkv, int NG,
-    int P0, int problems, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink) {
+    int P0, int sample_rows, int problems, int ctx_len, int64_t ctx_stride, int top_k, int window,
+    int n_sink) {
   constexpr int NT = kSampleThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   unsigned char* tbl = dyn_lds;
-  __shared__ uint32_t s_hist[2][kHistBins];   // two heads per word, 16-bit counts (<= 1024 each)
+  __shared__ uint32_t s_hist[2][kHistBins];   // two heads per word, 16-bit counts (a workgroup scores at most 8192 rows)
 
   int p, prob;
   xcd_map(blockIdx.x, P0, problems, prob, p);
@@ -472,7 +478,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
 
   // sampling plan for this sequence
-  const int s_p = min(kSampleRows, sr.ncand / P0);
+  const int s_p = min(sample_rows, sr.ncand / P0);
   const long s_all = (long)s_p * P0;
   int r_p = 0;
   bool take_all = sr.ncand <= top_k || s_p == 0;
@@ -1043,8 +1049,8 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
 
   if ((err = allow_dynamic_lds(sample_threshold_kernel<M>, coarse_bytes, s_sample)) != hipSuccess) return err;
   hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0 * problems), dim3(kSampleThreads),
-                     coarse_bytes, stream, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, plan.P0, problems,
-                     d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                     coarse_bytes, stream, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, plan.P0, plan.sample_rows,
+                     problems, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
   auto stream_kernel = M == 16 ? stream_select_kernel16 : stream_select_kernel32;

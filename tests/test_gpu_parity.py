@@ -339,6 +339,23 @@ def test_decode_prologue_equals_the_two_calls(name, n_new, mode):
     assert not torch.equal(res[0][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the rows were rewritten
 
 
+@pytest.mark.parametrize("top_k,expect_fast", [(2048, True), (4096, False)])
+def test_maximum_context_length_and_top_k(oracle, top_k, expect_fast):
+    """The largest context the library accepts (2^20 tokens) with the largest K of the streaming
+    route (2048) and the largest K of all (4096, exact route), whole step against the oracle."""
+    wl = synth.Workload(f"max_ctx_K{top_k}", 1, 4, 1, 128, 16, 1 << 20, top_k, 256, n_sink=4, seed=9)
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl)
+    H.log(f"  {res}")
+    assert res["excluded"] <= res["slots"] // 1000
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    surv, route = _routes(wl, xd, n_sink=4)
+    if expect_fast:
+        assert (route == 0).all() and surv.max() <= 4 * top_k
+    else:
+        assert (surv == 0x0FFFFFFF).all()   # the exact-only route reports no survivor lists
+
+
 def _routes(wl, xd, n_sink=0):
     """Run tables + score/top-K alone and return (survivors per head, route per head)."""
     dims = H.dims_of(wl, xd["codes"].shape[2])
