@@ -27,6 +27,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <cmath>
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -66,17 +67,22 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     if (chunks < 1) chunks = 1;
     if (chunks > 64) chunks = 64;
     // One survivor segment per (problem, chunk, wave) of the streaming pass: a header and row_cap
-    // row entries.  A row survives if any of the (up to) four heads wants it; with a threshold
-    // that lets about 2.5 K rows per head through that is at most 4 * 2.5 * K / ncand of the rows;
-    // row_cap is 1.5 times that share of a wave's rows.  Ranks inside a segment are stored in 10
-    // bits, so the context is cut into more chunks until row_cap fits 1024.
-    const double keep = std::min(1.0, 4.0 * 2.5 * top_k / (double)ncand);
+    // row entries.  The sampling rule (rank r with r - 5 sqrt(r) >= K S / N, plus one per part) lets
+    // about r N / S rows per head through -- for small K much more than K -- and a row survives if
+    // any of the (up to) four heads wants it.  row_cap is that share of a wave's rows with a margin
+    // for the spread of the estimate and for the Poisson scatter between segments.  Ranks inside a
+    // segment are stored in 10 bits, so the context is cut into more chunks until row_cap fits 1024.
+    const double r0 = (double)top_k * (double)s_tot / (double)ncand;
+    const double xr = 0.5 * (kSigma + std::sqrt(kSigma * kSigma + 4.0 * r0));
+    const double survivors = (xr * xr + 2.0 * p.P0) / (double)s_tot * (double)ncand * 1.25;
+    const double keep = std::min(1.0, 4.0 * survivors / (double)ncand);
     long rpc, cap_rows;
     for (;; ++chunks) {
       rpc = (ncand + chunks - 1) / chunks;
       rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
       const long rows_per_wave = rpc / kStreamWaves;
-      cap_rows = (long)(rows_per_wave * keep * 1.5) + 32;
+      const double mu = rows_per_wave * keep;
+      cap_rows = (long)(mu * 1.25 + 8.0 * std::sqrt(mu)) + 32;
       cap_rows = (cap_rows + 31) / 32 * 32;
       if (cap_rows < 64) cap_rows = 64;
       if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;   // rows_per_wave is a multiple of 64

@@ -388,6 +388,26 @@ def test_fast_route_is_taken_and_fallback_triggers():
     assert (route != 0).all(), route
 
 
+def test_streaming_route_serves_a_grid_of_shapes():
+    """Over a grid of context lengths, K and head layouts the streaming route must serve every head
+    (the planner's segment and sample sizes must follow from the shape, not from one workload)."""
+    bad = []
+    for N, K, (Bn, Hq, Hkv, M) in itertools.product((16700, 100000, 600000), (1, 256, 2048),
+                                                    ((1, 4, 1, 16), (2, 14, 2, 32), (8, 32, 8, 16))):
+        if 4 * K > N - 64:
+            continue
+        wl = synth.Workload("grid", Bn, Hq, Hkv, 128, M, N, K, 64, seed=N + K)
+        xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+        surv, route = _routes(wl, xd)
+        H.log(f"N={N} K={K} B{Bn} Hq{Hq} Hkv{Hkv} M{M}: survivors mean {surv.mean():.0f} max {surv.max()} "
+              f"routes {np.bincount(route.ravel(), minlength=5)}")
+        if (route != 0).any() or surv.max() > 8192:
+            bad.append((N, K, Bn, Hq, Hkv, M))
+        del xd
+        torch.cuda.empty_cache()
+    assert not bad, bad
+
+
 def test_decode_step_in_a_hip_graph():
     """A captured decode step must replay to the eager result every time, with eager work and
     synchronisations between the replays."""
