@@ -180,7 +180,7 @@ int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, co
   if (misaligned16(k_cache) || misaligned16(v_cache) || misaligned16(cos_win) || misaligned16(sin_win))
     return A2ATS_ERR_INVALID_ARG;
   const a2ats::AttnPlan plan = a2ats::make_attn_plan(*d, top_k, window, n_sink);
-  if (!ws || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
+  if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
   const hipError_t e = a2ats::launch_sparse_attn(*d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx,
                                                  topk_count, top_k, window, n_sink, cos_win, sin_win,
                                                  seq_lens, out, ws, (hipStream_t)stream);
