@@ -69,8 +69,9 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     // One survivor segment per (problem, chunk, wave) of the streaming pass: a header and row_cap
     // row entries.  The sampling rule (rank r with r - 5 sqrt(r) >= K S / N, plus one per part) lets
     // about r N / S rows per head through -- for small K much more than K -- and a row survives if
-    // any of the (up to) four heads wants it.  row_cap is that share of a wave's rows with a margin
-    // for the spread of the estimate and for the Poisson scatter between segments.  Ranks inside a
+    // any of the (up to) four heads wants it.  row_cap is twice that share of a wave's rows plus 16
+    // standard deviations of a Poisson count: survivors that come in runs (neighbouring tokens with
+    // similar scores) scatter far more between segments than independent ones.  Ranks inside a
     // segment are stored in 10 bits, so the context is cut into more chunks until row_cap fits 1024.
     const double r0 = (double)top_k * (double)s_tot / (double)ncand;
     const double xr = 0.5 * (kSigma + std::sqrt(kSigma * kSigma + 4.0 * r0));
@@ -82,7 +83,7 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
       rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
       const long rows_per_wave = rpc / kStreamWaves;
       const double mu = rows_per_wave * keep;
-      cap_rows = (long)(mu * 1.25 + 8.0 * std::sqrt(mu)) + 32;
+      cap_rows = (long)(mu * 2.0 + 16.0 * std::sqrt(mu)) + 64;   // generous: unused capacity costs only scratch
       cap_rows = (cap_rows + 31) / 32 * 32;
       if (cap_rows < 64) cap_rows = 64;
       if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;   // rows_per_wave is a multiple of 64
