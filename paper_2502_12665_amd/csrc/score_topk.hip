@@ -10,20 +10,23 @@
 //
 //  fast route (long contexts): the code matrix is streamed from HBM once, against a 16-bit
 //  coarse copy of the tables, and only the survivors are scored exactly.
-//    1. sample_threshold_kernel scores a strided sample of each sequence (about 1/16 of it) with
-//       the coarse tables and derives, per head, a coarse threshold below the K-th score with a
-//       5-sigma margin (distribution-free: it only uses ranks of the sample).
+//    1. sample_threshold_kernel scores a sample of each sequence (about 1/16 of it, taken in
+//       128-byte runs spread evenly over the candidates) with the coarse tables and derives, per
+//       head, a coarse threshold below the K-th score with a 5-sigma margin (distribution-free
+//       for independent rows: it only uses ranks of the sample).
 //    2. stream_select_kernel streams all code rows: one 8-byte LDS read per code byte serves the
 //       four heads of a group (two heads per 32-bit word, 16 bits each, so one integer add
-//       accumulates two heads).  Rows whose coarse score reaches the threshold are written, with
-//       their code bytes, to a per-(head, chunk, wave) segment in HBM (about 2K per head).
-//    3. final_select_kernel (one workgroup per head) scores the survivors exactly from the
-//       head's 32-bit table, radix-selects the exact K-th key among them, proves that no row
-//       outside the survivor list can reach that key (coarse and exact scores differ by less
-//       than M coarse units), and writes the winners in ascending position.  If the proof fails
-//       or a list is too short / overflowed -- possible only when the sample misled (about 1e-6
-//       per head) or for degenerate inputs -- the workgroup runs the exact route for its head,
-//       so the result is always exact with respect to the 32-bit scores.
+//       accumulates two heads).  A row whose coarse score reaches the threshold of any of the
+//       heads is written once -- an 8-byte header (position, wanting heads, rank per head) and
+//       its code bytes -- to the segment of its (problem, chunk, wave) in HBM.
+//    3. final_select_kernel (one workgroup per head) collects its head's survivors (about 1.7 K),
+//       scores them exactly from the head's 32-bit table, radix-selects the exact K-th key among
+//       them, proves that no row outside the survivor list can reach that key (coarse and exact
+//       scores differ by less than M coarse units), and writes the winners in ascending
+//       position.  If the proof fails or a list is too short / too long / overflowed -- the
+//       sample misled (about 1e-6 per head for independent rows, more when similar rows come in
+//       runs) or the input is degenerate -- the workgroup runs the exact route for its head, so
+//       the result is always exact with respect to the 32-bit scores.
 #include <math.h>
 
 #include <algorithm>
