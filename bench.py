@@ -77,6 +77,48 @@ def profiled_kernel_us(workload):
     return None
 
 
+def encode_prefill(args, torch, B, synth):
+    """Prefill side: a2ats_encode_keys over whole sequences under the per-dimension query-aware
+    distortion.  One step = one call over all keys; the bound is the vector ALU."""
+    wl = synth.WORKLOADS["c5_qwen7b_64k"].replace(batch=8)
+    N, M = wl.ctx_len, wl.n_sub
+    hm = synth.make_query_second_moment(wl)
+    cb = synth.make_codebook(wl, "cuda")
+    keys = synth.make_encode_keys(wl, N, device="cuda")
+    dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)
+    ws = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+    codes = torch.empty(wl.batch, wl.n_kv_heads, N, M, dtype=torch.uint8, device="cuda")
+    w = hm["h_diag"].cuda()
+    n_keys = wl.batch * wl.n_kv_heads * N
+    steps, warmup = min(args.steps, 8), min(args.warmup, 2)
+    for _ in range(warmup):
+        B.encode_keys(dims, keys, N, 0, cb, w, B.W_DIAG, codes, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.encode_keys(dims, keys, N, 0, cb, w, B.W_DIAG, codes, ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    evals = n_keys * M * 256                       # (key subvector, centroid) distance evaluations
+    # instruction mix of the inner loop (from the kernel's ISA, ds = 4): per evaluation 4 subtract,
+    # 1 multiply + 3 fused multiply-add, compare, select, median-of-3, minimum, 1.25 moves = 13.25
+    # vector instructions; peak issue rate taken as the published 157.3 TFLOP/s / 2 flop per FMA lane
+    ops_per_eval = 13.25
+    peak = 157.3e12 / 2 / 1e12
+    achieved = evals * ops_per_eval / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "encoded keys/s (prefill-side query-aware key encoding, per-dimension weights)",
+        "value": n_keys / (ms * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 distances, f64 re-check of near ties", "data": "synthetic",
+        "config": {"workload": "c5_qwen7b_64k encode, 8 of 32 sequences", "keys": n_keys, "n_sub": M,
+                   "sub_dim": wl.sub_dim, "weights": "W_DIAG"},
+        "roofline": {"kernel": "encode_kernel", "bound": "alu", "achieved": achieved, "peak": peak,
+                     "unit": "T vector lane-instructions/s", "frac": achieved / peak, "traffic": None,
+                     "distance_evaluations_per_s": evals / (ms * 1e-3)},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +135,9 @@ def main():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run 3 plain float32 copies (out = in + 0) of this many MiB, so that a "
                          "rocprofv3 --pmc run of this command holds a kernel of known HBM traffic")
+    ap.add_argument("--encode-prefill", action="store_true",
+                    help="measure the prefill-side key encoder (configuration 5 geometry, 8 of its 32 "
+                         "sequences) instead of the decode step, and print its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -105,6 +150,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.encode_prefill:
+        encode_prefill(args, torch, B, synth)
+        return
     wl = synth.WORKLOADS[args.workload]
     R = max(1, args.replicas)
     dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)
