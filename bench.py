@@ -101,9 +101,10 @@ def encode_prefill(args, torch, B, synth):
     ms = (time.perf_counter() - t0) * 1e3 / steps
     evals = n_keys * M * 256                       # (key subvector, centroid) distance evaluations
     # instruction mix of the inner loop (from the kernel's ISA, ds = 4): per evaluation 4 subtract,
-    # 1 multiply + 3 fused multiply-add, compare, select, median-of-3, minimum, 1.25 moves = 13.25
-    # vector instructions; peak issue rate taken as the published 157.3 TFLOP/s / 2 flop per FMA lane
-    ops_per_eval = 13.25
+    # 1 multiply + 3 fused multiply-add, and + add (index into the low mantissa bits), median-of-3,
+    # minimum = 12 vector instructions; peak issue rate taken as the published 157.3 TFLOP/s / 2 flop
+    # per FMA lane
+    ops_per_eval = 12.0
     peak = 157.3e12 / 2 / 1e12
     achieved = evals * ops_per_eval / (ms * 1e-3) / 1e12
     print(json.dumps({

@@ -106,8 +106,13 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(
 #pragma unroll
   for (int t = 0; t < DS; ++t) zz += z[t] * z[t];
 
-  float b1 = INFINITY, b2 = INFINITY;
-  int arg = 0;
+  // The centroid index rides in the low 8 mantissa bits of the distance.  Distances are >= 0, so
+  // their bit patterns order like the values and the tracking is done on unsigned integers
+  // (no denormal or NaN handling in the way): one minimum tracks the smallest distance together
+  // with its index, the lower index winning among distances equal in the remaining 16 mantissa
+  // bits; anything that close is re-decided in float64 below.
+  uint32_t k1 = 0x7f800000u, k2 = 0x7f800000u;   // +inf
+  const uint32_t keep = 0xffffff00u;
 #pragma unroll 4
   for (int c = 0; c < kCentroids; ++c) {
     float d = 0.f;
@@ -116,10 +121,12 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(
       const float e = z[t] - cp[c * DS + t];
       d += e * e;
     }
-    arg = d < b1 ? c : arg;
-    b2 = __builtin_amdgcn_fmed3f(b1, b2, d);   // with b1 <= b2: the new second smallest
-    b1 = fminf(b1, d);
+    const uint32_t key = (__float_as_uint(d) & keep) | (uint32_t)c;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(k2) : "v"(k1), "v"(k2), "v"(key));   // with k1 <= k2: the new second smallest
+    k1 = min(k1, key);
   }
+  int arg = (int)(k1 & 0xffu);
+  const float b1 = __uint_as_float(k1 & keep), b2 = __uint_as_float(k2 & keep);
 
   // float32 rounding reach of a distance: a few ulp of (|z| + |c|)^2-sized terms
   const float tol = 1e-4f * b2 + 4e-6f * zz + 1e-30f;
