@@ -202,9 +202,10 @@ int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window
 
 /*
  * Profiling aid (not part of the method): when both events are non-NULL, the next
- * a2ats_score_topk calls record ev_start / ev_stop (hipEvent_t passed as void*) on their
- * stream immediately around the code-streaming kernel, so a caller can time that kernel
- * alone.  Pass NULLs to switch it off.  Process-global, not thread-safe.
+ * a2ats_score_topk calls attach ev_start / ev_stop (hipEvent_t passed as void*) to the
+ * dispatch of the code-streaming kernel on their stream, so that the elapsed time between
+ * them is that kernel's own duration.  Pass NULLs to switch it off.  Process-global, not
+ * thread-safe.
  */
 void a2ats_profile_stream_kernel(void* ev_start, void* ev_stop);
 

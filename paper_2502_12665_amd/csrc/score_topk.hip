@@ -27,6 +27,7 @@
 //       sample misled (about 1e-6 per head for independent rows, more when similar rows come in
 //       runs) or the input is degenerate -- the workgroup runs the exact route for its head, so
 //       the result is always exact with respect to the 32-bit scores.
+#include <hip/hip_ext.h>
 #include <math.h>
 
 #include <algorithm>
@@ -1065,12 +1066,18 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
 
   auto stream_kernel = M == 16 ? stream_select_kernel16 : stream_select_kernel32;
   if ((err = allow_dynamic_lds(stream_kernel, coarse_bytes, s_stream)) != hipSuccess) return err;
-  if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_start, stream);
-  hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
-                     stream, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, plan.P0,
-                     plan.chunks, problems, plan.rows_per_chunk, plan.row_cap, d.ctx_len, d.ctx_stride,
-                     top_k, window, n_sink);
-  if (g_ev_start && g_ev_stop) (void)hipEventRecord(g_ev_stop, stream);
+  if (g_ev_start && g_ev_stop) {
+    // events attached to the dispatch itself: their difference is the kernel's own duration
+    hipExtLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
+                          stream, g_ev_start, g_ev_stop, 0, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq,
+                          Hkv, NG, plan.P0, plan.chunks, problems, plan.rows_per_chunk, plan.row_cap,
+                          d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+  } else {
+    hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
+                       stream, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, plan.P0,
+                       plan.chunks, problems, plan.rows_per_chunk, plan.row_cap, d.ctx_len, d.ctx_stride,
+                       top_k, window, n_sink);
+  }
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
   const size_t final_lds = lut1_bytes + (size_t)plan.cap * 8;
