@@ -2,6 +2,8 @@
 // the launch functions the C ABI layer calls.
 #pragma once
 
+#include <atomic>
+
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -38,14 +40,16 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
 
 // Raise a kernel's dynamic-LDS limit (needed above 64 KB).  The attribute is sticky, so it is set
 // once per kernel and device; `slot` (16 entries, one per device) caches the largest size set.
+// (Threads racing on a slot at worst set the same attribute twice.)
+typedef std::atomic<size_t> LdsSlot;
 template <typename K>
-inline hipError_t allow_dynamic_lds(K kernel, size_t bytes, size_t* slot) {
+inline hipError_t allow_dynamic_lds(K kernel, size_t bytes, LdsSlot* slot) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
-  if (slot[dev] >= bytes) return hipSuccess;
+  if (slot[dev].load(std::memory_order_acquire) >= bytes) return hipSuccess;
   const hipError_t e =
       hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-  if (e == hipSuccess) slot[dev] = bytes;
+  if (e == hipSuccess) slot[dev].store(bytes, std::memory_order_release);
   return e;
 }
 

@@ -1032,7 +1032,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   const size_t coarse_bytes = (size_t)kCoarseLdsBytes;
   const size_t lut1_bytes = kExactLdsBytes;
   hipError_t err;
-  static size_t s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_final[16];
+  static LdsSlot s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_final[16];
   if (heads == 0) return hipSuccess;
 
   if (scores_out) {
