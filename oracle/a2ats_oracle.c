@@ -16,7 +16,9 @@
  * Layout conventions (row-major, last index fastest):
  *   q, out        [B, Hq, D]
  *   codebook      [Hkv, M, L, ds]     (M*ds == D; subspace m covers dims m*ds .. m*ds+ds-1)
- *   codes         [B, Hkv, S, M]      uint8, S = token-axis capacity >= N
+ *   codes         [B, Hkv, S, M]      uint8 (code_bytes == 1) or uint16 (code_bytes == 2, for codebooks
+ *                                     of more than 256 codewords: section 5.1 uses 4096 per head with
+ *                                     M == 1), S = token-axis capacity >= N
  *   k, v          [B, Hkv, S, D]
  *   scores        [B, Hq, N]
  *   topk_idx      [B, Hq, K]          ascending token index, unused slots = -1
@@ -43,6 +45,14 @@
 #ifdef _OPENMP
 #include <omp.h>
 #endif
+
+static inline int code_at(const void *codes, int64_t i, int code_bytes) {
+  return code_bytes == 2 ? (int)((const uint16_t *)codes)[i] : (int)((const uint8_t *)codes)[i];
+}
+static inline void code_put(void *codes, int64_t i, int code_bytes, int c) {
+  if (code_bytes == 2) ((uint16_t *)codes)[i] = (uint16_t)c;
+  else ((uint8_t *)codes)[i] = (uint8_t)c;
+}
 
 int a2ats_oracle_threads(void) {
 #ifdef _OPENMP
@@ -80,8 +90,8 @@ int a2ats_oracle_rope(const float *x, int64_t rows, int D, const double *inv_fre
  * k^_j = concat_m codebook[kv, m, codes[j, m], :] and take the D-term dot
  * product with the WRoPE query q~ (q_rot, float64, [B,Hq,D]).
  * ------------------------------------------------------------------------- */
-int a2ats_oracle_scores_explicit(const double *q_rot, const float *codebook, const uint8_t *codes,
-                                 int B, int Hq, int Hkv, int M, int L, int ds, int64_t N,
+int a2ats_oracle_scores_explicit(const double *q_rot, const float *codebook, const void *codes,
+                                 int code_bytes, int B, int Hq, int Hkv, int M, int L, int ds, int64_t N,
                                  int64_t S, double *scores) {
   int D = M * ds, G = Hq / Hkv;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
@@ -91,9 +101,9 @@ int a2ats_oracle_scores_explicit(const double *q_rot, const float *codebook, con
       const double *qr = q_rot + ((int64_t)b * Hq + h) * D;
       double *khat = (double *)malloc(sizeof(double) * D);
       for (int64_t j = 0; j < N; ++j) {
-        const uint8_t *row = codes + (((int64_t)b * Hkv + kv) * S + j) * M;
+        const int64_t row = (((int64_t)b * Hkv + kv) * S + j) * M;
         for (int m = 0; m < M; ++m) {
-          const float *c = codebook + (((int64_t)kv * M + m) * L + row[m]) * ds;
+          const float *c = codebook + (((int64_t)kv * M + m) * L + code_at(codes, row + m, code_bytes)) * ds;
           for (int t = 0; t < ds; ++t) khat[m * ds + t] = (double)c[t];
         }
         double u = 0.0;
@@ -129,8 +139,8 @@ int a2ats_oracle_lut(const double *q_rot, const float *codebook, int B, int Hq, 
   return 0;
 }
 
-int a2ats_oracle_scores_lut(const double *lut, const uint8_t *codes, int B, int Hq, int Hkv, int M,
-                            int L, int64_t N, int64_t S, double *scores) {
+int a2ats_oracle_scores_lut(const double *lut, const void *codes, int code_bytes, int B, int Hq,
+                            int Hkv, int M, int L, int64_t N, int64_t S, double *scores) {
   int G = Hq / Hkv;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
   for (int b = 0; b < B; ++b)
@@ -138,9 +148,9 @@ int a2ats_oracle_scores_lut(const double *lut, const uint8_t *codes, int B, int 
       int kv = h / G;
       const double *t = lut + ((int64_t)b * Hq + h) * M * L;
       for (int64_t j = 0; j < N; ++j) {
-        const uint8_t *row = codes + (((int64_t)b * Hkv + kv) * S + j) * M;
+        const int64_t row = (((int64_t)b * Hkv + kv) * S + j) * M;
         double u = 0.0;
-        for (int m = 0; m < M; ++m) u += t[(int64_t)m * L + row[m]];
+        for (int m = 0; m < M; ++m) u += t[(int64_t)m * L + code_at(codes, row + m, code_bytes)];
         scores[((int64_t)b * Hq + h) * N + j] = u;
       }
     }
@@ -334,13 +344,14 @@ static double quad_form(const double *d, const float *Hm, int ds, int mode) {
 }
 
 int a2ats_oracle_encode(const float *keys, const float *codebook, const float *weights, int mode,
-                        int B, int Hkv, int64_t n, int M, int L, int ds, uint8_t *codes,
+                        int B, int Hkv, int64_t n, int M, int L, int ds, void *codes, int code_bytes,
                         double *best, double *second) {
   int D = M * ds;
+  if (ds > 128) return -2;
 #pragma omp parallel for collapse(2) schedule(dynamic, 1)
   for (int b = 0; b < B; ++b)
     for (int kv = 0; kv < Hkv; ++kv) {
-      double d[64];
+      double d[128];
       for (int64_t j = 0; j < n; ++j) {
         const float *key = keys + (((int64_t)b * Hkv + kv) * n + j) * D;
         for (int m = 0; m < M; ++m) {
@@ -362,7 +373,7 @@ int a2ats_oracle_encode(const float *keys, const float *codebook, const float *w
             }
           }
           int64_t o = (((int64_t)b * Hkv + kv) * n + j) * M + m;
-          codes[o] = (uint8_t)arg;
+          code_put(codes, o, code_bytes, arg);
           if (best) best[o] = b1;
           if (second) second[o] = b2;
         }
@@ -377,14 +388,15 @@ int a2ats_oracle_encode(const float *keys, const float *codebook, const float *w
  * weights is the block form [Hkv, M, ds, ds].  Returns -1 if a block is not
  * positive definite. */
 int a2ats_oracle_encode_cholesky(const float *keys, const float *codebook, const float *weights,
-                                 int B, int Hkv, int64_t n, int M, int L, int ds, uint8_t *codes) {
+                                 int B, int Hkv, int64_t n, int M, int L, int ds, void *codes,
+                                 int code_bytes, double *best, double *second) {
   int D = M * ds;
   int bad = 0;
+  if (ds > 128) return -2;
   for (int kv = 0; kv < Hkv; ++kv)
     for (int m = 0; m < M; ++m) {
       const float *Hm = weights + ((int64_t)kv * M + m) * ds * ds;
-      double Lc[64 * 64];
-      memset(Lc, 0, sizeof(double) * ds * ds);
+      double *Lc = (double *)calloc((size_t)ds * ds, sizeof(double));
       for (int r = 0; r < ds; ++r)
         for (int c = 0; c <= r; ++c) {
           double s = (double)Hm[r * ds + c];
@@ -409,13 +421,13 @@ int a2ats_oracle_encode_cholesky(const float *keys, const float *codebook, const
       for (int b = 0; b < B; ++b)
         for (int64_t j = 0; j < n; ++j) {
           const float *key = keys + (((int64_t)b * Hkv + kv) * n + j) * D + m * ds;
-          double z[64];
+          double z[128];
           for (int t = 0; t < ds; ++t) {
             double s = 0.0;
             for (int r = 0; r < ds; ++r) s += (double)key[r] * Lc[r * ds + t];
             z[t] = s;
           }
-          double b1 = INFINITY;
+          double b1 = INFINITY, b2 = INFINITY;
           int arg = 0;
           for (int c = 0; c < L; ++c) {
             double dist = 0.0;
@@ -424,13 +436,20 @@ int a2ats_oracle_encode_cholesky(const float *keys, const float *codebook, const
               dist += e * e;
             }
             if (dist < b1) {
+              b2 = b1;
               b1 = dist;
               arg = c;
+            } else if (dist < b2) {
+              b2 = dist;
             }
           }
-          codes[(((int64_t)b * Hkv + kv) * n + j) * M + m] = (uint8_t)arg;
+          int64_t o = (((int64_t)b * Hkv + kv) * n + j) * M + m;
+          code_put(codes, o, code_bytes, arg);
+          if (best) best[o] = b1;
+          if (second) second[o] = b2;
         }
       free(cz);
+      free(Lc);
     }
   return bad ? -1 : 0;
 }

@@ -58,6 +58,17 @@ def _f64(x) -> np.ndarray:
     return np.ascontiguousarray(x, dtype=np.float64)
 
 
+def _codes(x) -> np.ndarray:
+    """Codes as a contiguous uint8 or uint16 array (uint16 for codebooks of more than 256 codewords)."""
+    if hasattr(x, "detach"):
+        import torch
+        x = x.detach().to("cpu")
+        x = x.view(torch.int16).numpy().view(np.uint16) if x.dtype in (torch.int16, torch.uint16) else x.numpy()
+    x = np.asarray(x)
+    assert x.dtype in (np.uint8, np.uint16), x.dtype
+    return np.ascontiguousarray(x)
+
+
 def _u8(x) -> np.ndarray:
     if hasattr(x, "detach"):
         x = x.detach().to("cpu").numpy()
@@ -107,24 +118,24 @@ def scores_explicit(q_rot, codebook, codes, n_ctx: int) -> np.ndarray:
     """[B,Hq,N] approximate scores q~ . k^_j by explicit reconstruction."""
     q_rot = _f64(q_rot)
     cb = _f32(codebook)
-    codes = _u8(codes)
+    codes = _codes(codes)
     B, Hq, D = q_rot.shape
     Hkv, M, L, ds = cb.shape
     S = codes.shape[2]
     assert codes.shape == (B, Hkv, S, M) and n_ctx <= S
     out = np.empty((B, Hq, n_ctx), dtype=np.float64)
-    _load().a2ats_oracle_scores_explicit(_p(q_rot), _p(cb), _p(codes), _I(B), _I(Hq), _I(Hkv), _I(M),
+    _load().a2ats_oracle_scores_explicit(_p(q_rot), _p(cb), _p(codes), _I(codes.itemsize), _I(B), _I(Hq), _I(Hkv), _I(M),
                                          _I(L), _I(ds), _L(n_ctx), _L(S), _p(out))
     return out
 
 
 def scores_lut(lut_, codes, n_kv_heads: int, n_ctx: int) -> np.ndarray:
     lut_ = _f64(lut_)
-    codes = _u8(codes)
+    codes = _codes(codes)
     B, Hq, M, L = lut_.shape
     S = codes.shape[2]
     out = np.empty((B, Hq, n_ctx), dtype=np.float64)
-    _load().a2ats_oracle_scores_lut(_p(lut_), _p(codes), _I(B), _I(Hq), _I(n_kv_heads), _I(M), _I(L),
+    _load().a2ats_oracle_scores_lut(_p(lut_), _p(codes), _I(codes.itemsize), _I(B), _I(Hq), _I(n_kv_heads), _I(M), _I(L),
                                     _L(n_ctx), _L(S), _p(out))
     return out
 
@@ -182,23 +193,28 @@ def encode(keys, codebook, weights=None, mode: int = W_NONE, want_margins: bool 
     _, M, L, ds = cb.shape
     w = None if weights is None else _f32(weights)
     assert mode == W_NONE or w is not None
-    codes = np.empty((B, Hkv, n, M), dtype=np.uint8)
+    codes = np.empty((B, Hkv, n, M), dtype=np.uint8 if L <= 256 else np.uint16)
     best = np.empty((B, Hkv, n, M), dtype=np.float64) if want_margins else None
     second = np.empty((B, Hkv, n, M), dtype=np.float64) if want_margins else None
-    _load().a2ats_oracle_encode(_p(keys), _p(cb), _p(w), _I(mode), _I(B), _I(Hkv), _L(n), _I(M), _I(L),
-                                _I(ds), _p(codes), _p(best), _p(second))
+    rc = _load().a2ats_oracle_encode(_p(keys), _p(cb), _p(w), _I(mode), _I(B), _I(Hkv), _L(n), _I(M), _I(L),
+                                     _I(ds), _p(codes), _I(codes.itemsize), _p(best), _p(second))
+    assert rc == 0, rc
     if want_margins:
         return codes, best, second
     return codes
 
 
-def encode_cholesky(keys, codebook, h_block) -> np.ndarray:
+def encode_cholesky(keys, codebook, h_block, want_margins: bool = False):
     keys, cb, w = _f32(keys), _f32(codebook), _f32(h_block)
     B, Hkv, n, D = keys.shape
     _, M, L, ds = cb.shape
-    codes = np.empty((B, Hkv, n, M), dtype=np.uint8)
+    codes = np.empty((B, Hkv, n, M), dtype=np.uint8 if L <= 256 else np.uint16)
+    best = np.empty((B, Hkv, n, M), dtype=np.float64) if want_margins else None
+    second = np.empty((B, Hkv, n, M), dtype=np.float64) if want_margins else None
     rc = _load().a2ats_oracle_encode_cholesky(_p(keys), _p(cb), _p(w), _I(B), _I(Hkv), _L(n), _I(M),
-                                              _I(L), _I(ds), _p(codes))
+                                              _I(L), _I(ds), _p(codes), _I(codes.itemsize), _p(best), _p(second))
     if rc != 0:
         raise ValueError("weight block is not positive definite")
+    if want_margins:
+        return codes, best, second
     return codes

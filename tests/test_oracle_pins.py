@@ -390,3 +390,59 @@ def test_query_aware_assignment_lowers_weighted_distortion(oracle):
     qs = rng.standard_normal((200000, wl.sub_dim)) @ Lc.T            # E[q^T q] = H
     d = kk[0, 0, 0, 0] - cbd[0, 0][aware[0, 0, 0, 0]]
     np.testing.assert_allclose(np.mean((qs @ d) ** 2), d @ Hb[0, 0] @ d, rtol=0.02)
+
+
+# ---------------------------------------------------------------------------
+# The paper's own geometry (section 5.1): one codebook of 4096 codewords per head over all D
+# dimensions (M = 1), 16-bit codes, and the full D x D quadratic form of section 4.2.
+# ---------------------------------------------------------------------------
+def _single_codebook_case(seed, n_keys, Bn=1, Hkv=2, G=2, L=4096, D=128):
+    g = torch.Generator().manual_seed(seed)
+    cb = torch.randn(Hkv, 1, L, D, generator=g)
+    codes = torch.randint(0, L, (Bn, Hkv, n_keys, 1), generator=g).to(torch.int32).numpy().astype(np.uint16)
+    q_rot = torch.randn(Bn, Hkv * G, D, generator=g, dtype=torch.float64).numpy()
+    A = torch.randn(Hkv, D, D, generator=g, dtype=torch.float64)
+    H = (A @ A.transpose(1, 2) / D + 0.05 * torch.eye(D, dtype=torch.float64)).to(torch.float32)
+    return cb, codes, q_rot, H.reshape(Hkv, 1, D, D)
+
+
+def test_single_codebook_scores_with_16_bit_codes(oracle):
+    cb, codes, q_rot, _ = _single_codebook_case(11, 300)
+    assert codes.max() > 255   # the 16-bit path is exercised
+    ex = oracle.scores_explicit(q_rot, cb, codes, 300)
+    lut = oracle.lut(q_rot, cb, q_rot.shape[1])
+    via = oracle.scores_lut(lut, codes, cb.shape[0], 300)
+    # numpy: u_j = q~ . C[code_j], the paper's eq. "attention weights approximation"
+    want = np.empty_like(ex)
+    for h in range(q_rot.shape[1]):
+        kv = h // 2
+        want[0, h] = cb[kv, 0].double().numpy()[codes[0, kv, :, 0].astype(np.int64)] @ q_rot[0, h]
+    np.testing.assert_allclose(ex, want, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(via, want, rtol=1e-12, atol=1e-12)
+    # with one codeword per score there are at most L distinct scores per head: massive exact ties
+    assert len(np.unique(via[0, 0])) <= 4096
+
+
+def test_single_codebook_encode_full_quadratic_form(oracle):
+    cb, _, _, H = _single_codebook_case(12, 1)
+    g = torch.Generator().manual_seed(13)
+    keys = torch.randn(1, 2, 6, 128, generator=g)
+    # (a) H = I: the nearest codeword by torch.cdist
+    codes = oracle.encode(keys, cb)
+    assert codes.dtype == np.uint16
+    want = torch.cdist(keys.double(), cb[:, 0].double()[None]).argmin(dim=-1).numpy()
+    np.testing.assert_array_equal(codes[..., 0], want)
+    # (b) the full quadratic form (k - c) H (k - c)^T by numpy einsum, == the Cholesky route
+    cq, b1, b2 = oracle.encode(keys, cb, H, oracle.W_BLOCK, want_margins=True)
+    d = keys.double().numpy()[:, :, :, None, :] - cb[:, 0].double().numpy()[None, :, None, :, :]
+    dist = np.einsum("bknld,kde,bknle->bknl", d, H[:, 0].double().numpy(), d)
+    np.testing.assert_array_equal(cq[..., 0], dist.argmin(axis=-1))
+    np.testing.assert_allclose(b1[..., 0], dist.min(axis=-1), rtol=1e-10)
+    cc, c1, c2 = oracle.encode_cholesky(keys, cb, H, want_margins=True)
+    np.testing.assert_array_equal(cc, cq)
+    np.testing.assert_allclose(c1, b1, rtol=1e-9)
+    np.testing.assert_allclose(c2, b2, rtol=1e-9)
+    # (c) a key that is a codeword with an index above 255 gets that index
+    keys2 = cb[:, 0, [300, 4095]].reshape(1, 2, 2, 128).clone()
+    got = oracle.encode(keys2, cb, H, oracle.W_BLOCK)
+    np.testing.assert_array_equal(got[0, :, :, 0], np.array([[300, 4095], [300, 4095]]))
