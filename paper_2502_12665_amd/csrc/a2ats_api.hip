@@ -17,8 +17,11 @@ int check_dims(const a2ats_dims* d) {
   if (d->n_q_heads % d->n_kv_heads != 0) return A2ATS_ERR_INVALID_ARG;
   if ((int64_t)d->n_sub * d->sub_dim != d->head_dim) return A2ATS_ERR_INVALID_ARG;
   if (d->ctx_stride < d->ctx_len) return A2ATS_ERR_INVALID_ARG;
-  if (d->head_dim != 128 || d->n_centroids != 256) return A2ATS_ERR_UNSUPPORTED;
-  if (d->sub_dim != 4 && d->sub_dim != 8) return A2ATS_ERR_UNSUPPORTED;
+  if (d->head_dim != 128) return A2ATS_ERR_UNSUPPORTED;
+  if (!a2ats::single_codebook(*d)) {
+    if (d->n_centroids != 256) return A2ATS_ERR_UNSUPPORTED;
+    if (d->sub_dim != 4 && d->sub_dim != 8) return A2ATS_ERR_UNSUPPORTED;
+  }
   if (d->n_q_heads / d->n_kv_heads > 8) return A2ATS_ERR_UNSUPPORTED;
   if (d->ctx_len > (1 << 20)) return A2ATS_ERR_UNSUPPORTED;
   return A2ATS_OK;
@@ -45,6 +48,7 @@ const char* a2ats_status_string(int status) {
 
 size_t a2ats_lut_elems(const a2ats_dims* d) {
   if (check_dims(d) != A2ATS_OK) return 0;
+  if (a2ats::single_codebook(*d)) return (size_t)d->batch * d->n_q_heads * 4096;
   return a2ats::lut_layout(d->batch, d->n_q_heads, d->n_kv_heads, d->n_sub).total;
 }
 
@@ -55,6 +59,7 @@ size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t
     case A2ATS_OP_LUT: return 0;
     case A2ATS_OP_SCORE_TOPK: {
       if (top_k < 0 || window < 0) return (size_t)-1;
+      if (a2ats::single_codebook(*d)) return 0;
       // the plan does not depend on n_sink except through the candidate count; size for 0 sinks
       const a2ats::TopkPlan p = a2ats::make_topk_plan(*d, top_k, window, 0);
       return p.fast ? p.bytes : 0;
@@ -105,6 +110,7 @@ int a2ats_encode_keys(const a2ats_dims* d, const float* keys, int32_t n_new, int
     if (ws_bytes < a2ats::encode_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
   }
   if ((int64_t)n_new > 65535LL * 256) return A2ATS_ERR_UNSUPPORTED;
+  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
   const hipError_t e = a2ats::launch_encode(*d, keys, n_new, pos0, codebook, weights, weight_mode, codes,
                                             weight_mode != A2ATS_W_NONE ? ws : nullptr, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
@@ -117,8 +123,12 @@ int a2ats_build_lut(const a2ats_dims* d, const void* q, int q_dtype, const float
   if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
   if (!q || !cos_b || !sin_b || !codebook || !q_rot || !lut || !lut_scale) return A2ATS_ERR_INVALID_ARG;
   if (misaligned16(codebook) || misaligned16(lut)) return A2ATS_ERR_INVALID_ARG;
-  const hipError_t e = a2ats::launch_build_lut(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut,
-                                               lut_scale, (hipStream_t)stream);
+  const hipError_t e =
+      a2ats::single_codebook(*d)
+          ? a2ats::launch_build_lut_single(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
+                                           (hipStream_t)stream)
+          : a2ats::launch_build_lut(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
+                                    (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
@@ -138,6 +148,7 @@ int a2ats_decode_prologue(const a2ats_dims* d, const float* keys, int32_t n_new,
   if (misaligned16(codebook) || misaligned16(lut) || (n_new > 0 && misaligned16(keys)))
     return A2ATS_ERR_INVALID_ARG;
   if (n_new > 32) return A2ATS_ERR_UNSUPPORTED;   // prefill-sized batches go through a2ats_encode_keys
+  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
   const hipError_t e = a2ats::launch_decode_prologue(*d, keys, n_new, pos0, codebook, weights, weight_mode,
                                                      codes, q, q_dtype, cos_b, sin_b, q_rot, lut, lut_scale,
                                                      (hipStream_t)stream);
@@ -155,6 +166,12 @@ int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* l
   if (top_k > 0 && !topk_idx) return A2ATS_ERR_INVALID_ARG;
   if (misaligned16(codes) || misaligned16(lut)) return A2ATS_ERR_INVALID_ARG;
   if (top_k > 4096) return A2ATS_ERR_UNSUPPORTED;
+  if (a2ats::single_codebook(*d)) {
+    const hipError_t e = a2ats::launch_score_topk_single(*d, codes, lut, top_k, window, n_sink, seq_lens,
+                                                         topk_idx, topk_count, topk_score, scores_out,
+                                                         (hipStream_t)stream);
+    return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+  }
   const a2ats::TopkPlan plan = a2ats::make_topk_plan(*d, top_k, window, n_sink);
   if (plan.fast) {
     if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;

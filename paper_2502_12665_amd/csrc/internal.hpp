@@ -69,6 +69,17 @@ hipError_t launch_decode_prologue(const a2ats_dims& d, const float* keys, int n_
                                   const float* codebook, const float* weights, int mode, uint8_t* codes,
                                   const void* q, int q_dtype, const float* cos_b, const float* sin_b,
                                   float* q_rot, int32_t* lut, float* lut_scale, hipStream_t stream);
+// The paper's geometry: one codebook of 4096 codewords over all 128 dimensions, 16-bit codes.
+inline bool single_codebook(const a2ats_dims& d) {
+  return d.n_sub == 1 && d.sub_dim == 128 && d.n_centroids == 4096;
+}
+hipError_t launch_build_lut_single(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
+                                   const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
+                                   float* lut_scale, hipStream_t stream);
+hipError_t launch_score_topk_single(const a2ats_dims& d, const void* codes, const int32_t* lut, int top_k,
+                                    int window, int n_sink, const int32_t* seq_lens, int32_t* topk_idx,
+                                    int32_t* topk_count, float* topk_score, float* scores_out,
+                                    hipStream_t stream);
 hipError_t launch_encode(const a2ats_dims& d, const float* keys, int n_new, int pos0, const float* codebook,
                          const float* weights, int mode, uint8_t* codes, void* ws, hipStream_t stream);
 

@@ -53,7 +53,7 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
   long ncand = (long)d.ctx_len - window - n_sink;
   if (ncand < 0) ncand = 0;
   p.cap = 8192;
-  p.fast = ncand >= 16384 && top_k >= 1 && top_k <= 2048 && 4L * top_k <= ncand;
+  p.fast = !single_codebook(d) && ncand >= 16384 && top_k >= 1 && top_k <= 2048 && 4L * top_k <= ncand;
   if (p.fast) {
     // Sample a sixteenth of the candidates, in units of kSampleRows, shared by at most 8
     // workgroups: up to 8 * kSampleRows each workgroup scores kSampleRows rows, beyond that (very

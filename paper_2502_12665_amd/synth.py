@@ -41,6 +41,7 @@ class Workload:
     rope_base: float = 500000.0
     wrope_b: int = 2048      # paper section 5.1: b = 2048
     seed: int = 0
+    n_centroids: int = 256   # codewords per subspace; above 256 the codes are 16 bits wide
 
     @property
     def sub_dim(self) -> int:
@@ -63,6 +64,10 @@ WORKLOADS: Dict[str, Workload] = {
     "c4_long_128k": Workload("c4_long_128k", 4, 32, 8, 128, 16, 131072, 2048, 256),
     "c5_qwen7b_64k": Workload("c5_qwen7b_64k", 32, 28, 4, 128, 32, 65536, 2048, 128,
                               rope_base=1000000.0),
+    # The paper's own vector-quantisation geometry (section 5.1): one codebook of 4096 codewords
+    # per head over all 128 dimensions, on the shape of configuration 4.
+    "p4_single_codebook_128k": Workload("p4_single_codebook_128k", 4, 32, 8, 128, 1, 131072, 2048, 256,
+                                        n_centroids=4096),
 }
 
 
@@ -82,10 +87,16 @@ def inv_freq(head_dim: int, base: float) -> torch.Tensor:
     return torch.exp(-(2.0 * t / head_dim) * math.log(base))
 
 
+def code_dtype(wl: Workload) -> torch.dtype:
+    """uint8 codes for up to 256 codewords, else 16-bit codes (stored as int16: values stay below 2^15)."""
+    assert wl.n_centroids <= 32768
+    return torch.uint8 if wl.n_centroids <= 256 else torch.int16
+
+
 def make_codebook(wl: Workload, device="cpu") -> torch.Tensor:
-    """[Hkv, M, 256, ds] float32, standard normal."""
+    """[Hkv, M, L, ds] float32, standard normal."""
     g = _gen(wl.seed, 1, device)
-    return torch.randn(wl.n_kv_heads, wl.n_sub, N_CENTROIDS, wl.sub_dim,
+    return torch.randn(wl.n_kv_heads, wl.n_sub, wl.n_centroids, wl.sub_dim,
                        generator=g, device=device, dtype=torch.float32)
 
 
@@ -107,7 +118,7 @@ def make_decode_inputs(wl: Workload, device="cpu", with_kv: bool = True,
                        ctx_stride: Optional[int] = None) -> Dict[str, torch.Tensor]:
     """All tensors of one decode step.
 
-    codebook [Hkv,M,256,ds] f32 ; codes [B,Hkv,S,M] u8 ; k,v [B,Hkv,S,D] kv_dtype ;
+    codebook [Hkv,M,L,ds] f32 ; codes [B,Hkv,S,M] u8 (i16 for L > 256) ; k,v [B,Hkv,S,D] kv_dtype ;
     q [B,Hq,D] kv_dtype ; inv_freq [D/2] f64 (CPU).  S = ctx_stride >= N; rows past N
     are filled with a recognisable pattern that must never be read as data."""
     dt = _torch_dtype(wl.kv_dtype)
@@ -117,9 +128,10 @@ def make_decode_inputs(wl: Workload, device="cpu", with_kv: bool = True,
     out: Dict[str, torch.Tensor] = {}
     cb = make_codebook(wl, device)
     out["codebook"] = cb
-    codes = torch.full((B, Hkv, S, M), 255, dtype=torch.uint8, device=device)
-    codes[:, :, :N] = torch.randint(0, N_CENTROIDS, (B, Hkv, N, M), generator=_gen(wl.seed, 2, device),
-                                    device=device, dtype=torch.int32).to(torch.uint8)
+    cdt = code_dtype(wl)
+    codes = torch.full((B, Hkv, S, M), wl.n_centroids - 1, dtype=cdt, device=device)
+    codes[:, :, :N] = torch.randint(0, wl.n_centroids, (B, Hkv, N, M), generator=_gen(wl.seed, 2, device),
+                                    device=device, dtype=torch.int32).to(cdt)
     out["codes"] = codes
     if with_kv:
         k = torch.full((B, Hkv, S, D), 7.0, dtype=dt, device=device)
@@ -166,8 +178,8 @@ def make_encode_keys(wl: Workload, n_new: int, device="cpu", stress: bool = Fals
         return torch.randn(B, wl.n_kv_heads, n_new, wl.head_dim, generator=_gen(wl.seed, 8, device),
                            device=device, dtype=torch.float32)
     cb = make_codebook(wl, device)
-    codes = torch.randint(0, N_CENTROIDS, (B, wl.n_kv_heads, n_new, wl.n_sub),
-                          generator=_gen(wl.seed, 7, device), device=device, dtype=torch.int32).to(torch.uint8)
+    codes = torch.randint(0, wl.n_centroids, (B, wl.n_kv_heads, n_new, wl.n_sub),
+                          generator=_gen(wl.seed, 7, device), device=device, dtype=torch.int32).to(code_dtype(wl))
     keys = reconstruct(cb, codes)
     keys += 0.1 * torch.randn(keys.shape, generator=_gen(wl.seed, 9, device), device=device,
                               dtype=torch.float32)

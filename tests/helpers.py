@@ -29,7 +29,8 @@ def log(msg: str):
 
 
 def dims_of(wl: synth.Workload, ctx_stride=None):
-    return B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len, ctx_stride)
+    return B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len, ctx_stride,
+                       n_centroids=wl.n_centroids)
 
 
 def to_dev(x: dict, device="cuda") -> dict:

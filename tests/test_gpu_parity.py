@@ -356,6 +356,43 @@ def test_maximum_context_length_and_top_k(oracle, top_k, expect_fast):
         assert (surv == 0x0FFFFFFF).all()   # the exact-only route reports no survivor lists
 
 
+# ---------------------------------------------------------------------------
+# The paper's own geometry: one codebook of 4096 codewords per head (M = 1), 16-bit codes.
+# ---------------------------------------------------------------------------
+def _single(name, Bn, Hq, Hkv, N, K, w, **kw):
+    return synth.Workload(name, Bn, Hq, Hkv, 128, 1, N, K, w, n_centroids=4096, **kw)
+
+
+def test_single_codebook_small_shapes(oracle):
+    """Whole steps against the oracle over small shapes: tiny and ragged contexts, K from 0 to all
+    candidates, sinks, unaligned token-axis capacity, float32 and bf16 caches."""
+    w = 16
+    for G, (N, K), n_sink in itertools.product((1, 4, 7), [(1, 1), (w + 1, 1), (w + 7, 7), (257, 0), (257, 257),
+                                                           (1000, 7), (9000, 300)], (0, 4)):
+        wl = _single(f"single_G{G}_N{N}_K{K}_s{n_sink}", 2, 2 * G, 2, N, K, w, n_sink=n_sink,
+                     kv_dtype="f32" if G == 1 else "bf16", rope_base=10000.0, seed=N + K + G)
+        H.log(wl.name)
+        _run_and_check(oracle, wl, ctx_stride=N + (5 if G == 4 else 0))
+    wl = _single("single_ragged", 4, 8, 2, 600, 9, w, n_sink=4, seed=3)
+    H.log(wl.name)
+    _run_and_check(oracle, wl, seq_lens=[600, 0, 7, 333])
+
+
+def test_single_codebook_heavy_ties(oracle):
+    """With 4096 codewords there are at most 4096 distinct scores per head, so at 60000 tokens every
+    score is shared by ~15 tokens and the K-th score almost always is: the position tie-break decides."""
+    wl = _single("single_ties", 2, 8, 2, 60000, 1000, 64, seed=21)
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl)
+    H.log(f"  {res}")
+    assert res["excluded"] <= res["slots"] // 1000
+
+
+def test_single_codebook_full_size(oracle):
+    wl = synth.WORKLOADS["p4_single_codebook_128k"]
+    _full_size_check(oracle, wl, sample=[(0, 0), (3, 7)])
+
+
 def _routes(wl, xd, n_sink=0):
     """Run tables + score/top-K alone and return (survivors per head, route per head)."""
     dims = H.dims_of(wl, xd["codes"].shape[2])
