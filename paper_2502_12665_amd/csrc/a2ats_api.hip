@@ -55,7 +55,8 @@ size_t a2ats_lut_elems(const a2ats_dims* d) {
 size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t window) {
   if (check_dims(d) != A2ATS_OK) return (size_t)-1;
   switch (op) {
-    case A2ATS_OP_ENCODE: return a2ats::encode_ws_bytes(*d);
+    case A2ATS_OP_ENCODE:
+      return a2ats::single_codebook(*d) ? a2ats::encode_single_ws_bytes(*d) : a2ats::encode_ws_bytes(*d);
     case A2ATS_OP_LUT: return 0;
     case A2ATS_OP_SCORE_TOPK: {
       if (top_k < 0 || window < 0) return (size_t)-1;
@@ -105,12 +106,18 @@ int a2ats_encode_keys(const a2ats_dims* d, const float* keys, int32_t n_new, int
   if (!keys || !codebook || !codes) return A2ATS_ERR_INVALID_ARG;
   if (weight_mode != A2ATS_W_NONE && !weights) return A2ATS_ERR_INVALID_ARG;
   if (misaligned16(keys) || misaligned16(codebook)) return A2ATS_ERR_INVALID_ARG;
+  if (a2ats::single_codebook(*d)) {   // every weighting goes through the transformed codewords
+    if (!ws || misaligned16(ws) || ws_bytes < a2ats::encode_single_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
+    if ((int64_t)d->batch * d->n_kv_heads * (int64_t)n_new >= (1LL << 31)) return A2ATS_ERR_UNSUPPORTED;
+    const hipError_t e = a2ats::launch_encode_single(*d, keys, n_new, pos0, codebook, weights, weight_mode, codes,
+                                                     ws, (hipStream_t)stream);
+    return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+  }
   if (weight_mode != A2ATS_W_NONE) {
     if (!ws || misaligned16(ws)) return A2ATS_ERR_WORKSPACE;
     if (ws_bytes < a2ats::encode_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
   }
   if ((int64_t)n_new > 65535LL * 256) return A2ATS_ERR_UNSUPPORTED;
-  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
   const hipError_t e = a2ats::launch_encode(*d, keys, n_new, pos0, codebook, weights, weight_mode, codes,
                                             weight_mode != A2ATS_W_NONE ? ws : nullptr, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;

@@ -70,12 +70,17 @@ __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
   __syncthreads();
   const int c = chunk * kLutChunk + tid;
   const float4* cw = (const float4*)(codebook + ((size_t)kv * kCodewords + c) * kSD);
+  // A thread reads its codeword's 512-byte row by itself, so the loads of a wave do not coalesce
+  // and each takes long: all 32 are requested before the first is used.
+  float4 row[kSD / 4];
+#pragma unroll
+  for (int t4 = 0; t4 < kSD / 4; ++t4) row[t4] = cw[t4];
   double acc[8];
 #pragma unroll
   for (int g = 0; g < 8; ++g) acc[g] = 0.0;
-#pragma unroll 4
+#pragma unroll
   for (int t4 = 0; t4 < kSD / 4; ++t4) {
-    const float4 f = cw[t4];
+    const float4 f = row[t4];
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
       if (g < G) {
@@ -106,45 +111,71 @@ hipError_t launch_build_lut_single(const a2ats_dims& d, const void* q, int q_dty
 // ------------------------------------------------------------------------------------------
 // Selection
 // ------------------------------------------------------------------------------------------
-constexpr int kSelThreads = 1024;
+constexpr int kSelThreads = 512;
 constexpr int kPerThread = 8;                       // consecutive tokens per thread and round
 constexpr int kRound = kSelThreads * kPerThread;    // tokens per round
 
+constexpr int kSpan = 32;                           // rounds a thread keeps in registers
+constexpr int kSpanTokens = kSpan * kRound;         // 131072
+constexpr int kSelWaves = kSelThreads / 64;
+
 struct SelLds {
-  int32_t table[kCodewords];
+  int32_t table[kCodewords];    // the head's scores as order-preserving keys
+  uint32_t count[kCodewords + 1];   // candidate tokens per codeword (+ a spare bin)
   uint32_t hist[kHistBins];
-  uint32_t wave_a[kSelThreads / 64];
-  uint32_t wave_b[kSelThreads / 64];
+  uint32_t wave_tot[kSpan][kSelWaves];   // packed (above, equal) counts per round and wave
+  uint32_t wave_pre[kSpan][kSelWaves];   // ... exclusive over the waves of a round
+  uint32_t round_tot[kSpan];
+  uint32_t wave_a[kSelWaves];
   uint32_t res[2];
   uint32_t kmin, kmax;
 };
 
-// The keys of tokens [j0, j0 + 8) of a sequence (positions at or past `hi` and before `lo` get
-// `valid` false).  16-byte load when the row of codes allows it.
-__device__ __forceinline__ void load_keys8(const uint16_t* __restrict__ seq_codes, bool aligned, int j0,
-                                           int lo, int hi, const int32_t* table, uint32_t (&key)[kPerThread],
-                                           bool (&valid)[kPerThread]) {
-  uint16_t c[kPerThread];
-  if (aligned && j0 >= 0 && j0 + kPerThread <= hi) {
-    const uint4 v = *(const uint4*)(seq_codes + j0);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+// The codes of tokens [j0, j0 + 8) of a sequence.  Branch-free: a start beyond the row is moved
+// back into it (the caller masks such tokens by position), so every load is unconditional and a
+// thread's loads are all in flight together.  ALIGNED rows (16-byte aligned, a multiple of 8
+// codes long) take one 16-byte load, others eight 2-byte loads.
+template <bool ALIGNED>
+__device__ __forceinline__ uint4 load_codes8(const uint16_t* __restrict__ seq_codes, int j0, int row_len) {
+  if (ALIGNED) return *(const uint4*)(seq_codes + min(j0, row_len - kPerThread));
+  uint32_t w[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i) c[i] = (uint16_t)(w[i >> 1] >> (16 * (i & 1)));
-  } else {
-#pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-      const int j = j0 + i;
-      c[i] = (j >= 0 && j < hi) ? seq_codes[j] : (uint16_t)0;
-    }
-  }
-#pragma unroll
-  for (int i = 0; i < kPerThread; ++i) {
-    const int j = j0 + i;
-    valid[i] = j >= lo && j < hi;
-    key[i] = score_key(table[c[i] & (kCodewords - 1)]);   // the mask keeps a bad code inside the table
-  }
+  for (int i = 0; i < kPerThread; ++i) w[i >> 1] |= (uint32_t)seq_codes[min(j0 + i, row_len - 1)] << (16 * (i & 1));
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+__device__ __forceinline__ uint32_t code_of(const uint4& v, int i) {
+  const uint32_t w = i < 2 ? v.x : (i < 4 ? v.y : (i < 6 ? v.z : v.w));
+  return (w >> (16 * (i & 1))) & (kCodewords - 1);   // the mask keeps a bad code inside the table
+}
+// Bit i set when token j0 + i is a candidate, i.e. lies in [lo, hi).
+__device__ __forceinline__ uint32_t valid_mask8(int j0, int lo, int hi) {
+  const int a = min(max(lo - j0, 0), kPerThread), e = min(max(hi - j0, 0), kPerThread);
+  return ((1u << e) - 1u) & ~((1u << a) - 1u);
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (a shuffle
+// through the LDS crossbar costs a round trip per step and these scans sit on the critical path):
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of rows 0 and 2 is added
+// to rows 1 and 3, then lane 31 to the upper half.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);   // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);   // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);   // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);   // row_bcast:15
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31
+  return v;
+}
+
+// One workgroup per head.  A score is one table entry, so the K-th largest score over the
+// candidate tokens is a weighted selection over the 4096 codewords: (1) count the candidates per
+// codeword (one pass over the 2-byte codes), (2) MSB-first radix select over the 4096 keys weighted
+// by those counts, (3) a pass that emits the winners in ascending position, equal scores going to
+// the lower position.  A thread keeps the codes of 16 rounds of 8 consecutive tokens in registers
+// (one span = 131072 tokens per workgroup): all 16 loads are in flight together, a context of one
+// span is read once and serves both passes, and the 16 rounds share one scan of their packed
+// (above, equal) counts instead of one scan and two barriers per round.
+template <bool ALIGNED>
 __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
     const uint16_t* __restrict__ codes, const int32_t* __restrict__ lut, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ topk_count, float* __restrict__ topk_score,
@@ -152,6 +183,7 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
   constexpr int NT = kSelThreads;
   __shared__ SelLds L;
   const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq, G = Hq / Hkv, kv = h / G, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   int32_t* oi = topk_idx + (size_t)bh * top_k;
   float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
@@ -162,39 +194,70 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
   }
   if (sr.kk == 0) return;
 
+  const uint16_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride;
+  const int row_len = (int)ctx_stride;
+  const int lo = sr.sink_end, hi = sr.win_start;
+  const int first = lo & ~(kPerThread - 1);   // rounds start on a multiple of 8 tokens
+  const int n_span = (hi - first + kSpanTokens - 1) / kSpanTokens;
+  const bool take_all = sr.kk >= sr.ncand;
+
+  // Requests in the order their data is needed last-to-first is wrong for in-order returns: the
+  // table is asked for first (it is small), the codes after it, so the count pass can start on the
+  // first round's codes while the later rounds are still arriving.
+  constexpr int kTablePer = kCodewords / NT;
   const int32_t* head_table = lut + (size_t)bh * kCodewords;
+  int32_t tv[kTablePer];
+#pragma unroll
+  for (int i = 0; i < kTablePer; ++i) tv[i] = head_table[i * NT + tid];
+  uint4 cv[kSpan];
+  if (!take_all || n_span == 1) {
+#pragma unroll
+    for (int r = 0; r < kSpan; ++r) cv[r] = load_codes8<ALIGNED>(seq_codes, first + r * kRound + tid * kPerThread, row_len);
+  }
   uint32_t kmin = 0xffffffffu, kmax = 0u;
-  for (int e = tid; e < kCodewords; e += NT) {
-    const int32_t v = head_table[e];
-    L.table[e] = v;
-    kmin = min(kmin, score_key(v));
-    kmax = max(kmax, score_key(v));
+#pragma unroll
+  for (int i = 0; i < kTablePer; ++i) {
+    L.table[i * NT + tid] = tv[i];
+    L.count[i * NT + tid] = 0;
+    kmin = min(kmin, score_key(tv[i]));
+    kmax = max(kmax, score_key(tv[i]));
   }
   if (tid == 0) {
     L.kmin = 0xffffffffu;
     L.kmax = 0u;
   }
   __syncthreads();
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    kmin = min(kmin, __shfl_xor(kmin, off));
-    kmax = max(kmax, __shfl_xor(kmax, off));
-  }
-  if ((tid & 63) == 0) {
-    atomicMin(&L.kmin, kmin);
-    atomicMax(&L.kmax, kmax);
-  }
-  __syncthreads();
-  const uint32_t k_lo = L.kmin;
-
-  const uint16_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride;
-  const bool aligned = (((uintptr_t)seq_codes) & 15u) == 0;
-  const int lo = sr.sink_end, hi = sr.win_start;
-  const int first = lo & ~(kPerThread - 1);   // rounds start on a multiple of 8 tokens
 
   uint32_t kth = 0, k_rem = (uint32_t)sr.kk;
-  if (sr.kk < sr.ncand) {
-    // Radix digits are taken from key - smallest key of the table, MSB first.
+  if (!take_all) {
+    // (1) candidates per codeword
+#pragma unroll 1
+    for (int sp = 0; sp < n_span; ++sp) {
+      const int s0 = first + sp * kSpanTokens;
+      if (sp > 0) {
+#pragma unroll
+        for (int r = 0; r < kSpan; ++r) cv[r] = load_codes8<ALIGNED>(seq_codes, s0 + r * kRound + tid * kPerThread, row_len);
+      }
+#pragma unroll
+      for (int r = 0; r < kSpan; ++r) {
+        const uint32_t vm = valid_mask8(s0 + r * kRound + tid * kPerThread, lo, hi);
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i)   // tokens outside the candidate range count in a spare bin
+          atomicAdd(&L.count[(vm >> i) & 1u ? code_of(cv[r], i) : (uint32_t)kCodewords], 1u);
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      kmin = min(kmin, __shfl_xor(kmin, off));
+      kmax = max(kmax, __shfl_xor(kmax, off));
+    }
+    if (lane == 0) {
+      atomicMin(&L.kmin, kmin);
+      atomicMax(&L.kmax, kmax);
+    }
+    __syncthreads();
+    // (2) weighted radix select over the codewords; digits from key - smallest key, MSB first
+    const uint32_t k_lo = L.kmin;
     int remaining = 32 - __clz(L.kmax - k_lo);
     uint32_t prefix = 0, mask = 0;
 #pragma unroll 1
@@ -204,15 +267,9 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
       const uint32_t dmask = (1u << bits) - 1u;
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       __syncthreads();
-      for (int base = first; base < hi; base += kRound) {
-        uint32_t key[kPerThread];
-        bool valid[kPerThread];
-        load_keys8(seq_codes, aligned, base + tid * kPerThread, lo, hi, L.table, key, valid);
-#pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-          const uint32_t rel = key[i] - k_lo;
-          if (valid[i] && (rel & mask) == prefix) atomicAdd(&L.hist[(rel >> shift) & dmask], 1u);
-        }
+      for (int e = tid; e < kCodewords; e += NT) {
+        const uint32_t rel = score_key(L.table[e]) - k_lo, w = L.count[e];
+        if (w && (rel & mask) == prefix) atomicAdd(&L.hist[(rel >> shift) & dmask], w);
       }
       __syncthreads();
       block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
@@ -226,42 +283,87 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
     kth = prefix + k_lo;
   }
 
-  // Ordered emission: keys above the K-th, plus the first k_rem positions that equal it.  A thread
-  // owns 8 consecutive positions, so one scan of packed (above, equal) counts per round places
-  // every winner.
-  const bool take_all = sr.kk >= sr.ncand;
+  // (3) ordered emission: keys above the K-th, plus the first k_rem positions that equal it
   uint32_t out_n = 0, eq_seen = 0;
 #pragma unroll 1
-  for (int base = first; base < hi; base += kRound) {
-    uint32_t key[kPerThread];
-    bool valid[kPerThread];
-    const int j0 = base + tid * kPerThread;
-    load_keys8(seq_codes, aligned, j0, lo, hi, L.table, key, valid);
-    uint32_t loc = 0;
+  for (int sp = 0; sp < n_span; ++sp) {
+    const int s0 = first + sp * kSpanTokens;
+    if (n_span > 1) {
+      __syncthreads();   // the scan arrays of the span before are still being read
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-      const bool gt = valid[i] && (take_all || key[i] > kth);
-      const bool eq = valid[i] && !take_all && key[i] == kth;
-      loc += (gt ? 1u : 0u) + (eq ? 0x10000u : 0u);
+      for (int r = 0; r < kSpan; ++r) cv[r] = load_codes8<ALIGNED>(seq_codes, s0 + r * kRound + tid * kPerThread, row_len);
     }
-    uint32_t tot;
-    uint32_t pre = block_exclusive_scan<NT>(loc, (base / kRound) & 1 ? L.wave_b : L.wave_a, tot);
-    uint32_t gt_before = pre & 0xffffu, eq_before = eq_seen + (pre >> 16);
+    uint32_t gbits[kSpan / 4], ebits[kSpan / 4];
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-      const bool gt = valid[i] && (take_all || key[i] > kth);
-      const bool eq = valid[i] && !take_all && key[i] == kth;
-      if (gt || (eq && eq_before < k_rem)) {
-        const uint32_t slot = out_n + gt_before + min(eq_before, k_rem);
-        oi[slot] = j0 + i;
-        if (os) os[slot] = key_to_float(key_score(key[i]));
+    for (int i = 0; i < kSpan / 4; ++i) gbits[i] = ebits[i] = 0;
+#pragma unroll
+    for (int r = 0; r < kSpan; ++r) {
+      const uint32_t vm = valid_mask8(s0 + r * kRound + tid * kPerThread, lo, hi);
+      uint32_t g = 0, e = 0;
+#pragma unroll
+      for (int i = 0; i < kPerThread; ++i) {
+        const uint32_t key = score_key(L.table[code_of(cv[r], i)]);
+        g |= (take_all || key > kth ? 1u : 0u) << i;
+        e |= (!take_all && key == kth ? 1u : 0u) << i;
       }
-      gt_before += gt ? 1u : 0u;
-      eq_before += eq ? 1u : 0u;
+      g &= vm;
+      e &= vm;
+      gbits[r / 4] |= g << (8 * (r % 4));
+      ebits[r / 4] |= e << (8 * (r % 4));
+      const uint32_t v = wave_inclusive_scan((uint32_t)__popc(g) | ((uint32_t)__popc(e) << 16));
+      if (lane == 63) L.wave_tot[r][wave] = v;
     }
-    out_n += tot & 0xffffu;
-    eq_seen += tot >> 16;
-    if (out_n + min(eq_seen, k_rem) >= (uint32_t)sr.kk) break;   // uniform: tot is the block total
+    __syncthreads();
+    if (tid < kSpan * kSelWaves) {   // exclusive scan over the 16 waves of each round (16-lane groups)
+      const int r = tid / kSelWaves, w = tid % kSelWaves;
+      const uint32_t own = L.wave_tot[r][w];
+      uint32_t v = own;
+#pragma unroll
+      for (int off = 1; off < kSelWaves; off <<= 1) {
+        const uint32_t n = __shfl_up(v, off, kSelWaves);
+        if (w >= off) v += n;
+      }
+      L.wave_pre[r][w] = v - own;
+      if (w == kSelWaves - 1) L.round_tot[r] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSpan; ++r) {
+      const uint32_t g = (gbits[r / 4] >> (8 * (r % 4))) & 0xffu, e = (ebits[r / 4] >> (8 * (r % 4))) & 0xffu;
+      const uint32_t tot = L.round_tot[r];
+      // (the scan over the wave is recomputed rather than kept: 32 more registers would spill)
+      const uint32_t own = (uint32_t)__popc(g) | ((uint32_t)__popc(e) << 16);
+      const uint32_t own_pre = wave_inclusive_scan(own) - own;
+      if (g | e) {
+        const int j0 = s0 + r * kRound + tid * kPerThread;
+        const uint32_t p = own_pre + L.wave_pre[r][wave];
+        // winners of this thread: everything above the K-th, and the equal ones whose rank among
+        // the equal ones is below k_rem
+        const uint32_t gt_before = p & 0xffffu, eq_before = eq_seen + (p >> 16);
+        uint32_t e_take = 0;
+        if (e && eq_before < k_rem) {
+          const uint32_t room = k_rem - eq_before;   // >= 1
+          e_take = e;
+          if ((uint32_t)__popc(e) > room) {          // keep the lowest `room` set bits
+#pragma unroll 1
+            for (uint32_t drop = (uint32_t)__popc(e) - room; drop; --drop) e_take &= ~(0x80000000u >> __clz(e_take));
+          }
+        }
+        uint32_t m = g | e_take;
+#pragma unroll 1
+        while (m) {
+          const int i = __ffs(m) - 1;
+          const uint32_t below = (1u << i) - 1u;
+          const uint32_t slot = out_n + gt_before + (uint32_t)__popc(g & below) + min(eq_before, k_rem) + (uint32_t)__popc(e_take & below);
+          oi[slot] = j0 + i;
+          if (os) os[slot] = key_to_float(L.table[seq_codes[j0 + i] & (kCodewords - 1)]);
+          m &= m - 1;
+        }
+      }
+      out_n += tot & 0xffffu;
+      eq_seen += tot >> 16;
+    }
+    if (out_n + min(eq_seen, k_rem) >= (uint32_t)sr.kk) break;   // uniform over the workgroup
   }
 }
 
@@ -293,9 +395,15 @@ hipError_t launch_score_topk_single(const a2ats_dims& d, const void* codes, cons
     const hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
   }
-  hipLaunchKernelGGL(select_single_kernel, dim3(heads), dim3(kSelThreads), 0, stream, (const uint16_t*)codes,
-                     lut, seq_lens, topk_idx, topk_count, topk_score, d.n_q_heads, d.n_kv_heads, d.ctx_len,
-                     d.ctx_stride, top_k, window, n_sink);
+  const bool aligned = (((uintptr_t)codes) & 15u) == 0 && d.ctx_stride % kPerThread == 0 && d.ctx_stride >= kPerThread;
+  if (aligned)
+    hipLaunchKernelGGL(select_single_kernel<true>, dim3(heads), dim3(kSelThreads), 0, stream,
+                       (const uint16_t*)codes, lut, seq_lens, topk_idx, topk_count, topk_score, d.n_q_heads,
+                       d.n_kv_heads, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+  else
+    hipLaunchKernelGGL(select_single_kernel<false>, dim3(heads), dim3(kSelThreads), 0, stream,
+                       (const uint16_t*)codes, lut, seq_lens, topk_idx, topk_count, topk_score, d.n_q_heads,
+                       d.n_kv_heads, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   return hipGetLastError();
 }
 

@@ -388,6 +388,63 @@ def test_single_codebook_heavy_ties(oracle):
     assert res["excluded"] <= res["slots"] // 1000
 
 
+@pytest.mark.parametrize("mode", ["none", "diag", "block"])
+def test_single_codebook_encode(oracle, mode):
+    """Key encoder of the single-codebook geometry (full D x D matrix H in "block" mode) against the
+    oracle: the matrix-core route with ragged tiles, the few-key route, keys far from every codeword,
+    and keys planted so that two or three codewords are almost or exactly equally near (those go
+    through the float64 re-check)."""
+    wl = _single(f"single_enc_{mode}", 2, 4, 2, 3000, 16, 16, seed=33)
+    hm = synth.make_query_second_moment(wl)
+    cb = synth.make_codebook(wl)
+    cb[:, :, 77] = cb[:, :, 5]   # a duplicated codeword: exact ties, the lower code must win
+    code = {"none": B.W_NONE, "diag": B.W_DIAG, "block": B.W_BLOCK}[mode]
+    weights = {"none": None, "diag": hm["h_diag"], "block": hm["h_block"]}[mode]
+    stride = 3100
+    dims = H.dims_of(wl, stride)
+    ws = torch.empty(B.workspace_bytes(dims, B.OP_ENCODE), dtype=torch.uint8, device="cuda")
+    for n_new, pos0, kind in ((1300, 37, "near"), (777, 0, "far"), (3, 3096, "near"), (8, 5, "far"),
+                              (9, 0, "near"), (1100, 1000, "planted")):
+        H.log(f"{wl.name} n_new={n_new} {kind}")
+        keys = synth.make_encode_keys(wl, n_new, stress=(kind == "far"))
+        if kind == "planted":
+            g = torch.Generator().manual_seed(5)
+            a, b, c = (torch.randint(0, 4096, (n_new,), generator=g) for _ in range(3))
+            a[:50] = 5   # near the duplicated codeword
+            for kv in range(wl.n_kv_heads):
+                two = 0.5 * (cb[kv, 0, a] + cb[kv, 0, b])
+                three = (cb[kv, 0, a] + cb[kv, 0, b] + cb[kv, 0, c]) / 3.0
+                mid = torch.where((torch.arange(n_new) % 3 == 0)[:, None], three, two)
+                mid[:50] = cb[kv, 0, 5]
+                noise = torch.randn(wl.batch, n_new, 128, generator=g) * (10.0 ** -torch.randint(3, 7, (n_new, 1), generator=g))
+                keys[:, kv] = mid[None] + noise.to(torch.float32)
+        codes = torch.full((wl.batch, wl.n_kv_heads, stride, 1), 0x7EEE, dtype=torch.int16, device="cuda")
+        B.encode_keys(dims, keys.cuda(), n_new, pos0, cb.cuda(), None if weights is None else weights.cuda(),
+                      code, codes, ws)
+        torch.cuda.synchronize()
+        got = codes.cpu().numpy().view(np.uint16)
+        if mode == "block":
+            want, b1, b2 = oracle.encode_cholesky(keys, cb, weights, want_margins=True)
+        else:
+            want, b1, b2 = oracle.encode(keys, cb, weights, code, want_margins=True)
+        n_near = H.compare_codes(got[:, :, pos0:pos0 + n_new], want, b1, b2)
+        assert (got[:, :, :pos0] == 0x7EEE).all() and (got[:, :, pos0 + n_new:] == 0x7EEE).all()
+        if kind == "planted":
+            assert ((got[:, :, pos0:pos0 + 50] == 5) | (want[:, :, :50] != 5)).all()
+            close = ((b2 - b1) <= 1e-3 * np.maximum(1.0, b2)).mean()
+            assert close > 0.3, close
+        H.log(f"  near-tie exclusions: {n_near}")
+
+
+def test_single_codebook_long_context(oracle):
+    """More tokens than a workgroup keeps in registers at once (131072): the selection kernel then
+    walks the codes span by span, in both of its passes."""
+    wl = _single("single_long", 1, 4, 2, 300000, 2048, 64, n_sink=4, seed=8)
+    H.log(wl.name)
+    _run_and_check(oracle, wl)
+    _run_and_check(oracle, wl, ctx_stride=300003)
+
+
 def test_single_codebook_full_size(oracle):
     wl = synth.WORKLOADS["p4_single_codebook_128k"]
     _full_size_check(oracle, wl, sample=[(0, 0), (3, 7)])
