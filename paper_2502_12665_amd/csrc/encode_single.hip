@@ -13,14 +13,16 @@
 //   encode_single_codewords_kernel c^z = c L in float64; kept transposed in float64 for the exact
 //                                  re-check, and split into two bf16 terms (hi + lo, 16 significant
 //                                  bits) laid out in matrix-core operand order, with 1/2 ||c^z||^2
-//   encode_single_kernel           512 keys per workgroup: z = k L on the matrix cores, split the
-//                                  same way, kept in registers as the B operands; the codewords
-//                                  stream through LDS 32 at a time as the A operand; three bf16
-//                                  products per term (hi.hi + hi.lo + lo.hi, float32 accumulate)
-//                                  give the scores to about 2^-18 relative.  Every lane owns one
-//                                  key column of the 32 x 32 result tile, so the running smallest
-//                                  three scores (and the codes of the first two) are per-lane
-//                                  registers; nothing crosses lanes until the end.
+//   encode_single_transform_kernel z = k L in float64, rounded once to float32 (full-matrix mode only;
+//                                  a few k keys at a time, into a buffer the main pass reads as keys)
+//   encode_single_kernel           256 keys per workgroup: z is split the same way and kept in
+//                                  registers as the B operands; the codewords stream through LDS
+//                                  32 at a time as the A operand; three bf16 products per term
+//                                  (hi.hi + hi.lo + lo.hi, float32 accumulate) give the scores to
+//                                  about 2^-18 relative.  Every lane owns one key column of the
+//                                  32 x 32 result tile, so the running smallest three scores (and
+//                                  the codes of the first two) are per-lane registers; nothing
+//                                  crosses lanes until the end.
 //   encode_single_recheck_kernel   keys whose two smallest scores are closer than the rounding reach
 //                                  of the bf16 products are decided in float64 between those two
 //                                  codewords; keys with three that close (and the few-key append
@@ -34,20 +36,23 @@ namespace {
 
 constexpr int kCW = 4096;               // codewords per KV head
 constexpr int kD = 128;                 // head dimension
-constexpr int kEncWaves = 8;
+constexpr int kEncWaves = 4;           // two workgroups per CU: one wave of each per SIMD
 constexpr int kEncThreads = 64 * kEncWaves;
 constexpr int kKeysPerWave = 64;        // two 32-key column tiles
 constexpr int kKeysPerWG = kKeysPerWave * kEncWaves;
 constexpr int kFragBytes = 2 * 8 * 64 * 16;   // (hi, lo) x 8 k-steps x 64 lanes x 16 bytes: 32 rows of 128 dims
 constexpr int kBlocks = kCW / 32;       // streamed 32-codeword blocks
+static_assert(kFragBytes / 16 / kEncThreads == 4, "a thread stages four 16-byte pieces of a block");
 constexpr int kFewSingle = 8;           // at most this many keys per (sequence, KV head): float64 sweep only
-constexpr float kReach = 1.5e-5f;       // rounding reach of a score, relative to (|z| + |k| |L|_F) max|c^z|
+constexpr float kReach = 1.5e-5f;       // rounding reach of a score, relative to |z| max|c^z|
+constexpr int kChunk = 16384;           // keys per (sequence, KV head) transformed at a time
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 struct EncWs {
-  size_t off_L, off_sd, off_czT, off_cfrag, off_cbias, off_cstat, off_Lfrag, off_count, off_list, bytes;
+  size_t off_L, off_sd, off_czT, off_cfrag, off_cbias, off_cstat, off_z, off_count, off_list, bytes;
+  int chunk;   // keys per (sequence, KV head) the transform buffer holds
 };
 
 EncWs enc_single_ws(const a2ats_dims& d) {
@@ -66,7 +71,8 @@ EncWs enc_single_ws(const a2ats_dims& d) {
   w.off_cfrag = take(Hkv * kBlocks * (size_t)kFragBytes);
   w.off_cbias = take(Hkv * kCW * sizeof(float));
   w.off_cstat = take(Hkv * 4 * sizeof(float));
-  w.off_Lfrag = take(Hkv * 4 * (size_t)kFragBytes);
+  w.chunk = (int)(d.ctx_stride < kChunk ? d.ctx_stride : kChunk);
+  w.off_z = take((size_t)d.batch * Hkv * w.chunk * kD * sizeof(float));
   w.off_count = take(sizeof(uint32_t));
   w.off_list = take(keys_max * 2 * sizeof(uint32_t));
   w.bytes = o;
@@ -85,11 +91,11 @@ __device__ __forceinline__ void frag_slot(int t, int& kt, int& g, int& i) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Per KV head: the factor L (H = L L^T), its Frobenius norm, and L^T as bf16 hi/lo A operands.
+// Per KV head: the factor L (H = L L^T) and its Frobenius norm.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void encode_single_factor_kernel(
     const float* __restrict__ weights, int mode, double* __restrict__ Lmat, double* __restrict__ sd,
-    uint16_t* __restrict__ Lfrag, float* __restrict__ cstat, uint32_t* __restrict__ counter) {
+    float* __restrict__ cstat, uint32_t* __restrict__ counter) {
   extern __shared__ double s_A[];   // 128 x 128, lower triangle in use
   __shared__ double s_red[256];
   const int kv = blockIdx.x, tid = threadIdx.x;
@@ -138,18 +144,6 @@ __global__ __launch_bounds__(256) void encode_single_factor_kernel(
     cstat[kv * 4 + 0] = 0.f;
     cstat[kv * 4 + 1] = __double2float_ru(sqrt(s_red[0]));
   }
-  // A operand of the transform D[t'][key] = sum_r L[r][t'] k[r]: row t' = 32 rt + lane % 32,
-  // k-step kt, lane half g, element i <-> r = 16 kt + 8 g + i (the keys are loaded in that order).
-  uint16_t* frag = Lfrag + (size_t)kv * 4 * (kFragBytes / 2);
-  for (int e = tid; e < 4 * 8 * 64 * 8; e += 256) {
-    const int i = e & 7, l = (e >> 3) & 63, kt = (e >> 9) & 7, rt = e >> 12;
-    const int tp = 32 * rt + (l & 31), r = 16 * kt + 8 * (l >> 5) + i;
-    const double v = s_A[r * kD + tp];   // zero above the diagonal (r < t')
-    const uint16_t hi = f32_to_bf16((float)v);
-    const uint16_t lo = f32_to_bf16((float)(v - (double)bf16_to_f32(hi)));
-    frag[(size_t)rt * (kFragBytes / 2) + ((0 * 8 + kt) * 64 + l) * 8 + i] = hi;
-    frag[(size_t)rt * (kFragBytes / 2) + ((1 * 8 + kt) * 64 + l) * 8 + i] = lo;
-  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -191,8 +185,9 @@ __global__ __launch_bounds__(256) void encode_single_codewords_kernel(
     czT[((size_t)kv * kD + t) * kCW + cg] = acc[u];
     int kt, g, i;
     frag_slot(t, kt, g, i);
-    const uint16_t hi = f32_to_bf16((float)acc[u]);
-    const uint16_t lo = f32_to_bf16((float)(acc[u] - (double)bf16_to_f32(hi)));
+    const double neg = -acc[u];   // the operand is -c^z: the matrix core then leaves 1/2 |c^z|^2 - z . c^z
+    const uint16_t hi = f32_to_bf16((float)neg);
+    const uint16_t lo = f32_to_bf16((float)(neg - (double)bf16_to_f32(hi)));
     blk[((0 * 8 + kt) * 64 + row + 32 * g) * 8 + i] = hi;
     blk[((1 * 8 + kt) * 64 + row + 32 * g) * 8 + i] = lo;
   }
@@ -206,18 +201,56 @@ __global__ __launch_bounds__(256) void encode_single_codewords_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
+// z = k L for rows j0 .. j0 + n_part - 1 of every sequence, float64 accumulation, one rounding.
+// A thread owns one key and 32 consecutive output dimensions; the rows of L it needs are the same
+// for the whole wave.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void encode_single_transform_kernel(
+    const float* __restrict__ keys, const double* __restrict__ Lmat, float* __restrict__ z, int Hkv, int n_new,
+    int j0, int n_part, int chunk) {
+  __shared__ float s_k[64][kD + 1];
+  const int bkv = blockIdx.y, kv = bkv % Hkv, tid = threadIdx.x;
+  const int key = tid & 63, og = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int first = blockIdx.x * 64;
+  const float* src = keys + ((size_t)bkv * n_new + j0) * kD;
+  for (int e = tid; e < 64 * (kD / 4); e += 256) {
+    const int row = e / (kD / 4), c4 = e % (kD / 4);
+    const float4 f = *(const float4*)(src + (size_t)min(first + row, n_part - 1) * kD + 4 * c4);
+    s_k[row][4 * c4] = f.x, s_k[row][4 * c4 + 1] = f.y, s_k[row][4 * c4 + 2] = f.z, s_k[row][4 * c4 + 3] = f.w;
+  }
+  __syncthreads();
+  double acc[32];
+#pragma unroll
+  for (int u = 0; u < 32; ++u) acc[u] = 0.0;
+  const double* L = Lmat + (size_t)kv * kD * kD + 32 * og;
+  for (int r = 32 * og; r < kD; ++r) {   // L[r][t] = 0 for r < t
+    const double kr = (double)s_k[key][r];
+#pragma unroll
+    for (int u = 0; u < 32; ++u) acc[u] += kr * L[(size_t)r * kD + u];
+  }
+  if (first + key < n_part) {
+    float* dst = z + ((size_t)bkv * chunk + first + key) * kD + 32 * og;
+#pragma unroll
+    for (int u = 0; u < 32; u += 4)
+      *(float4*)(dst + u) = make_float4((float)acc[u], (float)acc[u + 1], (float)acc[u + 2], (float)acc[u + 3]);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Main pass
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ void split8(const float (&z)[8], bf16x8& hi, bf16x8& lo, float& n2) {
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const __bf16 h = (__bf16)z[i];
-    const float rest = z[i] - (float)h;
-    const __bf16 l = (__bf16)rest;
-    hi[i] = h;
-    lo[i] = l;
-    const float kept = (float)h + (float)l;
-    n2 += kept * kept;
+  for (int i = 0; i < 8; i += 2) {   // two at a time: one packed conversion each for hi and lo
+    const f32x2 v = {z[i], z[i + 1]};
+    const bf16x2 h = __builtin_convertvector(v, bf16x2);
+    const f32x2 back = __builtin_convertvector(h, f32x2);
+    const bf16x2 l = __builtin_convertvector(v - back, bf16x2);
+    hi[i] = h.x, hi[i + 1] = h.y;
+    lo[i] = l.x, lo[i + 1] = l.y;
+    n2 += z[i] * z[i] + z[i + 1] * z[i + 1];   // (the norm only scales the rounding reach)
   }
 }
 
@@ -232,146 +265,166 @@ __device__ __forceinline__ void top3_insert(float s, int c, float& s1, float& s2
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kEncThreads) void encode_single_kernel(
+__global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void encode_single_kernel(
     const float* __restrict__ keys, const double* __restrict__ sd, const uint8_t* __restrict__ cfrag,
-    const float* __restrict__ cbias, const float* __restrict__ cstat, const uint8_t* __restrict__ Lfrag,
-    uint16_t* __restrict__ codes, uint32_t* __restrict__ counter, uint32_t* __restrict__ list, int Hkv,
-    int n_new, int pos0, int64_t ctx_stride) {
-  __shared__ __align__(16) uint8_t s_mem[4 * kFragBytes];   // transform: all of L^T; main loop: two blocks
+    const float* __restrict__ cbias, const float* __restrict__ cstat, uint16_t* __restrict__ codes,
+    uint32_t* __restrict__ counter, uint32_t* __restrict__ list, int Hkv, int n_new, int pos0,
+    int64_t ctx_stride, int j0, int n_part, int64_t seq_stride) {
+  // `keys` holds rows j0 .. j0 + n_part - 1 of every sequence, seq_stride floats apart (the
+  // caller's keys themselves, or the transformed copy of one part of them).
+  __shared__ __align__(16) uint8_t s_mem[2 * (kFragBytes + 128)];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, col = lane & 31, g = lane >> 5;
   const int bkv = blockIdx.y, kv = bkv % Hkv;
   const long key_first = (long)blockIdx.x * kKeysPerWG + wave * kKeysPerWave;
-  const float* seq_keys = keys + (size_t)bkv * n_new * kD;
+  const float* seq_keys = keys + (size_t)bkv * seq_stride;
 
   bf16x8 zh[2][8], zl[2][8];
-  float zn2[2] = {0.f, 0.f}, kn2[2] = {0.f, 0.f};
-  if (MODE == A2ATS_W_BLOCK) {
-    const uint8_t* gl = Lfrag + (size_t)kv * 4 * kFragBytes;
-    for (int o = tid * 16; o < 4 * kFragBytes; o += kEncThreads * 16) *(uint4*)(s_mem + o) = *(const uint4*)(gl + o);
-    __syncthreads();
+  float zn2[2] = {0.f, 0.f};
+  {
+    // (four k-steps of loads in flight at a time: with all sixteen the registers they land in
+    // and the 128 the operands need do not fit, and the spills cost far more than the latency)
 #pragma unroll
     for (int tile = 0; tile < 2; ++tile) {
-      const long jr = min(key_first + 32 * tile + col, (long)n_new - 1);
-      const float* kp = seq_keys + (size_t)jr * kD;
-      bf16x8 kh[8], kl[8];
-#pragma unroll
-      for (int kt = 0; kt < 8; ++kt) {   // operand element i <-> dimension 16 kt + 8 g + i
-        const float4 a = *(const float4*)(kp + 16 * kt + 8 * g), b = *(const float4*)(kp + 16 * kt + 8 * g + 4);
-        const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        split8(x, kh[kt], kl[kt], kn2[tile]);
-      }
-#pragma unroll
-      for (int rt = 0; rt < 4; ++rt) {
-        f32x16 acc = {0};
-        const uint8_t* blk = s_mem + rt * kFragBytes;
-#pragma unroll
-        for (int kt = 2 * rt; kt < 8; ++kt) {   // L^T is upper triangular: rows 32 rt.. need r >= 32 rt only
-          const bf16x8 a_hi = *(const bf16x8*)(blk + ((0 * 8 + kt) * 64 + lane) * 16);
-          const bf16x8 a_lo = *(const bf16x8*)(blk + ((1 * 8 + kt) * 64 + lane) * 16);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, kh[kt], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, kl[kt], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, kh[kt], acc, 0, 0, 0);
-        }
-        // register v holds z[32 rt + 8 (v/4) + 4 g + v%4]: elements 0..7 of k-steps 2 rt and 2 rt + 1
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          float x[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) x[i] = acc[8 * half + i];
-          split8(x, zh[tile][2 * rt + half], zl[tile][2 * rt + half], zn2[tile]);
-        }
-      }
-    }
-    __syncthreads();   // L^T is done with; the main loop reuses the memory
-  } else {
-#pragma unroll
-    for (int tile = 0; tile < 2; ++tile) {
-      const long jr = min(key_first + 32 * tile + col, (long)n_new - 1);
+      const long jr = min(key_first + 32 * tile + col, (long)n_part - 1);
       const float* kp = seq_keys + (size_t)jr * kD;
 #pragma unroll
-      for (int kt = 0; kt < 8; ++kt) {   // operand element i <-> dimension 16 kt + 8 (i/4) + 4 g + i%4
-        const int t0 = 16 * kt + 4 * g;
-        const float4 a = *(const float4*)(kp + t0), b = *(const float4*)(kp + t0 + 8);
-        float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        if (MODE == A2ATS_W_DIAG) {
-          const double* s = sd + (size_t)kv * kD;
+      for (int k4 = 0; k4 < 8; k4 += 4) {
+        float4 a[4], b[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            x[i] *= (float)s[t0 + i];
-            x[4 + i] *= (float)s[t0 + 8 + i];
+        for (int u = 0; u < 4; ++u) {   // operand element i <-> dimension 16 kt + 8 (i/4) + 4 g + i%4
+          a[u] = *(const float4*)(kp + 16 * (k4 + u) + 4 * g);
+          b[u] = *(const float4*)(kp + 16 * (k4 + u) + 4 * g + 8);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int kt = k4 + u, t0 = 16 * kt + 4 * g;
+          float x[8] = {a[u].x, a[u].y, a[u].z, a[u].w, b[u].x, b[u].y, b[u].z, b[u].w};
+          if (MODE == A2ATS_W_DIAG) {
+            const double* s = sd + (size_t)kv * kD;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              x[i] *= (float)s[t0 + i];
+              x[4 + i] *= (float)s[t0 + 8 + i];
+            }
           }
+          split8(x, zh[tile][kt], zl[tile][kt], zn2[tile]);
         }
-        split8(x, zh[tile][kt], zl[tile][kt], zn2[tile]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
 
-  // main loop: blocks of 32 codewords through a double buffer in LDS
+  // Main loop: blocks of 32 codewords (operands + their 1/2 |c^z|^2) through a double buffer in
+  // LDS.  The accumulators start at 1/2 |c^z|^2 and the stored operands are -c^z, so the matrix
+  // core leaves the score itself.  Ranking: a score only matters if it is below the lane's third
+  // smallest so far, which after the first blocks is rare, so four scores at a time are tested by
+  // their minimum and the insertion is skipped by the whole wave when no lane needs it.  (The
+  // vector ALU issues one instruction per four cycles per SIMD and a product takes 32: ten
+  // instructions per score would cost more than the products.)  Two workgroups share a CU, one wave
+  // of each per SIMD, so one computes while the other waits at its barrier.
   const uint8_t* gblk = cfrag + (size_t)kv * kBlocks * kFragBytes;
   const float* gbias = cbias + (size_t)kv * kCW;
   constexpr int kBuf = kFragBytes + 128;
-  {
-    *(uint4*)(s_mem + tid * 32) = *(const uint4*)(gblk + tid * 32);
-    *(uint4*)(s_mem + tid * 32 + 16) = *(const uint4*)(gblk + tid * 32 + 16);
-    if (tid < 8) *(uint4*)(s_mem + kFragBytes + tid * 16) = *(const uint4*)(gbias + tid * 4);
-  }
-  __syncthreads();
   float s1[2], s2[2], s3[2];
   int c1[2] = {0, 0}, c2[2] = {0, 0};
 #pragma unroll
   for (int tile = 0; tile < 2; ++tile) s1[tile] = s2[tile] = s3[tile] = INFINITY;
+
+  // The loads of the next block are written as asm statements: as ordinary loads the compiler
+  // sinks them past the ranking branches down to their only use, the LDS store before the barrier,
+  // and every step then waits for global memory in the open.  The matching wait is explicit
+  // (loads the compiler does not know of only make its own, counted waits stricter).
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  auto prefetch = [&](int bi, u32x4 (&p)[kFragBytes / 16 / kEncThreads], float& pb) {
+    bi = min(bi, kBlocks - 1);   // the step of the last block loads it once more, unused
+    const uint8_t* src = gblk + (size_t)bi * kFragBytes + tid * 16;
+#pragma unroll
+    for (int i = 0; i < kFragBytes / 16 / kEncThreads; ++i)
+      asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(p[i]) : "v"(src + i * kEncThreads * 16) : "memory");
+    const float* bsrc = gbias + bi * 32 + (tid & 31);
+    asm volatile("global_load_dword %0, %1, off" : "=&v"(pb) : "v"(bsrc) : "memory");
+  };
+  auto stage = [&](int bi, u32x4 (&p)[kFragBytes / 16 / kEncThreads], float& pb) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(p[0]), "+v"(p[1]), "+v"(p[2]), "+v"(p[3]), "+v"(pb)::"memory");
+    uint8_t* dst = s_mem + (bi & 1) * kBuf;
+#pragma unroll
+    for (int i = 0; i < kFragBytes / 16 / kEncThreads; ++i) *(u32x4*)(dst + tid * 16 + i * kEncThreads * 16) = p[i];
+    *(float*)(dst + kFragBytes + (tid & 31) * 4) = pb;   // several threads write each word, all the same
+  };
+  {
+    u32x4 p[kFragBytes / 16 / kEncThreads];
+    float pb;
+    prefetch(0, p, pb);
+    stage(0, p, pb);
+  }
+  __syncthreads();
 #pragma unroll 1
   for (int cb = 0; cb < kBlocks; ++cb) {
+    // The order of the memory operations is pinned (nothing crosses a fence): the next block is
+    // requested from global memory first, and the operands of k-step kt + 1 are requested from
+    // LDS before the six products of k-step kt, so neither latency is waited for in the open.
+    u32x4 p[kFragBytes / 16 / kEncThreads];
+    float pb;
+    prefetch(cb + 1, p, pb);
+    __builtin_amdgcn_sched_barrier(0);
     const uint8_t* blk = s_mem + (cb & 1) * kBuf;
-    uint8_t* nxt = s_mem + ((cb + 1) & 1) * kBuf;
-    uint4 p0, p1, pb;
-    const bool more = cb + 1 < kBlocks;
-    if (more) {
-      const uint8_t* src = gblk + (size_t)(cb + 1) * kFragBytes + tid * 32;
-      p0 = *(const uint4*)src;
-      p1 = *(const uint4*)(src + 16);
-      if (tid < 8) pb = *(const uint4*)(gbias + (cb + 1) * 32 + tid * 4);
+    const uint8_t* fr = blk + lane * 16;
+    bf16x8 a_hi = *(const bf16x8*)fr, a_lo = *(const bf16x8*)(fr + 8 * 1024);
+    // register v of a tile: codeword 32 cb + 8 (v/4) + 4 g + v%4 (the 4 g is added at the end)
+    f32x16 acc0, acc1;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 f = *(const float4*)(blk + kFragBytes + (8 * q + 4 * g) * 4);
+      acc0[4 * q] = acc1[4 * q] = f.x;
+      acc0[4 * q + 1] = acc1[4 * q + 1] = f.y;
+      acc0[4 * q + 2] = acc1[4 * q + 2] = f.z;
+      acc0[4 * q + 3] = acc1[4 * q + 3] = f.w;
     }
-    f32x16 acc0 = {0}, acc1 = {0};
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kt = 0; kt < 8; ++kt) {
-      const bf16x8 a_hi = *(const bf16x8*)(blk + ((0 * 8 + kt) * 64 + lane) * 16);
-      const bf16x8 a_lo = *(const bf16x8*)(blk + ((1 * 8 + kt) * 64 + lane) * 16);
+      bf16x8 n_hi = a_hi, n_lo = a_lo;
+      if (kt < 7) {
+        n_hi = *(const bf16x8*)(fr + (kt + 1) * 1024);
+        n_lo = *(const bf16x8*)(fr + (8 + kt + 1) * 1024);
+      }
+      __builtin_amdgcn_sched_barrier(0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, zh[0][kt], acc0, 0, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, zh[1][kt], acc1, 0, 0, 0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, zl[0][kt], acc0, 0, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, zl[1][kt], acc1, 0, 0, 0);
       acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, zh[0][kt], acc0, 0, 0, 0);
       acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, zh[1][kt], acc1, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      a_hi = n_hi;
+      a_lo = n_lo;
     }
-    // register v of a tile: codeword 32 cb + 8 (v/4) + 4 g + v%4 (the 4 g is added at the end)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const float4 bias = *(const float4*)(blk + kFragBytes + (8 * q + 4 * g) * 4);
-      const float bq[4] = {bias.x, bias.y, bias.z, bias.w};
+      const float m0 = fminf(fminf(acc0[4 * q], acc0[4 * q + 1]), fminf(acc0[4 * q + 2], acc0[4 * q + 3]));
+      if (m0 < s3[0]) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int c = cb * 32 + 8 * q + r;
-        top3_insert(bq[r] - acc0[4 * q + r], c, s1[0], s2[0], s3[0], c1[0], c2[0]);
-        top3_insert(bq[r] - acc1[4 * q + r], c, s1[1], s2[1], s3[1], c1[1], c2[1]);
+        for (int r = 0; r < 4; ++r) top3_insert(acc0[4 * q + r], cb * 32 + 8 * q + r, s1[0], s2[0], s3[0], c1[0], c2[0]);
+      }
+      const float m1 = fminf(fminf(acc1[4 * q], acc1[4 * q + 1]), fminf(acc1[4 * q + 2], acc1[4 * q + 3]));
+      if (m1 < s3[1]) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) top3_insert(acc1[4 * q + r], cb * 32 + 8 * q + r, s1[1], s2[1], s3[1], c1[1], c2[1]);
       }
     }
-    if (more) {
-      *(uint4*)(nxt + tid * 32) = p0;
-      *(uint4*)(nxt + tid * 32 + 16) = p1;
-      if (tid < 8) *(uint4*)(nxt + kFragBytes + tid * 16) = pb;
-    }
+    stage(cb + 1, p, pb);
     __syncthreads();
   }
 
   // The two lane halves of a key column hold disjoint codewords: merge them, decide, flag.
-  const float cmax = cstat[kv * 4 + 0], lf = cstat[kv * 4 + 1];
+  const float cmax = cstat[kv * 4 + 0];
 #pragma unroll
   for (int tile = 0; tile < 2; ++tile) {
     const int a1 = c1[tile] + 4 * g, a2 = c2[tile] + 4 * g;
     const float o1 = __shfl_xor(s1[tile], 32), o2 = __shfl_xor(s2[tile], 32), o3 = __shfl_xor(s3[tile], 32);
     const int b1 = __shfl_xor(a1, 32), b2 = __shfl_xor(a2, 32);
-    const float zn = zn2[tile] + __shfl_xor(zn2[tile], 32), kn = kn2[tile] + __shfl_xor(kn2[tile], 32);
+    const float zn = zn2[tile] + __shfl_xor(zn2[tile], 32);
     // smallest three of the six, with the codes of the first two (equal scores: lower code first)
     float m1 = s1[tile], m2 = s2[tile], m3 = s3[tile];
     int d1 = a1, d2 = a2;
@@ -389,13 +442,13 @@ __global__ __launch_bounds__(kEncThreads) void encode_single_kernel(
       m1 = lt1 ? s : m1;
     }
     const long j = key_first + 32 * tile + col;
-    if (g == 0 && j < n_new) {
-      const float reach = kReach * (sqrtf(zn) + (MODE == A2ATS_W_BLOCK ? sqrtf(kn) * lf : 0.f)) * cmax;
-      codes[(size_t)bkv * ctx_stride + pos0 + j] = (uint16_t)d1;
+    if (g == 0 && j < n_part) {
+      const float reach = kReach * sqrtf(zn) * cmax;
+      codes[(size_t)bkv * ctx_stride + pos0 + j0 + j] = (uint16_t)d1;
       if (!(m2 - m1 > reach)) {
         const uint32_t at = atomicAdd(counter, 1u);
         const uint32_t full = !(m3 - m1 > reach) ? 0x80000000u : 0u;
-        list[2 * (size_t)at] = (uint32_t)((size_t)bkv * n_new + j) | full;
+        list[2 * (size_t)at] = (uint32_t)((size_t)bkv * n_new + j0 + j) | full;
         list[2 * (size_t)at + 1] = (uint32_t)d1 | ((uint32_t)d2 << 16);
       }
     }
@@ -522,7 +575,7 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
   uint8_t* cfrag = base + w.off_cfrag;
   float* cbias = (float*)(base + w.off_cbias);
   float* cstat = (float*)(base + w.off_cstat);
-  uint8_t* Lfrag = base + w.off_Lfrag;
+  float* zbuf = (float*)(base + w.off_z);
   uint32_t* counter = (uint32_t*)(base + w.off_count);
   uint32_t* list = (uint32_t*)(base + w.off_list);
   const int Hkv = d.n_kv_heads, bkv = d.batch * Hkv;
@@ -531,7 +584,7 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
   hipError_t err = allow_dynamic_lds(encode_single_factor_kernel, factor_lds, g_factor_lds);
   if (err != hipSuccess) return err;
   hipLaunchKernelGGL(encode_single_factor_kernel, dim3(Hkv), dim3(256), factor_lds, stream, weights, mode, Lmat,
-                     sd, (uint16_t*)Lfrag, cstat, counter);
+                     sd, cstat, counter);
   if ((err = hipGetLastError()) != hipSuccess) return err;
   hipLaunchKernelGGL(encode_single_codewords_kernel, dim3(kCW / 64, Hkv), dim3(256), 0, stream, codebook, mode,
                      Lmat, sd, czT, (uint16_t*)cfrag, cbias, cstat);
@@ -543,14 +596,26 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
                        (uint16_t*)codes, counter, (const uint32_t*)nullptr, n_all, Hkv, n_new, pos0, d.ctx_stride);
     return hipGetLastError();
   }
-  const dim3 grid((n_new + kKeysPerWG - 1) / kKeysPerWG, bkv), block(kEncThreads);
-#define A2ATS_LAUNCH_ENC1(MODE)                                                                        \
-  hipLaunchKernelGGL((encode_single_kernel<MODE>), grid, block, 0, stream, keys, sd, cfrag, cbias, cstat, \
-                     Lfrag, (uint16_t*)codes, counter, list, Hkv, n_new, pos0, d.ctx_stride)
-  if (mode == A2ATS_W_NONE) A2ATS_LAUNCH_ENC1(A2ATS_W_NONE);
-  else if (mode == A2ATS_W_DIAG) A2ATS_LAUNCH_ENC1(A2ATS_W_DIAG);
-  else A2ATS_LAUNCH_ENC1(A2ATS_W_BLOCK);
-#undef A2ATS_LAUNCH_ENC1
+  if (mode == A2ATS_W_BLOCK) {   // part by part: transform into the buffer, then the plain pass over it
+    for (int j0 = 0; j0 < n_new; j0 += w.chunk) {
+      const int n_part = n_new - j0 < w.chunk ? n_new - j0 : w.chunk;
+      hipLaunchKernelGGL(encode_single_transform_kernel, dim3((n_part + 63) / 64, bkv), dim3(256), 0, stream, keys,
+                         Lmat, zbuf, Hkv, n_new, j0, n_part, w.chunk);
+      if ((err = hipGetLastError()) != hipSuccess) return err;
+      hipLaunchKernelGGL((encode_single_kernel<A2ATS_W_NONE>), dim3((n_part + kKeysPerWG - 1) / kKeysPerWG, bkv),
+                         dim3(kEncThreads), 0, stream, zbuf, sd, cfrag, cbias, cstat, (uint16_t*)codes, counter, list,
+                         Hkv, n_new, pos0, d.ctx_stride, j0, n_part, (int64_t)w.chunk * kD);
+      if ((err = hipGetLastError()) != hipSuccess) return err;
+    }
+  } else {
+    const dim3 grid((n_new + kKeysPerWG - 1) / kKeysPerWG, bkv), block(kEncThreads);
+    if (mode == A2ATS_W_NONE)
+      hipLaunchKernelGGL((encode_single_kernel<A2ATS_W_NONE>), grid, block, 0, stream, keys, sd, cfrag, cbias, cstat,
+                         (uint16_t*)codes, counter, list, Hkv, n_new, pos0, d.ctx_stride, 0, n_new, (int64_t)n_new * kD);
+    else
+      hipLaunchKernelGGL((encode_single_kernel<A2ATS_W_DIAG>), grid, block, 0, stream, keys, sd, cfrag, cbias, cstat,
+                         (uint16_t*)codes, counter, list, Hkv, n_new, pos0, d.ctx_stride, 0, n_new, (int64_t)n_new * kD);
+  }
   if ((err = hipGetLastError()) != hipSuccess) return err;
   const uint32_t re_grid = n_all < 2048u ? n_all : 2048u;
   hipLaunchKernelGGL(encode_single_recheck_kernel, dim3(re_grid), dim3(256), 0, stream, keys, mode, Lmat, sd, czT,
