@@ -120,6 +120,141 @@ def encode_prefill(args, torch, B, synth):
     }))
 
 
+def single_codebook_encode_prefill(args, torch, B, synth, wl):
+    """Prefill side in the paper's own geometry: a2ats_encode_keys over whole sequences under the full
+    D x D query-aware distortion (4096 distances over 128 dimensions per key, on the matrix cores)."""
+    N, Hkv = wl.ctx_len, wl.n_kv_heads
+    hm = synth.make_query_second_moment(wl)
+    cb = synth.make_codebook(wl, "cuda")
+    keys = synth.make_encode_keys(wl, N, device="cuda")
+    dims = B.make_dims(wl.batch, wl.n_q_heads, Hkv, wl.head_dim, 1, N, n_centroids=wl.n_centroids)
+    ws = torch.empty(B.workspace_bytes(dims, B.OP_ENCODE), dtype=torch.uint8, device="cuda")
+    codes = torch.empty(wl.batch, Hkv, N, 1, dtype=torch.int16, device="cuda")
+    w = hm["h_block"].cuda()
+    n_keys = wl.batch * Hkv * N
+    steps, warmup = min(args.steps, 8), min(args.warmup, 2)
+    for _ in range(warmup):
+        B.encode_keys(dims, keys, N, 0, cb, w, B.W_BLOCK, codes, ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        B.encode_keys(dims, keys, N, 0, cb, w, B.W_BLOCK, codes, ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    flop = n_keys * 4096.0 * 128.0 * 2.0           # the contraction [keys x 128] . [128 x 4096]
+    achieved = flop / (ms * 1e-3) / 1e12
+    peak = 2500.0                                  # dense bf16 matrix-core peak, TFLOP/s
+    print(json.dumps({
+        "metric": "encoded keys/s (prefill-side query-aware key encoding, one codebook of 4096, full D x D matrix H)",
+        "value": n_keys / (ms * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 hi/lo split products with f32 accumulate; f64 transform and f64 re-check of near ties",
+        "data": "synthetic",
+        "config": {"workload": wl.name + " encode", "keys": n_keys, "codewords": 4096, "weights": "W_BLOCK"},
+        "roofline": {"kernel": "encode_single_kernel (+ float64 transform, factor, codeword and re-check kernels)",
+                     "bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "executed_bf16_TFLOPs": 3.0 * achieved, "executed_frac": 3.0 * achieved / peak,
+                     "note": "algorithmic flops; each term takes three bf16 products (hi.hi + hi.lo + lo.hi)"},
+    }))
+
+
+def single_codebook_step(args, torch, B, synth, wl):
+    """Decode step in the paper's own geometry (one codebook of 4096 codewords per KV head, 16-bit codes,
+    full D x D matrix H for the appended key)."""
+    R = max(1, args.replicas)
+    N, Bn, Hq, Hkv, D, K, w = wl.ctx_len, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.top_k, wl.window
+    dims = B.make_dims(Bn, Hq, Hkv, D, 1, N, n_centroids=wl.n_centroids)
+    reps = []
+    for r in range(R):
+        x = synth.make_decode_inputs(wl.replace(seed=wl.seed + r), device="cuda")
+        x["new_key"] = x["k"][:, :, N - 1:N, :].float().contiguous()
+        reps.append(x)
+    hm = synth.make_query_second_moment(wl)
+    h_block = hm["h_block"].cuda()
+    st = B.DecodeState(dims, K, w, wl.n_sink, reps[0]["q"].dtype, reps[0]["inv_freq"], wl.wrope_b)
+    enc_ws = torch.empty(B.workspace_bytes(dims, B.OP_ENCODE), dtype=torch.uint8, device="cuda")
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    # the factor of H and the transformed codewords depend on neither the step nor the sequence:
+    # derived once per codebook, outside the steps (every input replica has a codebook of its own)
+    for x in reps:
+        x["enc_ws"] = torch.empty_like(enc_ws)
+        B.encode_prepare(dims, x["codebook"], h_block, B.W_BLOCK, x["enc_ws"])
+
+    def step(i, timed):
+        x = reps[i % R]
+        if timed:
+            ev[i][0].record()
+        B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_block, B.W_BLOCK | B.W_PREPARED, x["codes"],
+                      x["enc_ws"])
+        if timed:
+            ev[i][1].record()
+        B.build_lut(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, st.lut, st.lut_scale)
+        if timed:
+            ev[i][2].record()
+        B.score_topk(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx, st.topk_count,
+                     None, None, st.ws)
+        if timed:
+            ev[i][3].record()
+        B.sparse_attn(dims, x["q"], st.q_rot, x["k"], x["v"], st.topk_idx, st.topk_count, K, w, wl.n_sink,
+                      st.cos_win, st.sin_win, None, st.out, st.ws)
+        if timed:
+            ev[i][4].record()
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, False)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    med = lambda v: float(sorted(v)[len(v) // 2])
+    ph = [med([ev[i][p].elapsed_time(ev[i][p + 1]) * 1e3 for i in range(args.steps)]) for p in range(4)]
+    rows = Bn * Hkv * N
+    kernel_bytes = rows * 2 + Bn * Hq * 4096 * 4 + Bn * Hq * K * 4   # codes once, tables, selected positions
+    achieved = kernel_bytes / (ph[2] * 1e-6) / 1e9
+    out = {
+        "metric": "scored keys/s (whole decode step, single codebook of 4096: encode 1 key + WRoPE/LUT + score/top-K "
+                  "+ sparse attention)",
+        "value": rows / (ms * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "launch": "eager", "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 scores as ordered int32 keys; bf16 K/V with f32 accumulate", "data": "synthetic",
+        "config": {"workload": wl.name, "batch": Bn, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "n_sub": 1,
+                   "codewords": 4096, "ctx_len": N, "top_k": K, "window": w, "replicas_cycled": R},
+        "us_per_decode_step": ms * 1e3,
+        "phase_us_median": {"encode_1key": ph[0], "wrope_lut": ph[1], "score_topk": ph[2], "sparse_attn": ph[3]},
+        "roofline": {"kernel": "select_single_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": kernel_bytes,
+                     "avg_launch_us": ph[2],
+                     "note": "duration = events around the a2ats_score_topk call (one kernel)"},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import oracle as orc
+        x = reps[0]
+        xc = {k: x[k].cpu() for k in ("q", "codes", "k", "v")}
+        cb, inv, nk = x["codebook"].cpu(), x["inv_freq"], x["new_key"].cpu()
+        n_rep, t0 = 0, time.perf_counter()
+        while True:
+            orc.encode_cholesky(nk, cb, hm["h_block"])
+            qrot = orc.rope(xc["q"], inv, wl.wrope_b)
+            sc = orc.scores_explicit(qrot, cb, xc["codes"], N)
+            idx, cnt, kth = orc.topk(sc, K, w, wl.n_sink)
+            orc.sparse_attn(xc["q"], xc["k"], xc["v"], idx, cnt, N, w, wl.n_sink, inv, float(wl.wrope_b))
+            n_rep += 1
+            dt = time.perf_counter() - t0
+            if dt >= args.cpu_baseline_seconds or n_rep >= 64:
+                break
+        out["cpu_baseline"] = {"value": n_rep * rows / dt, "unit": "keys/s", "cores": orc.threads(), "kind": "oracle",
+                               "sample": f"{n_rep} whole decode steps over the full batch of one input replica "
+                                         f"({Bn * Hkv} (sequence, KV head) problems of {N} keys), {dt:.1f} s"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,10 +286,16 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    if wl.n_centroids == 4096:   # the paper's own quantiser geometry: lines of its own
+        if args.encode_prefill:
+            single_codebook_encode_prefill(args, torch, B, synth, wl)
+        else:
+            single_codebook_step(args, torch, B, synth, wl)
+        return
     if args.encode_prefill:
         encode_prefill(args, torch, B, synth)
         return
-    wl = synth.WORKLOADS[args.workload]
     R = max(1, args.replicas)
     dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)
     N, Bn, Hq, Hkv, M, D, K, w = wl.ctx_len, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.n_sub, wl.head_dim, \

@@ -17,9 +17,16 @@
  *     current (query) token at position n - 1 with its key/value/code already cached.
  *   - seq_lens ([dev], nullable, int32 [B]): tokens per sequence, 0 <= seq_lens[b] <=
  *     ctx_len; NULL means every sequence has ctx_len tokens.
- *   - Supported shapes: head_dim == 128, n_centroids == 256, sub_dim in {4, 8}
- *     (n_sub * sub_dim == head_dim), G <= 8, ctx_len <= 2^20, top_k <= 4096.  Anything
- *     else returns A2ATS_ERR_UNSUPPORTED.
+ *   - Supported shapes: head_dim == 128, G <= 8, ctx_len <= 2^20, top_k <= 4096, and one of
+ *     two quantiser geometries:
+ *       product quantisation   n_centroids == 256, sub_dim in {4, 8} (n_sub * sub_dim ==
+ *                              head_dim), one uint8 code per subspace;
+ *       single codebook        n_sub == 1, sub_dim == 128, n_centroids == 4096 (the paper's
+ *                              own setting, section 5.1): one uint16 code per token, so every
+ *                              `codes` argument is read as uint16 [B*Hkv*ctx_stride] (2-byte
+ *                              aligned; its pointer type in the signatures stays uint8_t*).
+ *     Anything else returns A2ATS_ERR_UNSUPPORTED.  Differences of the single-codebook
+ *     geometry are stated with each call ("Single codebook:").
  *
  * Lookup-table format (shared by a2ats_build_lut and a2ats_score_topk)
  *   `lut` is one int32 array of a2ats_lut_elems() words produced by a2ats_build_lut and consumed
@@ -38,6 +45,10 @@
  *   exactly equal and ties resolve by token index.  Its coarse score sum_m coarse[.., codes[j,m],
  *   m, r] fits 16 bits and satisfies  exact = meta[0] + (coarse << s) + rem, 0 <= rem < M * 2^s,
  *   which is what lets the streaming pass filter with 16-bit arithmetic and still be exact.
+ *   Single codebook: a score is one table entry, so `lut` is just [B*Hq][4096] int32 with
+ *   lut[b,h,c] = the float32 value of <q_rot[b,h,:], codebook[kv,0,c,:]> (inner product in
+ *   float64, rounded once) mapped to a signed integer with the same order (bits b of a float
+ *   >= 0 map to b, of a float < 0 to b ^ 0x7fffffff), and lut_scale[b,h] = 1.
  */
 #ifndef A2ATS_H_
 #define A2ATS_H_
@@ -71,6 +82,7 @@ typedef enum a2ats_status {
 
 enum { A2ATS_F32 = 0, A2ATS_BF16 = 1 };                       /* element types of q / k / v / out */
 enum { A2ATS_W_NONE = 0, A2ATS_W_DIAG = 1, A2ATS_W_BLOCK = 2 }; /* encoder distortion              */
+enum { A2ATS_W_PREPARED = 0x100 };   /* flag for weight_mode, see a2ats_encode_prepare */
 enum { A2ATS_OP_ENCODE = 0, A2ATS_OP_LUT = 1, A2ATS_OP_SCORE_TOPK = 2, A2ATS_OP_ATTN = 3 };
 
 int a2ats_version(void);
@@ -111,10 +123,35 @@ int a2ats_rope_tables(int32_t head_dim, const double* inv_freq, int32_t b, int32
  * whenever the two smallest are closer than 1e-4 relative, so codes equal the float64
  * argmin.  The weighted modes need a2ats_workspace_bytes(dims, A2ATS_OP_ENCODE, 0, 0) bytes
  * of workspace (transformed centroids); A2ATS_W_NONE needs none.  n_new == 0 is a no-op.
+ * Single codebook: H is the full D x D matrix (A2ATS_W_BLOCK: weights [dev, f32 Hkv*D*D], the
+ * lower triangle is read) and the argmin is over 4096 codewords of all 128 dimensions:
+ * codes [dev, u16 B*Hkv*ctx_stride].  With the Cholesky factor of section 4.2 (H = L L^T,
+ * z = k L, c^z = c L) the distortion is ||z - c^z||^2; the scores 1/2||c^z||^2 - z.c^z are
+ * formed on the matrix cores from bf16 hi/lo splits of both operands (about 2^-18 relative),
+ * and every key whose two best scores are closer than that arithmetic can tell apart is decided
+ * again in float64, so codes equal the float64 argmin.  Every weight mode needs the workspace
+ * (L and c^z in three forms, 6.4 MB per KV head; a buffer of transformed keys for up to 16384
+ * rows per sequence and KV head; 8 bytes per key that ctx_stride allows); each call derives L
+ * and c^z again unless weight_mode carries A2ATS_W_PREPARED (see a2ats_encode_prepare).  Up to
+ * 8 keys per sequence and KV head (the decode-time append) are decided by float64 sweeps alone.
+ * B*Hkv*n_new must stay below 2^31.
  */
 int a2ats_encode_keys(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
                       const float* codebook, const float* weights, int weight_mode,
                       uint8_t* codes, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The part of a2ats_encode_keys that depends on the codebook and the weights only (paper section
+ * 4.2: the Cholesky factor L of H and the transformed codewords c^z = c L), for callers that
+ * encode against the same codebook and weights many times (one key per decode step).  Fills the
+ * codeword part of `ws`; a later a2ats_encode_keys with the same dims, codebook, weights, mode
+ * and workspace may then pass weight_mode | A2ATS_W_PREPARED to skip that part (it must not have
+ * used `ws` for anything else in between; a2ats_encode_keys itself leaves that part intact).
+ * Product quantisation: returns A2ATS_OK without doing anything, and A2ATS_W_PREPARED is ignored
+ * (the preparation there is a few microseconds).  Arguments as in a2ats_encode_keys.
+ */
+int a2ats_encode_prepare(const a2ats_dims* dims, const float* codebook, const float* weights,
+                         int weight_mode, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Steps 1-2 of a decode step (paper section 4.1: q~ = q R_b; section 4.2 last equation /
@@ -127,6 +164,7 @@ int a2ats_encode_keys(const a2ats_dims* dims, const float* keys, int32_t n_new, 
  *   lut       [dev, out, int32 a2ats_lut_elems()]   see "Lookup-table format" (16-byte aligned)
  *   lut_scale [dev, out, f32 B*Hq]
  * Inner products are accumulated in float64.  Needs no workspace.
+ * Single codebook: codebook [dev, f32 Hkv*4096*D]; see "Lookup-table format".
  */
 int a2ats_build_lut(const a2ats_dims* dims, const void* q, int q_dtype, const float* cos_b,
                     const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
@@ -138,7 +176,8 @@ int a2ats_build_lut(const a2ats_dims* dims, const void* q, int q_dtype, const fl
  * a2ats_build_lut in one launch.  The two do not depend on each other: the appended code rows are
  * at positions pos0 .. pos0 + n_new - 1.  Arguments, layouts and results are exactly those of the
  * two calls; needs no workspace; n_new > 32 returns A2ATS_ERR_UNSUPPORTED, n_new == 0 builds the
- * tables only (keys / codes may then be NULL).
+ * tables only (keys / codes may then be NULL).  Single codebook: A2ATS_ERR_UNSUPPORTED (its
+ * encoder needs a workspace; call a2ats_encode_keys and a2ats_build_lut).
  */
 int a2ats_decode_prologue(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
                           const float* codebook, const float* weights, int weight_mode,
@@ -162,6 +201,9 @@ int a2ats_decode_prologue(const a2ats_dims* dims, const float* keys, int32_t n_n
  *   scores_out [dev, out, nullable, f32 B*Hq*ctx_stride] debug: every token's score
  *              (positions >= n are not written)
  * top_k == 0 is allowed.  window >= 0, n_sink >= 0.
+ * Single codebook: codes [dev, u16 B*Hkv*ctx_stride]; a score is the table entry of the token's
+ * code, there are at most 4096 distinct scores per head and ties (by position) decide most
+ * selections; needs no workspace (a2ats_workspace_bytes returns 0) and lut_scale is not read.
  */
 int a2ats_score_topk(const a2ats_dims* dims, const uint8_t* codes, const int32_t* lut,
                      const float* lut_scale, int32_t top_k, int32_t window, int32_t n_sink,

@@ -17,8 +17,9 @@ LIB_PATH = os.path.join(_HERE, "liba2ats.so")
 
 F32, BF16 = 0, 1
 W_NONE, W_DIAG, W_BLOCK = 0, 1, 2
+W_PREPARED = 0x100
 OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN = 0, 1, 2, 3
-EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes",
+EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes", "a2ats_encode_prepare",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel",
            "a2ats_decode_prologue"]
@@ -61,6 +62,8 @@ def lib() -> ctypes.CDLL:
         L.a2ats_encode_keys.restype = ctypes.c_int
         L.a2ats_encode_keys.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, sz, vp]
         L.a2ats_build_lut.restype = ctypes.c_int
+        L.a2ats_encode_prepare.argtypes = [dp, vp, vp, ctypes.c_int, vp, sz, vp]
+        L.a2ats_encode_prepare.restype = ctypes.c_int
         L.a2ats_build_lut.argtypes = [dp, vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
         L.a2ats_decode_prologue.restype = ctypes.c_int
         L.a2ats_decode_prologue.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp,
@@ -147,6 +150,12 @@ def encode_keys(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, weig
                                  weight_mode, _ptr(codes), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
                                  _stream())
     _check(rc, "a2ats_encode_keys")
+
+
+def encode_prepare(dims: Dims, codebook, weights, weight_mode: int, ws: torch.Tensor):
+    rc = lib().a2ats_encode_prepare(ctypes.byref(dims), _ptr(codebook), _ptr(weights), weight_mode, _ptr(ws),
+                                    ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_encode_prepare")
 
 
 def build_lut(dims: Dims, q, cos_b, sin_b, codebook, q_rot, lut, lut_scale):

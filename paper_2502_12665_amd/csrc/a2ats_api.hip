@@ -101,6 +101,8 @@ int a2ats_encode_keys(const a2ats_dims* d, const float* keys, int32_t n_new, int
   int rc = check_dims(d);
   if (rc != A2ATS_OK) return rc;
   if (n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride) return A2ATS_ERR_INVALID_ARG;
+  const bool prepared = (weight_mode & A2ATS_W_PREPARED) != 0;
+  weight_mode &= ~A2ATS_W_PREPARED;
   if (weight_mode != A2ATS_W_NONE && weight_mode != A2ATS_W_DIAG && weight_mode != A2ATS_W_BLOCK)
     return A2ATS_ERR_INVALID_ARG;
   if (!keys || !codebook || !codes) return A2ATS_ERR_INVALID_ARG;
@@ -109,8 +111,8 @@ int a2ats_encode_keys(const a2ats_dims* d, const float* keys, int32_t n_new, int
   if (a2ats::single_codebook(*d)) {   // every weighting goes through the transformed codewords
     if (!ws || misaligned16(ws) || ws_bytes < a2ats::encode_single_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
     if ((int64_t)d->batch * d->n_kv_heads * (int64_t)n_new >= (1LL << 31)) return A2ATS_ERR_UNSUPPORTED;
-    const hipError_t e = a2ats::launch_encode_single(*d, keys, n_new, pos0, codebook, weights, weight_mode, codes,
-                                                     ws, (hipStream_t)stream);
+    const hipError_t e = a2ats::launch_encode_single(*d, keys, n_new, pos0, codebook, weights, weight_mode,
+                                                     prepared, codes, ws, (hipStream_t)stream);
     return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
   }
   if (weight_mode != A2ATS_W_NONE) {
@@ -120,6 +122,20 @@ int a2ats_encode_keys(const a2ats_dims* d, const float* keys, int32_t n_new, int
   if ((int64_t)n_new > 65535LL * 256) return A2ATS_ERR_UNSUPPORTED;
   const hipError_t e = a2ats::launch_encode(*d, keys, n_new, pos0, codebook, weights, weight_mode, codes,
                                             weight_mode != A2ATS_W_NONE ? ws : nullptr, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_encode_prepare(const a2ats_dims* d, const float* codebook, const float* weights, int weight_mode,
+                         void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (weight_mode != A2ATS_W_NONE && weight_mode != A2ATS_W_DIAG && weight_mode != A2ATS_W_BLOCK)
+    return A2ATS_ERR_INVALID_ARG;
+  if (!codebook || misaligned16(codebook)) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE && !weights) return A2ATS_ERR_INVALID_ARG;
+  if (!a2ats::single_codebook(*d)) return A2ATS_OK;   // nothing worth keeping between calls
+  if (!ws || misaligned16(ws) || ws_bytes < a2ats::encode_single_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
+  const hipError_t e = a2ats::launch_encode_single_prepare(*d, codebook, weights, weight_mode, ws, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 

@@ -44,6 +44,7 @@ constexpr int kFragBytes = 2 * 8 * 64 * 16;   // (hi, lo) x 8 k-steps x 64 lanes
 constexpr int kBlocks = kCW / 32;       // streamed 32-codeword blocks
 static_assert(kFragBytes / 16 / kEncThreads == 4, "a thread stages four 16-byte pieces of a block");
 constexpr int kFewSingle = 8;           // at most this many keys per (sequence, KV head): float64 sweep only
+constexpr int kSlices = 16;             // workgroups sharing the codewords of one such key
 constexpr float kReach = 1.5e-5f;       // rounding reach of a score, relative to |z| max|c^z|
 constexpr int kChunk = 16384;           // keys per (sequence, KV head) transformed at a time
 
@@ -51,7 +52,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 struct EncWs {
-  size_t off_L, off_sd, off_czT, off_cfrag, off_cbias, off_cstat, off_z, off_count, off_list, bytes;
+  size_t off_L, off_sd, off_czT, off_cfrag, off_cbias, off_cstat, off_z, off_count, off_list, off_part, bytes;
   int chunk;   // keys per (sequence, KV head) the transform buffer holds
 };
 
@@ -75,6 +76,7 @@ EncWs enc_single_ws(const a2ats_dims& d) {
   w.off_z = take((size_t)d.batch * Hkv * w.chunk * kD * sizeof(float));
   w.off_count = take(sizeof(uint32_t));
   w.off_list = take(keys_max * 2 * sizeof(uint32_t));
+  w.off_part = take((size_t)d.batch * Hkv * kFewSingle * kSlices * 2 * sizeof(double));
   w.bytes = o;
   return w;
 }
@@ -95,11 +97,10 @@ __device__ __forceinline__ void frag_slot(int t, int& kt, int& g, int& i) {
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void encode_single_factor_kernel(
     const float* __restrict__ weights, int mode, double* __restrict__ Lmat, double* __restrict__ sd,
-    float* __restrict__ cstat, uint32_t* __restrict__ counter) {
+    float* __restrict__ cstat) {
   extern __shared__ double s_A[];   // 128 x 128, lower triangle in use
   __shared__ double s_red[256];
   const int kv = blockIdx.x, tid = threadIdx.x;
-  if (kv == 0 && tid == 0) *counter = 0;
   double* L = Lmat + (size_t)kv * kD * kD;
   if (mode != A2ATS_W_BLOCK) {
     if (tid < kD) sd[(size_t)kv * kD + tid] = mode == A2ATS_W_DIAG ? sqrt((double)weights[(size_t)kv * kD + tid]) : 1.0;
@@ -557,15 +558,118 @@ __global__ __launch_bounds__(256) void encode_single_recheck_kernel(
   }
 }
 
+__global__ void encode_single_clear_kernel(uint32_t* counter) { *counter = 0; }
+
+// The few-key (append) route: every key is decided by a float64 sweep, its 4096 codewords split
+// over kSlices workgroups (one workgroup would read 4 MB of transformed codewords by itself).
+// part[key][slice] = {smallest distortion of the slice, its code as a double}.
+__global__ __launch_bounds__(1024) void encode_single_sweep_kernel(
+    const float* __restrict__ keys, int mode, const double* __restrict__ Lmat, const double* __restrict__ sd,
+    const double* __restrict__ czT, double* __restrict__ part, int Hkv, int n_new) {
+  constexpr int PER = kCW / kSlices;   // codewords per slice
+  static_assert(PER == 256, "a thread owns one codeword and a quarter of the dimensions");
+  __shared__ double s_k[kD], s_z[kD], s_p[4][PER];
+  __shared__ int s_i[PER];
+  const int tid = threadIdx.x, slice = blockIdx.y, key = blockIdx.x;
+  const int bkv = key / n_new, kv = bkv % Hkv;
+  if (tid < kD) s_k[tid] = (double)keys[(size_t)key * kD + tid];
+  __syncthreads();
+  if (tid < kD) {
+    double z;
+    if (mode == A2ATS_W_BLOCK) {   // z_t = sum_{r >= t} k_r L[r][t]; the loads do not depend on each other
+      const double* L = Lmat + (size_t)kv * kD * kD + tid;
+      double z0 = 0.0, z1 = 0.0;
+#pragma unroll 16
+      for (int r = 0; r < kD; r += 2) {
+        z0 += s_k[r] * L[(size_t)r * kD];
+        z1 += s_k[r + 1] * L[(size_t)(r + 1) * kD];
+      }
+      z = z0 + z1;   // (entries above the diagonal are zero)
+    } else {
+      z = s_k[tid] * sd[(size_t)kv * kD + tid];
+    }
+    s_z[tid] = z;
+  }
+  __syncthreads();
+  // thread = (codeword, quarter of the dimensions): 32 independent loads each, 16 in flight
+  const int cl = tid & (PER - 1), tq = tid >> 8, c = slice * PER + cl;
+  const double* cz = czT + ((size_t)kv * kD + 32 * tq) * kCW + c;
+  double d0 = 0.0, d1 = 0.0;
+#pragma unroll 16
+  for (int t = 0; t < 32; t += 2) {
+    const double e0 = s_z[32 * tq + t] - cz[(size_t)t * kCW], e1 = s_z[32 * tq + t + 1] - cz[(size_t)(t + 1) * kCW];
+    d0 += e0 * e0;
+    d1 += e1 * e1;
+  }
+  s_p[tq][cl] = d0 + d1;
+  __syncthreads();
+  if (tid < PER) {
+    s_p[0][tid] = (s_p[0][tid] + s_p[1][tid]) + (s_p[2][tid] + s_p[3][tid]);
+    s_i[tid] = c;
+  }
+  __syncthreads();
+  for (int s = PER / 2; s >= 1; s >>= 1) {
+    if (tid < s) {
+      const double o = s_p[0][tid + s];
+      const int oi = s_i[tid + s];
+      if (o < s_p[0][tid] || (o == s_p[0][tid] && oi < s_i[tid])) {
+        s_p[0][tid] = o;
+        s_i[tid] = oi;
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    part[((size_t)key * kSlices + slice) * 2] = s_p[0][0];
+    part[((size_t)key * kSlices + slice) * 2 + 1] = (double)s_i[0];
+  }
+}
+
+__global__ void encode_single_sweep_pick_kernel(const double* __restrict__ part, uint16_t* __restrict__ codes,
+                                                uint32_t n_all, int n_new, int pos0, int64_t ctx_stride) {
+  const uint32_t key = blockIdx.x * blockDim.x + threadIdx.x;
+  if (key >= n_all) return;
+  double best = part[(size_t)key * kSlices * 2];
+  int arg = (int)part[(size_t)key * kSlices * 2 + 1];
+  for (int s = 1; s < kSlices; ++s) {   // slices hold ascending codes: strict < keeps the lower code
+    const double d = part[((size_t)key * kSlices + s) * 2];
+    if (d < best) {
+      best = d;
+      arg = (int)part[((size_t)key * kSlices + s) * 2 + 1];
+    }
+  }
+  const int bkv = (int)(key / (uint32_t)n_new), j = (int)(key % (uint32_t)n_new);
+  codes[(size_t)bkv * ctx_stride + pos0 + j] = (uint16_t)arg;
+}
+
 LdsSlot g_factor_lds[16];
 
 }  // namespace
 
 size_t encode_single_ws_bytes(const a2ats_dims& d) { return enc_single_ws(d).bytes; }
 
+hipError_t launch_encode_single_prepare(const a2ats_dims& d, const float* codebook, const float* weights, int mode,
+                                        void* ws, hipStream_t stream) {
+  const EncWs w = enc_single_ws(d);
+  uint8_t* base = (uint8_t*)ws;
+  double* Lmat = (double*)(base + w.off_L);
+  double* sd = (double*)(base + w.off_sd);
+  float* cstat = (float*)(base + w.off_cstat);
+  const size_t factor_lds = (size_t)kD * kD * sizeof(double);
+  hipError_t err = allow_dynamic_lds(encode_single_factor_kernel, factor_lds, g_factor_lds);
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(encode_single_factor_kernel, dim3(d.n_kv_heads), dim3(256), factor_lds, stream, weights, mode,
+                     Lmat, sd, cstat);
+  if ((err = hipGetLastError()) != hipSuccess) return err;
+  hipLaunchKernelGGL(encode_single_codewords_kernel, dim3(kCW / 64, d.n_kv_heads), dim3(256), 0, stream, codebook,
+                     mode, Lmat, sd, (double*)(base + w.off_czT), (uint16_t*)(base + w.off_cfrag),
+                     (float*)(base + w.off_cbias), cstat);
+  return hipGetLastError();
+}
+
 hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_new, int pos0,
-                                const float* codebook, const float* weights, int mode, void* codes, void* ws,
-                                hipStream_t stream) {
+                                const float* codebook, const float* weights, int mode, bool prepared, void* codes,
+                                void* ws, hipStream_t stream) {
   if (n_new == 0 || d.batch == 0) return hipSuccess;
   const EncWs w = enc_single_ws(d);
   uint8_t* base = (uint8_t*)ws;
@@ -578,24 +682,23 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
   float* zbuf = (float*)(base + w.off_z);
   uint32_t* counter = (uint32_t*)(base + w.off_count);
   uint32_t* list = (uint32_t*)(base + w.off_list);
+  double* part = (double*)(base + w.off_part);
   const int Hkv = d.n_kv_heads, bkv = d.batch * Hkv;
-
-  const size_t factor_lds = (size_t)kD * kD * sizeof(double);
-  hipError_t err = allow_dynamic_lds(encode_single_factor_kernel, factor_lds, g_factor_lds);
-  if (err != hipSuccess) return err;
-  hipLaunchKernelGGL(encode_single_factor_kernel, dim3(Hkv), dim3(256), factor_lds, stream, weights, mode, Lmat,
-                     sd, cstat, counter);
-  if ((err = hipGetLastError()) != hipSuccess) return err;
-  hipLaunchKernelGGL(encode_single_codewords_kernel, dim3(kCW / 64, Hkv), dim3(256), 0, stream, codebook, mode,
-                     Lmat, sd, czT, (uint16_t*)cfrag, cbias, cstat);
-  if ((err = hipGetLastError()) != hipSuccess) return err;
+  hipError_t err;
+  if (!prepared && (err = launch_encode_single_prepare(d, codebook, weights, mode, ws, stream)) != hipSuccess)
+    return err;
 
   const uint32_t n_all = (uint32_t)((size_t)bkv * n_new);
   if (n_new <= kFewSingle) {
-    hipLaunchKernelGGL(encode_single_recheck_kernel, dim3(n_all), dim3(256), 0, stream, keys, mode, Lmat, sd, czT,
-                       (uint16_t*)codes, counter, (const uint32_t*)nullptr, n_all, Hkv, n_new, pos0, d.ctx_stride);
+    hipLaunchKernelGGL(encode_single_sweep_kernel, dim3(n_all, kSlices), dim3(1024), 0, stream, keys, mode, Lmat, sd,
+                       czT, part, Hkv, n_new);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+    hipLaunchKernelGGL(encode_single_sweep_pick_kernel, dim3((n_all + 63) / 64), dim3(64), 0, stream, part,
+                       (uint16_t*)codes, n_all, n_new, pos0, d.ctx_stride);
     return hipGetLastError();
   }
+  hipLaunchKernelGGL(encode_single_clear_kernel, dim3(1), dim3(1), 0, stream, counter);
+  if ((err = hipGetLastError()) != hipSuccess) return err;
   if (mode == A2ATS_W_BLOCK) {   // part by part: transform into the buffer, then the plain pass over it
     for (int j0 = 0; j0 < n_new; j0 += w.chunk) {
       const int n_part = n_new - j0 < w.chunk ? n_new - j0 : w.chunk;

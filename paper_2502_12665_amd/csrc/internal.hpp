@@ -83,8 +83,10 @@ hipError_t launch_score_topk_single(const a2ats_dims& d, const void* codes, cons
 hipError_t launch_encode(const a2ats_dims& d, const float* keys, int n_new, int pos0, const float* codebook,
                          const float* weights, int mode, uint8_t* codes, void* ws, hipStream_t stream);
 size_t encode_single_ws_bytes(const a2ats_dims& d);
+hipError_t launch_encode_single_prepare(const a2ats_dims& d, const float* codebook, const float* weights, int mode,
+                                        void* ws, hipStream_t stream);
 hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_new, int pos0,
-                                const float* codebook, const float* weights, int mode, void* codes, void* ws,
-                                hipStream_t stream);
+                                const float* codebook, const float* weights, int mode, bool prepared, void* codes,
+                                void* ws, hipStream_t stream);
 
 }  // namespace a2ats

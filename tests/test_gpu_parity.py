@@ -429,6 +429,13 @@ def test_single_codebook_encode(oracle, mode):
             want, b1, b2 = oracle.encode(keys, cb, weights, code, want_margins=True)
         n_near = H.compare_codes(got[:, :, pos0:pos0 + n_new], want, b1, b2)
         assert (got[:, :, :pos0] == 0x7EEE).all() and (got[:, :, pos0 + n_new:] == 0x7EEE).all()
+        # the same call on a prepared workspace (factor and transformed codewords kept) gives the same codes
+        again = torch.full_like(codes, 0x7EEE)
+        B.encode_prepare(dims, cb.cuda(), None if weights is None else weights.cuda(), code, ws)
+        B.encode_keys(dims, keys.cuda(), n_new, pos0, cb.cuda(), None if weights is None else weights.cuda(),
+                      code | B.W_PREPARED, again, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(again, codes)
         if kind == "planted":
             assert ((got[:, :, pos0:pos0 + 50] == 5) | (want[:, :, :50] != 5)).all()
             close = ((b2 - b1) <= 1e-3 * np.maximum(1.0, b2)).mean()
