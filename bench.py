@@ -255,6 +255,85 @@ def single_codebook_step(args, torch, B, synth, wl):
     print(json.dumps(out))
 
 
+def group_shared_step(args, torch, B, synth, wl):
+    """Decode step with ONE selection per KV head (the group's summed score): shared tables, score/top-K
+    over Hkv table heads, attention of all query heads over the shared rows."""
+    R = max(1, args.replicas)
+    N, Bn, Hq, Hkv, M, D, K, w = wl.ctx_len, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.n_sub, wl.head_dim, \
+        wl.top_k, wl.window
+    dims = B.make_dims(Bn, Hq, Hkv, D, M, N)
+    dims_kv = B.make_dims(Bn, Hkv, Hkv, D, M, N)
+    reps = []
+    for r in range(R):
+        x = synth.make_decode_inputs(wl.replace(seed=wl.seed + r), device="cuda")
+        x["new_key"] = x["k"][:, :, N - 1:N, :].float().contiguous()
+        reps.append(x)
+    h_diag = synth.make_query_second_moment(wl)["h_diag"].cuda()
+    st = B.DecodeState(dims, K, w, wl.n_sink, reps[0]["q"].dtype, reps[0]["inv_freq"], wl.wrope_b)
+    sk = B.DecodeState(dims_kv, K, w, wl.n_sink, reps[0]["q"].dtype, reps[0]["inv_freq"], wl.wrope_b)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    kev = HipEvents(args.steps)
+
+    def step(i, timed):
+        x = reps[i % R]
+        if timed:
+            ev[i][0].record()
+        B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
+        if timed:
+            ev[i][1].record()
+        B.build_lut_shared(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, sk.lut, sk.lut_scale)
+        if timed:
+            ev[i][2].record()
+            B.profile_stream_kernel(*kev.pair(i))
+        B.score_topk(dims_kv, x["codes"], sk.lut, sk.lut_scale, K, w, wl.n_sink, None, sk.topk_idx, sk.topk_count,
+                     None, None, sk.ws)
+        if timed:
+            ev[i][3].record()
+        B.sparse_attn_shared(dims, x["q"], st.q_rot, x["k"], x["v"], sk.topk_idx, sk.topk_count, K, w, wl.n_sink,
+                             st.cos_win, st.sin_win, None, st.out, st.ws)
+        if timed:
+            ev[i][4].record()
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, False)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    for i in range(args.steps):
+        step(i, True)
+    torch.cuda.synchronize()
+    B.profile_stream_kernel(None, None)
+    med = lambda v: float(sorted(v)[len(v) // 2])
+    ph = [med([ev[i][p].elapsed_time(ev[i][p + 1]) * 1e3 for i in range(args.steps)]) for p in range(4)]
+    k_us = sum(kev.elapsed_ms(i) * 1e3 for i in range(args.steps)) / args.steps
+    rows = Bn * Hkv * N
+    kernel_bytes = rows * M + Bn * Hkv * M * 256 * 4
+    e = 2 if wl.kv_dtype == "bf16" else 4
+    attn_bytes = Bn * Hkv * min(K, N - w) * 2 * D * e + Bn * Hkv * w * 2 * D * e   # rows once per KV head
+    achieved = kernel_bytes / (k_us * 1e-6) / 1e9
+    print(json.dumps({
+        "metric": "scored keys/s (whole decode step, one selection per KV head: encode 1 key + WRoPE/shared LUT + "
+                  "score/top-K + sparse attention over shared rows)",
+        "value": rows / (ms * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "launch": "eager", "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 fixed-point scores; bf16 K/V with f32 accumulate" if wl.kv_dtype == "bf16" else
+                 "int32 fixed-point scores; f32 K/V",
+        "data": "synthetic",
+        "config": {"workload": wl.name + ", selection shared by the query heads of a KV head", "batch": Bn,
+                   "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "n_sub": M, "ctx_len": N, "top_k": K,
+                   "window": w, "replicas_cycled": R},
+        "us_per_decode_step": ms * 1e3,
+        "phase_us_median": {"encode_1key": ph[0], "wrope_shared_lut": ph[1], "score_topk": ph[2], "sparse_attn": ph[3]},
+        "sparse_attn_phase": {"algorithmic_bytes": attn_bytes, "GBps": attn_bytes / (ph[3] * 1e-6) / 1e9},
+        "roofline": {"kernel": "stream_select_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": kernel_bytes, "avg_launch_us": k_us},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -271,6 +350,9 @@ def main():
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run 3 plain float32 copies (out = in + 0) of this many MiB, so that a "
                          "rocprofv3 --pmc run of this command holds a kernel of known HBM traffic")
+    ap.add_argument("--group-shared", action="store_true",
+                    help="one selection per KV head (sum of the group's scores) instead of one per query head; "
+                         "prints a line of its own")
     ap.add_argument("--encode-prefill", action="store_true",
                     help="measure the prefill-side key encoder (configuration 5 geometry, 8 of its 32 "
                          "sequences) instead of the decode step, and print its own JSON line")
@@ -295,6 +377,9 @@ def main():
         return
     if args.encode_prefill:
         encode_prefill(args, torch, B, synth)
+        return
+    if args.group_shared:
+        group_shared_step(args, torch, B, synth, wl)
         return
     R = max(1, args.replicas)
     dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)

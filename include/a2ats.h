@@ -232,6 +232,33 @@ int a2ats_sparse_attn(const a2ats_dims* dims, const void* q, const float* q_rot,
                       const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Selection shared by the query heads of a KV head (grouped-query attention; the paper selects
+ * "for each attention head" and does not say which kind, so per query head is the reading of the
+ * calls above and this is the alternative): the group's score of a token is the SUM over the G
+ * query heads of the approximate scores of section 4.2, sum_g q~_g . c_{s_j} = (sum_g q~_g) . c_{s_j};
+ * one top-K per KV head; all G heads attend the same retrieved rows, which are then fetched from
+ * HBM once per KV head instead of once per query head.
+ *   a2ats_build_lut_shared   as a2ats_build_lut, but `lut` / `lut_scale` describe ONE table head per
+ *                            KV head, built from the float32 sum of the G rotated queries: they have
+ *                            the format and size of a2ats_build_lut for dims with n_q_heads set to
+ *                            n_kv_heads (lut_scale [B*Hkv]).  q_rot is still [B*Hq*D], per head.
+ *   a2ats_score_topk         is then called with those dims (n_q_heads = n_kv_heads):
+ *                            topk_idx [B*Hkv*top_k], topk_count [B*Hkv].
+ *   a2ats_sparse_attn_shared as a2ats_sparse_attn with the real dims, topk_idx / topk_count per KV
+ *                            head as above; workspace as A2ATS_OP_ATTN.
+ * Product quantisation only (A2ATS_ERR_UNSUPPORTED for the single codebook).
+ */
+int a2ats_build_lut_shared(const a2ats_dims* dims, const void* q, int q_dtype, const float* cos_b,
+                           const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
+                           float* lut_scale, void* stream);
+int a2ats_sparse_attn_shared(const a2ats_dims* dims, const void* q, const float* q_rot,
+                             const void* k_cache, const void* v_cache, int kv_dtype,
+                             const int32_t* topk_idx, const int32_t* topk_count, int32_t top_k,
+                             int32_t window, int32_t n_sink, const float* cos_win,
+                             const float* sin_win, const int32_t* seq_lens, void* out, void* ws,
+                             size_t ws_bytes, void* stream);
+
+/*
  * Diagnostics (not part of the method): after an a2ats_score_topk call with the same dims /
  * top_k / window / n_sink and the same `ws`, write per head into cand_counts [dev, out, uint32
  * B*Hq] (asynchronously, on `stream`): bits 0-27 the number of rows the streaming pass kept

@@ -140,6 +140,20 @@ def scores_lut(lut_, codes, n_kv_heads: int, n_ctx: int) -> np.ndarray:
     return out
 
 
+def group_scores(scores, n_kv_heads: int) -> np.ndarray:
+    """[B,Hkv,N]: the scores of the G query heads of each KV head added up (grouped-query
+    attention with one selection per KV head; section 4 selects per attention head and leaves
+    the grouped case open -- the sum is this build's reading, stated in the design notes).
+    Query head h belongs to KV head h // G."""
+    s = _f64(scores)
+    B, Hq, N = s.shape
+    G = Hq // n_kv_heads
+    out = np.zeros((B, n_kv_heads, N), dtype=np.float64)
+    for g in range(G):                       # plain left-to-right sum over the group
+        out += s[:, [kv * G + g for kv in range(n_kv_heads)], :]
+    return out
+
+
 def topk(scores, top_k: int, window: int, n_sink: int = 0, seq_lens=None
          ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Full-sort top-K: (idx [B,Hq,K] ascending / -1 padded, count [B,Hq], kth score [B,Hq])."""

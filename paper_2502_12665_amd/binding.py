@@ -22,7 +22,7 @@ OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN = 0, 1, 2, 3
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes", "a2ats_encode_prepare",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel",
-           "a2ats_decode_prologue"]
+           "a2ats_decode_prologue", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared"]
 
 
 class A2atsError(RuntimeError):
@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.a2ats_sparse_attn.restype = ctypes.c_int
         L.a2ats_sparse_attn.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, vp,
                                         vp, vp, vp, sz, vp]
+        L.a2ats_sparse_attn_shared.restype = ctypes.c_int
+        L.a2ats_sparse_attn_shared.argtypes = L.a2ats_sparse_attn.argtypes
+        L.a2ats_build_lut_shared.restype = ctypes.c_int
+        L.a2ats_build_lut_shared.argtypes = L.a2ats_build_lut.argtypes
         L.a2ats_score_topk_stats.restype = ctypes.c_int
         L.a2ats_score_topk_stats.argtypes = [dp, i32, i32, i32, vp, vp, vp]
         L.a2ats_profile_stream_kernel.restype = None
@@ -190,6 +194,24 @@ def sparse_attn(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_count, to
                                  _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _ptr(ws),
                                  0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_sparse_attn")
+
+
+def build_lut_shared(dims: Dims, q, cos_b, sin_b, codebook, q_rot, lut, lut_scale):
+    """Tables of one head per KV head from the summed rotated queries of its group (lut / lut_scale
+    sized for dims with n_q_heads = n_kv_heads); q_rot per query head."""
+    rc = lib().a2ats_build_lut_shared(ctypes.byref(dims), _ptr(q), _dtype_code(q), _ptr(cos_b), _ptr(sin_b),
+                                      _ptr(codebook), _ptr(q_rot), _ptr(lut), _ptr(lut_scale), _stream())
+    _check(rc, "a2ats_build_lut_shared")
+
+
+def sparse_attn_shared(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k: int, window: int,
+                       n_sink: int, cos_win, sin_win, seq_lens, out, ws: Optional[torch.Tensor] = None):
+    """sparse_attn with one selection per KV head (topk_idx [B,Hkv,K], topk_count [B,Hkv])."""
+    rc = lib().a2ats_sparse_attn_shared(ctypes.byref(dims), _ptr(q), _ptr(q_rot), _ptr(k_cache), _ptr(v_cache),
+                                        _dtype_code(k_cache), _ptr(topk_idx), _ptr(topk_count), top_k, window,
+                                        n_sink, _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _ptr(ws),
+                                        0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_sparse_attn_shared")
 
 
 def score_topk_stats(dims: Dims, top_k: int, window: int, n_sink: int, ws, cand_counts):

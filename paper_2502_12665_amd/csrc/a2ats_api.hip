@@ -155,6 +155,20 @@ int a2ats_build_lut(const a2ats_dims* d, const void* q, int q_dtype, const float
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
+int a2ats_build_lut_shared(const a2ats_dims* d, const void* q, int q_dtype, const float* cos_b,
+                           const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
+                           float* lut_scale, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
+  if (!q || !cos_b || !sin_b || !codebook || !q_rot || !lut || !lut_scale) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(codebook) || misaligned16(lut)) return A2ATS_ERR_INVALID_ARG;
+  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
+  const hipError_t e = a2ats::launch_build_lut_shared(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut,
+                                                      lut_scale, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
 int a2ats_decode_prologue(const a2ats_dims* d, const float* keys, int32_t n_new, int32_t pos0,
                           const float* codebook, const float* weights, int weight_mode, uint8_t* codes,
                           const void* q, int q_dtype, const float* cos_b, const float* sin_b, float* q_rot,
@@ -205,11 +219,11 @@ int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* l
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
-int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
-                      const void* v_cache, int kv_dtype, const int32_t* topk_idx, const int32_t* topk_count,
-                      int32_t top_k, int32_t window, int32_t n_sink, const float* cos_win,
-                      const float* sin_win, const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes,
-                      void* stream) {
+static int sparse_attn_impl(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
+                            const void* v_cache, int kv_dtype, const int32_t* topk_idx,
+                            const int32_t* topk_count, int32_t top_k, int32_t window, int32_t n_sink,
+                            const float* cos_win, const float* sin_win, const int32_t* seq_lens, void* out,
+                            void* ws, size_t ws_bytes, bool shared, void* stream) {
   int rc = check_dims(d);
   if (rc != A2ATS_OK) return rc;
   if (kv_dtype != A2ATS_F32 && kv_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
@@ -223,8 +237,26 @@ int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, co
   if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
   const hipError_t e = a2ats::launch_sparse_attn(*d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx,
                                                  topk_count, top_k, window, n_sink, cos_win, sin_win,
-                                                 seq_lens, out, ws, (hipStream_t)stream);
+                                                 seq_lens, out, ws, shared, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
+                      const void* v_cache, int kv_dtype, const int32_t* topk_idx, const int32_t* topk_count,
+                      int32_t top_k, int32_t window, int32_t n_sink, const float* cos_win,
+                      const float* sin_win, const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes,
+                      void* stream) {
+  return sparse_attn_impl(d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx, topk_count, top_k, window, n_sink,
+                          cos_win, sin_win, seq_lens, out, ws, ws_bytes, false, stream);
+}
+
+int a2ats_sparse_attn_shared(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
+                             const void* v_cache, int kv_dtype, const int32_t* topk_idx,
+                             const int32_t* topk_count, int32_t top_k, int32_t window, int32_t n_sink,
+                             const float* cos_win, const float* sin_win, const int32_t* seq_lens, void* out,
+                             void* ws, size_t ws_bytes, void* stream) {
+  return sparse_attn_impl(d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx, topk_count, top_k, window, n_sink,
+                          cos_win, sin_win, seq_lens, out, ws, ws_bytes, true, stream);
 }
 
 int a2ats_score_topk_stats(const a2ats_dims* d, int32_t top_k, int32_t window, int32_t n_sink, const void* ws,

@@ -17,7 +17,10 @@ namespace a2ats {
 
 constexpr int kLutThreads = 1024;
 
-template <int DS, bool QBF16>
+// SHARED: one table per KV head, built from the sum of the rotated queries of its G heads (the
+// group's summed score sum_g q~_g . c equals (sum_g q~_g) . c); the rotated queries themselves
+// are still written per head.  The table array is then laid out as for n_q_heads == n_kv_heads.
+template <int DS, bool QBF16, bool SHARED = false>
 __device__ __forceinline__ void build_lut_body(
     int prob, const void* __restrict__ q_in, const float* __restrict__ cos_b,
     const float* __restrict__ sin_b, const float* __restrict__ codebook, float* __restrict__ q_rot,
@@ -32,7 +35,10 @@ __device__ __forceinline__ void build_lut_body(
   __shared__ int32_t s_min[M][kHeadsPerGroup], s_max[M][kHeadsPerGroup];
   __shared__ int32_t s_shift[kHeadsPerGroup];
 
-  const int G = Hq / Hkv;
+  const int Gq = Hq / Hkv;                 // query heads per KV head
+  const int G = SHARED ? 1 : Gq;           // table heads per KV head
+  const int Hq_q = Hq;
+  if (SHARED) Hq = Hkv;                    // table indexing below is per table head
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int tid = threadIdx.x;
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
@@ -52,14 +58,15 @@ __device__ __forceinline__ void build_lut_body(
     }
   }
 
-  // --- q~ = q R_b for the (up to) four heads of this group
-  if (tid < kHeadsPerGroup * HALF) {
+  // --- q~ = q R_b for the (up to) four heads of this group (SHARED: all G <= 8 heads of the KV head)
+  __shared__ float s_qall[SHARED ? 8 : 1][SHARED ? D : 1];
+  if (tid < (SHARED ? 8 : kHeadsPerGroup) * HALF) {
     const int r = tid / HALF, t = tid % HALF;
-    const int hg = g4 * kHeadsPerGroup + r;
+    const int hg = SHARED ? r : g4 * kHeadsPerGroup + r;
     float o1 = 0.f, o2 = 0.f;
-    if (hg < G) {
-      const int h = kv * G + hg;
-      const size_t base = ((size_t)b * Hq + h) * D;
+    if (hg < Gq) {
+      const int h = kv * Gq + hg;
+      const size_t base = ((size_t)b * Hq_q + h) * D;
       double x1, x2;
       if (QBF16) {
         const uint16_t* qp = (const uint16_t*)q_in;
@@ -76,8 +83,23 @@ __device__ __forceinline__ void build_lut_body(
       q_rot[base + t] = o1;
       q_rot[base + t + HALF] = o2;
     }
-    s_q[r][t] = o1;
-    s_q[r][t + HALF] = o2;
+    if (SHARED) {
+      s_qall[r][t] = o1;
+      s_qall[r][t + HALF] = o2;
+    } else {
+      s_q[r][t] = o1;
+      s_q[r][t + HALF] = o2;
+    }
+  }
+  if (SHARED) {
+    __syncthreads();
+    if (tid < kHeadsPerGroup * D) {
+      const int r = tid / D, t = tid % D;
+      double sum = 0.0;
+      if (r == 0)
+        for (int g = 0; g < 8; ++g) sum += (double)s_qall[g][t];   // heads past G hold zeros
+      s_q[r][t] = (float)sum;
+    }
   }
   if (tid < kHeadsPerGroup) s_maxbits[tid] = 0u;
   if (tid < M * kHeadsPerGroup) {
@@ -206,6 +228,14 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_kernel(
   build_lut_body<DS, QBF16>(blockIdx.x, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG);
 }
 
+template <int DS, bool QBF16>
+__global__ __launch_bounds__(kLutThreads) void build_lut_shared_kernel(
+    const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
+    const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
+    float* __restrict__ lut_scale, int B, int Hq, int Hkv) {
+  build_lut_body<DS, QBF16, true>(blockIdx.x, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, 1);
+}
+
 // Decode prologue in one launch: the first n_lut workgroups build the tables of the current query,
 // the others encode the few keys appended this step, four (key, subspace) pairs per workgroup.
 // The two halves touch disjoint data.
@@ -247,6 +277,23 @@ hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, con
     if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUT(4, true); else A2ATS_LAUNCH_LUT(4, false);
   }
 #undef A2ATS_LAUNCH_LUT
+  return hipGetLastError();
+}
+
+hipError_t launch_build_lut_shared(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
+                                   const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
+                                   float* lut_scale, hipStream_t stream) {
+  const dim3 grid(d.batch * d.n_kv_heads), block(kLutThreads);
+  if (grid.x == 0) return hipSuccess;
+#define A2ATS_LAUNCH_LUTS(DS, BF)                                                                          \
+  hipLaunchKernelGGL((build_lut_shared_kernel<DS, BF>), grid, block, 0, stream, q, cos_b, sin_b, codebook, \
+                     q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads)
+  if (d.sub_dim == 8) {
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUTS(8, true); else A2ATS_LAUNCH_LUTS(8, false);
+  } else {
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_LUTS(4, true); else A2ATS_LAUNCH_LUTS(4, false);
+  }
+#undef A2ATS_LAUNCH_LUTS
   return hipGetLastError();
 }
 

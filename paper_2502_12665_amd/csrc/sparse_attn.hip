@@ -81,7 +81,11 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float (&acc)[VEC
   m = mm;
 }
 
-template <typename T>
+// SHARED: topk_idx / topk_count are per KV head and the G query heads of a KV head attend the same
+// rows.  The grid is then one-dimensional and mapped so that the G workgroups that read the same
+// rows (same KV head, same part) run next to each other on one XCD: the rows come from HBM once
+// and from that XCD's L2 for the other G - 1 heads.
+template <typename T, bool SHARED>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     const T* __restrict__ q, const float* __restrict__ q_rot, const T* __restrict__ k_cache,
     const T* __restrict__ v_cache, const int32_t* __restrict__ topk_idx,
@@ -97,11 +101,23 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   __shared__ int32_t s_pos[kAttnTile];
   __shared__ float s_m[NWV], s_l[NWV], s_acc[NWV][kD];
 
-  const int part = blockIdx.x, bh = blockIdx.y, b = bh / Hq, h = bh % Hq;
-  const int G = Hq / Hkv, kv = h / G;
+  const int G = Hq / Hkv;
+  int part, bh;
+  if (SHARED) {
+    const int parts = n_far + n_win;
+    int prob, pg;
+    xcd_map(blockIdx.x, parts * G, (int)(gridDim.x / (parts * G)), prob, pg);
+    part = pg / G;
+    bh = prob * G + pg % G;   // prob = b * Hkv + kv
+  } else {
+    part = blockIdx.x;
+    bh = blockIdx.y;
+  }
+  const int b = bh / Hq, h = bh % Hq, kv = h / G;
+  const int ih = SHARED ? b * Hkv + kv : bh;   // whose selection this head attends
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, slot = lane / LPR, sub = lane % LPR;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
-  const int cnt = max(0, min(min(topk_count[bh], top_k), sr.ncand));
+  const int cnt = max(0, min(min(topk_count[ih], top_k), sr.ncand));
   // Far rows (sinks, then the retrieved rows) are dealt out round-robin to the first n_far
   // workgroups of the head, window rows to the other n_win.
   const bool win_part = part >= n_far;
@@ -113,7 +129,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   const float scale = 0.08838834764831845f;   // 1/sqrt(128)
   const T* kb = k_cache + ((size_t)b * Hkv + kv) * ctx_stride * kD + d0;
   const T* vb = v_cache + ((size_t)b * Hkv + kv) * ctx_stride * kD + d0;
-  const int32_t* idx = topk_idx + (size_t)bh * top_k;
+  const int32_t* idx = topk_idx + (size_t)ih * top_k;
   const size_t qb = (size_t)bh * kD;
 
   float m_run = -INFINITY, l_run = 0.f, acc[VEC];
@@ -312,14 +328,20 @@ static hipError_t launch_attn_t(const a2ats_dims& d, const AttnPlan& plan, const
                                 const void* k_cache, const void* v_cache, const int32_t* topk_idx,
                                 const int32_t* topk_count, int top_k, int window, int n_sink,
                                 const float* cos_win, const float* sin_win, const int32_t* seq_lens,
-                                void* out, void* ws, hipStream_t stream) {
+                                void* out, void* ws, bool shared, hipStream_t stream) {
   const int heads = d.batch * d.n_q_heads;
   if (heads == 0) return hipSuccess;
   const int parts = plan.n_far + plan.n_win;
-  hipLaunchKernelGGL((attn_partial_kernel<T>), dim3(parts, heads), dim3(kAttnThreads), 0, stream,
-                     (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
-                     cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
-                     d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win);
+  if (shared)
+    hipLaunchKernelGGL((attn_partial_kernel<T, true>), dim3(parts * heads), dim3(kAttnThreads), 0, stream,
+                       (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
+                       cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
+                       d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win);
+  else
+    hipLaunchKernelGGL((attn_partial_kernel<T, false>), dim3(parts, heads), dim3(kAttnThreads), 0, stream,
+                       (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
+                       cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
+                       d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   hipLaunchKernelGGL((attn_combine_kernel<T>), dim3(heads), dim3(kCombineGroups * kD), 0, stream,
@@ -331,13 +353,13 @@ hipError_t launch_sparse_attn(const a2ats_dims& d, const void* q, const float* q
                               const void* v_cache, int kv_dtype, const int32_t* topk_idx,
                               const int32_t* topk_count, int top_k, int window, int n_sink,
                               const float* cos_win, const float* sin_win, const int32_t* seq_lens,
-                              void* out, void* ws, hipStream_t stream) {
+                              void* out, void* ws, bool shared, hipStream_t stream) {
   const AttnPlan plan = make_attn_plan(d, top_k, window, n_sink);
   if (kv_dtype == A2ATS_BF16)
     return launch_attn_t<uint16_t>(d, plan, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k,
-                                   window, n_sink, cos_win, sin_win, seq_lens, out, ws, stream);
+                                   window, n_sink, cos_win, sin_win, seq_lens, out, ws, shared, stream);
   return launch_attn_t<float>(d, plan, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k, window,
-                              n_sink, cos_win, sin_win, seq_lens, out, ws, stream);
+                              n_sink, cos_win, sin_win, seq_lens, out, ws, shared, stream);
 }
 
 }  // namespace a2ats

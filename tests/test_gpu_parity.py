@@ -536,3 +536,53 @@ def test_decode_step_in_a_hip_graph():
         assert torch.equal(st.out.view(torch.int16), ref[1].view(torch.int16)), f"replay {it}: output differs"
         junk = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
         assert junk == junk
+
+
+def _group_shared_step(wl, xd, n_sink=0, want_scores=True):
+    """One decode step with one selection per KV head: shared tables, score/top-K on the dims of the
+    table heads, attention of all G heads over the shared rows."""
+    stride = xd["codes"].shape[2]
+    dims = H.dims_of(wl, stride)
+    kvw = wl.replace(n_q_heads=wl.n_kv_heads)
+    dims_kv = H.dims_of(kvw, stride)
+    st = B.DecodeState(dims, wl.top_k, wl.window, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+    sk = B.DecodeState(dims_kv, wl.top_k, wl.window, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b,
+                       want_scores=want_scores)
+    sk.topk_idx.fill_(-7)
+    sk.topk_count.fill_(-7)
+    B.build_lut_shared(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, sk.lut, sk.lut_scale)
+    B.score_topk(dims_kv, xd["codes"], sk.lut, sk.lut_scale, wl.top_k, wl.window, n_sink, None, sk.topk_idx,
+                 sk.topk_count, sk.topk_score, sk.scores, sk.ws)
+    B.sparse_attn_shared(dims, xd["q"], st.q_rot, xd["k"], xd["v"], sk.topk_idx, sk.topk_count, wl.top_k,
+                         wl.window, n_sink, st.cos_win, st.sin_win, None, st.out, st.ws)
+    torch.cuda.synchronize()
+    return st, sk
+
+
+@pytest.mark.parametrize("shape", [(2, 8, 2, 16, 9000, 300, 64), (1, 14, 2, 32, 5000, 64, 32),
+                                   (2, 8, 2, 16, 40000, 512, 128), (1, 3, 3, 16, 700, 700, 16)])
+def test_group_shared_selection(oracle, shape):
+    """One selection per KV head (sum of the group's scores), against the oracle: rotated queries per
+    head, group scores, the shared top-K, and the attention of every head over the shared rows."""
+    Bn, Hq, Hkv, M, N, K, w = shape
+    wl = synth.Workload("shared", Bn, Hq, Hkv, 128, M, N, K, w, seed=N + Hq)
+    x = synth.make_decode_inputs(wl)
+    xd = H.to_dev(x)
+    n_sink = 4 if N < 6000 else 0
+    st, sk = _group_shared_step(wl, xd, n_sink=n_sink)
+    G = wl.group
+    qrot = oracle.rope(x["q"], x["inv_freq"], wl.wrope_b)
+    err = np.abs(st.q_rot.cpu().numpy() - qrot)
+    assert (err <= 2e-6 * np.maximum(1.0, np.abs(qrot))).all()
+    grp = oracle.group_scores(oracle.scores_explicit(qrot, x["codebook"], x["codes"], N), Hkv)
+    H.check_scores(sk.scores.cpu().numpy()[:, :, :N].astype(np.float64), grp, "group scores")
+    idx, cnt, kth = oracle.topk(grp, K, w, n_sink)
+    exc, slots = H.compare_topk(sk.topk_idx.cpu().numpy(), sk.topk_count.cpu().numpy(), idx, cnt, grp, kth)
+    H.log(f"shared {shape}: {exc} near-tie exclusions in {slots} slots")
+    # every head of a group attends the group's rows (the GPU's own selection, so that a near-tie
+    # exclusion above does not leak into the attention comparison)
+    g_idx = np.repeat(sk.topk_idx.cpu().numpy(), G, axis=1)
+    g_cnt = np.repeat(sk.topk_count.cpu().numpy(), G, axis=1)
+    want = oracle.sparse_attn(x["q"], x["k"], x["v"], g_idx, g_cnt, N, w, n_sink, x["inv_freq"], float(wl.wrope_b))
+    aerr = np.abs(st.out.float().cpu().numpy().astype(np.float64) - want).max()
+    assert aerr <= (2e-2 if wl.kv_dtype == "bf16" else 2e-4), aerr

@@ -446,3 +446,23 @@ def test_single_codebook_encode_full_quadratic_form(oracle):
     keys2 = cb[:, 0, [300, 4095]].reshape(1, 2, 2, 128).clone()
     got = oracle.encode(keys2, cb, H, oracle.W_BLOCK)
     np.testing.assert_array_equal(got[0, :, :, 0], np.array([[300, 4095], [300, 4095]]))
+
+
+def test_group_scores_equal_the_scores_of_the_summed_query(oracle):
+    """One selection per KV head ranks tokens by the sum of its G heads' scores.  The score is linear in
+    the query (section 4.2: u^_j = q~ . c_{s_j}), so that sum must equal the score of the single query
+    sum_g q~_g -- a closed form that pins the head-to-group mapping (h // G, not h % G), and G = 1 must
+    be the identity."""
+    rng = np.random.default_rng(11)
+    Bn, Hkv, G, M, ds, L, N = 2, 3, 4, 16, 8, 256, 50
+    q_rot = rng.standard_normal((Bn, Hkv * G, M * ds))
+    cb = rng.standard_normal((Hkv, M, L, ds)).astype(np.float32)
+    codes = rng.integers(0, L, (Bn, Hkv, N, M)).astype(np.uint8)
+    per_head = oracle.scores_explicit(q_rot, cb, codes, N)
+    grouped = oracle.group_scores(per_head, Hkv)
+    q_sum = q_rot.reshape(Bn, Hkv, G, M * ds).sum(axis=2)
+    direct = oracle.scores_explicit(q_sum, cb, codes, N)
+    np.testing.assert_allclose(grouped, direct, rtol=0, atol=1e-10)
+    wrong = per_head.reshape(Bn, G, Hkv, N).sum(axis=1)          # the h % G mapping
+    assert np.abs(wrong - direct).max() > 1e-3
+    np.testing.assert_array_equal(oracle.group_scores(direct, Hkv), direct)
