@@ -46,6 +46,20 @@ __host__ __device__ inline LutLayout lut_layout(int B, int Hq, int Hkv, int M) {
 __device__ __forceinline__ uint32_t score_key(int32_t s) { return (uint32_t)s ^ 0x80000000u; }
 __device__ __forceinline__ int32_t key_score(uint32_t k) { return (int32_t)(k ^ 0x80000000u); }
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (a shuffle
+// goes through the LDS crossbar, one round trip per step, and these scans sit on critical paths):
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of rows 0 and 2 is added
+// to rows 1 and 3, then lane 31 to the upper half.  All 64 lanes must be active.
+__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);   // row_shr:2
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);   // row_shr:4
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);   // row_shr:8
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);   // row_bcast:15
+  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31
+  return v;
+}
+
 // Exclusive prefix sum of `v` over the block (NT threads, NT a multiple of 64).  `s_wave` is an
 // LDS array of NT/64 words owned by this call site.  Returns the exclusive prefix and the
 // block total.  One barrier; callers alternate between two `s_wave` arrays when they scan
@@ -54,12 +68,7 @@ template <int NT>
 __device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* s_wave,
                                                          uint32_t& total) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  uint32_t inc = v;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    uint32_t o = __shfl_up(inc, off);
-    if (lane >= off) inc += o;
-  }
+  const uint32_t inc = wave_inclusive_scan(v);
   if (lane == 63) s_wave[wv] = inc;
   __syncthreads();
   uint32_t base = 0, tot = 0;
@@ -92,12 +101,7 @@ __device__ __forceinline__ void block_find_rank_desc(Count count, uint32_t k, ui
     loc[i] = count(top - i);
     sum += loc[i];
   }
-  uint32_t inc = sum;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    uint32_t o = __shfl_up(inc, off);
-    if (lane >= off) inc += o;
-  }
+  uint32_t inc = wave_inclusive_scan(sum);
   if (lane == 63) s_wave[wv] = inc;
   __syncthreads();
   uint32_t base = 0;

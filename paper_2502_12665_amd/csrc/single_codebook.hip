@@ -153,20 +153,6 @@ __device__ __forceinline__ uint32_t valid_mask8(int j0, int lo, int hi) {
   return ((1u << e) - 1u) & ~((1u << a) - 1u);
 }
 
-// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (a shuffle
-// through the LDS crossbar costs a round trip per step and these scans sit on the critical path):
-// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the last lane of rows 0 and 2 is added
-// to rows 1 and 3, then lane 31 to the upper half.
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false);   // row_shr:1
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false);   // row_shr:2
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false);   // row_shr:4
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false);   // row_shr:8
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false);   // row_bcast:15
-  v += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false);   // row_bcast:31
-  return v;
-}
-
 // One workgroup per head.  A score is one table entry, so the K-th largest score over the
 // candidate tokens is a weighted selection over the 4096 codewords: (1) count the candidates per
 // codeword (one pass over the 2-byte codes), (2) MSB-first radix select over the 4096 keys weighted
