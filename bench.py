@@ -334,6 +334,69 @@ def group_shared_step(args, torch, B, synth, wl):
     }))
 
 
+def codebook_fit(args, torch, B, synth, wl):
+    """Offline codebook construction: one Lloyd iteration under the query-aware distortion (assignment by
+    a2ats_encode_keys with the full matrix H, centroid step by a2ats_codebook_update) over whole sequences,
+    and the second moment H itself from as many rotated query rows."""
+    N, Hkv = wl.ctx_len, wl.n_kv_heads
+    hm = synth.make_query_second_moment(wl)
+    cb = synth.make_codebook(wl, "cuda")
+    keys = synth.make_encode_keys(wl, N, device="cuda", stress=True)
+    dims = B.make_dims(wl.batch, wl.n_q_heads, Hkv, wl.head_dim, wl.n_sub, N, n_centroids=wl.n_centroids)
+    ws = torch.empty(B.workspace_bytes(dims, B.OP_ENCODE), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(B.workspace_bytes(dims, B.OP_FIT), dtype=torch.uint8, device="cuda")
+    codes = torch.empty(wl.batch, Hkv, N, wl.n_sub, dtype=synth.code_dtype(wl), device="cuda")
+    new_cb = torch.empty_like(cb)
+    w = hm["h_block"].cuda()
+    n_keys = wl.batch * Hkv * N
+    q_rows = torch.randn(N, wl.n_q_heads, wl.head_dim, device="cuda")
+    h_out = torch.empty(Hkv, wl.head_dim, wl.head_dim, device="cuda")
+    steps, warmup = min(args.steps, 8), min(args.warmup, 2)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+
+    def it(i, timed):
+        if timed:
+            ev[i][0].record()
+        B.encode_keys(dims, keys, N, 0, cb, w, B.W_BLOCK, codes, ws)
+        if timed:
+            ev[i][1].record()
+        B.codebook_update(dims, keys, N, 0, codes, cb, new_cb, None, ws_f)
+        if timed:
+            ev[i][2].record()
+        B.second_moment(dims, q_rows, N, h_out, ws_f)
+        if timed:
+            ev[i][3].record()
+
+    for i in range(warmup):
+        it(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        it(i, False)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    for i in range(steps):
+        it(i, True)
+    torch.cuda.synchronize()
+    med = lambda v: float(sorted(v)[len(v) // 2])
+    ph = [med([ev[i][p].elapsed_time(ev[i][p + 1]) for i in range(steps)]) for p in range(3)]
+    flop = n_keys * 4096.0 * 128.0 * 2.0
+    print(json.dumps({
+        "metric": "keys/s per Lloyd iteration (query-aware k-means: assignment under the full matrix H + centroid "
+                  "step; plus one second-moment accumulation)",
+        "value": n_keys / (ms * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 split products / f64 re-check for the assignment; f64 sums for means and moments",
+        "data": "synthetic",
+        "config": {"workload": wl.name + " codebook construction", "keys": n_keys, "codewords": wl.n_centroids,
+                   "query_rows": N * wl.n_q_heads},
+        "phase_ms_median": {"assign": ph[0], "centroid_step": ph[1], "second_moment": ph[2]},
+        "roofline": {"kernel": "encode_single_kernel", "bound": "mfma", "achieved": flop / (ph[0] * 1e-3) / 1e12,
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": flop / (ph[0] * 1e-3) / 1e12 / 2500.0,
+                     "traffic": None, "note": "algorithmic flops of the assignment over its whole call"},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -353,6 +416,9 @@ def main():
     ap.add_argument("--group-shared", action="store_true",
                     help="one selection per KV head (sum of the group's scores) instead of one per query head; "
                          "prints a line of its own")
+    ap.add_argument("--codebook-fit", action="store_true",
+                    help="offline codebook construction (single-codebook workloads): one Lloyd iteration and one "
+                         "second-moment accumulation; prints a line of its own")
     ap.add_argument("--encode-prefill", action="store_true",
                     help="measure the prefill-side key encoder (configuration 5 geometry, 8 of its 32 "
                          "sequences) instead of the decode step, and print its own JSON line")
@@ -370,7 +436,9 @@ def main():
     torch.cuda.set_device(0)
     wl = synth.WORKLOADS[args.workload]
     if wl.n_centroids == 4096:   # the paper's own quantiser geometry: lines of its own
-        if args.encode_prefill:
+        if args.codebook_fit:
+            codebook_fit(args, torch, B, synth, wl)
+        elif args.encode_prefill:
             single_codebook_encode_prefill(args, torch, B, synth, wl)
         else:
             single_codebook_step(args, torch, B, synth, wl)

@@ -83,7 +83,7 @@ typedef enum a2ats_status {
 enum { A2ATS_F32 = 0, A2ATS_BF16 = 1 };                       /* element types of q / k / v / out */
 enum { A2ATS_W_NONE = 0, A2ATS_W_DIAG = 1, A2ATS_W_BLOCK = 2 }; /* encoder distortion              */
 enum { A2ATS_W_PREPARED = 0x100 };   /* flag for weight_mode, see a2ats_encode_prepare */
-enum { A2ATS_OP_ENCODE = 0, A2ATS_OP_LUT = 1, A2ATS_OP_SCORE_TOPK = 2, A2ATS_OP_ATTN = 3 };
+enum { A2ATS_OP_ENCODE = 0, A2ATS_OP_LUT = 1, A2ATS_OP_SCORE_TOPK = 2, A2ATS_OP_ATTN = 3, A2ATS_OP_FIT = 4 };
 
 int a2ats_version(void);
 const char* a2ats_status_string(int status);
@@ -257,6 +257,33 @@ int a2ats_sparse_attn_shared(const a2ats_dims* dims, const void* q, const float*
                              int32_t window, int32_t n_sink, const float* cos_win,
                              const float* sin_win, const int32_t* seq_lens, void* out, void* ws,
                              size_t ws_bytes, void* stream);
+
+/*
+ * Offline codebook construction (paper section 4.2).
+ *
+ * a2ats_second_moment: H = E[q~^T q~], one D x D matrix per KV head, from n_samples rotated query
+ * rows; the G query heads of a KV head are pooled.
+ *   q_rot  [dev, f32 n_samples*Hq*D]   rotated queries (e.g. the q_rot output of a2ats_build_lut)
+ *   h_out  [dev, out, f32 Hkv*D*D]     accumulated in float64, rounded once; zeros if n_samples == 0
+ * H (or its diagonal / diagonal blocks) is the `weights` argument of a2ats_encode_keys.
+ *
+ * a2ats_codebook_update: the centroid step of k-means under the query-aware distortion.  The paper
+ * runs k-means on z = k L and maps the centroids back with L^-1; the mean is linear, so the new
+ * codeword is the mean of the keys assigned to it.  One Lloyd iteration is a2ats_encode_keys (the
+ * assignment under (k - c) H (k - c)^T) followed by this call on the same keys and codes.
+ *   keys, n_new, pos0, codes   as written by a2ats_encode_keys (all B sequences are pooled per KV head)
+ *   codebook      [dev, f32 Hkv*M*L*ds]       the codebook the codes refer to
+ *   codebook_out  [dev, out, f32 Hkv*M*L*ds]  means in float64, rounded once; a codeword without keys
+ *                                             keeps its value (may alias `codebook`)
+ *   counts        [dev, out, nullable, int32 Hkv*M*L]  keys per codeword
+ * The sums are float64 hardware atomics: the last bits of a mean can differ from run to run.
+ * Both calls need a2ats_workspace_bytes(dims, A2ATS_OP_FIT, 0, 0) bytes of workspace.
+ */
+int a2ats_second_moment(const a2ats_dims* dims, const float* q_rot, int64_t n_samples, float* h_out,
+                        void* ws, size_t ws_bytes, void* stream);
+int a2ats_codebook_update(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
+                          const uint8_t* codes, const float* codebook, float* codebook_out,
+                          int32_t* counts, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Diagnostics (not part of the method): after an a2ats_score_topk call with the same dims /

@@ -232,3 +232,59 @@ def encode_cholesky(keys, codebook, h_block, want_margins: bool = False):
     if want_margins:
         return codes, best, second
     return codes
+
+
+# ---------------------------------------------------------------------------------------------
+# Offline codebook construction (section 4.2: second moment of the queries, k-means under the
+# query-aware distortion).  Plain numpy, float64.
+# ---------------------------------------------------------------------------------------------
+def second_moment(q_rot, n_kv_heads: int) -> np.ndarray:
+    """H [Hkv,D,D] = E[q~^T q~] (section 4.2), the mean of the outer products of the rotated
+    queries q_rot [n,Hq,D]; the G query heads of a KV head share its codebook, so their samples
+    are pooled (query head h belongs to KV head h // G)."""
+    q = _f64(q_rot)
+    n, Hq, D = q.shape
+    G = Hq // n_kv_heads
+    H = np.zeros((n_kv_heads, D, D), dtype=np.float64)
+    for kv in range(n_kv_heads):
+        for g in range(G):
+            x = q[:, kv * G + g, :]
+            for i in range(n):
+                H[kv] += np.outer(x[i], x[i])
+        H[kv] /= n * G
+    return H
+
+
+def distortion(keys, codebook, codes, h_full) -> np.ndarray:
+    """J' [Hkv] = sum over the keys of (k - c) H (k - c)^T (section 4.2, the query-aware objective),
+    keys [B,Hkv,n,D], one codebook [Hkv,1,L,D], codes [B,Hkv,n,1], H [Hkv,D,D]."""
+    k, cb, H = _f64(keys), _f64(codebook), _f64(h_full)
+    c = np.asarray(codes).astype(np.int64).reshape(k.shape[0], k.shape[1], k.shape[2])
+    out = np.zeros(k.shape[1], dtype=np.float64)
+    for kv in range(k.shape[1]):
+        for b in range(k.shape[0]):
+            e = k[b, kv] - cb[kv, 0][c[b, kv]]
+            out[kv] += np.einsum("nd,de,ne->", e, H[kv], e)
+    return out
+
+
+def lloyd_update(keys, codes, codebook):
+    """The centroid step of k-means (section 4.2 runs k-means on z = k L and maps the centroids
+    back with L^-1; the mean is linear, so that is the mean of the assigned keys themselves):
+    new codebook [Hkv,1,L,D] float64 and counts [Hkv,L]; a codeword that no key was assigned to
+    keeps its old value.  The keys of all B sequences are pooled per KV head."""
+    k, cb = _f64(keys), _f64(codebook)
+    B, Hkv, n, D = k.shape
+    L = cb.shape[2]
+    c = np.asarray(codes).astype(np.int64).reshape(B, Hkv, n)
+    new = cb.copy()
+    counts = np.zeros((Hkv, L), dtype=np.int64)
+    for kv in range(Hkv):
+        sums = np.zeros((L, D), dtype=np.float64)
+        for b in range(B):
+            for j in range(n):
+                sums[c[b, kv, j]] += k[b, kv, j]
+                counts[kv, c[b, kv, j]] += 1
+        used = counts[kv] > 0
+        new[kv, 0][used] = sums[used] / counts[kv][used, None]
+    return new, counts

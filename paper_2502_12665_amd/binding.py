@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_HERE, "liba2ats.so")
 F32, BF16 = 0, 1
 W_NONE, W_DIAG, W_BLOCK = 0, 1, 2
 W_PREPARED = 0x100
-OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN = 0, 1, 2, 3
+OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN, OP_FIT = 0, 1, 2, 3, 4
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes", "a2ats_encode_prepare",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel",
-           "a2ats_decode_prologue", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared"]
+           "a2ats_decode_prologue", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
+           "a2ats_second_moment", "a2ats_codebook_update"]
 
 
 class A2atsError(RuntimeError):
@@ -77,6 +78,10 @@ def lib() -> ctypes.CDLL:
         L.a2ats_sparse_attn_shared.argtypes = L.a2ats_sparse_attn.argtypes
         L.a2ats_build_lut_shared.restype = ctypes.c_int
         L.a2ats_build_lut_shared.argtypes = L.a2ats_build_lut.argtypes
+        L.a2ats_second_moment.restype = ctypes.c_int
+        L.a2ats_second_moment.argtypes = [dp, vp, ctypes.c_int64, vp, vp, sz, vp]
+        L.a2ats_codebook_update.restype = ctypes.c_int
+        L.a2ats_codebook_update.argtypes = [dp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.a2ats_score_topk_stats.restype = ctypes.c_int
         L.a2ats_score_topk_stats.argtypes = [dp, i32, i32, i32, vp, vp, vp]
         L.a2ats_profile_stream_kernel.restype = None
@@ -212,6 +217,19 @@ def sparse_attn_shared(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_co
                                         n_sink, _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _ptr(ws),
                                         0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_sparse_attn_shared")
+
+
+def second_moment(dims: Dims, q_rot, n_samples: int, h_out, ws: torch.Tensor):
+    rc = lib().a2ats_second_moment(ctypes.byref(dims), _ptr(q_rot), n_samples, _ptr(h_out), _ptr(ws),
+                                   ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_second_moment")
+
+
+def codebook_update(dims: Dims, keys, n_new: int, pos0: int, codes, codebook, codebook_out, counts, ws: torch.Tensor):
+    rc = lib().a2ats_codebook_update(ctypes.byref(dims), _ptr(keys), n_new, pos0, _ptr(codes), _ptr(codebook),
+                                     _ptr(codebook_out), _ptr(counts), _ptr(ws), ws.numel() * ws.element_size(),
+                                     _stream())
+    _check(rc, "a2ats_codebook_update")
 
 
 def score_topk_stats(dims: Dims, top_k: int, window: int, n_sink: int, ws, cand_counts):

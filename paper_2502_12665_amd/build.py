@@ -10,7 +10,7 @@ _ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "liba2ats.so")
 SOURCES = ["a2ats_api.hip", "build_lut.hip", "score_topk.hip", "sparse_attn.hip", "encode_keys.hip",
-           "single_codebook.hip", "encode_single.hip"]
+           "single_codebook.hip", "encode_single.hip", "codebook_fit.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms

@@ -71,6 +71,7 @@ size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t
       // (a call with more sinks than that may ask for more and is refused if `ws` is too small).
       return a2ats::make_attn_plan(*d, top_k, window, 64).bytes;
     }
+    case A2ATS_OP_FIT: return a2ats::fit_ws_bytes(*d);
     default: return (size_t)-1;
   }
 }
@@ -136,6 +137,31 @@ int a2ats_encode_prepare(const a2ats_dims* d, const float* codebook, const float
   if (!a2ats::single_codebook(*d)) return A2ATS_OK;   // nothing worth keeping between calls
   if (!ws || misaligned16(ws) || ws_bytes < a2ats::encode_single_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
   const hipError_t e = a2ats::launch_encode_single_prepare(*d, codebook, weights, weight_mode, ws, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_second_moment(const a2ats_dims* d, const float* q_rot, int64_t n_samples, float* h_out, void* ws,
+                        size_t ws_bytes, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (n_samples < 0 || !h_out || (n_samples > 0 && !q_rot)) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(q_rot)) return A2ATS_ERR_INVALID_ARG;
+  if (!ws || misaligned16(ws) || ws_bytes < a2ats::fit_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
+  const hipError_t e = a2ats::launch_second_moment(*d, q_rot, n_samples, h_out, ws, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_codebook_update(const a2ats_dims* d, const float* keys, int32_t n_new, int32_t pos0, const uint8_t* codes,
+                          const float* codebook, float* codebook_out, int32_t* counts, void* ws, size_t ws_bytes,
+                          void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride) return A2ATS_ERR_INVALID_ARG;
+  if (!codebook || !codebook_out || (n_new > 0 && (!keys || !codes))) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(keys)) return A2ATS_ERR_INVALID_ARG;
+  if (!ws || misaligned16(ws) || ws_bytes < a2ats::fit_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
+  const hipError_t e = a2ats::launch_codebook_update(*d, keys, n_new, pos0, codes, codebook, codebook_out, counts,
+                                                     ws, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 

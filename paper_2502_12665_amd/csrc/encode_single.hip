@@ -25,9 +25,10 @@
 //                                  crosses lanes until the end.
 //   encode_single_recheck_kernel   keys whose two smallest scores are closer than the rounding reach
 //                                  of the bf16 products are decided in float64 between those two
-//                                  codewords; keys with three that close (and the few-key append
-//                                  path) by a float64 sweep over all 4096.  So the emitted code is
-//                                  the float64 argmin.
+//                                  codewords; keys with three that close by a float64 sweep over all
+//                                  4096.  So the emitted code is the float64 argmin.
+//   encode_single_sweep_kernel     the few-key (decode-time append) route: float64 sweeps only, 16
+//                                  workgroups per key, then encode_single_sweep_pick_kernel
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -462,19 +463,14 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(2, 
 __global__ __launch_bounds__(256) void encode_single_recheck_kernel(
     const float* __restrict__ keys, int mode, const double* __restrict__ Lmat, const double* __restrict__ sd,
     const double* __restrict__ czT, uint16_t* __restrict__ codes, const uint32_t* __restrict__ counter,
-    const uint32_t* __restrict__ list, uint32_t n_all, int Hkv, int n_new, int pos0, int64_t ctx_stride) {
+    const uint32_t* __restrict__ list, int Hkv, int n_new, int pos0, int64_t ctx_stride) {
   __shared__ double s_k[kD], s_z[kD], s_d[256];
   __shared__ int s_i[256];
   const int tid = threadIdx.x;
-  const uint32_t count = list ? *counter : n_all;   // no list: every key, by a full sweep
+  const uint32_t count = *counter;
   for (uint32_t it = blockIdx.x; it < count; it += gridDim.x) {
-    uint32_t key = it, pair = 0;
-    bool full = true;
-    if (list) {
-      key = list[2 * (size_t)it] & 0x7fffffffu;
-      full = (list[2 * (size_t)it] >> 31) != 0;
-      pair = list[2 * (size_t)it + 1];
-    }
+    const uint32_t key = list[2 * (size_t)it] & 0x7fffffffu, pair = list[2 * (size_t)it + 1];
+    const bool full = (list[2 * (size_t)it] >> 31) != 0;
     const int bkv = (int)(key / (uint32_t)n_new), j = (int)(key % (uint32_t)n_new), kv = bkv % Hkv;
     __syncthreads();   // the arrays of the key before are still being read
     if (tid < kD) s_k[tid] = (double)keys[((size_t)bkv * n_new + j) * kD + tid];
@@ -722,7 +718,7 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
   if ((err = hipGetLastError()) != hipSuccess) return err;
   const uint32_t re_grid = n_all < 2048u ? n_all : 2048u;
   hipLaunchKernelGGL(encode_single_recheck_kernel, dim3(re_grid), dim3(256), 0, stream, keys, mode, Lmat, sd, czT,
-                     (uint16_t*)codes, counter, (const uint32_t*)list, n_all, Hkv, n_new, pos0, d.ctx_stride);
+                     (uint16_t*)codes, counter, (const uint32_t*)list, Hkv, n_new, pos0, d.ctx_stride);
   return hipGetLastError();
 }
 

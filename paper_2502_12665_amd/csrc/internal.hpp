@@ -92,4 +92,11 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
                                 const float* codebook, const float* weights, int mode, bool prepared, void* codes,
                                 void* ws, hipStream_t stream);
 
+size_t fit_ws_bytes(const a2ats_dims& d);
+hipError_t launch_second_moment(const a2ats_dims& d, const float* q_rot, int64_t n_samples, float* h_out, void* ws,
+                                hipStream_t stream);
+hipError_t launch_codebook_update(const a2ats_dims& d, const float* keys, int n_new, int pos0, const void* codes,
+                                  const float* codebook, float* codebook_out, int32_t* counts_out, void* ws,
+                                  hipStream_t stream);
+
 }  // namespace a2ats

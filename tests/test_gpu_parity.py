@@ -586,3 +586,89 @@ def test_group_shared_selection(oracle, shape):
     want = oracle.sparse_attn(x["q"], x["k"], x["v"], g_idx, g_cnt, N, w, n_sink, x["inv_freq"], float(wl.wrope_b))
     aerr = np.abs(st.out.float().cpu().numpy().astype(np.float64) - want).max()
     assert aerr <= (2e-2 if wl.kv_dtype == "bf16" else 2e-4), aerr
+
+
+def test_second_moment(oracle):
+    """H = E[q~^T q~] per KV head from rotated query samples (heads of a KV head pooled), ragged sample
+    counts included, against the oracle; it is positive definite enough for the encoder's Cholesky."""
+    for Hq, Hkv, n in ((8, 2, 777), (3, 3, 1), (14, 2, 5000), (4, 1, 0)):
+        wl = synth.Workload("moment", 1, Hq, Hkv, 128, 16, 64, 1, 1, seed=n)
+        dims = H.dims_of(wl, 64)
+        g = torch.Generator().manual_seed(n + Hq)
+        q = torch.randn(max(n, 1), Hq, 128, generator=g) * torch.linspace(0.2, 3.0, 128)
+        ws = torch.empty(B.workspace_bytes(dims, B.OP_FIT), dtype=torch.uint8, device="cuda")
+        out = torch.full((Hkv, 128, 128), float("nan"), device="cuda")
+        B.second_moment(dims, q.cuda(), n, out, ws)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        if n == 0:
+            assert (got == 0).all()
+            continue
+        want = oracle.second_moment(q[:n].numpy(), Hkv)
+        err = np.abs(got - want)
+        assert (err <= 2e-7 * np.maximum(1.0, np.abs(want))).all(), err.max()
+
+
+@pytest.mark.parametrize("geometry", ["single", "pq16"])
+def test_lloyd_iterations(oracle, geometry):
+    """k-means under the query-aware distortion, three iterations of a2ats_encode_keys +
+    a2ats_codebook_update from the same start as the oracle: assignments (near-ties excluded), counts
+    and centroids agree at every iteration, empty codewords keep their value, and the query-aware
+    objective J' never rises."""
+    if geometry == "single":
+        wl = _single("lloyd_single", 2, 4, 2, 3000, 1, 1, seed=12)
+        mode, wkey = B.W_BLOCK, "h_block"
+    else:
+        wl = synth.Workload("lloyd_pq", 2, 4, 2, 128, 16, 3000, 1, 1, seed=12)
+        mode, wkey = B.W_BLOCK, "h_block"
+    hm = synth.make_query_second_moment(wl)
+    n = 3000
+    keys = synth.make_encode_keys(wl, n, stress=True)           # far from the start codebook: clusters move
+    cb = synth.make_codebook(wl) * 0.5
+    dims = H.dims_of(wl, n)
+    ws_e = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+    ws_f = torch.empty(B.workspace_bytes(dims, B.OP_FIT), dtype=torch.uint8, device="cuda")
+    kd, wd = keys.cuda(), hm[wkey].cuda()
+    cb_g = cb.cuda()
+    cb_o = cb.numpy().copy()
+    cdt = torch.int16 if geometry == "single" else torch.uint8
+    prev = None
+    for it in range(3):
+        codes = torch.zeros(wl.batch, wl.n_kv_heads, n, wl.n_sub, dtype=cdt, device="cuda")
+        B.encode_keys(dims, kd, n, 0, cb_g, wd, mode, codes, ws_e)
+        new_g = torch.empty_like(cb_g)
+        counts = torch.empty(wl.n_kv_heads, wl.n_sub, wl.n_centroids, dtype=torch.int32, device="cuda")
+        B.codebook_update(dims, kd, n, 0, codes, cb_g, new_g, counts, ws_f)
+        torch.cuda.synchronize()
+        got_codes = codes.cpu().numpy()
+        got_codes = got_codes.view(np.uint16) if geometry == "single" else got_codes
+        # the oracle's iteration from the GPU's current codebook (float32, as both sides store it)
+        cur = cb_g.cpu().numpy()
+        if geometry == "single":
+            want_codes, b1, b2 = oracle.encode_cholesky(keys, cur, hm[wkey], want_margins=True)
+        else:
+            want_codes, b1, b2 = oracle.encode(keys, cur, hm[wkey], mode, want_margins=True)
+        n_near = H.compare_codes(got_codes, want_codes, b1, b2)
+        # centroid step checked on the GPU's own assignment, so that an excluded near-tie does not leak
+        if geometry == "single":
+            want_cb, want_counts = oracle.lloyd_update(keys, got_codes, cur)
+        else:
+            want_cb = np.empty(cur.shape, dtype=np.float64)
+            want_counts = np.empty((wl.n_kv_heads, wl.n_sub, 256), dtype=np.int64)
+            ds = wl.sub_dim
+            for m in range(wl.n_sub):   # a product quantiser is M independent k-means problems
+                c_m, n_m = oracle.lloyd_update(keys[..., m * ds:(m + 1) * ds], got_codes[..., m:m + 1], cur[:, m:m + 1])
+                want_cb[:, m], want_counts[:, m] = c_m[:, 0], n_m
+        np.testing.assert_array_equal(counts.cpu().numpy().reshape(want_counts.shape), want_counts)
+        err = np.abs(new_g.cpu().numpy().astype(np.float64) - want_cb.reshape(cur.shape))
+        assert (err <= 1e-6 * np.maximum(1.0, np.abs(want_cb.reshape(cur.shape)))).all(), err.max()
+        empty = want_counts.reshape(-1) == 0
+        assert geometry != "single" or empty.any()   # 6000 keys per KV head leave some of 4096 codewords without keys
+        assert (new_g.cpu().numpy().reshape(empty.size, -1)[empty] == cur.reshape(empty.size, -1)[empty]).all()
+        if geometry == "single":
+            j = oracle.distortion(keys, new_g.cpu().numpy(), got_codes, hm["H"].numpy())
+            if prev is not None:
+                assert (j <= prev * (1 + 1e-6)).all(), (j, prev)
+            prev = j
+        H.log(f"{wl.name} iteration {it}: near-tie exclusions {n_near}, codewords in use {(~empty).sum()}")
+        cb_g = new_g

@@ -466,3 +466,55 @@ def test_group_scores_equal_the_scores_of_the_summed_query(oracle):
     wrong = per_head.reshape(Bn, G, Hkv, N).sum(axis=1)          # the h % G mapping
     assert np.abs(wrong - direct).max() > 1e-3
     np.testing.assert_array_equal(oracle.group_scores(direct, Hkv), direct)
+
+
+def test_second_moment_closed_forms(oracle):
+    """H = E[q~^T q~] (section 4.2): for samples that are all the same vector it is that vector's
+    outer product; its trace is the mean squared norm; it is symmetric positive semi-definite; and the
+    heads of a KV head are pooled (h // G)."""
+    rng = np.random.default_rng(5)
+    n, Hkv, G, D = 40, 2, 3, 8
+    q = rng.standard_normal((n, Hkv * G, D))
+    H = oracle.second_moment(q, Hkv)
+    for kv in range(Hkv):
+        grp = q[:, kv * G:(kv + 1) * G, :].reshape(-1, D)
+        assert abs(np.trace(H[kv]) - (grp ** 2).sum() / grp.shape[0]) < 1e-12
+        np.testing.assert_allclose(H[kv], H[kv].T, atol=1e-15)
+        assert np.linalg.eigvalsh(H[kv]).min() > -1e-12
+        v = rng.standard_normal(D)                      # v H v^T = mean (q . v)^2
+        assert abs(v @ H[kv] @ v - ((grp @ v) ** 2).mean()) < 1e-12
+    same = np.broadcast_to(np.arange(1.0, D + 1.0), (n, Hkv * G, D))
+    np.testing.assert_allclose(oracle.second_moment(same, Hkv)[1], np.outer(same[0, 0], same[0, 0]), atol=1e-12)
+
+
+def test_lloyd_iteration_never_raises_the_query_aware_objective(oracle):
+    """k-means under the query-aware distortion (section 4.2): the assignment step and the centroid
+    step each minimise J' = sum (k - c) H (k - c)^T over what they control (for any positive definite H
+    the minimiser over c of a cluster's distortion is its mean), so J' never rises; a hand example
+    pins the means, the counts and the rule for empty clusters."""
+    wl = synth.Workload("lloyd", 2, 2, 2, 128, 1, 300, 1, 1, n_centroids=4096, seed=2)
+    hm = synth.make_query_second_moment(wl)
+    rng = np.random.default_rng(3)
+    cb = synth.make_codebook(wl).double().numpy()[:, :, :64].copy()   # 64 codewords keep the loops short
+    keys = rng.standard_normal((2, 2, 300, 128)).astype(np.float32)
+    Hm = hm["H"].numpy()
+    prev = None
+    for it in range(3):
+        codes = oracle.encode_cholesky(keys, cb.astype(np.float32), hm["h_block"])
+        j_assigned = oracle.distortion(keys, cb.astype(np.float32), codes, Hm)
+        if prev is not None:
+            assert (j_assigned <= prev * (1 + 1e-6)).all()
+        cb32 = cb.astype(np.float32)
+        new, counts = oracle.lloyd_update(keys, codes, cb32)
+        assert counts.sum() == 2 * 2 * 300
+        j_updated = oracle.distortion(keys, new, codes, Hm)
+        assert (j_updated <= j_assigned * (1 + 1e-12)).all()
+        shifted = new + 1e-3 * rng.standard_normal(new.shape) * (counts > 0)[:, None, :, None]
+        assert (oracle.distortion(keys, shifted, codes, Hm) >= j_updated).all()   # the mean is the minimiser
+        prev, cb = j_updated, new
+    k = np.array([[[[1.0, 2.0], [3.0, 6.0], [10.0, 0.0]]]])                 # B = 1, Hkv = 1, three keys of D = 2
+    c = np.array([[[[2], [2], [0]]]])
+    old = np.array([[[[0.0, 0.0], [7.0, 7.0], [9.0, 9.0]]]])
+    new, counts = oracle.lloyd_update(k, c, old)
+    np.testing.assert_array_equal(new[0, 0], [[10.0, 0.0], [7.0, 7.0], [2.0, 4.0]])
+    np.testing.assert_array_equal(counts[0], [1, 0, 2])
