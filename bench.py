@@ -416,6 +416,9 @@ def main():
     ap.add_argument("--group-shared", action="store_true",
                     help="one selection per KV head (sum of the group's scores) instead of one per query head; "
                          "prints a line of its own")
+    ap.add_argument("--kv-on-host", action="store_true",
+                    help="keep the K/V caches in pinned host memory; the attention kernels read the selected rows "
+                         "over PCIe (codes, tables and everything else stay in HBM)")
     ap.add_argument("--codebook-fit", action="store_true",
                     help="offline codebook construction (single-codebook workloads): one Lloyd iteration and one "
                          "second-moment accumulation; prints a line of its own")
@@ -459,6 +462,11 @@ def main():
     for r in range(R):
         x = synth.make_decode_inputs(wl.replace(seed=wl.seed + r), device="cuda")
         x["new_key"] = x["k"][:, :, N - 1:N, :].float().contiguous()
+        if args.kv_on_host:
+            for name in ("k", "v"):
+                host = x[name].cpu().pin_memory()
+                assert B.host_device_pointer(host) == host.data_ptr()
+                x[name + "_hbm"], x[name] = x[name], host
         reps.append(x)
     hm = synth.make_query_second_moment(wl)
     h_diag = hm["h_diag"].cuda()
@@ -579,7 +587,9 @@ def main():
                  "int32 fixed-point scores; f32 K/V",
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": Bn, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D,
-                   "n_sub": M, "ctx_len": N, "top_k": K, "window": w, "replicas_cycled": R},
+                   "n_sub": M, "ctx_len": N, "top_k": K, "window": w, "replicas_cycled": R,
+                   "kv_cache": "pinned host memory, read by the attention kernels over PCIe" if args.kv_on_host
+                   else "HBM"},
         "us_per_decode_step": ms_per_step * 1e3,
         "prologue": "encode_keys + build_lut" if args.separate_prologue else "decode_prologue (one launch)",
         "phase_us_median": ({"encode_1key": med(ph[0]), "wrope_lut": med(ph[1])} if args.separate_prologue else

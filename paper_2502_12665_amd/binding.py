@@ -112,6 +112,21 @@ def _ptr(t: Optional[torch.Tensor]):
     return ctypes.c_void_p(t.data_ptr())
 
 
+def host_device_pointer(t: torch.Tensor) -> int:
+    """Device-side address of a pinned host tensor (hipHostGetDevicePointer); raises if the memory is
+    not mapped into the device's address space.  For caches kept in host memory and read by the GPU
+    over PCIe."""
+    assert t.device.type == "cpu" and t.is_pinned() and t.is_contiguous()
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipHostGetDevicePointer.restype = ctypes.c_int
+    hip.hipHostGetDevicePointer.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_void_p, ctypes.c_uint]
+    dev = ctypes.c_void_p()
+    rc = hip.hipHostGetDevicePointer(ctypes.byref(dev), ctypes.c_void_p(t.data_ptr()), 0)
+    if rc != 0 or not dev.value:
+        raise RuntimeError(f"hipHostGetDevicePointer failed ({rc}): the tensor is not mapped for the device")
+    return int(dev.value)
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 

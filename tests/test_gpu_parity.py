@@ -672,3 +672,26 @@ def test_lloyd_iterations(oracle, geometry):
             prev = j
         H.log(f"{wl.name} iteration {it}: near-tie exclusions {n_near}, codewords in use {(~empty).sum()}")
         cb_g = new_g
+
+
+def test_kv_cache_in_pinned_host_memory(oracle):
+    """Heterogeneous placement (section 4.3 keeps the KV cache in host memory): the attention kernels
+    read K and V rows straight from pinned host memory over PCIe; everything else stays in HBM."""
+    wl = synth.Workload("kv_on_host", 2, 8, 2, 128, 16, 6000, 96, 64, seed=9)
+    x = synth.make_decode_inputs(wl)
+    xd = H.to_dev({k: v for k, v in x.items() if k not in ("k", "v")})
+    kh, vh = x["k"].pin_memory(), x["v"].pin_memory()
+    for t in (kh, vh):   # the address the device uses must be the one the call is given
+        assert B.host_device_pointer(t) == t.data_ptr()
+    dims = H.dims_of(wl, 6000)
+    st = B.DecodeState(dims, wl.top_k, wl.window, 0, kh.dtype, x["inv_freq"], wl.wrope_b)
+    B.build_lut(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, st.lut, st.lut_scale)
+    B.score_topk(dims, xd["codes"], st.lut, st.lut_scale, wl.top_k, wl.window, 0, None, st.topk_idx, st.topk_count,
+                 None, None, st.ws)
+    B.sparse_attn(dims, xd["q"], st.q_rot, kh, vh, st.topk_idx, st.topk_count, wl.top_k, wl.window, 0, st.cos_win,
+                  st.sin_win, None, st.out, st.ws)
+    torch.cuda.synchronize()
+    want = oracle.sparse_attn(x["q"], x["k"], x["v"], st.topk_idx.cpu().numpy(), st.topk_count.cpu().numpy(),
+                              wl.ctx_len, wl.window, 0, x["inv_freq"], float(wl.wrope_b))
+    aerr = np.abs(st.out.float().cpu().numpy().astype(np.float64) - want).max()
+    assert aerr <= 2e-2, aerr
