@@ -381,6 +381,19 @@ def codebook_fit(args, torch, B, synth, wl):
     med = lambda v: float(sorted(v)[len(v) // 2])
     ph = [med([ev[i][p].elapsed_time(ev[i][p + 1]) for i in range(steps)]) for p in range(3)]
     flop = n_keys * 4096.0 * 128.0 * 2.0
+    # k-means++ seeding (4096 sequential draws, one workgroup per KV head) on a calibration-sized subset
+    n_seed = 8192
+    dims_s = B.make_dims(wl.batch, wl.n_q_heads, Hkv, wl.head_dim, wl.n_sub, n_seed, n_centroids=wl.n_centroids)
+    ws_s = torch.empty(B.workspace_bytes(dims_s, B.OP_SEED), dtype=torch.uint8, device="cuda")
+    u = torch.rand(Hkv, 4096, dtype=torch.float64, device="cuda")
+    seed_keys = keys[:, :, :n_seed].contiguous()
+    seed_cb = torch.empty_like(cb)
+    B.kmeanspp_seed(dims_s, seed_keys, n_seed, w, B.W_BLOCK, u, seed_cb, None, ws_s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    B.kmeanspp_seed(dims_s, seed_keys, n_seed, w, B.W_BLOCK, u, seed_cb, None, ws_s)
+    torch.cuda.synchronize()
+    seed_ms = (time.perf_counter() - t0) * 1e3
     print(json.dumps({
         "metric": "keys/s per Lloyd iteration (query-aware k-means: assignment under the full matrix H + centroid "
                   "step; plus one second-moment accumulation)",
@@ -391,6 +404,7 @@ def codebook_fit(args, torch, B, synth, wl):
         "config": {"workload": wl.name + " codebook construction", "keys": n_keys, "codewords": wl.n_centroids,
                    "query_rows": N * wl.n_q_heads},
         "phase_ms_median": {"assign": ph[0], "centroid_step": ph[1], "second_moment": ph[2]},
+        "kmeanspp_seed_ms": {"keys_per_kv_head": wl.batch * n_seed, "ms": seed_ms},
         "roofline": {"kernel": "encode_single_kernel", "bound": "mfma", "achieved": flop / (ph[0] * 1e-3) / 1e12,
                      "peak": 2500.0, "unit": "TFLOP/s", "frac": flop / (ph[0] * 1e-3) / 1e12 / 2500.0,
                      "traffic": None, "note": "algorithmic flops of the assignment over its whole call"},

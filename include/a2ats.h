@@ -83,7 +83,8 @@ typedef enum a2ats_status {
 enum { A2ATS_F32 = 0, A2ATS_BF16 = 1 };                       /* element types of q / k / v / out */
 enum { A2ATS_W_NONE = 0, A2ATS_W_DIAG = 1, A2ATS_W_BLOCK = 2 }; /* encoder distortion              */
 enum { A2ATS_W_PREPARED = 0x100 };   /* flag for weight_mode, see a2ats_encode_prepare */
-enum { A2ATS_OP_ENCODE = 0, A2ATS_OP_LUT = 1, A2ATS_OP_SCORE_TOPK = 2, A2ATS_OP_ATTN = 3, A2ATS_OP_FIT = 4 };
+enum { A2ATS_OP_ENCODE = 0, A2ATS_OP_LUT = 1, A2ATS_OP_SCORE_TOPK = 2, A2ATS_OP_ATTN = 3, A2ATS_OP_FIT = 4,
+       A2ATS_OP_SEED = 5 };
 
 int a2ats_version(void);
 const char* a2ats_status_string(int status);
@@ -279,6 +280,23 @@ int a2ats_sparse_attn_shared(const a2ats_dims* dims, const void* q, const float*
  * The sums are float64 hardware atomics: the last bits of a mean can differ from run to run.
  * Both calls need a2ats_workspace_bytes(dims, A2ATS_OP_FIT, 0, 0) bytes of workspace.
  */
+/*
+ * k-means++ seeding of a single codebook under the query-aware distortion (section 4.2 initialises
+ * its k-means with k-means++).  The keys of all B sequences are pooled per KV head (row i = b*n_new
+ * + j); codeword 0 is row min(rows - 1, floor(u[kv,0] * rows)); codeword r > 0 is the first row whose
+ * inclusive prefix sum of d exceeds u[kv,r] * sum(d) (so row i is drawn with probability d_i / sum(d)), d_i being the distortion of row i to the nearest
+ * codeword chosen so far, (k - c) H (k - c)^T evaluated as ||z_i - z_c||^2 in float64 over z = k L
+ * rounded once to float32 (if every d is zero: row floor(u * rows)).
+ *   keys, weights, weight_mode   as in a2ats_encode_keys, 1 <= n_new <= ctx_stride
+ *   u             [dev, f64 Hkv*4096]      uniform numbers in [0, 1) supplied by the caller
+ *   codebook_out  [dev, out, f32 Hkv*4096*D] the chosen keys
+ *   picks         [dev, out, nullable, int32 Hkv*4096] their row numbers
+ * Workspace a2ats_workspace_bytes(dims, A2ATS_OP_SEED, 0, 0).  One workgroup per KV head runs the 4096
+ * sequential draws: meant for calibration sets of up to ~10^5 keys per KV head.  Single codebook only.
+ */
+int a2ats_kmeanspp_seed(const a2ats_dims* dims, const float* keys, int32_t n_new, const float* weights,
+                        int weight_mode, const double* u, float* codebook_out, int32_t* picks, void* ws,
+                        size_t ws_bytes, void* stream);
 int a2ats_second_moment(const a2ats_dims* dims, const float* q_rot, int64_t n_samples, float* h_out,
                         void* ws, size_t ws_bytes, void* stream);
 int a2ats_codebook_update(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,

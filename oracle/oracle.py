@@ -288,3 +288,39 @@ def lloyd_update(keys, codes, codebook):
         used = counts[kv] > 0
         new[kv, 0][used] = sums[used] / counts[kv][used, None]
     return new, counts
+
+
+def kmeanspp_seed(keys, h_full, u, n_codewords: int):
+    """k-means++ seeding (Arthur & Vassilvitskii; section 4.2 initialises its k-means with it) under
+    the query-aware distortion (k - c) H (k - c)^T = ||z_k - z_c||^2, z = k L, H = L L^T.
+    keys [B,Hkv,n,D] (pooled per KV head, row i = b*n + j), H [Hkv,D,D] float64 (None: identity),
+    u [Hkv,n_codewords] uniform numbers in [0,1) standing in for the random draws.  Codeword 0 is row
+    floor(u_0 rows); codeword r is the first row whose inclusive prefix sum of d exceeds u_r sum(d)
+    (inverse of the cumulative distribution: a row is drawn with probability d_i / sum(d)),
+    d_i the distortion of row i to the nearest codeword chosen so far.  z is rounded once to
+    float32 (as the encoder stores it); everything else is float64.  Returns picks [Hkv,n_codewords]."""
+    k = _f64(keys)
+    B, Hkv, n, D = k.shape
+    uu = _f64(u)
+    picks = np.zeros((Hkv, n_codewords), dtype=np.int64)
+    for kv in range(Hkv):
+        rows = k[:, kv].reshape(B * n, D)
+        Lc = np.eye(D) if h_full is None else np.linalg.cholesky(_f64(h_full)[kv])
+        z = (rows @ Lc).astype(np.float32).astype(np.float64)
+        pick = min(B * n - 1, int(uu[kv, 0] * (B * n)))
+        d = None
+        for r in range(n_codewords):
+            picks[kv, r] = pick
+            if r == n_codewords - 1:
+                break
+            e = z - z[pick]
+            dist = np.zeros(B * n)
+            for t in range(D):          # plain left-to-right sum over the dimensions
+                dist += e[:, t] * e[:, t]
+            d = dist if d is None else np.minimum(d, dist)
+            cum = np.cumsum(d)
+            if cum[-1] > 0.0:
+                pick = min(B * n - 1, int(np.searchsorted(cum, uu[kv, r + 1] * cum[-1], side="right")))
+            else:
+                pick = min(B * n - 1, int(uu[kv, r + 1] * (B * n)))
+    return picks

@@ -18,12 +18,12 @@ LIB_PATH = os.path.join(_HERE, "liba2ats.so")
 F32, BF16 = 0, 1
 W_NONE, W_DIAG, W_BLOCK = 0, 1, 2
 W_PREPARED = 0x100
-OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN, OP_FIT = 0, 1, 2, 3, 4
+OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN, OP_FIT, OP_SEED = 0, 1, 2, 3, 4, 5
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes", "a2ats_encode_prepare",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel",
            "a2ats_decode_prologue", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
-           "a2ats_second_moment", "a2ats_codebook_update"]
+           "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed"]
 
 
 class A2atsError(RuntimeError):
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
         L.a2ats_sparse_attn_shared.argtypes = L.a2ats_sparse_attn.argtypes
         L.a2ats_build_lut_shared.restype = ctypes.c_int
         L.a2ats_build_lut_shared.argtypes = L.a2ats_build_lut.argtypes
+        L.a2ats_kmeanspp_seed.restype = ctypes.c_int
+        L.a2ats_kmeanspp_seed.argtypes = [dp, vp, i32, vp, ctypes.c_int, vp, vp, vp, vp, sz, vp]
         L.a2ats_second_moment.restype = ctypes.c_int
         L.a2ats_second_moment.argtypes = [dp, vp, ctypes.c_int64, vp, vp, sz, vp]
         L.a2ats_codebook_update.restype = ctypes.c_int
@@ -232,6 +234,13 @@ def sparse_attn_shared(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_co
                                         n_sink, _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _ptr(ws),
                                         0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_sparse_attn_shared")
+
+
+def kmeanspp_seed(dims: Dims, keys, n_new: int, weights, weight_mode: int, u, codebook_out, picks, ws: torch.Tensor):
+    rc = lib().a2ats_kmeanspp_seed(ctypes.byref(dims), _ptr(keys), n_new, _ptr(weights), weight_mode, _ptr(u),
+                                   _ptr(codebook_out), _ptr(picks), _ptr(ws), ws.numel() * ws.element_size(),
+                                   _stream())
+    _check(rc, "a2ats_kmeanspp_seed")
 
 
 def second_moment(dims: Dims, q_rot, n_samples: int, h_out, ws: torch.Tensor):

@@ -72,6 +72,7 @@ size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t
       return a2ats::make_attn_plan(*d, top_k, window, 64).bytes;
     }
     case A2ATS_OP_FIT: return a2ats::fit_ws_bytes(*d);
+    case A2ATS_OP_SEED: return a2ats::single_codebook(*d) ? a2ats::kmeanspp_ws_bytes(*d) : (size_t)-1;
     default: return (size_t)-1;
   }
 }
@@ -137,6 +138,23 @@ int a2ats_encode_prepare(const a2ats_dims* d, const float* codebook, const float
   if (!a2ats::single_codebook(*d)) return A2ATS_OK;   // nothing worth keeping between calls
   if (!ws || misaligned16(ws) || ws_bytes < a2ats::encode_single_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
   const hipError_t e = a2ats::launch_encode_single_prepare(*d, codebook, weights, weight_mode, ws, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_kmeanspp_seed(const a2ats_dims* d, const float* keys, int32_t n_new, const float* weights,
+                        int weight_mode, const double* u, float* codebook_out, int32_t* picks, void* ws,
+                        size_t ws_bytes, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (!a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
+  if (weight_mode != A2ATS_W_NONE && weight_mode != A2ATS_W_DIAG && weight_mode != A2ATS_W_BLOCK)
+    return A2ATS_ERR_INVALID_ARG;
+  if (n_new < 1 || n_new > d->ctx_stride || d->batch < 1) return A2ATS_ERR_INVALID_ARG;
+  if (!keys || !u || !codebook_out || misaligned16(keys)) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE && !weights) return A2ATS_ERR_INVALID_ARG;
+  if (!ws || misaligned16(ws) || ws_bytes < a2ats::kmeanspp_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
+  const hipError_t e = a2ats::launch_kmeanspp_seed(*d, keys, n_new, weights, weight_mode, u, codebook_out, picks,
+                                                   ws, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 

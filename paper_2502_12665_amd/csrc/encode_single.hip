@@ -638,6 +638,160 @@ __global__ void encode_single_sweep_pick_kernel(const double* __restrict__ part,
   codes[(size_t)bkv * ctx_stride + pos0 + j] = (uint16_t)arg;
 }
 
+// ------------------------------------------------------------------------------------------
+// k-means++ seeding under the query-aware distortion (section 4.2 initialises its k-means that
+// way): the first codeword is key floor(u_0 n), every further one is drawn with probability
+// proportional to the distortion to the nearest codeword chosen so far.  The draws are sequential,
+// so one workgroup per KV head runs all of them; the caller supplies the uniform numbers u.
+// Distortions are ||z_i - z_c||^2 in float64 over the float32 transformed keys z = k L.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void scale_keys_kernel(const float* __restrict__ keys, const double* __restrict__ sd,
+                                                         float* __restrict__ z, int Hkv, size_t n_rows_per_seq) {
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;   // element of [B*Hkv][n][128]
+  const int bkv = blockIdx.y, kv = bkv % Hkv;
+  if (e >= n_rows_per_seq * kD) return;
+  const size_t at = (size_t)bkv * n_rows_per_seq * kD + e;
+  z[at] = (float)((double)keys[at] * sd[(size_t)kv * kD + e % kD]);
+}
+
+constexpr int kSeedThreads = 1024;
+constexpr int kSeedChunk = 4;   // consecutive rows per thread of the update kernel = rows per partial sum
+
+// State of the draws of one KV head between the kernels of a round.
+struct SeedState {
+  long pick;          // row of the codeword drawn last
+  float zc[kD];       // its transformed key
+};
+
+__device__ __forceinline__ const float* seed_row(const float* base, long i, int kv, int Hkv, int n_new) {
+  return base + (((size_t)(i / n_new) * Hkv + kv) * n_new + i % n_new) * kD;
+}
+
+// Records draw r (st->pick): the codeword is the key itself; keeps its transformed key for the update.
+__device__ __forceinline__ void seed_record(SeedState* st, const float* keys, const float* z, float* codebook_out,
+                                            int32_t* picks, long pick, int r, int kv, int Hkv, int n_new, int tid) {
+  if (tid < kD) {
+    codebook_out[((size_t)kv * kCW + r) * kD + tid] = seed_row(keys, pick, kv, Hkv, n_new)[tid];
+    st->zc[tid] = seed_row(z, pick, kv, Hkv, n_new)[tid];
+  }
+  if (tid == 0) {
+    st->pick = pick;
+    if (picks) picks[(size_t)kv * kCW + r] = (int32_t)pick;
+  }
+}
+
+__global__ __launch_bounds__(128) void seed_first_kernel(const float* __restrict__ keys, const float* __restrict__ z,
+                                                         const double* __restrict__ u, SeedState* __restrict__ state,
+                                                         float* __restrict__ codebook_out, int32_t* __restrict__ picks,
+                                                         int B, int Hkv, int n_new) {
+  const int kv = blockIdx.x;
+  const long rows = (long)B * n_new;
+  const long pick = min(rows - 1, (long)(u[(size_t)kv * kCW] * (double)rows));
+  seed_record(state + kv, keys, z, codebook_out, picks, pick, 0, kv, Hkv, n_new, threadIdx.x);
+}
+
+// Distortions of every row to the codeword drawn last, running minimum, and one partial sum per
+// kSeedChunk consecutive rows (summed in row order).
+__global__ __launch_bounds__(256) void seed_update_kernel(const float* __restrict__ z, const SeedState* __restrict__ state,
+                                                          double* __restrict__ dmin, double* __restrict__ partial,
+                                                          int B, int Hkv, int n_new, int first_round) {
+  __shared__ double s_zc[kD];
+  const int kv = blockIdx.y, tid = threadIdx.x;
+  const long rows = (long)B * n_new, n_part = (rows + kSeedChunk - 1) / kSeedChunk;
+  if (tid < kD) s_zc[tid] = (double)state[kv].zc[tid];
+  __syncthreads();
+  const long p = (long)blockIdx.x * 256 + tid;
+  if (p >= n_part) return;
+  double* d = dmin + (size_t)kv * rows;
+  double own = 0.0;
+  for (long i = p * kSeedChunk; i < min(rows, (p + 1) * kSeedChunk); ++i) {
+    const float4* zi = (const float4*)seed_row(z, i, kv, Hkv, n_new);
+    double acc = 0.0;
+#pragma unroll 8
+    for (int t4 = 0; t4 < kD / 4; ++t4) {
+      const float4 f = zi[t4];
+      const double e0 = (double)f.x - s_zc[4 * t4], e1 = (double)f.y - s_zc[4 * t4 + 1];
+      const double e2 = (double)f.z - s_zc[4 * t4 + 2], e3 = (double)f.w - s_zc[4 * t4 + 3];
+      acc += e0 * e0;
+      acc += e1 * e1;
+      acc += e2 * e2;
+      acc += e3 * e3;
+    }
+    const double dm = first_round ? acc : fmin(d[i], acc);
+    d[i] = dm;
+    own += dm;
+  }
+  partial[(size_t)kv * n_part + p] = own;
+}
+
+// Draw r: the first row whose inclusive prefix sum of the distortions exceeds u_r times their total.
+__global__ __launch_bounds__(kSeedThreads) void seed_pick_kernel(
+    const float* __restrict__ keys, const float* __restrict__ z, const double* __restrict__ u,
+    const double* __restrict__ dmin, const double* __restrict__ partial, SeedState* __restrict__ state,
+    float* __restrict__ codebook_out, int32_t* __restrict__ picks, int B, int Hkv, int n_new, int r) {
+  __shared__ double s_wave[kSeedThreads / 64];
+  __shared__ long s_pick;
+  __shared__ int s_owner;
+  const int kv = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const long rows = (long)B * n_new, n_part = (rows + kSeedChunk - 1) / kSeedChunk;
+  const long per = (n_part + kSeedThreads - 1) / kSeedThreads;
+  const long p_lo = min(n_part, tid * per), p_hi = min(n_part, p_lo + per);   // this thread's contiguous partials
+  const double* pk = partial + (size_t)kv * n_part;
+  double own = 0.0;
+  for (long p = p_lo; p < p_hi; ++p) own += pk[p];
+  double inc = own;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const double o = __shfl_up(inc, off);
+    if (lane >= off) inc += o;
+  }
+  if (lane == 63) s_wave[wave] = inc;
+  __syncthreads();
+  double base = 0.0, total = 0.0;
+  for (int w = 0; w < kSeedThreads / 64; ++w) {
+    if (w < wave) base += s_wave[w];
+    total += s_wave[w];
+  }
+  base += inc - own;
+  const double ur = u[(size_t)kv * kCW + r], target = ur * total;
+  // all distortions zero (every key equals a chosen codeword): a uniform draw instead
+  if (tid == 0) {
+    s_pick = total > 0.0 ? 0 : min(rows - 1, (long)(ur * (double)rows));
+    s_owner = -1;
+  }
+  __syncthreads();
+  // the row belongs to the last thread whose exclusive prefix does not exceed the target
+  // (prefixes do not decrease with the thread index)
+  const uint64_t below = __ballot(total > 0.0 && p_lo < p_hi && base <= target);
+  if (lane == 0 && below) atomicMax(&s_owner, wave * 64 + 63 - (int)__clzll((unsigned long long)below));
+  __syncthreads();
+  if (tid == s_owner) {
+    const double* d = dmin + (size_t)kv * rows;
+    double run = base;
+    long found = min(rows, p_hi * kSeedChunk) - 1;   // (rounding: if the walk falls short, the thread's last row)
+    bool done = false;
+    for (long p = p_lo; p < p_hi && !done; ++p) {
+      if (run + pk[p] > target || p == p_hi - 1) {   // the row is in this partial (or the walk ends here)
+        for (long i = p * kSeedChunk; i < min(rows, (p + 1) * kSeedChunk); ++i) {
+          run += d[i];
+          if (run > target) {
+            found = i;
+            done = true;
+            break;
+          }
+        }
+        if (!done && p < p_hi - 1) continue;   // rounding: the partial fell just short; go on
+        done = true;
+      } else {
+        run += pk[p];
+      }
+    }
+    s_pick = found;
+  }
+  __syncthreads();
+  seed_record(state + kv, keys, z, codebook_out, picks, s_pick, r, kv, Hkv, n_new, tid);
+}
+
 LdsSlot g_factor_lds[16];
 
 }  // namespace
@@ -720,6 +874,71 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
   hipLaunchKernelGGL(encode_single_recheck_kernel, dim3(re_grid), dim3(256), 0, stream, keys, mode, Lmat, sd, czT,
                      (uint16_t*)codes, counter, (const uint32_t*)list, Hkv, n_new, pos0, d.ctx_stride);
   return hipGetLastError();
+}
+
+struct SeedWs {
+  size_t off_z, off_d, off_partial, off_state, bytes;
+};
+static SeedWs seed_ws(const a2ats_dims& d) {
+  const size_t rows = (size_t)d.batch * d.n_kv_heads * (size_t)d.ctx_stride;
+  SeedWs w;
+  size_t o = enc_single_ws(d).bytes;
+  auto take = [&](size_t bytes) {
+    const size_t at = o;
+    o += (bytes + 255) & ~(size_t)255;
+    return at;
+  };
+  w.off_z = take(rows * kD * sizeof(float));
+  w.off_d = take(rows * sizeof(double));
+  w.off_partial = take((rows / kSeedChunk + d.n_kv_heads) * sizeof(double));
+  w.off_state = take((size_t)d.n_kv_heads * sizeof(SeedState));
+  w.bytes = o;
+  return w;
+}
+
+size_t kmeanspp_ws_bytes(const a2ats_dims& d) { return seed_ws(d).bytes; }
+
+hipError_t launch_kmeanspp_seed(const a2ats_dims& d, const float* keys, int n_new, const float* weights, int mode,
+                                const double* u, float* codebook_out, int32_t* picks, void* ws, hipStream_t stream) {
+  if (d.n_kv_heads == 0) return hipSuccess;
+  const EncWs w = enc_single_ws(d);
+  const SeedWs sw = seed_ws(d);
+  uint8_t* base = (uint8_t*)ws;
+  double* Lmat = (double*)(base + w.off_L);
+  double* sd = (double*)(base + w.off_sd);
+  float* cstat = (float*)(base + w.off_cstat);
+  float* z = (float*)(base + sw.off_z);
+  double* dmin = (double*)(base + sw.off_d);
+  double* partial = (double*)(base + sw.off_partial);
+  SeedState* state = (SeedState*)(base + sw.off_state);
+  const int Hkv = d.n_kv_heads, bkv = d.batch * Hkv;
+  const size_t factor_lds = (size_t)kD * kD * sizeof(double);
+  hipError_t err = allow_dynamic_lds(encode_single_factor_kernel, factor_lds, g_factor_lds);
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(encode_single_factor_kernel, dim3(Hkv), dim3(256), factor_lds, stream, weights, mode, Lmat, sd,
+                     cstat);
+  if ((err = hipGetLastError()) != hipSuccess) return err;
+  if (mode == A2ATS_W_BLOCK)
+    hipLaunchKernelGGL(encode_single_transform_kernel, dim3((n_new + 63) / 64, bkv), dim3(256), 0, stream, keys, Lmat,
+                       z, Hkv, n_new, 0, n_new, n_new);
+  else
+    hipLaunchKernelGGL(scale_keys_kernel, dim3((unsigned)(((size_t)n_new * kD + 255) / 256), bkv), dim3(256), 0,
+                       stream, keys, sd, z, Hkv, (size_t)n_new);
+  if ((err = hipGetLastError()) != hipSuccess) return err;
+  // 4096 sequential draws: per draw one kernel over all rows (distortions to the codeword drawn
+  // last) and one workgroup per KV head that turns the partial sums into the next draw
+  const long rows = (long)d.batch * n_new, n_part = (rows + kSeedChunk - 1) / kSeedChunk;
+  hipLaunchKernelGGL(seed_first_kernel, dim3(Hkv), dim3(128), 0, stream, keys, z, u, state, codebook_out, picks,
+                     d.batch, Hkv, n_new);
+  if ((err = hipGetLastError()) != hipSuccess) return err;
+  for (int r = 1; r < kCW; ++r) {
+    hipLaunchKernelGGL(seed_update_kernel, dim3((unsigned)((n_part + 255) / 256), Hkv), dim3(256), 0, stream, z, state,
+                       dmin, partial, d.batch, Hkv, n_new, r == 1 ? 1 : 0);
+    hipLaunchKernelGGL(seed_pick_kernel, dim3(Hkv), dim3(kSeedThreads), 0, stream, keys, z, u, dmin, partial, state,
+                       codebook_out, picks, d.batch, Hkv, n_new, r);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+  }
+  return hipSuccess;
 }
 
 }  // namespace a2ats

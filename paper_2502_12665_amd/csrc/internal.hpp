@@ -92,6 +92,9 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
                                 const float* codebook, const float* weights, int mode, bool prepared, void* codes,
                                 void* ws, hipStream_t stream);
 
+size_t kmeanspp_ws_bytes(const a2ats_dims& d);
+hipError_t launch_kmeanspp_seed(const a2ats_dims& d, const float* keys, int n_new, const float* weights, int mode,
+                                const double* u, float* codebook_out, int32_t* picks, void* ws, hipStream_t stream);
 size_t fit_ws_bytes(const a2ats_dims& d);
 hipError_t launch_second_moment(const a2ats_dims& d, const float* q_rot, int64_t n_samples, float* h_out, void* ws,
                                 hipStream_t stream);

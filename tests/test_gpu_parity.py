@@ -695,3 +695,33 @@ def test_kv_cache_in_pinned_host_memory(oracle):
                               wl.ctx_len, wl.window, 0, x["inv_freq"], float(wl.wrope_b))
     aerr = np.abs(st.out.float().cpu().numpy().astype(np.float64) - want).max()
     assert aerr <= 2e-2, aerr
+
+
+@pytest.mark.parametrize("mode", ["block", "none"])
+def test_kmeanspp_seeding(oracle, mode):
+    """The 4096 sequential k-means++ draws under the query-aware distortion pick the same keys as the
+    oracle (same uniform numbers), and the seed codebook is exactly those keys; duplicated keys included,
+    so that zero distortions occur."""
+    wl = _single("seed", 2, 4, 2, 2600, 1, 1, seed=17)
+    hm = synth.make_query_second_moment(wl)
+    n = 2600
+    keys = synth.make_encode_keys(wl, n, stress=True)
+    keys[:, :, 100:140] = keys[:, :, 60:100]                     # 40 duplicated keys per sequence
+    g = torch.Generator().manual_seed(3)
+    u = torch.rand(wl.n_kv_heads, 4096, generator=g, dtype=torch.float64)
+    u[0, 7] = 0.0
+    dims = H.dims_of(wl, n)
+    ws = torch.empty(B.workspace_bytes(dims, B.OP_SEED), dtype=torch.uint8, device="cuda")
+    out = torch.full((wl.n_kv_heads, 1, 4096, 128), float("nan"), device="cuda")
+    picks = torch.full((wl.n_kv_heads, 4096), -1, dtype=torch.int32, device="cuda")
+    w = hm["h_block"].cuda() if mode == "block" else None
+    B.kmeanspp_seed(dims, keys.cuda(), n, w, B.W_BLOCK if mode == "block" else B.W_NONE, u.cuda(), out, picks, ws)
+    torch.cuda.synchronize()
+    hfull = hm["h_block"].numpy().astype(np.float64)[:, 0] if mode == "block" else None
+    want = oracle.kmeanspp_seed(keys, hfull, u.numpy(), 4096)
+    got = picks.cpu().numpy()
+    first_diff = np.argmax(got != want, axis=1)
+    assert (got == want).all(), f"picks differ from draw {first_diff} on"
+    pooled = keys.permute(1, 0, 2, 3).reshape(wl.n_kv_heads, wl.batch * n, 128)
+    for kv in range(wl.n_kv_heads):
+        assert torch.equal(out[kv, 0].cpu(), pooled[kv][torch.as_tensor(want[kv])])

@@ -518,3 +518,31 @@ def test_lloyd_iteration_never_raises_the_query_aware_objective(oracle):
     new, counts = oracle.lloyd_update(k, c, old)
     np.testing.assert_array_equal(new[0, 0], [[10.0, 0.0], [7.0, 7.0], [2.0, 4.0]])
     np.testing.assert_array_equal(counts[0], [1, 0, 2])
+
+
+def test_kmeanspp_seeding_properties(oracle):
+    """k-means++ draws: never the same key twice while distinct keys remain (a chosen key has distortion
+    0, so no prefix step reaches a target at it); with u = 0 every draw is the first key with positive
+    distortion; on well-separated clusters the draws hit every cluster once before any twice; and the
+    draw is D^2-weighted under H, not under the identity (a direction H ignores does not attract draws)."""
+    rng = np.random.default_rng(8)
+    D, n = 16, 60
+    keys = rng.standard_normal((1, 1, n, D)).astype(np.float32)
+    u = rng.random((1, n))
+    p = oracle.kmeanspp_seed(keys, None, u, n)[0]
+    assert sorted(p.tolist()) == list(range(n))                       # n draws from n distinct keys: a permutation
+    p0 = oracle.kmeanspp_seed(keys, None, np.zeros((1, 4)), 4)[0]
+    assert p0[0] == 0 and p0[1] == 1                                  # u = 0: first key, then the first with d > 0
+    centres = 100.0 * np.eye(D)[:5]
+    cl = np.repeat(np.arange(5), 12)
+    ck = (centres[cl] + 0.01 * rng.standard_normal((60, D))).astype(np.float32)[None, None]
+    pc = oracle.kmeanspp_seed(ck, None, rng.random((1, 5)), 5)[0]
+    assert sorted(cl[pc].tolist()) == [0, 1, 2, 3, 4]
+    # H that ignores dimension 0: keys that differ only there are at distortion ~0 from each other
+    Hm = np.diag([1e-12] + [1.0] * (D - 1))[None]
+    far0 = np.zeros((1, 1, 40, D), dtype=np.float32)
+    far0[0, 0, :20, 0] = 1000.0 * rng.standard_normal(20)             # spread along the ignored direction
+    far0[0, 0, 20:, 1] = 5.0 + rng.random(20)                          # a modest offset in a direction that counts
+    ph = oracle.kmeanspp_seed(far0, Hm, np.array([[0.0, 0.5]]), 2)[0]
+    pi = oracle.kmeanspp_seed(far0, None, np.array([[0.0, 0.5]]), 2)[0]
+    assert ph[1] >= 20 and pi[1] < 20
