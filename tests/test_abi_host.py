@@ -85,6 +85,50 @@ def test_dims_validation_and_plans(binding):
         binding.workspace_bytes(bad, binding.OP_LUT)
 
 
+def test_validation_of_the_single_codebook_and_construction_calls(binding):
+    """Argument checks of the entry points added for the paper's own geometry (one codebook of 4096,
+    16-bit codes), the selection shared per KV head and the offline construction: all on the host,
+    before any launch."""
+    L = binding.lib()
+    null, one = ctypes.c_void_p(0), ctypes.c_void_p(16)
+    pq = binding.make_dims(2, 8, 2, 128, 16, 4096)
+    sc = binding.make_dims(2, 8, 2, 128, 1, 4096, n_centroids=4096)
+    assert binding.lut_elems(sc) == 2 * 8 * 4096
+    assert binding.workspace_bytes(sc, binding.OP_SCORE_TOPK, 64, 16) == 0
+    for op in (binding.OP_ENCODE, binding.OP_FIT, binding.OP_SEED):
+        assert binding.workspace_bytes(sc, op) > 0
+    assert binding.workspace_bytes(sc, binding.OP_SEED) > binding.workspace_bytes(sc, binding.OP_ENCODE)
+    with pytest.raises(binding.A2atsError):
+        binding.workspace_bytes(pq, binding.OP_SEED)                       # seeding: single codebook only
+    # a codebook of 4096 needs M = 1, ds = 128
+    assert L.a2ats_build_lut(ctypes.byref(binding.make_dims(1, 4, 1, 128, 16, 64, n_centroids=4096, sub_dim=8)),
+                             one, 0, one, one, one, one, one, one, null) == -2
+    # encoder: every mode needs the workspace; prepared flag accepted; bad mode refused
+    assert L.a2ats_encode_keys(ctypes.byref(sc), one, 4, 0, one, null, 0, one, null, 0, null) == -3
+    assert L.a2ats_encode_keys(ctypes.byref(sc), one, 4, 0, one, null, 0x100, one, one, 64, null) == -3
+    assert L.a2ats_encode_keys(ctypes.byref(sc), one, 4, 0, one, null, 0x103, one, one, 1 << 40, null) == -1
+    assert L.a2ats_encode_prepare(ctypes.byref(sc), one, null, 2, one, 1 << 40, null) == -1   # weights missing
+    assert L.a2ats_encode_prepare(ctypes.byref(sc), one, one, 2, null, 0, null) == -3
+    assert L.a2ats_encode_prepare(ctypes.byref(pq), one, one, 2, null, 0, null) == 0          # nothing to keep
+    assert L.a2ats_decode_prologue(ctypes.byref(sc), one, 1, 0, one, null, 0, one, one, 0, one, one, one, one,
+                                   one, null) == -2
+    # shared selection
+    assert L.a2ats_build_lut_shared(ctypes.byref(sc), one, 0, one, one, one, one, one, one, null) == -2
+    assert L.a2ats_build_lut_shared(ctypes.byref(pq), one, 0, one, one, one, null, one, one, null) == -1
+    assert L.a2ats_sparse_attn_shared(ctypes.byref(pq), one, one, one, one, 1, one, one, 64, 16, 0, one, one, null,
+                                      one, null, 0, null) == -3
+    # construction
+    assert L.a2ats_second_moment(ctypes.byref(pq), one, -1, one, one, 1 << 40, null) == -1
+    assert L.a2ats_second_moment(ctypes.byref(pq), one, 10, one, null, 0, null) == -3
+    assert L.a2ats_codebook_update(ctypes.byref(pq), one, 4, 4094, one, one, one, null, one, 1 << 40, null) == -1
+    assert L.a2ats_codebook_update(ctypes.byref(pq), one, 4, 0, one, one, null, null, one, 1 << 40, null) == -1
+    assert L.a2ats_codebook_update(ctypes.byref(pq), one, 4, 0, one, one, one, null, one, 8, null) == -3
+    assert L.a2ats_kmeanspp_seed(ctypes.byref(pq), one, 4, null, 0, one, one, null, one, 1 << 40, null) == -2
+    assert L.a2ats_kmeanspp_seed(ctypes.byref(sc), one, 0, null, 0, one, one, null, one, 1 << 40, null) == -1
+    assert L.a2ats_kmeanspp_seed(ctypes.byref(sc), one, 4, null, 2, one, one, null, one, 1 << 40, null) == -1
+    assert L.a2ats_kmeanspp_seed(ctypes.byref(sc), one, 4, null, 0, one, one, null, one, 64, null) == -3
+
+
 def test_rope_tables_against_numpy(binding):
     from paper_2502_12665_amd import synth
     inv = synth.inv_freq(128, 500000.0)
