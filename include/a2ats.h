@@ -247,7 +247,7 @@ int a2ats_sparse_attn(const a2ats_dims* dims, const void* q, const float* q_rot,
  *                            topk_idx [B*Hkv*top_k], topk_count [B*Hkv].
  *   a2ats_sparse_attn_shared as a2ats_sparse_attn with the real dims, topk_idx / topk_count per KV
  *                            head as above; workspace as A2ATS_OP_ATTN.
- * Product quantisation only (A2ATS_ERR_UNSUPPORTED for the single codebook).
+ * Both quantiser geometries.
  */
 int a2ats_build_lut_shared(const a2ats_dims* dims, const void* q, int q_dtype, const float* cos_b,
                            const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,

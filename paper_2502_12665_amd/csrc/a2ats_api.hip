@@ -192,7 +192,7 @@ int a2ats_build_lut(const a2ats_dims* d, const void* q, int q_dtype, const float
   if (misaligned16(codebook) || misaligned16(lut)) return A2ATS_ERR_INVALID_ARG;
   const hipError_t e =
       a2ats::single_codebook(*d)
-          ? a2ats::launch_build_lut_single(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
+          ? a2ats::launch_build_lut_single(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale, false,
                                            (hipStream_t)stream)
           : a2ats::launch_build_lut(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
                                     (hipStream_t)stream);
@@ -207,9 +207,12 @@ int a2ats_build_lut_shared(const a2ats_dims* d, const void* q, int q_dtype, cons
   if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
   if (!q || !cos_b || !sin_b || !codebook || !q_rot || !lut || !lut_scale) return A2ATS_ERR_INVALID_ARG;
   if (misaligned16(codebook) || misaligned16(lut)) return A2ATS_ERR_INVALID_ARG;
-  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
-  const hipError_t e = a2ats::launch_build_lut_shared(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut,
-                                                      lut_scale, (hipStream_t)stream);
+  const hipError_t e =
+      a2ats::single_codebook(*d)
+          ? a2ats::launch_build_lut_single(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale, true,
+                                           (hipStream_t)stream)
+          : a2ats::launch_build_lut_shared(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
+                                           (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 

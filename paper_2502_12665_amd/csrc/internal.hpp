@@ -78,7 +78,7 @@ inline bool single_codebook(const a2ats_dims& d) {
 }
 hipError_t launch_build_lut_single(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                                    const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
-                                   float* lut_scale, hipStream_t stream);
+                                   float* lut_scale, bool shared, hipStream_t stream);
 hipError_t launch_score_topk_single(const a2ats_dims& d, const void* codes, const int32_t* lut, int top_k,
                                     int window, int n_sink, const int32_t* seq_lens, int32_t* topk_idx,
                                     int32_t* topk_count, float* topk_score, float* scores_out,

@@ -35,11 +35,13 @@ __device__ __forceinline__ float key_to_float(int32_t k) {
 // ------------------------------------------------------------------------------------------
 constexpr int kLutChunk = 256;   // codewords per workgroup
 
+// `shared`: one table per KV head, from the float32 sum of its heads' rotated queries (selection
+// shared by the query heads of a KV head); the table array is then laid out for Hq = Hkv.
 template <bool QBF16>
 __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
     const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
     const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
-    float* __restrict__ lut_scale, int Hq, int Hkv) {
+    float* __restrict__ lut_scale, int Hq, int Hkv, int shared) {
   constexpr int HALF = kSD / 2;
   __shared__ float s_q[8][kSD];   // q~ of the (up to) 8 query heads of this KV head
   const int chunk = blockIdx.x, bkv = blockIdx.y, b = bkv / Hkv, kv = bkv % Hkv;
@@ -64,10 +66,20 @@ __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
     if (chunk == 0) {
       q_rot[base + t] = o1;
       q_rot[base + t + HALF] = o2;
-      if (t == 0) lut_scale[(size_t)b * Hq + kv * G + g] = 1.f;
+      if (t == 0 && !shared) lut_scale[(size_t)b * Hq + kv * G + g] = 1.f;
     }
   }
   __syncthreads();
+  if (shared) {
+    double sum = 0.0;
+    if (tid < kSD)
+      for (int g = 0; g < G; ++g) sum += (double)s_q[g][tid];
+    __syncthreads();
+    if (tid < kSD) s_q[0][tid] = (float)sum;
+    if (chunk == 0 && tid == 0) lut_scale[(size_t)b * Hkv + kv] = 1.f;
+    __syncthreads();
+  }
+  const int Gt = shared ? 1 : G, Ht = shared ? Hkv : Hq;   // table heads
   const int c = chunk * kLutChunk + tid;
   const float4* cw = (const float4*)(codebook + ((size_t)kv * kCodewords + c) * kSD);
   // A thread reads its codeword's 512-byte row by itself, so the loads of a wave do not coalesce
@@ -83,7 +95,7 @@ __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
     const float4 f = row[t4];
 #pragma unroll
     for (int g = 0; g < 8; ++g) {
-      if (g < G) {
+      if (g < Gt) {
         acc[g] += (double)s_q[g][4 * t4] * (double)f.x + (double)s_q[g][4 * t4 + 1] * (double)f.y +
                   (double)s_q[g][4 * t4 + 2] * (double)f.z + (double)s_q[g][4 * t4 + 3] * (double)f.w;
       }
@@ -91,20 +103,20 @@ __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
   }
 #pragma unroll
   for (int g = 0; g < 8; ++g)
-    if (g < G) lut[((size_t)b * Hq + kv * G + g) * kCodewords + c] = float_to_key((float)acc[g]);
+    if (g < Gt) lut[((size_t)b * Ht + kv * Gt + g) * kCodewords + c] = float_to_key((float)acc[g]);
 }
 
 hipError_t launch_build_lut_single(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                                    const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
-                                   float* lut_scale, hipStream_t stream) {
+                                   float* lut_scale, bool shared, hipStream_t stream) {
   const dim3 grid(kCodewords / kLutChunk, d.batch * d.n_kv_heads), block(kLutChunk);
   if (grid.y == 0) return hipSuccess;
   if (q_dtype == A2ATS_BF16)
     hipLaunchKernelGGL((build_lut_single_kernel<true>), grid, block, 0, stream, q, cos_b, sin_b, codebook,
-                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads);
+                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads, shared ? 1 : 0);
   else
     hipLaunchKernelGGL((build_lut_single_kernel<false>), grid, block, 0, stream, q, cos_b, sin_b, codebook,
-                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads);
+                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads, shared ? 1 : 0);
   return hipGetLastError();
 }
 

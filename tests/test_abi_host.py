@@ -113,7 +113,6 @@ def test_validation_of_the_single_codebook_and_construction_calls(binding):
     assert L.a2ats_decode_prologue(ctypes.byref(sc), one, 1, 0, one, null, 0, one, one, 0, one, one, one, one,
                                    one, null) == -2
     # shared selection
-    assert L.a2ats_build_lut_shared(ctypes.byref(sc), one, 0, one, one, one, one, one, one, null) == -2
     assert L.a2ats_build_lut_shared(ctypes.byref(pq), one, 0, one, one, one, null, one, one, null) == -1
     assert L.a2ats_sparse_attn_shared(ctypes.byref(pq), one, one, one, one, 1, one, one, 64, 16, 0, one, one, null,
                                       one, null, 0, null) == -3

@@ -560,12 +560,16 @@ def _group_shared_step(wl, xd, n_sink=0, want_scores=True):
 
 
 @pytest.mark.parametrize("shape", [(2, 8, 2, 16, 9000, 300, 64), (1, 14, 2, 32, 5000, 64, 32),
-                                   (2, 8, 2, 16, 40000, 512, 128), (1, 3, 3, 16, 700, 700, 16)])
+                                   (2, 8, 2, 16, 40000, 512, 128), (1, 3, 3, 16, 700, 700, 16),
+                                   (2, 8, 2, 1, 9000, 300, 64), (1, 7, 1, 1, 40000, 512, 128)])
 def test_group_shared_selection(oracle, shape):
     """One selection per KV head (sum of the group's scores), against the oracle: rotated queries per
     head, group scores, the shared top-K, and the attention of every head over the shared rows."""
     Bn, Hq, Hkv, M, N, K, w = shape
-    wl = synth.Workload("shared", Bn, Hq, Hkv, 128, M, N, K, w, seed=N + Hq)
+    if M == 1:   # the single codebook of 4096
+        wl = _single("shared_single", Bn, Hq, Hkv, N, K, w, seed=N + Hq)
+    else:
+        wl = synth.Workload("shared", Bn, Hq, Hkv, 128, M, N, K, w, seed=N + Hq)
     x = synth.make_decode_inputs(wl)
     xd = H.to_dev(x)
     n_sink = 4 if N < 6000 else 0
