@@ -68,6 +68,18 @@ __device__ __forceinline__ float load_elem(const uint16_t* p) { return bf16_to_f
 __device__ __forceinline__ void store_elem(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_elem(uint16_t* p, float v) { *p = f32_to_bf16(v); }
 
+// Sum over the 16 lanes of a DPP row, result in every lane: two swaps inside quads, then the mirror
+// images within 8 and within 16 lanes.  (A __shfl_xor is a round trip through the LDS crossbar; four
+// of them in a chain per attended row were the longest dependency of the kernel.)  The 16 lanes must
+// be all active or all inactive.
+__device__ __forceinline__ float row16_sum(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false));   // row_half_mirror
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false));   // row_mirror
+  return v;
+}
+
 // Merge two online-softmax states.
 template <int VEC>
 __device__ __forceinline__ void merge_state(float& m, float& l, float (&acc)[VEC], float m2, float l2,
@@ -138,8 +150,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
 
   // One row's contribution, given this lane's part of q . k
   auto absorb = [&](float dot, const uint4& vraw) {
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
+    dot = row16_sum(dot);
+    if (LPR == 32) dot += __shfl_xor(dot, 16);   // a float32 row spans two DPP rows
     float vr[VEC];
     RowVec<T>::widen(vraw, vr);
     const float logit = dot * scale;
