@@ -126,13 +126,11 @@ __device__ __forceinline__ void build_lut_body(
 
   // --- per-head power-of-two scale: M * max|entry| * 2^e < 2^30.  Non-negative floats order like
   // their bit patterns, so the block maximum is an integer atomic max in LDS (one per wave and head
-  // after a butterfly over the wave).
+  // after a reduction over the wave).
 #pragma unroll
   for (int r = 0; r < kHeadsPerGroup; ++r) {
-    float v = mx[r];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
-    if ((tid & 63) == 0) atomicMax(&s_maxbits[r], __float_as_uint(v));
+    const uint32_t v = wave_max_to_last_lane(__float_as_uint(mx[r]));
+    if ((tid & 63) == 63) atomicMax(&s_maxbits[r], v);
   }
   __syncthreads();
   if (tid < kHeadsPerGroup) {

@@ -60,6 +60,32 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
   return v;
 }
 
+// Maximum over the 64 lanes of a wave, valid in lane 63 (same moves as wave_inclusive_scan).
+__device__ __forceinline__ uint32_t wave_max_to_last_lane(uint32_t v) {
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x111, 0xf, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x112, 0xf, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xf, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xf, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xa, 0xf, false));
+  v = max(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xc, 0xf, false));
+  return v;
+}
+
+// Sum / bitwise OR over aligned groups of 8 lanes, result in every lane of the group (swaps inside
+// quads, then the mirror image within 8 lanes).
+__device__ __forceinline__ int32_t group8_sum(int32_t v) {
+  v += __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false);    // quad_perm [1,0,3,2]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false);    // quad_perm [2,3,0,1]
+  v += __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false);   // row_half_mirror
+  return v;
+}
+__device__ __forceinline__ int32_t group8_or(int32_t v) {
+  v |= __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, false);
+  v |= __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, false);
+  v |= __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, false);
+  return v;
+}
+
 // Exclusive prefix sum of `v` over the block (NT threads, NT a multiple of 64).  `s_wave` is an
 // LDS array of NT/64 words owned by this call site.  Returns the exclusive prefix and the
 // block total.  One barrier; callers alternate between two `s_wave` arrays when they scan

@@ -284,11 +284,8 @@ template <int NH>
 __device__ __forceinline__ void combine_thresholds(int32_t v, int n_valid, int P0, int32_t (&T)[NH]) {
   int32_t all_rows = v == INT32_MIN ? 1 : 0;
   int32_t sum = all_rows ? 0 : v;   // thresholds are >= 0 and below 2^16
-#pragma unroll
-  for (int off = 1; off < 8; off <<= 1) {
-    sum += __shfl_xor(sum, off);
-    all_rows |= __shfl_xor(all_rows, off);
-  }
+  sum = group8_sum(sum);
+  all_rows = group8_or(all_rows);
 #pragma unroll
   for (int i = 0; i < NH; ++i) {
     const int32_t s_i = __builtin_amdgcn_readlane(sum, 8 * i), a_i = __builtin_amdgcn_readlane(all_rows, 8 * i);
