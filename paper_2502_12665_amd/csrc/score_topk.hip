@@ -552,26 +552,18 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
       const int ii = (i + lane) & 31;   // rotate the walk so the lanes of a read hit different banks
       sum += (hrow[32 * lane + ii] >> fsh) & 0xffffu;
     }
-    uint32_t inc = sum;   // inclusive suffix sum over lanes (higher lanes hold higher bins)
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t o = __shfl_down(inc, off);
-      if (lane + off < 64) inc += o;
-    }
+    // inclusive suffix sum over lanes (higher lanes hold higher bins) = total - exclusive prefix
+    const uint32_t pre = wave_inclusive_scan(sum);
+    const uint32_t inc = (uint32_t)__builtin_amdgcn_readlane((int)pre, 63) - pre + sum;
     const uint32_t k = (uint32_t)r_p, above_lane = inc - sum;
     const uint64_t owner = __ballot(above_lane < k && k <= inc);   // the lane whose 32 bins hold the rank
     if (owner != 0 && hg < G) {
       // Second level, by the whole wave: lane i < 32 takes bin 31 - i of the owner's range (so
       // bins descend with the lane index) and a prefix sum finds the first lane that reaches k.
       const int src = __ffsll((unsigned long long)owner) - 1;
-      const uint32_t above = __shfl(above_lane, src);
+      const uint32_t above = (uint32_t)__builtin_amdgcn_readlane((int)above_lane, src);
       const uint32_t c = lane < 32 ? (hrow[32 * src + 31 - lane] >> fsh) & 0xffffu : 0u;
-      uint32_t incl = c;
-#pragma unroll
-      for (int off = 1; off < 32; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-      }
+      const uint32_t incl = wave_inclusive_scan(c);   // lanes >= 32 hold zeros
       const uint64_t reach = __ballot(lane < 32 && above + incl >= k);
       const int bin = 32 * src + 31 - (__ffsll((unsigned long long)reach) - 1);
       // Lower edge of the bin holding the r_p-th largest sample (at least r_p samples reach it),
