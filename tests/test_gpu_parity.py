@@ -443,6 +443,26 @@ def test_single_codebook_encode(oracle, mode):
         H.log(f"  near-tie exclusions: {n_near}")
 
 
+def test_single_codebook_encode_many_keys(oracle):
+    """More keys per sequence than the transform buffer holds at once (16384): the full-matrix mode then
+    works part by part; every part must land at its own positions."""
+    wl = _single("single_enc_parts", 1, 1, 1, 40000, 16, 16, seed=5)
+    hm = synth.make_query_second_moment(wl)
+    cb = synth.make_codebook(wl)
+    n = 40000
+    keys = synth.make_encode_keys(wl, n, stress=True)
+    dims = H.dims_of(wl, n + 7)
+    ws = torch.empty(B.workspace_bytes(dims, B.OP_ENCODE), dtype=torch.uint8, device="cuda")
+    codes = torch.full((1, 1, n + 7, 1), 0x7EEE, dtype=torch.int16, device="cuda")
+    B.encode_keys(dims, keys.cuda(), n, 3, cb.cuda(), hm["h_block"].cuda(), B.W_BLOCK, codes, ws)
+    torch.cuda.synchronize()
+    got = codes.cpu().numpy().view(np.uint16)
+    want, b1, b2 = oracle.encode_cholesky(keys, cb, hm["h_block"], want_margins=True)
+    n_near = H.compare_codes(got[:, :, 3:3 + n], want, b1, b2)
+    assert (got[:, :, :3] == 0x7EEE).all() and (got[:, :, 3 + n:] == 0x7EEE).all()
+    H.log(f"{wl.name}: near-tie exclusions {n_near}")
+
+
 def test_single_codebook_long_context(oracle):
     """More tokens than a workgroup keeps in registers at once (131072): the selection kernel then
     walks the codes span by span, in both of its passes."""
