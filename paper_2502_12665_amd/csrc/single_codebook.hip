@@ -7,11 +7,10 @@
 //   build_lut_single_kernel    q~ = q R_b and the 4096 scores q~ . c per head, float64 inner
 //                              products rounded once to float32 and stored as order-preserving
 //                              32-bit keys (no fixed-point scale is needed: a score is one entry)
-//   select_single_kernel       exact top-K per head: MSB-first radix select over the keys by
-//                              re-streaming the codes, then one ordered pass that emits the winners
-//                              in ascending position, equal scores going to the lower position
-//   encode_single_*            query-aware assignment argmin_c (k - c) H (k - c)^T with the full
-//                              D x D matrix H through its Cholesky factor (section 4.2)
+//   select_single_kernel       exact top-K per head: candidates counted per codeword, a weighted
+//                              radix select over the 4096 codewords, then one ordered pass that emits
+//                              the winners in ascending position, equal scores to the lower position
+// (the key encoder of this geometry lives in encode_single.hip)
 #include "common.hpp"
 #include "internal.hpp"
 
