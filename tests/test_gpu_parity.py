@@ -749,3 +749,44 @@ def test_kmeanspp_seeding(oracle, mode):
     pooled = keys.permute(1, 0, 2, 3).reshape(wl.n_kv_heads, wl.batch * n, 128)
     for kv in range(wl.n_kv_heads):
         assert torch.equal(out[kv, 0].cpu(), pooled[kv][torch.as_tensor(want[kv])])
+
+
+def test_single_codebook_step_in_a_hip_graph():
+    """The decode step of the single-codebook geometry (append of one key on a prepared workspace, tables,
+    selection, attention) and a prefill-sized encode, captured in HIP graphs: every replay must give the
+    eager result, with eager work and synchronisations between the replays."""
+    wl = _single("single_graph", 2, 8, 2, 40000, 700, 128, seed=6)
+    xd = H.to_dev(synth.make_decode_inputs(wl))
+    hm = synth.make_query_second_moment(wl)
+    w = hm["h_block"].cuda()
+    dims = H.dims_of(wl, 40000)
+    st = B.DecodeState(dims, wl.top_k, wl.window, 0, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+    enc_ws = torch.empty(B.workspace_bytes(dims, B.OP_ENCODE), dtype=torch.uint8, device="cuda")
+    B.encode_prepare(dims, xd["codebook"], w, B.W_BLOCK, enc_ws)
+    new_key = xd["k"][:, :, -1:, :].float().contiguous()
+    many = synth.make_encode_keys(wl, 2000, stress=True).cuda()
+    many_codes = torch.zeros(wl.batch, wl.n_kv_heads, 40000, 1, dtype=torch.int16, device="cuda")
+
+    def step():
+        B.encode_keys(dims, new_key, 1, wl.ctx_len - 1, xd["codebook"], w, B.W_BLOCK | B.W_PREPARED, xd["codes"], enc_ws)
+        st.step(xd["q"], xd["codes"], xd["k"], xd["v"], xd["codebook"])
+        B.encode_keys(dims, many, 2000, 5, xd["codebook"], w, B.W_BLOCK | B.W_PREPARED, many_codes, enc_ws)
+    step()
+    torch.cuda.synchronize()
+    ref = (st.topk_idx.clone(), st.out.clone(), xd["codes"].clone(), many_codes.clone())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for it in range(3):
+        st.topk_idx.fill_(-3)
+        st.out.zero_()
+        many_codes.zero_()
+        xd["codes"][:, :, -1].fill_(0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(st.topk_idx, ref[0]), f"replay {it}: top-K differs"
+        assert torch.equal(st.out.view(torch.int16), ref[1].view(torch.int16)), f"replay {it}: output differs"
+        assert torch.equal(xd["codes"], ref[2]) and torch.equal(many_codes, ref[3]), f"replay {it}: codes differ"
+        junk = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
+        assert junk == junk
