@@ -465,11 +465,16 @@ def test_single_codebook_encode_many_keys(oracle):
 
 def test_single_codebook_long_context(oracle):
     """More tokens than a workgroup keeps in registers at once (131072): the selection kernel then
-    walks the codes span by span, in both of its passes."""
+    walks the codes span by span, in both of its passes; and the largest context and K the library
+    accepts (2^20 tokens, K = 4096)."""
     wl = _single("single_long", 1, 4, 2, 300000, 2048, 64, n_sink=4, seed=8)
     H.log(wl.name)
     _run_and_check(oracle, wl)
     _run_and_check(oracle, wl, ctx_stride=300003)
+    wl = _single("single_max", 1, 2, 1, 1 << 20, 4096, 256, n_sink=4, seed=10)
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl)
+    H.log(f"  {res}")
 
 
 def test_single_codebook_full_size(oracle):
