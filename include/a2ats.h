@@ -233,6 +233,24 @@ int a2ats_sparse_attn(const a2ats_dims* dims, const void* q, const float* q_rot,
                       const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * a2ats_sparse_attn over a PAGED key/value cache: k_pool / v_pool are pools of pages,
+ *   [dev, kv_dtype n_pages * Hkv * page_size * D], page p holding page_size consecutive tokens of one
+ *   sequence for all KV heads ([Hkv][page_size][D]), and
+ *   page_table [dev, int32 B * ceil(ctx_stride / page_size)] maps (sequence b, token j) to page
+ *   page_table[b][j / page_size] (row j % page_size of it).  page_size: a power of two >= 16.
+ * Every page number reachable through seq_lens / ctx_len must be a valid page of the pools (not
+ * checked on the device).  The code matrix of a2ats_score_topk stays contiguous per sequence (it is
+ * 3-6 % of the cache bytes).  Everything else as a2ats_sparse_attn; results are identical to the
+ * contiguous layout.
+ */
+int a2ats_sparse_attn_paged(const a2ats_dims* dims, const void* q, const float* q_rot, const void* k_pool,
+                            const void* v_pool, int kv_dtype, const int32_t* page_table,
+                            int32_t page_size, const int32_t* topk_idx, const int32_t* topk_count,
+                            int32_t top_k, int32_t window, int32_t n_sink, const float* cos_win,
+                            const float* sin_win, const int32_t* seq_lens, void* out, void* ws,
+                            size_t ws_bytes, void* stream);
+
+/*
  * Selection shared by the query heads of a KV head (grouped-query attention; the paper selects
  * "for each attention head" and does not say which kind, so per query head is the reading of the
  * calls above and this is the alternative): the group's score of a token is the SUM over the G

@@ -23,7 +23,7 @@ EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_wor
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel",
            "a2ats_decode_prologue", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
-           "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed"]
+           "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged"]
 
 
 class A2atsError(RuntimeError):
@@ -76,6 +76,9 @@ def lib() -> ctypes.CDLL:
                                         vp, vp, vp, sz, vp]
         L.a2ats_sparse_attn_shared.restype = ctypes.c_int
         L.a2ats_sparse_attn_shared.argtypes = L.a2ats_sparse_attn.argtypes
+        L.a2ats_sparse_attn_paged.restype = ctypes.c_int
+        L.a2ats_sparse_attn_paged.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int, vp, i32, vp, vp, i32, i32, i32, vp, vp,
+                                              vp, vp, vp, sz, vp]
         L.a2ats_build_lut_shared.restype = ctypes.c_int
         L.a2ats_build_lut_shared.argtypes = L.a2ats_build_lut.argtypes
         L.a2ats_kmeanspp_seed.restype = ctypes.c_int
@@ -254,6 +257,16 @@ def codebook_update(dims: Dims, keys, n_new: int, pos0: int, codes, codebook, co
                                      _ptr(codebook_out), _ptr(counts), _ptr(ws), ws.numel() * ws.element_size(),
                                      _stream())
     _check(rc, "a2ats_codebook_update")
+
+
+def sparse_attn_paged(dims: Dims, q, q_rot, k_pool, v_pool, page_table, page_size: int, topk_idx, topk_count,
+                      top_k: int, window: int, n_sink: int, cos_win, sin_win, seq_lens, out, ws: torch.Tensor):
+    """sparse_attn over pools of pages [page][Hkv][page_size][D] addressed through page_table [B, pages]."""
+    rc = lib().a2ats_sparse_attn_paged(ctypes.byref(dims), _ptr(q), _ptr(q_rot), _ptr(k_pool), _ptr(v_pool),
+                                       _dtype_code(k_pool), _ptr(page_table), page_size, _ptr(topk_idx),
+                                       _ptr(topk_count), top_k, window, n_sink, _ptr(cos_win), _ptr(sin_win),
+                                       _ptr(seq_lens), _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_sparse_attn_paged")
 
 
 def score_topk_stats(dims: Dims, top_k: int, window: int, n_sink: int, ws, cand_counts):

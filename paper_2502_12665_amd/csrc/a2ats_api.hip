@@ -270,8 +270,14 @@ static int sparse_attn_impl(const a2ats_dims* d, const void* q, const float* q_r
                             const void* v_cache, int kv_dtype, const int32_t* topk_idx,
                             const int32_t* topk_count, int32_t top_k, int32_t window, int32_t n_sink,
                             const float* cos_win, const float* sin_win, const int32_t* seq_lens, void* out,
-                            void* ws, size_t ws_bytes, bool shared, void* stream) {
+                            void* ws, size_t ws_bytes, bool shared, const int32_t* page_table, int page_size,
+                            void* stream) {
   int rc = check_dims(d);
+  int page_shift = 0;
+  if (page_table) {   // a power of two of at least 16 tokens
+    if (page_size < 16 || (page_size & (page_size - 1))) return A2ATS_ERR_INVALID_ARG;
+    while ((1 << page_shift) < page_size) ++page_shift;
+  }
   if (rc != A2ATS_OK) return rc;
   if (kv_dtype != A2ATS_F32 && kv_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
   if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
@@ -284,7 +290,8 @@ static int sparse_attn_impl(const a2ats_dims* d, const void* q, const float* q_r
   if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
   const hipError_t e = a2ats::launch_sparse_attn(*d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx,
                                                  topk_count, top_k, window, n_sink, cos_win, sin_win,
-                                                 seq_lens, out, ws, shared, (hipStream_t)stream);
+                                                 seq_lens, out, ws, shared, page_table, page_shift,
+                                                 (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
@@ -294,7 +301,17 @@ int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, co
                       const float* sin_win, const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes,
                       void* stream) {
   return sparse_attn_impl(d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx, topk_count, top_k, window, n_sink,
-                          cos_win, sin_win, seq_lens, out, ws, ws_bytes, false, stream);
+                          cos_win, sin_win, seq_lens, out, ws, ws_bytes, false, nullptr, 0, stream);
+}
+
+int a2ats_sparse_attn_paged(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_pool,
+                            const void* v_pool, int kv_dtype, const int32_t* page_table, int32_t page_size,
+                            const int32_t* topk_idx, const int32_t* topk_count, int32_t top_k, int32_t window,
+                            int32_t n_sink, const float* cos_win, const float* sin_win, const int32_t* seq_lens,
+                            void* out, void* ws, size_t ws_bytes, void* stream) {
+  if (!page_table) return A2ATS_ERR_INVALID_ARG;
+  return sparse_attn_impl(d, q, q_rot, k_pool, v_pool, kv_dtype, topk_idx, topk_count, top_k, window, n_sink,
+                          cos_win, sin_win, seq_lens, out, ws, ws_bytes, false, page_table, page_size, stream);
 }
 
 int a2ats_sparse_attn_shared(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
@@ -303,7 +320,7 @@ int a2ats_sparse_attn_shared(const a2ats_dims* d, const void* q, const float* q_
                              const float* cos_win, const float* sin_win, const int32_t* seq_lens, void* out,
                              void* ws, size_t ws_bytes, void* stream) {
   return sparse_attn_impl(d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx, topk_count, top_k, window, n_sink,
-                          cos_win, sin_win, seq_lens, out, ws, ws_bytes, true, stream);
+                          cos_win, sin_win, seq_lens, out, ws, ws_bytes, true, nullptr, 0, stream);
 }
 
 int a2ats_score_topk_stats(const a2ats_dims* d, int32_t top_k, int32_t window, int32_t n_sink, const void* ws,

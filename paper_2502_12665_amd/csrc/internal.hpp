@@ -64,7 +64,8 @@ hipError_t launch_sparse_attn(const a2ats_dims& d, const void* q, const float* q
                               const void* v_cache, int kv_dtype, const int32_t* topk_idx,
                               const int32_t* topk_count, int top_k, int window, int n_sink,
                               const float* cos_win, const float* sin_win, const int32_t* seq_lens,
-                              void* out, void* ws, bool shared, hipStream_t stream);
+                              void* out, void* ws, bool shared, const int32_t* page_table, int page_shift,
+                              hipStream_t stream);
 hipError_t launch_build_lut_shared(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                                    const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
                                    float* lut_scale, hipStream_t stream);

@@ -104,13 +104,17 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
     const int32_t* __restrict__ topk_count, const float* __restrict__ cos_win,
     const float* __restrict__ sin_win, const int32_t* __restrict__ seq_lens,
     float* __restrict__ partial, int Hq, int Hkv, int ctx_len, int64_t ctx_stride, int top_k,
-    int window, int n_sink, int n_far, int n_win) {
+    int window, int n_sink, int n_far, int n_win, const int32_t* __restrict__ page_table, int page_shift,
+    int pages_per_seq) {
+  // page_table != NULL: k_cache / v_cache are pools of pages [page][Hkv][2^page_shift][D] and token j of
+  // sequence b lives in page page_table[b][j >> page_shift]; else row j of [B][Hkv][ctx_stride][D].
   constexpr int LPR = RowVec<T>::LPR, VEC = RowVec<T>::VEC;
   constexpr int SLOTS = 64 / LPR;            // rows a wave reads at once
   constexpr int NWV = kAttnThreads / 64;
   constexpr int RB = NWV * SLOTS;            // rows per block step
   constexpr int HALF = kD / 2;
-  __shared__ int32_t s_pos[kAttnTile];
+  __shared__ int32_t s_pos[kAttnTile];     // token positions of the staged rows
+  __shared__ uint32_t s_row[kAttnTile];    // their row numbers in the cache (or pool)
   __shared__ float s_m[NWV], s_l[NWV], s_acc[NWV][kD];
 
   const int G = Hq / Hkv;
@@ -139,8 +143,10 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
 
   const int d0 = sub * VEC;
   const float scale = 0.08838834764831845f;   // 1/sqrt(128)
-  const T* kb = k_cache + ((size_t)b * Hkv + kv) * ctx_stride * kD + d0;
-  const T* vb = v_cache + ((size_t)b * Hkv + kv) * ctx_stride * kD + d0;
+  const size_t seq_base = page_table ? 0 : ((size_t)b * Hkv + kv) * ctx_stride * kD;
+  const T* kb = k_cache + seq_base + d0;
+  const T* vb = v_cache + seq_base + d0;
+  const int32_t* pages = page_table ? page_table + (size_t)b * pages_per_seq : nullptr;
   const int32_t* idx = topk_idx + (size_t)ih * top_k;
   const size_t qb = (size_t)bh * kD;
 
@@ -171,7 +177,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
       int j;
       if (win_part) j = sr.win_start + t;
       else j = t < sr.sink_end ? t : idx[t - sr.sink_end];
-      s_pos[i] = min(max(j, 0), sr.n - 1);   // a bad caller index must not leave the cache
+      j = min(max(j, 0), sr.n - 1);   // a bad caller index must not leave the cache
+      s_pos[i] = j;
+      s_row[i] = pages ? (((uint32_t)pages[j >> page_shift] * (uint32_t)Hkv + (uint32_t)kv) << page_shift) +
+                             (uint32_t)(j & ((1 << page_shift) - 1))
+                       : (uint32_t)j;
     }
     __syncthreads();
 
@@ -188,9 +198,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
       auto load_set = [&](int i0, uint4 (&kr)[U], uint4 (&vr)[U]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          const int j = s_pos[min(i0 + u * RB, tn - 1)];
-          kr[u] = RowVec<T>::load(kb + (size_t)j * kD);
-          vr[u] = RowVec<T>::load(vb + (size_t)j * kD);
+          const uint32_t row = s_row[min(i0 + u * RB, tn - 1)];
+          kr[u] = RowVec<T>::load(kb + (size_t)row * kD);
+          vr[u] = RowVec<T>::load(vb + (size_t)row * kD);
         }
       };
       auto use_set = [&](int i0, const uint4 (&kr)[U], const uint4 (&vr)[U]) {
@@ -232,8 +242,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const int j = s_pos[min(i0 + u * RB, tn - 1)];
-          kr[u] = RowVec<T>::load(kb + (size_t)j * kD);
-          vr[u] = RowVec<T>::load(vb + (size_t)j * kD);
+          const uint32_t row = s_row[min(i0 + u * RB, tn - 1)];
+          kr[u] = RowVec<T>::load(kb + (size_t)row * kD);
+          vr[u] = RowVec<T>::load(vb + (size_t)row * kD);
           const int delta = min(max(sr.n - 1 - j, 0), window - 1);
           const float* cp = cos_win + (size_t)delta * HALF + (d0 & (HALF - 1));
           const float* sp = sin_win + (size_t)delta * HALF + (d0 & (HALF - 1));
@@ -340,20 +351,24 @@ static hipError_t launch_attn_t(const a2ats_dims& d, const AttnPlan& plan, const
                                 const void* k_cache, const void* v_cache, const int32_t* topk_idx,
                                 const int32_t* topk_count, int top_k, int window, int n_sink,
                                 const float* cos_win, const float* sin_win, const int32_t* seq_lens,
-                                void* out, void* ws, bool shared, hipStream_t stream) {
+                                void* out, void* ws, bool shared, const int32_t* page_table, int page_shift,
+                                hipStream_t stream) {
   const int heads = d.batch * d.n_q_heads;
+  const int pages_per_seq = page_table ? (int)((d.ctx_stride + (1 << page_shift) - 1) >> page_shift) : 0;
   if (heads == 0) return hipSuccess;
   const int parts = plan.n_far + plan.n_win;
   if (shared)
     hipLaunchKernelGGL((attn_partial_kernel<T, true>), dim3(parts * heads), dim3(kAttnThreads), 0, stream,
                        (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
                        cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
-                       d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win);
+                       d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win, page_table, page_shift,
+                       pages_per_seq);
   else
     hipLaunchKernelGGL((attn_partial_kernel<T, false>), dim3(parts, heads), dim3(kAttnThreads), 0, stream,
                        (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
                        cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
-                       d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win);
+                       d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win, page_table, page_shift,
+                       pages_per_seq);
   hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
   hipLaunchKernelGGL((attn_combine_kernel<T>), dim3(heads), dim3(kCombineGroups * kD), 0, stream,
@@ -365,13 +380,15 @@ hipError_t launch_sparse_attn(const a2ats_dims& d, const void* q, const float* q
                               const void* v_cache, int kv_dtype, const int32_t* topk_idx,
                               const int32_t* topk_count, int top_k, int window, int n_sink,
                               const float* cos_win, const float* sin_win, const int32_t* seq_lens,
-                              void* out, void* ws, bool shared, hipStream_t stream) {
+                              void* out, void* ws, bool shared, const int32_t* page_table, int page_shift,
+                              hipStream_t stream) {
   const AttnPlan plan = make_attn_plan(d, top_k, window, n_sink);
   if (kv_dtype == A2ATS_BF16)
     return launch_attn_t<uint16_t>(d, plan, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k,
-                                   window, n_sink, cos_win, sin_win, seq_lens, out, ws, shared, stream);
+                                   window, n_sink, cos_win, sin_win, seq_lens, out, ws, shared, page_table, page_shift,
+                                   stream);
   return launch_attn_t<float>(d, plan, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k, window,
-                              n_sink, cos_win, sin_win, seq_lens, out, ws, shared, stream);
+                              n_sink, cos_win, sin_win, seq_lens, out, ws, shared, page_table, page_shift, stream);
 }
 
 }  // namespace a2ats

@@ -116,6 +116,11 @@ def test_validation_of_the_single_codebook_and_construction_calls(binding):
     assert L.a2ats_build_lut_shared(ctypes.byref(pq), one, 0, one, one, one, null, one, one, null) == -1
     assert L.a2ats_sparse_attn_shared(ctypes.byref(pq), one, one, one, one, 1, one, one, 64, 16, 0, one, one, null,
                                       one, null, 0, null) == -3
+    # paged key/value cache: a page table and a power-of-two page size of at least 16 tokens
+    def paged(table, page_size):
+        return L.a2ats_sparse_attn_paged(ctypes.byref(pq), one, one, one, one, 1, table, page_size, one, one, 64, 16, 0,
+                                         one, one, null, one, one, 1 << 40, null)
+    assert paged(null, 64) == -1 and paged(one, 48) == -1 and paged(one, 8) == -1
     # construction
     assert L.a2ats_second_moment(ctypes.byref(pq), one, -1, one, one, 1 << 40, null) == -1
     assert L.a2ats_second_moment(ctypes.byref(pq), one, 10, one, null, 0, null) == -3

@@ -795,3 +795,37 @@ def test_single_codebook_step_in_a_hip_graph():
         assert torch.equal(xd["codes"], ref[2]) and torch.equal(many_codes, ref[3]), f"replay {it}: codes differ"
         junk = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
         assert junk == junk
+
+
+@pytest.mark.parametrize("page_size", [16, 256])
+def test_paged_kv_cache(oracle, page_size):
+    """K and V in pools of pages reached through a page table (pages of a sequence scattered over the pool,
+    pools larger than needed, ragged lengths): the attention output must equal the contiguous layout's bit
+    for bit, and so the oracle's within tolerance."""
+    wl = synth.Workload("paged", 3, 8, 2, 128, 16, 5000, 200, 100, n_sink=4, seed=14)
+    stride = 5120 if page_size == 256 else 5008
+    x = synth.make_decode_inputs(wl, ctx_stride=stride)
+    xd = H.to_dev(x)
+    lens = [5000, 1234, 40]
+    st = H.gpu_decode(wl, xd, seq_lens=lens, want_scores=False, ctx_stride=stride)
+    ref = st.out.clone()
+    n_pages_seq = stride // page_size
+    n_phys = wl.batch * n_pages_seq + 7
+    g = torch.Generator().manual_seed(page_size)
+    perm = torch.randperm(n_phys, generator=g)[: wl.batch * n_pages_seq].reshape(wl.batch, n_pages_seq)
+    pools = []
+    for name in ("k", "v"):
+        pool = torch.full((n_phys, wl.n_kv_heads, page_size, 128), float("nan"), dtype=x[name].dtype)
+        pages = x[name].reshape(wl.batch, wl.n_kv_heads, n_pages_seq, page_size, 128).permute(0, 2, 1, 3, 4)
+        pool[perm.reshape(-1)] = pages.reshape(-1, wl.n_kv_heads, page_size, 128)
+        pools.append(pool.cuda())
+    table = perm.to(torch.int32).cuda()
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    st.out.zero_()
+    B.sparse_attn_paged(st.dims, xd["q"], st.q_rot, pools[0], pools[1], table, page_size, st.topk_idx, st.topk_count,
+                        wl.top_k, wl.window, 4, st.cos_win, st.sin_win, sl, st.out, st.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(st.out.view(torch.int16), ref.view(torch.int16))
+    want = oracle.sparse_attn(x["q"], x["k"], x["v"], st.topk_idx.cpu().numpy(), st.topk_count.cpu().numpy(),
+                              wl.ctx_len, wl.window, 4, x["inv_freq"], float(wl.wrope_b), np.asarray(lens, dtype=np.int32))
+    assert np.abs(st.out.float().cpu().numpy().astype(np.float64) - want).max() <= 2e-2
