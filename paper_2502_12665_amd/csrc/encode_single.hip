@@ -564,36 +564,43 @@ __global__ __launch_bounds__(1024) void encode_single_sweep_kernel(
     const double* __restrict__ czT, double* __restrict__ part, int Hkv, int n_new) {
   constexpr int PER = kCW / kSlices;   // codewords per slice
   static_assert(PER == 256, "a thread owns one codeword and a quarter of the dimensions");
-  __shared__ double s_k[kD], s_z[kD], s_p[4][PER];
+  __shared__ double s_k[kD], s_z[kD], s_p[4][PER], s_zp[8][kD];
   __shared__ int s_i[PER];
   const int tid = threadIdx.x, slice = blockIdx.y, key = blockIdx.x;
   const int bkv = key / n_new, kv = bkv % Hkv;
-  if (tid < kD) s_k[tid] = (double)keys[(size_t)key * kD + tid];
-  __syncthreads();
-  if (tid < kD) {
-    double z;
-    if (mode == A2ATS_W_BLOCK) {   // z_t = sum_{r >= t} k_r L[r][t]; the loads do not depend on each other
-      const double* L = Lmat + (size_t)kv * kD * kD + tid;
-      double z0 = 0.0, z1 = 0.0;
-#pragma unroll 16
-      for (int r = 0; r < kD; r += 2) {
-        z0 += s_k[r] * L[(size_t)r * kD];
-        z1 += s_k[r + 1] * L[(size_t)(r + 1) * kD];
-      }
-      z = z0 + z1;   // (entries above the diagonal are zero)
-    } else {
-      z = s_k[tid] * sd[(size_t)kv * kD + tid];
-    }
-    s_z[tid] = z;
-  }
-  __syncthreads();
-  // thread = (codeword, quarter of the dimensions): 32 independent loads each, 16 in flight
+  // thread = (codeword, quarter of the dimensions).  Its 32 transformed-codeword entries do not
+  // depend on the key, so they are requested first and arrive while z is being computed.
   const int cl = tid & (PER - 1), tq = tid >> 8, c = slice * PER + cl;
   const double* cz = czT + ((size_t)kv * kD + 32 * tq) * kCW + c;
+  double cv[32];
+#pragma unroll
+  for (int t = 0; t < 32; ++t) cv[t] = cz[(size_t)t * kCW];
+  if (tid < kD) s_k[tid] = (double)keys[(size_t)key * kD + tid];
+  __syncthreads();
+  if (mode == A2ATS_W_BLOCK) {
+    // z_t = sum_{r >= t} k_r L[r][t] (entries above the diagonal are stored zeros): eight threads
+    // per dimension take 16 rows each, all loads independent
+    const int t = tid & (kD - 1), pt = tid >> 7;
+    const double* L = Lmat + ((size_t)kv * kD + 16 * pt) * kD + t;
+    double z0 = 0.0, z1 = 0.0;
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      z0 += s_k[16 * pt + r] * L[(size_t)r * kD];
+      z1 += s_k[16 * pt + r + 1] * L[(size_t)(r + 1) * kD];
+    }
+    s_zp[pt][t] = z0 + z1;
+    __syncthreads();
+    if (tid < kD)
+      s_z[tid] = ((s_zp[0][tid] + s_zp[1][tid]) + (s_zp[2][tid] + s_zp[3][tid])) +
+                 ((s_zp[4][tid] + s_zp[5][tid]) + (s_zp[6][tid] + s_zp[7][tid]));
+  } else if (tid < kD) {
+    s_z[tid] = s_k[tid] * sd[(size_t)kv * kD + tid];
+  }
+  __syncthreads();
   double d0 = 0.0, d1 = 0.0;
-#pragma unroll 16
+#pragma unroll
   for (int t = 0; t < 32; t += 2) {
-    const double e0 = s_z[32 * tq + t] - cz[(size_t)t * kCW], e1 = s_z[32 * tq + t + 1] - cz[(size_t)(t + 1) * kCW];
+    const double e0 = s_z[32 * tq + t] - cv[t], e1 = s_z[32 * tq + t + 1] - cv[t + 1];
     d0 += e0 * e0;
     d1 += e1 * e1;
   }

@@ -32,6 +32,19 @@ __device__ __forceinline__ float key_to_float(int32_t k) {
 // ------------------------------------------------------------------------------------------
 // Tables
 // ------------------------------------------------------------------------------------------
+// float64 sum over aligned groups of 8 lanes, the same value in every lane of the group.
+template <int CTRL>
+__device__ __forceinline__ double add_dpp_f64(double x) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(x), CTRL, 0xf, 0xf, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(x), CTRL, 0xf, 0xf, false);
+  return x + __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double group8_sum_f64(double v) {
+  v = add_dpp_f64<0xB1>(v);      // quad_perm [1,0,3,2]
+  v = add_dpp_f64<0x4E>(v);      // quad_perm [2,3,0,1]
+  return add_dpp_f64<0x141>(v);  // row_half_mirror
+}
+
 constexpr int kLutChunk = 256;   // codewords per workgroup
 
 // `shared`: one table per KV head, from the float32 sum of its heads' rotated queries (selection
@@ -42,7 +55,8 @@ __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
     const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
     float* __restrict__ lut_scale, int Hq, int Hkv, int shared) {
   constexpr int HALF = kSD / 2;
-  __shared__ float s_q[8][kSD];   // q~ of the (up to) 8 query heads of this KV head
+  __shared__ __align__(16) float s_q[8][kSD];   // q~ of the (up to) 8 query heads of this KV head
+  __shared__ int32_t s_out[8][kLutChunk];       // the chunk's table entries, written out in one coalesced pass
   const int chunk = blockIdx.x, bkv = blockIdx.y, b = bkv / Hkv, kv = bkv % Hkv;
   const int G = Hq / Hkv, tid = threadIdx.x;
   for (int i = tid; i < G * HALF; i += kLutChunk) {
@@ -79,30 +93,58 @@ __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
     __syncthreads();
   }
   const int Gt = shared ? 1 : G, Ht = shared ? Hkv : Hq;   // table heads
-  const int c = chunk * kLutChunk + tid;
-  const float4* cw = (const float4*)(codebook + ((size_t)kv * kCodewords + c) * kSD);
-  // A thread reads its codeword's 512-byte row by itself, so the loads of a wave do not coalesce
-  // and each takes long: all 32 are requested before the first is used.
-  float4 row[kSD / 4];
+  // Eight lanes share a codeword: lane part p holds dimensions {32 i + 4 p .. + 3}, i < 4, so that one
+  // load instruction of a wave reads eight whole 128-byte lines (a lane reading its own 512-byte row
+  // touches 64 lines per instruction and the rows of the waves of a CU evict each other from the
+  // vector cache).  A lane row handles 8 consecutive codewords, one per pass; the query (as float64,
+  // four heads at a time) stays in registers across the passes.
+  const int lane = tid & 63, wave = tid >> 6, p = lane & 7, r = lane >> 3;
+  const int cl0 = wave * 64 + r * 8;   // first of this lane row's codewords, within the chunk
+  const float* cw0 = codebook + ((size_t)kv * kCodewords + chunk * kLutChunk + cl0) * kSD + 4 * p;
+#pragma unroll 1
+  for (int g0 = 0; g0 < Gt; g0 += 4) {
+    double qd[4][16];
 #pragma unroll
-  for (int t4 = 0; t4 < kSD / 4; ++t4) row[t4] = cw[t4];
-  double acc[8];
+    for (int gg = 0; gg < 4; ++gg) {
+      const int g = g0 + gg < Gt ? g0 + gg : g0;   // a head past the end repeats the first; its result is dropped
 #pragma unroll
-  for (int g = 0; g < 8; ++g) acc[g] = 0.0;
+      for (int i = 0; i < 4; ++i) {
+        const float4 f = *(const float4*)&s_q[g][32 * i + 4 * p];
+        qd[gg][4 * i] = (double)f.x;
+        qd[gg][4 * i + 1] = (double)f.y;
+        qd[gg][4 * i + 2] = (double)f.z;
+        qd[gg][4 * i + 3] = (double)f.w;
+      }
+    }
+#pragma unroll 1
+    for (int half = 0; half < 2; ++half) {
+      float4 row[4][4];
 #pragma unroll
-  for (int t4 = 0; t4 < kSD / 4; ++t4) {
-    const float4 f = row[t4];
+      for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-    for (int g = 0; g < 8; ++g) {
-      if (g < Gt) {
-        acc[g] += (double)s_q[g][4 * t4] * (double)f.x + (double)s_q[g][4 * t4 + 1] * (double)f.y +
-                  (double)s_q[g][4 * t4 + 2] * (double)f.z + (double)s_q[g][4 * t4 + 3] * (double)f.w;
+        for (int i = 0; i < 4; ++i) row[jj][i] = *(const float4*)(cw0 + (size_t)(4 * half + jj) * kSD + 32 * i);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const double c0 = (double)row[jj][i].x, c1 = (double)row[jj][i].y, c2 = (double)row[jj][i].z,
+                       c3 = (double)row[jj][i].w;
+#pragma unroll
+          for (int gg = 0; gg < 4; ++gg)
+            acc[gg] += qd[gg][4 * i] * c0 + qd[gg][4 * i + 1] * c1 + qd[gg][4 * i + 2] * c2 + qd[gg][4 * i + 3] * c3;
+        }
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          const double tot = group8_sum_f64(acc[gg]);
+          if (p == gg && g0 + gg < Gt) s_out[g0 + gg][cl0 + 4 * half + jj] = float_to_key((float)tot);
+        }
       }
     }
   }
-#pragma unroll
-  for (int g = 0; g < 8; ++g)
-    if (g < Gt) lut[((size_t)b * Ht + kv * Gt + g) * kCodewords + c] = float_to_key((float)acc[g]);
+  __syncthreads();
+  for (int g = 0; g < Gt; ++g)
+    lut[((size_t)b * Ht + kv * Gt + g) * kCodewords + chunk * kLutChunk + tid] = s_out[g][tid];
 }
 
 hipError_t launch_build_lut_single(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
