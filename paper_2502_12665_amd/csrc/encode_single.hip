@@ -27,8 +27,11 @@
 //                                  of the bf16 products are decided in float64 between those two
 //                                  codewords; keys with three that close by a float64 sweep over all
 //                                  4096.  So the emitted code is the float64 argmin.
-//   encode_single_sweep_kernel     the few-key (decode-time append) route: float64 sweeps only, 16
-//                                  workgroups per key, then encode_single_sweep_pick_kernel
+//   encode_single_heff_kernel      L L^T (full-matrix mode), for w = c (L L^T) kept beside c^z
+//   encode_single_sweep_kernel     the few-key (decode-time append) route: the distortion expanded as
+//                                  |z|^2 - 2 k . w_c + |c^z|^2, so one float64 pass of dot products
+//                                  over w decides the key; 16 workgroups per key, then
+//                                  encode_single_sweep_pick_kernel
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -53,7 +56,8 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 struct EncWs {
-  size_t off_L, off_sd, off_czT, off_cfrag, off_cbias, off_cstat, off_z, off_count, off_list, off_part, bytes;
+  size_t off_L, off_sd, off_heff, off_czT, off_wT, off_chalf, off_cfrag, off_cbias, off_cstat, off_z, off_count, off_list,
+      off_part, bytes;
   int chunk;   // keys per (sequence, KV head) the transform buffer holds
 };
 
@@ -69,7 +73,10 @@ EncWs enc_single_ws(const a2ats_dims& d) {
   };
   w.off_L = take(Hkv * kD * kD * sizeof(double));
   w.off_sd = take(Hkv * kD * sizeof(double));
+  w.off_heff = take(Hkv * kD * kD * sizeof(double));
   w.off_czT = take(Hkv * kD * kCW * sizeof(double));
+  w.off_wT = take(Hkv * kD * kCW * sizeof(double));
+  w.off_chalf = take(Hkv * kCW * sizeof(double));
   w.off_cfrag = take(Hkv * kBlocks * (size_t)kFragBytes);
   w.off_cbias = take(Hkv * kCW * sizeof(float));
   w.off_cstat = take(Hkv * 4 * sizeof(float));
@@ -149,11 +156,33 @@ __global__ __launch_bounds__(256) void encode_single_factor_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// c^z = c L for 64 codewords per workgroup (float64), in the three forms the other kernels read.
+// L L^T, the matrix the factor stands for (equal to H up to rounding when H is positive definite;
+// the few-key route weighs with it so that both routes minimise the same distortion).
+// One workgroup per row i: thread j sums L[i][m] L[j][m] over m.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kD) void encode_single_heff_kernel(const double* __restrict__ Lmat,
+                                                                double* __restrict__ heff) {
+  const int kv = blockIdx.y, i = blockIdx.x, j = threadIdx.x;
+  const double* L = Lmat + (size_t)kv * kD * kD;
+  double s0 = 0.0, s1 = 0.0;
+  const int m_end = (i < j ? i : j) + 1;   // L[r][m] = 0 for m > r
+  int m = 0;
+  for (; m + 1 < m_end; m += 2) {
+    s0 += L[(size_t)i * kD + m] * L[(size_t)j * kD + m];
+    s1 += L[(size_t)i * kD + m + 1] * L[(size_t)j * kD + m + 1];
+  }
+  if (m < m_end) s0 += L[(size_t)i * kD + m] * L[(size_t)j * kD + m];
+  heff[((size_t)kv * kD + i) * kD + j] = s0 + s1;
+}
+
+// ------------------------------------------------------------------------------------------
+// c^z = c L for 64 codewords per workgroup (float64), in the three forms the other kernels read,
+// and w = c (L L^T) with 1/2 |c^z|^2 in float64 for the few-key route.
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void encode_single_codewords_kernel(
     const float* __restrict__ codebook, int mode, const double* __restrict__ Lmat, const double* __restrict__ sd,
-    double* __restrict__ czT, uint16_t* __restrict__ cfrag, float* __restrict__ cbias, float* __restrict__ cstat) {
+    const double* __restrict__ heff, double* __restrict__ czT, double* __restrict__ wT, double* __restrict__ chalf,
+    uint16_t* __restrict__ cfrag, float* __restrict__ cbias, float* __restrict__ cstat) {
   __shared__ float s_c[64][kD + 1];
   __shared__ double s_n[4][64];
   const int kv = blockIdx.y, c0 = blockIdx.x * 64, tid = threadIdx.x;
@@ -197,9 +226,29 @@ __global__ __launch_bounds__(256) void encode_single_codewords_kernel(
   if (tq == 0) {
     const double n = s_n[0][c] + s_n[1][c] + s_n[2][c] + s_n[3][c];
     cbias[(size_t)kv * kCW + cg] = (float)(0.5 * n);
+    chalf[(size_t)kv * kCW + cg] = 0.5 * n;
     // max over the codewords of |c^z|, rounded up (a non-negative float orders like its bits)
     atomicMax((uint32_t*)&cstat[kv * 4 + 0], __float_as_uint(__double2float_ru(sqrt(n))));
   }
+  // w = c (L L^T): the distortion is |z|^2 - 2 k . w + |c^z|^2, so the few-key route needs no z
+  if (mode == A2ATS_W_BLOCK) {
+#pragma unroll
+    for (int u = 0; u < 32; ++u) acc[u] = 0.0;
+    const double* Hm = heff + (size_t)kv * kD * kD + 32 * tq;
+    for (int r = 0; r < kD; ++r) {
+      const double cv = (double)s_c[c][r];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) acc[u] += cv * Hm[(size_t)r * kD + u];
+    }
+  } else {
+#pragma unroll
+    for (int u = 0; u < 32; ++u) {
+      const double sdu = sd[(size_t)kv * kD + 32 * tq + u];
+      acc[u] = (double)s_c[c][32 * tq + u] * sdu * sdu;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 32; ++u) wT[((size_t)kv * kD + 32 * tq + u) * kCW + cg] = acc[u];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -557,57 +606,52 @@ __global__ __launch_bounds__(256) void encode_single_recheck_kernel(
 __global__ void encode_single_clear_kernel(uint32_t* counter) { *counter = 0; }
 
 // The few-key (append) route: every key is decided by a float64 sweep, its 4096 codewords split
-// over kSlices workgroups (one workgroup would read 4 MB of transformed codewords by itself).
-// part[key][slice] = {smallest distortion of the slice, its code as a double}.
-__global__ __launch_bounds__(1024) void encode_single_sweep_kernel(
-    const float* __restrict__ keys, int mode, const double* __restrict__ Lmat, const double* __restrict__ sd,
-    const double* __restrict__ czT, double* __restrict__ part, int Hkv, int n_new) {
+// over kSlices workgroups (one workgroup would read 4 MB by itself).  With w_c = c (L L^T) the
+// distortion of codeword c is |z|^2 - 2 k . w_c + |c^z|^2, so the sweep minimises
+// 1/2 |c^z|^2 - k . w_c and needs neither z nor L: one pass of dot products over wT.
+// part[key][slice] = {smallest value of the slice, its code as a double}.
+// 512 threads and at most 128 registers each, so that the two workgroups per CU of the usual
+// decode batch (32 keys x 16 slices on 256 CUs) are resident together.
+constexpr int kSweepThreads = 512;
+__global__ __launch_bounds__(kSweepThreads) __attribute__((amdgpu_waves_per_eu(4, 4))) void encode_single_sweep_kernel(
+    const float* __restrict__ keys, const double* __restrict__ wT, const double* __restrict__ chalf,
+    double* __restrict__ part, int Hkv, int n_new) {
   constexpr int PER = kCW / kSlices;   // codewords per slice
-  static_assert(PER == 256, "a thread owns one codeword and a quarter of the dimensions");
-  __shared__ double s_k[kD], s_z[kD], s_p[4][PER], s_zp[8][kD];
+  static_assert(PER == 256 && kSweepThreads == 2 * PER, "a thread owns one codeword and half of the dimensions");
+  __shared__ double s_k[kD], s_p[2][PER];
   __shared__ int s_i[PER];
   const int tid = threadIdx.x, slice = blockIdx.y, key = blockIdx.x;
   const int bkv = key / n_new, kv = bkv % Hkv;
-  // thread = (codeword, quarter of the dimensions).  Its 32 transformed-codeword entries do not
-  // depend on the key, so they are requested first and arrive while z is being computed.
-  const int cl = tid & (PER - 1), tq = tid >> 8, c = slice * PER + cl;
-  const double* cz = czT + ((size_t)kv * kD + 32 * tq) * kCW + c;
-  double cv[32];
+  // thread = (codeword, half of the dimensions): the first 32 of its 64 entries are requested before
+  // the key is looked at; each is replaced by its successor as it is used.  (The fences keep the
+  // compiler from requesting the second half up front as well, which would not fit the registers.)
+  const int cl = tid & (PER - 1), th = tid >> 8, c = slice * PER + cl;
+  const double* w = wT + ((size_t)kv * kD + 64 * th) * kCW + c;
+  double wv[32];
 #pragma unroll
-  for (int t = 0; t < 32; ++t) cv[t] = cz[(size_t)t * kCW];
+  for (int t = 0; t < 32; ++t) wv[t] = w[(size_t)t * kCW];
+  const double half = chalf[(size_t)kv * kCW + c];
   if (tid < kD) s_k[tid] = (double)keys[(size_t)key * kD + tid];
-  __syncthreads();
-  if (mode == A2ATS_W_BLOCK) {
-    // z_t = sum_{r >= t} k_r L[r][t] (entries above the diagonal are stored zeros): eight threads
-    // per dimension take 16 rows each, all loads independent
-    const int t = tid & (kD - 1), pt = tid >> 7;
-    const double* L = Lmat + ((size_t)kv * kD + 16 * pt) * kD + t;
-    double z0 = 0.0, z1 = 0.0;
-#pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-      z0 += s_k[16 * pt + r] * L[(size_t)r * kD];
-      z1 += s_k[16 * pt + r + 1] * L[(size_t)(r + 1) * kD];
-    }
-    s_zp[pt][t] = z0 + z1;
-    __syncthreads();
-    if (tid < kD)
-      s_z[tid] = ((s_zp[0][tid] + s_zp[1][tid]) + (s_zp[2][tid] + s_zp[3][tid])) +
-                 ((s_zp[4][tid] + s_zp[5][tid]) + (s_zp[6][tid] + s_zp[7][tid]));
-  } else if (tid < kD) {
-    s_z[tid] = s_k[tid] * sd[(size_t)kv * kD + tid];
-  }
+  __builtin_amdgcn_sched_barrier(0);
   __syncthreads();
   double d0 = 0.0, d1 = 0.0;
 #pragma unroll
   for (int t = 0; t < 32; t += 2) {
-    const double e0 = s_z[32 * tq + t] - cv[t], e1 = s_z[32 * tq + t + 1] - cv[t + 1];
-    d0 += e0 * e0;
-    d1 += e1 * e1;
+    d0 += s_k[64 * th + t] * wv[t];
+    d1 += s_k[64 * th + t + 1] * wv[t + 1];
+    wv[t] = w[(size_t)(32 + t) * kCW];
+    wv[t + 1] = w[(size_t)(32 + t + 1) * kCW];
+    __builtin_amdgcn_sched_barrier(0);
   }
-  s_p[tq][cl] = d0 + d1;
+#pragma unroll
+  for (int t = 0; t < 32; t += 2) {
+    d0 += s_k[64 * th + 32 + t] * wv[t];
+    d1 += s_k[64 * th + 32 + t + 1] * wv[t + 1];
+  }
+  s_p[th][cl] = d0 + d1;
   __syncthreads();
   if (tid < PER) {
-    s_p[0][tid] = (s_p[0][tid] + s_p[1][tid]) + (s_p[2][tid] + s_p[3][tid]);
+    s_p[0][tid] = half - (s_p[0][tid] + s_p[1][tid]);
     s_i[tid] = c;
   }
   __syncthreads();
@@ -818,9 +862,15 @@ hipError_t launch_encode_single_prepare(const a2ats_dims& d, const float* codebo
   hipLaunchKernelGGL(encode_single_factor_kernel, dim3(d.n_kv_heads), dim3(256), factor_lds, stream, weights, mode,
                      Lmat, sd, cstat);
   if ((err = hipGetLastError()) != hipSuccess) return err;
+  double* heff = (double*)(base + w.off_heff);
+  if (mode == A2ATS_W_BLOCK) {
+    hipLaunchKernelGGL(encode_single_heff_kernel, dim3(kD, d.n_kv_heads), dim3(kD), 0, stream, Lmat, heff);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+  }
   hipLaunchKernelGGL(encode_single_codewords_kernel, dim3(kCW / 64, d.n_kv_heads), dim3(256), 0, stream, codebook,
-                     mode, Lmat, sd, (double*)(base + w.off_czT), (uint16_t*)(base + w.off_cfrag),
-                     (float*)(base + w.off_cbias), cstat);
+                     mode, Lmat, sd, heff, (double*)(base + w.off_czT), (double*)(base + w.off_wT),
+                     (double*)(base + w.off_chalf), (uint16_t*)(base + w.off_cfrag), (float*)(base + w.off_cbias),
+                     cstat);
   return hipGetLastError();
 }
 
@@ -847,8 +897,8 @@ hipError_t launch_encode_single(const a2ats_dims& d, const float* keys, int n_ne
 
   const uint32_t n_all = (uint32_t)((size_t)bkv * n_new);
   if (n_new <= kFewSingle) {
-    hipLaunchKernelGGL(encode_single_sweep_kernel, dim3(n_all, kSlices), dim3(1024), 0, stream, keys, mode, Lmat, sd,
-                       czT, part, Hkv, n_new);
+    hipLaunchKernelGGL(encode_single_sweep_kernel, dim3(n_all, kSlices), dim3(kSweepThreads), 0, stream, keys,
+                       (const double*)(base + w.off_wT), (const double*)(base + w.off_chalf), part, Hkv, n_new);
     if ((err = hipGetLastError()) != hipSuccess) return err;
     hipLaunchKernelGGL(encode_single_sweep_pick_kernel, dim3((n_all + 63) / 64), dim3(64), 0, stream, part,
                        (uint16_t*)codes, n_all, n_new, pos0, d.ctx_stride);
