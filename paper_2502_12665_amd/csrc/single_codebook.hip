@@ -171,6 +171,7 @@ constexpr int kRound = kSelThreads * kPerThread;    // tokens per round
 constexpr int kSpan = 32;                           // rounds a thread keeps in registers
 constexpr int kSpanTokens = kSpan * kRound;         // 131072
 constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kSmallSel = 128;                      // a K-th-key bin of at most this many codewords is finished by counting
 
 struct SelLds {
   int32_t table[kCodewords];    // the head's scores as order-preserving keys
@@ -182,6 +183,9 @@ struct SelLds {
   uint32_t wave_a[kSelWaves];
   uint32_t res[2];
   uint32_t kmin, kmax;
+  uint32_t small_n;                 // codewords in the bin of the K-th key after a radix level
+  uint32_t small_key[kSmallSel], small_w[kSmallSel];
+  uint8_t cls[kCodewords];          // per codeword: 1 = above the K-th key, 2 = equal to it, 0 = below
 };
 
 // The codes of tokens [j0, j0 + 8) of a sequence.  Branch-free: a start beyond the row is moved
@@ -206,6 +210,13 @@ __device__ __forceinline__ uint32_t valid_mask8(int j0, int lo, int hi) {
   return ((1u << e) - 1u) & ~((1u << a) - 1u);
 }
 
+// Bit 2i set when bit i of an 8-bit mask is.
+__device__ __forceinline__ uint32_t spread8(uint32_t m) {
+  m = (m | (m << 4)) & 0x0f0fu;
+  m = (m | (m << 2)) & 0x3333u;
+  return (m | (m << 1)) & 0x5555u;
+}
+
 // One workgroup per head.  A score is one table entry, so the K-th largest score over the
 // candidate tokens is a weighted selection over the 4096 codewords: (1) count the candidates per
 // codeword (one pass over the 2-byte codes), (2) MSB-first radix select over the 4096 keys weighted
@@ -222,7 +233,7 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
   constexpr int NT = kSelThreads;
   __shared__ SelLds L;
   const int bh = blockIdx.x, b = bh / Hq, h = bh % Hq, G = Hq / Hkv, kv = h / G, tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63, wave = tid >> 6, wave_u = __builtin_amdgcn_readfirstlane(wave);
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   int32_t* oi = topk_idx + (size_t)bh * top_k;
   float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
@@ -279,10 +290,16 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
       }
 #pragma unroll
       for (int r = 0; r < kSpan; ++r) {
-        const uint32_t vm = valid_mask8(s0 + r * kRound + tid * kPerThread, lo, hi);
+        const int jw = s0 + r * kRound + wave_u * (64 * kPerThread);   // first token of this wave's share
+        if (jw >= lo && jw + 64 * kPerThread <= hi) {   // (wave-uniform) every token is a candidate
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i)   // tokens outside the candidate range count in a spare bin
-          atomicAdd(&L.count[(vm >> i) & 1u ? code_of(cv[r], i) : (uint32_t)kCodewords], 1u);
+          for (int i = 0; i < kPerThread; ++i) atomicAdd(&L.count[code_of(cv[r], i)], 1u);
+        } else {
+          const uint32_t vm = valid_mask8(s0 + r * kRound + tid * kPerThread, lo, hi);
+#pragma unroll
+          for (int i = 0; i < kPerThread; ++i)   // tokens outside the candidate range count in a spare bin
+            atomicAdd(&L.count[(vm >> i) & 1u ? code_of(cv[r], i) : (uint32_t)kCodewords], 1u);
+        }
       }
     }
 #pragma unroll
@@ -305,6 +322,7 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
       const int shift = remaining - bits;
       const uint32_t dmask = (1u << bits) - 1u;
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
+      if (tid == 0) L.small_n = 0;
       __syncthreads();
       for (int e = tid; e < kCodewords; e += NT) {
         const uint32_t rel = score_key(L.table[e]) - k_lo, w = L.count[e];
@@ -318,9 +336,58 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
       mask |= dmask << shift;
       remaining = shift;
       __syncthreads();
+      if (remaining == 0) break;
+      // The bin of the K-th key usually holds a handful of codewords: list them, and let every
+      // member add up the candidates above and at its own key; the one whose range contains
+      // k_rem is the K-th key.  A crowded bin goes on with the next radix level.
+      for (int e = tid; e < kCodewords; e += NT) {
+        const uint32_t rel = score_key(L.table[e]) - k_lo, w = L.count[e];
+        if (w && (rel & mask) == prefix) {
+          const uint32_t at = atomicAdd(&L.small_n, 1u);
+          if (at < (uint32_t)kSmallSel) {
+            L.small_key[at] = rel;
+            L.small_w[at] = w;
+          }
+        }
+      }
+      __syncthreads();
+      const uint32_t n_small = L.small_n;
+      if (n_small <= (uint32_t)kSmallSel) {
+        if ((uint32_t)tid < n_small) {
+          const uint32_t key = L.small_key[tid];
+          uint32_t gt = 0, eq = 0;
+          for (uint32_t u = 0; u < n_small; ++u) {
+            const uint32_t ku = L.small_key[u], wu = L.small_w[u];
+            gt += ku > key ? wu : 0u;
+            eq += ku == key ? wu : 0u;
+          }
+          if (gt < k_rem && k_rem <= gt + eq) {   // every member at the K-th key writes the same two words
+            L.res[0] = key;
+            L.res[1] = k_rem - gt;
+          }
+        }
+        __syncthreads();
+        prefix = L.res[0];
+        k_rem = L.res[1];
+        break;
+      }
     }
     kth = prefix + k_lo;
   }
+  // class of every codeword, one byte each: the emission pass then costs one byte read per token
+  {
+    uint32_t pk[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t key = score_key(L.table[tid * 8 + i]);
+      const uint32_t c = take_all ? 1u : (key > kth ? 1u : (key == kth ? 2u : 0u));
+      pk[i >> 2] |= c << (8 * (i & 3));
+    }
+    static_assert(kCodewords == 8 * NT, "a thread classifies 8 codewords");
+    ((uint32_t*)L.cls)[tid * 2] = pk[0];
+    ((uint32_t*)L.cls)[tid * 2 + 1] = pk[1];
+  }
+  __syncthreads();
 
   // (3) ordered emission: keys above the K-th, plus the first k_rem positions that equal it
   uint32_t out_n = 0, eq_seen = 0;
@@ -332,24 +399,22 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
 #pragma unroll
       for (int r = 0; r < kSpan; ++r) cv[r] = load_codes8<ALIGNED>(seq_codes, s0 + r * kRound + tid * kPerThread, row_len);
     }
-    uint32_t gbits[kSpan / 4], ebits[kSpan / 4];
+    // two bits per token (bit 2i: above the K-th key, bit 2i + 1: equal to it), two rounds per word
+    uint32_t cbits[kSpan / 2];
 #pragma unroll
-    for (int i = 0; i < kSpan / 4; ++i) gbits[i] = ebits[i] = 0;
+    for (int i = 0; i < kSpan / 2; ++i) cbits[i] = 0;
 #pragma unroll
     for (int r = 0; r < kSpan; ++r) {
-      const uint32_t vm = valid_mask8(s0 + r * kRound + tid * kPerThread, lo, hi);
-      uint32_t g = 0, e = 0;
+      uint32_t c2 = 0;
 #pragma unroll
-      for (int i = 0; i < kPerThread; ++i) {
-        const uint32_t key = score_key(L.table[code_of(cv[r], i)]);
-        g |= (take_all || key > kth ? 1u : 0u) << i;
-        e |= (!take_all && key == kth ? 1u : 0u) << i;
+      for (int i = 0; i < kPerThread; ++i) c2 |= (uint32_t)L.cls[code_of(cv[r], i)] << (2 * i);
+      const int jw = s0 + r * kRound + wave_u * (64 * kPerThread);
+      if (!(jw >= lo && jw + 64 * kPerThread <= hi)) {   // (wave-uniform) some tokens are not candidates
+        const uint32_t vm = spread8(valid_mask8(s0 + r * kRound + tid * kPerThread, lo, hi));
+        c2 &= vm | (vm << 1);
       }
-      g &= vm;
-      e &= vm;
-      gbits[r / 4] |= g << (8 * (r % 4));
-      ebits[r / 4] |= e << (8 * (r % 4));
-      const uint32_t v = wave_inclusive_scan((uint32_t)__popc(g) | ((uint32_t)__popc(e) << 16));
+      cbits[r / 2] |= c2 << (16 * (r % 2));
+      const uint32_t v = wave_inclusive_scan((uint32_t)__popc(c2 & 0x5555u) | ((uint32_t)__popc(c2 & 0xaaaau) << 16));
       if (lane == 63) L.wave_tot[r][wave] = v;
     }
     __syncthreads();
@@ -368,7 +433,8 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < kSpan; ++r) {
-      const uint32_t g = (gbits[r / 4] >> (8 * (r % 4))) & 0xffu, e = (ebits[r / 4] >> (8 * (r % 4))) & 0xffu;
+      const uint32_t c2 = (cbits[r / 2] >> (16 * (r % 2))) & 0xffffu;
+      const uint32_t g = c2 & 0x5555u, e = (c2 >> 1) & 0x5555u;   // token i at bit 2i
       const uint32_t tot = L.round_tot[r];
       // (the scan over the wave is recomputed rather than kept: 32 more registers would spill)
       const uint32_t own = (uint32_t)__popc(g) | ((uint32_t)__popc(e) << 16);
@@ -391,8 +457,8 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
         uint32_t m = g | e_take;
 #pragma unroll 1
         while (m) {
-          const int i = __ffs(m) - 1;
-          const uint32_t below = (1u << i) - 1u;
+          const int bit = __ffs(m) - 1, i = bit >> 1;
+          const uint32_t below = (1u << bit) - 1u;
           const uint32_t slot = out_n + gt_before + (uint32_t)__popc(g & below) + min(eq_before, k_rem) + (uint32_t)__popc(e_take & below);
           oi[slot] = j0 + i;
           if (os) os[slot] = key_to_float(L.table[seq_codes[j0 + i] & (kCodewords - 1)]);
