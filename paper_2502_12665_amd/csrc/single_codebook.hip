@@ -312,40 +312,42 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
       atomicMax(&L.kmax, kmax);
     }
     __syncthreads();
-    // (2) weighted radix select over the codewords; digits from key - smallest key, MSB first
+    // (2) the K-th largest key over the codewords weighted by those counts.  First a level of
+    // 2048 bins LINEAR in the score between the smallest and the largest table entry (the bit
+    // pattern of a float spends its leading digits on the exponent: a level on those would put
+    // every score of one binade into one bin); the mapping is monotone, so the bin of the K-th
+    // key is exact.  That bin usually holds a handful of codewords: they are listed, and every
+    // member adds up the candidates above and at its own key -- the member whose range contains
+    // k_rem is the K-th key.  A crowded bin (many equal or nearly equal scores), or a table whose
+    // range is empty or not finite, is finished by an MSB-first radix select on the keys.
     const uint32_t k_lo = L.kmin;
-    int remaining = 32 - __clz(L.kmax - k_lo);
-    uint32_t prefix = 0, mask = 0;
-#pragma unroll 1
-    while (remaining > 0) {
-      const int bits = remaining < 11 ? remaining : 11;
-      const int shift = remaining - bits;
-      const uint32_t dmask = (1u << bits) - 1u;
+    const float s_lo = key_to_float(key_score(k_lo)), span = key_to_float(key_score(L.kmax)) - s_lo;
+    const bool use_lin = span >= 1e-30f && span < INFINITY;
+    const float lin_scale = use_lin ? (float)kHistBins / span : 0.f;
+    auto lin_bin = [&](int32_t entry) {
+      return (uint32_t)min((int)((key_to_float(entry) - s_lo) * lin_scale), kHistBins - 1);
+    };
+    uint32_t bin1 = 0;
+    bool found = false;
+    if (use_lin) {
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       if (tid == 0) L.small_n = 0;
       __syncthreads();
       for (int e = tid; e < kCodewords; e += NT) {
-        const uint32_t rel = score_key(L.table[e]) - k_lo, w = L.count[e];
-        if (w && (rel & mask) == prefix) atomicAdd(&L.hist[(rel >> shift) & dmask], w);
+        const uint32_t w = L.count[e];
+        if (w) atomicAdd(&L.hist[lin_bin(L.table[e])], w);
       }
       __syncthreads();
       block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
-      const uint32_t bin = L.res[0], above = L.res[1];
-      k_rem -= above;
-      prefix |= bin << shift;
-      mask |= dmask << shift;
-      remaining = shift;
-      __syncthreads();
-      if (remaining == 0) break;
-      // The bin of the K-th key usually holds a handful of codewords: list them, and let every
-      // member add up the candidates above and at its own key; the one whose range contains
-      // k_rem is the K-th key.  A crowded bin goes on with the next radix level.
+      bin1 = L.res[0];
+      k_rem -= L.res[1];
       for (int e = tid; e < kCodewords; e += NT) {
-        const uint32_t rel = score_key(L.table[e]) - k_lo, w = L.count[e];
-        if (w && (rel & mask) == prefix) {
+        const uint32_t w = L.count[e];
+        const int32_t entry = L.table[e];
+        if (w && lin_bin(entry) == bin1) {
           const uint32_t at = atomicAdd(&L.small_n, 1u);
           if (at < (uint32_t)kSmallSel) {
-            L.small_key[at] = rel;
+            L.small_key[at] = score_key(entry);
             L.small_w[at] = w;
           }
         }
@@ -367,12 +369,38 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
           }
         }
         __syncthreads();
-        prefix = L.res[0];
+        kth = L.res[0];
         k_rem = L.res[1];
-        break;
+        found = true;
       }
     }
-    kth = prefix + k_lo;
+    if (!found) {
+      int remaining = 32 - __clz(L.kmax - k_lo);
+      uint32_t prefix = 0, mask = 0;
+#pragma unroll 1
+      while (remaining > 0) {
+        const int bits = remaining < 11 ? remaining : 11;
+        const int shift = remaining - bits;
+        const uint32_t dmask = (1u << bits) - 1u;
+        __syncthreads();   // the histogram may still be read
+        for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
+        __syncthreads();
+        for (int e = tid; e < kCodewords; e += NT) {
+          const int32_t entry = L.table[e];
+          const uint32_t rel = score_key(entry) - k_lo, w = L.count[e];
+          if (w && (!use_lin || lin_bin(entry) == bin1) && (rel & mask) == prefix)
+            atomicAdd(&L.hist[(rel >> shift) & dmask], w);
+        }
+        __syncthreads();
+        block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
+        const uint32_t bin = L.res[0], above = L.res[1];
+        k_rem -= above;
+        prefix |= bin << shift;
+        mask |= dmask << shift;
+        remaining = shift;
+      }
+      kth = prefix + k_lo;
+    }
   }
   // class of every codeword, one byte each: the emission pass then costs one byte read per token
   {
@@ -401,6 +429,7 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
     }
     // two bits per token (bit 2i: above the K-th key, bit 2i + 1: equal to it), two rounds per word
     uint32_t cbits[kSpan / 2];
+    uint32_t pre[kSpan];   // packed (above, equal) counts of the lanes before this one, per round
 #pragma unroll
     for (int i = 0; i < kSpan / 2; ++i) cbits[i] = 0;
 #pragma unroll
@@ -414,7 +443,9 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
         c2 &= vm | (vm << 1);
       }
       cbits[r / 2] |= c2 << (16 * (r % 2));
-      const uint32_t v = wave_inclusive_scan((uint32_t)__popc(c2 & 0x5555u) | ((uint32_t)__popc(c2 & 0xaaaau) << 16));
+      const uint32_t own = (uint32_t)__popc(c2 & 0x5555u) | ((uint32_t)__popc(c2 & 0xaaaau) << 16);
+      const uint32_t v = wave_inclusive_scan(own);
+      pre[r] = v - own;
       if (lane == 63) L.wave_tot[r][wave] = v;
     }
     __syncthreads();
@@ -436,9 +467,7 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
       const uint32_t c2 = (cbits[r / 2] >> (16 * (r % 2))) & 0xffffu;
       const uint32_t g = c2 & 0x5555u, e = (c2 >> 1) & 0x5555u;   // token i at bit 2i
       const uint32_t tot = L.round_tot[r];
-      // (the scan over the wave is recomputed rather than kept: 32 more registers would spill)
-      const uint32_t own = (uint32_t)__popc(g) | ((uint32_t)__popc(e) << 16);
-      const uint32_t own_pre = wave_inclusive_scan(own) - own;
+      const uint32_t own_pre = pre[r];
       if (g | e) {
         const int j0 = s0 + r * kRound + tid * kPerThread;
         const uint32_t p = own_pre + L.wave_pre[r][wave];
