@@ -330,25 +330,30 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
     uint32_t bin1 = 0;
     bool found = false;
     if (use_lin) {
+      // this thread's 8 codewords, read once (the loops below would otherwise wait for LDS per codeword)
+      uint32_t w8[kTablePer], b8[kTablePer];
+#pragma unroll
+      for (int i = 0; i < kTablePer; ++i) {
+        w8[i] = L.count[i * NT + tid];
+        b8[i] = lin_bin(tv[i]);
+      }
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       if (tid == 0) L.small_n = 0;
       __syncthreads();
-      for (int e = tid; e < kCodewords; e += NT) {
-        const uint32_t w = L.count[e];
-        if (w) atomicAdd(&L.hist[lin_bin(L.table[e])], w);
-      }
+#pragma unroll
+      for (int i = 0; i < kTablePer; ++i)
+        if (w8[i]) atomicAdd(&L.hist[b8[i]], w8[i]);
       __syncthreads();
       block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
       bin1 = L.res[0];
       k_rem -= L.res[1];
-      for (int e = tid; e < kCodewords; e += NT) {
-        const uint32_t w = L.count[e];
-        const int32_t entry = L.table[e];
-        if (w && lin_bin(entry) == bin1) {
+#pragma unroll
+      for (int i = 0; i < kTablePer; ++i) {
+        if (w8[i] && b8[i] == bin1) {
           const uint32_t at = atomicAdd(&L.small_n, 1u);
           if (at < (uint32_t)kSmallSel) {
-            L.small_key[at] = score_key(entry);
-            L.small_w[at] = w;
+            L.small_key[at] = score_key(tv[i]);
+            L.small_w[at] = w8[i];
           }
         }
       }
@@ -403,17 +408,10 @@ __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
     }
   }
   // class of every codeword, one byte each: the emission pass then costs one byte read per token
-  {
-    uint32_t pk[2] = {0u, 0u};
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const uint32_t key = score_key(L.table[tid * 8 + i]);
-      const uint32_t c = take_all ? 1u : (key > kth ? 1u : (key == kth ? 2u : 0u));
-      pk[i >> 2] |= c << (8 * (i & 3));
-    }
-    static_assert(kCodewords == 8 * NT, "a thread classifies 8 codewords");
-    ((uint32_t*)L.cls)[tid * 2] = pk[0];
-    ((uint32_t*)L.cls)[tid * 2 + 1] = pk[1];
+  for (int i = 0; i < kTablePer; ++i) {
+    const uint32_t key = score_key(tv[i]);
+    L.cls[i * NT + tid] = take_all ? 1 : (key > kth ? 1 : (key == kth ? 2 : 0));
   }
   __syncthreads();
 

@@ -388,6 +388,36 @@ def test_single_codebook_heavy_ties(oracle):
     assert res["excluded"] <= res["slots"] // 1000
 
 
+def test_single_codebook_crowded_and_degenerate_tables(oracle):
+    """The selection finds the K-th score with one level of bins linear in the score and finishes a bin
+    of few codewords by counting.  Tables it cannot finish that way: thousands of nearly equal and
+    hundreds of exactly equal scores around the K-th (the bin is crowded: radix levels inside it),
+    and a table of identical scores (empty range: the lowest positions win)."""
+    wl = _single("single_crowded", 2, 8, 2, 8000, 3900, 64, n_sink=4, seed=17)
+
+    def crowd(x):
+        g = torch.Generator().manual_seed(3)
+        cb = x["codebook"]
+        cb[:, 0, :3000] = 1e-3 * torch.randn(cb.shape[0], 3000, cb.shape[-1], generator=g)
+        cb[:, 0, 3000:3200] = cb[:, 0, 2999:3000]
+        x["codes"][...] = torch.randint(0, 4096, x["codes"].shape, generator=g).to(x["codes"].dtype)
+
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl, mutate=crowd)
+    H.log(f"  {res}")
+    assert res["excluded"] <= res["slots"] // 100
+
+    def flat(x):
+        x["q"].zero_()
+
+    wl = _single("single_flat", 1, 4, 2, 5000, 700, 64, n_sink=4, seed=18)
+    H.log(wl.name)
+    st, res = _run_and_check(oracle, wl, mutate=flat)
+    torch.cuda.synchronize()
+    idx = st.topk_idx.cpu().numpy()
+    assert (idx[:, :, :700] == np.arange(4, 704)[None, None]).all()   # after the 4 sinks
+
+
 @pytest.mark.parametrize("mode", ["none", "diag", "block"])
 def test_single_codebook_encode(oracle, mode):
     """Key encoder of the single-codebook geometry (full D x D matrix H in "block" mode) against the
