@@ -131,10 +131,11 @@ int a2ats_rope_tables(int32_t head_dim, const double* inv_freq, int32_t b, int32
  * formed on the matrix cores from bf16 hi/lo splits of both operands (about 2^-18 relative),
  * and every key whose two best scores are closer than that arithmetic can tell apart is decided
  * again in float64, so codes equal the float64 argmin.  Every weight mode needs the workspace
- * (L and c^z in three forms, 6.4 MB per KV head; a buffer of transformed keys for up to 16384
- * rows per sequence and KV head; 8 bytes per key that ctx_stride allows); each call derives L
- * and c^z again unless weight_mode carries A2ATS_W_PREPARED (see a2ats_encode_prepare).  Up to
- * 8 keys per sequence and KV head (the decode-time append) are decided by float64 sweeps alone.
+ * (L, c^z in three forms and w = c (L L^T), 10.8 MB per KV head; a buffer of transformed keys for
+ * up to 16384 rows per sequence and KV head; 8 bytes per key that ctx_stride allows); each call
+ * derives them again unless weight_mode carries A2ATS_W_PREPARED (see a2ats_encode_prepare).  Up
+ * to 8 keys per sequence and KV head (the decode-time append) are decided by one float64 sweep
+ * each, over the expanded form 1/2||c^z||^2 - k.w of the same distortion.
  * B*Hkv*n_new must stay below 2^31.
  */
 int a2ats_encode_keys(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
@@ -310,7 +311,7 @@ int a2ats_sparse_attn_shared(const a2ats_dims* dims, const void* q, const float*
  *   codebook_out  [dev, out, f32 Hkv*4096*D] the chosen keys
  *   picks         [dev, out, nullable, int32 Hkv*4096] their row numbers
  * Workspace a2ats_workspace_bytes(dims, A2ATS_OP_SEED, 0, 0).  One workgroup per KV head runs the 4096
- * sequential draws: meant for calibration sets of up to ~10^5 keys per KV head.  Single codebook only.
+ * sequential draws (one update and one pick launch per draw): meant for calibration sets of up to ~10^5 keys per KV head.  Single codebook only.
  */
 int a2ats_kmeanspp_seed(const a2ats_dims* dims, const float* keys, int32_t n_new, const float* weights,
                         int weight_mode, const double* u, float* codebook_out, int32_t* picks, void* ws,
