@@ -8,7 +8,7 @@
 //                              products rounded once to float32 and stored as order-preserving
 //                              32-bit keys (no fixed-point scale is needed: a score is one entry)
 //   select_single_kernel       exact top-K per head: candidates counted per codeword, a weighted
-//                              radix select over the 4096 codewords, then one ordered pass that emits
+//                              selection over the 4096 codewords, then one ordered pass that emits
 //                              the winners in ascending position, equal scores to the lower position
 // (the key encoder of this geometry lives in encode_single.hip)
 #include "common.hpp"
@@ -219,12 +219,12 @@ __device__ __forceinline__ uint32_t spread8(uint32_t m) {
 
 // One workgroup per head.  A score is one table entry, so the K-th largest score over the
 // candidate tokens is a weighted selection over the 4096 codewords: (1) count the candidates per
-// codeword (one pass over the 2-byte codes), (2) MSB-first radix select over the 4096 keys weighted
-// by those counts, (3) a pass that emits the winners in ascending position, equal scores going to
-// the lower position.  A thread keeps the codes of 16 rounds of 8 consecutive tokens in registers
-// (one span = 131072 tokens per workgroup): all 16 loads are in flight together, a context of one
-// span is read once and serves both passes, and the 16 rounds share one scan of their packed
-// (above, equal) counts instead of one scan and two barriers per round.
+// codeword (one pass over the 2-byte codes), (2) find the K-th key over the 4096 keys weighted by
+// those counts, (3) a pass that emits the winners in ascending position, equal scores going to
+// the lower position.  A thread keeps the codes of kSpan rounds of 8 consecutive tokens in
+// registers (one span = 131072 tokens per workgroup): all its loads are in flight together, a
+// context of one span is read once and serves both passes, and the rounds share one scan of their
+// packed (above, equal) counts over the waves instead of one scan and two barriers per round.
 template <bool ALIGNED>
 __global__ __launch_bounds__(kSelThreads) void select_single_kernel(
     const uint16_t* __restrict__ codes, const int32_t* __restrict__ lut, const int32_t* __restrict__ seq_lens,
