@@ -164,6 +164,21 @@ __device__ __forceinline__ void xcd_map(int linear, int parts, int problems, int
   }
 }
 
+// The same for problems that come in sets of `ng` reading the same rows (the head groups of one KV
+// head, problem = kv_problem * ng + g): all parts of all ng problems of a set run on XCD
+// (kv_problem % 8), and the ng workgroups that stream the same part are neighbours in the launch
+// order, so the rows come from HBM once and from that XCD's L2 for the others.
+__device__ __forceinline__ void xcd_map_sets(int linear, int parts, int problems, int ng, int& problem, int& part) {
+  if (ng > 1 && problems % (8 * ng) == 0) {
+    const int xcd = linear & 7, slot = linear >> 3;
+    const int unit = slot / (parts * ng), inner = slot % (parts * ng);
+    problem = (unit * 8 + xcd) * ng + inner % ng;
+    part = inner / ng;
+  } else {
+    xcd_map(linear, parts, problems, problem, part);
+  }
+}
+
 // Per-sequence geometry of the candidate range (sinks and window never compete).
 struct SeqRange {
   int n;          // tokens in the sequence

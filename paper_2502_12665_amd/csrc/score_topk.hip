@@ -70,35 +70,57 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
     if (chunks > 64) chunks = 64;
-    // One survivor segment per (problem, chunk, wave) of the streaming pass: a header and row_cap
-    // row entries.  The sampling rule (rank r with r - 5 sqrt(r) >= K S / N, plus one per part) lets
-    // about r N / S rows per head through -- for small K much more than K -- and a row survives if
-    // any of the (up to) four heads wants it.  row_cap is twice that share of a wave's rows plus 16
-    // standard deviations of a Poisson count: survivors that come in runs (neighbouring tokens with
-    // similar scores) scatter far more between segments than independent ones.  Ranks inside a
-    // segment are stored in 10 bits, so the context is cut into more chunks until row_cap fits 1024.
+    // Survivor segments: a header and row_cap row entries each.  The sampling rule (rank r with
+    // r - 5 sqrt(r) >= K S / N, plus one per part) lets about r N / S rows per head through -- for
+    // small K much more than K -- and a row survives if any of the (up to) four heads wants it.
+    // row_cap is twice that share of a segment's rows plus 16 standard deviations of a Poisson
+    // count: survivors that come in runs (neighbouring tokens with similar scores) scatter far more
+    // between segments than independent ones.  Ranks inside a segment are stored in 10 bits, so
+    // row_cap must fit 1024: a wave whose rows would need more cuts them into `subs` runs of a
+    // multiple of 512 rows (one iteration of its loop), one segment each; the final kernel handles
+    // at most 512 segments per problem, beyond that the context is cut into more chunks instead.
     const double r0 = (double)top_k * (double)s_tot / (double)ncand;
     const double xr = 0.5 * (kSigma + std::sqrt(kSigma * kSigma + 4.0 * r0));
     const double survivors = (xr * xr + 2.0 * p.P0) / (double)s_tot * (double)ncand * 1.25;
     const double keep = std::min(1.0, 4.0 * survivors / (double)ncand);
-    long rpc, cap_rows;
+    auto cap_for = [&](long rows) {   // rows is a multiple of 64
+      const double mu = rows * keep;
+      long c = (long)(mu * 2.0 + 16.0 * std::sqrt(mu)) + 64;   // generous: unused capacity costs only scratch
+      c = (c + 31) / 32 * 32;
+      if (c < 64) c = 64;
+      return c > rows ? rows : c;
+    };
+    long rpc, cap_rows, subs, sub_rows;
     for (;; ++chunks) {
       rpc = (ncand + chunks - 1) / chunks;
       rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
       const long rows_per_wave = rpc / kStreamWaves;
-      const double mu = rows_per_wave * keep;
-      cap_rows = (long)(mu * 2.0 + 16.0 * std::sqrt(mu)) + 64;   // generous: unused capacity costs only scratch
-      cap_rows = (cap_rows + 31) / 32 * 32;
-      if (cap_rows < 64) cap_rows = 64;
-      if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;   // rows_per_wave is a multiple of 64
+      subs = 1;
+      sub_rows = rows_per_wave;
+      cap_rows = cap_for(rows_per_wave);
       if (cap_rows <= 1024 || chunks >= 64) break;
+      const long max_subs = 512 / (chunks * kStreamWaves);
+      bool ok = false;
+      for (long sb = 2; sb <= max_subs && !ok; ++sb) {
+        const long sr = ((rows_per_wave + sb - 1) / sb + 511) / 512 * 512;
+        if (cap_for(sr) <= 1024) {
+          subs = sb;
+          sub_rows = sr;
+          cap_rows = cap_for(sr);
+          rpc = sb * sr * kStreamWaves;
+          ok = true;
+        }
+      }
+      if (ok) break;
     }
     if (cap_rows > 1024) cap_rows = 1024;   // cannot happen for contexts up to 2^20 tokens (64 chunks of <= 2048 rows per wave)
     p.chunks = (int)((ncand + rpc - 1) / rpc);
     p.rows_per_chunk = (int)rpc;
+    p.subs = (int)subs;
+    p.sub_rows = (int)sub_rows;
     p.row_cap = (int)cap_rows;                // a multiple of 32
     const size_t heads = (size_t)d.batch * d.n_q_heads;
-    const size_t segs = (size_t)problems * p.chunks * kStreamWaves;
+    const size_t segs = (size_t)problems * p.chunks * kStreamWaves * p.subs;
     const size_t entry_bytes = 8 + d.n_sub;   // header + code bytes
     p.off_thr = 0;
     p.off_route = (p.off_thr + heads * p.P0 * sizeof(int32_t) + 255) / 256 * 256;
@@ -247,8 +269,9 @@ __device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const uns
 #pragma unroll
   for (int qd = 0; qd < M / 16; ++qd) {
     // z[d] = row dword (d ^ (rho >> 2))
-    const uint32_t x0 = sw.swap1 ? w[qd].y : w[qd].x, x1 = sw.swap1 ? w[qd].x : w[qd].y;
-    const uint32_t x2 = sw.swap1 ? w[qd].w : w[qd].z, x3 = sw.swap1 ? w[qd].z : w[qd].w;
+    const uint4 wq = w[qd];
+    const uint32_t x0 = sw.swap1 ? wq.y : wq.x, x1 = sw.swap1 ? wq.x : wq.y;
+    const uint32_t x2 = sw.swap1 ? wq.w : wq.z, x3 = sw.swap1 ? wq.z : wq.w;
     const uint32_t z[4] = {sw.swap2 ? x2 : x0, sw.swap2 ? x3 : x1, sw.swap2 ? x0 : x2, sw.swap2 ? x1 : x3};
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
@@ -480,7 +503,7 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
   __shared__ uint32_t s_hist[2][kHistBins];   // two heads per word, 16-bit counts (a workgroup scores at most 8192 rows)
 
   int p, prob;
-  xcd_map(blockIdx.x, P0, problems, prob, p);
+  xcd_map_sets(blockIdx.x, P0, problems, NG, prob, p);
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
@@ -577,19 +600,22 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
 // ------------------------------------------------------------------------------------------
 // Fast route, stage 2: one pass over the code matrix
 // ------------------------------------------------------------------------------------------
-template <int M>
+// RESHARED: the rows are read by more than one problem (the head groups of a KV head, placed next
+// to each other on one XCD): ordinary loads, so that the line stays in that L2 for the neighbour;
+// otherwise non-temporal loads (each row is read once).
+template <int M, bool RESHARED>
 __device__ __forceinline__ void stream_select_body(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
     uint32_t* __restrict__ seg_meta, uint32_t* __restrict__ cand, int B, int Hq, int Hkv, int NG,
-    int P0, int n_chunks, int problems, int rows_per_chunk, int row_cap, int ctx_len,
+    int P0, int n_chunks, int problems, int rows_per_chunk, int subs, int sub_rows, int row_cap, int ctx_len,
     int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   unsigned char* tbl = dyn_lds;
 
   int chunk, prob;
-  xcd_map(blockIdx.x, n_chunks, problems, prob, chunk);
+  xcd_map_sets(blockIdx.x, n_chunks, problems, NG, prob, chunk);
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
@@ -601,8 +627,9 @@ __device__ __forceinline__ void stream_select_body(
   const long wbegin = begin + (long)wv * rows_per_wave;
   const int wend = (int)min((long)end, wbegin + rows_per_wave);
 
-  // Every (problem, chunk, wave) owns one survivor segment in HBM: no atomics, no contention.
-  const size_t seg = ((size_t)prob * n_chunks + chunk) * kStreamWaves + wv;
+  // Every (problem, chunk, wave) owns `subs` survivor segments in HBM, one per run of sub_rows of
+  // its rows: no atomics, no contention.
+  const size_t seg = (((size_t)prob * n_chunks + chunk) * kStreamWaves + wv) * subs;
   uint32_t* my_meta = seg_meta + seg * kSegMeta;
   // thresholds of the group's heads: requested here, combined after the table copy has been issued
   const int32_t thr_lane = request_thresholds<4>(thr, (size_t)b * Hq + kv * G + g4 * kHeadsPerGroup,
@@ -613,7 +640,8 @@ __device__ __forceinline__ void stream_select_body(
   // an overflowing segment instead: the final kernel then takes the exact route.
   const bool misplaced = (uint32_t)(uintptr_t)tbl != 0u;
   if (begin >= sr.win_start || misplaced) {   // nothing to score in this chunk: empty segments
-    if (lane < kSegMeta) my_meta[lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
+    for (int sb = 0; sb < subs; ++sb)
+      if (lane < kSegMeta) my_meta[sb * kSegMeta + lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
     return;
   }
 
@@ -625,6 +653,19 @@ __device__ __forceinline__ void stream_select_body(
   uint32_t* my_seg = cand + seg * segment_words<M>(row_cap);
   uint2* my_hdr = (uint2*)my_seg;
   uint4* my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
+  int sub = 0;   // the run (and segment) the wave is in
+  auto publish = [&](int sb, bool counted) {   // header of segment sb: rows written, rows per head
+    if (lane < kSegMeta) {
+      uint32_t v = 0;
+      if (counted) {
+        if (lane == 0) v = (uint32_t)n_rows;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (lane == 1 + r) v = (uint32_t)n_head[r];
+      }
+      my_meta[sb * kSegMeta + lane] = v;
+    }
+  };
 
   const bool has_rows = wbegin < wend;   // wave-uniform
   {
@@ -642,7 +683,8 @@ __device__ __forceinline__ void stream_select_body(
         const int jl = j < wend ? j : wend - 1;
 #pragma unroll
         for (int qd = 0; qd < M / 16; ++qd)
-          dst[u][qd] = load_stream_u4(seq_codes + (size_t)jl * M + qd * 16);
+          dst[u][qd] = RESHARED ? *(const uint4*)(seq_codes + (size_t)jl * M + qd * 16)
+                                : load_stream_u4(seq_codes + (size_t)jl * M + qd * 16);
       }
     };
     auto process = [&](int base, const uint4 (&rows)[U][M / 16]) {
@@ -696,40 +738,51 @@ __device__ __forceinline__ void stream_select_body(
     load_coarse_table<M, NT>(lut, lut_layout(B, Hq, Hkv, M), prob, tbl);
     combine_thresholds<4>(thr_lane, G - g4 * kHeadsPerGroup, P0, T);
     __syncthreads();
+    long sub_end = wbegin + sub_rows;
 #pragma unroll 1
     for (int base = (int)wbegin; base < wend; base += 2 * STEP) {
+      if (base >= sub_end) {   // (wave-uniform; runs are whole iterations long) on to the next segment
+        publish(sub, true);
+        ++sub;
+        sub_end += sub_rows;
+        n_rows = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) n_head[r] = 0;
+        my_seg += segment_words<M>(row_cap);
+        my_hdr = (uint2*)my_seg;
+        my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
+      }
       load_rows(base + STEP, rows_b);
       process(base, rows_a);
       load_rows(base + 2 * STEP, rows_a);
       process(base + STEP, rows_b);
     }
   }
-  if (lane < kSegMeta) {
-    uint32_t v = 0;
-    if (lane == 0) v = (uint32_t)n_rows;
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-      if (lane == 1 + r) v = (uint32_t)n_head[r];
-    my_meta[lane] = v;
-  }
+  publish(sub, true);
+  for (int sb = sub + 1; sb < subs; ++sb) publish(sb, false);   // runs beyond the end of the sequence
 }
 
 #define A2ATS_STREAM_ARGS                                                                          \
   const uint8_t *__restrict__ codes, const int32_t *__restrict__ lut,                             \
       const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ thr,                      \
       uint32_t *__restrict__ seg_meta, uint32_t *__restrict__ cand, int B, int Hq, int Hkv, int NG,  \
-      int P0, int n_chunks, int problems, int rows_per_chunk, int row_cap, int ctx_len,            \
+      int P0, int n_chunks, int problems, int rows_per_chunk, int subs, int sub_rows, int row_cap,  \
+      int ctx_len,                                                                                 \
       int64_t ctx_stride, int top_k, int window, int n_sink
 #define A2ATS_STREAM_PASS                                                                          \
   codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, P0, n_chunks, problems,               \
-      rows_per_chunk, row_cap, ctx_len, ctx_stride, top_k, window, n_sink
+      rows_per_chunk, subs, sub_rows, row_cap, ctx_len, ctx_stride, top_k, window, n_sink
 
 // 64 KB of LDS per workgroup.  M = 16: 128 VGPRs -> 4 waves per SIMD (two workgroups per CU).
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void stream_select_kernel16(A2ATS_STREAM_ARGS) { stream_select_body<16>(A2ATS_STREAM_PASS); }
+void stream_select_kernel16(A2ATS_STREAM_ARGS) { stream_select_body<16, false>(A2ATS_STREAM_PASS); }
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void stream_select_kernel16r(A2ATS_STREAM_ARGS) { stream_select_body<16, true>(A2ATS_STREAM_PASS); }
 // M = 32: twice the row registers.
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
-void stream_select_kernel32(A2ATS_STREAM_ARGS) { stream_select_body<32>(A2ATS_STREAM_PASS); }
+void stream_select_kernel32(A2ATS_STREAM_ARGS) { stream_select_body<32, false>(A2ATS_STREAM_PASS); }
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
+void stream_select_kernel32r(A2ATS_STREAM_ARGS) { stream_select_body<32, true>(A2ATS_STREAM_PASS); }
 
 // ------------------------------------------------------------------------------------------
 // Fast route, stage 3: exact scores of the survivors, exact selection, ordered output
@@ -752,7 +805,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
 
   // one workgroup per (problem, head slot), on the XCD that streamed the problem
   int prob, r;
-  xcd_map(blockIdx.x, kHeadsPerGroup, problems, prob, r);
+  xcd_map_sets(blockIdx.x, kHeadsPerGroup, problems, NG, prob, r);
   const int G = Hq / Hkv;
   const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
   const int hg = g4 * kHeadsPerGroup + r;
@@ -1006,7 +1059,7 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
   hipLaunchKernelGGL(sum_segments_kernel, dim3((heads + 255) / 256), dim3(256), 0, stream,
                      (const uint32_t*)((const unsigned char*)ws + plan.off_count),
                      (const uint32_t*)((const unsigned char*)ws + plan.off_route), cand_counts, d.batch,
-                     d.n_q_heads, d.n_kv_heads, plan.NG, plan.chunks * kStreamWaves);
+                     d.n_q_heads, d.n_kv_heads, plan.NG, plan.chunks * kStreamWaves * plan.subs);
   return hipGetLastError();
 }
 
@@ -1021,7 +1074,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   const size_t coarse_bytes = (size_t)kCoarseLdsBytes;
   const size_t lut1_bytes = kExactLdsBytes;
   hipError_t err;
-  static LdsSlot s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_final[16];
+  static LdsSlot s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_stream_r[16], s_final[16];
   if (heads == 0) return hipSuccess;
 
   if (scores_out) {
@@ -1053,19 +1106,20 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
                      problems, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
-  auto stream_kernel = M == 16 ? stream_select_kernel16 : stream_select_kernel32;
-  if ((err = allow_dynamic_lds(stream_kernel, coarse_bytes, s_stream)) != hipSuccess) return err;
+  auto stream_kernel = M == 16 ? (NG > 1 ? stream_select_kernel16r : stream_select_kernel16)
+                               : (NG > 1 ? stream_select_kernel32r : stream_select_kernel32);
+  if ((err = allow_dynamic_lds(stream_kernel, coarse_bytes, NG > 1 ? s_stream_r : s_stream)) != hipSuccess) return err;
   if (g_ev_start && g_ev_stop) {
     // events attached to the dispatch itself: their difference is the kernel's own duration
     hipExtLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
                           stream, g_ev_start, g_ev_stop, 0, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq,
-                          Hkv, NG, plan.P0, plan.chunks, problems, plan.rows_per_chunk, plan.row_cap,
-                          d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                          Hkv, NG, plan.P0, plan.chunks, problems, plan.rows_per_chunk, plan.subs, plan.sub_rows,
+                          plan.row_cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   } else {
     hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
                        stream, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, plan.P0,
-                       plan.chunks, problems, plan.rows_per_chunk, plan.row_cap, d.ctx_len, d.ctx_stride,
-                       top_k, window, n_sink);
+                       plan.chunks, problems, plan.rows_per_chunk, plan.subs, plan.sub_rows, plan.row_cap,
+                       d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   }
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
@@ -1073,8 +1127,8 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   if ((err = allow_dynamic_lds(final_select_kernel<M>, final_lds, s_final)) != hipSuccess) return err;
   hipLaunchKernelGGL((final_select_kernel<M>), dim3(problems * kHeadsPerGroup), dim3(kExactThreads),
                      final_lds, stream, codes, lut, lut_scale, seq_lens, thr, seg_meta, cand, route, topk_idx,
-                     topk_count, topk_score, B, Hq, Hkv, NG, plan.P0, problems, plan.chunks * kStreamWaves,
-                     plan.row_cap, plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                     topk_count, topk_score, B, Hq, Hkv, NG, plan.P0, problems,
+                     plan.chunks * kStreamWaves * plan.subs, plan.row_cap, plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   return hipGetLastError();
 }
 
