@@ -316,7 +316,7 @@ __device__ __forceinline__ void combine_thresholds(int32_t v, int n_valid, int P
   }
 }
 
-// Survivor entries.  The streaming pass writes, per (problem, chunk, wave) segment, row_cap
+// Survivor entries.  The streaming pass writes, per segment (a run of rows of one wave), row_cap
 // 8-byte headers followed by row_cap rows of code bytes.  A header packs the token position (20
 // bits: contexts are at most 2^20 tokens), the mask of the heads that want the row (4 bits) and,
 // for each head, the row's rank among the rows of its segment that the head wants (10 bits each:
@@ -622,7 +622,7 @@ __device__ __forceinline__ void stream_select_body(
   const long begin = (long)sr.sink_end + (long)chunk * rows_per_chunk;
   const int end = (int)min((long)sr.win_start, begin + rows_per_chunk);
   // A wave owns a contiguous run of rows, so its survivors come out in ascending position and
-  // the segments of a problem, taken in (chunk, wave) order, are sorted by position.
+  // the segments of a problem, taken in (chunk, wave, run) order, are sorted by position.
   const int rows_per_wave = rows_per_chunk / kStreamWaves;
   const long wbegin = begin + (long)wv * rows_per_wave;
   const int wend = (int)min((long)end, wbegin + rows_per_wave);
@@ -859,7 +859,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     s_kth = 0;
   }
   __syncthreads();
-  // Survivor segments of this head's problem (one per chunk and wave of the streaming pass,
+  // Survivor segments of this head's problem (one per chunk, wave and run of the streaming pass,
   // sorted by position when taken in order): exclusive prefix of the number of rows this head
   // wants in each.  n_seg <= 512 <= NT.
   __shared__ uint16_t s_seg_rows[512];
@@ -1039,6 +1039,11 @@ void set_profile_events(void* a, void* b) {
   g_ev_stop = (hipEvent_t)b;
 }
 
+__global__ void fill_words_kernel(uint32_t* __restrict__ out, uint32_t value, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = value;
+}
+
 __global__ void sum_segments_kernel(const uint32_t* __restrict__ seg_meta, const uint32_t* __restrict__ route,
                                     uint32_t* __restrict__ out, int B, int Hq, int Hkv, int NG, int n_seg) {
   const int bh = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1055,7 +1060,11 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
   const TopkPlan plan = make_topk_plan(d, top_k, window, n_sink);
   const int heads = d.batch * d.n_q_heads;
   if (heads == 0) return hipSuccess;
-  if (!plan.fast) return hipMemsetAsync(cand_counts, 0xff, (size_t)heads * sizeof(uint32_t), stream);
+  if (!plan.fast) {   // (a fill kernel, not a memset node: the call may be captured into a graph)
+    hipLaunchKernelGGL(fill_words_kernel, dim3((heads + 255) / 256), dim3(256), 0, stream, cand_counts, 0xffffffffu,
+                       heads);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(sum_segments_kernel, dim3((heads + 255) / 256), dim3(256), 0, stream,
                      (const uint32_t*)((const unsigned char*)ws + plan.off_count),
                      (const uint32_t*)((const unsigned char*)ws + plan.off_route), cand_counts, d.batch,
