@@ -234,6 +234,25 @@ def _full_size_check(oracle, wl, sample, plant=False, n_sink=0):
     return st, tot_exc
 
 
+def test_ragged_batch_with_several_segments_per_wave(oracle):
+    """A batch large enough that a wave of the streaming pass owns several survivor segments (the
+    configuration-3 shape: two runs per wave), with sequences that end inside a run, inside the first
+    run, below the streaming route's minimum, and at zero length."""
+    wl = synth.Workload("ragged_runs", 16, 32, 8, 128, 16, 32768, 1024, 128, n_sink=4, seed=29)
+    lens = [32768, 0, 100, 16384 + 77, 20000, 32768, 5000, 24577, 32767, 17000, 31000, 28673, 19999, 32768, 16600, 300]
+    H.log(f"{wl.name}: generating inputs on the GPU")
+    xd = synth.make_decode_inputs(wl, device="cuda")
+    st = H.gpu_decode(wl, xd, seq_lens=lens, want_scores=True)
+    cnt = st.topk_count.cpu().numpy()
+    for b, n in enumerate(lens):
+        assert (cnt[b] == min(wl.top_k, max(0, n - wl.window - min(4, max(0, n - wl.window))))).all(), (b, n)
+    for (b, kv) in [(0, 0), (3, 5), (4, 2), (7, 7), (8, 1), (2, 3), (6, 4)]:
+        H.log(f"{wl.name}: oracle on problem (b={b}, kv={kv}, n={lens[b]})")
+        sub, x = H.slice_problem(wl, xd, b, kv)
+        res = H.check_step_against_oracle(oracle, wl, st, x, b_sel=b, kv_sel=kv, seq_lens=lens)
+        H.log(f"  {res}")
+
+
 def _plant_similar_keys(oracle, wl, xd):
     """Give 1 % of the candidate tokens of every (sequence, KV head) a key pulled towards the rotated
     query of the group's first head, and re-encode those keys (nearest centroid), so that the top-K
