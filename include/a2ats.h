@@ -334,6 +334,17 @@ int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window
                            const void* ws, uint32_t* cand_counts, void* stream);
 
 /*
+ * Diagnostics (not part of the method; host only, no GPU needed): how a2ats_score_topk would lay out
+ * its work for these dims / top_k / window / n_sink.  Writes 10 numbers to plan [host, out, int32 10]:
+ * [0] 1 if the sampled-threshold + streaming route is used (0: the exact route alone, the rest is 0),
+ * [1] groups of four query heads per KV head, [2] sampling workgroups per (sequence, KV head, group),
+ * [3] rows each of them scores, [4] streaming workgroups (chunks) per problem, [5] rows per chunk,
+ * [6] survivor segments per wave of a chunk, [7] rows per segment, [8] entries a segment can hold,
+ * [9] survivors per head the final kernel can hold.
+ */
+int a2ats_score_topk_plan(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink, int32_t* plan);
+
+/*
  * Profiling aid (not part of the method): when both events are non-NULL, the next
  * a2ats_score_topk calls attach ev_start / ev_stop (hipEvent_t passed as void*) to the
  * dispatch of the code-streaming kernel on their stream, so that the elapsed time between

@@ -21,7 +21,7 @@ W_PREPARED = 0x100
 OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN, OP_FIT, OP_SEED = 0, 1, 2, 3, 4, 5
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes", "a2ats_encode_prepare",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
-           "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_profile_stream_kernel",
+           "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_profile_stream_kernel",
            "a2ats_decode_prologue", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
            "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged"]
 
@@ -87,6 +87,8 @@ def lib() -> ctypes.CDLL:
         L.a2ats_second_moment.argtypes = [dp, vp, ctypes.c_int64, vp, vp, sz, vp]
         L.a2ats_codebook_update.restype = ctypes.c_int
         L.a2ats_codebook_update.argtypes = [dp, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.a2ats_score_topk_plan.restype = ctypes.c_int
+        L.a2ats_score_topk_plan.argtypes = [dp, i32, i32, i32, ctypes.POINTER(ctypes.c_int32)]
         L.a2ats_score_topk_stats.restype = ctypes.c_int
         L.a2ats_score_topk_stats.argtypes = [dp, i32, i32, i32, vp, vp, vp]
         L.a2ats_profile_stream_kernel.restype = None
@@ -267,6 +269,17 @@ def sparse_attn_paged(dims: Dims, q, q_rot, k_pool, v_pool, page_table, page_siz
                                        _ptr(topk_count), top_k, window, n_sink, _ptr(cos_win), _ptr(sin_win),
                                        _ptr(seq_lens), _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_sparse_attn_paged")
+
+
+PLAN_FIELDS = ("fast", "head_groups", "sample_parts", "sample_rows", "chunks", "rows_per_chunk",
+               "segments_per_wave", "rows_per_segment", "segment_capacity", "survivor_capacity")
+
+
+def score_topk_plan(dims: Dims, top_k: int, window: int, n_sink: int) -> dict:
+    """How a2ats_score_topk lays out its work for this shape (host only; no GPU needed)."""
+    out = (ctypes.c_int32 * 10)()
+    _check(lib().a2ats_score_topk_plan(ctypes.byref(dims), top_k, window, n_sink, out), "a2ats_score_topk_plan")
+    return dict(zip(PLAN_FIELDS, (int(v) for v in out)))
 
 
 def score_topk_stats(dims: Dims, top_k: int, window: int, n_sink: int, ws, cand_counts):

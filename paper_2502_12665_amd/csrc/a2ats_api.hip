@@ -334,6 +334,17 @@ int a2ats_score_topk_stats(const a2ats_dims* d, int32_t top_k, int32_t window, i
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
+int a2ats_score_topk_plan(const a2ats_dims* d, int32_t top_k, int32_t window, int32_t n_sink, int32_t* out) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (top_k < 0 || window < 0 || n_sink < 0 || !out) return A2ATS_ERR_INVALID_ARG;
+  const a2ats::TopkPlan p = a2ats::make_topk_plan(*d, top_k, window, n_sink);
+  const int32_t v[10] = {p.fast ? 1 : 0, p.NG, p.P0, p.sample_rows, p.chunks, p.rows_per_chunk,
+                         p.subs, p.sub_rows, p.row_cap, p.cap};
+  for (int i = 0; i < 10; ++i) out[i] = p.fast || i == 0 ? v[i] : 0;
+  return A2ATS_OK;
+}
+
 void a2ats_profile_stream_kernel(void* ev_start, void* ev_stop) { a2ats::set_profile_events(ev_start, ev_stop); }
 
 }  // extern "C"

@@ -1,6 +1,7 @@
 """Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
 plans workspaces, builds rotation tables, and rejects bad arguments before touching a GPU."""
 import ctypes
+import itertools
 import math
 import os
 import re
@@ -83,6 +84,45 @@ def test_dims_validation_and_plans(binding):
     assert rc == -3                                                     # split attention needs a workspace
     with pytest.raises(binding.A2atsError):
         binding.workspace_bytes(bad, binding.OP_LUT)
+
+
+def test_score_topk_plan_invariants(binding):
+    """Host logic of a2ats_score_topk over a grid of shapes: whatever the batch, context, K and window,
+    the plan must cover every candidate row exactly once with chunks of whole loop iterations, keep
+    every survivor segment within what the 10-bit ranks address, keep the segments of a problem within
+    what the final kernel handles (512), and ask for a workspace that holds them."""
+    n_fast = n_runs = 0
+    for Bn, (Hq, Hkv, M), N, K, w, n_sink in itertools.product(
+            (1, 2, 4, 16, 32, 64), ((4, 1, 16), (32, 8, 16), (28, 4, 32), (8, 8, 16), (64, 8, 32)),
+            (4096, 16384 + 300, 32768, 65536, 131072, 500000, 1 << 20), (1, 64, 1024, 2048, 4096), (16, 256), (0, 4)):
+        d = binding.make_dims(Bn, Hq, Hkv, 128, M, N)
+        p = binding.score_topk_plan(d, K, w, n_sink)
+        ncand = max(0, N - w - n_sink)
+        ws = binding.workspace_bytes(d, binding.OP_SCORE_TOPK, K, w)
+        if not p["fast"]:
+            assert ws == 0 or ncand < 16384 or K > 2048 or 4 * K > ncand or K < 1, (Bn, Hq, N, K, p)
+            continue
+        n_fast += 1
+        G = Hq // Hkv
+        assert ncand >= 16384 and 1 <= K <= 2048 and 4 * K <= ncand
+        assert p["head_groups"] == (G + 3) // 4
+        assert 1 <= p["sample_parts"] <= 8 and p["sample_rows"] <= 8192
+        assert p["sample_parts"] * p["sample_rows"] <= ncand
+        rpc, chunks, subs, sub_rows = p["rows_per_chunk"], p["chunks"], p["segments_per_wave"], p["rows_per_segment"]
+        assert rpc % 512 == 0 and 1 <= chunks <= 64
+        assert chunks * rpc >= ncand > (chunks - 1) * rpc                  # every row in exactly one chunk, none empty
+        assert subs >= 1 and subs * sub_rows == rpc // 8                   # a wave's rows = its runs
+        if subs > 1:
+            n_runs += 1
+            assert sub_rows % 512 == 0                                     # runs are whole loop iterations
+        assert chunks * 8 * subs <= 512                                    # segments per problem
+        cap = p["segment_capacity"]
+        assert 64 <= cap <= 1024 and cap % 32 == 0 and cap <= sub_rows
+        assert p["survivor_capacity"] >= 2 * K
+        problems = Bn * Hkv * p["head_groups"]
+        segs = problems * chunks * 8 * subs
+        assert ws >= segs * (cap * (8 + M) + 32) + Bn * Hq * (4 * p["sample_parts"] + 4)
+    assert n_fast > 500 and n_runs > 20
 
 
 def test_validation_of_the_single_codebook_and_construction_calls(binding):
