@@ -177,15 +177,17 @@ int a2ats_build_lut(const a2ats_dims* dims, const void* q, int q_dtype, const fl
  * current token's key: paper section 4.3, the GPU "assigns codewords to key states" each step) and
  * a2ats_build_lut in one launch.  The two do not depend on each other: the appended code rows are
  * at positions pos0 .. pos0 + n_new - 1.  Arguments, layouts and results are exactly those of the
- * two calls; needs no workspace; n_new > 32 returns A2ATS_ERR_UNSUPPORTED, n_new == 0 builds the
- * tables only (keys / codes may then be NULL).  Single codebook: A2ATS_ERR_UNSUPPORTED (its
- * encoder needs a workspace; call a2ats_encode_keys and a2ats_build_lut).
+ * two calls; n_new > 32 returns A2ATS_ERR_UNSUPPORTED, n_new == 0 builds the tables only (keys /
+ * codes may then be NULL).  Product quantisation needs no workspace (ws may be NULL).
+ * Single codebook: at most 8 keys per sequence and KV head; two launches (the float64 sweep of
+ * a2ats_encode_keys' few-key route, then the table build, which also picks the codes); `ws` as for
+ * a2ats_encode_keys, and weight_mode may carry A2ATS_W_PREPARED in the same way.
  */
 int a2ats_decode_prologue(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
                           const float* codebook, const float* weights, int weight_mode,
                           uint8_t* codes, const void* q, int q_dtype, const float* cos_b,
                           const float* sin_b, float* q_rot, int32_t* lut, float* lut_scale,
-                          void* stream);
+                          void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Step 3 of a decode step: approximate scores for every cached token by gather-summing

@@ -68,7 +68,7 @@ def lib() -> ctypes.CDLL:
         L.a2ats_build_lut.argtypes = [dp, vp, ctypes.c_int, vp, vp, vp, vp, vp, vp, vp]
         L.a2ats_decode_prologue.restype = ctypes.c_int
         L.a2ats_decode_prologue.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp,
-                                            vp, vp, vp, vp, vp]
+                                            vp, vp, vp, vp, vp, sz, vp]
         L.a2ats_score_topk.restype = ctypes.c_int
         L.a2ats_score_topk.argtypes = [dp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.a2ats_sparse_attn.restype = ctypes.c_int
@@ -196,12 +196,12 @@ def build_lut(dims: Dims, q, cos_b, sin_b, codebook, q_rot, lut, lut_scale):
 
 
 def decode_prologue(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, weight_mode: int, codes,
-                    q, cos_b, sin_b, q_rot, lut, lut_scale):
-    """encode_keys (n_new <= 32) and build_lut in one launch."""
+                    q, cos_b, sin_b, q_rot, lut, lut_scale, ws: Optional[torch.Tensor] = None):
+    """encode_keys (the decode-time append of a few keys) and build_lut fused; `ws` for the single codebook."""
     rc = lib().a2ats_decode_prologue(ctypes.byref(dims), _ptr(keys), n_new, pos0, _ptr(codebook),
                                      _ptr(weights), weight_mode, _ptr(codes), _ptr(q), _dtype_code(q),
                                      _ptr(cos_b), _ptr(sin_b), _ptr(q_rot), _ptr(lut), _ptr(lut_scale),
-                                     _stream())
+                                     _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_decode_prologue")
 
 

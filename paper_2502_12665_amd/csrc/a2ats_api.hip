@@ -193,6 +193,7 @@ int a2ats_build_lut(const a2ats_dims* d, const void* q, int q_dtype, const float
   const hipError_t e =
       a2ats::single_codebook(*d)
           ? a2ats::launch_build_lut_single(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale, false,
+                                           a2ats::FewKeyPick{nullptr, nullptr, 0, 0},
                                            (hipStream_t)stream)
           : a2ats::launch_build_lut(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
                                     (hipStream_t)stream);
@@ -210,6 +211,7 @@ int a2ats_build_lut_shared(const a2ats_dims* d, const void* q, int q_dtype, cons
   const hipError_t e =
       a2ats::single_codebook(*d)
           ? a2ats::launch_build_lut_single(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale, true,
+                                           a2ats::FewKeyPick{nullptr, nullptr, 0, 0},
                                            (hipStream_t)stream)
           : a2ats::launch_build_lut_shared(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
                                            (hipStream_t)stream);
@@ -219,10 +221,12 @@ int a2ats_build_lut_shared(const a2ats_dims* d, const void* q, int q_dtype, cons
 int a2ats_decode_prologue(const a2ats_dims* d, const float* keys, int32_t n_new, int32_t pos0,
                           const float* codebook, const float* weights, int weight_mode, uint8_t* codes,
                           const void* q, int q_dtype, const float* cos_b, const float* sin_b, float* q_rot,
-                          int32_t* lut, float* lut_scale, void* stream) {
+                          int32_t* lut, float* lut_scale, void* ws, size_t ws_bytes, void* stream) {
   int rc = check_dims(d);
   if (rc != A2ATS_OK) return rc;
   if (n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride) return A2ATS_ERR_INVALID_ARG;
+  const bool prepared = (weight_mode & A2ATS_W_PREPARED) != 0;
+  weight_mode &= ~A2ATS_W_PREPARED;
   if (weight_mode != A2ATS_W_NONE && weight_mode != A2ATS_W_DIAG && weight_mode != A2ATS_W_BLOCK)
     return A2ATS_ERR_INVALID_ARG;
   if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
@@ -232,7 +236,20 @@ int a2ats_decode_prologue(const a2ats_dims* d, const float* keys, int32_t n_new,
   if (misaligned16(codebook) || misaligned16(lut) || (n_new > 0 && misaligned16(keys)))
     return A2ATS_ERR_INVALID_ARG;
   if (n_new > 32) return A2ATS_ERR_UNSUPPORTED;   // prefill-sized batches go through a2ats_encode_keys
-  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
+  if (a2ats::single_codebook(*d)) {
+    // the float64 sweep for the appended keys, then the table build, which also picks their codes
+    if (n_new > a2ats::kFewSingleKeys) return A2ATS_ERR_UNSUPPORTED;
+    a2ats::FewKeyPick pick{nullptr, (uint16_t*)codes, n_new, pos0};
+    if (n_new > 0 && d->batch > 0) {
+      if (!ws || misaligned16(ws) || ws_bytes < a2ats::encode_single_ws_bytes(*d)) return A2ATS_ERR_WORKSPACE;
+      if (a2ats::launch_encode_single_sweep(*d, keys, n_new, codebook, weights, weight_mode, prepared, ws,
+                                            &pick.part, (hipStream_t)stream) != hipSuccess)
+        return A2ATS_ERR_HIP;
+    }
+    const hipError_t e = a2ats::launch_build_lut_single(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut,
+                                                        lut_scale, false, pick, (hipStream_t)stream);
+    return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+  }
   const hipError_t e = a2ats::launch_decode_prologue(*d, keys, n_new, pos0, codebook, weights, weight_mode,
                                                      codes, q, q_dtype, cos_b, sin_b, q_rot, lut, lut_scale,
                                                      (hipStream_t)stream);

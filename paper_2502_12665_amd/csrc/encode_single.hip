@@ -47,8 +47,8 @@ constexpr int kKeysPerWG = kKeysPerWave * kEncWaves;
 constexpr int kFragBytes = 2 * 8 * 64 * 16;   // (hi, lo) x 8 k-steps x 64 lanes x 16 bytes: 32 rows of 128 dims
 constexpr int kBlocks = kCW / 32;       // streamed 32-codeword blocks
 static_assert(kFragBytes / 16 / kEncThreads == 4, "a thread stages four 16-byte pieces of a block");
-constexpr int kFewSingle = 8;           // at most this many keys per (sequence, KV head): float64 sweep only
-constexpr int kSlices = 16;             // workgroups sharing the codewords of one such key
+constexpr int kFewSingle = kFewSingleKeys;   // at most this many keys per (sequence, KV head): float64 sweep only
+constexpr int kSlices = kEncodeSlices;  // workgroups sharing the codewords of one such key
 constexpr float kReach = 1.5e-5f;       // rounding reach of a score, relative to |z| max|c^z|
 constexpr int kChunk = 16384;           // keys per (sequence, KV head) transformed at a time
 
@@ -871,6 +871,23 @@ hipError_t launch_encode_single_prepare(const a2ats_dims& d, const float* codebo
                      mode, Lmat, sd, heff, (double*)(base + w.off_czT), (double*)(base + w.off_wT),
                      (double*)(base + w.off_chalf), (uint16_t*)(base + w.off_cfrag), (float*)(base + w.off_cbias),
                      cstat);
+  return hipGetLastError();
+}
+
+hipError_t launch_encode_single_sweep(const a2ats_dims& d, const float* keys, int n_new, const float* codebook,
+                                      const float* weights, int mode, bool prepared, void* ws,
+                                      const double** part_out, hipStream_t stream) {
+  const EncWs w = enc_single_ws(d);
+  uint8_t* base = (uint8_t*)ws;
+  double* part = (double*)(base + w.off_part);
+  *part_out = part;
+  hipError_t err;
+  if (!prepared && (err = launch_encode_single_prepare(d, codebook, weights, mode, ws, stream)) != hipSuccess)
+    return err;
+  const uint32_t n_all = (uint32_t)((size_t)d.batch * d.n_kv_heads * n_new);
+  hipLaunchKernelGGL(encode_single_sweep_kernel, dim3(n_all, kSlices), dim3(kSweepThreads), 0, stream, keys,
+                     (const double*)(base + w.off_wT), (const double*)(base + w.off_chalf), part, d.n_kv_heads,
+                     n_new);
   return hipGetLastError();
 }
 

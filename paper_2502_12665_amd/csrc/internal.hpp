@@ -79,9 +79,24 @@ hipError_t launch_decode_prologue(const a2ats_dims& d, const float* keys, int n_
 inline bool single_codebook(const a2ats_dims& d) {
   return d.n_sub == 1 && d.sub_dim == 128 && d.n_centroids == 4096;
 }
+// The few-key route of the single-codebook encoder decides a key in two steps: kEncodeSlices
+// workgroups each find the best codeword of their slice ("sweep": part[key][slice] = {value, code}),
+// then the smallest of the slices is picked.  `pick` hands the second step to the table-build
+// kernel, which follows the sweep in the fused decode prologue.
+constexpr int kEncodeSlices = 16;
+constexpr int kFewSingleKeys = 8;   // at most this many keys per (sequence, KV head) take that route
+struct FewKeyPick {
+  const double* part;   // nullptr: nothing to pick
+  uint16_t* codes;
+  int n_new, pos0;
+};
 hipError_t launch_build_lut_single(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                                    const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
-                                   float* lut_scale, bool shared, hipStream_t stream);
+                                   float* lut_scale, bool shared, FewKeyPick pick, hipStream_t stream);
+// The sweep alone (n_new <= kFewSingleKeys); returns where its results are in *part.
+hipError_t launch_encode_single_sweep(const a2ats_dims& d, const float* keys, int n_new, const float* codebook,
+                                      const float* weights, int mode, bool prepared, void* ws,
+                                      const double** part, hipStream_t stream);
 hipError_t launch_score_topk_single(const a2ats_dims& d, const void* codes, const int32_t* lut, int top_k,
                                     int window, int n_sink, const int32_t* seq_lens, int32_t* topk_idx,
                                     int32_t* topk_count, float* topk_score, float* scores_out,

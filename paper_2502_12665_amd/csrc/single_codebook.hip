@@ -53,7 +53,7 @@ template <bool QBF16>
 __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
     const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
     const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
-    float* __restrict__ lut_scale, int Hq, int Hkv, int shared) {
+    float* __restrict__ lut_scale, int Hq, int Hkv, int shared, FewKeyPick pick, int64_t ctx_stride) {
   constexpr int HALF = kSD / 2;
   __shared__ __align__(16) float s_q[8][kSD];   // q~ of the (up to) 8 query heads of this KV head
   __shared__ int32_t s_out[8][kLutChunk];       // the chunk's table entries, written out in one coalesced pass
@@ -145,19 +145,35 @@ __global__ __launch_bounds__(kLutChunk) void build_lut_single_kernel(
   __syncthreads();
   for (int g = 0; g < Gt; ++g)
     lut[((size_t)b * Ht + kv * Gt + g) * kCodewords + chunk * kLutChunk + tid] = s_out[g][tid];
+  // Fused decode prologue: the launch before this one swept the codewords for the keys appended in
+  // this step; the first workgroup of a (sequence, KV head) picks the smallest of the slices for each
+  // of its keys (slices hold ascending codes: strict < keeps the lower code on equal values).
+  if (pick.part && chunk == 0 && tid < pick.n_new) {
+    const double* mine = pick.part + ((size_t)bkv * pick.n_new + tid) * kEncodeSlices * 2;
+    double best = mine[0];
+    int arg = (int)mine[1];
+    for (int sl = 1; sl < kEncodeSlices; ++sl) {
+      const double dv = mine[2 * sl];
+      if (dv < best) {
+        best = dv;
+        arg = (int)mine[2 * sl + 1];
+      }
+    }
+    pick.codes[(size_t)bkv * ctx_stride + pick.pos0 + tid] = (uint16_t)arg;
+  }
 }
 
 hipError_t launch_build_lut_single(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                                    const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
-                                   float* lut_scale, bool shared, hipStream_t stream) {
+                                   float* lut_scale, bool shared, FewKeyPick pick, hipStream_t stream) {
   const dim3 grid(kCodewords / kLutChunk, d.batch * d.n_kv_heads), block(kLutChunk);
   if (grid.y == 0) return hipSuccess;
   if (q_dtype == A2ATS_BF16)
     hipLaunchKernelGGL((build_lut_single_kernel<true>), grid, block, 0, stream, q, cos_b, sin_b, codebook,
-                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads, shared ? 1 : 0);
+                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads, shared ? 1 : 0, pick, d.ctx_stride);
   else
     hipLaunchKernelGGL((build_lut_single_kernel<false>), grid, block, 0, stream, q, cos_b, sin_b, codebook,
-                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads, shared ? 1 : 0);
+                       q_rot, lut, lut_scale, d.n_q_heads, d.n_kv_heads, shared ? 1 : 0, pick, d.ctx_stride);
   return hipGetLastError();
 }
 

@@ -150,8 +150,13 @@ def test_validation_of_the_single_codebook_and_construction_calls(binding):
     assert L.a2ats_encode_prepare(ctypes.byref(sc), one, null, 2, one, 1 << 40, null) == -1   # weights missing
     assert L.a2ats_encode_prepare(ctypes.byref(sc), one, one, 2, null, 0, null) == -3
     assert L.a2ats_encode_prepare(ctypes.byref(pq), one, one, 2, null, 0, null) == 0          # nothing to keep
-    assert L.a2ats_decode_prologue(ctypes.byref(sc), one, 1, 0, one, null, 0, one, one, 0, one, one, one, one,
-                                   one, null) == -2
+    # fused prologue: at most 8 appended keys, and the encoder's workspace
+    def prologue(d, n_new, ws, ws_bytes):
+        return L.a2ats_decode_prologue(ctypes.byref(d), one, n_new, 0, one, null, 0, one, one, 0, one, one, one, one,
+                                       one, ws, ws_bytes, null)
+    assert prologue(sc, 9, one, 1 << 40) == -2
+    assert prologue(sc, 1, null, 0) == -3 and prologue(sc, 1, one, 64) == -3
+    assert prologue(pq, 33, null, 0) == -2
     # shared selection
     assert L.a2ats_build_lut_shared(ctypes.byref(pq), one, 0, one, one, one, null, one, one, null) == -1
     assert L.a2ats_sparse_attn_shared(ctypes.byref(pq), one, one, one, one, 1, one, one, 64, 16, 0, one, one, null,

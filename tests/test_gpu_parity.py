@@ -358,6 +358,43 @@ def test_decode_prologue_equals_the_two_calls(name, n_new, mode):
     assert not torch.equal(res[0][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the rows were rewritten
 
 
+@pytest.mark.parametrize("mode,n_new", [("none", 1), ("diag", 3), ("block", 8)])
+def test_single_codebook_decode_prologue_equals_the_two_calls(mode, n_new):
+    """The fused prologue in the single-codebook geometry (the sweep of the few-key encoder, then the
+    table build that also picks the codes) writes bit for bit what the two calls write, with and
+    without a prepared workspace."""
+    wl = _single(f"single_prologue_{mode}", 3, 8, 2, 3000, 16, 16, seed=41)
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    hm = synth.make_query_second_moment(wl)
+    wmode = {"none": B.W_NONE, "diag": B.W_DIAG, "block": B.W_BLOCK}[mode]
+    weights = None if mode == "none" else hm["h_diag" if mode == "diag" else "h_block"].cuda()
+    keys = synth.make_encode_keys(wl, n_new, device="cuda", stress=True)
+    dims = H.dims_of(wl)
+    pos0 = wl.ctx_len - n_new
+    res = []
+    for how in ("two calls", "fused", "fused, prepared"):
+        st = B.DecodeState(dims, wl.top_k, wl.window, 0, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+        st.lut.fill_(-1)
+        codes = xd["codes"].clone()
+        ws = torch.empty(B.workspace_bytes(dims, B.OP_ENCODE), dtype=torch.uint8, device="cuda")
+        if how == "two calls":
+            B.encode_keys(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, ws)
+            B.build_lut(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, st.lut, st.lut_scale)
+        else:
+            flag = 0
+            if how == "fused, prepared":
+                B.encode_prepare(dims, xd["codebook"], weights, wmode, ws)
+                flag = B.W_PREPARED
+            B.decode_prologue(dims, keys, n_new, pos0, xd["codebook"], weights, wmode | flag, codes, xd["q"],
+                              st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale, ws)
+        torch.cuda.synchronize()
+        res.append((codes.cpu(), st.lut.cpu(), st.lut_scale.cpu(), st.q_rot.cpu()))
+    for other in res[1:]:
+        for a, b in zip(res[0], other):
+            assert torch.equal(a, b)
+    assert not torch.equal(res[0][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the rows were rewritten
+
+
 @pytest.mark.parametrize("top_k,expect_fast", [(2048, True), (4096, False)])
 def test_maximum_context_length_and_top_k(oracle, top_k, expect_fast):
     """The largest context the library accepts (2^20 tokens) with the largest K of the streaming
