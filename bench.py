@@ -432,6 +432,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays")
     ap.add_argument("--separate-prologue", action="store_true",
                     help="a2ats_encode_keys and a2ats_build_lut as two launches instead of a2ats_decode_prologue")
+    ap.add_argument("--two-calls", action="store_true",
+                    help="a2ats_decode_prologue and a2ats_score_topk as two calls instead of a2ats_decode_select")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run 3 plain float32 copies (out = in + 0) of this many MiB, so that a "
                          "rocprofv3 --pmc run of this command holds a kernel of known HBM traffic")
@@ -500,24 +502,34 @@ def main():
     phase_ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
 
     def step(i, timed, stats=False):
+        # The timed-for-`value` steps make two calls (a2ats_decode_select, a2ats_sparse_attn); the steps
+        # that carry events between the phases use a2ats_decode_prologue + a2ats_score_topk instead (same
+        # kernels except that the threshold sampling is a launch of its own), so that the phases can be
+        # told apart.
         x = reps[i % R]
+        fused = not (args.separate_prologue or args.two_calls or timed)
         if timed:
             phase_ev[i][0].record()
-        if args.separate_prologue:
-            B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
+        if fused:
+            B.decode_select(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], x["q"],
+                            st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale, K, w, wl.n_sink, None,
+                            st.topk_idx, st.topk_count, None, st.ws)
+        else:
+            if args.separate_prologue:
+                B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
+                if timed:
+                    phase_ev[i][1].record()
+                B.build_lut(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, st.lut, st.lut_scale)
+            else:   # the key encode and the table build in one launch
+                if timed:
+                    phase_ev[i][1].record()
+                B.decode_prologue(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"],
+                                  x["q"], st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale)
             if timed:
-                phase_ev[i][1].record()
-            B.build_lut(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, st.lut, st.lut_scale)
-        else:   # the key encode and the table build in one launch
-            if timed:
-                phase_ev[i][1].record()
-            B.decode_prologue(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"],
-                              x["q"], st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale)
-        if timed:
-            phase_ev[i][2].record()
-            B.profile_stream_kernel(*kev.pair(i))
-        B.score_topk(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx, st.topk_count,
-                     None, None, st.ws)
+                phase_ev[i][2].record()
+                B.profile_stream_kernel(*kev.pair(i))
+            B.score_topk(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx,
+                         st.topk_count, None, None, st.ws)
         if timed:
             phase_ev[i][3].record()
         elif stats:   # candidate-list sizes, read before the attention reuses the workspace
@@ -613,10 +625,14 @@ def main():
                    "kv_cache": "pinned host memory, read by the attention kernels over PCIe" if args.kv_on_host
                    else "HBM"},
         "us_per_decode_step": ms_per_step * 1e3,
-        "prologue": "encode_keys + build_lut" if args.separate_prologue else "decode_prologue (one launch)",
+        "calls_per_step": "encode_keys, build_lut, score_topk, sparse_attn" if args.separate_prologue else
+                          ("decode_prologue, score_topk, sparse_attn" if args.two_calls else
+                           "decode_select (prologue and threshold sampling in one launch, then the streaming and "
+                           "final kernels), sparse_attn"),
         "phase_us_median": ({"encode_1key": med(ph[0]), "wrope_lut": med(ph[1])} if args.separate_prologue else
                             {"encode_1key_and_wrope_lut": med(ph[1])}) |
-                           {"score_topk": med(ph[2]), "sparse_attn": med(ph[3])},
+                           {"score_topk": med(ph[2]), "sparse_attn": med(ph[3]),
+                            "note": "from steps made of decode_prologue + score_topk + sparse_attn with events between"},
         "score_topk_phase": {"scored_keys_per_s": rows / (med(ph[2]) * 1e-6),
                              "query_head_scores_per_s": Bn * Hq * N / (med(ph[2]) * 1e-6),
                              "algorithmic_bytes": phase_bytes,

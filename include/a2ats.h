@@ -190,6 +190,26 @@ int a2ats_decode_prologue(const a2ats_dims* dims, const float* keys, int32_t n_n
                           void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * a2ats_decode_prologue followed by a2ats_score_topk (without its debug output) as one call: steps
+ * 1-3 of a decode step plus the append of the current token's key (paper sections 4.1-4.3).  Where
+ * a2ats_score_topk takes its streaming route (product quantisation, at least 16384 candidates,
+ * 1 <= top_k <= 2048, 4 top_k <= candidates) the call needs one launch less than the two: the
+ * workgroups that sample the thresholds build their problem's tables themselves and keep the coarse
+ * copy in LDS.  Elsewhere it simply makes the two calls.  Arguments are the union of theirs; every
+ * output (codes, q_rot, lut, lut_scale, topk_*) is bit for bit what the two calls write.
+ * `ws`: a2ats_workspace_bytes(dims, A2ATS_OP_SCORE_TOPK, top_k, window) bytes for product
+ * quantisation (the prologue needs none there), a2ats_workspace_bytes(dims, A2ATS_OP_ENCODE, 0, 0)
+ * for the single codebook (its selection needs none).
+ */
+int a2ats_decode_select(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
+                        const float* codebook, const float* weights, int weight_mode, uint8_t* codes,
+                        const void* q, int q_dtype, const float* cos_b, const float* sin_b,
+                        float* q_rot, int32_t* lut, float* lut_scale, int32_t top_k, int32_t window,
+                        int32_t n_sink, const int32_t* seq_lens, int32_t* topk_idx,
+                        int32_t* topk_count, float* topk_score, void* ws, size_t ws_bytes,
+                        void* stream);
+
+/*
  * Step 3 of a decode step: approximate scores for every cached token by gather-summing
  * table entries through its codes, then exact top-K (paper section 4: "retrieves the
  * top-K tokens with the highest attention scores").  For sequence b with n tokens the

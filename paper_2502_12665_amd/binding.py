@@ -22,7 +22,7 @@ OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN, OP_FIT, OP_SEED = 0, 1, 2, 3, 4, 5
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes", "a2ats_encode_prepare",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_profile_stream_kernel",
-           "a2ats_decode_prologue", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
+           "a2ats_decode_prologue", "a2ats_decode_select", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
            "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged"]
 
 
@@ -69,6 +69,9 @@ def lib() -> ctypes.CDLL:
         L.a2ats_decode_prologue.restype = ctypes.c_int
         L.a2ats_decode_prologue.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp,
                                             vp, vp, vp, vp, vp, sz, vp]
+        L.a2ats_decode_select.restype = ctypes.c_int
+        L.a2ats_decode_select.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, vp,
+                                          vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.a2ats_score_topk.restype = ctypes.c_int
         L.a2ats_score_topk.argtypes = [dp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.a2ats_sparse_attn.restype = ctypes.c_int
@@ -203,6 +206,18 @@ def decode_prologue(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, 
                                      _ptr(cos_b), _ptr(sin_b), _ptr(q_rot), _ptr(lut), _ptr(lut_scale),
                                      _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_decode_prologue")
+
+
+def decode_select(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, weight_mode: int, codes,
+                  q, cos_b, sin_b, q_rot, lut, lut_scale, top_k: int, window: int, n_sink: int, seq_lens,
+                  topk_idx, topk_count, topk_score=None, ws: Optional[torch.Tensor] = None):
+    """decode_prologue + score_topk as one call (one launch less on the streaming route)."""
+    rc = lib().a2ats_decode_select(ctypes.byref(dims), _ptr(keys), n_new, pos0, _ptr(codebook), _ptr(weights),
+                                   weight_mode, _ptr(codes), _ptr(q), _dtype_code(q), _ptr(cos_b), _ptr(sin_b),
+                                   _ptr(q_rot), _ptr(lut), _ptr(lut_scale), top_k, window, n_sink, _ptr(seq_lens),
+                                   _ptr(topk_idx), _ptr(topk_count), _ptr(topk_score), _ptr(ws),
+                                   0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_decode_select")
 
 
 def score_topk(dims: Dims, codes, lut, lut_scale, top_k: int, window: int, n_sink: int, seq_lens,

@@ -256,6 +256,47 @@ int a2ats_decode_prologue(const a2ats_dims* d, const float* keys, int32_t n_new,
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
+int a2ats_decode_select(const a2ats_dims* d, const float* keys, int32_t n_new, int32_t pos0,
+                        const float* codebook, const float* weights, int weight_mode, uint8_t* codes,
+                        const void* q, int q_dtype, const float* cos_b, const float* sin_b, float* q_rot,
+                        int32_t* lut, float* lut_scale, int32_t top_k, int32_t window, int32_t n_sink,
+                        const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count, float* topk_score,
+                        void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  const a2ats::TopkPlan plan = a2ats::make_topk_plan(*d, top_k < 0 ? 0 : top_k, window < 0 ? 0 : window,
+                                                     n_sink < 0 ? 0 : n_sink);
+  if (a2ats::single_codebook(*d) || !plan.fast) {   // nothing to fuse: the two calls, with their own checks
+    rc = a2ats_decode_prologue(d, keys, n_new, pos0, codebook, weights, weight_mode, codes, q, q_dtype, cos_b,
+                               sin_b, q_rot, lut, lut_scale, ws, ws_bytes, stream);
+    if (rc != A2ATS_OK) return rc;
+    return a2ats_score_topk(d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
+                            topk_score, nullptr, ws, ws_bytes, stream);
+  }
+  // the checks of a2ats_decode_prologue and a2ats_score_topk for the streaming route
+  if (n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride) return A2ATS_ERR_INVALID_ARG;
+  weight_mode &= ~A2ATS_W_PREPARED;
+  if (weight_mode != A2ATS_W_NONE && weight_mode != A2ATS_W_DIAG && weight_mode != A2ATS_W_BLOCK)
+    return A2ATS_ERR_INVALID_ARG;
+  if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
+  if (!codebook || !q || !cos_b || !sin_b || !q_rot || !lut || !lut_scale || !codes || !topk_idx || !topk_count)
+    return A2ATS_ERR_INVALID_ARG;
+  if (n_new > 0 && !keys) return A2ATS_ERR_INVALID_ARG;
+  if (weight_mode != A2ATS_W_NONE && !weights) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(codebook) || misaligned16(lut) || misaligned16(codes) || (n_new > 0 && misaligned16(keys)))
+    return A2ATS_ERR_INVALID_ARG;
+  if (n_new > 32) return A2ATS_ERR_UNSUPPORTED;
+  if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
+  hipError_t e = a2ats::launch_decode_select_prologue(
+      *d, keys, n_new, pos0, codebook, weights, weight_mode, codes, q, q_dtype, cos_b, sin_b, q_rot, lut, lut_scale,
+      seq_lens, (int32_t*)((unsigned char*)ws + plan.off_thr), plan.P0, plan.sample_rows, top_k, window, n_sink,
+      (hipStream_t)stream);
+  if (e != hipSuccess) return A2ATS_ERR_HIP;
+  e = a2ats::launch_score_topk(*d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
+                               topk_score, nullptr, ws, true, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
 int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut, const float* lut_scale,
                      int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
                      int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,
@@ -278,7 +319,7 @@ int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* l
     if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
   }
   const hipError_t e = a2ats::launch_score_topk(*d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
-                                                topk_idx, topk_count, topk_score, scores_out, ws,
+                                                topk_idx, topk_count, topk_score, scores_out, ws, false,
                                                 (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }

@@ -12,6 +12,7 @@
 #include "common.hpp"
 #include "internal.hpp"
 #include "encode_few.hpp"
+#include "coarse_score.hpp"
 
 namespace a2ats {
 
@@ -24,7 +25,11 @@ template <int DS, bool QBF16, bool SHARED = false>
 __device__ __forceinline__ void build_lut_body(
     int prob, const void* __restrict__ q_in, const float* __restrict__ cos_b,
     const float* __restrict__ sin_b, const float* __restrict__ codebook, float* __restrict__ q_rot,
-    int32_t* __restrict__ lut, float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG) {
+    int32_t* __restrict__ lut, float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG,
+    bool write_out = true, unsigned char* coarse_lds = nullptr) {
+  // write_out false: the tables are computed but nothing is written to global memory (another
+  // workgroup does that); coarse_lds: the group's coarse table is also put there, in the layout the
+  // scoring kernels read (one 256-byte row per centroid id).
   constexpr int D = 128, HALF = 64, M = D / DS;
   constexpr int ENTRIES = kCentroids * M;
   constexpr int EPT = ENTRIES / kLutThreads;
@@ -80,8 +85,10 @@ __device__ __forceinline__ void build_lut_body(
       const double c = (double)cos_b[t], s = (double)sin_b[t];
       o1 = (float)(x1 * c - x2 * s);
       o2 = (float)(x2 * c + x1 * s);
-      q_rot[base + t] = o1;
-      q_rot[base + t + HALF] = o2;
+      if (write_out) {
+        q_rot[base + t] = o1;
+        q_rot[base + t + HALF] = o2;
+      }
     }
     if (SHARED) {
       s_qall[r][t] = o1;
@@ -144,7 +151,7 @@ __device__ __forceinline__ void build_lut_body(
     }
     s_exp[tid] = e;
     const int hg = g4 * kHeadsPerGroup + tid;
-    if (hg < G) lut_scale[(size_t)b * Hq + kv * G + hg] = (float)ldexp(1.0, -e);
+    if (hg < G && write_out) lut_scale[(size_t)b * Hq + kv * G + hg] = (float)ldexp(1.0, -e);
   }
   __syncthreads();
 
@@ -183,7 +190,7 @@ __device__ __forceinline__ void build_lut_body(
     while ((range >> sh) > (uint32_t)MAXQ) ++sh;
     s_shift[r] = sh;
     const int hg = g4 * kHeadsPerGroup + r;
-    if (hg < G) {
+    if (hg < G && write_out) {
       int32_t* meta = lut + lay.off_meta + ((size_t)b * Hq + kv * G + hg) * 4;
       meta[0] = base;   // sum over subspaces of the smallest entry
       meta[1] = sh;     // coarse entry = (exact entry - subspace minimum) >> sh
@@ -195,7 +202,7 @@ __device__ __forceinline__ void build_lut_body(
 #pragma unroll
   for (int r = 0; r < kHeadsPerGroup; ++r) {
     const int hg = g4 * kHeadsPerGroup + r;
-    if (hg < G) {
+    if (hg < G && write_out) {
       int32_t* ex = lut + lay.off_exact + ((size_t)b * Hq + kv * G + hg) * ENTRIES;
 #pragma unroll
       for (int k = 0; k < EPT; ++k) ex[tid + k * kLutThreads] = iv[k][r];
@@ -213,7 +220,9 @@ __device__ __forceinline__ void build_lut_body(
       const int c = (tid + k * kLutThreads) / M;
       const uint32_t q0 = (uint32_t)(iv[k][0] - mn0) >> sh0, q1 = (uint32_t)(iv[k][1] - mn1) >> sh1;
       const uint32_t q2 = (uint32_t)(iv[k][2] - mn2) >> sh2, q3 = (uint32_t)(iv[k][3] - mn3) >> sh3;
-      coarse[(m >> 4) * (kCentroids * 16) + c * 16 + (m & 15)] = make_uint2(q0 | (q1 << 16), q2 | (q3 << 16));
+      const uint2 entry = make_uint2(q0 | (q1 << 16), q2 | (q3 << 16));
+      if (write_out) coarse[(m >> 4) * (kCentroids * 16) + c * 16 + (m & 15)] = entry;
+      if (coarse_lds) *(uint2*)(coarse_lds + (c << 8) + ((m >> 4) << 7) + ((m & 15) << 3)) = entry;
     }
   }
 }
@@ -257,6 +266,77 @@ __global__ __launch_bounds__(kLutThreads) void decode_prologue_kernel(
   const int m = (int)(pair % M), j = (int)((pair / M) % n_new), bkv = (int)(pair / ((long)M * n_new));
   encode_few_pair<DS>(keys, codebook, weights, mode, codes, Hkv, M, n_new, pos0, ctx_stride, m, j, bkv, c,
                       grp, pair < n_pairs, s_d, s_i);
+}
+
+// The decode prologue and the first launch of a2ats_score_topk's streaming route in one: every
+// sampling workgroup (P0 per problem) builds its problem's tables itself -- the arithmetic is a few
+// microseconds and identical in all of them -- keeps the coarse table in LDS and scores its share of
+// the sample against it; part 0 of a problem also writes the tables out for the launches that
+// follow.  The remaining workgroups encode the appended keys.  Saves one launch and the copy of the
+// table from global memory per step; every result is bit for bit that of the separate calls.
+template <int DS, bool QBF16>
+__global__ __launch_bounds__(kLutThreads) void decode_select_prologue_kernel(
+    const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
+    const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
+    float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG, int n_sample,
+    const float* __restrict__ keys, const float* __restrict__ weights, int mode,
+    uint8_t* __restrict__ codes, int n_new, int pos0, int64_t ctx_stride,
+    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int P0, int sample_rows, int ctx_len,
+    int top_k, int window, int n_sink) {
+  constexpr int M = 128 / DS;
+  extern __shared__ __align__(16) unsigned char dyn_lds[];
+  if ((int)blockIdx.x < n_sample) {
+    int prob, p;
+    xcd_map_sets(blockIdx.x, P0, n_sample / P0, NG, prob, p);
+    build_lut_body<DS, QBF16>(prob, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG, p == 0,
+                              dyn_lds);
+    __syncthreads();
+    sample_threshold_body<M, kLutThreads, true>(prob, p, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, P0, sample_rows,
+                                                ctx_len, ctx_stride, top_k, window, n_sink, dyn_lds);
+    return;
+  }
+  __shared__ double s_d[kLutThreads / 64];
+  __shared__ int s_i[kLutThreads / 64];
+  const int grp = threadIdx.x >> 8, c = threadIdx.x & 255;
+  const long pair = (long)(blockIdx.x - n_sample) * (kLutThreads / kCentroids) + grp;
+  const long n_pairs = (long)B * Hkv * n_new * M;
+  const int m = (int)(pair % M), j = (int)((pair / M) % n_new), bkv = (int)(pair / ((long)M * n_new));
+  encode_few_pair<DS>(keys, codebook, weights, mode, codes, Hkv, M, n_new, pos0, ctx_stride, m, j, bkv, c,
+                      grp, pair < n_pairs, s_d, s_i);
+}
+
+hipError_t launch_decode_select_prologue(const a2ats_dims& d, const float* keys, int n_new, int pos0,
+                                         const float* codebook, const float* weights, int mode, uint8_t* codes,
+                                         const void* q, int q_dtype, const float* cos_b, const float* sin_b,
+                                         float* q_rot, int32_t* lut, float* lut_scale, const int32_t* seq_lens,
+                                         int32_t* thr, int P0, int sample_rows, int top_k, int window, int n_sink,
+                                         hipStream_t stream) {
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const int NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
+  const int n_sample = d.batch * d.n_kv_heads * NG * P0;
+  const long n_pairs = (long)d.batch * d.n_kv_heads * n_new * d.n_sub;
+  const int per_wg = kLutThreads / kCentroids;
+  const dim3 grid(n_sample + (unsigned)((n_pairs + per_wg - 1) / per_wg)), block(kLutThreads);
+  if (grid.x == 0) return hipSuccess;
+  static LdsSlot s_lds[4][16];
+  hipError_t err;
+#define A2ATS_LAUNCH_SEL(DS, BF, SLOT)                                                                       \
+  do {                                                                                                       \
+    if ((err = allow_dynamic_lds(decode_select_prologue_kernel<DS, BF>, (size_t)kCoarseLdsBytes, s_lds[SLOT])) != \
+        hipSuccess)                                                                                          \
+      return err;                                                                                            \
+    hipLaunchKernelGGL((decode_select_prologue_kernel<DS, BF>), grid, block, kCoarseLdsBytes, stream, q, cos_b, \
+                       sin_b, codebook, q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG, n_sample, \
+                       keys, weights, mode, codes, n_new, pos0, d.ctx_stride, seq_lens, thr, P0, sample_rows,  \
+                       d.ctx_len, top_k, window, n_sink);                                                    \
+  } while (0)
+  if (d.sub_dim == 8) {
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_SEL(8, true, 0); else A2ATS_LAUNCH_SEL(8, false, 1);
+  } else {
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_SEL(4, true, 2); else A2ATS_LAUNCH_SEL(4, false, 3);
+  }
+#undef A2ATS_LAUNCH_SEL
+  return hipGetLastError();
 }
 
 hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,

@@ -34,6 +34,7 @@
 #include <cmath>
 #include "common.hpp"
 #include "internal.hpp"
+#include "coarse_score.hpp"
 
 namespace a2ats {
 
@@ -44,7 +45,6 @@ constexpr int kSampleThreads = 512;
 constexpr int kSegMeta = 8;          // words of a segment header: rows, 4 per-head counts, padding
 constexpr int kSampleRows = 1024;    // rows scored by one sampling workgroup
 constexpr int kSmallList = 1024;     // members of the K-th key's bin ranked by brute force
-constexpr float kSigma = 5.0f;
 
 TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) {
   TopkPlan p{};
@@ -217,74 +217,6 @@ __device__ __forceinline__ int32_t score_exact_row(const uint8_t* row, const uns
   return score_exact<M>(w, tbl, sw);
 }
 
-// Coarse scores of one token for the four heads of a group.  The coarse table sits in LDS with
-// one 256-byte row per centroid id c: the 8-byte entry (two 32-bit words, each holding two heads'
-// 16-bit values) of subspace m is at byte (c << 8) | ((m >> 4) << 7) | ((m & 15) << 3).  (For
-// M = 16 the upper half of each row is unused.)
-//
-// LDS serves an 8-byte read 16 lanes at a time; lanes collide when they touch the same banks.
-// With this layout the banks of a read depend only on m, not on the (random) code byte, so lane
-// L visits the subspaces of its row in the order m = t ^ (L & 15), t = 0..15 (per 16-byte half
-// row): the 16 lanes served together always touch 16 different entries of their rows, and
-// random codes cause no conflicts.  The visiting order does not change the result because the
-// scores are integer sums.  One v_perm_b32 assembles the whole LDS address of a read from the
-// code byte and a per-lane constant.
-constexpr int kCoarseLdsBytes = kCentroids * 256;
-
-template <int M>
-struct LaneSwizzle {
-  uint32_t mc[M / 4];   // byte t&3 of mc[t>>2]: low address byte for step t of this lane
-  uint32_t sel[4];      // v_perm selectors: address byte 1 <- code byte (k ^ b), byte 0 <- mc byte k
-  bool swap1, swap2;    // dword index of the row is XORed with (rho >> 2)
-  __device__ __forceinline__ void init(int lane) {
-    const uint32_t rho = lane & 15, b = rho & 3;
-#pragma unroll
-    for (int d = 0; d < M / 4; ++d) {
-      uint32_t v = 0;
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const uint32_t t = 4 * d + k;                       // step within the whole row
-        const uint32_t m_low = (t ^ rho) & 15u, half = t >> 4;
-        v |= ((half << 7) | (m_low << 3)) << (8 * k);
-      }
-      mc[d] = v;
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) sel[k] = 0x0c0c0000u | ((4u + ((uint32_t)k ^ b)) << 8) | (uint32_t)k;
-    swap1 = (rho >> 2) & 1;
-    swap2 = (rho >> 3) & 1;
-  }
-};
-
-typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
-typedef __attribute__((address_space(3))) const u32x2_t* lds_u2_ptr;
-
-// kBaseZero: the table starts at LDS address 0 (kernel without static LDS), so the v_perm result
-// is the address itself; otherwise it is an offset from `tbl`.
-template <int M, bool kBaseZero>
-__device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const unsigned char* tbl,
-                                             const LaneSwizzle<M>& sw, uint32_t& a01, uint32_t& a23) {
-  a01 = 0;
-  a23 = 0;
-#pragma unroll
-  for (int qd = 0; qd < M / 16; ++qd) {
-    // z[d] = row dword (d ^ (rho >> 2))
-    const uint4 wq = w[qd];
-    const uint32_t x0 = sw.swap1 ? wq.y : wq.x, x1 = sw.swap1 ? wq.x : wq.y;
-    const uint32_t x2 = sw.swap1 ? wq.w : wq.z, x3 = sw.swap1 ? wq.z : wq.w;
-    const uint32_t z[4] = {sw.swap2 ? x2 : x0, sw.swap2 ? x3 : x1, sw.swap2 ? x0 : x2, sw.swap2 ? x1 : x3};
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const uint32_t off = __builtin_amdgcn_perm(z[t >> 2], sw.mc[qd * 4 + (t >> 2)], sw.sel[t & 3]);
-      u32x2_t e;
-      if (kBaseZero) e = *(lds_u2_ptr)(uintptr_t)off;
-      else e = *(const u32x2_t*)(tbl + off);
-      a01 += e.x;
-      a23 += e.y;
-    }
-  }
-}
-
 // The P0 sampling workgroups of a problem each estimate a head's threshold from their share of the
 // sample; the streaming and final kernels use the mean of the estimates (rounded down), which is
 // close to what one rank search over the merged sample would give.  INT32_MIN ("take every row")
@@ -334,18 +266,6 @@ __device__ __forceinline__ bool entry_wanted(uint32_t w0, int r) { return (w0 >>
 __device__ __forceinline__ uint32_t entry_rank(uint32_t w0, uint32_t w1, int r) {
   if (r == 0) return (w0 >> 24) | ((w1 & 3u) << 8);
   return (w1 >> (10 * r - 8)) & 1023u;
-}
-
-// Copy a problem's coarse table from its global order [half][c][16 m] to the LDS layout above.
-template <int M, int NT>
-__device__ __forceinline__ void load_coarse_table(const int32_t* __restrict__ lut, const LutLayout& lay,
-                                                  int prob, unsigned char* tbl) {
-  const int4* src = (const int4*)(lut + lay.off_coarse + (size_t)prob * (kCentroids * M * 2));
-#pragma unroll 4
-  for (int e = threadIdx.x; e < kCentroids * M / 2; e += NT) {   // e: pair of entries (2 * e, 2 * e + 1)
-    const int half = e / (kCentroids * 8), c = (e / 8) % kCentroids, mp = e % 8;
-    *(int4*)(tbl + (c << 8) + (half << 7) + (mp << 4)) = src[e];
-  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -497,104 +417,11 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
     const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int B, int Hq, int Hkv, int NG,
     int P0, int sample_rows, int problems, int ctx_len, int64_t ctx_stride, int top_k, int window,
     int n_sink) {
-  constexpr int NT = kSampleThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
-  unsigned char* tbl = dyn_lds;
-  __shared__ uint32_t s_hist[2][kHistBins];   // two heads per word, 16-bit counts (a workgroup scores at most 8192 rows)
-
   int p, prob;
   xcd_map_sets(blockIdx.x, P0, problems, NG, prob, p);
-  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
-  const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-  const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
-
-  // sampling plan for this sequence
-  const int s_p = min(sample_rows, sr.ncand / P0);
-  const long s_all = (long)s_p * P0;
-  int r_p = 0;
-  bool take_all = sr.ncand <= top_k || s_p == 0;
-  if (!take_all) {
-    // rank r in the merged sample with r - sigma * sqrt(r) >= K * S / N, shared out over the P0 parts
-    const float r0 = (float)top_k * (float)s_all / (float)sr.ncand;
-    const float x = 0.5f * (kSigma + sqrtf(kSigma * kSigma + 4.f * r0));
-    r_p = (int)ceilf(x * x / (float)P0) + 1;
-    if (r_p > s_p) take_all = true;
-  }
-  if (take_all) {
-    if (tid < kHeadsPerGroup) {
-      const int hg = g4 * kHeadsPerGroup + tid;
-      if (hg < G) thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = INT32_MIN;
-    }
-    return;
-  }
-
-  const LutLayout lay = lut_layout(B, Hq, Hkv, M);
-  load_coarse_table<M, NT>(lut, lay, prob, tbl);
-  for (int i = tid; i < 2 * kHistBins; i += NT) (&s_hist[0][0])[i] = 0;
-  __syncthreads();
-
-  // Score this workgroup's share of the strided sample.  A coarse score is below 2^16, so
-  // score >> 5 indexes a 2048-bin histogram directly.
-  LaneSwizzle<M> sw;
-  sw.init(lane);
-  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
-  // The sample is taken in runs of kRun consecutive rows (one 128-byte line of the code matrix),
-  // the runs evenly spread over the candidates: HBM delivers whole lines, so a row-strided sample
-  // would fetch eight times the bytes it uses.  (For rows drawn independently, as in the synthetic
-  // workloads, this changes nothing statistically; if neighbouring tokens' scores are correlated
-  // the estimate is noisier, which costs at most a detour over the exact route.)
-  constexpr int kRun = 128 / M;
-  const long n_runs = (s_all + kRun - 1) / kRun;
-  for (int i = tid; i < s_p; i += NT) {
-    const long g = (long)p * s_p + i;
-    const long run = g / kRun;
-    int j = sr.sink_end + (int)((run * sr.ncand) / n_runs);
-    j = max(sr.sink_end, j & ~(kRun - 1)) + (int)(g % kRun);
-    j = min(j, sr.win_start - 1);
-    uint4 w[M / 16];
-#pragma unroll
-    for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
-    uint32_t a01, a23;
-    score_coarse<M, false>(w, tbl, sw, a01, a23);
-    atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);
-    atomicAdd(&s_hist[0][a01 >> 21], 1u << 16);
-    atomicAdd(&s_hist[1][(a23 & 0xffffu) >> 5], 1u);
-    atomicAdd(&s_hist[1][a23 >> 21], 1u << 16);
-  }
-  __syncthreads();
-  // Rank search, one wave per head: lane l owns bins [32 l, 32 l + 32); a suffix scan over the
-  // lanes finds the one whose range holds the r_p-th largest sample; the wave then searches that range.
-  if (wv < kHeadsPerGroup) {
-    const int r = wv;
-    const int hg = g4 * kHeadsPerGroup + r;
-    const uint32_t* hrow = s_hist[r >> 1];
-    const int fsh = 16 * (r & 1);
-    uint32_t sum = 0;
-#pragma unroll
-    for (int i = 0; i < 32; ++i) {
-      const int ii = (i + lane) & 31;   // rotate the walk so the lanes of a read hit different banks
-      sum += (hrow[32 * lane + ii] >> fsh) & 0xffffu;
-    }
-    // inclusive suffix sum over lanes (higher lanes hold higher bins) = total - exclusive prefix
-    const uint32_t pre = wave_inclusive_scan(sum);
-    const uint32_t inc = (uint32_t)__builtin_amdgcn_readlane((int)pre, 63) - pre + sum;
-    const uint32_t k = (uint32_t)r_p, above_lane = inc - sum;
-    const uint64_t owner = __ballot(above_lane < k && k <= inc);   // the lane whose 32 bins hold the rank
-    if (owner != 0 && hg < G) {
-      // Second level, by the whole wave: lane i < 32 takes bin 31 - i of the owner's range (so
-      // bins descend with the lane index) and a prefix sum finds the first lane that reaches k.
-      const int src = __ffsll((unsigned long long)owner) - 1;
-      const uint32_t above = (uint32_t)__builtin_amdgcn_readlane((int)above_lane, src);
-      const uint32_t c = lane < 32 ? (hrow[32 * src + 31 - lane] >> fsh) & 0xffffu : 0u;
-      const uint32_t incl = wave_inclusive_scan(c);   // lanes >= 32 hold zeros
-      const uint64_t reach = __ballot(lane < 32 && above + incl >= k);
-      const int bin = 32 * src + 31 - (__ffsll((unsigned long long)reach) - 1);
-      // Lower edge of the bin holding the r_p-th largest sample (at least r_p samples reach it),
-      // lowered by M: a row's coarse score is below its exact score by less than M coarse units,
-      // and the final kernel needs that much slack to prove its result complete.
-      if (lane == 0) thr[((size_t)b * Hq + kv * G + hg) * P0 + p] = max(0, (bin << 5) - M);
-    }
-  }
+  sample_threshold_body<M, kSampleThreads, false>(prob, p, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, P0, sample_rows,
+                                                  ctx_len, ctx_stride, top_k, window, n_sink, dyn_lds);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1077,7 +904,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
                                       const int32_t* lut, const float* lut_scale, int top_k, int window,
                                       int n_sink, const int32_t* seq_lens, int32_t* topk_idx,
                                       int32_t* topk_count, float* topk_score, float* scores_out,
-                                      void* ws, hipStream_t stream) {
+                                      void* ws, bool presampled, hipStream_t stream) {
   const int B = d.batch, Hq = d.n_q_heads, Hkv = d.n_kv_heads, NG = plan.NG;
   const int heads = B * Hq, problems = B * Hkv * NG;
   const size_t coarse_bytes = (size_t)kCoarseLdsBytes;
@@ -1109,11 +936,13 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   uint32_t* route = (uint32_t*)(wsb + plan.off_route);
   uint32_t* cand = (uint32_t*)(wsb + plan.off_cand);
 
-  if ((err = allow_dynamic_lds(sample_threshold_kernel<M>, coarse_bytes, s_sample)) != hipSuccess) return err;
-  hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0 * problems), dim3(kSampleThreads),
-                     coarse_bytes, stream, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, plan.P0, plan.sample_rows,
-                     problems, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
-  if ((err = hipGetLastError()) != hipSuccess) return err;
+  if (!presampled) {   // (the fused decode launch has written the thresholds already)
+    if ((err = allow_dynamic_lds(sample_threshold_kernel<M>, coarse_bytes, s_sample)) != hipSuccess) return err;
+    hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0 * problems), dim3(kSampleThreads),
+                       coarse_bytes, stream, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, plan.P0, plan.sample_rows,
+                       problems, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+    if ((err = hipGetLastError()) != hipSuccess) return err;
+  }
 
   auto stream_kernel = M == 16 ? (NG > 1 ? stream_select_kernel16r : stream_select_kernel16)
                                : (NG > 1 ? stream_select_kernel32r : stream_select_kernel32);
@@ -1144,13 +973,14 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
 hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const int32_t* lut,
                              const float* lut_scale, int top_k, int window, int n_sink,
                              const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
-                             float* topk_score, float* scores_out, void* ws, hipStream_t stream) {
+                             float* topk_score, float* scores_out, void* ws, bool presampled,
+                             hipStream_t stream) {
   const TopkPlan plan = make_topk_plan(d, top_k, window, n_sink);
   if (d.n_sub == 16)
     return launch_score_topk_m<16>(d, plan, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
-                                   topk_idx, topk_count, topk_score, scores_out, ws, stream);
+                                   topk_idx, topk_count, topk_score, scores_out, ws, presampled, stream);
   return launch_score_topk_m<32>(d, plan, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
-                                 topk_idx, topk_count, topk_score, scores_out, ws, stream);
+                                 topk_idx, topk_count, topk_score, scores_out, ws, presampled, stream);
 }
 
 }  // namespace a2ats

@@ -358,6 +358,55 @@ def test_decode_prologue_equals_the_two_calls(name, n_new, mode):
     assert not torch.equal(res[0][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the rows were rewritten
 
 
+@pytest.mark.parametrize("name,Bn,G,M,N,K,w,n_sink,n_new,mode,seq_lens", [
+    ("sel_m16_g4", 2, 4, 16, 40000, 600, 128, 0, 1, "diag", None),
+    ("sel_m16_g4_ragged", 4, 4, 16, 24000, 512, 64, 4, 2, "block", [24000, 17001, 300, 0]),
+    ("sel_m32_g7", 2, 7, 32, 20000, 500, 100, 4, 1, "diag", [20000, 16500]),
+    ("sel_m16_g8", 8, 8, 16, 33000, 2048, 256, 0, 1, "none", None),
+    ("sel_exact_route", 2, 4, 16, 3000, 64, 32, 0, 1, "diag", None),
+])
+def test_decode_select_equals_the_two_calls(name, Bn, G, M, N, K, w, n_sink, n_new, mode, seq_lens):
+    """a2ats_decode_select (append-time encode, tables and threshold sampling in one launch, then the
+    streaming and final kernels) writes bit for bit what a2ats_decode_prologue + a2ats_score_topk write:
+    codes, rotated queries, the whole table blob, scales, indices, counts and scores; and the same
+    survivor statistics, i.e. the same thresholds.  Also on a shape of the exact route (plain two calls)."""
+    wl = synth.Workload(name, Bn, 2 * G, 2, 128, M, N, K, w, n_sink=n_sink, seed=61)
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    hm = synth.make_query_second_moment(wl)
+    wmode = {"none": B.W_NONE, "diag": B.W_DIAG, "block": B.W_BLOCK}[mode]
+    weights = None if mode == "none" else hm["h_diag" if mode == "diag" else "h_block"].cuda()
+    keys = synth.make_encode_keys(wl, n_new, device="cuda", stress=True)
+    dims = H.dims_of(wl)
+    pos0 = N - n_new
+    sl = None if seq_lens is None else torch.as_tensor(seq_lens, dtype=torch.int32, device="cuda")
+    res = []
+    for fused in (False, True):
+        st = B.DecodeState(dims, K, w, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+        st.lut.fill_(-1)
+        st.ws.fill_(0x5a)
+        st.topk_idx.fill_(-7)
+        codes = xd["codes"].clone()
+        if fused:
+            B.decode_select(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, xd["q"], st.cos_b,
+                            st.sin_b, st.q_rot, st.lut, st.lut_scale, K, w, n_sink, sl, st.topk_idx, st.topk_count,
+                            st.topk_score, st.ws)
+        else:
+            B.decode_prologue(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, xd["q"], st.cos_b,
+                              st.sin_b, st.q_rot, st.lut, st.lut_scale)
+            B.score_topk(dims, codes, st.lut, st.lut_scale, K, w, n_sink, sl, st.topk_idx, st.topk_count,
+                         st.topk_score, None, st.ws)
+        stats = torch.empty(Bn, 2 * G, dtype=torch.int32, device="cuda")
+        B.score_topk_stats(dims, K, w, n_sink, st.ws, stats)
+        torch.cuda.synchronize()
+        res.append((codes.cpu(), st.lut.cpu(), st.lut_scale.cpu(), st.q_rot.cpu(), st.topk_idx.cpu(),
+                    st.topk_count.cpu(), st.topk_score.cpu(), stats.cpu()))
+    for i, (a, b) in enumerate(zip(*res)):
+        assert torch.equal(a, b), f"output {i} differs"
+    fast = B.score_topk_plan(dims, K, w, n_sink)["fast"]
+    assert fast == (name != "sel_exact_route")
+    assert int(res[1][5].max()) > 0
+
+
 @pytest.mark.parametrize("mode,n_new", [("none", 1), ("diag", 3), ("block", 8)])
 def test_single_codebook_decode_prologue_equals_the_two_calls(mode, n_new):
     """The fused prologue in the single-codebook geometry (the sweep of the few-key encoder, then the
