@@ -195,7 +195,8 @@ int a2ats_decode_prologue(const a2ats_dims* dims, const float* keys, int32_t n_n
  * a2ats_score_topk takes its streaming route (product quantisation, at least 16384 candidates,
  * 1 <= top_k <= 2048, 4 top_k <= candidates) the call needs one launch less than the two: the
  * workgroups that sample the thresholds build their problem's tables themselves and keep the coarse
- * copy in LDS.  Elsewhere it simply makes the two calls.  Arguments are the union of theirs; every
+ * copy in LDS (done while those workgroups, batch * n_kv_heads * head groups * sampling parts, number
+ * at most 256, one per CU).  Elsewhere it simply makes the two calls.  Arguments are the union of theirs; every
  * output (codes, q_rot, lut, lut_scale, topk_*) is bit for bit what the two calls write.
  * `ws`: a2ats_workspace_bytes(dims, A2ATS_OP_SCORE_TOPK, top_k, window) bytes for product
  * quantisation (the prologue needs none there), a2ats_workspace_bytes(dims, A2ATS_OP_ENCODE, 0, 0)

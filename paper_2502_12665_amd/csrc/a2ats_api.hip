@@ -266,7 +266,10 @@ int a2ats_decode_select(const a2ats_dims* d, const float* keys, int32_t n_new, i
   if (rc != A2ATS_OK) return rc;
   const a2ats::TopkPlan plan = a2ats::make_topk_plan(*d, top_k < 0 ? 0 : top_k, window < 0 ? 0 : window,
                                                      n_sink < 0 ? 0 : n_sink);
-  if (a2ats::single_codebook(*d) || !plan.fast) {   // nothing to fuse: the two calls, with their own checks
+  // The fused launch has every sampling workgroup build its problem's tables: worth it while those
+  // workgroups fit the 256 CUs in one round, a loss when they queue up behind each other.
+  const long n_sample = (long)d->batch * d->n_kv_heads * plan.NG * plan.P0;
+  if (a2ats::single_codebook(*d) || !plan.fast || n_sample > 256) {   // the two calls, with their own checks
     rc = a2ats_decode_prologue(d, keys, n_new, pos0, codebook, weights, weight_mode, codes, q, q_dtype, cos_b,
                                sin_b, q_rot, lut, lut_scale, ws, ws_bytes, stream);
     if (rc != A2ATS_OK) return rc;
