@@ -669,9 +669,11 @@ def test_streaming_route_serves_a_grid_of_shapes():
     assert not bad, bad
 
 
-def test_decode_step_in_a_hip_graph():
+@pytest.mark.parametrize("calls", ["four calls", "decode_select"])
+def test_decode_step_in_a_hip_graph(calls):
     """A captured decode step must replay to the eager result every time, with eager work and
-    synchronisations between the replays."""
+    synchronisations between the replays; as the four separate calls and as a2ats_decode_select +
+    a2ats_sparse_attn."""
     wl = synth.Workload("graph", 2, 8, 2, 128, 16, 30000, 900, 128, seed=8)
     xd = H.to_dev(synth.make_decode_inputs(wl))
     st = H.gpu_decode(wl, xd, want_scores=False)           # eager reference (also warms the library)
@@ -679,8 +681,15 @@ def test_decode_step_in_a_hip_graph():
     new_key = xd["k"][:, :, -1:, :].float().contiguous()
 
     def step():
-        B.encode_keys(st.dims, new_key, 1, wl.ctx_len - 1, xd["codebook"], None, B.W_NONE, xd["codes"], st.ws)
-        st.step(xd["q"], xd["codes"], xd["k"], xd["v"], xd["codebook"])
+        if calls == "four calls":
+            B.encode_keys(st.dims, new_key, 1, wl.ctx_len - 1, xd["codebook"], None, B.W_NONE, xd["codes"], st.ws)
+            st.step(xd["q"], xd["codes"], xd["k"], xd["v"], xd["codebook"])
+        else:
+            B.decode_select(st.dims, new_key, 1, wl.ctx_len - 1, xd["codebook"], None, B.W_NONE, xd["codes"], xd["q"],
+                            st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale, wl.top_k, wl.window, 0, None,
+                            st.topk_idx, st.topk_count, None, st.ws)
+            B.sparse_attn(st.dims, xd["q"], st.q_rot, xd["k"], xd["v"], st.topk_idx, st.topk_count, wl.top_k,
+                          wl.window, 0, st.cos_win, st.sin_win, None, st.out, st.ws)
     step()
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
