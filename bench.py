@@ -292,9 +292,11 @@ def group_shared_step(args, torch, B, synth, wl):
         B.build_lut_shared(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, sk.lut, sk.lut_scale)
         if timed:
             ev[i][2].record()
-            B.profile_stream_kernel(*kev.pair(i))
-        B.score_topk(dims_kv, x["codes"], sk.lut, sk.lut_scale, K, w, wl.n_sink, None, sk.topk_idx, sk.topk_count,
-                     None, None, sk.ws)
+            B.score_topk_profiled(dims_kv, x["codes"], sk.lut, sk.lut_scale, K, w, wl.n_sink, None, sk.topk_idx,
+                                  sk.topk_count, None, None, sk.ws, *kev.pair(i))
+        else:
+            B.score_topk(dims_kv, x["codes"], sk.lut, sk.lut_scale, K, w, wl.n_sink, None, sk.topk_idx,
+                         sk.topk_count, None, None, sk.ws)
         if timed:
             ev[i][3].record()
         B.sparse_attn_shared(dims, x["q"], st.q_rot, x["k"], x["v"], sk.topk_idx, sk.topk_count, K, w, wl.n_sink,
@@ -313,7 +315,6 @@ def group_shared_step(args, torch, B, synth, wl):
     for i in range(args.steps):
         step(i, True)
     torch.cuda.synchronize()
-    B.profile_stream_kernel(None, None)
     med = lambda v: float(sorted(v)[len(v) // 2])
     ph = [med([ev[i][p].elapsed_time(ev[i][p + 1]) * 1e3 for i in range(args.steps)]) for p in range(4)]
     k_us = sum(kev.elapsed_ms(i) * 1e3 for i in range(args.steps)) / args.steps
@@ -527,9 +528,11 @@ def main():
                                   x["q"], st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale)
             if timed:
                 phase_ev[i][2].record()
-                B.profile_stream_kernel(*kev.pair(i))
-            B.score_topk(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx,
-                         st.topk_count, None, None, st.ws)
+                B.score_topk_profiled(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx,
+                                      st.topk_count, None, None, st.ws, *kev.pair(i))
+            else:
+                B.score_topk(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx,
+                             st.topk_count, None, None, st.ws)
         if timed:
             phase_ev[i][3].record()
         elif stats:   # candidate-list sizes, read before the attention reuses the workspace
@@ -586,7 +589,6 @@ def main():
         step(i, True)
     torch.cuda.synchronize()
     te1 = time.perf_counter()
-    B.profile_stream_kernel(None, None)
 
     ph = [[phase_ev[i][p].elapsed_time(phase_ev[i][p + 1]) * 1e3 for i in range(args.steps)] for p in range(4)]
     med = lambda v: float(sorted(v)[len(v) // 2])

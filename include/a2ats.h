@@ -93,8 +93,8 @@ const char* a2ats_status_string(int status);
 size_t a2ats_lut_elems(const a2ats_dims* dims);
 
 /* Scratch bytes `op` needs for these dims (0 if it needs none; (size_t)-1 on bad dims).  For
- * A2ATS_OP_ATTN the figure covers up to 64 sink tokens; a call with more may need more and is
- * refused with A2ATS_ERR_WORKSPACE if `ws` is too small. */
+ * A2ATS_OP_ATTN and A2ATS_OP_SCORE_TOPK the figure covers every call with up to 64 sink tokens; a
+ * call with more may need more and is refused with A2ATS_ERR_WORKSPACE if `ws` is too small. */
 size_t a2ats_workspace_bytes(const a2ats_dims* dims, int op, int32_t top_k, int32_t window);
 
 /*
@@ -195,9 +195,12 @@ int a2ats_decode_prologue(const a2ats_dims* dims, const float* keys, int32_t n_n
  * a2ats_score_topk takes its streaming route (product quantisation, at least 16384 candidates,
  * 1 <= top_k <= 2048, 4 top_k <= candidates) the call needs one launch less than the two: the
  * workgroups that sample the thresholds build their problem's tables themselves and keep the coarse
- * copy in LDS (done while those workgroups, batch * n_kv_heads * head groups * sampling parts, number
- * at most 256, one per CU).  Elsewhere it simply makes the two calls.  Arguments are the union of theirs; every
- * output (codes, q_rot, lut, lut_scale, topk_*) is bit for bit what the two calls write.
+ * copy in LDS.  That is done while (a) those workgroups, batch * n_kv_heads * head groups * sampling
+ * parts, number at most 256, one per CU, and (b) no appended row can be a candidate of any sequence,
+ * pos0 >= ctx_len - window (the usual append of the current token; the sampling workgroups read
+ * candidate rows while others write the appended ones).  Elsewhere it simply makes the two calls.
+ * Arguments are the union of theirs and are all checked before anything is enqueued; every output
+ * (codes, q_rot, lut, lut_scale, topk_*) is bit for bit what the two calls write.
  * `ws`: a2ats_workspace_bytes(dims, A2ATS_OP_SCORE_TOPK, top_k, window) bytes for product
  * quantisation (the prologue needs none there), a2ats_workspace_bytes(dims, A2ATS_OP_ENCODE, 0, 0)
  * for the single codebook (its selection needs none).
@@ -222,7 +225,9 @@ int a2ats_decode_select(const a2ats_dims* dims, const float* keys, int32_t n_new
  *   topk_idx   [dev, out, int32 B*Hq*top_k]  selected positions in ascending order;
  *                                            slots past topk_count are -1
  *   topk_count [dev, out, int32 B*Hq]        K' = min(top_k, #candidates)
- *   topk_score [dev, out, nullable, f32 B*Hq*top_k] score of each selected position
+ *   topk_score [dev, out, nullable, f32 B*Hq*top_k] score of each selected position (on the
+ *              streaming route most winners are decided without their exact score, so asking
+ *              for it costs one exact evaluation per selected position)
  *   scores_out [dev, out, nullable, f32 B*Hq*ctx_stride] debug: every token's score
  *              (positions >= n are not written)
  * top_k == 0 is allowed.  window >= 0, n_sink >= 0.
@@ -345,36 +350,45 @@ int a2ats_codebook_update(const a2ats_dims* dims, const float* keys, int32_t n_n
                           const uint8_t* codes, const float* codebook, float* codebook_out,
                           int32_t* counts, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Diagnostics and profiling aids.  None of these is part of the method; nothing above needs them.
+ * ------------------------------------------------------------------------------------------------ */
+
 /*
- * Diagnostics (not part of the method): after an a2ats_score_topk call with the same dims /
- * top_k / window / n_sink and the same `ws`, write per head into cand_counts [dev, out, uint32
- * B*Hq] (asynchronously, on `stream`): bits 0-27 the number of rows the streaming pass kept
- * for that head, bits 28-31 the route the final kernel took (0 = fast; 1 = too few survivors,
- * 2 = too many, 3 = a segment overflowed, 4 = completeness proof failed: exact fallback).  For
- * shapes served by the exact route alone every entry is 0xFFFFFFFF.
+ * After an a2ats_score_topk call with the same dims / top_k / window / n_sink and the same `ws`,
+ * write per head into cand_counts [dev, out, uint32 B*Hq] (asynchronously, on `stream`): bits 0-27
+ * the number of rows the streaming pass kept for that head, bits 28-31 the route the final kernel
+ * took (0 = fast; 1 = fewer survivors than K, 2 = more than the list holds, 3 = a segment
+ * overflowed, 4 = the list could not be shown complete, 5 = too many rows too close to the K-th
+ * coarse score to rank: 1-5 end in the exact fallback).  For shapes served by the exact route alone
+ * every entry is 0xFFFFFFFF.
  */
 int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink,
                            const void* ws, uint32_t* cand_counts, void* stream);
 
 /*
- * Diagnostics (not part of the method; host only, no GPU needed): how a2ats_score_topk would lay out
- * its work for these dims / top_k / window / n_sink.  Writes 10 numbers to plan [host, out, int32 10]:
+ * Host only, no GPU needed: how a2ats_score_topk would lay out its work for these dims / top_k /
+ * window / n_sink.  Writes 11 numbers to plan [host, out, int32 11]:
  * [0] 1 if the sampled-threshold + streaming route is used (0: the exact route alone, the rest is 0),
  * [1] groups of four query heads per KV head, [2] sampling workgroups per (sequence, KV head, group),
- * [3] rows each of them scores, [4] streaming workgroups (chunks) per problem, [5] rows per chunk,
- * [6] survivor segments per wave of a chunk, [7] rows per segment, [8] entries a segment can hold,
- * [9] survivors per head the final kernel can hold.
+ * [3] rows each of them scores, [4] streaming workgroups per problem, [5] tiles per problem (a tile
+ * is a run of consecutive candidate rows scored by one wave, with one survivor segment), [6] tiles
+ * per streaming workgroup, [7] rows per tile, [8] entries a tile's segment can hold, [9] survivors
+ * per head the final kernel can hold, [10] workspace bytes the call needs, divided by 256.
  */
 int a2ats_score_topk_plan(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink, int32_t* plan);
 
 /*
- * Profiling aid (not part of the method): when both events are non-NULL, the next
- * a2ats_score_topk calls attach ev_start / ev_stop (hipEvent_t passed as void*) to the
- * dispatch of the code-streaming kernel on their stream, so that the elapsed time between
- * them is that kernel's own duration.  Pass NULLs to switch it off.  Process-global, not
- * thread-safe.
+ * a2ats_score_topk with a pair of events (hipEvent_t passed as void*, both non-NULL, created by the
+ * caller) attached to the dispatch of the code-streaming kernel on `stream`, so that the elapsed
+ * time between them is that kernel's own duration.  Everything else as a2ats_score_topk; the events
+ * are only used where the streaming route runs.  No state is kept between calls.
  */
-void a2ats_profile_stream_kernel(void* ev_start, void* ev_stop);
+int a2ats_score_topk_profiled(const a2ats_dims* dims, const uint8_t* codes, const int32_t* lut,
+                              const float* lut_scale, int32_t top_k, int32_t window, int32_t n_sink,
+                              const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
+                              float* topk_score, float* scores_out, void* ws, size_t ws_bytes,
+                              void* stream, void* ev_start, void* ev_stop);
 
 #ifdef __cplusplus
 }

@@ -290,37 +290,101 @@ def lloyd_update(keys, codes, codebook):
     return new, counts
 
 
-def kmeanspp_seed(keys, h_full, u, n_codewords: int):
-    """k-means++ seeding (Arthur & Vassilvitskii; section 4.2 initialises its k-means with it) under
-    the query-aware distortion (k - c) H (k - c)^T = ||z_k - z_c||^2, z = k L, H = L L^T.
-    keys [B,Hkv,n,D] (pooled per KV head, row i = b*n + j), H [Hkv,D,D] float64 (None: identity),
-    u [Hkv,n_codewords] uniform numbers in [0,1) standing in for the random draws.  Codeword 0 is row
-    floor(u_0 rows); codeword r is the first row whose inclusive prefix sum of d exceeds u_r sum(d)
-    (inverse of the cumulative distribution: a row is drawn with probability d_i / sum(d)),
-    d_i the distortion of row i to the nearest codeword chosen so far.  z is rounded once to
-    float32 (as the encoder stores it); everything else is float64.  Returns picks [Hkv,n_codewords]."""
+def _seed_distortions(z, pick):
+    """||z_i - z_pick||^2 for every row i (float64)."""
+    e = z - z[pick]
+    return np.einsum("nd,nd->n", e, e)
+
+
+def _seed_draw(d, u_r, n_rows):
+    """One k-means++ draw: the first row whose inclusive prefix sum of d exceeds u_r * sum(d) (inverse
+    of the cumulative distribution: row i is drawn with probability d_i / sum(d)); uniform over the
+    rows if every distortion is zero.  Returns (row, prefix sums, target)."""
+    cum = np.cumsum(d)
+    if cum[-1] > 0.0:
+        target = u_r * cum[-1]
+        return min(n_rows - 1, int(np.searchsorted(cum, target, side="right"))), cum, target
+    return min(n_rows - 1, int(u_r * n_rows)), cum, 0.0
+
+
+def _seed_rows(keys, h_full, kv):
     k = _f64(keys)
     B, Hkv, n, D = k.shape
+    rows = k[:, kv].reshape(B * n, D)
+    Lc = np.eye(D) if h_full is None else np.linalg.cholesky(_f64(h_full)[kv])
+    return rows @ Lc
+
+
+def kmeanspp_seed(keys, h_full, u, n_codewords: int):
+    """k-means++ seeding (Arthur & Vassilvitskii; section 4.2 initialises its k-means with it) under
+    the query-aware distortion (k - c) H (k - c)^T = ||z_k - z_c||^2, z = k L, H = L L^T (section 4.2,
+    Cholesky reformulation).  keys [B,Hkv,n,D] (pooled per KV head, row i = b*n + j), H [Hkv,D,D]
+    (None: identity), u [Hkv,n_codewords] uniform numbers in [0,1) standing in for the random draws.
+    Codeword 0 is row floor(u_0 rows); codeword r is drawn with probability d_i / sum(d), d_i the
+    distortion of row i to the nearest codeword chosen so far.  Float64 throughout.
+    Returns picks [Hkv,n_codewords]."""
+    B, Hkv, n, D = np.asarray(keys).shape
     uu = _f64(u)
     picks = np.zeros((Hkv, n_codewords), dtype=np.int64)
     for kv in range(Hkv):
-        rows = k[:, kv].reshape(B * n, D)
-        Lc = np.eye(D) if h_full is None else np.linalg.cholesky(_f64(h_full)[kv])
-        z = (rows @ Lc).astype(np.float32).astype(np.float64)
+        z = _seed_rows(keys, h_full, kv)
         pick = min(B * n - 1, int(uu[kv, 0] * (B * n)))
         d = None
         for r in range(n_codewords):
             picks[kv, r] = pick
             if r == n_codewords - 1:
                 break
-            e = z - z[pick]
-            dist = np.zeros(B * n)
-            for t in range(D):          # plain left-to-right sum over the dimensions
-                dist += e[:, t] * e[:, t]
+            dist = _seed_distortions(z, pick)
             d = dist if d is None else np.minimum(d, dist)
-            cum = np.cumsum(d)
-            if cum[-1] > 0.0:
-                pick = min(B * n - 1, int(np.searchsorted(cum, uu[kv, r + 1] * cum[-1], side="right")))
-            else:
-                pick = min(B * n - 1, int(uu[kv, r + 1] * (B * n)))
+            pick, _, _ = _seed_draw(d, uu[kv, r + 1], B * n)
     return picks
+
+
+def kmeanspp_check(keys, h_full, u, picks, rel_tol: float):
+    """Checks a sequence of k-means++ draws made elsewhere against the definition, draw by draw.
+    The draws are sequential (each depends on the codewords chosen before it), so one draw decided
+    differently changes all later ones; here draw r is therefore evaluated GIVEN picks[:, :r] as the
+    history.  For every draw the definition's row (kmeanspp_seed's rule, float64) is compared with
+    picks[kv, r]:
+      equal                                  -> counted in n_equal;
+      different, but picks[kv, r] is the row the rule gives for a target moved by at most
+      rel_tol * sum(d) (its prefix interval [cum[g-1], cum[g]) comes that close to the target, and
+      d_g > 0)                               -> counted in n_near (a draw on a prefix boundary);
+      anything else                          -> recorded in wrong [(kv, r, definition's row, given row)].
+    Returns (n_equal, n_near, wrong)."""
+    B, Hkv, n, D = np.asarray(keys).shape
+    uu = _f64(u)
+    pk = np.asarray(picks).astype(np.int64)
+    n_codewords = pk.shape[1]
+    n_equal = n_near = 0
+    wrong = []
+    for kv in range(Hkv):
+        z = _seed_rows(keys, h_full, kv)
+        want0 = min(B * n - 1, int(uu[kv, 0] * (B * n)))
+        if pk[kv, 0] == want0:
+            n_equal += 1
+        else:
+            wrong.append((kv, 0, want0, int(pk[kv, 0])))
+        d = None
+        for r in range(1, n_codewords):
+            prev = int(pk[kv, r - 1])
+            if not 0 <= prev < B * n:
+                wrong.append((kv, r - 1, -1, prev))
+                break
+            dist = _seed_distortions(z, prev)
+            d = dist if d is None else np.minimum(d, dist)
+            want, cum, target = _seed_draw(d, uu[kv, r], B * n)
+            g = int(pk[kv, r])
+            if g == want:
+                n_equal += 1
+                continue
+            tol = rel_tol * cum[-1]
+            ok = 0 <= g < B * n and cum[-1] > 0.0 and d[g] > 0.0
+            if ok:
+                lo = cum[g - 1] if g > 0 else 0.0
+                ok = lo - tol <= target <= cum[g] + tol
+            if ok:
+                n_near += 1
+            else:
+                wrong.append((kv, r, want, g))
+    return n_equal, n_near, wrong

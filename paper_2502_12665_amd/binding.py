@@ -21,7 +21,7 @@ W_PREPARED = 0x100
 OP_ENCODE, OP_LUT, OP_SCORE_TOPK, OP_ATTN, OP_FIT, OP_SEED = 0, 1, 2, 3, 4, 5
 EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_workspace_bytes", "a2ats_encode_prepare",
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
-           "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_profile_stream_kernel",
+           "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_score_topk_profiled",
            "a2ats_decode_prologue", "a2ats_decode_select", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
            "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged"]
 
@@ -94,8 +94,8 @@ def lib() -> ctypes.CDLL:
         L.a2ats_score_topk_plan.argtypes = [dp, i32, i32, i32, ctypes.POINTER(ctypes.c_int32)]
         L.a2ats_score_topk_stats.restype = ctypes.c_int
         L.a2ats_score_topk_stats.argtypes = [dp, i32, i32, i32, vp, vp, vp]
-        L.a2ats_profile_stream_kernel.restype = None
-        L.a2ats_profile_stream_kernel.argtypes = [vp, vp]
+        L.a2ats_score_topk_profiled.restype = ctypes.c_int
+        L.a2ats_score_topk_profiled.argtypes = L.a2ats_score_topk.argtypes + [vp, vp]
         _lib = L
     return _lib
 
@@ -286,13 +286,13 @@ def sparse_attn_paged(dims: Dims, q, q_rot, k_pool, v_pool, page_table, page_siz
     _check(rc, "a2ats_sparse_attn_paged")
 
 
-PLAN_FIELDS = ("fast", "head_groups", "sample_parts", "sample_rows", "chunks", "rows_per_chunk",
-               "segments_per_wave", "rows_per_segment", "segment_capacity", "survivor_capacity")
+PLAN_FIELDS = ("fast", "head_groups", "sample_parts", "sample_rows", "chunks", "tiles",
+               "tiles_per_chunk", "rows_per_tile", "segment_capacity", "survivor_capacity", "workspace_bytes_div_256")
 
 
 def score_topk_plan(dims: Dims, top_k: int, window: int, n_sink: int) -> dict:
     """How a2ats_score_topk lays out its work for this shape (host only; no GPU needed)."""
-    out = (ctypes.c_int32 * 10)()
+    out = (ctypes.c_int32 * len(PLAN_FIELDS))()
     _check(lib().a2ats_score_topk_plan(ctypes.byref(dims), top_k, window, n_sink, out), "a2ats_score_topk_plan")
     return dict(zip(PLAN_FIELDS, (int(v) for v in out)))
 
@@ -303,8 +303,16 @@ def score_topk_stats(dims: Dims, top_k: int, window: int, n_sink: int, ws, cand_
     _check(rc, "a2ats_score_topk_stats")
 
 
-def profile_stream_kernel(ev_start: Optional[int], ev_stop: Optional[int]):
-    lib().a2ats_profile_stream_kernel(ctypes.c_void_p(ev_start or 0), ctypes.c_void_p(ev_stop or 0))
+def score_topk_profiled(dims: Dims, codes, lut, lut_scale, top_k: int, window: int, n_sink: int, seq_lens,
+                        topk_idx, topk_count, topk_score, scores_out, ws: Optional[torch.Tensor],
+                        ev_start: int, ev_stop: int):
+    """score_topk with a pair of HIP events (handles) attached to the dispatch of the code-streaming kernel."""
+    rc = lib().a2ats_score_topk_profiled(ctypes.byref(dims), _ptr(codes), _ptr(lut), _ptr(lut_scale), top_k, window,
+                                         n_sink, _ptr(seq_lens), _ptr(topk_idx), _ptr(topk_count), _ptr(topk_score),
+                                         _ptr(scores_out), _ptr(ws),
+                                         0 if ws is None else ws.numel() * ws.element_size(), _stream(),
+                                         ctypes.c_void_p(ev_start), ctypes.c_void_p(ev_stop))
+    _check(rc, "a2ats_score_topk_profiled")
 
 
 class DecodeState:

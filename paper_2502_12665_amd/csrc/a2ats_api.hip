@@ -61,9 +61,14 @@ size_t a2ats_workspace_bytes(const a2ats_dims* d, int op, int32_t top_k, int32_t
     case A2ATS_OP_SCORE_TOPK: {
       if (top_k < 0 || window < 0) return (size_t)-1;
       if (a2ats::single_codebook(*d)) return 0;
-      // the plan does not depend on n_sink except through the candidate count; size for 0 sinks
-      const a2ats::TopkPlan p = a2ats::make_topk_plan(*d, top_k, window, 0);
-      return p.fast ? p.bytes : 0;
+      // The plan depends on the number of sinks through the candidate count: the figure covers
+      // every call with up to 64 sinks.
+      size_t need = 0;
+      for (int n_sink = 0; n_sink <= 64; ++n_sink) {
+        const a2ats::TopkPlan p = a2ats::make_topk_plan(*d, top_k, window, n_sink);
+        if (p.fast && p.bytes > need) need = p.bytes;
+      }
+      return need;
     }
     case A2ATS_OP_ATTN: {
       if (top_k < 0 || window < 0) return (size_t)-1;
@@ -264,12 +269,22 @@ int a2ats_decode_select(const a2ats_dims* d, const float* keys, int32_t n_new, i
                         void* ws, size_t ws_bytes, void* stream) {
   int rc = check_dims(d);
   if (rc != A2ATS_OK) return rc;
-  const a2ats::TopkPlan plan = a2ats::make_topk_plan(*d, top_k < 0 ? 0 : top_k, window < 0 ? 0 : window,
-                                                     n_sink < 0 ? 0 : n_sink);
+  // the selection arguments are checked before the prologue is enqueued (nothing may be launched on an error)
+  if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
+  if (top_k > 4096) return A2ATS_ERR_UNSUPPORTED;
+  if (!codes || !lut || !lut_scale || !topk_count || (top_k > 0 && !topk_idx)) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(codes)) return A2ATS_ERR_INVALID_ARG;
+  const a2ats::TopkPlan plan = a2ats::make_topk_plan(*d, top_k, window, n_sink);
+  if (!a2ats::single_codebook(*d) && plan.fast && (!ws || misaligned16(ws) || ws_bytes < plan.bytes))
+    return A2ATS_ERR_WORKSPACE;
   // The fused launch has every sampling workgroup build its problem's tables: worth it while those
-  // workgroups fit the 256 CUs in one round, a loss when they queue up behind each other.
+  // workgroups fit the 256 CUs in one round, a loss when they queue up behind each other.  Its
+  // sampling workgroups read candidate rows while others write the appended rows, so it is only
+  // taken when no appended row can be a candidate of any sequence (pos0 >= ctx_len - window: the
+  // usual append of the current token); otherwise the two calls run one after the other.
   const long n_sample = (long)d->batch * d->n_kv_heads * plan.NG * plan.P0;
-  if (a2ats::single_codebook(*d) || !plan.fast || n_sample > 256) {   // the two calls, with their own checks
+  const bool appended_rows_compete = n_new > 0 && (int64_t)pos0 < (int64_t)d->ctx_len - window;
+  if (a2ats::single_codebook(*d) || !plan.fast || n_sample > 256 || appended_rows_compete) {   // the two calls, with their own checks
     rc = a2ats_decode_prologue(d, keys, n_new, pos0, codebook, weights, weight_mode, codes, q, q_dtype, cos_b,
                                sin_b, q_rot, lut, lut_scale, ws, ws_bytes, stream);
     if (rc != A2ATS_OK) return rc;
@@ -300,10 +315,10 @@ int a2ats_decode_select(const a2ats_dims* d, const float* keys, int32_t n_new, i
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
-int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut, const float* lut_scale,
-                     int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
-                     int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,
-                     size_t ws_bytes, void* stream) {
+static int score_topk_impl(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut, const float* lut_scale,
+                           int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
+                           int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,
+                           size_t ws_bytes, void* stream, void* ev_start, void* ev_stop) {
   int rc = check_dims(d);
   if (rc != A2ATS_OK) return rc;
   if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
@@ -323,8 +338,26 @@ int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* l
   }
   const hipError_t e = a2ats::launch_score_topk(*d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
                                                 topk_idx, topk_count, topk_score, scores_out, ws, false,
-                                                (hipStream_t)stream);
+                                                (hipStream_t)stream, (hipEvent_t)ev_start, (hipEvent_t)ev_stop);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut, const float* lut_scale,
+                     int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
+                     int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,
+                     size_t ws_bytes, void* stream) {
+  return score_topk_impl(d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
+                         topk_score, scores_out, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int a2ats_score_topk_profiled(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut,
+                              const float* lut_scale, int32_t top_k, int32_t window, int32_t n_sink,
+                              const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
+                              float* topk_score, float* scores_out, void* ws, size_t ws_bytes, void* stream,
+                              void* ev_start, void* ev_stop) {
+  if (!ev_start || !ev_stop) return A2ATS_ERR_INVALID_ARG;
+  return score_topk_impl(d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
+                         topk_score, scores_out, ws, ws_bytes, stream, ev_start, ev_stop);
 }
 
 static int sparse_attn_impl(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
@@ -400,12 +433,10 @@ int a2ats_score_topk_plan(const a2ats_dims* d, int32_t top_k, int32_t window, in
   if (rc != A2ATS_OK) return rc;
   if (top_k < 0 || window < 0 || n_sink < 0 || !out) return A2ATS_ERR_INVALID_ARG;
   const a2ats::TopkPlan p = a2ats::make_topk_plan(*d, top_k, window, n_sink);
-  const int32_t v[10] = {p.fast ? 1 : 0, p.NG, p.P0, p.sample_rows, p.chunks, p.rows_per_chunk,
-                         p.subs, p.sub_rows, p.row_cap, p.cap};
-  for (int i = 0; i < 10; ++i) out[i] = p.fast || i == 0 ? v[i] : 0;
+  const int32_t v[11] = {p.fast ? 1 : 0, p.NG, p.P0, p.sample_rows, p.chunks, p.n_tiles,
+                         p.tiles_per_chunk, p.tile_rows, p.row_cap, p.cap, (int32_t)(p.bytes / 256)};
+  for (int i = 0; i < 11; ++i) out[i] = p.fast || i == 0 ? v[i] : 0;
   return A2ATS_OK;
 }
-
-void a2ats_profile_stream_kernel(void* ev_start, void* ev_stop) { a2ats::set_profile_events(ev_start, ev_stop); }
 
 }  // extern "C"

@@ -222,7 +222,7 @@ __device__ __forceinline__ void build_lut_body(
       const uint32_t q2 = (uint32_t)(iv[k][2] - mn2) >> sh2, q3 = (uint32_t)(iv[k][3] - mn3) >> sh3;
       const uint2 entry = make_uint2(q0 | (q1 << 16), q2 | (q3 << 16));
       if (write_out) coarse[(m >> 4) * (kCentroids * 16) + c * 16 + (m & 15)] = entry;
-      if (coarse_lds) *(uint2*)(coarse_lds + (c << 8) + ((m >> 4) << 7) + ((m & 15) << 3)) = entry;
+      if (coarse_lds) store_coarse_lds<M>(coarse_lds, c, m, entry);
     }
   }
 }

@@ -10,32 +10,50 @@ constexpr float kSigma = 5.0f;   // margin of the sampled rank, in standard devi
 
 // Coarse scores of one token for the four heads of a group.  The coarse table sits in LDS with
 // one 256-byte row per centroid id c: the 8-byte entry (two 32-bit words, each holding two heads'
-// 16-bit values) of subspace m is at byte (c << 8) | ((m >> 4) << 7) | ((m & 15) << 3).  (For
-// M = 16 the upper half of each row is unused.)
+// 16-bit values) of subspace m is at byte (c << 8) | ((m >> 4) << 7) | ((m & 15) << 3); for
+// M = 16 the upper half of each row holds a second copy of the lower half.
 //
-// LDS serves an 8-byte read 16 lanes at a time; lanes collide when they touch the same banks.
-// With this layout the banks of a read depend only on m, not on the (random) code byte, so lane
-// L visits the subspaces of its row in the order m = t ^ (L & 15), t = 0..15 (per 16-byte half
-// row): the 16 lanes served together always touch 16 different entries of their rows, and
-// random codes cause no conflicts.  The visiting order does not change the result because the
-// scores are integer sums.  One v_perm_b32 assembles the whole LDS address of a read from the
-// code byte and a per-lane constant.
+// The LDS of this part has 64 four-byte banks (a 256-byte row spans all of them once) and serves
+// an 8-byte read 32 lanes at a time; lanes collide when they touch the same banks.  With this
+// layout the banks of a read depend only on the column, not on the (random) code byte.  Lane L
+// visits the subspaces of a 16-byte half row in the order m = t ^ (L & 15), t = 0..15, and lanes
+// 16..31 of each half-wave are on the other half of the row from lanes 0..15 (the second copy for
+// M = 16; the two half rows in the other order for M = 32): the 32 lanes served together always
+// touch 32 different entries, so random codes cause no conflicts.  (Measured per 64-lane read,
+// two 8-wave workgroups per CU: 3.2 clocks; 4.8 with the columns of one half only; 62 with every
+// lane on the same column.)  The visiting order does not change the result because the scores are
+// integer sums.  One v_perm_b32 assembles the whole LDS address of a read from the code byte and a
+// per-lane constant.
 constexpr int kCoarseLdsBytes = kCentroids * 256;
+
+// Byte offset of the coarse entry of (centroid c, subspace m) in the LDS table.
+__device__ __forceinline__ uint32_t coarse_lds_offset(int c, int m) {
+  return ((uint32_t)c << 8) | (((uint32_t)m >> 4) << 7) | (((uint32_t)m & 15u) << 3);
+}
+// Put one entry (or two neighbouring ones, V = int4) there, with its second copy when M = 16.
+template <int M, typename V>
+__device__ __forceinline__ void store_coarse_lds(unsigned char* tbl, int c, int m, const V& entry) {
+  *(V*)(tbl + coarse_lds_offset(c, m)) = entry;
+  if (M == 16) *(V*)(tbl + coarse_lds_offset(c, m) + 128) = entry;
+}
 
 template <int M>
 struct LaneSwizzle {
   uint32_t mc[M / 4];   // byte t&3 of mc[t>>2]: low address byte for step t of this lane
   uint32_t sel[4];      // v_perm selectors: address byte 1 <- code byte (k ^ b), byte 0 <- mc byte k
   bool swap1, swap2;    // dword index of the row is XORed with (rho >> 2)
+  // M = 32: lanes 16..31 of a half-wave take the two 16-byte halves of a code row in the other
+  // order.  A caller loads  w[qd] = 16 bytes at row + ((16 * qd) ^ row_swz)  (0 or 16).
+  uint32_t row_swz;
   __device__ __forceinline__ void init(int lane) {
-    const uint32_t rho = lane & 15, b = rho & 3;
+    const uint32_t rho = lane & 15, b = rho & 3, hi = (lane >> 4) & 1;
 #pragma unroll
     for (int d = 0; d < M / 4; ++d) {
       uint32_t v = 0;
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const uint32_t t = 4 * d + k;                       // step within the whole row
-        const uint32_t m_low = (t ^ rho) & 15u, half = t >> 4;
+        const uint32_t m_low = (t ^ rho) & 15u, half = M == 16 ? hi : ((t >> 4) ^ hi);
         v |= ((half << 7) | (m_low << 3)) << (8 * k);
       }
       mc[d] = v;
@@ -44,6 +62,7 @@ struct LaneSwizzle {
     for (int k = 0; k < 4; ++k) sel[k] = 0x0c0c0000u | ((4u + ((uint32_t)k ^ b)) << 8) | (uint32_t)k;
     swap1 = (rho >> 2) & 1;
     swap2 = (rho >> 3) & 1;
+    row_swz = (M == 32 && hi) ? 16u : 0u;
   }
 };
 
@@ -51,7 +70,8 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) const u32x2_t* lds_u2_ptr;
 
 // kBaseZero: the table starts at LDS address 0 (kernel without static LDS), so the v_perm result
-// is the address itself; otherwise it is an offset from `tbl`.
+// is the address itself; otherwise it is an offset from `tbl`.  `w` holds the lane's code row as
+// loaded under LaneSwizzle::row_swz.
 template <int M, bool kBaseZero>
 __device__ __forceinline__ void score_coarse(const uint4 (&w)[M / 16], const unsigned char* tbl,
                                              const LaneSwizzle<M>& sw, uint32_t& a01, uint32_t& a23) {
@@ -84,7 +104,7 @@ __device__ __forceinline__ void load_coarse_table(const int32_t* __restrict__ lu
 #pragma unroll 4
   for (int e = threadIdx.x; e < kCentroids * M / 2; e += NT) {   // e: pair of entries (2 * e, 2 * e + 1)
     const int half = e / (kCentroids * 8), c = (e / 8) % kCentroids, mp = e % 8;
-    *(int4*)(tbl + (c << 8) + (half << 7) + (mp << 4)) = src[e];
+    store_coarse_lds<M>(tbl, c, 16 * half + 2 * mp, src[e]);
   }
 }
 
@@ -148,7 +168,8 @@ __device__ __forceinline__ void sample_threshold_body(
     j = min(j, sr.win_start - 1);
     uint4 w[M / 16];
 #pragma unroll
-    for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + qd * 16);
+    for (int qd = 0; qd < M / 16; ++qd)
+      w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + ((uint32_t)(qd * 16) ^ sw.row_swz));
     uint32_t a01, a23;
     score_coarse<M, false>(w, tbl, sw, a01, a23);
     atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);

@@ -19,11 +19,11 @@ struct TopkPlan {
   int P0;               // sampling workgroups per (sequence, KV head, head group)
   int sample_rows;      // rows each of them scores
   int chunks;           // streaming workgroups per (sequence, KV head, head group)
-  int rows_per_chunk;
-  int subs;             // survivor segments per wave of the streaming pass (its rows in `subs` equal runs)
-  int sub_rows;         // rows per such run (a multiple of 512 when subs > 1)
+  int tile_rows;        // candidate rows per tile (a multiple of 256); one wave scores a tile, one survivor segment per tile
+  int n_tiles;          // tiles per problem (at most 512)
+  int tiles_per_chunk;  // consecutive tiles owned by one streaming workgroup
   int cap;              // survivor capacity per head in the final kernel's LDS
-  int row_cap;          // row entries of one survivor segment in HBM
+  int row_cap;          // entries of one survivor segment in HBM
   size_t off_thr, off_route, off_count, off_cand, bytes;
 };
 
@@ -36,7 +36,6 @@ struct AttnPlan {
 TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink);
 AttnPlan make_attn_plan(const a2ats_dims& d, int top_k, int window, int n_sink);
 size_t encode_ws_bytes(const a2ats_dims& d);
-void set_profile_events(void* ev_start, void* ev_stop);
 hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sink, const void* ws,
                            uint32_t* cand_counts, hipStream_t stream);
 
@@ -61,7 +60,8 @@ hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, con
 hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const int32_t* lut,
                              const float* lut_scale, int top_k, int window, int n_sink,
                              const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
-                             float* topk_score, float* scores_out, void* ws, bool presampled, hipStream_t stream);
+                             float* topk_score, float* scores_out, void* ws, bool presampled, hipStream_t stream,
+                             hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // Decode prologue (append-time encode + tables) and the threshold sampling of the streaming route in
 // one launch; launch_score_topk(..., presampled = true) then skips its sampling launch.
 hipError_t launch_decode_select_prologue(const a2ats_dims& d, const float* keys, int n_new, int pos0,

@@ -872,9 +872,14 @@ def test_kv_cache_in_pinned_host_memory(oracle):
 
 @pytest.mark.parametrize("mode", ["block", "none"])
 def test_kmeanspp_seeding(oracle, mode):
-    """The 4096 sequential k-means++ draws under the query-aware distortion pick the same keys as the
-    oracle (same uniform numbers), and the seed codebook is exactly those keys; duplicated keys included,
-    so that zero distortions occur."""
+    """The 4096 sequential k-means++ draws under the query-aware distortion follow the definition
+    (same uniform numbers), and the seed codebook is exactly the drawn keys; duplicated keys included,
+    so that zero distortions occur.  The oracle evaluates the definition in float64; the kernel rounds
+    z = k L once to float32, which moves a distortion by at most 2.4e-7 of itself, hence a prefix sum
+    and the target u * sum(d) by at most 5e-7 * sum(d) together.  The draws are sequential, so every
+    draw is judged given the library's earlier draws (oracle.kmeanspp_check); a draw that differs from
+    the definition's is excluded iff the target lies within 5e-7 * sum(d) of the library row's prefix
+    interval.  Exclusions are counted and printed."""
     wl = _single("seed", 2, 4, 2, 2600, 1, 1, seed=17)
     hm = synth.make_query_second_moment(wl)
     n = 2600
@@ -891,13 +896,15 @@ def test_kmeanspp_seeding(oracle, mode):
     B.kmeanspp_seed(dims, keys.cuda(), n, w, B.W_BLOCK if mode == "block" else B.W_NONE, u.cuda(), out, picks, ws)
     torch.cuda.synchronize()
     hfull = hm["h_block"].numpy().astype(np.float64)[:, 0] if mode == "block" else None
-    want = oracle.kmeanspp_seed(keys, hfull, u.numpy(), 4096)
     got = picks.cpu().numpy()
-    first_diff = np.argmax(got != want, axis=1)
-    assert (got == want).all(), f"picks differ from draw {first_diff} on"
+    n_equal, n_near, wrong = oracle.kmeanspp_check(keys, hfull, u.numpy(), got, 5e-7)
+    print(f"k-means++ seeding ({mode}): draws compared {got.size}/{got.size}, equal {n_equal}, "
+          f"excluded on a prefix boundary {n_near}, wrong {len(wrong)}")
+    assert not wrong, f"draws that do not follow the definition: {wrong[:5]}"
+    assert n_near <= got.size // 1000
     pooled = keys.permute(1, 0, 2, 3).reshape(wl.n_kv_heads, wl.batch * n, 128)
     for kv in range(wl.n_kv_heads):
-        assert torch.equal(out[kv, 0].cpu(), pooled[kv][torch.as_tensor(want[kv])])
+        assert torch.equal(out[kv, 0].cpu(), pooled[kv][torch.as_tensor(got[kv].astype(np.int64))])
 
 
 def test_query_aware_codebook_lowers_the_query_aware_distortion_on_a_mixture(oracle):

@@ -546,3 +546,34 @@ def test_kmeanspp_seeding_properties(oracle):
     ph = oracle.kmeanspp_seed(far0, Hm, np.array([[0.0, 0.5]]), 2)[0]
     pi = oracle.kmeanspp_seed(far0, None, np.array([[0.0, 0.5]]), 2)[0]
     assert ph[1] >= 20 and pi[1] < 20
+
+
+def test_kmeanspp_check_follows_the_definition(oracle):
+    """The draw-by-draw checker used for the GPU seeding: it accepts the definition's own draws, flags a
+    planted wrong draw (and only that draw: later ones are judged given the history as it stands), and
+    accepts the neighbouring row only when the target lies on the prefix boundary between the two."""
+    rng = np.random.default_rng(9)
+    D, n = 8, 50
+    keys = rng.standard_normal((1, 2, n, D)).astype(np.float32)
+    A = rng.standard_normal((2, D, D))
+    Hm = np.einsum("kij,klj->kil", A, A) / D + 0.05 * np.eye(D)
+    u = rng.random((2, 12))
+    p = oracle.kmeanspp_seed(keys, Hm, u, 12)
+    assert oracle.kmeanspp_check(keys, Hm, u, p, 0.0) == (24, 0, [])
+    bad = p.copy()
+    unused = [i for i in range(n) if i not in set(p[1].tolist())]
+    bad[1, 5] = unused[0]
+    n_eq, n_near, wrong = oracle.kmeanspp_check(keys, Hm, u, bad, 1e-9)
+    assert [w[:2] for w in wrong if w[1] == 5] == [(1, 5)] and n_near == 0
+    # hand example in one dimension: keys 0, 1, -1, sqrt(2) -> after choosing row 0, d = [0, 1, 1, 2],
+    # prefix sums [0, 1, 2, 4]; u = 0.25 puts the target exactly on the boundary between rows 1 and 2
+    k1 = np.array([0.0, 1.0, -1.0, np.sqrt(2.0)], dtype=np.float64).reshape(1, 1, 4, 1)
+    u1 = np.array([[0.0, 0.25]])
+    assert oracle.kmeanspp_seed(k1, None, u1, 2)[0].tolist() == [0, 2]        # first prefix sum above 1.0
+    d2 = float(k1[0, 0, 3, 0] ** 2)
+    tol = 1e-12 + abs(d2 - 2.0)
+    assert oracle.kmeanspp_check(k1, None, u1, np.array([[0, 2]]), tol)[:2] == (2, 0)
+    assert oracle.kmeanspp_check(k1, None, u1, np.array([[0, 1]]), tol)[:2] == (1, 1)   # on the boundary
+    assert oracle.kmeanspp_check(k1, None, u1, np.array([[0, 3]]), tol)[2] == [(0, 1, 2, 3)]
+    assert oracle.kmeanspp_check(k1, None, u1, np.array([[0, 0]]), tol)[2] == [(0, 1, 2, 0)]   # d = 0: never drawn
+
