@@ -225,9 +225,7 @@ int a2ats_decode_select(const a2ats_dims* dims, const float* keys, int32_t n_new
  *   topk_idx   [dev, out, int32 B*Hq*top_k]  selected positions in ascending order;
  *                                            slots past topk_count are -1
  *   topk_count [dev, out, int32 B*Hq]        K' = min(top_k, #candidates)
- *   topk_score [dev, out, nullable, f32 B*Hq*top_k] score of each selected position (on the
- *              streaming route most winners are decided without their exact score, so asking
- *              for it costs one exact evaluation per selected position)
+ *   topk_score [dev, out, nullable, f32 B*Hq*top_k] score of each selected position
  *   scores_out [dev, out, nullable, f32 B*Hq*ctx_stride] debug: every token's score
  *              (positions >= n are not written)
  * top_k == 0 is allowed.  window >= 0, n_sink >= 0.
@@ -358,10 +356,9 @@ int a2ats_codebook_update(const a2ats_dims* dims, const float* keys, int32_t n_n
  * After an a2ats_score_topk call with the same dims / top_k / window / n_sink and the same `ws`,
  * write per head into cand_counts [dev, out, uint32 B*Hq] (asynchronously, on `stream`): bits 0-27
  * the number of rows the streaming pass kept for that head, bits 28-31 the route the final kernel
- * took (0 = fast; 1 = fewer survivors than K, 2 = more than the list holds, 3 = a segment
- * overflowed, 4 = the list could not be shown complete, 5 = too many rows too close to the K-th
- * coarse score to rank: 1-5 end in the exact fallback).  For shapes served by the exact route alone
- * every entry is 0xFFFFFFFF.
+ * took (0 = fast; 1 = too few survivors, 2 = too many, 3 = a segment overflowed, 4 = completeness
+ * proof failed: 1-4 end in the exact fallback).  For shapes served by the exact route alone every
+ * entry is 0xFFFFFFFF.
  */
 int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink,
                            const void* ws, uint32_t* cand_counts, void* stream);
@@ -371,10 +368,9 @@ int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window
  * window / n_sink.  Writes 11 numbers to plan [host, out, int32 11]:
  * [0] 1 if the sampled-threshold + streaming route is used (0: the exact route alone, the rest is 0),
  * [1] groups of four query heads per KV head, [2] sampling workgroups per (sequence, KV head, group),
- * [3] rows each of them scores, [4] streaming workgroups per problem, [5] tiles per problem (a tile
- * is a run of consecutive candidate rows scored by one wave, with one survivor segment), [6] tiles
- * per streaming workgroup, [7] rows per tile, [8] entries a tile's segment can hold, [9] survivors
- * per head the final kernel can hold, [10] workspace bytes the call needs, divided by 256.
+ * [3] rows each of them scores, [4] streaming workgroups (chunks) per problem, [5] rows per chunk,
+ * [6] survivor segments per wave of a chunk, [7] rows per segment, [8] entries a segment can hold,
+ * [9] survivors per head the final kernel can hold, [10] workspace bytes the call needs, divided by 256.
  */
 int a2ats_score_topk_plan(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink, int32_t* plan);
 

@@ -286,8 +286,9 @@ def sparse_attn_paged(dims: Dims, q, q_rot, k_pool, v_pool, page_table, page_siz
     _check(rc, "a2ats_sparse_attn_paged")
 
 
-PLAN_FIELDS = ("fast", "head_groups", "sample_parts", "sample_rows", "chunks", "tiles",
-               "tiles_per_chunk", "rows_per_tile", "segment_capacity", "survivor_capacity", "workspace_bytes_div_256")
+PLAN_FIELDS = ("fast", "head_groups", "sample_parts", "sample_rows", "chunks", "rows_per_chunk",
+               "segments_per_wave", "rows_per_segment", "segment_capacity", "survivor_capacity",
+               "workspace_bytes_div_256")
 
 
 def score_topk_plan(dims: Dims, top_k: int, window: int, n_sink: int) -> dict:

@@ -433,8 +433,8 @@ int a2ats_score_topk_plan(const a2ats_dims* d, int32_t top_k, int32_t window, in
   if (rc != A2ATS_OK) return rc;
   if (top_k < 0 || window < 0 || n_sink < 0 || !out) return A2ATS_ERR_INVALID_ARG;
   const a2ats::TopkPlan p = a2ats::make_topk_plan(*d, top_k, window, n_sink);
-  const int32_t v[11] = {p.fast ? 1 : 0, p.NG, p.P0, p.sample_rows, p.chunks, p.n_tiles,
-                         p.tiles_per_chunk, p.tile_rows, p.row_cap, p.cap, (int32_t)(p.bytes / 256)};
+  const int32_t v[11] = {p.fast ? 1 : 0, p.NG, p.P0, p.sample_rows, p.chunks, p.rows_per_chunk,
+                         p.subs, p.sub_rows, p.row_cap, p.cap, (int32_t)(p.bytes / 256)};
   for (int i = 0; i < 11; ++i) out[i] = p.fast || i == 0 ? v[i] : 0;
   return A2ATS_OK;
 }

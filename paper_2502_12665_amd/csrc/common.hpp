@@ -179,6 +179,62 @@ __device__ __forceinline__ void xcd_map_sets(int linear, int parts, int problems
   }
 }
 
+// Division of small block-index-sized numbers by a launch constant without the ~35-instruction
+// software division (which every wave of a workgroup would run before its first load):
+// n / d = umulhi(n, 2^32 / d + 1), exact while n * d < 2^32.
+struct FastDiv {
+  uint32_t d, m;
+};
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d < 1u ? 1u : d;
+  f.m = f.d == 1u ? 0u : (uint32_t)((1ull << 32) / f.d + 1ull);
+  return f;
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv& f) { return f.d == 1u ? n : __umulhi(n, f.m); }
+
+// xcd_map / xcd_map_sets with the divisions prepared on the host, plus the split of a problem
+// index ((b * Hkv + kv) * NG + g4) into its parts.  All indices stay far below the 2^32 / d limit
+// (workgroups per launch <= 2^20, divisors <= 2^11).
+struct GridMap {
+  FastDiv parts, ng, parts_ng, hkv;
+  int mode;   // 0: linear = problem * parts + part; 1: xcd_map; 2: xcd_map_sets
+};
+inline GridMap make_grid_map(int parts, int problems, int ng, int hkv) {
+  GridMap g;
+  g.parts = make_fastdiv((uint32_t)parts);
+  g.ng = make_fastdiv((uint32_t)ng);
+  g.parts_ng = make_fastdiv((uint32_t)(parts * ng));
+  g.hkv = make_fastdiv((uint32_t)hkv);
+  g.mode = (ng > 1 && problems % (8 * ng) == 0) ? 2 : ((problems & 7) == 0 ? 1 : 0);
+  return g;
+}
+__device__ __forceinline__ void map_block(uint32_t linear, const GridMap& gm, int& problem, int& part) {
+  if (gm.mode == 2) {
+    const uint32_t xcd = linear & 7u, slot = linear >> 3;
+    const uint32_t unit = fast_div(slot, gm.parts_ng), inner = slot - unit * gm.parts_ng.d;
+    const uint32_t pt = fast_div(inner, gm.ng);
+    problem = (int)((unit * 8u + xcd) * gm.ng.d + (inner - pt * gm.ng.d));
+    part = (int)pt;
+  } else if (gm.mode == 1) {
+    const uint32_t xcd = linear & 7u, slot = linear >> 3;
+    const uint32_t q = fast_div(slot, gm.parts);
+    problem = (int)(q * 8u + xcd);
+    part = (int)(slot - q * gm.parts.d);
+  } else {
+    const uint32_t q = fast_div(linear, gm.parts);
+    problem = (int)q;
+    part = (int)(linear - q * gm.parts.d);
+  }
+}
+__device__ __forceinline__ void split_problem(int prob, const GridMap& gm, int& b, int& kv, int& g4) {
+  const uint32_t bkv = fast_div((uint32_t)prob, gm.ng);
+  g4 = (int)((uint32_t)prob - bkv * gm.ng.d);
+  const uint32_t bb = fast_div(bkv, gm.hkv);
+  b = (int)bb;
+  kv = (int)(bkv - bb * gm.hkv.d);
+}
+
 // Per-sequence geometry of the candidate range (sinks and window never compete).
 struct SeqRange {
   int n;          // tokens in the sequence

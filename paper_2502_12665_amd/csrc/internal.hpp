@@ -19,11 +19,11 @@ struct TopkPlan {
   int P0;               // sampling workgroups per (sequence, KV head, head group)
   int sample_rows;      // rows each of them scores
   int chunks;           // streaming workgroups per (sequence, KV head, head group)
-  int tile_rows;        // candidate rows per tile (a multiple of 256); one wave scores a tile, one survivor segment per tile
-  int n_tiles;          // tiles per problem (at most 512)
-  int tiles_per_chunk;  // consecutive tiles owned by one streaming workgroup
+  int rows_per_chunk;
+  int subs;             // survivor segments per wave of the streaming pass (its rows in `subs` equal runs)
+  int sub_rows;         // rows per such run (a multiple of 512 when subs > 1)
   int cap;              // survivor capacity per head in the final kernel's LDS
-  int row_cap;          // entries of one survivor segment in HBM
+  int row_cap;          // row entries of one survivor segment in HBM
   size_t off_thr, off_route, off_count, off_cand, bytes;
 };
 

@@ -9,7 +9,7 @@
 //  winners in ascending position, equal scores going to the lower position.
 //
 //  fast route (long contexts): the code matrix is streamed from HBM once, against a 16-bit
-//  coarse copy of the tables, and only rows near the K-th score are ever scored exactly.
+//  coarse copy of the tables, and only the survivors are scored exactly.
 //    1. sample_threshold_kernel scores a sample of each sequence (about 1/16 of it, taken in
 //       128-byte runs spread evenly over the candidates) with the coarse tables and derives, per
 //       head, a coarse threshold below the K-th score with a 5-sigma margin (distribution-free
@@ -17,21 +17,16 @@
 //    2. stream_select_kernel streams all code rows: one 8-byte LDS read per code byte serves the
 //       four heads of a group (two heads per 32-bit word, 16 bits each, so one integer add
 //       accumulates two heads).  A row whose coarse score reaches the threshold of any of the
-//       heads is written once -- its position and the two words of coarse scores, 12 bytes -- to
-//       the segment of its tile (a run of 256..2048 consecutive rows scored by one wave) in HBM.
-//    3. final_select_kernel (one workgroup per head) gathers its head's survivors (about 1.7 K)
-//       in position order, finds the K-th largest COARSE score c_K among them exactly, and uses
-//         exact score = base + (coarse << s) + rem,  0 <= rem < M 2^s
-//       twice: a row with coarse >= c_K + M beats every row with coarse <= c_K, of which all but
-//       at most K - 1 are, so it is a winner; a row with coarse <= c_K - M loses to the at least
-//       K rows with coarse >= c_K.  Only the rows in between (a few dozen) are scored exactly,
-//       from their code bytes and the head's 32-bit table, and ranked (score, then position).
-//       Every row with coarse > c_K - M must be on the list, i.e. threshold <= c_K - M + 1; if
-//       that fails, or a list is too short / too long / overflowed, or the band in between is
-//       too large (the sample misled -- about 1e-6 per head for independent rows, more when
-//       similar rows come in runs -- or the input is degenerate, e.g. all rows equal), the
-//       workgroup runs the exact route for its head, so the result is always exact with respect
-//       to the 32-bit scores.
+//       heads is written once -- an 8-byte header (position, wanting heads, rank per head) and
+//       its code bytes -- to the segment of its (problem, chunk, wave) in HBM.
+//    3. final_select_kernel (one workgroup per head) collects its head's survivors (about 1.7 K),
+//       scores them exactly from the head's 32-bit table, radix-selects the exact K-th key among
+//       them, proves that no row outside the survivor list can reach that key (coarse and exact
+//       scores differ by less than M coarse units), and writes the winners in ascending
+//       position.  If the proof fails or a list is too short / too long / overflowed -- the
+//       sample misled (about 1e-6 per head for independent rows, more when similar rows come in
+//       runs) or the input is degenerate -- the workgroup runs the exact route for its head, so
+//       the result is always exact with respect to the 32-bit scores.
 #include <hip/hip_ext.h>
 #include <math.h>
 
@@ -49,10 +44,7 @@ constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kSampleThreads = 512;
 constexpr int kSegMeta = 8;          // words of a segment header: rows, 4 per-head counts, padding
 constexpr int kSampleRows = 1024;    // rows scored by one sampling workgroup
-constexpr int kTileUnit = 256;       // rows a wave scores per step (4 per lane)
-constexpr int kMaxTiles = 512;       // tiles (= survivor segments) per problem the final kernel handles
-constexpr int kEntryWords = 3;       // a survivor entry: position, coarse scores of heads 0|1, of heads 2|3
-constexpr int kBandMax = 1024;       // rows within M coarse units of the K-th coarse score that are ranked exactly
+constexpr int kSmallList = 1024;     // members of the K-th key's bin ranked by brute force
 
 TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) {
   TopkPlan p{};
@@ -73,43 +65,68 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     p.P0 = (int)std::min<long>(8, s_tot / kSampleRows);
     p.sample_rows = (int)(s_tot / p.P0);   // at most 8192: the histogram counts are 16 bits wide
     const long problems = (long)d.batch * d.n_kv_heads * p.NG;
-    // Tiles: runs of tile_rows consecutive candidates, each scored by one wave and owning one
-    // survivor segment; the segments of a problem taken in tile order are sorted by position.
-    long tile_rows = (ncand + (long)kMaxTiles * kTileUnit - 1) / ((long)kMaxTiles * kTileUnit) * kTileUnit;
-    const long n_tiles = (ncand + tile_rows - 1) / tile_rows;   // 64 .. 512
-    // Workgroups: two per CU over the whole launch, each with at least one tile per wave.
     long chunks = (512 + problems - 1) / problems;
-    const long max_chunks = (n_tiles + kStreamWaves - 1) / kStreamWaves;
+    const long max_chunks = (ncand + 2047) / 2048;
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
-    const long tpc = (n_tiles + chunks - 1) / chunks;
-    chunks = (n_tiles + tpc - 1) / tpc;   // none empty
-    // Survivor segments.  The sampling rule (rank r with r - 5 sqrt(r) >= K S / N, plus one per
-    // part) lets about r N / S rows per head through -- for small K much more than K -- and a row
-    // survives if any of the (up to) four heads wants it.  row_cap is twice that share of a tile's
-    // rows plus 16 standard deviations of a Poisson count: survivors that come in runs
-    // (neighbouring tokens with similar scores) scatter far more between tiles than independent
-    // ones.  Unused capacity costs only scratch.
+    if (chunks > 64) chunks = 64;
+    // Survivor segments: a header and row_cap row entries each.  The sampling rule (rank r with
+    // r - 5 sqrt(r) >= K S / N, plus one per part) lets about r N / S rows per head through -- for
+    // small K much more than K -- and a row survives if any of the (up to) four heads wants it.
+    // row_cap is twice that share of a segment's rows plus 16 standard deviations of a Poisson
+    // count: survivors that come in runs (neighbouring tokens with similar scores) scatter far more
+    // between segments than independent ones.  Ranks inside a segment are stored in 10 bits, so
+    // row_cap must fit 1024: a wave whose rows would need more cuts them into `subs` runs of a
+    // multiple of 512 rows (one iteration of its loop), one segment each; the final kernel handles
+    // at most 512 segments per problem, beyond that the context is cut into more chunks instead.
     const double r0 = (double)top_k * (double)s_tot / (double)ncand;
     const double xr = 0.5 * (kSigma + std::sqrt(kSigma * kSigma + 4.0 * r0));
     const double survivors = (xr * xr + 2.0 * p.P0) / (double)s_tot * (double)ncand * 1.25;
     const double keep = std::min(1.0, 4.0 * survivors / (double)ncand);
-    const double mu = (double)tile_rows * keep;
-    long cap_rows = (long)(mu * 2.0 + 16.0 * std::sqrt(mu)) + 64;
-    cap_rows = (cap_rows + 31) / 32 * 32;
-    if (cap_rows > tile_rows) cap_rows = tile_rows;
-    p.chunks = (int)chunks;
-    p.tile_rows = (int)tile_rows;
-    p.n_tiles = (int)n_tiles;
-    p.tiles_per_chunk = (int)tpc;
+    auto cap_for = [&](long rows) {   // rows is a multiple of 64
+      const double mu = rows * keep;
+      long c = (long)(mu * 2.0 + 16.0 * std::sqrt(mu)) + 64;   // generous: unused capacity costs only scratch
+      c = (c + 31) / 32 * 32;
+      if (c < 64) c = 64;
+      return c > rows ? rows : c;
+    };
+    long rpc, cap_rows, subs, sub_rows;
+    for (;; ++chunks) {
+      rpc = (ncand + chunks - 1) / chunks;
+      rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
+      const long rows_per_wave = rpc / kStreamWaves;
+      subs = 1;
+      sub_rows = rows_per_wave;
+      cap_rows = cap_for(rows_per_wave);
+      if (cap_rows <= 1024 || chunks >= 64) break;
+      const long max_subs = 512 / (chunks * kStreamWaves);
+      bool ok = false;
+      for (long sb = 2; sb <= max_subs && !ok; ++sb) {
+        const long sr = ((rows_per_wave + sb - 1) / sb + 511) / 512 * 512;
+        if (cap_for(sr) <= 1024) {
+          subs = sb;
+          sub_rows = sr;
+          cap_rows = cap_for(sr);
+          rpc = sb * sr * kStreamWaves;
+          ok = true;
+        }
+      }
+      if (ok) break;
+    }
+    if (cap_rows > 1024) cap_rows = 1024;   // cannot happen for contexts up to 2^20 tokens (64 chunks of <= 2048 rows per wave)
+    p.chunks = (int)((ncand + rpc - 1) / rpc);
+    p.rows_per_chunk = (int)rpc;
+    p.subs = (int)subs;
+    p.sub_rows = (int)sub_rows;
     p.row_cap = (int)cap_rows;                // a multiple of 32
     const size_t heads = (size_t)d.batch * d.n_q_heads;
-    const size_t segs = (size_t)problems * p.n_tiles;
+    const size_t segs = (size_t)problems * p.chunks * kStreamWaves * p.subs;
+    const size_t entry_bytes = 8 + d.n_sub;   // header + code bytes
     p.off_thr = 0;
     p.off_route = (p.off_thr + heads * p.P0 * sizeof(int32_t) + 255) / 256 * 256;
     p.off_count = (p.off_route + heads * sizeof(uint32_t) + 255) / 256 * 256;
     p.off_cand = (p.off_count + segs * kSegMeta * sizeof(uint32_t) + 255) / 256 * 256;
-    p.bytes = (p.off_cand + segs * (size_t)p.row_cap * kEntryWords * sizeof(uint32_t) + 255) / 256 * 256;
+    p.bytes = (p.off_cand + segs * (size_t)p.row_cap * entry_bytes + 255) / 256 * 256;
   }
   return p;
 }
@@ -231,30 +248,24 @@ __device__ __forceinline__ void combine_thresholds(int32_t v, int n_valid, int P
   }
 }
 
-// Sum over aligned groups of 16 lanes (one DPP row), result in every lane of the group.
-__device__ __forceinline__ int32_t group16_sum(int32_t v) {
-  v = group8_sum(v);
-  v += __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, false);   // row_mirror
-  return v;
-}
-
-// Exact score of the token at `row` (its M code bytes) for one head, straight from the head's
-// [c][m] table in global memory, by one thread (used for a handful of rows only).
+// Survivor entries.  The streaming pass writes, per segment (a run of rows of one wave), row_cap
+// 8-byte headers followed by row_cap rows of code bytes.  A header packs the token position (20
+// bits: contexts are at most 2^20 tokens), the mask of the heads that want the row (4 bits) and,
+// for each head, the row's rank among the rows of its segment that the head wants (10 bits each:
+// a segment holds at most 1024 rows).
 template <int M>
-__device__ __forceinline__ int32_t score_exact_global(const uint8_t* __restrict__ row,
-                                                      const int32_t* __restrict__ head_table) {
-  int32_t s = 0;
-#pragma unroll
-  for (int qd = 0; qd < M / 16; ++qd) {
-    const uint4 w = *(const uint4*)(row + qd * 16);
-    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-    for (int t = 0; t < 16; ++t) {
-      const uint32_t c = (ww[t >> 2] >> (8 * (t & 3))) & 0xffu;
-      s += head_table[c * M + qd * 16 + t];
-    }
-  }
-  return s;
+__host__ __device__ __forceinline__ size_t segment_words(int row_cap) {
+  return (size_t)row_cap * (2 + M / 4);
+}
+// `hm20`: the head mask already shifted to bits 20..23
+__device__ __forceinline__ uint2 pack_entry_header(uint32_t pos, uint32_t hm20, const uint32_t (&rk)[4]) {
+  return make_uint2(pos | hm20 | (rk[0] << 24), (rk[0] >> 8) | (rk[1] << 2) | (rk[2] << 12) | (rk[3] << 22));
+}
+__device__ __forceinline__ uint32_t entry_pos(uint32_t w0) { return w0 & 0xfffffu; }
+__device__ __forceinline__ bool entry_wanted(uint32_t w0, int r) { return (w0 >> (20 + r)) & 1u; }
+__device__ __forceinline__ uint32_t entry_rank(uint32_t w0, uint32_t w1, int r) {
+  if (r == 0) return (w0 >> 24) | ((w1 & 3u) << 8);
+  return (w1 >> (10 * r - 8)) & 1023u;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -419,211 +430,175 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
 // RESHARED: the rows are read by more than one problem (the head groups of a KV head, placed next
 // to each other on one XCD): ordinary loads, so that the line stays in that L2 for the neighbour;
 // otherwise non-temporal loads (each row is read once).
-//
-// A workgroup owns tiles_per_chunk consecutive tiles of one problem; wave w takes every eighth of
-// them starting at the w-th, so the eight waves stream one contiguous region together.  A wave
-// works in units of 256 rows (4 per lane) with two register sets: both are requested right after
-// the workgroup's table copy has been requested (loads return in order, so the table must not
-// queue behind cold rows), and each is requested again as soon as it has been consumed, so HBM
-// streams from the first microsecond on while the table is still on its way to LDS.
 template <int M, bool RESHARED>
 __device__ __forceinline__ void stream_select_body(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
-    uint32_t* __restrict__ seg_meta, uint32_t* __restrict__ cand, int B, int Hq, int Hkv, int NG,
-    int P0, int n_chunks, int problems, int n_tiles, int tiles_per_chunk, int tile_rows, int row_cap,
-    int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink) {
+    uint32_t* __restrict__ seg_meta, uint32_t* __restrict__ cand, GridMap gm, int B, int Hq, int Hkv, int G,
+    int NG, int P0, int n_chunks, int rows_per_chunk, int subs, int sub_rows, int row_cap, int ctx_len,
+    int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
-  constexpr int U = kTileUnit / 64;   // rows per lane and unit
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   unsigned char* tbl = dyn_lds;
 
-  int chunk, prob;
-  xcd_map_sets(blockIdx.x, n_chunks, problems, NG, prob, chunk);
-  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
-  const int G = Hq / Hkv, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  int chunk, prob, b, kv, g4;
+  map_block(blockIdx.x, gm, prob, chunk);
+  split_problem(prob, gm, b, kv, g4);
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
-  const int t_begin = chunk * tiles_per_chunk, t_end = min(n_tiles, t_begin + tiles_per_chunk);
-  const int tsub = tile_rows / kTileUnit;
-  uint32_t* meta0 = seg_meta + (size_t)prob * n_tiles * kSegMeta;
-  uint32_t* cand0 = cand + (size_t)prob * n_tiles * ((size_t)row_cap * kEntryWords);
-  auto tile_row0 = [&](int t) { return (long)sr.sink_end + (long)t * tile_rows; };
+  const long begin = (long)sr.sink_end + (long)chunk * rows_per_chunk;
+  const int end = (int)min((long)sr.win_start, begin + rows_per_chunk);
+  // A wave owns a contiguous run of rows, so its survivors come out in ascending position and
+  // the segments of a problem, taken in (chunk, wave, run) order, are sorted by position.
+  const int rows_per_wave = rows_per_chunk / kStreamWaves;
+  const long wbegin = begin + (long)wv * rows_per_wave;
+  const int wend = (int)min((long)end, wbegin + rows_per_wave);
 
+  // Every (problem, chunk, wave) owns `subs` survivor segments in HBM, one per run of sub_rows of
+  // its rows: no atomics, no contention.
+  const size_t seg = (((size_t)prob * n_chunks + chunk) * kStreamWaves + wv) * subs;
+  uint32_t* my_meta = seg_meta + seg * kSegMeta;
   // thresholds of the group's heads: requested here, combined after the table copy has been issued
   const int32_t thr_lane = request_thresholds<4>(thr, (size_t)b * Hq + kv * G + g4 * kHeadsPerGroup,
                                                 G - g4 * kHeadsPerGroup, P0);
   int32_t T[4];   // padded heads never want a row
-  // This wave's tiles: t_begin + wv, + 8, ...; those that start inside the candidate range are
-  // scored (they come first), the others (a sequence shorter than the planned context) only get
-  // an empty segment header.
-  int my_tiles = 0, n_live = 0;
-  for (int t = t_begin + wv; t < t_end; t += kStreamWaves) {
-    ++my_tiles;
-    if (tile_row0(t) < sr.win_start) ++n_live;
-  }
   // The scoring loop addresses the table by absolute LDS address (it must start at 0, which holds
   // because this kernel has no static LDS).  Should a toolchain ever place it elsewhere, publish
-  // overflowing segments instead: the final kernel then takes the exact route.
+  // an overflowing segment instead: the final kernel then takes the exact route.
   const bool misplaced = (uint32_t)(uintptr_t)tbl != 0u;
-  auto publish_empty = [&](int first) {   // headers of this wave's tiles from its `first`-th on
-    for (int i = first; i < my_tiles; ++i)
-      if (lane < kSegMeta)
-        meta0[(size_t)(t_begin + wv + i * kStreamWaves) * kSegMeta + lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
-  };
-  if (tile_row0(t_begin) >= sr.win_start || misplaced) {   // nothing to score in this workgroup (uniform over it)
-    publish_empty(0);
+  if (begin >= sr.win_start || misplaced) {   // nothing to score in this chunk: empty segments
+    for (int sb = 0; sb < subs; ++sb)
+      if (lane < kSegMeta) my_meta[sb * kSegMeta + lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
     return;
   }
 
   LaneSwizzle<M> sw;
   sw.init(lane);
-  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
-  const int n_units = n_live * tsub;
-
-  struct Cursor { int t, sub; };
-  auto advance = [&](Cursor& c) {
-    if (++c.sub == tsub) {
-      c.sub = 0;
-      c.t += kStreamWaves;
-    }
-  };
-  // Rows of a unit.  Loads are never skipped, also not for a unit past the wave's last one: a load
-  // under a branch would make every later wait cover all loads in flight instead of the older
-  // register set only.  The row index is clamped into the candidate range (this workgroup has
-  // candidates), and rows past the end of a tile are masked out when they are scored.
-  uint4 rows_a[U][M / 16], rows_b[U][M / 16];
-  auto load_rows = [&](const Cursor& c, uint4 (&dst)[U][M / 16]) {
-    const long t0 = min(tile_row0(c.t), (long)sr.win_start - 1);
-    const int last = (int)min((long)sr.win_start, t0 + tile_rows) - 1;   // >= t0 >= sink_end
-    const int base = (int)t0 + c.sub * kTileUnit;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int j = base + u * 64 + lane;
-      const int jl = j < last ? j : last;
-#pragma unroll
-      for (int qd = 0; qd < M / 16; ++qd)
-        dst[u][qd] = load_global_u4<!RESHARED>(seq_codes + (size_t)jl * M + ((uint32_t)(qd * 16) ^ sw.row_swz));
-    }
-  };
-
-  int n_rows = 0;                  // entries written to the current segment by this wave (wave-uniform)
+  int n_rows = 0;                  // row entries written by this wave (wave-uniform)
   int n_head[4] = {0, 0, 0, 0};    // of which wanted by each head
-  uint32_t* my_ent = cand0;
-  auto process = [&](const Cursor& c, const uint4 (&rows)[U][M / 16]) {
-    const long t0 = tile_row0(c.t);
-    const int end = (int)min((long)sr.win_start, t0 + tile_rows);
-    const int base = (int)t0 + c.sub * kTileUnit;
-    if (c.sub == 0) {   // (wave-uniform) a new tile: a new segment
-      n_rows = 0;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) n_head[r] = 0;
-      my_ent = cand0 + (size_t)c.t * ((size_t)row_cap * kEntryWords);
-    }
-    // Scores and the per-head "reaches the threshold" wave masks are formed together, so the
-    // gathered table entries die inside this straight-line block.  The masks live in scalar
-    // registers; their popcounts cost no vector instructions.
-    uint64_t hit[U][4];
-    uint32_t a01[U], a23[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      score_coarse<M, true>(rows[u], tbl, sw, a01[u], a23[u]);
-      const uint64_t valid = __builtin_amdgcn_ballot_w64(base + u * 64 + lane < end);
-      hit[u][0] = __builtin_amdgcn_ballot_w64((int32_t)(a01[u] & 0xffffu) >= T[0]) & valid;
-      hit[u][1] = __builtin_amdgcn_ballot_w64((int32_t)(a01[u] >> 16) >= T[1]) & valid;
-      hit[u][2] = __builtin_amdgcn_ballot_w64((int32_t)(a23[u] & 0xffffu) >= T[2]) & valid;
-      hit[u][3] = __builtin_amdgcn_ballot_w64((int32_t)(a23[u] >> 16) >= T[3]) & valid;
-      if (u & 1) __builtin_amdgcn_sched_barrier(0);   // two rows' gathers at a time: bounds live registers
-    }
-    // A surviving row is written once: position and the coarse scores of the four heads (the final
-    // kernel of a head tells from them whether the head wants the row).  Slots come from the lane
-    // masks: no atomics, and the entries of a segment are in ascending position.
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint64_t any = hit[u][0] | hit[u][1] | hit[u][2] | hit[u][3];
-      if (any) {
-        if (__builtin_amdgcn_inverse_ballot_w64(any)) {
-          const int slot = (int)__builtin_amdgcn_mbcnt_hi(
-              (uint32_t)(any >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)any, (uint32_t)n_rows));
-          if (slot < row_cap) {   // rows past the capacity are dropped but still counted
-            uint32_t* e = my_ent + (size_t)slot * kEntryWords;
-            e[0] = (uint32_t)(base + u * 64 + lane);
-            e[1] = a01[u];
-            e[2] = a23[u];
-          }
-        }
-        n_rows += __popcll(any);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) n_head[r] += __popcll(hit[u][r]);
-      }
-    }
-    if (c.sub == tsub - 1 && lane < kSegMeta) {   // header of the tile's segment: entries written, rows per head
+  // A segment is row_cap 8-byte entry headers followed by row_cap rows of code bytes.
+  uint32_t* my_seg = cand + seg * segment_words<M>(row_cap);
+  uint2* my_hdr = (uint2*)my_seg;
+  uint4* my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
+  int sub = 0;   // the run (and segment) the wave is in
+  auto publish = [&](int sb, bool counted) {   // header of segment sb: rows written, rows per head
+    if (lane < kSegMeta) {
       uint32_t v = 0;
-      if (lane == 0) v = (uint32_t)n_rows;
+      if (counted) {
+        if (lane == 0) v = (uint32_t)n_rows;
 #pragma unroll
-      for (int r = 0; r < 4; ++r)
-        if (lane == 1 + r) v = (uint32_t)n_head[r];
-      meta0[(size_t)c.t * kSegMeta + lane] = v;
+        for (int r = 0; r < 4; ++r)
+          if (lane == 1 + r) v = (uint32_t)n_head[r];
+      }
+      my_meta[sb * kSegMeta + lane] = v;
     }
   };
 
-  // The table copy is requested first, then the first two units of rows; the table is put into
-  // LDS as soon as it has arrived (the rows, requested later, are still in flight then).
-  constexpr int TPT = kCentroids * M / 2 / NT;   // 16-byte pieces of the table per thread
-  int4 tv[TPT];
+  const bool has_rows = wbegin < wend;   // wave-uniform
   {
-    const LutLayout lay = lut_layout(B, Hq, Hkv, M);
-    const int4* src = (const int4*)(lut + lay.off_coarse + (size_t)prob * (kCentroids * M * 2));
-    // Both pointers pass through an empty asm, so the compiler no longer knows that they point to
-    // read-only, unaliased memory and keeps the table loads, the asm below and the row loads in
-    // this order (it otherwise issues the row loads first).
-    asm volatile("" : "+s"(src));
-    asm volatile("" : "+s"(seq_codes));
+    const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+    // Rows are read U at a time per lane, one full step ahead of their use (two register sets
+    // used alternately); loads are unconditional (row index clamped into the wave's range) so
+    // that the wait before the gathers only covers the older of the two sets in flight.
+    constexpr int U = 4;
+    constexpr int STEP = 64 * U;
+    uint4 rows_a[U][M / 16], rows_b[U][M / 16];
+    auto load_rows = [&](int base, uint4 (&dst)[U][M / 16]) {
 #pragma unroll
-    for (int k = 0; k < TPT; ++k) {
-      const uint4 v = load_global_u4<false>(src + tid + k * NT);
-      tv[k] = make_int4((int)v.x, (int)v.y, (int)v.z, (int)v.w);
-    }
-  }
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_sched_barrier(0);
-  Cursor ld{t_begin + wv, 0}, pr{t_begin + wv, 0};
-  load_rows(ld, rows_a);
-  advance(ld);
-  load_rows(ld, rows_b);
-  advance(ld);
+      for (int u = 0; u < U; ++u) {
+        const int j = base + u * 64 + lane;
+        const int jl = j < wend ? j : wend - 1;
 #pragma unroll
-  for (int k = 0; k < TPT; ++k) {
-    const int e = tid + k * NT;   // pair of entries (2 e, 2 e + 1) of the global order [half][c][16 m]
-    const int half = e / (kCentroids * 8), c = (e / 8) % kCentroids, mp = e % 8;
-    store_coarse_lds<M>(tbl, c, 16 * half + 2 * mp, tv[k]);
-  }
-  combine_thresholds<4>(thr_lane, G - g4 * kHeadsPerGroup, P0, T);
-  __syncthreads();   // (every wave of the workgroup gets here, also one without live tiles)
+        for (int qd = 0; qd < M / 16; ++qd)
+          dst[u][qd] = RESHARED ? *(const uint4*)(seq_codes + (size_t)jl * M + ((uint32_t)(qd * 16) ^ sw.row_swz))
+                                : load_stream_u4(seq_codes + (size_t)jl * M + ((uint32_t)(qd * 16) ^ sw.row_swz));
+      }
+    };
+    auto process = [&](int base, const uint4 (&rows)[U][M / 16]) {
+      // Scores and the per-head "reaches the threshold" wave masks are formed together, so the
+      // gathered table entries die inside this straight-line block.  The masks live in scalar
+      // registers; their popcounts cost no vector instructions.
+      uint64_t hit[U][4];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        uint32_t a01, a23;
+        score_coarse<M, true>(rows[u], tbl, sw, a01, a23);
+        const uint64_t valid = __builtin_amdgcn_ballot_w64(base + u * 64 + lane < wend);
+        hit[u][0] = __builtin_amdgcn_ballot_w64((int32_t)(a01 & 0xffffu) >= T[0]) & valid;
+        hit[u][1] = __builtin_amdgcn_ballot_w64((int32_t)(a01 >> 16) >= T[1]) & valid;
+        hit[u][2] = __builtin_amdgcn_ballot_w64((int32_t)(a23 & 0xffffu) >= T[2]) & valid;
+        hit[u][3] = __builtin_amdgcn_ballot_w64((int32_t)(a23 >> 16) >= T[3]) & valid;
+        if (u & 1) __builtin_amdgcn_sched_barrier(0);   // two rows' gathers at a time: bounds live registers
+      }
+      // A surviving row is written once, with the mask of the heads that want it and, for each
+      // of them, its rank among the rows of this segment that the head wants (so the final kernel
+      // can place every entry without looking at the others).
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t any = hit[u][0] | hit[u][1] | hit[u][2] | hit[u][3];
+        if (any) {
+          if (__builtin_amdgcn_inverse_ballot_w64(any)) {
+            const int slot = (int)__builtin_amdgcn_mbcnt_hi(
+                (uint32_t)(any >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)any, (uint32_t)n_rows));
+            if (slot < row_cap) {   // rows past the capacity are dropped but still counted
+              uint32_t hm = 0, rk[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                hm |= __builtin_amdgcn_inverse_ballot_w64(hit[u][r]) ? (1u << (20 + r)) : 0u;
+                rk[r] = __builtin_amdgcn_mbcnt_hi(
+                    (uint32_t)(hit[u][r] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit[u][r], (uint32_t)n_head[r]));
+              }
+              my_hdr[slot] = pack_entry_header((uint32_t)(base + u * 64 + lane), hm, rk);
+#pragma unroll
+              for (int qd = 0; qd < M / 16; ++qd)   // (row_swz: which half of the row this register holds)
+                my_codes[slot * (M / 16) + (qd ^ (int)(sw.row_swz >> 4))] = rows[u][qd];
+            }
+          }
+          n_rows += __popcll(any);
+#pragma unroll
+          for (int r = 0; r < 4; ++r) n_head[r] += __popcll(hit[u][r]);
+        }
+      }
+    };
+    // The first rows are requested before the table is copied to LDS, so both latencies overlap.
+    // (Every wave of the workgroup reaches the barrier, also one whose row range is empty.)
+    if (has_rows) load_rows((int)wbegin, rows_a);
+    load_coarse_table<M, NT>(lut, lut_layout(B, Hq, Hkv, M), prob, tbl);
+    combine_thresholds<4>(thr_lane, G - g4 * kHeadsPerGroup, P0, T);
+    __syncthreads();
+    long sub_end = wbegin + sub_rows;
 #pragma unroll 1
-  for (int v = 0; v < n_units; v += 2) {
-    process(pr, rows_a);
-    advance(pr);
-    load_rows(ld, rows_a);
-    advance(ld);
-    if (v + 1 < n_units) {
-      process(pr, rows_b);
-      advance(pr);
+    for (int base = (int)wbegin; base < wend; base += 2 * STEP) {
+      if (base >= sub_end) {   // (wave-uniform; runs are whole iterations long) on to the next segment
+        publish(sub, true);
+        ++sub;
+        sub_end += sub_rows;
+        n_rows = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) n_head[r] = 0;
+        my_seg += segment_words<M>(row_cap);
+        my_hdr = (uint2*)my_seg;
+        my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
+      }
+      load_rows(base + STEP, rows_b);
+      process(base, rows_a);
+      load_rows(base + 2 * STEP, rows_a);
+      process(base + STEP, rows_b);
     }
-    load_rows(ld, rows_b);
-    advance(ld);
   }
-  publish_empty(n_live);
+  publish(sub, true);
+  for (int sb = sub + 1; sb < subs; ++sb) publish(sb, false);   // runs beyond the end of the sequence
 }
 
 #define A2ATS_STREAM_ARGS                                                                          \
   const uint8_t *__restrict__ codes, const int32_t *__restrict__ lut,                             \
       const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ thr,                      \
-      uint32_t *__restrict__ seg_meta, uint32_t *__restrict__ cand, int B, int Hq, int Hkv, int NG,  \
-      int P0, int n_chunks, int problems, int n_tiles, int tiles_per_chunk, int tile_rows,         \
+      uint32_t *__restrict__ seg_meta, uint32_t *__restrict__ cand, GridMap gm, int B, int Hq,     \
+      int Hkv, int G, int NG, int P0, int n_chunks, int rows_per_chunk, int subs, int sub_rows,    \
       int row_cap, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink
 #define A2ATS_STREAM_PASS                                                                          \
-  codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, P0, n_chunks, problems, n_tiles,      \
-      tiles_per_chunk, tile_rows, row_cap, ctx_len, ctx_stride, top_k, window, n_sink
+  codes, lut, seq_lens, thr, seg_meta, cand, gm, B, Hq, Hkv, G, NG, P0, n_chunks, rows_per_chunk,  \
+      subs, sub_rows, row_cap, ctx_len, ctx_stride, top_k, window, n_sink
 
 // 64 KB of LDS per workgroup.  M = 16: 128 VGPRs -> 4 waves per SIMD (two workgroups per CU).
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
@@ -637,38 +612,31 @@ __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(
 void stream_select_kernel32r(A2ATS_STREAM_ARGS) { stream_select_body<32, true>(A2ATS_STREAM_PASS); }
 
 // ------------------------------------------------------------------------------------------
-// Fast route, stage 3: the K-th coarse score, exact ranking of the rows around it, ordered output
+// Fast route, stage 3: exact scores of the survivors, exact selection, ordered output
 // ------------------------------------------------------------------------------------------
-// Route words (diagnostics): 0 fast; 1 fewer survivors than K; 2 more than the LDS list holds;
-// 3 a segment overflowed; 4 the threshold is not far enough below the K-th coarse score for the
-// list to be complete; 5 more than kBandMax rows within M coarse units of the K-th coarse score.
-// 1..5 end in the exact route for that head.
 template <int M>
 __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
     const int32_t* __restrict__ thr, const uint32_t* __restrict__ seg_meta,
     const uint32_t* __restrict__ cand, uint32_t* __restrict__ route, int32_t* __restrict__ topk_idx,
-    int32_t* __restrict__ topk_count, float* __restrict__ topk_score, int B, int Hq, int Hkv, int NG,
-    int P0, int problems, int n_seg, int row_cap, int cap, int ctx_len, int64_t ctx_stride, int top_k,
+    int32_t* __restrict__ topk_count, float* __restrict__ topk_score, GridMap gm, int B, int Hq, int Hkv,
+    int G, int NG, int P0, int n_seg, int row_cap, int cap, int ctx_len, int64_t ctx_stride, int top_k,
     int window, int n_sink) {
   constexpr int NT = kExactThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ ExactLds L;
-  __shared__ uint32_t s_seg_off[kMaxTiles + 1];
-  __shared__ uint16_t s_seg_rows[kMaxTiles];
-  __shared__ uint16_t s_band_idx[kBandMax];
-  __shared__ uint32_t s_sub[32];
-  __shared__ uint32_t s_overflow, s_n_band, s_n_sure, s_ck, s_ngt;
+  __shared__ uint32_t s_seg_off[513];
+  __shared__ uint32_t s_overflow, s_small_n, s_kth;
+  __shared__ uint32_t s_small_key[kSmallList];
 
   // one workgroup per (problem, head slot), on the XCD that streamed the problem
-  int prob, r;
-  xcd_map_sets(blockIdx.x, kHeadsPerGroup, problems, NG, prob, r);
-  const int G = Hq / Hkv;
-  const int g4 = prob % NG, kv = (prob / NG) % Hkv, b = prob / (NG * Hkv);
+  int prob, r, b, kv, g4;
+  map_block(blockIdx.x, gm, prob, r);
+  split_problem(prob, gm, b, kv, g4);
   const int hg = g4 * kHeadsPerGroup + r;
   if (hg >= G) return;
-  const int bh = b * Hq + kv * G + hg, tid = threadIdx.x, lane = tid & 63;
+  const int bh = b * Hq + kv * G + hg, tid = threadIdx.x;
   const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
   int32_t* oi = topk_idx + (size_t)bh * top_k;
   float* os = topk_score ? topk_score + (size_t)bh * top_k : nullptr;
@@ -684,15 +652,16 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   const float scale = lut_scale[bh];
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
   const int32_t* head_table = lut + lay.off_exact + (size_t)bh * (kCentroids * M);
-  const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
   const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
 
-  // LDS: the head's survivors in position order -- coarse score (bit 17: winner) and position.
-  // (The exact route, if it comes to that, puts the head's table over them.)
-  uint32_t* c_key = (uint32_t*)dyn_lds;
+  // LDS carve-up: the head's exact table, survivor keys and positions
+  unsigned char* tbl = dyn_lds;
+  uint32_t* c_key = (uint32_t*)(dyn_lds + kExactLdsBytes);
   uint32_t* c_pos = c_key + cap;
 
-  // Segment headers of the problem (one per tile of the streaming pass) and the head's threshold.
+  // Everything this workgroup needs from global memory before it can look at a survivor is
+  // requested here in one go, so the latencies overlap: the segment headers, the threshold and
+  // table constants of the completeness check (used at the very end), and the head's table.
   uint32_t seg_rows = 0, my_cnt = 0;
   if (tid < n_seg) {
     const uint32_t* mt = seg_meta + ((size_t)prob * n_seg + tid) * kSegMeta;
@@ -700,212 +669,189 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     my_cnt = mt[1 + r];
   }
   const int32_t thr_lane = request_thresholds<1>(thr, (size_t)bh, 1, P0);
+  const int32_t* meta = lut + lay.off_meta + (size_t)bh * 4;
+  const int32_t m_base = meta[0], m_shift = meta[1], m_top = meta[2];
+  load_exact_table<M, NT>(head_table, tbl);
   int32_t tc1[1];
   combine_thresholds<1>(thr_lane, 1, P0, tc1);
   const int32_t tc = tc1[0];
+  const long proof_bound = (long)m_base + (((long)tc - 1 + M) << m_shift);
+  ExactSwizzle<M> sw;
+  sw.init(tid & 63);
   for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
-  if (tid < 32) s_sub[tid] = 0;
   if (tid == 0) {
     s_overflow = 0;
-    s_n_band = 0;
-    s_n_sure = 0;
+    s_small_n = 0;
+    s_kth = 0;
   }
   __syncthreads();
+  // Survivor segments of this head's problem (one per chunk, wave and run of the streaming pass,
+  // sorted by position when taken in order): exclusive prefix of the number of rows this head
+  // wants in each.  n_seg <= 512 <= NT.
+  __shared__ uint16_t s_seg_rows[512];
   if (tid < n_seg) {
     if (seg_rows > (uint32_t)row_cap) s_overflow = 1;
     s_seg_rows[tid] = (uint16_t)min(seg_rows, 65535u);
   }
-  uint32_t n_c;   // rows this head wants, over all segments
+  uint32_t n_c;
   const uint32_t my_off = block_exclusive_scan<NT>(my_cnt, L.wave_a, n_c);
   if (tid < n_seg) s_seg_off[tid] = my_off;
+  if (tid == 0) s_seg_off[n_seg] = n_c;
   __syncthreads();
   if (s_overflow || n_c > (uint32_t)cap || n_c < (uint32_t)sr.kk) {
-    if (tid == 0) route[bh] = s_overflow ? 3u : (n_c > (uint32_t)cap ? 2u : 1u);
-    exact_select_block<M>(seq_codes, head_table, meta, scale, sr, oi, os, dyn_lds, L);
+    if (tid == 0) route[bh] = s_overflow ? 3u : (n_c > (uint32_t)cap ? 2u : 1u);   // diagnostics only
+    exact_select_block<M>(seq_codes, head_table, meta, scale, sr, oi, os, tbl, L);
     return;
   }
 
-  // Every row the head wants has a coarse score in [lo, 65535]; the first histogram level spreads
-  // its 2048 bins over that range (bins of 2^shift1 <= 32 values).
-  const uint32_t lo = tc == INT32_MIN ? 0u : (uint32_t)min(max(tc, 0), 65535);
-  const int nbits = 32 - __clz(65535u - lo);
+  // Keys are taken relative to a lower bound of every survivor's exact key (a survivor's coarse
+  // score reaches the threshold, so its exact score is at least base + (Tc << s)), and the first
+  // radix level spreads the 2048 bins over the range up to the largest possible score.  Both
+  // bounds are known before any survivor is looked at, so the histogram is filled while the keys
+  // are computed.
+  const long lo_score = tc == INT32_MIN ? (long)m_base : (long)m_base + ((long)max(tc, 0) << m_shift);
+  const uint32_t klo = score_key((int32_t)max(lo_score, (long)INT32_MIN + 1));
+  const uint32_t khi = max(klo, score_key(m_top));
+  const int nbits = 32 - __clz(khi - klo);
   const int bits1 = nbits < 11 ? nbits : 11, shift1 = nbits - bits1;
   {
-    // Pass 1: the rows this head wants, out of the problem's entries, into LDS in position order.
-    // A group of tps lanes (a power of two, inside one wave) shares a segment and walks its
-    // entries tps at a time; destination = head's rows in earlier segments + rows the group has
-    // passed + rank among the lanes of this step (a ballot), so no thread waits for another.
-    int tps = 64;
-    while (tps > 1 && tps * n_seg > NT) tps >>= 1;   // n_seg <= 512: at least 2
-    const int g = tid / tps, pl = tid % tps;
-    const bool act = g < n_seg;
-    const uint32_t n_rows = act ? (uint32_t)s_seg_rows[g] : 0u, dst0 = act ? s_seg_off[g] : 0u;
-    const uint32_t max_rows = (uint32_t)__builtin_amdgcn_readlane((int)wave_max_to_last_lane(n_rows), 63);
-    const uint32_t* ent = cand + ((size_t)prob * n_seg + (act ? g : 0)) * ((size_t)row_cap * kEntryWords);
-    const int gshift = (lane / tps) * tps;
-    const uint64_t gmask = (tps == 64 ? ~0ull : ((1ull << tps) - 1ull)) << gshift;
-    const uint64_t below = gmask & ((1ull << lane) - 1ull);
-    constexpr int kInFlight = 4;
-    uint32_t running = 0;
-    for (uint32_t i0 = 0; i0 < max_rows; i0 += kInFlight * tps) {
-      uint32_t e_pos[kInFlight], e_w[kInFlight];
+    // Pass 1: pick this head's rows out of the problem's entry headers.  tps threads share a
+    // segment; every header carries its own destination (segment offset + rank), so all loads
+    // are independent and no thread waits for another.  c_key temporarily holds where the entry's
+    // code bytes are (in 16-byte units from the start of the problem's segments).
+    constexpr int kInFlight = 8;
+    const int tps = NT / n_seg > 0 ? NT / n_seg : 1;
+    const size_t seg_words = segment_words<M>(row_cap);
+    const uint32_t* seg0 = cand + (size_t)prob * n_seg * seg_words;
+    const uint32_t seg_q = (uint32_t)(seg_words / 4), codes_q = (uint32_t)row_cap / 2;   // in 16-byte units
+    for (int s_ = tid / tps; s_ < n_seg; s_ += NT / tps) {
+      const uint32_t n_rows = s_seg_rows[s_], dst0 = s_seg_off[s_];
+      const u32x2_t* hdr = (const u32x2_t*)(seg0 + (size_t)s_ * seg_words);
+      for (uint32_t i0 = tid % tps; i0 < n_rows; i0 += kInFlight * tps) {
+        // The headers are fetched together before any of them is looked at (the empty asm keeps the
+        // compiler from sinking a load behind the "does this head want the row" branch, which
+        // would serialise the latencies).
+        u32x2_t hd[kInFlight];
 #pragma unroll
-      for (int k = 0; k < kInFlight; ++k) {
-        const uint32_t i = i0 + k * tps + pl;
-        e_pos[k] = 0;
-        e_w[k] = 0;
-        if (i < n_rows) {
-          const uint32_t* e = ent + (size_t)i * kEntryWords;
-          e_pos[k] = e[0];
-          e_w[k] = e[1 + (r >> 1)];
-        }
-      }
+        for (int k = 0; k < kInFlight; ++k) hd[k] = hdr[min(i0 + k * tps, n_rows - 1)];
 #pragma unroll
-      for (int k = 0; k < kInFlight; ++k) {
-        const uint32_t i = i0 + k * tps + pl;
-        const uint32_t coarse = (r & 1) ? (e_w[k] >> 16) : (e_w[k] & 0xffffu);
-        const bool wanted = i < n_rows && (int32_t)coarse >= tc;
-        const uint64_t m = __builtin_amdgcn_ballot_w64(wanted);
-        if (wanted) {
-          const uint32_t dst = dst0 + running + (uint32_t)__popcll(m & below);
-          if (dst < n_c) {   // always true for a consistent workspace; keeps LDS writes in range whatever it holds
-            c_pos[dst] = e_pos[k];
-            c_key[dst] = coarse;
-            atomicAdd(&L.hist[min((coarse - lo) >> shift1, (uint32_t)kHistBins - 1)], 1u);
+        for (int k = 0; k < kInFlight; ++k) asm volatile("" : "+v"(hd[k]));
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) {
+          const uint32_t i = i0 + k * tps;
+          if (i < n_rows && entry_wanted(hd[k].x, r)) {
+            const uint32_t dst = dst0 + entry_rank(hd[k].x, hd[k].y, r);
+            if (dst < n_c) {   // always true for entries the streaming pass wrote; keeps LDS writes in range whatever the workspace holds
+              c_pos[dst] = entry_pos(hd[k].x);
+              c_key[dst] = (uint32_t)s_ * seg_q + codes_q + i * (M / 16);
+            }
           }
         }
-        running += (uint32_t)__popcll(m & gmask);
       }
     }
-  }
-  __syncthreads();
-
-  // The K-th largest coarse score c_K and the number of rows above it: first level by bins, then
-  // the values inside the K-th row's bin (at most 32).
-  block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, (uint32_t)sr.kk, L.wave_a, L.res);
-  const uint32_t bin1 = L.res[0], above1 = L.res[1];
-  uint32_t c_k, n_gt;
-  if (shift1 == 0) {
-    c_k = lo + bin1;
-    n_gt = above1;
-  } else {
-    const uint32_t nsub = 1u << shift1, smask = nsub - 1u;
+    __syncthreads();
+    // Pass 2: exact keys of this head's survivors, densely (no divergence), and their histogram.
+    const uint4* codes0 = (const uint4*)seg0;
+    const uint32_t last_q = (uint32_t)n_seg * seg_q - M / 16;   // the clamp below is a no-op for a consistent workspace
+#pragma unroll 2
     for (uint32_t i = tid; i < n_c; i += NT) {
-      const uint32_t rel = c_key[i] - lo;
-      if ((rel >> shift1) == bin1) atomicAdd(&s_sub[rel & smask], 1u);
-    }
-    __syncthreads();
-    if (tid < 64) {   // lane l < nsub looks at value nsub - 1 - l of the bin (values descend with the lane)
-      const uint32_t v = (uint32_t)lane < nsub ? s_sub[nsub - 1u - lane] : 0u;
-      const uint32_t incl = wave_inclusive_scan(v);
-      const uint64_t reach = __builtin_amdgcn_ballot_w64((uint32_t)lane < nsub && above1 + incl >= (uint32_t)sr.kk);
-      const int l0 = reach ? __ffsll((unsigned long long)reach) - 1 : 0;
-      if (lane == l0) {
-        s_ck = lo + (bin1 << shift1) + (nsub - 1u - (uint32_t)l0);
-        s_ngt = above1 + incl - v;
-      }
-    }
-    __syncthreads();
-    c_k = s_ck;
-    n_gt = s_ngt;
-  }
-  (void)n_gt;
-
-  // Completeness: every row with coarse score above c_K - M must be on the list, i.e. the
-  // threshold (a row is listed iff its coarse score reaches it) must not exceed c_K - M + 1.
-  if (tc != INT32_MIN && (long)c_k < (long)tc + M - 1) {
-    if (tid == 0) route[bh] = 4u;
-    exact_select_block<M>(seq_codes, head_table, meta, scale, sr, oi, os, dyn_lds, L);
-    return;
-  }
-
-  // Classes: coarse >= c_K + M wins (bit 17); c_K - M < coarse < c_K + M is decided below by exact
-  // scores; anything else loses.  Counts and band slots are aggregated per wave.
-  for (uint32_t i0 = 0; i0 < n_c; i0 += NT) {
-    const uint32_t i = i0 + tid;
-    const uint32_t key = i < n_c ? c_key[i] : 0u;
-    const bool sure = i < n_c && key >= c_k + (uint32_t)M;
-    const bool band = i < n_c && !sure && key + (uint32_t)M > c_k;
-    const uint64_t ms = __builtin_amdgcn_ballot_w64(sure), mb = __builtin_amdgcn_ballot_w64(band);
-    uint32_t base_b = 0;
-    if (lane == 0) {
-      if (ms) atomicAdd(&s_n_sure, (uint32_t)__popcll(ms));
-      if (mb) base_b = atomicAdd(&s_n_band, (uint32_t)__popcll(mb));
-    }
-    base_b = (uint32_t)__builtin_amdgcn_readfirstlane((int)base_b);
-    if (sure) c_key[i] = key | 0x20000u;
-    if (band) {
-      const uint32_t j = base_b + (uint32_t)lanes_below(mb);
-      if (j < (uint32_t)kBandMax) s_band_idx[j] = (uint16_t)i;
-    }
-  }
-  __syncthreads();
-  const uint32_t n_band = s_n_band, n_sure = s_n_sure;
-  if (n_band > (uint32_t)kBandMax) {
-    if (tid == 0) route[bh] = 5u;
-    exact_select_block<M>(seq_codes, head_table, meta, scale, sr, oi, os, dyn_lds, L);
-    return;
-  }
-  if (tid == 0) route[bh] = 0u;
-  // At most K - 1 rows have a coarse score above c_K, so fewer than K are sure winners, and at
-  // least K reach c_K, so the band holds the rest.
-  const uint32_t k_need = (uint32_t)sr.kk - n_sure;
-
-  // Exact scores of the band rows: 16 lanes per row, each adds the entries of M / 16 subspaces
-  // (code bytes from the code matrix, entries from the head's table in global memory), summed
-  // over the 16 lanes.  Keys and positions go where the histogram was.
-  uint32_t* b_key = L.hist;
-  uint32_t* b_pos = L.hist + kBandMax;
-  for (uint32_t b0 = 0; b0 < n_band; b0 += NT / 16) {
-    const uint32_t bi = b0 + (uint32_t)tid / 16u, l16 = (uint32_t)tid & 15u;
-    int32_t e = 0;
-    uint32_t pos = 0;
-    if (bi < n_band) {
-      pos = c_pos[s_band_idx[bi]];
-      const uint8_t* row = seq_codes + (size_t)pos * M;
+      const uint4* e = codes0 + min(c_key[i], last_q);
+      uint4 w[M / 16];
 #pragma unroll
-      for (int qd = 0; qd < M / 16; ++qd) {
-        const uint32_t m = l16 + 16u * qd;
-        e += head_table[(uint32_t)row[m] * M + m];
+      for (int qd = 0; qd < M / 16; ++qd) w[qd] = e[qd];
+      const uint32_t key = max(score_key(score_exact<M>(w, tbl, sw)), klo) - klo;
+      c_key[i] = key;
+      atomicAdd(&L.hist[min(key >> shift1, (uint32_t)kHistBins - 1)], 1u);
+    }
+  }
+  const uint32_t kmin = klo;
+  __syncthreads();
+  block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, (uint32_t)sr.kk, L.wave_a, L.res);
+  const uint32_t bin1 = L.res[0], above1 = L.res[1], m_bin = L.hist[bin1];
+  uint32_t k_rem = (uint32_t)sr.kk - above1;   // winners still to pick inside bin1
+  uint32_t kth;                                // K-th largest relative key
+  if (m_bin <= (uint32_t)kSmallList) {
+    // Usual case: the bin of the K-th key holds a handful of survivors; the k_rem-th largest of
+    // them is found by counting, for each member, the members above it.
+    for (uint32_t i = tid; i < n_c; i += NT)
+      if ((c_key[i] >> shift1) == bin1) s_small_key[atomicAdd(&s_small_n, 1u)] = c_key[i];
+    __syncthreads();
+    if ((uint32_t)tid < m_bin) {
+      const uint32_t key = s_small_key[tid];
+      uint32_t gt = 0, eq = 0;
+      for (uint32_t u = 0; u < m_bin; ++u) {
+        const uint32_t ku = s_small_key[u];
+        gt += ku > key ? 1u : 0u;
+        eq += ku == key ? 1u : 0u;
       }
+      if (gt < k_rem && k_rem <= gt + eq) s_kth = key;   // every thread that qualifies holds this key
     }
-    e = group16_sum(e);
-    if (bi < n_band && l16 == 0) {
-      b_key[bi] = score_key(e);
-      b_pos[bi] = pos;
+    __syncthreads();
+    kth = s_kth;
+  } else {
+    // Heavy ties: finish the radix select level by level.
+    uint32_t prefix = bin1 << shift1, mask = ((1u << bits1) - 1u) << shift1;
+    int remaining = shift1;
+    __syncthreads();
+#pragma unroll 1
+    while (remaining > 0) {
+      const int bits = remaining < 11 ? remaining : 11;
+      const int shift = remaining - bits;
+      const uint32_t dmask = (1u << bits) - 1u;
+      for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
+      __syncthreads();
+      for (uint32_t i = tid; i < n_c; i += NT) {
+        const uint32_t key = c_key[i];
+        if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
+      }
+      __syncthreads();
+      block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
+      const uint32_t bin = L.res[0], above = L.res[1];
+      k_rem -= above;
+      prefix |= bin << shift;
+      mask |= dmask << shift;
+      remaining = shift;
+      __syncthreads();
     }
+    kth = prefix;
   }
-  __syncthreads();
-  // Rank inside the band: a row wins iff fewer than k_need band rows beat it (higher exact score,
-  // or the same score at a lower position).
-  for (uint32_t bi = tid; bi < n_band; bi += NT) {
-    const uint32_t key = b_key[bi], pos = b_pos[bi];
-    uint32_t beat = 0;
-    for (uint32_t j = 0; j < n_band; ++j) {
-      const uint32_t kj = b_key[j];
-      beat += (kj > key || (kj == key && b_pos[j] < pos)) ? 1u : 0u;
-    }
-    if (beat < k_need) c_key[s_band_idx[bi]] |= 0x20000u;
-  }
-  __syncthreads();
 
-  // Winners in ascending position: the list is sorted by position, so a winner's output slot is
-  // the number of winners before it (one block scan over per-thread counts of a contiguous run).
+  // Completeness: a row that is not a survivor has coarse score <= Tc - 1, hence exact score
+  // below base + ((Tc - 1 + M) << shift).  If the K-th survivor key reaches that bound, no such
+  // row can displace (or tie with) a winner.  Otherwise redo this head by the exact route.
+  {
+    const long kth_score = (long)key_score(kth + kmin);
+    if (tc != INT32_MIN && kth_score < proof_bound) {
+      if (tid == 0) route[bh] = 4u;
+      exact_select_block<M>(seq_codes, head_table, meta, scale, sr, oi, os, tbl, L);
+      return;
+    }
+    if (tid == 0) route[bh] = 0u;
+  }
+
+  // Winners: keys above the K-th, plus the first (K - #above) survivors equal to it.  Survivors
+  // are in ascending position, so a winner's output slot is the number of winners before it:
+  // one block scan over (above, equal) counts packed in a word.
   const uint32_t per = (n_c + NT - 1) / NT;
   const uint32_t i0 = min(n_c, (uint32_t)tid * per), i1 = min(n_c, i0 + per);
   uint32_t loc = 0;
-  for (uint32_t i = i0; i < i1; ++i) loc += (c_key[i] >> 17) & 1u;
-  uint32_t tot;
-  uint32_t slot = block_exclusive_scan<NT>(loc, L.wave_b, tot);
   for (uint32_t i = i0; i < i1; ++i) {
-    if ((c_key[i] >> 17) & 1u) {
-      const uint32_t pos = c_pos[i];
-      if (slot < (uint32_t)sr.kk) {
-        oi[slot] = (int32_t)pos;
-        if (os) os[slot] = (float)score_exact_global<M>(seq_codes + (size_t)pos * M, head_table) * scale;
-      }
-      ++slot;
+    const uint32_t key = c_key[i];
+    loc += (key > kth ? 1u : 0u) + (key == kth ? 0x10000u : 0u);
+  }
+  uint32_t tot;
+  uint32_t pre = block_exclusive_scan<NT>(loc, L.wave_b, tot);
+  const uint32_t k_eq = (uint32_t)sr.kk - (tot & 0xffffu);   // equal keys that still fit
+  for (uint32_t i = i0; i < i1; ++i) {
+    const uint32_t key = c_key[i];
+    const uint32_t gt_before = pre & 0xffffu, eq_before = pre >> 16;
+    const bool win = key > kth || (key == kth && eq_before < k_eq);
+    if (win) {
+      const uint32_t slot = gt_before + min(eq_before, k_eq);
+      oi[slot] = (int32_t)c_pos[i];
+      if (os) os[slot] = (float)key_score(key + kmin) * scale;
     }
+    pre += (key > kth ? 1u : 0u) + (key == kth ? 0x10000u : 0u);
   }
 }
 
@@ -941,7 +887,7 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
   hipLaunchKernelGGL(sum_segments_kernel, dim3((heads + 255) / 256), dim3(256), 0, stream,
                      (const uint32_t*)((const unsigned char*)ws + plan.off_count),
                      (const uint32_t*)((const unsigned char*)ws + plan.off_route), cand_counts, d.batch,
-                     d.n_q_heads, d.n_kv_heads, plan.NG, plan.n_tiles);
+                     d.n_q_heads, d.n_kv_heads, plan.NG, plan.chunks * kStreamWaves * plan.subs);
   return hipGetLastError();
 }
 
@@ -994,26 +940,31 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   auto stream_kernel = M == 16 ? (NG > 1 ? stream_select_kernel16r : stream_select_kernel16)
                                : (NG > 1 ? stream_select_kernel32r : stream_select_kernel32);
   if ((err = allow_dynamic_lds(stream_kernel, coarse_bytes, NG > 1 ? s_stream_r : s_stream)) != hipSuccess) return err;
+  // (the index arithmetic of a workgroup -- which problem, which part of it -- is prepared here:
+  // its divisions would otherwise be the first thing every wave does)
+  const int G = Hq / Hkv;
+  const GridMap gm_stream = make_grid_map(plan.chunks, problems, NG, Hkv);
   if (ev_start && ev_stop) {
     // events attached to the dispatch itself: their difference is the kernel's own duration
     hipExtLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
-                          stream, ev_start, ev_stop, 0, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq,
-                          Hkv, NG, plan.P0, plan.chunks, problems, plan.n_tiles, plan.tiles_per_chunk,
-                          plan.tile_rows, plan.row_cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                          stream, ev_start, ev_stop, 0, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, B,
+                          Hq, Hkv, G, NG, plan.P0, plan.chunks, plan.rows_per_chunk, plan.subs, plan.sub_rows,
+                          plan.row_cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   } else {
     hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
-                       stream, codes, lut, seq_lens, thr, seg_meta, cand, B, Hq, Hkv, NG, plan.P0,
-                       plan.chunks, problems, plan.n_tiles, plan.tiles_per_chunk, plan.tile_rows,
-                       plan.row_cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                       stream, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, B, Hq, Hkv, G, NG, plan.P0,
+                       plan.chunks, plan.rows_per_chunk, plan.subs, plan.sub_rows, plan.row_cap,
+                       d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   }
   if ((err = hipGetLastError()) != hipSuccess) return err;
 
-  const size_t final_lds = std::max(lut1_bytes, (size_t)plan.cap * 8);
+  const size_t final_lds = lut1_bytes + (size_t)plan.cap * 8;
   if ((err = allow_dynamic_lds(final_select_kernel<M>, final_lds, s_final)) != hipSuccess) return err;
   hipLaunchKernelGGL((final_select_kernel<M>), dim3(problems * kHeadsPerGroup), dim3(kExactThreads),
                      final_lds, stream, codes, lut, lut_scale, seq_lens, thr, seg_meta, cand, route, topk_idx,
-                     topk_count, topk_score, B, Hq, Hkv, NG, plan.P0, problems, plan.n_tiles, plan.row_cap,
-                     plan.cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
+                     topk_count, topk_score, make_grid_map(kHeadsPerGroup, problems, NG, Hkv), B, Hq, Hkv, G, NG,
+                     plan.P0, plan.chunks * kStreamWaves * plan.subs, plan.row_cap, plan.cap, d.ctx_len, d.ctx_stride,
+                     top_k, window, n_sink);
   return hipGetLastError();
 }
 

@@ -40,7 +40,7 @@ def test_dims_validation_and_plans(binding):
     g7 = binding.make_dims(2, 28, 4, 128, 32, 65536)
     assert binding.lut_elems(g7) == 2 * 28 * 32 * 256 + 2 * 4 * 2 * 256 * 32 * 2 + 2 * 28 * 4
     assert binding.workspace_bytes(good, binding.OP_LUT) == 0
-    assert binding.workspace_bytes(good, binding.OP_SCORE_TOPK, 2048, 256) > 128 * 2048 * 12
+    assert binding.workspace_bytes(good, binding.OP_SCORE_TOPK, 2048, 256) > 128 * 2048 * 24
     small = binding.make_dims(1, 4, 1, 128, 16, 4096)
     assert binding.workspace_bytes(small, binding.OP_SCORE_TOPK, 128, 64) == 0
     assert binding.workspace_bytes(good, binding.OP_ENCODE) == 8 * 16 * (64 + 256 * 8) * 4
@@ -88,10 +88,10 @@ def test_dims_validation_and_plans(binding):
 
 def test_score_topk_plan_invariants(binding):
     """Host logic of a2ats_score_topk over a grid of shapes: whatever the batch, context, K and window,
-    the plan must cover every candidate row by exactly one tile of whole 256-row units, give every
-    streaming workgroup at least one tile, keep the tiles of a problem within what the final kernel
-    handles (512), and ask for a workspace that holds the segments."""
-    n_fast = n_long = 0
+    the plan must cover every candidate row exactly once with chunks of whole loop iterations, keep
+    every survivor segment within what the 10-bit ranks address, keep the segments of a problem within
+    what the final kernel handles (512), and ask for a workspace that holds them."""
+    n_fast = n_runs = 0
     for Bn, (Hq, Hkv, M), N, K, w, n_sink in itertools.product(
             (1, 2, 4, 16, 32, 64), ((4, 1, 16), (32, 8, 16), (28, 4, 32), (8, 8, 16), (64, 8, 32)),
             (4096, 16384 + 300, 32768, 65536, 131072, 500000, 1 << 20), (1, 64, 1024, 2048, 4096), (16, 256), (0, 4)):
@@ -108,19 +108,21 @@ def test_score_topk_plan_invariants(binding):
         assert p["head_groups"] == (G + 3) // 4
         assert 1 <= p["sample_parts"] <= 8 and p["sample_rows"] <= 8192
         assert p["sample_parts"] * p["sample_rows"] <= ncand
-        tiles, tpc, rows, chunks = p["tiles"], p["tiles_per_chunk"], p["rows_per_tile"], p["chunks"]
-        assert rows % 256 == 0 and rows >= 256 and 1 <= tiles <= 512
-        assert tiles * rows >= ncand > (tiles - 1) * rows                  # every row in exactly one tile, none empty
-        assert chunks * tpc >= tiles > (chunks - 1) * tpc                  # every tile in exactly one workgroup, none idle
-        if rows > 256:
-            n_long += 1
+        rpc, chunks, subs, sub_rows = p["rows_per_chunk"], p["chunks"], p["segments_per_wave"], p["rows_per_segment"]
+        assert rpc % 512 == 0 and 1 <= chunks <= 64
+        assert chunks * rpc >= ncand > (chunks - 1) * rpc                  # every row in exactly one chunk, none empty
+        assert subs >= 1 and subs * sub_rows == rpc // 8                   # a wave's rows = its runs
+        if subs > 1:
+            n_runs += 1
+            assert sub_rows % 512 == 0                                     # runs are whole loop iterations
+        assert chunks * 8 * subs <= 512                                    # segments per problem
         cap = p["segment_capacity"]
-        assert 64 <= cap <= rows and cap % 32 == 0
+        assert 64 <= cap <= 1024 and cap % 32 == 0 and cap <= sub_rows
         assert p["survivor_capacity"] >= 2 * K
         problems = Bn * Hkv * p["head_groups"]
-        segs = problems * tiles
-        assert ws >= segs * (cap * 12 + 32) + Bn * Hq * (4 * p["sample_parts"] + 4)
-    assert n_fast > 500 and n_long > 20
+        segs = problems * chunks * 8 * subs
+        assert ws >= segs * (cap * (8 + M) + 32) + Bn * Hq * (4 * p["sample_parts"] + 4)
+    assert n_fast > 500 and n_runs > 20
 
 
 def test_score_topk_workspace_covers_sink_counts(binding):
