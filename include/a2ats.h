@@ -260,6 +260,25 @@ int a2ats_sparse_attn(const a2ats_dims* dims, const void* q, const float* q_rot,
                       const int32_t* seq_lens, void* out, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * a2ats_sparse_attn for callers that cannot allocate or pass scratch memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the partial attention states that
+ * a2ats_sparse_attn keeps in `ws` live in an 8 MiB array inside the library instead (one per GPU the
+ * library runs on, held until the process ends).  The call allocates nothing.  Arguments and results
+ * are those of a2ats_sparse_attn without `ws` / `ws_bytes`.  A shape whose
+ * a2ats_workspace_bytes(dims, A2ATS_OP_ATTN, ...) figure for this n_sink exceeds 8 MiB is refused with
+ * A2ATS_ERR_WORKSPACE before anything is enqueued (at 520 bytes per query head and workgroup, that is
+ * beyond every shape of section 5: 0.7 MB at batch 4 x 32 heads, 1.4 MB at batch 32 x 28 heads).
+ * Every call on a GPU uses that GPU's array: calls that overlap in time on one GPU (different
+ * streams, different threads) race and must be serialised by the caller.  Nothing in the array has
+ * to start at zero: every state a call reads has been written by the same call.
+ */
+int a2ats_sparse_attn_static(const a2ats_dims* dims, const void* q, const float* q_rot,
+                             const void* k_cache, const void* v_cache, int kv_dtype,
+                             const int32_t* topk_idx, const int32_t* topk_count, int32_t top_k,
+                             int32_t window, int32_t n_sink, const float* cos_win, const float* sin_win,
+                             const int32_t* seq_lens, void* out, void* stream);
+
+/*
  * a2ats_sparse_attn over a PAGED key/value cache: k_pool / v_pool are pools of pages,
  *   [dev, kv_dtype n_pages * Hkv * page_size * D], page p holding page_size consecutive tokens of one
  *   sequence for all KV heads ([Hkv][page_size][D]), and

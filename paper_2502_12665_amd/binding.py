@@ -23,7 +23,8 @@ EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_wor
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_score_topk_profiled",
            "a2ats_decode_prologue", "a2ats_decode_select", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
-           "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged"]
+           "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged",
+           "a2ats_sparse_attn_static"]
 
 
 class A2atsError(RuntimeError):
@@ -77,6 +78,9 @@ def lib() -> ctypes.CDLL:
         L.a2ats_sparse_attn.restype = ctypes.c_int
         L.a2ats_sparse_attn.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, vp,
                                         vp, vp, vp, sz, vp]
+        L.a2ats_sparse_attn_static.restype = ctypes.c_int
+        L.a2ats_sparse_attn_static.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int, vp, vp, i32, i32, i32, vp, vp,
+                                               vp, vp, vp]
         L.a2ats_sparse_attn_shared.restype = ctypes.c_int
         L.a2ats_sparse_attn_shared.argtypes = L.a2ats_sparse_attn.argtypes
         L.a2ats_sparse_attn_paged.restype = ctypes.c_int
@@ -236,6 +240,15 @@ def sparse_attn(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_count, to
                                  _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _ptr(ws),
                                  0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_sparse_attn")
+
+
+def sparse_attn_static(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k: int, window: int,
+                       n_sink: int, cos_win, sin_win, seq_lens, out):
+    """sparse_attn with its scratch memory inside the library (allocates nothing; at most 8 MiB of it)."""
+    rc = lib().a2ats_sparse_attn_static(ctypes.byref(dims), _ptr(q), _ptr(q_rot), _ptr(k_cache), _ptr(v_cache),
+                                        _dtype_code(k_cache), _ptr(topk_idx), _ptr(topk_count), top_k, window,
+                                        n_sink, _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _stream())
+    _check(rc, "a2ats_sparse_attn_static")
 
 
 def build_lut_shared(dims: Dims, q, cos_b, sin_b, codebook, q_rot, lut, lut_scale):

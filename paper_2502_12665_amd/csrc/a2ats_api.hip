@@ -7,7 +7,26 @@
 #include "internal.hpp"
 
 
+// Scratch memory of a2ats_sparse_attn_static: one array per GPU the library runs on, held until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the
+// device address it yields (one per device) is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[8u << 20];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up once per device), or nullptr.
+void* scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p) return p;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+  g_scratch_ptr[dev].store(p, std::memory_order_release);   // (threads racing here store the same address)
+  return p;
+}
 
 int check_dims(const a2ats_dims* d) {
   if (!d) return A2ATS_ERR_INVALID_ARG;
@@ -396,6 +415,22 @@ int a2ats_sparse_attn(const a2ats_dims* d, const void* q, const float* q_rot, co
                       void* stream) {
   return sparse_attn_impl(d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx, topk_count, top_k, window, n_sink,
                           cos_win, sin_win, seq_lens, out, ws, ws_bytes, false, nullptr, 0, stream);
+}
+
+int a2ats_sparse_attn_static(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_cache,
+                             const void* v_cache, int kv_dtype, const int32_t* topk_idx,
+                             const int32_t* topk_count, int32_t top_k, int32_t window, int32_t n_sink,
+                             const float* cos_win, const float* sin_win, const int32_t* seq_lens, void* out,
+                             void* stream) {
+  // the size check comes first, so that a shape beyond the array is refused without touching a GPU
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
+  if (a2ats::make_attn_plan(*d, top_k, window, n_sink).bytes > sizeof(scratch)) return A2ATS_ERR_WORKSPACE;
+  void* ws = scratch_on_current_device();
+  if (!ws) return A2ATS_ERR_HIP;
+  return sparse_attn_impl(d, q, q_rot, k_cache, v_cache, kv_dtype, topk_idx, topk_count, top_k, window, n_sink,
+                          cos_win, sin_win, seq_lens, out, ws, sizeof(scratch), false, nullptr, 0, stream);
 }
 
 int a2ats_sparse_attn_paged(const a2ats_dims* d, const void* q, const float* q_rot, const void* k_pool,

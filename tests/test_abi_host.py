@@ -254,3 +254,20 @@ def test_product_path_does_not_touch_the_oracle():
                 assert "oracle" not in text.lower() or f == "synth.py", f
     text = open(os.path.join(pkg, "synth.py")).read()
     assert "import oracle" not in text and "from oracle" not in text
+
+
+def test_static_scratch_entry_point_refuses_what_does_not_fit(binding):
+    """a2ats_sparse_attn_static keeps its partial states in an 8 MiB array of the library: a shape that
+    needs more is refused with the workspace status, and bad arguments with theirs, before any GPU call."""
+    L = binding.lib()
+    null, one = ctypes.c_void_p(0), ctypes.c_void_p(16)
+
+    def call(d, top_k=64, window=1024, n_sink=0, q=one):
+        return L.a2ats_sparse_attn_static(ctypes.byref(d), q, one, one, one, 1, one, one, top_k, window, n_sink,
+                                          one, one, null, one, null)
+    huge = binding.make_dims(64, 64, 8, 128, 16, 8192)
+    assert binding.workspace_bytes(huge, binding.OP_ATTN, 64, 1024) > 8 << 20
+    assert call(huge) == -3
+    assert call(huge, top_k=-1) == -1
+    assert call(binding.make_dims(1, 4, 3, 128, 16, 64)) == -1
+
