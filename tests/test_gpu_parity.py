@@ -273,19 +273,129 @@ def _plant_similar_keys(oracle, wl, xd):
             xd["codes"][b, kv, pos.cuda()] = torch.from_numpy(codes).cuda()
 
 
+def _timed_path_against_oracle_everywhere(oracle, wl, plant=False, n_sink=0, seq_lens=None):
+    """The step bench.py times -- a2ats_decode_select (append of the current token's key under the
+    per-dimension query-aware distortion, rotation, tables, threshold sampling, streaming and final
+    kernels) followed by a2ats_sparse_attn -- at a benchmark configuration's full size, compared with
+    the oracle for EVERY (sequence, KV head) problem: the appended code row, the rotated queries, the
+    top-K index sets (near-tie rule of tests/helpers.py, exclusions counted) and the attention output.
+    The oracle runs one sequence (all its KV heads) at a time."""
+    N, K, w, G = wl.ctx_len, wl.top_k, wl.window, wl.group
+    H.log(f"{wl.name}: generating inputs on the GPU")
+    xd = synth.make_decode_inputs(wl, device="cuda")
+    if plant:
+        _plant_similar_keys(oracle, wl, xd)
+    hm = synth.make_query_second_moment(wl)
+    h_diag = hm["h_diag"].cuda()
+    new_key = xd["k"][:, :, N - 1:N, :].float().contiguous()
+    dims = H.dims_of(wl)
+    st = B.DecodeState(dims, K, w, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+    sl = None if seq_lens is None else torch.as_tensor(seq_lens, dtype=torch.int32, device="cuda")
+    st.topk_idx.fill_(-7)
+    st.topk_count.fill_(-7)
+    xd["codes"][:, :, N - 1].fill_(0xEE)   # the row the call has to write
+    H.log(f"{wl.name}: decode_select + sparse_attn")
+    B.decode_select(dims, new_key, 1, N - 1, xd["codebook"], h_diag, B.W_DIAG, xd["codes"], xd["q"], st.cos_b,
+                    st.sin_b, st.q_rot, st.lut, st.lut_scale, K, w, n_sink, sl, st.topk_idx, st.topk_count, None,
+                    st.ws)
+    stats = torch.empty(wl.batch, wl.n_q_heads, dtype=torch.int32, device="cuda")
+    B.score_topk_stats(dims, K, w, n_sink, st.ws, stats)
+    B.sparse_attn(dims, xd["q"], st.q_rot, xd["k"], xd["v"], st.topk_idx, st.topk_count, K, w, n_sink, st.cos_win,
+                  st.sin_win, sl, st.out, st.ws)
+    torch.cuda.synchronize()
+    raw = stats.cpu().numpy().astype(np.int64) & 0xFFFFFFFF
+    fallback_heads = int(((raw >> 28) != 0).sum()) if (raw != 0xFFFFFFFF).all() else -1
+    want_code, b1, b2 = oracle.encode(new_key.cpu(), xd["codebook"].cpu(), hm["h_diag"], oracle.W_DIAG,
+                                      want_margins=True)
+    n_code = H.compare_codes(xd["codes"][:, :, N - 1:N].cpu().numpy(), want_code, b1, b2)
+    g_qrot = st.q_rot.cpu().numpy().astype(np.float64)
+    g_idx, g_cnt = st.topk_idx.cpu().numpy(), st.topk_count.cpu().numpy()
+    g_out = st.out.float().cpu().numpy().astype(np.float64)
+    tol = 2e-2 if wl.kv_dtype == "bf16" else 2e-4
+    exc = slots = 0
+    worst = 0.0
+    for b in range(wl.batch):
+        x = {k: xd[k][b:b + 1].cpu() for k in ("q", "codes", "k", "v")}
+        lens_b = None if seq_lens is None else np.asarray(seq_lens[b:b + 1], dtype=np.int32)
+        sub = wl.replace(batch=1)
+        qrot = oracle.rope(x["q"], xd["inv_freq"], wl.wrope_b)
+        err = np.abs(g_qrot[b:b + 1] - qrot)
+        assert (err <= 2e-6 * np.maximum(1.0, np.abs(qrot))).all(), f"q_rot err {err.max():.3e} (b={b})"
+        scores = oracle.scores_explicit(qrot, xd["codebook"].cpu(), x["codes"], N)
+        idx, cnt, kth = oracle.topk(scores, K, w, n_sink, lens_b)
+        e, s_ = H.compare_topk(g_idx[b:b + 1], g_cnt[b:b + 1], idx, cnt, scores, kth)
+        exc += e
+        slots += s_
+        # the library's own selection goes into the oracle's attention (a near-tie swap would otherwise
+        # show up twice); identical to the oracle's whenever nothing was excluded
+        out = oracle.sparse_attn(x["q"], x["k"], x["v"], g_idx[b:b + 1], g_cnt[b:b + 1], N, w, n_sink,
+                                 xd["inv_freq"], float(wl.wrope_b), lens_b)
+        aerr = float(np.abs(g_out[b:b + 1] - out).max())
+        assert aerr <= tol, f"attention err {aerr:.3e} > {tol} (b={b})"
+        worst = max(worst, aerr)
+        if b % 4 == 0 or b == wl.batch - 1:
+            H.log(f"{wl.name}: sequences 0..{b} compared")
+    n_prob = wl.batch * wl.n_kv_heads
+    H.log(f"{wl.name}: problems compared {n_prob}/{n_prob} (query heads {wl.batch * wl.n_q_heads}), top-K exclusions "
+          f"{exc} of {slots} slots, code exclusions {n_code}, attention max err {worst:.2e}, heads on the exact "
+          f"fallback {fallback_heads}")
+    assert exc <= 1e-3 * max(slots, 1)
+    return exc
+
+
 def test_config3_batched_32k_planted(oracle):
     wl = synth.WORKLOADS["c3_batched_32k"]
     _full_size_check(oracle, wl, sample=[(0, 0), (7, 3), (15, 7)], plant=True)
+    _timed_path_against_oracle_everywhere(oracle, wl, plant=True)
 
 
 def test_config4_long_128k(oracle):
     wl = synth.WORKLOADS["c4_long_128k"]
     _full_size_check(oracle, wl, sample=[(0, 0), (1, 5), (3, 7)])
+    _timed_path_against_oracle_everywhere(oracle, wl)
+
+
+def test_config4_size_with_sinks_and_ragged_lengths(oracle):
+    """The 131072-token shape with 4 sink tokens and per-sequence lengths: a full one, one that ends
+    inside a streaming chunk, one just above the streaming route's minimum and a short one."""
+    wl = synth.WORKLOADS["c4_long_128k"].replace(name="c4_sinks_ragged", n_sink=4, seed=77)
+    _timed_path_against_oracle_everywhere(oracle, wl, n_sink=4, seq_lens=[131072, 100003, 16700, 3000])
 
 
 def test_config5_qwen7b_64k_decode(oracle):
     wl = synth.WORKLOADS["c5_qwen7b_64k"]
     _full_size_check(oracle, wl, sample=[(0, 0), (13, 2), (31, 3)])
+    _timed_path_against_oracle_everywhere(oracle, wl)
+
+
+def test_single_codebook_full_size_every_problem(oracle):
+    """The paper's own geometry (one codebook of 4096, 16-bit codes) at the 131072-token shape: one
+    decode step (tables, selection, attention), every problem against the oracle."""
+    wl = synth.WORKLOADS["p4_single_codebook_128k"]
+    N, K, w = wl.ctx_len, wl.top_k, wl.window
+    H.log(f"{wl.name}: generating inputs on the GPU")
+    xd = synth.make_decode_inputs(wl, device="cuda")
+    st = H.gpu_decode(wl, xd, want_scores=False)
+    g_idx, g_cnt = st.topk_idx.cpu().numpy(), st.topk_count.cpu().numpy()
+    g_out = st.out.float().cpu().numpy().astype(np.float64)
+    exc = slots = 0
+    worst = 0.0
+    for b in range(wl.batch):
+        x = {k: xd[k][b:b + 1].cpu() for k in ("q", "codes", "k", "v")}
+        qrot = oracle.rope(x["q"], xd["inv_freq"], wl.wrope_b)
+        # a score of this geometry is one float32 table entry: the oracle's float64 score rounded once
+        scores = oracle.scores_explicit(qrot, xd["codebook"].cpu(), x["codes"], N).astype(np.float32).astype(np.float64)
+        idx, cnt, kth = oracle.topk(scores, K, w, 0, None)
+        e, s_ = H.compare_topk(g_idx[b:b + 1], g_cnt[b:b + 1], idx, cnt, scores, kth)
+        exc += e
+        slots += s_
+        out = oracle.sparse_attn(x["q"], x["k"], x["v"], g_idx[b:b + 1], g_cnt[b:b + 1], N, w, 0, xd["inv_freq"],
+                                 float(wl.wrope_b), None)
+        worst = max(worst, float(np.abs(g_out[b:b + 1] - out).max()))
+    n_prob = wl.batch * wl.n_kv_heads
+    H.log(f"{wl.name}: problems compared {n_prob}/{n_prob}, top-K exclusions {exc} of {slots} slots, attention "
+          f"max err {worst:.2e}")
+    assert worst <= 2e-2 and exc <= 1e-3 * slots
 
 
 def test_config5_encode_then_decode(oracle):
