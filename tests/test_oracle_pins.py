@@ -577,3 +577,20 @@ def test_kmeanspp_check_follows_the_definition(oracle):
     assert oracle.kmeanspp_check(k1, None, u1, np.array([[0, 3]]), tol)[2] == [(0, 1, 2, 3)]
     assert oracle.kmeanspp_check(k1, None, u1, np.array([[0, 0]]), tol)[2] == [(0, 1, 2, 0)]   # d = 0: never drawn
 
+
+def test_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The C oracle, built with -fsanitize=address,undefined (host code; the runtime linked statically so
+    that nothing has to be preloaded), runs tests/sanitize_driver.c: every routine on small ragged cases
+    in exactly sized heap buffers.  Any report of the sanitizers fails the run."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "oracle_sanitize")
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fopenmp", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan", "-Wall", "-Wextra", "-o", exe,
+           os.path.join(root, "tests", "sanitize_driver.c"), os.path.join(root, "oracle", "a2ats_oracle.c"), "-lm"]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    env = dict(os.environ, OMP_NUM_THREADS="2", ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    assert r.returncode == 0 and "sanitize ok" in r.stdout, (r.returncode, r.stdout[-2000:], r.stderr[-4000:])
+    assert "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-4000:]
+
