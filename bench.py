@@ -48,39 +48,86 @@ class HipEvents:
         return ms.value
 
 
+def _summary_commit(path):
+    """The 'source commit:' line a summary under profiles/ carries (the commit whose build it profiled)."""
+    try:
+        for line in open(path):
+            if line.lower().startswith("source commit:"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def measured_traffic(workload):
     """HBM bytes per launch of the streaming kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE + WRITE_SIZE, each scaled by what it reads for a plain copy of known size).
     Counters cannot be collected from inside this process, so the figure is the one of the
-    profile of this same command; None if there is no summary for the workload."""
-    path = os.path.join(ROOT, "profiles", f"stream_select_{workload}_hbm_traffic.txt")
+    profile of this same command; (None, None) if there is no summary for the workload.
+    Returns (bytes, where the figure comes from)."""
+    rel = os.path.join("profiles", f"stream_select_{workload}_hbm_traffic.txt")
+    path = os.path.join(ROOT, rel)
     try:
         for line in open(path):
             if line.startswith("stream_select traffic_bytes_per_launch ="):
-                return float(line.split("=")[1])
+                return float(line.split("=")[1]), (f"{rel} (rocprofv3 --pmc runs of this command at commit "
+                                                   f"{_summary_commit(path)}; read from the file, not measured "
+                                                   "in this run)")
     except OSError:
         pass
-    return None
+    return None, None
 
 
 def profiled_kernel_us(workload):
     """Average duration of the streaming kernel in the committed rocprofv3 --kernel-trace summary of
-    this command (None if there is none): the event pair above also covers the dispatch between
-    two commands, which the profiler's kernel time does not."""
-    path = os.path.join(ROOT, "profiles", f"decode_step_{workload}_kernel_stats.txt")
+    this command ((None, None) if there is none): the event pair above also covers the dispatch
+    between two commands, which the profiler's kernel time does not.  Returns (us, source)."""
+    rel = os.path.join("profiles", f"decode_step_{workload}_kernel_stats.txt")
+    path = os.path.join(ROOT, rel)
     try:
         for line in open(path):
             if line.startswith("a2ats::stream_select_kernel"):
-                return float(line.split()[2])
+                return float(line.split()[2]), (f"{rel} (rocprofv3 --kernel-trace --stats of this command at commit "
+                                                f"{_summary_commit(path)}; read from the file, not measured in "
+                                                "this run)")
     except (OSError, ValueError, IndexError):
         pass
-    return None
+    return None, None
+
+
+def measured_machine_peaks(torch):
+    """What this machine sustains on the two access patterns of the path, measured in this run with
+    plain library kernels (for scale beside the nominal 8 TB/s): a 1 GiB device-to-device copy (bytes
+    read + written) and a gather of 2^20 random 256-byte rows out of 4 GiB (bytes read + written)."""
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * reps)]
+        for r in range(reps):
+            ev[2 * r].record()
+            fn()
+            ev[2 * r + 1].record()
+        torch.cuda.synchronize()
+        return sorted(ev[2 * r].elapsed_time(ev[2 * r + 1]) for r in range(reps))[reps // 2] * 1e-3
+    src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    t_copy = timed(lambda: dst.copy_(src))
+    del dst
+    rows = torch.empty((1 << 24, 128), dtype=torch.bfloat16, device="cuda")
+    rows.view(torch.int16).random_(0, 100)
+    idx = torch.randint(0, 1 << 24, (1 << 20,), device="cuda")
+    out = torch.empty((1 << 20, 128), dtype=torch.bfloat16, device="cuda")
+    t_gather = timed(lambda: torch.index_select(rows, 0, idx, out=out))
+    del src, rows, idx, out
+    return {"copy_1GiB_read_plus_write_GBps": 2 * (1 << 30) / t_copy / 1e9,
+            "gather_256B_rows_read_plus_write_GBps": 2 * (1 << 20) * 256 / t_gather / 1e9,
+            "note": "torch library kernels, measured in this run; nominal peak 8000 GB/s"}
 
 
 def encode_prefill(args, torch, B, synth):
     """Prefill side: a2ats_encode_keys over whole sequences under the per-dimension query-aware
     distortion.  One step = one call over all keys; the bound is the vector ALU."""
-    wl = synth.WORKLOADS["c5_qwen7b_64k"].replace(batch=8)
+    wl = synth.WORKLOADS["c5_qwen7b_64k"]   # all 32 sequences: 8.4 M keys, 4.3 GB of float32 keys
     N, M = wl.ctx_len, wl.n_sub
     hm = synth.make_query_second_moment(wl)
     cb = synth.make_codebook(wl, "cuda")
@@ -112,7 +159,7 @@ def encode_prefill(args, torch, B, synth):
         "value": n_keys / (ms * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 distances, f64 re-check of near ties", "data": "synthetic",
-        "config": {"workload": "c5_qwen7b_64k encode, 8 of 32 sequences", "keys": n_keys, "n_sub": M,
+        "config": {"workload": "c5_qwen7b_64k encode, all 32 sequences", "keys": n_keys, "n_sub": M,
                    "sub_dim": wl.sub_dim, "weights": "W_DIAG"},
         "roofline": {"kernel": "encode_kernel", "bound": "alu", "achieved": achieved, "peak": peak,
                      "unit": "T vector lane-instructions/s", "frac": achieved / peak, "traffic": None,
@@ -607,11 +654,13 @@ def main():
     e = 2 if wl.kv_dtype == "bf16" else 4
     attn_bytes = Bn * Hq * min(K, N - w) * 2 * D * e + Bn * Hkv * w * 2 * D * e
     k_us = mean(kern_us)
-    prof_us = profiled_kernel_us(wl.name)
+    prof_us, prof_src = profiled_kernel_us(wl.name)
+    traffic, traffic_src = measured_traffic(wl.name)
     achieved = kernel_bytes / (k_us * 1e-6) / 1e9 if k_us == k_us else None
 
     out = {
-        "metric": "scored keys/s (whole decode step: encode 1 key + WRoPE/LUT + score/top-K + sparse attention)",
+        "metric": "scored keys/s = B * Hkv * N code rows / time of the WHOLE decode step (encode 1 key + WRoPE/LUT + "
+                  "score/top-K + sparse attention); the rate over the score/top-K phase alone is in score_topk_phase",
         "value": rows / (ms_per_step * 1e-3),
         "unit": "keys/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -648,10 +697,13 @@ def main():
         if fast_route else None,
         "roofline": {"kernel": "stream_select_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                     "traffic": measured_traffic(wl.name), "algorithmic_bytes_per_launch": kernel_bytes,
+                     "traffic": traffic, "traffic_source": traffic_src,
+                     "algorithmic_bytes_per_launch": kernel_bytes,
                      "avg_launch_us": k_us if k_us == k_us else None,
-                     "avg_launch_us_rocprofv3": prof_us,
+                     "avg_launch_us_source": "HIP event pair attached to the kernel's dispatch, measured in this run",
+                     "avg_launch_us_rocprofv3": prof_us, "rocprofv3_source": prof_src,
                      "frac_rocprofv3": (kernel_bytes / (prof_us * 1e-6) / 1e9 / HBM_PEAK_GBS) if prof_us else None},
+        "measured_machine_peaks": measured_machine_peaks(torch),
     }
 
     if not args.no_cpu_baseline:
@@ -664,18 +716,29 @@ def main():
         inv = x["inv_freq"]
         nk = x["new_key"].cpu()
         n_rep, t0 = 0, time.perf_counter()
+        phase_s = [0.0] * 5
         while True:
+            ts = [time.perf_counter()]
             orc.encode(nk, cb, hm["h_diag"], orc.W_DIAG)
+            ts.append(time.perf_counter())
             qrot = orc.rope(xc["q"], inv, wl.wrope_b)
+            ts.append(time.perf_counter())
             sc = orc.scores_explicit(qrot, cb, xc["codes"], N)
+            ts.append(time.perf_counter())
             idx, cnt, kth = orc.topk(sc, K, w, wl.n_sink)
+            ts.append(time.perf_counter())
             orc.sparse_attn(xc["q"], xc["k"], xc["v"], idx, cnt, N, w, wl.n_sink, inv, float(wl.wrope_b))
+            ts.append(time.perf_counter())
+            for i in range(5):
+                phase_s[i] += ts[i + 1] - ts[i]
             n_rep += 1
             dt = time.perf_counter() - t0
             if dt >= args.cpu_baseline_seconds or n_rep >= 64:
                 break
         out["cpu_baseline"] = {"value": n_rep * rows / dt, "unit": "keys/s", "cores": orc.threads(),
                                "kind": "oracle",
+                               "phase_ms_per_step": dict(zip(("encode_1key", "rope", "scores_explicit", "topk_full_sort",
+                                                              "sparse_attn"), (1e3 * v / n_rep for v in phase_s))),
                                "sample": f"{n_rep} whole decode steps (encode 1 key, rotate query, explicit-"
                                          f"reconstruction scores, full-sort top-K, selective attention) over the "
                                          f"full batch of one input replica ({Bn * Hkv} (sequence, KV head) "
