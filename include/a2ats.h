@@ -388,7 +388,7 @@ int a2ats_score_topk_stats(const a2ats_dims* dims, int32_t top_k, int32_t window
  * [0] 1 if the sampled-threshold + streaming route is used (0: the exact route alone, the rest is 0),
  * [1] groups of four query heads per KV head, [2] sampling workgroups per (sequence, KV head, group),
  * [3] rows each of them scores, [4] streaming workgroups (chunks) per problem, [5] rows per chunk,
- * [6] survivor segments per wave of a chunk, [7] rows per segment, [8] entries a segment can hold,
+ * [6] survivor segments per wave of a chunk (always 1), [7] rows per segment, [8] entries a segment can hold,
  * [9] survivors per head the final kernel can hold, [10] workspace bytes the call needs, divided by 256.
  */
 int a2ats_score_topk_plan(const a2ats_dims* dims, int32_t top_k, int32_t window, int32_t n_sink, int32_t* plan);

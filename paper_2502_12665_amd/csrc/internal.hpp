@@ -20,8 +20,8 @@ struct TopkPlan {
   int sample_rows;      // rows each of them scores
   int chunks;           // streaming workgroups per (sequence, KV head, head group)
   int rows_per_chunk;
-  int subs;             // survivor segments per wave of the streaming pass (its rows in `subs` equal runs)
-  int sub_rows;         // rows per such run (a multiple of 512 when subs > 1)
+  int subs;             // survivor segments per wave of the streaming pass (always 1)
+  int sub_rows;         // rows of a wave (rows_per_chunk / 8)
   int cap;              // survivor capacity per head in the final kernel's LDS
   int row_cap;          // row entries of one survivor segment in HBM
   size_t off_thr, off_route, off_count, off_cand, bytes;

@@ -17,8 +17,8 @@
 //    2. stream_select_kernel streams all code rows: one 8-byte LDS read per code byte serves the
 //       four heads of a group (two heads per 32-bit word, 16 bits each, so one integer add
 //       accumulates two heads).  A row whose coarse score reaches the threshold of any of the
-//       heads is written once -- an 8-byte header (position, wanting heads, rank per head) and
-//       its code bytes -- to the segment of its (problem, chunk, wave) in HBM.
+//       heads is written once -- a 4-byte header (position, wanting heads) and its code bytes --
+//       to the segment of its (problem, chunk, wave) in HBM, in row order.
 //    3. final_select_kernel (one workgroup per head) collects its head's survivors (about 1.7 K),
 //       scores them exactly from the head's 32-bit table, radix-selects the exact K-th key among
 //       them, proves that no row outside the survivor list can reach that key (coarse and exact
@@ -70,58 +70,32 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     if (chunks > max_chunks) chunks = max_chunks;
     if (chunks < 1) chunks = 1;
     if (chunks > 64) chunks = 64;
-    // Survivor segments: a header and row_cap row entries each.  The sampling rule (rank r with
-    // r - 5 sqrt(r) >= K S / N, plus one per part) lets about r N / S rows per head through -- for
-    // small K much more than K -- and a row survives if any of the (up to) four heads wants it.
-    // row_cap is twice that share of a segment's rows plus 16 standard deviations of a Poisson
-    // count: survivors that come in runs (neighbouring tokens with similar scores) scatter far more
-    // between segments than independent ones.  Ranks inside a segment are stored in 10 bits, so
-    // row_cap must fit 1024: a wave whose rows would need more cuts them into `subs` runs of a
-    // multiple of 512 rows (one iteration of its loop), one segment each; the final kernel handles
-    // at most 512 segments per problem, beyond that the context is cut into more chunks instead.
+    // Survivor segments, one per (problem, chunk, wave): a header and row_cap row entries each.
+    // The sampling rule (rank r with r - 5 sqrt(r) >= K S / N, plus one per part) lets about
+    // r N / S rows per head through -- for small K much more than K -- and a row survives if any of
+    // the (up to) four heads wants it.  row_cap is twice that share of a wave's rows plus 16
+    // standard deviations of a Poisson count: survivors that come in runs (neighbouring tokens with
+    // similar scores) scatter far more between segments than independent ones.  The final kernel
+    // handles at most 512 segments per problem, i.e. 64 chunks.
     const double r0 = (double)top_k * (double)s_tot / (double)ncand;
     const double xr = 0.5 * (kSigma + std::sqrt(kSigma * kSigma + 4.0 * r0));
     const double survivors = (xr * xr + 2.0 * p.P0) / (double)s_tot * (double)ncand * 1.25;
     const double keep = std::min(1.0, 4.0 * survivors / (double)ncand);
-    auto cap_for = [&](long rows) {   // rows is a multiple of 64
-      const double mu = rows * keep;
-      long c = (long)(mu * 2.0 + 16.0 * std::sqrt(mu)) + 64;   // generous: unused capacity costs only scratch
-      c = (c + 31) / 32 * 32;
-      if (c < 64) c = 64;
-      return c > rows ? rows : c;
-    };
-    long rpc, cap_rows, subs, sub_rows;
-    for (;; ++chunks) {
-      rpc = (ncand + chunks - 1) / chunks;
-      rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
-      const long rows_per_wave = rpc / kStreamWaves;
-      subs = 1;
-      sub_rows = rows_per_wave;
-      cap_rows = cap_for(rows_per_wave);
-      if (cap_rows <= 1024 || chunks >= 64) break;
-      const long max_subs = 512 / (chunks * kStreamWaves);
-      bool ok = false;
-      for (long sb = 2; sb <= max_subs && !ok; ++sb) {
-        const long sr = ((rows_per_wave + sb - 1) / sb + 511) / 512 * 512;
-        if (cap_for(sr) <= 1024) {
-          subs = sb;
-          sub_rows = sr;
-          cap_rows = cap_for(sr);
-          rpc = sb * sr * kStreamWaves;
-          ok = true;
-        }
-      }
-      if (ok) break;
-    }
-    if (cap_rows > 1024) cap_rows = 1024;   // cannot happen for contexts up to 2^20 tokens (64 chunks of <= 2048 rows per wave)
+    long rpc = (ncand + chunks - 1) / chunks;
+    rpc = (rpc + kStreamThreads - 1) / kStreamThreads * kStreamThreads;
+    const long rows_per_wave = rpc / kStreamWaves;   // a multiple of 64
+    const double mu = rows_per_wave * keep;
+    long cap_rows = (long)(mu * 2.0 + 16.0 * std::sqrt(mu)) + 64;   // generous: unused capacity costs only scratch
+    cap_rows = (cap_rows + 31) / 32 * 32;
+    if (cap_rows > rows_per_wave) cap_rows = rows_per_wave;
     p.chunks = (int)((ncand + rpc - 1) / rpc);
     p.rows_per_chunk = (int)rpc;
-    p.subs = (int)subs;
-    p.sub_rows = (int)sub_rows;
+    p.subs = 1;                               // (one segment per wave)
+    p.sub_rows = (int)rows_per_wave;
     p.row_cap = (int)cap_rows;                // a multiple of 32
     const size_t heads = (size_t)d.batch * d.n_q_heads;
-    const size_t segs = (size_t)problems * p.chunks * kStreamWaves * p.subs;
-    const size_t entry_bytes = 8 + d.n_sub;   // header + code bytes
+    const size_t segs = (size_t)problems * p.chunks * kStreamWaves;
+    const size_t entry_bytes = 4 + d.n_sub;   // header + code bytes
     p.off_thr = 0;
     p.off_route = (p.off_thr + heads * p.P0 * sizeof(int32_t) + 255) / 256 * 256;
     p.off_count = (p.off_route + heads * sizeof(uint32_t) + 255) / 256 * 256;
@@ -249,24 +223,14 @@ __device__ __forceinline__ void combine_thresholds(int32_t v, int n_valid, int P
 }
 
 // Survivor entries.  The streaming pass writes, per segment (a run of rows of one wave), row_cap
-// 8-byte headers followed by row_cap rows of code bytes.  A header packs the token position (20
-// bits: contexts are at most 2^20 tokens), the mask of the heads that want the row (4 bits) and,
-// for each head, the row's rank among the rows of its segment that the head wants (10 bits each:
-// a segment holds at most 1024 rows).
+// 4-byte headers followed by row_cap rows of code bytes.  A header packs the token position (20
+// bits: contexts are at most 2^20 tokens) and the mask of the heads that want the row (4 bits).
 template <int M>
 __host__ __device__ __forceinline__ size_t segment_words(int row_cap) {
-  return (size_t)row_cap * (2 + M / 4);
-}
-// `hm20`: the head mask already shifted to bits 20..23
-__device__ __forceinline__ uint2 pack_entry_header(uint32_t pos, uint32_t hm20, const uint32_t (&rk)[4]) {
-  return make_uint2(pos | hm20 | (rk[0] << 24), (rk[0] >> 8) | (rk[1] << 2) | (rk[2] << 12) | (rk[3] << 22));
+  return (size_t)row_cap * (1 + M / 4);
 }
 __device__ __forceinline__ uint32_t entry_pos(uint32_t w0) { return w0 & 0xfffffu; }
 __device__ __forceinline__ bool entry_wanted(uint32_t w0, int r) { return (w0 >> (20 + r)) & 1u; }
-__device__ __forceinline__ uint32_t entry_rank(uint32_t w0, uint32_t w1, int r) {
-  if (r == 0) return (w0 >> 24) | ((w1 & 3u) << 8);
-  return (w1 >> (10 * r - 8)) & 1023u;
-}
 
 // ------------------------------------------------------------------------------------------
 // Exact route (also the fallback of the fast route)
@@ -435,7 +399,7 @@ __device__ __forceinline__ void stream_select_body(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
     uint32_t* __restrict__ seg_meta, uint32_t* __restrict__ cand, GridMap gm, int B, int Hq, int Hkv, int G,
-    int NG, int P0, int n_chunks, int rows_per_chunk, int subs, int sub_rows, int row_cap, int ctx_len,
+    int NG, int P0, int n_chunks, int rows_per_chunk, int row_cap, int ctx_len,
     int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
@@ -449,14 +413,13 @@ __device__ __forceinline__ void stream_select_body(
   const long begin = (long)sr.sink_end + (long)chunk * rows_per_chunk;
   const int end = (int)min((long)sr.win_start, begin + rows_per_chunk);
   // A wave owns a contiguous run of rows, so its survivors come out in ascending position and
-  // the segments of a problem, taken in (chunk, wave, run) order, are sorted by position.
+  // the segments of a problem, taken in (chunk, wave) order, are sorted by position.
   const int rows_per_wave = rows_per_chunk / kStreamWaves;
   const long wbegin = begin + (long)wv * rows_per_wave;
   const int wend = (int)min((long)end, wbegin + rows_per_wave);
 
-  // Every (problem, chunk, wave) owns `subs` survivor segments in HBM, one per run of sub_rows of
-  // its rows: no atomics, no contention.
-  const size_t seg = (((size_t)prob * n_chunks + chunk) * kStreamWaves + wv) * subs;
+  // Every (problem, chunk, wave) owns one survivor segment in HBM: no atomics, no contention.
+  const size_t seg = ((size_t)prob * n_chunks + chunk) * kStreamWaves + wv;
   uint32_t* my_meta = seg_meta + seg * kSegMeta;
   // thresholds of the group's heads: requested here, combined after the table copy has been issued
   const int32_t thr_lane = request_thresholds<4>(thr, (size_t)b * Hq + kv * G + g4 * kHeadsPerGroup,
@@ -466,9 +429,8 @@ __device__ __forceinline__ void stream_select_body(
   // because this kernel has no static LDS).  Should a toolchain ever place it elsewhere, publish
   // an overflowing segment instead: the final kernel then takes the exact route.
   const bool misplaced = (uint32_t)(uintptr_t)tbl != 0u;
-  if (begin >= sr.win_start || misplaced) {   // nothing to score in this chunk: empty segments
-    for (int sb = 0; sb < subs; ++sb)
-      if (lane < kSegMeta) my_meta[sb * kSegMeta + lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
+  if (begin >= sr.win_start || misplaced) {   // nothing to score in this chunk: an empty segment
+    if (lane < kSegMeta) my_meta[lane] = misplaced && lane == 0 ? 0xffffffffu : 0u;
     return;
   }
 
@@ -476,23 +438,10 @@ __device__ __forceinline__ void stream_select_body(
   sw.init(lane);
   int n_rows = 0;                  // row entries written by this wave (wave-uniform)
   int n_head[4] = {0, 0, 0, 0};    // of which wanted by each head
-  // A segment is row_cap 8-byte entry headers followed by row_cap rows of code bytes.
+  // A segment is row_cap 4-byte entry headers followed by row_cap rows of code bytes.
   uint32_t* my_seg = cand + seg * segment_words<M>(row_cap);
-  uint2* my_hdr = (uint2*)my_seg;
-  uint4* my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
-  int sub = 0;   // the run (and segment) the wave is in
-  auto publish = [&](int sb, bool counted) {   // header of segment sb: rows written, rows per head
-    if (lane < kSegMeta) {
-      uint32_t v = 0;
-      if (counted) {
-        if (lane == 0) v = (uint32_t)n_rows;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (lane == 1 + r) v = (uint32_t)n_head[r];
-      }
-      my_meta[sb * kSegMeta + lane] = v;
-    }
-  };
+  uint32_t* my_hdr = my_seg;
+  uint4* my_codes = (uint4*)(my_seg + (size_t)row_cap);
 
   const bool has_rows = wbegin < wend;   // wave-uniform
   {
@@ -530,9 +479,9 @@ __device__ __forceinline__ void stream_select_body(
         hit[u][3] = __builtin_amdgcn_ballot_w64((int32_t)(a23 >> 16) >= T[3]) & valid;
         if (u & 1) __builtin_amdgcn_sched_barrier(0);   // two rows' gathers at a time: bounds live registers
       }
-      // A surviving row is written once, with the mask of the heads that want it and, for each
-      // of them, its rank among the rows of this segment that the head wants (so the final kernel
-      // can place every entry without looking at the others).
+      // A surviving row is written once, with the mask of the heads that want it; entries keep
+      // the order of the rows, so the final kernel finds a row's place among the rows a head
+      // wants by counting mask bits.
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const uint64_t any = hit[u][0] | hit[u][1] | hit[u][2] | hit[u][3];
@@ -541,14 +490,11 @@ __device__ __forceinline__ void stream_select_body(
             const int slot = (int)__builtin_amdgcn_mbcnt_hi(
                 (uint32_t)(any >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)any, (uint32_t)n_rows));
             if (slot < row_cap) {   // rows past the capacity are dropped but still counted
-              uint32_t hm = 0, rk[4];
+              uint32_t hdr = (uint32_t)(base + u * 64 + lane);
 #pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                hm |= __builtin_amdgcn_inverse_ballot_w64(hit[u][r]) ? (1u << (20 + r)) : 0u;
-                rk[r] = __builtin_amdgcn_mbcnt_hi(
-                    (uint32_t)(hit[u][r] >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)hit[u][r], (uint32_t)n_head[r]));
-              }
-              my_hdr[slot] = pack_entry_header((uint32_t)(base + u * 64 + lane), hm, rk);
+              for (int r = 0; r < 4; ++r)
+                hdr |= __builtin_amdgcn_inverse_ballot_w64(hit[u][r]) ? (1u << (20 + r)) : 0u;
+              my_hdr[slot] = hdr;
 #pragma unroll
               for (int qd = 0; qd < M / 16; ++qd)   // (row_swz: which half of the row this register holds)
                 my_codes[slot * (M / 16) + (qd ^ (int)(sw.row_swz >> 4))] = rows[u][qd];
@@ -566,39 +512,34 @@ __device__ __forceinline__ void stream_select_body(
     load_coarse_table<M, NT>(lut, lut_layout(B, Hq, Hkv, M), prob, tbl);
     combine_thresholds<4>(thr_lane, G - g4 * kHeadsPerGroup, P0, T);
     __syncthreads();
-    long sub_end = wbegin + sub_rows;
 #pragma unroll 1
     for (int base = (int)wbegin; base < wend; base += 2 * STEP) {
-      if (base >= sub_end) {   // (wave-uniform; runs are whole iterations long) on to the next segment
-        publish(sub, true);
-        ++sub;
-        sub_end += sub_rows;
-        n_rows = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) n_head[r] = 0;
-        my_seg += segment_words<M>(row_cap);
-        my_hdr = (uint2*)my_seg;
-        my_codes = (uint4*)(my_seg + 2 * (size_t)row_cap);
-      }
       load_rows(base + STEP, rows_b);
       process(base, rows_a);
       load_rows(base + 2 * STEP, rows_a);
       process(base + STEP, rows_b);
     }
   }
-  publish(sub, true);
-  for (int sb = sub + 1; sb < subs; ++sb) publish(sb, false);   // runs beyond the end of the sequence
+  // header of the segment: rows written, rows per head
+  if (lane < kSegMeta) {
+    uint32_t v = 0;
+    if (lane == 0) v = (uint32_t)n_rows;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (lane == 1 + r) v = (uint32_t)n_head[r];
+    my_meta[lane] = v;
+  }
 }
 
 #define A2ATS_STREAM_ARGS                                                                          \
   const uint8_t *__restrict__ codes, const int32_t *__restrict__ lut,                             \
       const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ thr,                      \
       uint32_t *__restrict__ seg_meta, uint32_t *__restrict__ cand, GridMap gm, int B, int Hq,     \
-      int Hkv, int G, int NG, int P0, int n_chunks, int rows_per_chunk, int subs, int sub_rows,    \
-      int row_cap, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink
+      int Hkv, int G, int NG, int P0, int n_chunks, int rows_per_chunk, int row_cap, int ctx_len,  \
+      int64_t ctx_stride, int top_k, int window, int n_sink
 #define A2ATS_STREAM_PASS                                                                          \
   codes, lut, seq_lens, thr, seg_meta, cand, gm, B, Hq, Hkv, G, NG, P0, n_chunks, rows_per_chunk,  \
-      subs, sub_rows, row_cap, ctx_len, ctx_stride, top_k, window, n_sink
+      row_cap, ctx_len, ctx_stride, top_k, window, n_sink
 
 // 64 KB of LDS per workgroup.  M = 16: 128 VGPRs -> 4 waves per SIMD (two workgroups per CU).
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
@@ -685,13 +626,13 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     s_kth = 0;
   }
   __syncthreads();
-  // Survivor segments of this head's problem (one per chunk, wave and run of the streaming pass,
+  // Survivor segments of this head's problem (one per chunk and wave of the streaming pass,
   // sorted by position when taken in order): exclusive prefix of the number of rows this head
   // wants in each.  n_seg <= 512 <= NT.
-  __shared__ uint16_t s_seg_rows[512];
+  __shared__ uint32_t s_seg_rows[512];
   if (tid < n_seg) {
     if (seg_rows > (uint32_t)row_cap) s_overflow = 1;
-    s_seg_rows[tid] = (uint16_t)min(seg_rows, 65535u);
+    s_seg_rows[tid] = seg_rows;
   }
   uint32_t n_c;
   const uint32_t my_off = block_exclusive_scan<NT>(my_cnt, L.wave_a, n_c);
@@ -715,37 +656,45 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   const int nbits = 32 - __clz(khi - klo);
   const int bits1 = nbits < 11 ? nbits : 11, shift1 = nbits - bits1;
   {
-    // Pass 1: pick this head's rows out of the problem's entry headers.  tps threads share a
-    // segment; every header carries its own destination (segment offset + rank), so all loads
-    // are independent and no thread waits for another.  c_key temporarily holds where the entry's
-    // code bytes are (in 16-byte units from the start of the problem's segments).
+    // Pass 1: pick this head's rows out of the problem's entry headers.  A group of tps lanes
+    // (a power of two, at most a wave) takes a segment at a time; entries keep the order of their
+    // rows, so an entry's place in the head's list is the segment's offset plus the number of
+    // wanted entries before it: wave ballots restricted to the group's lanes, no exchange between
+    // threads.  All header loads of a sweep are in flight together.  c_key temporarily holds where
+    // the entry's code bytes are (in 16-byte units from the start of the problem's segments).
     constexpr int kInFlight = 8;
-    const int tps = NT / n_seg > 0 ? NT / n_seg : 1;
+    int tps = 64;
+    while (tps > 1 && tps * n_seg > NT) tps >>= 1;
+    const int lane = tid & 63, gl = lane & (tps - 1);
+    const uint64_t gmask = (tps == 64 ? ~0ull : ((1ull << tps) - 1ull)) << (lane - gl);
+    const uint64_t gbelow = gmask & ((1ull << lane) - 1ull);
     const size_t seg_words = segment_words<M>(row_cap);
     const uint32_t* seg0 = cand + (size_t)prob * n_seg * seg_words;
-    const uint32_t seg_q = (uint32_t)(seg_words / 4), codes_q = (uint32_t)row_cap / 2;   // in 16-byte units
+    const uint32_t seg_q = (uint32_t)(seg_words / 4), codes_q = (uint32_t)row_cap / 4;   // in 16-byte units
     for (int s_ = tid / tps; s_ < n_seg; s_ += NT / tps) {
-      const uint32_t n_rows = s_seg_rows[s_], dst0 = s_seg_off[s_];
-      const u32x2_t* hdr = (const u32x2_t*)(seg0 + (size_t)s_ * seg_words);
-      for (uint32_t i0 = tid % tps; i0 < n_rows; i0 += kInFlight * tps) {
+      const uint32_t n_rows = s_seg_rows[s_];
+      uint32_t dst = s_seg_off[s_];   // of the next wanted entry of the group's sweep
+      const uint32_t* hdr = seg0 + (size_t)s_ * seg_words;
+      for (uint32_t i0 = 0; i0 < n_rows; i0 += kInFlight * tps) {   // (uniform within the group)
         // The headers are fetched together before any of them is looked at (the empty asm keeps the
         // compiler from sinking a load behind the "does this head want the row" branch, which
         // would serialise the latencies).
-        u32x2_t hd[kInFlight];
+        uint32_t hd[kInFlight];
 #pragma unroll
-        for (int k = 0; k < kInFlight; ++k) hd[k] = hdr[min(i0 + k * tps, n_rows - 1)];
+        for (int k = 0; k < kInFlight; ++k) hd[k] = hdr[min(i0 + k * tps + gl, n_rows - 1)];
 #pragma unroll
         for (int k = 0; k < kInFlight; ++k) asm volatile("" : "+v"(hd[k]));
 #pragma unroll
         for (int k = 0; k < kInFlight; ++k) {
-          const uint32_t i = i0 + k * tps;
-          if (i < n_rows && entry_wanted(hd[k].x, r)) {
-            const uint32_t dst = dst0 + entry_rank(hd[k].x, hd[k].y, r);
-            if (dst < n_c) {   // always true for entries the streaming pass wrote; keeps LDS writes in range whatever the workspace holds
-              c_pos[dst] = entry_pos(hd[k].x);
-              c_key[dst] = (uint32_t)s_ * seg_q + codes_q + i * (M / 16);
-            }
+          const uint32_t i = i0 + k * tps + gl;
+          const bool want = i < n_rows && entry_wanted(hd[k], r);
+          const uint64_t wm = __builtin_amdgcn_ballot_w64(want);
+          const uint32_t at = dst + (uint32_t)__popcll(wm & gbelow);
+          if (want && at < n_c) {   // always in range for entries the streaming pass wrote; keeps LDS writes in range whatever the workspace holds
+            c_pos[at] = entry_pos(hd[k]);
+            c_key[at] = (uint32_t)s_ * seg_q + codes_q + i * (M / 16);
           }
+          dst += (uint32_t)__popcll(wm & gmask);
         }
       }
     }
@@ -887,7 +836,7 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
   hipLaunchKernelGGL(sum_segments_kernel, dim3((heads + 255) / 256), dim3(256), 0, stream,
                      (const uint32_t*)((const unsigned char*)ws + plan.off_count),
                      (const uint32_t*)((const unsigned char*)ws + plan.off_route), cand_counts, d.batch,
-                     d.n_q_heads, d.n_kv_heads, plan.NG, plan.chunks * kStreamWaves * plan.subs);
+                     d.n_q_heads, d.n_kv_heads, plan.NG, plan.chunks * kStreamWaves);
   return hipGetLastError();
 }
 
@@ -948,12 +897,12 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
     // events attached to the dispatch itself: their difference is the kernel's own duration
     hipExtLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
                           stream, ev_start, ev_stop, 0, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, B,
-                          Hq, Hkv, G, NG, plan.P0, plan.chunks, plan.rows_per_chunk, plan.subs, plan.sub_rows,
+                          Hq, Hkv, G, NG, plan.P0, plan.chunks, plan.rows_per_chunk,
                           plan.row_cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   } else {
     hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
                        stream, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, B, Hq, Hkv, G, NG, plan.P0,
-                       plan.chunks, plan.rows_per_chunk, plan.subs, plan.sub_rows, plan.row_cap,
+                       plan.chunks, plan.rows_per_chunk, plan.row_cap,
                        d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   }
   if ((err = hipGetLastError()) != hipSuccess) return err;
@@ -963,7 +912,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   hipLaunchKernelGGL((final_select_kernel<M>), dim3(problems * kHeadsPerGroup), dim3(kExactThreads),
                      final_lds, stream, codes, lut, lut_scale, seq_lens, thr, seg_meta, cand, route, topk_idx,
                      topk_count, topk_score, make_grid_map(kHeadsPerGroup, problems, NG, Hkv), B, Hq, Hkv, G, NG,
-                     plan.P0, plan.chunks * kStreamWaves * plan.subs, plan.row_cap, plan.cap, d.ctx_len, d.ctx_stride,
+                     plan.P0, plan.chunks * kStreamWaves, plan.row_cap, plan.cap, d.ctx_len, d.ctx_stride,
                      top_k, window, n_sink);
   return hipGetLastError();
 }
