@@ -167,6 +167,70 @@ def encode_prefill(args, torch, B, synth):
     }))
 
 
+def paged_codes_phase(args, torch, B, synth, wl):
+    """The score/top-K phase over a paged code matrix (pages of --paged-codes tokens scattered over a
+    pool) beside the same phase over the contiguous matrix: same tables, same results, timed by events
+    around the call, replicas cycled."""
+    R = max(1, min(args.replicas, 4))
+    page = args.paged_codes
+    dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)
+    N, K, w = wl.ctx_len, wl.top_k, wl.window
+    assert N % page == 0, "--paged-codes must divide the context length"
+    sts, reps = [], []
+    for r in range(R):
+        x = synth.make_decode_inputs(wl.replace(seed=wl.seed + r), device="cuda", with_kv=False)
+        n_slots = N // page
+        n_phys = wl.batch * n_slots + 3
+        perm = torch.randperm(n_phys, device="cuda")[: wl.batch * n_slots].reshape(wl.batch, n_slots)
+        pool = torch.zeros(n_phys, wl.n_kv_heads, page, wl.n_sub, dtype=torch.uint8, device="cuda")
+        pool[perm.reshape(-1)] = x["codes"].reshape(wl.batch, wl.n_kv_heads, n_slots, page, wl.n_sub) \
+            .permute(0, 2, 1, 3, 4).reshape(-1, wl.n_kv_heads, page, wl.n_sub)
+        x["pool"], x["table"] = pool, perm.to(torch.int32)
+        st = B.DecodeState(dims, K, w, wl.n_sink, x["q"].dtype, x["inv_freq"], wl.wrope_b)
+        B.build_lut(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, st.lut, st.lut_scale)
+        reps.append(x)
+        sts.append(st)
+    torch.cuda.synchronize()
+
+    def timed(fn):
+        ts = []
+        for i in range(args.warmup + args.steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            fn(i % R)
+            b.record()
+            b.synchronize()
+            if i >= args.warmup:
+                ts.append(a.elapsed_time(b) * 1e3)
+        return sorted(ts)[len(ts) // 2]
+
+    def flat(r):
+        x, st = reps[r], sts[r]
+        B.score_topk(dims, x["codes"], st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx, st.topk_count,
+                     st.topk_score, None, st.ws)
+
+    def paged(r):
+        x, st = reps[r], sts[r]
+        B.score_topk_paged(dims, x["pool"], x["table"], page, st.lut, st.lut_scale, K, w, wl.n_sink, None,
+                           st.topk_idx, st.topk_count, st.topk_score, None, st.ws)
+
+    flat(0)
+    torch.cuda.synchronize()
+    want = sts[0].topk_idx.clone()
+    paged(0)
+    torch.cuda.synchronize()
+    same = bool(torch.equal(want, sts[0].topk_idx))
+    t_flat, t_paged = timed(flat), timed(paged)
+    rows = wl.batch * wl.n_kv_heads * N
+    print(json.dumps({
+        "metric": "scored keys/s, score/top-K phase over a PAGED code matrix (events around the call)",
+        "value": rows / (t_paged * 1e-6), "unit": "keys/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": t_paged * 1e-3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 fixed-point scores", "data": "synthetic",
+        "config": {"workload": wl.name + " score/top-K phase", "page_size": page, "replicas_cycled": R},
+        "us_paged": t_paged, "us_contiguous": t_flat, "indices_equal_to_contiguous": same}))
+
+
 def single_codebook_encode_prefill(args, torch, B, synth, wl):
     """Prefill side in the paper's own geometry: a2ats_encode_keys over whole sequences under the full
     D x D query-aware distortion (4096 distances over 128 dimensions per key, on the matrix cores)."""
@@ -494,6 +558,9 @@ def main():
     ap.add_argument("--codebook-fit", action="store_true",
                     help="offline codebook construction (single-codebook workloads): one Lloyd iteration and one "
                          "second-moment accumulation; prints a line of its own")
+    ap.add_argument("--paged-codes", type=int, default=0,
+                    help="time the score/top-K phase over a code matrix in pages of this many tokens beside the "
+                         "contiguous one; prints a line of its own")
     ap.add_argument("--encode-prefill", action="store_true",
                     help="measure the prefill-side key encoder (configuration 5 geometry, 8 of its 32 "
                          "sequences) instead of the decode step, and print its own JSON line")
@@ -523,6 +590,9 @@ def main():
         return
     if args.group_shared:
         group_shared_step(args, torch, B, synth, wl)
+        return
+    if args.paged_codes:
+        paged_codes_phase(args, torch, B, synth, wl)
         return
     R = max(1, args.replicas)
     dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)

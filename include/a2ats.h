@@ -285,8 +285,8 @@ int a2ats_sparse_attn_static(const a2ats_dims* dims, const void* q, const float*
  *   page_table [dev, int32 B * ceil(ctx_stride / page_size)] maps (sequence b, token j) to page
  *   page_table[b][j / page_size] (row j % page_size of it).  page_size: a power of two >= 16.
  * Every page number reachable through seq_lens / ctx_len must be a valid page of the pools (not
- * checked on the device).  The code matrix of a2ats_score_topk stays contiguous per sequence (it is
- * 3-6 % of the cache bytes).  Everything else as a2ats_sparse_attn; results are identical to the
+ * checked on the device).  (a2ats_score_topk_paged reads a code matrix paged the same way.)
+ * Everything else as a2ats_sparse_attn; results are identical to the
  * contiguous layout.
  */
 int a2ats_sparse_attn_paged(const a2ats_dims* dims, const void* q, const float* q_rot, const void* k_pool,
@@ -295,6 +295,33 @@ int a2ats_sparse_attn_paged(const a2ats_dims* dims, const void* q, const float* 
                             int32_t top_k, int32_t window, int32_t n_sink, const float* cos_win,
                             const float* sin_win, const int32_t* seq_lens, void* out, void* ws,
                             size_t ws_bytes, void* stream);
+
+/*
+ * a2ats_score_topk over a PAGED code matrix (section 4.3 keeps the codes beside the key/value cache;
+ * serving stacks keep that cache in pages): code_pool [dev, uint8 n_pages * Hkv * page_size * M] holds
+ * pages of page_size consecutive tokens of one sequence for all KV heads ([Hkv][page_size][M]), and
+ * page_table [dev, int32 B * ceil(ctx_stride / page_size)] maps (sequence b, token j) to page
+ * page_table[b][j / page_size] (row j % page_size of it) -- the table and page size of
+ * a2ats_sparse_attn_paged.  page_size: a power of two >= 16.  Every page number reachable through
+ * seq_lens / ctx_len must be a valid page of the pool (not checked on the device).  Product-quantised
+ * codes only (n_sub 16 or 32; the single-codebook geometry returns A2ATS_ERR_UNSUPPORTED).  Everything
+ * else as a2ats_score_topk (same workspace size, same outputs, scores_out stays [B*Hq][ctx_stride]);
+ * results are identical to the contiguous layout.
+ */
+int a2ats_score_topk_paged(const a2ats_dims* dims, const uint8_t* code_pool, const int32_t* page_table,
+                           int32_t page_size, const int32_t* lut, const float* lut_scale, int32_t top_k,
+                           int32_t window, int32_t n_sink, const int32_t* seq_lens, int32_t* topk_idx,
+                           int32_t* topk_count, float* topk_score, float* scores_out, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/*
+ * Append path of the paged code matrix: copy the code rows of n_new freshly encoded tokens,
+ * new_codes [dev, uint8 B * Hkv * n_new * M] (what a2ats_encode_keys writes for dims with
+ * ctx_stride = n_new and pos0 = 0), to tokens pos0 .. pos0 + n_new - 1 of every sequence in code_pool
+ * through page_table (layouts as in a2ats_score_topk_paged).  pos0 + n_new <= ctx_stride.
+ */
+int a2ats_codes_to_pages(const a2ats_dims* dims, const uint8_t* new_codes, int32_t n_new, int32_t pos0,
+                         uint8_t* code_pool, const int32_t* page_table, int32_t page_size, void* stream);
 
 /*
  * Selection shared by the query heads of a KV head (grouped-query attention; the paper selects

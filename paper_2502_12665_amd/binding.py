@@ -24,7 +24,7 @@ EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_wor
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_score_topk_profiled",
            "a2ats_decode_prologue", "a2ats_decode_select", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
            "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged",
-           "a2ats_sparse_attn_static"]
+           "a2ats_sparse_attn_static", "a2ats_score_topk_paged", "a2ats_codes_to_pages"]
 
 
 class A2atsError(RuntimeError):
@@ -297,6 +297,24 @@ def sparse_attn_paged(dims: Dims, q, q_rot, k_pool, v_pool, page_table, page_siz
                                        _ptr(topk_count), top_k, window, n_sink, _ptr(cos_win), _ptr(sin_win),
                                        _ptr(seq_lens), _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_sparse_attn_paged")
+
+
+def score_topk_paged(dims: Dims, code_pool, page_table, page_size: int, lut, lut_scale, top_k: int, window: int,
+                     n_sink: int, seq_lens, topk_idx, topk_count, topk_score=None, scores_out=None,
+                     ws: Optional[torch.Tensor] = None):
+    """score_topk over a pool of code pages [page][Hkv][page_size][M] addressed through page_table [B, pages]."""
+    rc = lib().a2ats_score_topk_paged(ctypes.byref(dims), _ptr(code_pool), _ptr(page_table), page_size, _ptr(lut),
+                                      _ptr(lut_scale), top_k, window, n_sink, _ptr(seq_lens), _ptr(topk_idx),
+                                      _ptr(topk_count), _ptr(topk_score), _ptr(scores_out), _ptr(ws),
+                                      0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_score_topk_paged")
+
+
+def codes_to_pages(dims: Dims, new_codes, n_new: int, pos0: int, code_pool, page_table, page_size: int):
+    """Copy the code rows [B, Hkv, n_new, M] of freshly encoded tokens to tokens pos0.. of the paged pool."""
+    rc = lib().a2ats_codes_to_pages(ctypes.byref(dims), _ptr(new_codes), n_new, pos0, _ptr(code_pool),
+                                    _ptr(page_table), page_size, _stream())
+    _check(rc, "a2ats_codes_to_pages")
 
 
 PLAN_FIELDS = ("fast", "head_groups", "sample_parts", "sample_rows", "chunks", "rows_per_chunk",

@@ -329,17 +329,34 @@ int a2ats_decode_select(const a2ats_dims* d, const float* keys, int32_t n_new, i
       seq_lens, (int32_t*)((unsigned char*)ws + plan.off_thr), plan.P0, plan.sample_rows, top_k, window, n_sink,
       (hipStream_t)stream);
   if (e != hipSuccess) return A2ATS_ERR_HIP;
-  e = a2ats::launch_score_topk(*d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
-                               topk_score, nullptr, ws, true, (hipStream_t)stream);
+  e = a2ats::launch_score_topk(*d, codes, a2ats::CodePages{nullptr, 0, 0}, lut, lut_scale, top_k, window, n_sink,
+                               seq_lens, topk_idx, topk_count, topk_score, nullptr, ws, true, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
-static int score_topk_impl(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut, const float* lut_scale,
+// page_table null: contiguous codes.  Otherwise a pool of pages of page_size tokens.
+static int code_pages(const a2ats_dims* d, const int32_t* page_table, int32_t page_size, a2ats::CodePages* pg) {
+  pg->table = nullptr;
+  pg->pages_per_seq = 0;
+  pg->shift = 0;
+  if (!page_table) return A2ATS_OK;
+  if (page_size < 16 || (page_size & (page_size - 1))) return A2ATS_ERR_INVALID_ARG;   // a power of two >= 16
+  while ((1 << pg->shift) < page_size) ++pg->shift;
+  pg->table = page_table;
+  pg->pages_per_seq = (int32_t)((d->ctx_stride + page_size - 1) / page_size);
+  return A2ATS_OK;
+}
+
+static int score_topk_impl(const a2ats_dims* d, const uint8_t* codes, const int32_t* page_table, int32_t page_size,
+                           const int32_t* lut, const float* lut_scale,
                            int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
                            int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,
                            size_t ws_bytes, void* stream, void* ev_start, void* ev_stop) {
   int rc = check_dims(d);
   if (rc != A2ATS_OK) return rc;
+  a2ats::CodePages pg;
+  if ((rc = code_pages(d, page_table, page_size, &pg)) != A2ATS_OK) return rc;
+  if (page_table && a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
   if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
   if (!codes || !lut || !lut_scale || !topk_count) return A2ATS_ERR_INVALID_ARG;
   if (top_k > 0 && !topk_idx) return A2ATS_ERR_INVALID_ARG;
@@ -355,7 +372,7 @@ static int score_topk_impl(const a2ats_dims* d, const uint8_t* codes, const int3
   if (plan.fast) {
     if (!ws || misaligned16(ws) || ws_bytes < plan.bytes) return A2ATS_ERR_WORKSPACE;
   }
-  const hipError_t e = a2ats::launch_score_topk(*d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
+  const hipError_t e = a2ats::launch_score_topk(*d, codes, pg, lut, lut_scale, top_k, window, n_sink, seq_lens,
                                                 topk_idx, topk_count, topk_score, scores_out, ws, false,
                                                 (hipStream_t)stream, (hipEvent_t)ev_start, (hipEvent_t)ev_stop);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
@@ -365,8 +382,35 @@ int a2ats_score_topk(const a2ats_dims* d, const uint8_t* codes, const int32_t* l
                      int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
                      int32_t* topk_idx, int32_t* topk_count, float* topk_score, float* scores_out, void* ws,
                      size_t ws_bytes, void* stream) {
-  return score_topk_impl(d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
+  return score_topk_impl(d, codes, nullptr, 0, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
                          topk_score, scores_out, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int a2ats_score_topk_paged(const a2ats_dims* d, const uint8_t* code_pool, const int32_t* page_table,
+                           int32_t page_size, const int32_t* lut, const float* lut_scale, int32_t top_k,
+                           int32_t window, int32_t n_sink, const int32_t* seq_lens, int32_t* topk_idx,
+                           int32_t* topk_count, float* topk_score, float* scores_out, void* ws, size_t ws_bytes,
+                           void* stream) {
+  if (!page_table) return A2ATS_ERR_INVALID_ARG;
+  return score_topk_impl(d, code_pool, page_table, page_size, lut, lut_scale, top_k, window, n_sink, seq_lens,
+                         topk_idx, topk_count, topk_score, scores_out, ws, ws_bytes, stream, nullptr, nullptr);
+}
+
+int a2ats_codes_to_pages(const a2ats_dims* d, const uint8_t* new_codes, int32_t n_new, int32_t pos0,
+                         uint8_t* code_pool, const int32_t* page_table, int32_t page_size, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (!page_table || !code_pool || n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride)
+    return A2ATS_ERR_INVALID_ARG;
+  if (n_new > 0 && !new_codes) return A2ATS_ERR_INVALID_ARG;
+  a2ats::CodePages pg;
+  if ((rc = code_pages(d, page_table, page_size, &pg)) != A2ATS_OK) return rc;
+  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;   // (16-bit codes are not paged)
+  const int row_bytes = d->n_sub;
+  if (misaligned16(new_codes) || misaligned16(code_pool)) return A2ATS_ERR_INVALID_ARG;
+  const hipError_t e = a2ats::launch_codes_to_pages(*d, new_codes, n_new, pos0, row_bytes, code_pool, pg,
+                                                    (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }
 
 int a2ats_score_topk_profiled(const a2ats_dims* d, const uint8_t* codes, const int32_t* lut,
@@ -375,7 +419,7 @@ int a2ats_score_topk_profiled(const a2ats_dims* d, const uint8_t* codes, const i
                               float* topk_score, float* scores_out, void* ws, size_t ws_bytes, void* stream,
                               void* ev_start, void* ev_stop) {
   if (!ev_start || !ev_stop) return A2ATS_ERR_INVALID_ARG;
-  return score_topk_impl(d, codes, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
+  return score_topk_impl(d, codes, nullptr, 0, lut, lut_scale, top_k, window, n_sink, seq_lens, topk_idx, topk_count,
                          topk_score, scores_out, ws, ws_bytes, stream, ev_start, ev_stop);
 }
 

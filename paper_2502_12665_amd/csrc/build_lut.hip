@@ -291,7 +291,7 @@ __global__ __launch_bounds__(kLutThreads) void decode_select_prologue_kernel(
     build_lut_body<DS, QBF16>(prob, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG, p == 0,
                               dyn_lds);
     __syncthreads();
-    sample_threshold_body<M, kLutThreads, true>(prob, p, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, P0, sample_rows,
+    sample_threshold_body<M, kLutThreads, true>(prob, p, codes, CodePages{nullptr, 0, 0}, lut, seq_lens, thr, B, Hq, Hkv, NG, P0, sample_rows,
                                                 ctx_len, ctx_stride, top_k, window, n_sink, dyn_lds);
     return;
   }

@@ -113,7 +113,7 @@ __device__ __forceinline__ void load_coarse_table(const int32_t* __restrict__ lu
 // the caller has put the table there already (and synchronised), otherwise it is copied from `lut`.
 template <int M, int NT, bool TABLE_IN_LDS>
 __device__ __forceinline__ void sample_threshold_body(
-    int prob, int p, const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
+    int prob, int p, const uint8_t* __restrict__ codes, const CodePages& pg, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int B, int Hq, int Hkv, int NG,
     int P0, int sample_rows, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink,
     unsigned char* tbl) {
@@ -152,7 +152,7 @@ __device__ __forceinline__ void sample_threshold_body(
   // score >> 5 indexes a 2048-bin histogram directly.
   LaneSwizzle<M> sw;
   sw.init(lane);
-  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  const SeqCodes seq_codes = seq_codes_of<M>(codes, pg, b, kv, Hkv, ctx_stride);
   // The sample is taken in runs of kRun consecutive rows (one 128-byte line of the code matrix),
   // the runs evenly spread over the candidates: HBM delivers whole lines, so a row-strided sample
   // would fetch eight times the bytes it uses.  (For rows drawn independently, as in the synthetic
@@ -167,9 +167,9 @@ __device__ __forceinline__ void sample_threshold_body(
     j = max(sr.sink_end, j & ~(kRun - 1)) + (int)(g % kRun);
     j = min(j, sr.win_start - 1);
     uint4 w[M / 16];
+    const uint8_t* row = row_ptr<M>(seq_codes, j);
 #pragma unroll
-    for (int qd = 0; qd < M / 16; ++qd)
-      w[qd] = *(const uint4*)(seq_codes + (size_t)j * M + ((uint32_t)(qd * 16) ^ sw.row_swz));
+    for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(row + ((uint32_t)(qd * 16) ^ sw.row_swz));
     uint32_t a01, a23;
     score_coarse<M, false>(w, tbl, sw, a01, a23);
     atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);

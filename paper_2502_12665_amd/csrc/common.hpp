@@ -256,6 +256,52 @@ __device__ __forceinline__ SeqRange seq_range(int ctx_len, const int32_t* seq_le
   return r;
 }
 
+// Optional paging of the code matrix.  With `table` set, `codes` is a pool of pages
+// [page][Hkv][page_size][M] (page_size = 1 << shift tokens of one sequence, all KV heads) and
+// table[b * pages_per_seq + (j >> shift)] names the page that holds token j of sequence b;
+// with `table` null the matrix is contiguous, [B][Hkv][ctx_stride][M].
+struct CodePages {
+  const int32_t* table;
+  int32_t pages_per_seq;
+  int32_t shift;
+};
+// The code rows of one (sequence, KV head).
+struct SeqCodes {
+  const uint8_t* base;    // contiguous: row 0; paged: the KV head's rows inside page 0 of the pool
+  const int32_t* pages;   // paged: the sequence's page numbers (else null)
+  uint32_t shift, mask;   // token -> (page slot j >> shift, row j & mask)
+  size_t page_bytes;      // bytes from a page to the next
+};
+template <int M>
+__device__ __forceinline__ SeqCodes seq_codes_of(const uint8_t* codes, const CodePages& pg, int b, int kv, int Hkv,
+                                                 int64_t ctx_stride) {
+  SeqCodes s;
+  if (pg.table == nullptr) {
+    s.base = codes + ((size_t)b * Hkv + kv) * (size_t)ctx_stride * M;
+    s.pages = nullptr;
+    s.shift = 0;
+    s.mask = 0;
+    s.page_bytes = 0;
+  } else {
+    s.base = codes + ((size_t)kv << pg.shift) * M;
+    s.pages = pg.table + (size_t)b * pg.pages_per_seq;
+    s.shift = (uint32_t)pg.shift;
+    s.mask = (1u << pg.shift) - 1u;
+    s.page_bytes = ((size_t)Hkv << pg.shift) * M;
+  }
+  return s;
+}
+// Row j given the number of its page (paged layout only).
+template <int M>
+__device__ __forceinline__ const uint8_t* row_in_page(const SeqCodes& s, int page, int j) {
+  return s.base + (size_t)page * s.page_bytes + (size_t)((uint32_t)j & s.mask) * M;
+}
+template <int M>
+__device__ __forceinline__ const uint8_t* row_ptr(const SeqCodes& s, int j) {
+  if (s.pages == nullptr) return s.base + (size_t)j * M;
+  return row_in_page<M>(s, s.pages[(uint32_t)j >> s.shift], j);
+}
+
 // 16-byte load that tells the caches the line will not be reused (streamed data).
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 load_stream_u4(const void* p) {

@@ -9,6 +9,7 @@
 #include <stdint.h>
 
 #include "a2ats.h"
+#include "common.hpp"
 
 namespace a2ats {
 
@@ -57,7 +58,8 @@ inline hipError_t allow_dynamic_lds(K kernel, size_t bytes, LdsSlot* slot) {
 hipError_t launch_build_lut(const a2ats_dims& d, const void* q, int q_dtype, const float* cos_b,
                             const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
                             float* lut_scale, hipStream_t stream);
-hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const int32_t* lut,
+// `pg.table` null: `codes` is the contiguous matrix; else a pool of pages (see CodePages).
+hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const CodePages& pg, const int32_t* lut,
                              const float* lut_scale, int top_k, int window, int n_sink,
                              const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
                              float* topk_score, float* scores_out, void* ws, bool presampled, hipStream_t stream,
@@ -127,5 +129,9 @@ hipError_t launch_second_moment(const a2ats_dims& d, const float* q_rot, int64_t
 hipError_t launch_codebook_update(const a2ats_dims& d, const float* keys, int n_new, int pos0, const void* codes,
                                   const float* codebook, float* codebook_out, int32_t* counts_out, void* ws,
                                   hipStream_t stream);
+
+// Copy freshly encoded code rows [B][Hkv][n_new][row_bytes] to tokens pos0 .. pos0 + n_new - 1 of a paged pool.
+hipError_t launch_codes_to_pages(const a2ats_dims& d, const uint8_t* rows, int n_new, int pos0, int row_bytes,
+                                 uint8_t* pool, const CodePages& pg, hipStream_t stream);
 
 }  // namespace a2ats

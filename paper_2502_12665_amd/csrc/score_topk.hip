@@ -247,7 +247,7 @@ struct ExactLds {
 // out_idx[0..kk) ascending (and out_score); the caller has written the count and the -1 padding.
 // Requires sr.kk >= 1.
 template <int M>
-__device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
+__device__ void exact_select_block(const SeqCodes& seq_codes,
                                    const int32_t* __restrict__ head_table,
                                    const int32_t* __restrict__ meta, float scale,
                                    const SeqRange& sr, int32_t* __restrict__ out_idx,
@@ -277,7 +277,7 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       __syncthreads();
       for (int j = lo + tid; j < hi; j += NT) {
-        const uint32_t key = score_key(score_exact_row<M>(seq_codes + (size_t)j * M, tbl, sw)) - k_lo;
+        const uint32_t key = score_key(score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw)) - k_lo;
         if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
       }
       __syncthreads();
@@ -301,7 +301,7 @@ __device__ void exact_select_block(const uint8_t* __restrict__ seq_codes,
     int32_t s = 0;
     uint32_t gt = 0, eq = 0;
     if (j < hi) {
-      s = score_exact_row<M>(seq_codes + (size_t)j * M, tbl, sw);
+      s = score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw);
       const uint32_t key = score_key(s);
       gt = take_all ? 1u : (key > kth ? 1u : 0u);
       eq = take_all ? 0u : (key == kth ? 1u : 0u);
@@ -326,7 +326,7 @@ __global__ __launch_bounds__(kExactThreads) void select_exact_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
     int32_t* __restrict__ topk_idx, int32_t* __restrict__ topk_count,
-    float* __restrict__ topk_score, int B, int Hq, int Hkv, int ctx_len, int64_t ctx_stride,
+    float* __restrict__ topk_score, CodePages pg, int B, int Hq, int Hkv, int ctx_len, int64_t ctx_stride,
     int top_k, int window, int n_sink) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ ExactLds L;
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(kExactThreads) void select_exact_kernel(
   }
   if (sr.kk == 0) return;
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
-  exact_select_block<M>(codes + ((size_t)b * Hkv + kv) * ctx_stride * M,
+  exact_select_block<M>(seq_codes_of<M>(codes, pg, b, kv, Hkv, ctx_stride),
                         lut + lay.off_exact + (size_t)bh * (kCentroids * M), lut + lay.off_meta + (size_t)bh * 4,
                         lut_scale[bh], sr, oi, os, dyn_lds, L);
 }
@@ -354,7 +354,7 @@ template <int M>
 __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
-    float* __restrict__ scores_out, int B, int Hq, int Hkv, int ctx_len, int64_t ctx_stride) {
+    float* __restrict__ scores_out, CodePages pg, int B, int Hq, int Hkv, int ctx_len, int64_t ctx_stride) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   unsigned char* tbl = dyn_lds;
   const int bh = blockIdx.y, b = bh / Hq, h = bh % Hq;
@@ -366,10 +366,10 @@ __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
   __syncthreads();
   int n = seq_lens ? seq_lens[b] : ctx_len;
   n = n < 0 ? 0 : (n > ctx_len ? ctx_len : n);
-  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  const SeqCodes seq_codes = seq_codes_of<M>(codes, pg, b, kv, Hkv, ctx_stride);
   const float sc = lut_scale[bh];
   for (int j = blockIdx.x * kStreamThreads + threadIdx.x; j < n; j += gridDim.x * kStreamThreads)
-    scores_out[(size_t)bh * ctx_stride + j] = (float)score_exact_row<M>(seq_codes + (size_t)j * M, tbl, sw) * sc;
+    scores_out[(size_t)bh * ctx_stride + j] = (float)score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw) * sc;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -378,13 +378,13 @@ __global__ __launch_bounds__(kStreamThreads) void score_dense_kernel(
 template <int M>
 __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
-    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int B, int Hq, int Hkv, int NG,
-    int P0, int sample_rows, int problems, int ctx_len, int64_t ctx_stride, int top_k, int window,
+    const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, CodePages pg, int B, int Hq, int Hkv,
+    int NG, int P0, int sample_rows, int problems, int ctx_len, int64_t ctx_stride, int top_k, int window,
     int n_sink) {
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   int p, prob;
   xcd_map_sets(blockIdx.x, P0, problems, NG, prob, p);
-  sample_threshold_body<M, kSampleThreads, false>(prob, p, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, P0, sample_rows,
+  sample_threshold_body<M, kSampleThreads, false>(prob, p, codes, pg, lut, seq_lens, thr, B, Hq, Hkv, NG, P0, sample_rows,
                                                   ctx_len, ctx_stride, top_k, window, n_sink, dyn_lds);
 }
 
@@ -394,11 +394,15 @@ __global__ __launch_bounds__(kSampleThreads) void sample_threshold_kernel(
 // RESHARED: the rows are read by more than one problem (the head groups of a KV head, placed next
 // to each other on one XCD): ordinary loads, so that the line stays in that L2 for the neighbour;
 // otherwise non-temporal loads (each row is read once).
-template <int M, bool RESHARED>
+// PAGED: the code rows live in a pool of pages; the page numbers of the workgroup's chunk are
+// staged in LDS behind the table (up to kPageSlice of them, else they are read from the page table
+// row by row), and rows are read with ordinary loads.
+constexpr int kPageSlice = 2048;
+template <int M, bool RESHARED, bool PAGED>
 __device__ __forceinline__ void stream_select_body(
     const uint8_t* __restrict__ codes, const int32_t* __restrict__ lut,
     const int32_t* __restrict__ seq_lens, const int32_t* __restrict__ thr,
-    uint32_t* __restrict__ seg_meta, uint32_t* __restrict__ cand, GridMap gm, int B, int Hq, int Hkv, int G,
+    uint32_t* __restrict__ seg_meta, uint32_t* __restrict__ cand, GridMap gm, CodePages pg, int B, int Hq, int Hkv, int G,
     int NG, int P0, int n_chunks, int rows_per_chunk, int row_cap, int ctx_len,
     int64_t ctx_stride, int top_k, int window, int n_sink) {
   constexpr int NT = kStreamThreads;
@@ -445,22 +449,33 @@ __device__ __forceinline__ void stream_select_body(
 
   const bool has_rows = wbegin < wend;   // wave-uniform
   {
-    const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+    const SeqCodes seq_codes = seq_codes_of<M>(codes, pg, b, kv, Hkv, ctx_stride);
+    int32_t* pg_lds = (int32_t*)(dyn_lds + kCoarseLdsBytes);
+    const int pg0 = PAGED ? (int)((uint32_t)begin >> seq_codes.shift) : 0;                  // first page slot of the chunk
+    const int n_pg = PAGED ? (int)((uint32_t)(end - 1) >> seq_codes.shift) - pg0 + 1 : 0;   // (begin < end here)
+    const bool pg_staged = PAGED && n_pg <= kPageSlice;
     // Rows are read U at a time per lane, one full step ahead of their use (two register sets
     // used alternately); loads are unconditional (row index clamped into the wave's range) so
     // that the wait before the gathers only covers the older of the two sets in flight.
     constexpr int U = 4;
     constexpr int STEP = 64 * U;
     uint4 rows_a[U][M / 16], rows_b[U][M / 16];
-    auto load_rows = [&](int base, uint4 (&dst)[U][M / 16]) {
+    auto load_rows = [&](int base, uint4 (&dst)[U][M / 16], bool pages_in_lds) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int j = base + u * 64 + lane;
         const int jl = j < wend ? j : wend - 1;
+        const uint8_t* row;
+        if (PAGED) {
+          const int slot = (int)((uint32_t)jl >> seq_codes.shift);
+          row = row_in_page<M>(seq_codes, pages_in_lds ? pg_lds[slot - pg0] : seq_codes.pages[slot], jl);
+        } else {
+          row = seq_codes.base + (size_t)jl * M;
+        }
 #pragma unroll
         for (int qd = 0; qd < M / 16; ++qd)
-          dst[u][qd] = RESHARED ? *(const uint4*)(seq_codes + (size_t)jl * M + ((uint32_t)(qd * 16) ^ sw.row_swz))
-                                : load_stream_u4(seq_codes + (size_t)jl * M + ((uint32_t)(qd * 16) ^ sw.row_swz));
+          dst[u][qd] = (RESHARED || PAGED) ? *(const uint4*)(row + ((uint32_t)(qd * 16) ^ sw.row_swz))
+                                           : load_stream_u4(row + ((uint32_t)(qd * 16) ^ sw.row_swz));
       }
     };
     auto process = [&](int base, const uint4 (&rows)[U][M / 16]) {
@@ -508,15 +523,17 @@ __device__ __forceinline__ void stream_select_body(
     };
     // The first rows are requested before the table is copied to LDS, so both latencies overlap.
     // (Every wave of the workgroup reaches the barrier, also one whose row range is empty.)
-    if (has_rows) load_rows((int)wbegin, rows_a);
+    if (has_rows) load_rows((int)wbegin, rows_a, false);
     load_coarse_table<M, NT>(lut, lut_layout(B, Hq, Hkv, M), prob, tbl);
+    if (pg_staged)
+      for (int i = tid; i < n_pg; i += NT) pg_lds[i] = seq_codes.pages[pg0 + i];
     combine_thresholds<4>(thr_lane, G - g4 * kHeadsPerGroup, P0, T);
     __syncthreads();
 #pragma unroll 1
     for (int base = (int)wbegin; base < wend; base += 2 * STEP) {
-      load_rows(base + STEP, rows_b);
+      load_rows(base + STEP, rows_b, pg_staged);
       process(base, rows_a);
-      load_rows(base + 2 * STEP, rows_a);
+      load_rows(base + 2 * STEP, rows_a, pg_staged);
       process(base + STEP, rows_b);
     }
   }
@@ -534,23 +551,28 @@ __device__ __forceinline__ void stream_select_body(
 #define A2ATS_STREAM_ARGS                                                                          \
   const uint8_t *__restrict__ codes, const int32_t *__restrict__ lut,                             \
       const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ thr,                      \
-      uint32_t *__restrict__ seg_meta, uint32_t *__restrict__ cand, GridMap gm, int B, int Hq,     \
-      int Hkv, int G, int NG, int P0, int n_chunks, int rows_per_chunk, int row_cap, int ctx_len,  \
-      int64_t ctx_stride, int top_k, int window, int n_sink
+      uint32_t *__restrict__ seg_meta, uint32_t *__restrict__ cand, GridMap gm, CodePages pg,      \
+      int B, int Hq, int Hkv, int G, int NG, int P0, int n_chunks, int rows_per_chunk,             \
+      int row_cap, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink
 #define A2ATS_STREAM_PASS                                                                          \
-  codes, lut, seq_lens, thr, seg_meta, cand, gm, B, Hq, Hkv, G, NG, P0, n_chunks, rows_per_chunk,  \
-      row_cap, ctx_len, ctx_stride, top_k, window, n_sink
+  codes, lut, seq_lens, thr, seg_meta, cand, gm, pg, B, Hq, Hkv, G, NG, P0, n_chunks,              \
+      rows_per_chunk, row_cap, ctx_len, ctx_stride, top_k, window, n_sink
 
-// 64 KB of LDS per workgroup.  M = 16: 128 VGPRs -> 4 waves per SIMD (two workgroups per CU).
+// 64 KB of LDS per workgroup (72 KB with a staged page slice).  M = 16: 128 VGPRs -> 4 waves per
+// SIMD (two workgroups per CU).
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void stream_select_kernel16(A2ATS_STREAM_ARGS) { stream_select_body<16, false>(A2ATS_STREAM_PASS); }
+void stream_select_kernel16(A2ATS_STREAM_ARGS) { stream_select_body<16, false, false>(A2ATS_STREAM_PASS); }
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
-void stream_select_kernel16r(A2ATS_STREAM_ARGS) { stream_select_body<16, true>(A2ATS_STREAM_PASS); }
+void stream_select_kernel16r(A2ATS_STREAM_ARGS) { stream_select_body<16, true, false>(A2ATS_STREAM_PASS); }
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
+void stream_select_kernel16p(A2ATS_STREAM_ARGS) { stream_select_body<16, true, true>(A2ATS_STREAM_PASS); }
 // M = 32: twice the row registers.
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
-void stream_select_kernel32(A2ATS_STREAM_ARGS) { stream_select_body<32, false>(A2ATS_STREAM_PASS); }
+void stream_select_kernel32(A2ATS_STREAM_ARGS) { stream_select_body<32, false, false>(A2ATS_STREAM_PASS); }
 __global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
-void stream_select_kernel32r(A2ATS_STREAM_ARGS) { stream_select_body<32, true>(A2ATS_STREAM_PASS); }
+void stream_select_kernel32r(A2ATS_STREAM_ARGS) { stream_select_body<32, true, false>(A2ATS_STREAM_PASS); }
+__global__ __launch_bounds__(kStreamThreads) __attribute__((amdgpu_waves_per_eu(2, 4)))
+void stream_select_kernel32p(A2ATS_STREAM_ARGS) { stream_select_body<32, true, true>(A2ATS_STREAM_PASS); }
 
 // ------------------------------------------------------------------------------------------
 // Fast route, stage 3: exact scores of the survivors, exact selection, ordered output
@@ -561,9 +583,9 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
     const float* __restrict__ lut_scale, const int32_t* __restrict__ seq_lens,
     const int32_t* __restrict__ thr, const uint32_t* __restrict__ seg_meta,
     const uint32_t* __restrict__ cand, uint32_t* __restrict__ route, int32_t* __restrict__ topk_idx,
-    int32_t* __restrict__ topk_count, float* __restrict__ topk_score, GridMap gm, int B, int Hq, int Hkv,
-    int G, int NG, int P0, int n_seg, int row_cap, int cap, int ctx_len, int64_t ctx_stride, int top_k,
-    int window, int n_sink) {
+    int32_t* __restrict__ topk_count, float* __restrict__ topk_score, GridMap gm, CodePages pg, int B,
+    int Hq, int Hkv, int G, int NG, int P0, int n_seg, int row_cap, int cap, int ctx_len, int64_t ctx_stride,
+    int top_k, int window, int n_sink) {
   constexpr int NT = kExactThreads;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   __shared__ ExactLds L;
@@ -593,7 +615,7 @@ __global__ __launch_bounds__(kExactThreads) void final_select_kernel(
   const float scale = lut_scale[bh];
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
   const int32_t* head_table = lut + lay.off_exact + (size_t)bh * (kCentroids * M);
-  const uint8_t* seq_codes = codes + ((size_t)b * Hkv + kv) * ctx_stride * M;
+  const SeqCodes seq_codes = seq_codes_of<M>(codes, pg, b, kv, Hkv, ctx_stride);
 
   // LDS carve-up: the head's exact table, survivor keys and positions
   unsigned char* tbl = dyn_lds;
@@ -842,7 +864,7 @@ hipError_t copy_topk_stats(const a2ats_dims& d, int top_k, int window, int n_sin
 
 template <int M>
 static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan, const uint8_t* codes,
-                                      const int32_t* lut, const float* lut_scale, int top_k, int window,
+                                      const CodePages& pg, const int32_t* lut, const float* lut_scale, int top_k, int window,
                                       int n_sink, const int32_t* seq_lens, int32_t* topk_idx,
                                       int32_t* topk_count, float* topk_score, float* scores_out,
                                       void* ws, bool presampled, hipStream_t stream, hipEvent_t ev_start,
@@ -852,7 +874,7 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   const size_t coarse_bytes = (size_t)kCoarseLdsBytes;
   const size_t lut1_bytes = kExactLdsBytes;
   hipError_t err;
-  static LdsSlot s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_stream_r[16], s_final[16];
+  static LdsSlot s_dense[16], s_exact[16], s_sample[16], s_stream[16], s_stream_r[16], s_stream_p[16], s_final[16];
   if (heads == 0) return hipSuccess;
 
   if (scores_out) {
@@ -860,14 +882,14 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
     int gx = (d.ctx_len + kStreamThreads * 8 - 1) / (kStreamThreads * 8);
     gx = gx < 1 ? 1 : gx;
     hipLaunchKernelGGL((score_dense_kernel<M>), dim3(gx, heads), dim3(kStreamThreads), lut1_bytes, stream,
-                       codes, lut, lut_scale, seq_lens, scores_out, B, Hq, Hkv, d.ctx_len, d.ctx_stride);
+                       codes, lut, lut_scale, seq_lens, scores_out, pg, B, Hq, Hkv, d.ctx_len, d.ctx_stride);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
 
   if (!plan.fast) {
     if ((err = allow_dynamic_lds(select_exact_kernel<M>, lut1_bytes, s_exact)) != hipSuccess) return err;
     hipLaunchKernelGGL((select_exact_kernel<M>), dim3(heads), dim3(kExactThreads), lut1_bytes, stream,
-                       codes, lut, lut_scale, seq_lens, topk_idx, topk_count, topk_score, B, Hq, Hkv,
+                       codes, lut, lut_scale, seq_lens, topk_idx, topk_count, topk_score, pg, B, Hq, Hkv,
                        d.ctx_len, d.ctx_stride, top_k, window, n_sink);
     return hipGetLastError();
   }
@@ -881,27 +903,32 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   if (!presampled) {   // (the fused decode launch has written the thresholds already)
     if ((err = allow_dynamic_lds(sample_threshold_kernel<M>, coarse_bytes, s_sample)) != hipSuccess) return err;
     hipLaunchKernelGGL((sample_threshold_kernel<M>), dim3(plan.P0 * problems), dim3(kSampleThreads),
-                       coarse_bytes, stream, codes, lut, seq_lens, thr, B, Hq, Hkv, NG, plan.P0, plan.sample_rows,
+                       coarse_bytes, stream, codes, lut, seq_lens, thr, pg, B, Hq, Hkv, NG, plan.P0, plan.sample_rows,
                        problems, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
     if ((err = hipGetLastError()) != hipSuccess) return err;
   }
 
-  auto stream_kernel = M == 16 ? (NG > 1 ? stream_select_kernel16r : stream_select_kernel16)
-                               : (NG > 1 ? stream_select_kernel32r : stream_select_kernel32);
-  if ((err = allow_dynamic_lds(stream_kernel, coarse_bytes, NG > 1 ? s_stream_r : s_stream)) != hipSuccess) return err;
+  const bool paged = pg.table != nullptr;
+  auto stream_kernel = paged ? (M == 16 ? stream_select_kernel16p : stream_select_kernel32p)
+                             : (M == 16 ? (NG > 1 ? stream_select_kernel16r : stream_select_kernel16)
+                                        : (NG > 1 ? stream_select_kernel32r : stream_select_kernel32));
+  const size_t stream_lds = coarse_bytes + (paged ? (size_t)kPageSlice * sizeof(int32_t) : 0);
+  if ((err = allow_dynamic_lds(stream_kernel, stream_lds, paged ? s_stream_p : (NG > 1 ? s_stream_r : s_stream))) !=
+      hipSuccess)
+    return err;
   // (the index arithmetic of a workgroup -- which problem, which part of it -- is prepared here:
   // its divisions would otherwise be the first thing every wave does)
   const int G = Hq / Hkv;
   const GridMap gm_stream = make_grid_map(plan.chunks, problems, NG, Hkv);
   if (ev_start && ev_stop) {
     // events attached to the dispatch itself: their difference is the kernel's own duration
-    hipExtLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
-                          stream, ev_start, ev_stop, 0, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, B,
+    hipExtLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), stream_lds,
+                          stream, ev_start, ev_stop, 0, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, pg, B,
                           Hq, Hkv, G, NG, plan.P0, plan.chunks, plan.rows_per_chunk,
                           plan.row_cap, d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   } else {
-    hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), coarse_bytes,
-                       stream, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, B, Hq, Hkv, G, NG, plan.P0,
+    hipLaunchKernelGGL(stream_kernel, dim3(plan.chunks * problems), dim3(kStreamThreads), stream_lds,
+                       stream, codes, lut, seq_lens, thr, seg_meta, cand, gm_stream, pg, B, Hq, Hkv, G, NG, plan.P0,
                        plan.chunks, plan.rows_per_chunk, plan.row_cap,
                        d.ctx_len, d.ctx_stride, top_k, window, n_sink);
   }
@@ -911,23 +938,44 @@ static hipError_t launch_score_topk_m(const a2ats_dims& d, const TopkPlan& plan,
   if ((err = allow_dynamic_lds(final_select_kernel<M>, final_lds, s_final)) != hipSuccess) return err;
   hipLaunchKernelGGL((final_select_kernel<M>), dim3(problems * kHeadsPerGroup), dim3(kExactThreads),
                      final_lds, stream, codes, lut, lut_scale, seq_lens, thr, seg_meta, cand, route, topk_idx,
-                     topk_count, topk_score, make_grid_map(kHeadsPerGroup, problems, NG, Hkv), B, Hq, Hkv, G, NG,
+                     topk_count, topk_score, make_grid_map(kHeadsPerGroup, problems, NG, Hkv), pg, B, Hq, Hkv, G, NG,
                      plan.P0, plan.chunks * kStreamWaves, plan.row_cap, plan.cap, d.ctx_len, d.ctx_stride,
                      top_k, window, n_sink);
   return hipGetLastError();
 }
 
-hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const int32_t* lut,
+__global__ void codes_to_pages_kernel(const uint8_t* __restrict__ rows, uint8_t* __restrict__ pool, CodePages pg,
+                                      int Hkv, int n_new, int pos0, int row_bytes, int total) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;   // one 4-byte word of one row
+  const int wpr = row_bytes / 4;
+  if (i >= total) return;
+  const int w = i % wpr, r = i / wpr, t = r % n_new, bkv = r / n_new, kv = bkv % Hkv, b = bkv / Hkv;
+  const int j = pos0 + t;
+  const size_t page = (size_t)pg.table[(size_t)b * pg.pages_per_seq + (j >> pg.shift)];
+  const size_t dst = ((page * Hkv + kv) << pg.shift) + (size_t)(j & ((1 << pg.shift) - 1));
+  ((uint32_t*)(pool + dst * row_bytes))[w] = ((const uint32_t*)(rows + (size_t)r * row_bytes))[w];
+}
+
+hipError_t launch_codes_to_pages(const a2ats_dims& d, const uint8_t* rows, int n_new, int pos0, int row_bytes,
+                                 uint8_t* pool, const CodePages& pg, hipStream_t stream) {
+  const long total = (long)d.batch * d.n_kv_heads * n_new * (row_bytes / 4);
+  if (total == 0) return hipSuccess;
+  hipLaunchKernelGGL(codes_to_pages_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, rows, pool,
+                     pg, d.n_kv_heads, n_new, pos0, row_bytes, (int)total);
+  return hipGetLastError();
+}
+
+hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const CodePages& pg, const int32_t* lut,
                              const float* lut_scale, int top_k, int window, int n_sink,
                              const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
                              float* topk_score, float* scores_out, void* ws, bool presampled,
                              hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const TopkPlan plan = make_topk_plan(d, top_k, window, n_sink);
   if (d.n_sub == 16)
-    return launch_score_topk_m<16>(d, plan, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
+    return launch_score_topk_m<16>(d, plan, codes, pg, lut, lut_scale, top_k, window, n_sink, seq_lens,
                                    topk_idx, topk_count, topk_score, scores_out, ws, presampled, stream,
                                    ev_start, ev_stop);
-  return launch_score_topk_m<32>(d, plan, codes, lut, lut_scale, top_k, window, n_sink, seq_lens,
+  return launch_score_topk_m<32>(d, plan, codes, pg, lut, lut_scale, top_k, window, n_sink, seq_lens,
                                  topk_idx, topk_count, topk_score, scores_out, ws, presampled, stream,
                                  ev_start, ev_stop);
 }

@@ -268,3 +268,33 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit(binding):
     assert call(huge, top_k=-1) == -1
     assert call(binding.make_dims(1, 4, 3, 128, 16, 64)) == -1
 
+
+
+def test_paged_code_entry_points_check_their_arguments(binding):
+    """a2ats_score_topk_paged and a2ats_codes_to_pages refuse a missing page table, a page size that is
+    not a power of two of at least 16, the single-codebook geometry and rows outside the token capacity --
+    all on the host, before any GPU call."""
+    L = binding.lib()
+    null, one = ctypes.c_void_p(0), ctypes.c_void_p(16)
+    d = binding.make_dims(1, 8, 2, 128, 16, 4096)
+
+    def topk(d, table=one, page=16, top_k=64):
+        return L.a2ats_score_topk_paged(ctypes.byref(d), one, table, page, one, one, top_k, 64, 0, null, one, one,
+                                        null, null, null, ctypes.c_size_t(0), null)
+    assert topk(d, table=null) == -1
+    for bad in (0, 8, 24, 100, -16):
+        assert topk(d, page=bad) == -1
+    assert topk(d, top_k=-1) == -1
+    single = binding.make_dims(1, 8, 2, 128, 1, 4096, n_centroids=4096)
+    assert topk(single) == -2
+    big = binding.make_dims(4, 32, 8, 128, 16, 131072)       # streaming route: the workspace is checked too
+    assert topk(big, top_k=2048) == -3
+
+    def scatter(d, n_new=1, pos0=0, table=one, page=16, rows=one, pool=one):
+        return L.a2ats_codes_to_pages(ctypes.byref(d), rows, n_new, pos0, pool, table, page, null)
+    assert scatter(d, table=null) == -1
+    assert scatter(d, page=48) == -1
+    assert scatter(d, n_new=2, pos0=4095) == -1
+    assert scatter(d, n_new=-1) == -1
+    assert scatter(d, rows=null) == -1
+    assert scatter(single) == -2

@@ -1134,3 +1134,91 @@ def test_paged_kv_cache(oracle, page_size):
     want = oracle.sparse_attn(x["q"], x["k"], x["v"], st.topk_idx.cpu().numpy(), st.topk_count.cpu().numpy(),
                               wl.ctx_len, wl.window, 4, x["inv_freq"], float(wl.wrope_b), np.asarray(lens, dtype=np.int32))
     assert np.abs(st.out.float().cpu().numpy().astype(np.float64) - want).max() <= 2e-2
+
+
+def _page_codes(codes_cpu, page_size, seed, spare=5):
+    """Scatter a contiguous code matrix [B, Hkv, stride, M] over a pool of pages [page][Hkv][page_size][M]
+    (a random page per (sequence, slot), the pool larger than needed and poisoned elsewhere)."""
+    Bn, Hkv, stride, M = codes_cpu.shape
+    n_slots = stride // page_size
+    n_phys = Bn * n_slots + spare
+    perm = torch.randperm(n_phys, generator=torch.Generator().manual_seed(seed))[: Bn * n_slots].reshape(Bn, n_slots)
+    pool = torch.full((n_phys, Hkv, page_size, M), 0xEE, dtype=torch.uint8)
+    pages = codes_cpu.reshape(Bn, Hkv, n_slots, page_size, M).permute(0, 2, 1, 3, 4)
+    pool[perm.reshape(-1)] = pages.reshape(-1, Hkv, page_size, M)
+    return pool.cuda(), perm.to(torch.int32).cuda()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("case", ["exact_route", "stream_m16", "stream_m32_two_groups", "stream_long_chunks"])
+def test_paged_code_matrix(case):
+    """The code matrix in a pool of pages reached through a page table (the page table of the paged key/value
+    cache): indices, counts, scores of the winners, the dense scores and the survivor statistics must equal
+    those of the contiguous layout bit for bit -- on the exact route, on the streaming route with the page
+    numbers staged in LDS (M = 16; M = 32 with two head groups per KV head) and with page numbers read from
+    the table (chunks longer than the staged slice), with sinks and ragged lengths."""
+    if case == "exact_route":
+        wl, stride, lens, page_sizes = synth.Workload("pg1", 3, 8, 2, 128, 16, 5000, 200, 100, n_sink=4, seed=31), 5120, [5000, 1234, 40], (16, 256)
+    elif case == "stream_m16":
+        wl, stride, lens, page_sizes = synth.Workload("pg2", 3, 8, 2, 128, 16, 40000, 512, 128, n_sink=4, seed=32), 40960, [40000, 21111, 300], (16, 256)
+    elif case == "stream_m32_two_groups":
+        wl, stride, lens, page_sizes = synth.Workload("pg3", 2, 14, 2, 128, 32, 36000, 256, 64, n_sink=0, seed=33), 36864, [36000, 17000], (64,)
+    else:   # 512 problems, so one chunk of 35984 rows each: 2250 pages of 16 tokens, more than the staged slice
+        wl, stride, lens, page_sizes = synth.Workload("pg4", 64, 8, 8, 128, 16, 36000, 64, 16, n_sink=0, seed=34), 36864, None, (16,)
+    x = synth.make_decode_inputs(wl, with_kv=False, ctx_stride=stride)
+    xd = H.to_dev(x)
+    want_scores = case != "stream_long_chunks"
+    dims = H.dims_of(wl, stride)
+    st = B.DecodeState(dims, wl.top_k, wl.window, wl.n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b,
+                       want_scores=want_scores)
+    sl = None if lens is None else torch.tensor(lens, dtype=torch.int32, device="cuda")
+    B.build_lut(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, st.lut, st.lut_scale)
+    B.score_topk(dims, xd["codes"], st.lut, st.lut_scale, wl.top_k, wl.window, wl.n_sink, sl, st.topk_idx,
+                 st.topk_count, st.topk_score, st.scores if want_scores else None, st.ws)
+    plan = B.score_topk_plan(st.dims, wl.top_k, wl.window, wl.n_sink)
+    assert bool(plan["fast"]) == (case != "exact_route")
+    heads = wl.batch * wl.n_q_heads
+    ref_stats = torch.zeros(heads, dtype=torch.int32, device="cuda")
+    B.score_topk_stats(st.dims, wl.top_k, wl.window, wl.n_sink, st.ws, ref_stats)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (st.topk_idx, st.topk_count, st.topk_score)] + [st.scores.clone() if want_scores else None]
+    if case == "stream_long_chunks":
+        assert plan["chunks"] == 1 and plan["rows_per_chunk"] // 16 > 2048
+    for page_size in page_sizes:
+        pool, table = _page_codes(x["codes"], page_size, seed=page_size)
+        H.log(f"paged codes {case}: page size {page_size}, pool {tuple(pool.shape)}, plan {plan}")
+        st.topk_idx.fill_(-7); st.topk_count.fill_(-7); st.topk_score.fill_(-7.0)
+        if want_scores:
+            st.scores.fill_(float("nan"))
+        st.ws.zero_()
+        B.score_topk_paged(st.dims, pool, table, page_size, st.lut, st.lut_scale, wl.top_k, wl.window, wl.n_sink, sl,
+                           st.topk_idx, st.topk_count, st.topk_score, st.scores if want_scores else None, st.ws)
+        stats = torch.zeros(heads, dtype=torch.int32, device="cuda")
+        B.score_topk_stats(st.dims, wl.top_k, wl.window, wl.n_sink, st.ws, stats)
+        torch.cuda.synchronize()
+        assert torch.equal(st.topk_count, ref[1])
+        assert torch.equal(st.topk_idx, ref[0])
+        assert torch.equal(st.topk_score.view(torch.int32), ref[2].view(torch.int32))
+        assert torch.equal(stats, ref_stats)
+        if want_scores:
+            n = torch.tensor(lens if lens is not None else [wl.ctx_len] * wl.batch, device="cuda")
+            live = (torch.arange(stride, device="cuda")[None, :] < n[:, None])[:, None, :].expand_as(st.scores)
+            assert torch.equal(st.scores[live].view(torch.int32), ref[3][live].view(torch.int32))
+
+
+@pytest.mark.gpu
+def test_codes_to_pages_append():
+    """The append path of the paged code matrix: rows encoded into a staging buffer and copied through the
+    page table land where the contiguous layout has them."""
+    wl = synth.Workload("pg5", 3, 8, 2, 128, 16, 1000, 16, 16, seed=35)
+    stride, page_size, n_new, pos0 = 1024, 16, 5, 990
+    x = synth.make_decode_inputs(wl, ctx_stride=stride)
+    pool, table = _page_codes(x["codes"], page_size, seed=7)
+    fresh = torch.randint(0, 256, (wl.batch, wl.n_kv_heads, n_new, wl.n_sub), dtype=torch.uint8, device="cuda")
+    dims = H.dims_of(wl, stride)
+    B.codes_to_pages(dims, fresh, n_new, pos0, pool, table, page_size)
+    torch.cuda.synchronize()
+    want = x["codes"].clone()
+    want[:, :, pos0:pos0 + n_new] = fresh.cpu()
+    want_pool, _ = _page_codes(want, page_size, seed=7)
+    assert torch.equal(pool, want_pool)
