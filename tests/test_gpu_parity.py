@@ -474,12 +474,16 @@ def test_decode_prologue_equals_the_two_calls(name, n_new, mode):
     ("sel_m32_g7", 2, 7, 32, 20000, 500, 100, 4, 1, "diag", [20000, 16500]),
     ("sel_m16_g8", 8, 8, 16, 33000, 2048, 256, 0, 1, "none", None),
     ("sel_exact_route", 2, 4, 16, 3000, 64, 32, 0, 1, "diag", None),
+    ("sel_window_0", 2, 4, 16, 20000, 256, 0, 0, 1, "diag", None),          # the appended row is a candidate
+    ("sel_window_below_n_new", 2, 4, 16, 20000, 256, 1, 0, 3, "diag", None),   # two of the three appended rows are
 ])
 def test_decode_select_equals_the_two_calls(name, Bn, G, M, N, K, w, n_sink, n_new, mode, seq_lens):
     """a2ats_decode_select (append-time encode, tables and threshold sampling in one launch, then the
     streaming and final kernels) writes bit for bit what a2ats_decode_prologue + a2ats_score_topk write:
     codes, rotated queries, the whole table blob, scales, indices, counts and scores; and the same
-    survivor statistics, i.e. the same thresholds.  Also on a shape of the exact route (plain two calls)."""
+    survivor statistics, i.e. the same thresholds.  Also on a shape of the exact route (plain two calls) and
+    with a window shorter than the append (appended rows are candidates: the call must not sample the code
+    matrix while they are being written, so it makes the two calls)."""
     wl = synth.Workload(name, Bn, 2 * G, 2, 128, M, N, K, w, n_sink=n_sink, seed=61)
     xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
     hm = synth.make_query_second_moment(wl)
