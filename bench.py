@@ -231,6 +231,69 @@ def paged_codes_phase(args, torch, B, synth, wl):
         "us_paged": t_paged, "us_contiguous": t_flat, "indices_equal_to_contiguous": same}))
 
 
+def host_attention_step(args, torch, B, synth, wl):
+    """The placement of section 4.3: K/V caches in (pinned) host memory, selection on the GPU, attention over
+    the retrieved rows on the host CPU (a2ats_sparse_attn_host).  A step = a2ats_decode_select on the GPU,
+    indices / counts / rotated queries to the host, host attention, output back to the GPU; wall clock per
+    step, with the host kernel's share timed separately."""
+    R = max(1, min(args.replicas, 2))
+    dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)
+    N, K, w = wl.ctx_len, wl.top_k, wl.window
+    hm = synth.make_query_second_moment(wl)
+    h_diag = hm["h_diag"].cuda()
+    reps = []
+    for r in range(R):
+        x = synth.make_decode_inputs(wl.replace(seed=wl.seed + r), device="cuda")
+        x["new_key"] = x["k"][:, :, N - 1:N, :].float().contiguous()
+        for name in ("k", "v"):
+            x[name] = x[name].cpu().pin_memory()
+        x["q_h"] = x["q"].cpu().pin_memory()
+        reps.append(x)
+    st = B.DecodeState(dims, K, w, wl.n_sink, reps[0]["q"].dtype, reps[0]["inv_freq"], wl.wrope_b)
+    pin = lambda t: torch.empty_like(t, device="cpu").pin_memory()
+    idx_h, cnt_h, qrot_h, out_h = pin(st.topk_idx), pin(st.topk_count), pin(st.q_rot), pin(st.out)
+    cos_h, sin_h = st.cos_win.cpu(), st.sin_win.cpu()
+    t_host = []
+
+    def step(i):
+        x = reps[i % R]
+        B.decode_select(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], x["q"],
+                        st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale, K, w, wl.n_sink, None, st.topk_idx,
+                        st.topk_count, None, st.ws)
+        idx_h.copy_(st.topk_idx, non_blocking=True)
+        cnt_h.copy_(st.topk_count, non_blocking=True)
+        qrot_h.copy_(st.q_rot, non_blocking=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        B.sparse_attn_host(dims, x["q_h"], qrot_h, x["k"], x["v"], idx_h, cnt_h, K, w, wl.n_sink, cos_h, sin_h,
+                           None, out_h, args.host_threads)
+        t_host.append(time.perf_counter() - t0)
+        st.out.copy_(out_h, non_blocking=True)
+
+    steps, warmup = min(args.steps, 16), min(args.warmup, 4)
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_host.clear()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    e = 2 if wl.kv_dtype == "bf16" else 4
+    attn_bytes = wl.batch * wl.n_q_heads * (min(K, N - w) + w) * 2 * wl.head_dim * e   # rows each head reads
+    host_ms = sorted(t_host)[len(t_host) // 2] * 1e3
+    print(json.dumps({
+        "metric": "scored keys/s, whole decode step with the K/V caches in host memory and the attention on the host CPU",
+        "value": wl.batch * wl.n_kv_heads * N / (ms * 1e-3), "unit": "keys/s", "n_gpus": 1, "steps": steps,
+        "warmup": warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 fixed-point scores on the GPU; bf16 K/V with f32 accumulate on the CPU", "data": "synthetic",
+        "config": {"workload": wl.name, "kv_cache": "pinned host memory", "attention": "host CPU",
+                   "host_threads": args.host_threads or "OpenMP default", "replicas_cycled": R},
+        "host_attention_ms_median": host_ms, "host_attention_bytes": attn_bytes,
+        "host_attention_GBps": attn_bytes / (host_ms * 1e-3) / 1e9}))
+
+
 def single_codebook_encode_prefill(args, torch, B, synth, wl):
     """Prefill side in the paper's own geometry: a2ats_encode_keys over whole sequences under the full
     D x D query-aware distortion (4096 distances over 128 dimensions per key, on the matrix cores)."""
@@ -558,6 +621,10 @@ def main():
     ap.add_argument("--codebook-fit", action="store_true",
                     help="offline codebook construction (single-codebook workloads): one Lloyd iteration and one "
                          "second-moment accumulation; prints a line of its own")
+    ap.add_argument("--host-attention", action="store_true",
+                    help="K/V caches in pinned host memory, selection on the GPU, attention on the host CPU "
+                         "(a2ats_sparse_attn_host); prints a line of its own")
+    ap.add_argument("--host-threads", type=int, default=0, help="threads of --host-attention (0: OpenMP default)")
     ap.add_argument("--paged-codes", type=int, default=0,
                     help="time the score/top-K phase over a code matrix in pages of this many tokens beside the "
                          "contiguous one; prints a line of its own")
@@ -593,6 +660,9 @@ def main():
         return
     if args.paged_codes:
         paged_codes_phase(args, torch, B, synth, wl)
+        return
+    if args.host_attention:
+        host_attention_step(args, torch, B, synth, wl)
         return
     R = max(1, args.replicas)
     dims = B.make_dims(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.n_sub, wl.ctx_len)

@@ -324,6 +324,22 @@ int a2ats_codes_to_pages(const a2ats_dims* dims, const uint8_t* new_codes, int32
                          uint8_t* code_pool, const int32_t* page_table, int32_t page_size, void* stream);
 
 /*
+ * a2ats_sparse_attn on the HOST CPU, for a key/value cache kept in host memory (the placement of
+ * section 4.3: the GPU scores and selects, the CPU attends over the retrieved tokens next to the
+ * cache, and only indices, queries and outputs cross the bus).  Same function and arguments as
+ * a2ats_sparse_attn, except that EVERY pointer is a host pointer (q, q_rot, k_cache, v_cache,
+ * topk_idx, topk_count, cos_win, sin_win, seq_lens, out), there is no workspace and no stream: the
+ * call runs on n_threads OpenMP threads (0 = the runtime's default) and returns when `out` is
+ * written.  It never touches a GPU and is not a fallback of anything: no other entry point calls it.
+ * float32 accumulation; AVX2 + FMA inner loops when the CPU has them, scalar otherwise.  head_dim 128.
+ */
+int a2ats_sparse_attn_host(const a2ats_dims* dims, const void* q, const float* q_rot, const void* k_cache,
+                           const void* v_cache, int kv_dtype, const int32_t* topk_idx,
+                           const int32_t* topk_count, int32_t top_k, int32_t window, int32_t n_sink,
+                           const float* cos_win, const float* sin_win, const int32_t* seq_lens, void* out,
+                           int32_t n_threads);
+
+/*
  * Selection shared by the query heads of a KV head (grouped-query attention; the paper selects
  * "for each attention head" and does not say which kind, so per query head is the reading of the
  * calls above and this is the alternative): the group's score of a token is the SUM over the G

@@ -24,7 +24,8 @@ EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_wor
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_score_topk_profiled",
            "a2ats_decode_prologue", "a2ats_decode_select", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
            "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged",
-           "a2ats_sparse_attn_static", "a2ats_score_topk_paged", "a2ats_codes_to_pages"]
+           "a2ats_sparse_attn_static", "a2ats_score_topk_paged", "a2ats_codes_to_pages",
+           "a2ats_sparse_attn_host"]
 
 
 class A2atsError(RuntimeError):
@@ -249,6 +250,17 @@ def sparse_attn_static(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_co
                                         _dtype_code(k_cache), _ptr(topk_idx), _ptr(topk_count), top_k, window,
                                         n_sink, _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), _stream())
     _check(rc, "a2ats_sparse_attn_static")
+
+
+def sparse_attn_host(dims: Dims, q, q_rot, k_cache, v_cache, topk_idx, topk_count, top_k: int, window: int,
+                     n_sink: int, cos_win, sin_win, seq_lens, out, n_threads: int = 0):
+    """sparse_attn on the host CPU over a cache in host memory: every tensor is a CPU tensor."""
+    for t in (q, q_rot, k_cache, v_cache, topk_idx, topk_count, cos_win, sin_win, seq_lens, out):
+        assert t is None or t.device.type == "cpu", "a2ats_sparse_attn_host takes host pointers"
+    rc = lib().a2ats_sparse_attn_host(ctypes.byref(dims), _ptr(q), _ptr(q_rot), _ptr(k_cache), _ptr(v_cache),
+                                      _dtype_code(k_cache), _ptr(topk_idx), _ptr(topk_count), top_k, window, n_sink,
+                                      _ptr(cos_win), _ptr(sin_win), _ptr(seq_lens), _ptr(out), n_threads)
+    _check(rc, "a2ats_sparse_attn_host")
 
 
 def build_lut_shared(dims: Dims, q, cos_b, sin_b, codebook, q_rot, lut, lut_scale):
