@@ -9,6 +9,8 @@
 // each, a wave works on 4 (2) rows at a time with a second set of rows already requested, and
 // the rows of one head are split over several workgroups whose partial (max, sum, accumulator)
 // triples a second small kernel merges.
+#include <type_traits>
+
 #include "common.hpp"
 #include "internal.hpp"
 
@@ -98,8 +100,8 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float (&acc)[VEC
 // rows (same KV head, same part) run next to each other on one XCD: the rows come from HBM once
 // and from that XCD's L2 for the other G - 1 heads.
 template <typename T, bool SHARED>
-__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
-    const T* __restrict__ q, const float* __restrict__ q_rot, const T* __restrict__ k_cache,
+__device__ __forceinline__ void attn_partial_body(
+    int part, int bh, const T* __restrict__ q, const float* __restrict__ q_rot, const T* __restrict__ k_cache,
     const T* __restrict__ v_cache, const int32_t* __restrict__ topk_idx,
     const int32_t* __restrict__ topk_count, const float* __restrict__ cos_win,
     const float* __restrict__ sin_win, const int32_t* __restrict__ seq_lens,
@@ -118,17 +120,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   __shared__ float s_m[NWV], s_l[NWV], s_acc[NWV][kD];
 
   const int G = Hq / Hkv;
-  int part, bh;
-  if (SHARED) {
-    const int parts = n_far + n_win;
-    int prob, pg;
-    xcd_map(blockIdx.x, parts * G, (int)(gridDim.x / (parts * G)), prob, pg);
-    part = pg / G;
-    bh = prob * G + pg % G;   // prob = b * Hkv + kv
-  } else {
-    part = blockIdx.x;
-    bh = blockIdx.y;
-  }
   const int b = bh / Hq, h = bh % Hq, kv = h / G;
   const int ih = SHARED ? b * Hkv + kv : bh;   // whose selection this head attends
   const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, slot = lane / LPR, sub = lane % LPR;
@@ -294,6 +285,265 @@ __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(
   }
 }
 
+#define A2ATS_ATTN_ARGS                                                                                \
+  const T *__restrict__ q, const float *__restrict__ q_rot, const T *__restrict__ k_cache,               \
+      const T *__restrict__ v_cache, const int32_t *__restrict__ topk_idx,                               \
+      const int32_t *__restrict__ topk_count, const float *__restrict__ cos_win,                         \
+      const float *__restrict__ sin_win, const int32_t *__restrict__ seq_lens,                           \
+      float *__restrict__ partial, int Hq, int Hkv, int ctx_len, int64_t ctx_stride, int top_k,          \
+      int window, int n_sink, int n_far, int n_win, const int32_t *__restrict__ page_table,              \
+      int page_shift, int pages_per_seq
+#define A2ATS_ATTN_PASS                                                                                \
+  q, q_rot, k_cache, v_cache, topk_idx, topk_count, cos_win, sin_win, seq_lens, partial, Hq, Hkv,        \
+      ctx_len, ctx_stride, top_k, window, n_sink, n_far, n_win, page_table, page_shift, pages_per_seq
+
+template <typename T, bool SHARED>
+__global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(A2ATS_ATTN_ARGS) {
+  int part, bh;
+  if (SHARED) {
+    const int G = Hq / Hkv, parts = n_far + n_win;
+    int prob, pg;
+    xcd_map(blockIdx.x, parts * G, (int)(gridDim.x / (parts * G)), prob, pg);
+    part = pg / G;
+    bh = prob * G + pg % G;   // prob = b * Hkv + kv
+  } else {
+    part = blockIdx.x;
+    bh = blockIdx.y;
+  }
+  attn_partial_body<T, SHARED>(part, bh, A2ATS_ATTN_PASS);
+}
+
+// ------------------------------------------------------------------------------------------
+// One selection per KV head, bf16 cache: the far rows (sinks + retrieved) of a KV head are the same
+// for its G query heads, so q~ K^T is a real (if thin) matrix product: G x 128 times 128 x rows.
+// A wave takes 16 rows at a time as the B operand of v_mfma_f32_16x16x32_bf16 (lane = row n +
+// 16 * (k / 8): eight consecutive dimensions of one row, straight from the row's memory, no LDS),
+// the rotated queries as the A operand (head m in row m, rows >= G zero; the float32 queries are
+// split into two bf16 terms so that the logits keep float32-like precision), four k-steps of 32.
+// Accumulator register i of lane L holds head 4 * (L / 16) + i, row L % 16.  The softmax
+// statistics run over the 16 lanes of a DPP row; P V stays on the vector ALU with the
+// probabilities broadcast through scalar registers: every lane owns two output dimensions and a
+// value row is read with one coalesced 4-byte load per lane.  Each row comes from HBM once for all
+// G heads.  GP: G padded to 4 or 8.
+typedef __attribute__((ext_vector_type(8))) __bf16 attn_bf16x8;
+typedef __attribute__((ext_vector_type(4))) float attn_f32x4;
+
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false)));
+  v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, false)));
+  return v;
+}
+__device__ __forceinline__ float lane_value(float v, int src_lane) {   // src_lane: a compile-time constant
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+template <int GP>
+__device__ __forceinline__ void attn_far_shared_mfma_body(
+    int prob, int part, const float* __restrict__ q_rot, const uint16_t* __restrict__ k_cache,
+    const uint16_t* __restrict__ v_cache, const int32_t* __restrict__ topk_idx,
+    const int32_t* __restrict__ topk_count, const int32_t* __restrict__ seq_lens, float* __restrict__ partial,
+    int Hq, int Hkv, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink, int n_far, int n_win,
+    const int32_t* __restrict__ page_table, int page_shift, int pages_per_seq) {
+  constexpr int NWV = kAttnThreads / 64;
+  __shared__ uint32_t s_row[kAttnTile];
+  __shared__ float s_m[NWV][GP], s_l[NWV][GP], s_o[NWV][GP][kD];
+
+  const int G = Hq / Hkv;
+  const int b = prob / Hkv, kv = prob % Hkv;   // prob = b * Hkv + kv
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, n = lane & 15, kg = lane >> 4;
+  const SeqRange sr = seq_range(ctx_len, seq_lens, b, window, n_sink, top_k);
+  const int cnt = max(0, min(min(topk_count[prob], top_k), sr.ncand));
+  const int n_rows = sr.sink_end + cnt;
+  const int n_mine = n_rows > part ? (n_rows - part + n_far - 1) / n_far : 0;
+  const size_t seq_base = page_table ? 0 : ((size_t)b * Hkv + kv) * ctx_stride * kD;
+  const uint16_t* kb = k_cache + seq_base;
+  const uint16_t* vb = v_cache + seq_base;
+  const int32_t* pages = page_table ? page_table + (size_t)b * pages_per_seq : nullptr;
+  const int32_t* idx = topk_idx + (size_t)prob * top_k;
+  const float scale = 0.08838834764831845f;   // 1/sqrt(128)
+
+  // A operand: head n of the KV head, dimensions 32 s + 8 kg .. + 8, as hi + lo bf16 (rows >= G: zero).
+  // Eight 16-byte loads per lane, all in flight together; hi is the float truncated to bf16 and lo
+  // the (exactly representable) rest rounded down to bf16, packed with integer operations.  (A first
+  // version filled the operand vectors element by element from 32 scalar loads: 6.5 us before the
+  // first row was requested.)
+  attn_bf16x8 a_hi[4], a_lo[4];
+  {
+    const float4* qh = (const float4*)(q_rot + ((size_t)b * Hq + (size_t)kv * G + (n < G ? n : 0)) * kD + kg * 8);
+    float4 qv[8];
+#pragma unroll
+    for (int s_ = 0; s_ < 4; ++s_) {
+      qv[2 * s_] = qh[s_ * 8];
+      qv[2 * s_ + 1] = qh[s_ * 8 + 1];
+    }
+    const float keep = n < G ? 1.f : 0.f;
+#pragma unroll
+    for (int s_ = 0; s_ < 4; ++s_) {
+      const float x[8] = {qv[2 * s_].x, qv[2 * s_].y, qv[2 * s_].z, qv[2 * s_].w,
+                          qv[2 * s_ + 1].x, qv[2 * s_ + 1].y, qv[2 * s_ + 1].z, qv[2 * s_ + 1].w};
+      uint32_t hw[4], lw[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x0 = x[2 * e] * keep, x1 = x[2 * e + 1] * keep;
+        const uint32_t h0 = __float_as_uint(x0) & 0xffff0000u, h1 = __float_as_uint(x1) & 0xffff0000u;
+        const float r0 = x0 - __uint_as_float(h0), r1 = x1 - __uint_as_float(h1);   // exact
+        hw[e] = (h0 >> 16) | h1;
+        lw[e] = (__float_as_uint(r0) >> 16) | (__float_as_uint(r1) & 0xffff0000u);
+      }
+      a_hi[s_] = __builtin_bit_cast(attn_bf16x8, make_uint4(hw[0], hw[1], hw[2], hw[3]));
+      a_lo[s_] = __builtin_bit_cast(attn_bf16x8, make_uint4(lw[0], lw[1], lw[2], lw[3]));
+    }
+  }
+
+  // running state of head 4 kg + i (identical in the 16 lanes of a lane group) and this lane's two
+  // output dimensions (2 lane, 2 lane + 1) of every head
+  float m_run[4], l_run[4], o[GP][2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { m_run[i] = -INFINITY; l_run[i] = 0.f; }
+#pragma unroll
+  for (int g = 0; g < GP; ++g) { o[g][0] = 0.f; o[g][1] = 0.f; }
+
+  for (int tb = 0; tb < n_mine; tb += kAttnTile) {
+    const int tn = min(kAttnTile, n_mine - tb);
+    __syncthreads();
+    for (int i = tid; i < tn; i += kAttnThreads) {
+      const int t = part + (tb + i) * n_far;
+      int j = t < sr.sink_end ? t : idx[t - sr.sink_end];
+      j = min(max(j, 0), sr.n - 1);   // a bad caller index must not leave the cache
+      s_row[i] = pages ? (((uint32_t)pages[j >> page_shift] * (uint32_t)Hkv + (uint32_t)kv) << page_shift) +
+                             (uint32_t)(j & ((1 << page_shift) - 1))
+                       : (uint32_t)j;
+    }
+    __syncthreads();
+
+    // Tiles of 16 rows, dealt to the waves in turn; the next tile's rows are requested
+    // (unconditionally, tile index clamped) before the current one is used: two register sets.
+    const int n_tiles = (tn + 15) >> 4;
+    uint4 kA[4], kB[4];
+    uint32_t vA[16], vB[16];
+    auto load_tile = [&](int tile, uint4 (&kr)[4], uint32_t (&vr)[16]) {
+      const int t0 = min(tile, n_tiles - 1) << 4;
+      const uint32_t row = s_row[min(t0 + n, tn - 1)];
+      const uint16_t* kp = kb + (size_t)row * kD + kg * 8;
+#pragma unroll
+      for (int s_ = 0; s_ < 4; ++s_) kr[s_] = *(const uint4*)(kp + s_ * 32);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const uint32_t rr = s_row[min(t0 + r, tn - 1)];   // (one address for the wave: an LDS broadcast)
+        vr[r] = *(const uint32_t*)(vb + (size_t)rr * kD + 2 * lane);
+      }
+    };
+    auto use_tile = [&](int tile, const uint4 (&kr)[4], const uint32_t (&vr)[16]) {
+      const int t0 = tile << 4;
+      attn_f32x4 sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s_ = 0; s_ < 4; ++s_) {
+        const attn_bf16x8 bk = __builtin_bit_cast(attn_bf16x8, kr[s_]);
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_hi[s_], bk, sacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_lo[s_], bk, sacc, 0, 0, 0);
+      }
+      const bool valid = t0 + n < tn;
+      float pr[4], alpha[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float logit = valid ? sacc[i] * scale : -INFINITY;
+        const float mn = fmaxf(m_run[i], row16_max(logit));   // finite: a tile has at least one valid row
+        alpha[i] = __expf(m_run[i] - mn);
+        pr[i] = __expf(logit - mn);
+        l_run[i] = l_run[i] * alpha[i] + row16_sum(pr[i]);
+        m_run[i] = mn;
+      }
+      float v0[16], v1[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        v0[r] = __uint_as_float(vr[r] << 16);
+        v1[r] = __uint_as_float(vr[r] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int g = 0; g < GP; ++g) {
+        const int i = g & 3, src = 16 * (g >> 2);   // head g: register i of lane group g / 4
+        const float al = lane_value(alpha[i], src);
+        float o0 = o[g][0] * al, o1 = o[g][1] * al;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float pv = lane_value(pr[i], src + r);
+          o0 += pv * v0[r];
+          o1 += pv * v1[r];
+        }
+        o[g][0] = o0;
+        o[g][1] = o1;
+      }
+    };
+    load_tile(wv, kA, vA);
+#pragma unroll 1
+    for (int tile = wv; tile < n_tiles; tile += 2 * NWV) {
+      load_tile(tile + NWV, kB, vB);
+      use_tile(tile, kA, vA);
+      load_tile(tile + 2 * NWV, kA, vA);
+      if (tile + NWV < n_tiles) use_tile(tile + NWV, kB, vB);
+    }
+  }
+
+  // merge the waves of the block, one thread per output dimension, head by head
+  if (n == 0 && kg < GP / 4) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s_m[wv][4 * kg + i] = m_run[i];
+      s_l[wv][4 * kg + i] = l_run[i];
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < GP; ++g) {
+    s_o[wv][g][2 * lane] = o[g][0];
+    s_o[wv][g][2 * lane + 1] = o[g][1];
+  }
+  __syncthreads();
+  if (tid < kD) {
+    for (int g = 0; g < G; ++g) {
+      float m = s_m[0][g], l = s_l[0][g], a[1] = {s_o[0][g][tid]};
+      for (int w = 1; w < NWV; ++w) {
+        const float a2[1] = {s_o[w][g][tid]};
+        merge_state<1>(m, l, a, s_m[w][g], s_l[w][g], a2);
+      }
+      const size_t bh = (size_t)b * Hq + (size_t)kv * G + g;
+      float* pp = partial + (bh * (n_far + n_win) + part) * (kD + 2);
+      pp[tid] = a[0];
+      if (tid == 0) { pp[kD] = m; pp[kD + 1] = l; }
+    }
+  }
+}
+
+// The launch of the shared selection: the first n_far workgroups of every (sequence, KV head) take the
+// far rows on the matrix cores for all G heads; after them come, per query head, the n_win workgroups
+// of the window rows (a rotation per row: the per-head vector-ALU path), mapped so that the G heads of a
+// KV head read the same rows side by side on one XCD.
+template <int GP>
+__global__ __launch_bounds__(kAttnThreads) void attn_shared_mfma_kernel(
+    const uint16_t* __restrict__ q, const float* __restrict__ q_rot, const uint16_t* __restrict__ k_cache,
+    const uint16_t* __restrict__ v_cache, const int32_t* __restrict__ topk_idx,
+    const int32_t* __restrict__ topk_count, const float* __restrict__ cos_win,
+    const float* __restrict__ sin_win, const int32_t* __restrict__ seq_lens, float* __restrict__ partial,
+    int Hq, int Hkv, int ctx_len, int64_t ctx_stride, int top_k, int window, int n_sink, int n_far, int n_win,
+    const int32_t* __restrict__ page_table, int page_shift, int pages_per_seq, int problems) {
+  const int far_blocks = n_far * problems;
+  if ((int)blockIdx.x < far_blocks) {   // (uniform over the workgroup)
+    int prob, part;
+    xcd_map(blockIdx.x, n_far, problems, prob, part);
+    attn_far_shared_mfma_body<GP>(prob, part, q_rot, k_cache, v_cache, topk_idx, topk_count, seq_lens, partial, Hq,
+                                  Hkv, ctx_len, ctx_stride, top_k, window, n_sink, n_far, n_win, page_table,
+                                  page_shift, pages_per_seq);
+  } else {
+    const int G = Hq / Hkv;
+    int prob, pg;
+    xcd_map((int)blockIdx.x - far_blocks, n_win * G, problems, prob, pg);
+    attn_partial_body<uint16_t, true>(n_far + pg / G, prob * G + pg % G, q, q_rot, k_cache, v_cache, topk_idx,
+                                      topk_count, cos_win, sin_win, seq_lens, partial, Hq, Hkv, ctx_len, ctx_stride,
+                                      top_k, window, n_sink, n_far, n_win, page_table, page_shift, pages_per_seq);
+  }
+}
+
 // Merge the partial states of a head: 4 groups of 128 threads (one thread per output dimension)
 // each fold every fourth state into a running one -- four states' loads are issued together, so a
 // head with up to 16 workgroups costs one load latency -- then the four are folded through LDS.
@@ -357,7 +607,22 @@ static hipError_t launch_attn_t(const a2ats_dims& d, const AttnPlan& plan, const
   const int pages_per_seq = page_table ? (int)((d.ctx_stride + (1 << page_shift) - 1) >> page_shift) : 0;
   if (heads == 0) return hipSuccess;
   const int parts = plan.n_far + plan.n_win;
-  if (shared)
+  const int G = d.n_q_heads / d.n_kv_heads;
+  if (shared && std::is_same<T, uint16_t>::value && G <= 8) {
+    // bf16 cache: far rows on the matrix cores once per KV head, window rows per head, one launch
+    const int problems = d.batch * d.n_kv_heads;
+    const dim3 grid(plan.n_far * problems + plan.n_win * heads);
+    if (G <= 4)
+      hipLaunchKernelGGL((attn_shared_mfma_kernel<4>), grid, dim3(kAttnThreads), 0, stream, (const uint16_t*)q, q_rot,
+                         (const uint16_t*)k_cache, (const uint16_t*)v_cache, topk_idx, topk_count, cos_win, sin_win,
+                         seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len, d.ctx_stride, top_k, window,
+                         n_sink, plan.n_far, plan.n_win, page_table, page_shift, pages_per_seq, problems);
+    else
+      hipLaunchKernelGGL((attn_shared_mfma_kernel<8>), grid, dim3(kAttnThreads), 0, stream, (const uint16_t*)q, q_rot,
+                         (const uint16_t*)k_cache, (const uint16_t*)v_cache, topk_idx, topk_count, cos_win, sin_win,
+                         seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len, d.ctx_stride, top_k, window,
+                         n_sink, plan.n_far, plan.n_win, page_table, page_shift, pages_per_seq, problems);
+  } else if (shared)
     hipLaunchKernelGGL((attn_partial_kernel<T, true>), dim3(parts * heads), dim3(kAttnThreads), 0, stream,
                        (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
                        cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
