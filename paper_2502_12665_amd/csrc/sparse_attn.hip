@@ -8,7 +8,9 @@
 // loads in flight: a row is read by 16 (bf16) or 32 (float32) lanes with one 16-byte load
 // each, a wave works on 4 (2) rows at a time with a second set of rows already requested, and
 // the rows of one head are split over several workgroups whose partial (max, sum, accumulator)
-// triples a second small kernel merges.
+// triples a second small kernel merges.  With one selection per KV head (the shared variant) the
+// far rows are the same for the G heads of a KV head and q~ K^T is a thin matrix product: that case
+// (bf16 caches) goes through the matrix cores, see attn_shared_mfma_kernel.
 #include <type_traits>
 
 #include "common.hpp"
