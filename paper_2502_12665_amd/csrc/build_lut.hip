@@ -34,9 +34,10 @@ __device__ __forceinline__ void build_lut_body(
   constexpr int ENTRIES = kCentroids * M;
   constexpr int EPT = ENTRIES / kLutThreads;
   constexpr int MAXQ = 65535 / M;       // a sum of M coarse entries fits 16 bits
+  constexpr int LOG2M = M == 16 ? 4 : 5;
+  static_assert(M == 16 || M == 32, "M is 16 or 32");
   __shared__ float s_q[kHeadsPerGroup][D];
   __shared__ uint32_t s_maxbits[kHeadsPerGroup];   // largest |entry| per head, as float bits
-  __shared__ int s_exp[kHeadsPerGroup];
   __shared__ int32_t s_min[M][kHeadsPerGroup], s_max[M][kHeadsPerGroup];
   __shared__ int32_t s_shift[kHeadsPerGroup];
 
@@ -140,20 +141,30 @@ __device__ __forceinline__ void build_lut_body(
     if ((tid & 63) == 63) atomicMax(&s_maxbits[r], v);
   }
   __syncthreads();
-  if (tid < kHeadsPerGroup) {
-    const double v = (double)__uint_as_float(s_maxbits[tid]);
+  // Every thread derives the four exponents itself (M is a power of two and v a float, so the
+  // exponent of v * M is the float's exponent field plus a constant; a subnormal maximum takes the
+  // general route): no second barrier, no double-precision library call on the critical path.
+  int s_exp[kHeadsPerGroup];
+#pragma unroll
+  for (int r = 0; r < kHeadsPerGroup; ++r) {
+    const uint32_t bits = s_maxbits[r];
     int e = 0;
-    if (v > 0.0) {
-      int x;
-      frexp(v * (double)M, &x);   // v*M < 2^x
+    if (bits != 0u) {
+      int x;   // v * M < 2^x
+      if ((bits >> 23) != 0u) {
+        x = (int)(bits >> 23) - 126 + LOG2M;
+      } else {
+        frexp((double)__uint_as_float(bits) * (double)M, &x);
+      }
       e = 30 - x;
       e = e > 100 ? 100 : (e < -100 ? -100 : e);
     }
-    s_exp[tid] = e;
-    const int hg = g4 * kHeadsPerGroup + tid;
-    if (hg < G && write_out) lut_scale[(size_t)b * Hq + kv * G + hg] = (float)ldexp(1.0, -e);
+    s_exp[r] = e;
   }
-  __syncthreads();
+  if (tid < kHeadsPerGroup) {
+    const int hg = g4 * kHeadsPerGroup + tid;
+    if (hg < G && write_out) lut_scale[(size_t)b * Hq + kv * G + hg] = (float)ldexp(1.0, -s_exp[tid]);
+  }
 
   // --- exact fixed-point entries; per-(subspace, head) minimum and maximum over the centroids
   // (LDS atomics: the four lanes of a wave that share a subspace collide, nothing else does)
