@@ -301,18 +301,13 @@ __device__ __forceinline__ void attn_partial_body(
 
 template <typename T, bool SHARED>
 __global__ __launch_bounds__(kAttnThreads) void attn_partial_kernel(A2ATS_ATTN_ARGS) {
-  int part, bh;
-  if (SHARED) {
-    const int G = Hq / Hkv, parts = n_far + n_win;
-    int prob, pg;
-    xcd_map(blockIdx.x, parts * G, (int)(gridDim.x / (parts * G)), prob, pg);
-    part = pg / G;
-    bh = prob * G + pg % G;   // prob = b * Hkv + kv
-  } else {
-    part = blockIdx.x;
-    bh = blockIdx.y;
-  }
-  attn_partial_body<T, SHARED>(part, bh, A2ATS_ATTN_PASS);
+  // All workgroups of a (sequence, KV head) run on one XCD, the G heads of a part side by side: the
+  // window rows and sinks (per-head selection) or all rows (shared selection) that the G heads have
+  // in common come from HBM once and from that XCD's L2 for the others.
+  const int G = Hq / Hkv, parts = n_far + n_win;
+  int prob, pg;
+  xcd_map(blockIdx.x, parts * G, (int)(gridDim.x / (parts * G)), prob, pg);   // prob = b * Hkv + kv
+  attn_partial_body<T, SHARED>(pg / G, prob * G + pg % G, A2ATS_ATTN_PASS);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -631,7 +626,7 @@ static hipError_t launch_attn_t(const a2ats_dims& d, const AttnPlan& plan, const
                        d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win, page_table, page_shift,
                        pages_per_seq);
   else
-    hipLaunchKernelGGL((attn_partial_kernel<T, false>), dim3(parts, heads), dim3(kAttnThreads), 0, stream,
+    hipLaunchKernelGGL((attn_partial_kernel<T, false>), dim3(parts * heads), dim3(kAttnThreads), 0, stream,
                        (const T*)q, q_rot, (const T*)k_cache, (const T*)v_cache, topk_idx, topk_count,
                        cos_win, sin_win, seq_lens, (float*)ws, d.n_q_heads, d.n_kv_heads, d.ctx_len,
                        d.ctx_stride, top_k, window, n_sink, plan.n_far, plan.n_win, page_table, page_shift,
