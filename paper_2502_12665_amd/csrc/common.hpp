@@ -308,16 +308,6 @@ __device__ __forceinline__ uint4 load_stream_u4(const void* p) {
   const u32x4_t v = __builtin_nontemporal_load((const u32x4_t*)p);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
-// 16-byte loads through a pointer that is only known to be in global memory (an address that went
-// through an empty asm has lost that knowledge, and a generic load would wait on two counters).
-typedef __attribute__((address_space(1))) const u32x4_t* global_u4_ptr;
-template <bool STREAMED>
-__device__ __forceinline__ uint4 load_global_u4(const void* p) {
-  const global_u4_ptr g = (global_u4_ptr)(uintptr_t)p;
-  const u32x4_t v = STREAMED ? __builtin_nontemporal_load(g) : *g;
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
-
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
 
 // Round-to-nearest-even float -> bf16 (finite inputs; NaN is kept a NaN).
