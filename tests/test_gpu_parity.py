@@ -821,9 +821,10 @@ def test_decode_step_in_a_hip_graph(calls):
         assert junk == junk
 
 
-def _group_shared_step(wl, xd, n_sink=0, want_scores=True):
+def _group_shared_step(wl, xd, n_sink=0, want_scores=True, seq_lens=None):
     """One decode step with one selection per KV head: shared tables, score/top-K on the dims of the
     table heads, attention of all G heads over the shared rows."""
+    sl = None if seq_lens is None else torch.as_tensor(seq_lens, dtype=torch.int32, device="cuda")
     stride = xd["codes"].shape[2]
     dims = H.dims_of(wl, stride)
     kvw = wl.replace(n_q_heads=wl.n_kv_heads)
@@ -834,10 +835,10 @@ def _group_shared_step(wl, xd, n_sink=0, want_scores=True):
     sk.topk_idx.fill_(-7)
     sk.topk_count.fill_(-7)
     B.build_lut_shared(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, sk.lut, sk.lut_scale)
-    B.score_topk(dims_kv, xd["codes"], sk.lut, sk.lut_scale, wl.top_k, wl.window, n_sink, None, sk.topk_idx,
+    B.score_topk(dims_kv, xd["codes"], sk.lut, sk.lut_scale, wl.top_k, wl.window, n_sink, sl, sk.topk_idx,
                  sk.topk_count, sk.topk_score, sk.scores, sk.ws)
     B.sparse_attn_shared(dims, xd["q"], st.q_rot, xd["k"], xd["v"], sk.topk_idx, sk.topk_count, wl.top_k,
-                         wl.window, n_sink, st.cos_win, st.sin_win, None, st.out, st.ws)
+                         wl.window, n_sink, st.cos_win, st.sin_win, sl, st.out, st.ws)
     torch.cuda.synchronize()
     return st, sk
 
@@ -877,6 +878,29 @@ def test_group_shared_selection(oracle, shape):
     aerr = np.abs(st.out.float().cpu().numpy().astype(np.float64) - want).max()
     H.log(f"shared {shape}: attention max error {aerr:.3e}")
     assert aerr <= (2e-2 if wl.kv_dtype == "bf16" else 2e-4), aerr
+
+
+def test_group_shared_selection_ragged(oracle):
+    """Shared selection with ragged lengths (a full sequence, one shorter than window + top-K, one shorter
+    than the window, an empty one) and sinks: the matrix-core attention against the oracle."""
+    wl = synth.Workload("shared_ragged", 4, 8, 2, 128, 16, 20000, 600, 128, seed=88)
+    lens = [20000, 500, 90, 0]
+    x = synth.make_decode_inputs(wl)
+    st, sk = _group_shared_step(wl, H.to_dev(x), n_sink=4, want_scores=False, seq_lens=lens)
+    sl = np.asarray(lens, dtype=np.int32)
+    qrot = oracle.rope(x["q"], x["inv_freq"], wl.wrope_b)
+    grp = oracle.group_scores(oracle.scores_explicit(qrot, x["codebook"], x["codes"], wl.ctx_len), wl.n_kv_heads)
+    idx, cnt, kth = oracle.topk(grp, wl.top_k, wl.window, 4, sl)
+    exc, slots = H.compare_topk(sk.topk_idx.cpu().numpy(), sk.topk_count.cpu().numpy(), idx, cnt, grp, kth)
+    g_idx = np.repeat(sk.topk_idx.cpu().numpy(), wl.group, axis=1)
+    g_cnt = np.repeat(sk.topk_count.cpu().numpy(), wl.group, axis=1)
+    want = oracle.sparse_attn(x["q"], x["k"], x["v"], g_idx, g_cnt, wl.ctx_len, wl.window, 4, x["inv_freq"],
+                              float(wl.wrope_b), sl)
+    got = st.out.float().cpu().numpy().astype(np.float64)
+    aerr = np.abs(got - want).max()
+    H.log(f"shared ragged: {exc} near-tie exclusions in {slots} slots, attention max error {aerr:.3e}")
+    assert aerr <= 2e-2, aerr
+    assert np.abs(got[3]).max() == 0.0
 
 
 def test_second_moment(oracle):
