@@ -1239,6 +1239,46 @@ def test_paged_code_matrix(case):
 
 
 @pytest.mark.gpu
+def test_paged_code_matrix_random_shapes():
+    """Twelve seeded random shapes (batch, head grouping, M, context length, K, window, sinks, ragged lengths,
+    page size): a2ats_score_topk_paged equals a2ats_score_topk bit for bit."""
+    rng = np.random.default_rng(2024)
+    for case in range(12):
+        Bn = int(rng.integers(1, 4))
+        Hkv = int(rng.choice([1, 2, 4]))
+        G = int(rng.choice([1, 2, 4, 7]))
+        M = int(rng.choice([16, 32]))
+        N = int(rng.integers(17000, 45000))
+        K = int(rng.choice([1, 64, 500, 2048]))
+        w = int(rng.choice([0, 16, 128, 300]))
+        n_sink = int(rng.choice([0, 4]))
+        page = int(rng.choice([16, 32, 64, 128]))
+        stride = (N + page - 1) // page * page
+        lens = [int(N if i == 0 else rng.integers(0, N + 1)) for i in range(Bn)]
+        wl = synth.Workload(f"pgr{case}", Bn, Hkv * G, Hkv, 128, M, N, K, w, n_sink=n_sink, seed=100 + case)
+        x = synth.make_decode_inputs(wl, with_kv=False, ctx_stride=stride)
+        xd = H.to_dev(x)
+        dims = H.dims_of(wl, stride)
+        st = B.DecodeState(dims, K, w, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+        sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        B.build_lut(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, st.lut, st.lut_scale)
+        B.score_topk(dims, xd["codes"], st.lut, st.lut_scale, K, w, n_sink, sl, st.topk_idx, st.topk_count,
+                     st.topk_score, None, st.ws)
+        torch.cuda.synchronize()
+        ref = [t.clone() for t in (st.topk_idx, st.topk_count, st.topk_score)]
+        pool, table = _page_codes(x["codes"], page, seed=case)
+        st.topk_idx.fill_(-7); st.topk_count.fill_(-7); st.topk_score.fill_(-7.0)
+        B.score_topk_paged(dims, pool, table, page, st.lut, st.lut_scale, K, w, n_sink, sl, st.topk_idx,
+                           st.topk_count, st.topk_score, None, st.ws)
+        torch.cuda.synchronize()
+        what = f"case {case}: B {Bn} Hkv {Hkv} G {G} M {M} N {N} K {K} w {w} sinks {n_sink} page {page} lens {lens}"
+        assert torch.equal(st.topk_count, ref[1]), what
+        assert torch.equal(st.topk_idx, ref[0]), what
+        assert torch.equal(st.topk_score.view(torch.int32), ref[2].view(torch.int32)), what
+        H.log("paged ok: " + what)
+
+
+@pytest.mark.gpu
 def test_codes_to_pages_append():
     """The append path of the paged code matrix: rows encoded into a staging buffer and copied through the
     page table land where the contiguous layout has them."""
