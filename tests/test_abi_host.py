@@ -298,3 +298,14 @@ def test_paged_code_entry_points_check_their_arguments(binding):
     assert scatter(d, n_new=-1) == -1
     assert scatter(d, rows=null) == -1
     assert scatter(single) == -2
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only: --gpus 2 exits with a message and a non-zero status before touching a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in p.stderr
