@@ -63,8 +63,19 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
     if (s_tot < kSampleRows) s_tot = kSampleRows;
     if (s_tot > 64 * kSampleRows) s_tot = 64 * kSampleRows;
     p.P0 = (int)std::min<long>(8, s_tot / kSampleRows);
-    p.sample_rows = (int)(s_tot / p.P0);   // at most 8192: the histogram counts are 16 bits wide
     const long problems = (long)d.batch * d.n_kv_heads * p.NG;
+    // Large batches (more sampling workgroups than fit one round of the CUs, so the sampling is a
+    // launch of its own anyway): an eighth of the candidates in workgroups of up to 4096 rows.  The
+    // survivors the streaming pass writes and the final kernel reads back (1.95 K per head at a
+    // sixteenth) are a quarter of the phase's HBM traffic there; the larger sample costs less than
+    // it saves only when its table copies are shared by more rows.
+    if (problems * p.P0 > 256) {
+      s_tot = ncand / 8 / kSampleRows * kSampleRows;
+      if (s_tot < kSampleRows) s_tot = kSampleRows;
+      if (s_tot > 64 * kSampleRows) s_tot = 64 * kSampleRows;
+      p.P0 = (int)std::min<long>(8, (s_tot + 4 * kSampleRows - 1) / (4 * kSampleRows));
+    }
+    p.sample_rows = (int)(s_tot / p.P0);   // at most 8192: the histogram counts are 16 bits wide
     long chunks = (512 + problems - 1) / problems;
     const long max_chunks = (ncand + 2047) / 2048;
     if (chunks > max_chunks) chunks = max_chunks;
