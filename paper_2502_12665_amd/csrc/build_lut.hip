@@ -118,7 +118,7 @@ __device__ __forceinline__ void build_lut_body(
 
   // --- table entries in float64
   double val[EPT][kHeadsPerGroup];
-  float mx[kHeadsPerGroup] = {0.f, 0.f, 0.f, 0.f};
+  double mxd[kHeadsPerGroup] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
   for (int k = 0; k < EPT; ++k) {
 #pragma unroll
@@ -127,10 +127,15 @@ __device__ __forceinline__ void build_lut_body(
 #pragma unroll
       for (int t = 0; t < DS; ++t) acc += (double)s_q[r][m * DS + t] * (double)cv[k][t];
       val[k][r] = acc;
-      // rounded away from zero, so the float maximum is never below the true one
-      mx[r] = fmaxf(mx[r], __double2float_ru(fabs(acc)));
+      mxd[r] = fmax(mxd[r], fabs(acc));
     }
   }
+  // The thread's maximum as a float rounded up, so that it is never below the true one (rounding is
+  // monotone: the same number as the maximum of the rounded entries, with one change of the rounding
+  // mode per head instead of one per entry).
+  float mx[kHeadsPerGroup];
+#pragma unroll
+  for (int r = 0; r < kHeadsPerGroup; ++r) mx[r] = __double2float_ru(mxd[r]);
 
   // --- per-head power-of-two scale: M * max|entry| * 2^e < 2^30.  Non-negative floats order like
   // their bit patterns, so the block maximum is an integer atomic max in LDS (one per wave and head
@@ -254,29 +259,47 @@ __global__ __launch_bounds__(kLutThreads) void build_lut_shared_kernel(
   build_lut_body<DS, QBF16, true>(blockIdx.x, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, 1);
 }
 
+// An encoding workgroup of the prologues below: wave w takes the pairs (block * sweeps + s) * 16 + w.
+template <int DS>
+__device__ __forceinline__ void encode_few_block(int block, int sweeps, const float* __restrict__ keys,
+                                                 const float* __restrict__ codebook,
+                                                 const float* __restrict__ weights, int mode,
+                                                 uint8_t* __restrict__ codes, int B, int Hkv, int n_new, int pos0,
+                                                 int64_t ctx_stride) {
+  constexpr int M = 128 / DS;
+  static_assert(kLutThreads / 64 == kFewPairsPerSweep, "one pair per wave and sweep");
+  const long n_pairs = (long)B * Hkv * n_new * M;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int s = 0; s < sweeps; ++s) {
+    const long pair = ((long)block * sweeps + s) * kFewPairsPerSweep + wave;
+    if (pair < n_pairs)   // (uniform over the wave)
+      encode_few_wave<DS>(keys, codebook, weights, mode, codes, Hkv, M, n_new, pos0, ctx_stride, pair, lane);
+  }
+}
+
 // Decode prologue in one launch: the first n_lut workgroups build the tables of the current query,
-// the others encode the few keys appended this step, four (key, subspace) pairs per workgroup.
-// The two halves touch disjoint data.
+// the others encode the few keys appended this step, one (key, subspace) pair per wave and sweep.
+// The two halves touch disjoint data.  The kernel holds one workgroup per CU, so when the two kinds
+// together would not fit one round of the CUs the launch is "folded": no encoding workgroups, the
+// table workgroups share the pairs out among themselves.
 template <int DS, bool QBF16>
 __global__ __launch_bounds__(kLutThreads) void decode_prologue_kernel(
     const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
     const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
     float* __restrict__ lut_scale, int B, int Hq, int Hkv, int NG, int n_lut,
     const float* __restrict__ keys, const float* __restrict__ weights, int mode,
-    uint8_t* __restrict__ codes, int n_new, int pos0, int64_t ctx_stride) {
-  constexpr int M = 128 / DS;
+    uint8_t* __restrict__ codes, int n_new, int pos0, int64_t ctx_stride, int sweeps, int folded) {
   if ((int)blockIdx.x < n_lut) {
     build_lut_body<DS, QBF16>(blockIdx.x, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG);
+    // folded: the table workgroups encode as well, after their stores have been issued (their tail
+    // waits for those to drain anyway)
+    if (folded)
+      encode_few_block<DS>((int)blockIdx.x, sweeps, keys, codebook, weights, mode, codes, B, Hkv, n_new, pos0,
+                           ctx_stride);
     return;
   }
-  __shared__ double s_d[kLutThreads / 64];
-  __shared__ int s_i[kLutThreads / 64];
-  const int grp = threadIdx.x >> 8, c = threadIdx.x & 255;
-  const long pair = (long)(blockIdx.x - n_lut) * (kLutThreads / kCentroids) + grp;
-  const long n_pairs = (long)B * Hkv * n_new * M;
-  const int m = (int)(pair % M), j = (int)((pair / M) % n_new), bkv = (int)(pair / ((long)M * n_new));
-  encode_few_pair<DS>(keys, codebook, weights, mode, codes, Hkv, M, n_new, pos0, ctx_stride, m, j, bkv, c,
-                      grp, pair < n_pairs, s_d, s_i);
+  encode_few_block<DS>((int)blockIdx.x - n_lut, sweeps, keys, codebook, weights, mode, codes, B, Hkv, n_new, pos0,
+                       ctx_stride);
 }
 
 // The decode prologue and the first launch of a2ats_score_topk's streaming route in one: every
@@ -293,7 +316,7 @@ __global__ __launch_bounds__(kLutThreads) void decode_select_prologue_kernel(
     const float* __restrict__ keys, const float* __restrict__ weights, int mode,
     uint8_t* __restrict__ codes, int n_new, int pos0, int64_t ctx_stride,
     const int32_t* __restrict__ seq_lens, int32_t* __restrict__ thr, int P0, int sample_rows, int ctx_len,
-    int top_k, int window, int n_sink) {
+    int top_k, int window, int n_sink, int sweeps) {
   constexpr int M = 128 / DS;
   extern __shared__ __align__(16) unsigned char dyn_lds[];
   if ((int)blockIdx.x < n_sample) {
@@ -306,14 +329,8 @@ __global__ __launch_bounds__(kLutThreads) void decode_select_prologue_kernel(
                                                 ctx_len, ctx_stride, top_k, window, n_sink, dyn_lds);
     return;
   }
-  __shared__ double s_d[kLutThreads / 64];
-  __shared__ int s_i[kLutThreads / 64];
-  const int grp = threadIdx.x >> 8, c = threadIdx.x & 255;
-  const long pair = (long)(blockIdx.x - n_sample) * (kLutThreads / kCentroids) + grp;
-  const long n_pairs = (long)B * Hkv * n_new * M;
-  const int m = (int)(pair % M), j = (int)((pair / M) % n_new), bkv = (int)(pair / ((long)M * n_new));
-  encode_few_pair<DS>(keys, codebook, weights, mode, codes, Hkv, M, n_new, pos0, ctx_stride, m, j, bkv, c,
-                      grp, pair < n_pairs, s_d, s_i);
+  encode_few_block<DS>((int)blockIdx.x - n_sample, sweeps, keys, codebook, weights, mode, codes, B, Hkv, n_new, pos0,
+                       ctx_stride);
 }
 
 hipError_t launch_decode_select_prologue(const a2ats_dims& d, const float* keys, int n_new, int pos0,
@@ -326,7 +343,8 @@ hipError_t launch_decode_select_prologue(const a2ats_dims& d, const float* keys,
   const int NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
   const int n_sample = d.batch * d.n_kv_heads * NG * P0;
   const long n_pairs = (long)d.batch * d.n_kv_heads * n_new * d.n_sub;
-  const int per_wg = kLutThreads / kCentroids;
+  const int sweeps = encode_few_sweeps(n_pairs);
+  const long per_wg = (long)kFewPairsPerSweep * sweeps;
   const dim3 grid(n_sample + (unsigned)((n_pairs + per_wg - 1) / per_wg)), block(kLutThreads);
   if (grid.x == 0) return hipSuccess;
   static LdsSlot s_lds[4][16];
@@ -339,7 +357,7 @@ hipError_t launch_decode_select_prologue(const a2ats_dims& d, const float* keys,
     hipLaunchKernelGGL((decode_select_prologue_kernel<DS, BF>), grid, block, kCoarseLdsBytes, stream, q, cos_b, \
                        sin_b, codebook, q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG, n_sample, \
                        keys, weights, mode, codes, n_new, pos0, d.ctx_stride, seq_lens, thr, P0, sample_rows,  \
-                       d.ctx_len, top_k, window, n_sink);                                                    \
+                       d.ctx_len, top_k, window, n_sink, sweeps);                                            \
   } while (0)
   if (d.sub_dim == 8) {
     if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_SEL(8, true, 0); else A2ATS_LAUNCH_SEL(8, false, 1);
@@ -394,13 +412,19 @@ hipError_t launch_decode_prologue(const a2ats_dims& d, const float* keys, int n_
   const int NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
   const int n_lut = d.batch * d.n_kv_heads * NG;
   const long n_pairs = (long)d.batch * d.n_kv_heads * n_new * d.n_sub;
-  const int per_wg = kLutThreads / kCentroids;
-  const dim3 grid(n_lut + (unsigned)((n_pairs + per_wg - 1) / per_wg)), block(kLutThreads);
+  int sweeps = encode_few_sweeps(n_pairs);
+  long n_enc = (n_pairs + (long)kFewPairsPerSweep * sweeps - 1) / ((long)kFewPairsPerSweep * sweeps);
+  const int folded = n_lut > 0 && n_lut + n_enc > 256;
+  if (folded) {
+    sweeps = (int)((n_pairs + (long)kFewPairsPerSweep * n_lut - 1) / ((long)kFewPairsPerSweep * n_lut));
+    n_enc = 0;
+  }
+  const dim3 grid(n_lut + (unsigned)n_enc), block(kLutThreads);
   if (grid.x == 0) return hipSuccess;
 #define A2ATS_LAUNCH_PRO(DS, BF)                                                                       \
   hipLaunchKernelGGL((decode_prologue_kernel<DS, BF>), grid, block, 0, stream, q, cos_b, sin_b, codebook, \
                      q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG, n_lut, keys, weights, \
-                     mode, codes, n_new, pos0, d.ctx_stride)
+                     mode, codes, n_new, pos0, d.ctx_stride, sweeps, folded)
   if (d.sub_dim == 8) {
     if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_PRO(8, true); else A2ATS_LAUNCH_PRO(8, false);
   } else {

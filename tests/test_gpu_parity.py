@@ -468,6 +468,42 @@ def test_decode_prologue_equals_the_two_calls(name, n_new, mode):
     assert not torch.equal(res[0][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the rows were rewritten
 
 
+@pytest.mark.parametrize("name,Bn,Hkv,M,n_new,mode", [
+    ("many_pairs_several_sweeps", 8, 8, 16, 32, "diag"),     # 32768 pairs: 128 encoding workgroups of 16 sweeps
+    ("folded_two_sweeps", 40, 8, 16, 2, "block"),            # 320 table workgroups: they encode as well, 2 pairs a wave
+    ("folded_m32_ragged_share", 33, 8, 32, 3, "none"),       # 264 table workgroups, 25344 pairs: the last ones idle
+])
+def test_decode_prologue_launch_shapes(name, Bn, Hkv, M, n_new, mode):
+    """The prologue's ways of sharing out the append-time encoding (one pair per wave and sweep in
+    workgroups of their own, or, when those would not fit beside the table workgroups, in the table
+    workgroups themselves) write bit for bit what a2ats_encode_keys and a2ats_build_lut write."""
+    wl = synth.Workload(name, Bn, Hkv, Hkv, 128, M, 2048, 64, 32, seed=83)
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    hm = synth.make_query_second_moment(wl)
+    wmode = {"none": B.W_NONE, "diag": B.W_DIAG, "block": B.W_BLOCK}[mode]
+    weights = None if mode == "none" else hm["h_diag" if mode == "diag" else "h_block"].cuda()
+    keys = synth.make_encode_keys(wl, n_new, device="cuda", stress=True)
+    dims = H.dims_of(wl)
+    pos0 = wl.ctx_len - n_new
+    res = []
+    for fused in (False, True):
+        st = B.DecodeState(dims, wl.top_k, wl.window, 0, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+        st.lut.fill_(-1)
+        codes = xd["codes"].clone()
+        if fused:
+            B.decode_prologue(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, xd["q"],
+                              st.cos_b, st.sin_b, st.q_rot, st.lut, st.lut_scale)
+        else:
+            ws = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+            B.encode_keys(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, ws)
+            B.build_lut(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, st.lut, st.lut_scale)
+        torch.cuda.synchronize()
+        res.append((codes.cpu(), st.lut.cpu(), st.lut_scale.cpu(), st.q_rot.cpu()))
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+    assert not torch.equal(res[0][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the rows were rewritten
+
+
 @pytest.mark.parametrize("name,Bn,G,M,N,K,w,n_sink,n_new,mode,seq_lens", [
     ("sel_m16_g4", 2, 4, 16, 40000, 600, 128, 0, 1, "diag", None),
     ("sel_m16_g4_ragged", 4, 4, 16, 24000, 512, 64, 4, 2, "block", [24000, 17001, 300, 0]),
