@@ -158,12 +158,15 @@ __device__ __forceinline__ void sample_threshold_body(
   // would fetch eight times the bytes it uses.  (For rows drawn independently, as in the synthetic
   // workloads, this changes nothing statistically; if neighbouring tokens' scores are correlated
   // the estimate is noisier, which costs at most a detour over the exact route.)
+  // (run * ncand / n_runs in 32-bit pieces: with ncand = qn * n_runs + rn it is run * qn + run * rn /
+  // n_runs, and run * rn < n_runs^2 <= 2^29; a 64-bit division is ~150 instructions per row)
   constexpr int kRun = 128 / M;
-  const long n_runs = (s_all + kRun - 1) / kRun;
+  const uint32_t n_runs = (uint32_t)((s_all + kRun - 1) / kRun);
+  const uint32_t qn = (uint32_t)sr.ncand / n_runs, rn = (uint32_t)sr.ncand - qn * n_runs;
   for (int i = tid; i < s_p; i += NT) {
-    const long g = (long)p * s_p + i;
-    const long run = g / kRun;
-    int j = sr.sink_end + (int)((run * sr.ncand) / n_runs);
+    const uint32_t g = (uint32_t)p * (uint32_t)s_p + (uint32_t)i;
+    const uint32_t run = g / kRun;
+    int j = sr.sink_end + (int)(run * qn + (run * rn) / n_runs);
     j = max(sr.sink_end, j & ~(kRun - 1)) + (int)(g % kRun);
     j = min(j, sr.win_start - 1);
     uint4 w[M / 16];
