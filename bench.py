@@ -457,26 +457,28 @@ def group_shared_step(args, torch, B, synth, wl):
     kev = HipEvents(args.steps)
 
     def step(i, timed):
+        # the steps timed for `value` make two calls (a2ats_decode_select_shared: append, shared tables and
+        # threshold sampling in one launch, then the streaming and final kernels; a2ats_sparse_attn_shared);
+        # the steps with events between the phases make the four separate calls
         x = reps[i % R]
-        if timed:
-            ev[i][0].record()
+        if not timed:
+            B.decode_select_shared(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], x["q"],
+                                   st.cos_b, st.sin_b, st.q_rot, sk.lut, sk.lut_scale, K, w, wl.n_sink, None,
+                                   sk.topk_idx, sk.topk_count, None, sk.ws)
+            B.sparse_attn_shared(dims, x["q"], st.q_rot, x["k"], x["v"], sk.topk_idx, sk.topk_count, K, w,
+                                 wl.n_sink, st.cos_win, st.sin_win, None, st.out, st.ws)
+            return
+        ev[i][0].record()
         B.encode_keys(dims, x["new_key"], 1, N - 1, x["codebook"], h_diag, B.W_DIAG, x["codes"], st.ws)
-        if timed:
-            ev[i][1].record()
+        ev[i][1].record()
         B.build_lut_shared(dims, x["q"], st.cos_b, st.sin_b, x["codebook"], st.q_rot, sk.lut, sk.lut_scale)
-        if timed:
-            ev[i][2].record()
-            B.score_topk_profiled(dims_kv, x["codes"], sk.lut, sk.lut_scale, K, w, wl.n_sink, None, sk.topk_idx,
-                                  sk.topk_count, None, None, sk.ws, *kev.pair(i))
-        else:
-            B.score_topk(dims_kv, x["codes"], sk.lut, sk.lut_scale, K, w, wl.n_sink, None, sk.topk_idx,
-                         sk.topk_count, None, None, sk.ws)
-        if timed:
-            ev[i][3].record()
+        ev[i][2].record()
+        B.score_topk_profiled(dims_kv, x["codes"], sk.lut, sk.lut_scale, K, w, wl.n_sink, None, sk.topk_idx,
+                              sk.topk_count, None, None, sk.ws, *kev.pair(i))
+        ev[i][3].record()
         B.sparse_attn_shared(dims, x["q"], st.q_rot, x["k"], x["v"], sk.topk_idx, sk.topk_count, K, w, wl.n_sink,
                              st.cos_win, st.sin_win, None, st.out, st.ws)
-        if timed:
-            ev[i][4].record()
+        ev[i][4].record()
 
     for i in range(args.warmup):
         step(i, False)
@@ -509,7 +511,11 @@ def group_shared_step(args, torch, B, synth, wl):
                    "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": D, "n_sub": M, "ctx_len": N, "top_k": K,
                    "window": w, "replicas_cycled": R},
         "us_per_decode_step": ms * 1e3,
-        "phase_us_median": {"encode_1key": ph[0], "wrope_shared_lut": ph[1], "score_topk": ph[2], "sparse_attn": ph[3]},
+        "calls_per_step": "decode_select_shared (append, shared tables and threshold sampling in one launch, then the "
+                          "streaming and final kernels), sparse_attn_shared",
+        "phase_us_median": {"encode_1key": ph[0], "wrope_shared_lut": ph[1], "score_topk": ph[2], "sparse_attn": ph[3],
+                            "note": "from steps made of encode_keys + build_lut_shared + score_topk + "
+                                    "sparse_attn_shared with events between"},
         "sparse_attn_phase": {"algorithmic_bytes": attn_bytes, "GBps": attn_bytes / (ph[3] * 1e-6) / 1e9},
         "roofline": {"kernel": "stream_select_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,

@@ -354,7 +354,17 @@ int a2ats_sparse_attn_host(const a2ats_dims* dims, const void* q, const float* q
  *                            topk_idx [B*Hkv*top_k], topk_count [B*Hkv].
  *   a2ats_sparse_attn_shared as a2ats_sparse_attn with the real dims, topk_idx / topk_count per KV
  *                            head as above; workspace as A2ATS_OP_ATTN.
- * Both quantiser geometries.
+ *   a2ats_decode_select_shared  a2ats_encode_keys (the append of up to 32 keys per sequence and KV head)
+ *                            + a2ats_build_lut_shared + a2ats_score_topk with those dims, as one call
+ *                            (what a2ats_decode_select is for the per-head selection: on the streaming
+ *                            route, with at most 256 sampling workgroups = batch * n_kv_heads * sampling
+ *                            parts and pos0 >= ctx_len - window, one launch does the append, the
+ *                            tables and the threshold sampling; elsewhere the three launches follow
+ *                            each other).  `dims` are the real ones; lut, lut_scale, topk_* and `ws`
+ *                            (a2ats_workspace_bytes(.., A2ATS_OP_SCORE_TOPK, ..)) are those of dims with
+ *                            n_q_heads = n_kv_heads.  Every output is bit for bit what the three calls
+ *                            write.  Product quantisation only (A2ATS_ERR_UNSUPPORTED otherwise).
+ * The other three serve both quantiser geometries.
  */
 int a2ats_build_lut_shared(const a2ats_dims* dims, const void* q, int q_dtype, const float* cos_b,
                            const float* sin_b, const float* codebook, float* q_rot, int32_t* lut,
@@ -365,6 +375,13 @@ int a2ats_sparse_attn_shared(const a2ats_dims* dims, const void* q, const float*
                              int32_t window, int32_t n_sink, const float* cos_win,
                              const float* sin_win, const int32_t* seq_lens, void* out, void* ws,
                              size_t ws_bytes, void* stream);
+int a2ats_decode_select_shared(const a2ats_dims* dims, const float* keys, int32_t n_new, int32_t pos0,
+                               const float* codebook, const float* weights, int weight_mode,
+                               uint8_t* codes, const void* q, int q_dtype, const float* cos_b,
+                               const float* sin_b, float* q_rot, int32_t* lut, float* lut_scale,
+                               int32_t top_k, int32_t window, int32_t n_sink, const int32_t* seq_lens,
+                               int32_t* topk_idx, int32_t* topk_count, float* topk_score, void* ws,
+                               size_t ws_bytes, void* stream);
 
 /*
  * Offline codebook construction (paper section 4.2).

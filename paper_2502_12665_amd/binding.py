@@ -23,6 +23,7 @@ EXPORTS = ["a2ats_version", "a2ats_status_string", "a2ats_lut_elems", "a2ats_wor
            "a2ats_rope_tables", "a2ats_encode_keys", "a2ats_build_lut", "a2ats_score_topk",
            "a2ats_sparse_attn", "a2ats_score_topk_stats", "a2ats_score_topk_plan", "a2ats_score_topk_profiled",
            "a2ats_decode_prologue", "a2ats_decode_select", "a2ats_build_lut_shared", "a2ats_sparse_attn_shared",
+           "a2ats_decode_select_shared",
            "a2ats_second_moment", "a2ats_codebook_update", "a2ats_kmeanspp_seed", "a2ats_sparse_attn_paged",
            "a2ats_sparse_attn_static", "a2ats_score_topk_paged", "a2ats_codes_to_pages",
            "a2ats_sparse_attn_host"]
@@ -74,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.a2ats_decode_select.restype = ctypes.c_int
         L.a2ats_decode_select.argtypes = [dp, vp, i32, i32, vp, vp, ctypes.c_int, vp, vp, ctypes.c_int, vp, vp, vp,
                                           vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.a2ats_decode_select_shared.restype = ctypes.c_int
+        L.a2ats_decode_select_shared.argtypes = L.a2ats_decode_select.argtypes
         L.a2ats_score_topk.restype = ctypes.c_int
         L.a2ats_score_topk.argtypes = [dp, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.a2ats_sparse_attn.restype = ctypes.c_int
@@ -223,6 +226,20 @@ def decode_select(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, we
                                    _ptr(topk_idx), _ptr(topk_count), _ptr(topk_score), _ptr(ws),
                                    0 if ws is None else ws.numel() * ws.element_size(), _stream())
     _check(rc, "a2ats_decode_select")
+
+
+def decode_select_shared(dims: Dims, keys, n_new: int, pos0: int, codebook, weights, weight_mode: int, codes,
+                         q, cos_b, sin_b, q_rot, lut, lut_scale, top_k: int, window: int, n_sink: int, seq_lens,
+                         topk_idx, topk_count, topk_score=None, ws: Optional[torch.Tensor] = None):
+    """encode_keys + build_lut_shared + score_topk (one selection per KV head) as one call; `dims` are the
+    real ones, lut / lut_scale / topk_* / ws those of dims with n_q_heads = n_kv_heads."""
+    rc = lib().a2ats_decode_select_shared(ctypes.byref(dims), _ptr(keys), n_new, pos0, _ptr(codebook),
+                                          _ptr(weights), weight_mode, _ptr(codes), _ptr(q), _dtype_code(q),
+                                          _ptr(cos_b), _ptr(sin_b), _ptr(q_rot), _ptr(lut), _ptr(lut_scale), top_k,
+                                          window, n_sink, _ptr(seq_lens), _ptr(topk_idx), _ptr(topk_count),
+                                          _ptr(topk_score), _ptr(ws),
+                                          0 if ws is None else ws.numel() * ws.element_size(), _stream())
+    _check(rc, "a2ats_decode_select_shared")
 
 
 def score_topk(dims: Dims, codes, lut, lut_scale, top_k: int, window: int, n_sink: int, seq_lens,

@@ -327,9 +327,62 @@ int a2ats_decode_select(const a2ats_dims* d, const float* keys, int32_t n_new, i
   hipError_t e = a2ats::launch_decode_select_prologue(
       *d, keys, n_new, pos0, codebook, weights, weight_mode, codes, q, q_dtype, cos_b, sin_b, q_rot, lut, lut_scale,
       seq_lens, (int32_t*)((unsigned char*)ws + plan.off_thr), plan.P0, plan.sample_rows, top_k, window, n_sink,
-      (hipStream_t)stream);
+      false, (hipStream_t)stream);
   if (e != hipSuccess) return A2ATS_ERR_HIP;
   e = a2ats::launch_score_topk(*d, codes, a2ats::CodePages{nullptr, 0, 0}, lut, lut_scale, top_k, window, n_sink,
+                               seq_lens, topk_idx, topk_count, topk_score, nullptr, ws, true, (hipStream_t)stream);
+  return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+}
+
+int a2ats_decode_select_shared(const a2ats_dims* d, const float* keys, int32_t n_new, int32_t pos0,
+                               const float* codebook, const float* weights, int weight_mode, uint8_t* codes,
+                               const void* q, int q_dtype, const float* cos_b, const float* sin_b, float* q_rot,
+                               int32_t* lut, float* lut_scale, int32_t top_k, int32_t window, int32_t n_sink,
+                               const int32_t* seq_lens, int32_t* topk_idx, int32_t* topk_count,
+                               float* topk_score, void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_dims(d);
+  if (rc != A2ATS_OK) return rc;
+  if (a2ats::single_codebook(*d)) return A2ATS_ERR_UNSUPPORTED;
+  if (top_k < 0 || window < 0 || n_sink < 0) return A2ATS_ERR_INVALID_ARG;
+  if (top_k > 4096) return A2ATS_ERR_UNSUPPORTED;
+  if (n_new < 0 || pos0 < 0 || (int64_t)pos0 + n_new > d->ctx_stride) return A2ATS_ERR_INVALID_ARG;
+  if (n_new > 32) return A2ATS_ERR_UNSUPPORTED;
+  const int mode = weight_mode & ~A2ATS_W_PREPARED;
+  if (mode != A2ATS_W_NONE && mode != A2ATS_W_DIAG && mode != A2ATS_W_BLOCK) return A2ATS_ERR_INVALID_ARG;
+  if (q_dtype != A2ATS_F32 && q_dtype != A2ATS_BF16) return A2ATS_ERR_INVALID_ARG;
+  if (!codebook || !q || !cos_b || !sin_b || !q_rot || !lut || !lut_scale || !codes || !topk_count ||
+      (top_k > 0 && !topk_idx))
+    return A2ATS_ERR_INVALID_ARG;
+  if (n_new > 0 && !keys) return A2ATS_ERR_INVALID_ARG;
+  if (mode != A2ATS_W_NONE && !weights) return A2ATS_ERR_INVALID_ARG;
+  if (misaligned16(codebook) || misaligned16(lut) || misaligned16(codes) || (n_new > 0 && misaligned16(keys)))
+    return A2ATS_ERR_INVALID_ARG;
+  a2ats_dims dk = *d;   // the score/top-K side sees one table head per KV head
+  dk.n_q_heads = d->n_kv_heads;
+  const a2ats::TopkPlan plan = a2ats::make_topk_plan(dk, top_k, window, n_sink);
+  if (plan.fast && (!ws || misaligned16(ws) || ws_bytes < plan.bytes)) return A2ATS_ERR_WORKSPACE;
+  const long n_sample = (long)d->batch * d->n_kv_heads * plan.P0;
+  const bool appended_rows_compete = n_new > 0 && (int64_t)pos0 < (int64_t)d->ctx_len - window;
+  hipError_t e;
+  if (!plan.fast || n_sample > 256 || appended_rows_compete) {   // the three launches one after the other
+    // (at most 32 keys per sequence: the append-time encoder, which needs no workspace)
+    if ((e = a2ats::launch_encode(*d, keys, n_new, pos0, codebook, weights, mode, codes, nullptr,
+                                  (hipStream_t)stream)) != hipSuccess)
+      return A2ATS_ERR_HIP;
+    if ((e = a2ats::launch_build_lut_shared(*d, q, q_dtype, cos_b, sin_b, codebook, q_rot, lut, lut_scale,
+                                            (hipStream_t)stream)) != hipSuccess)
+      return A2ATS_ERR_HIP;
+    e = a2ats::launch_score_topk(dk, codes, a2ats::CodePages{nullptr, 0, 0}, lut, lut_scale, top_k, window, n_sink,
+                                 seq_lens, topk_idx, topk_count, topk_score, nullptr, ws, false,
+                                 (hipStream_t)stream);
+    return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
+  }
+  e = a2ats::launch_decode_select_prologue(*d, keys, n_new, pos0, codebook, weights, mode, codes, q, q_dtype, cos_b,
+                                           sin_b, q_rot, lut, lut_scale, seq_lens,
+                                           (int32_t*)((unsigned char*)ws + plan.off_thr), plan.P0, plan.sample_rows,
+                                           top_k, window, n_sink, true, (hipStream_t)stream);
+  if (e != hipSuccess) return A2ATS_ERR_HIP;
+  e = a2ats::launch_score_topk(dk, codes, a2ats::CodePages{nullptr, 0, 0}, lut, lut_scale, top_k, window, n_sink,
                                seq_lens, topk_idx, topk_count, topk_score, nullptr, ws, true, (hipStream_t)stream);
   return e == hipSuccess ? A2ATS_OK : A2ATS_ERR_HIP;
 }

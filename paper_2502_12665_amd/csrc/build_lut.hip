@@ -308,7 +308,9 @@ __global__ __launch_bounds__(kLutThreads) void decode_prologue_kernel(
 // the sample against it; part 0 of a problem also writes the tables out for the launches that
 // follow.  The remaining workgroups encode the appended keys.  Saves one launch and the copy of the
 // table from global memory per step; every result is bit for bit that of the separate calls.
-template <int DS, bool QBF16>
+// SHARED: one table per KV head from the summed rotated queries of its heads (build_lut_body<.., true>);
+// the thresholds are then per KV head (NG is 1 and the sampling sees Hkv table heads).
+template <int DS, bool QBF16, bool SHARED>
 __global__ __launch_bounds__(kLutThreads) void decode_select_prologue_kernel(
     const void* __restrict__ q_in, const float* __restrict__ cos_b, const float* __restrict__ sin_b,
     const float* __restrict__ codebook, float* __restrict__ q_rot, int32_t* __restrict__ lut,
@@ -322,11 +324,12 @@ __global__ __launch_bounds__(kLutThreads) void decode_select_prologue_kernel(
   if ((int)blockIdx.x < n_sample) {
     int prob, p;
     xcd_map_sets(blockIdx.x, P0, n_sample / P0, NG, prob, p);
-    build_lut_body<DS, QBF16>(prob, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG, p == 0,
-                              dyn_lds);
+    build_lut_body<DS, QBF16, SHARED>(prob, q_in, cos_b, sin_b, codebook, q_rot, lut, lut_scale, B, Hq, Hkv, NG,
+                                      p == 0, dyn_lds);
     __syncthreads();
-    sample_threshold_body<M, kLutThreads, true>(prob, p, codes, CodePages{nullptr, 0, 0}, lut, seq_lens, thr, B, Hq, Hkv, NG, P0, sample_rows,
-                                                ctx_len, ctx_stride, top_k, window, n_sink, dyn_lds);
+    sample_threshold_body<M, kLutThreads, true>(prob, p, codes, CodePages{nullptr, 0, 0}, lut, seq_lens, thr, B,
+                                                SHARED ? Hkv : Hq, Hkv, NG, P0, sample_rows, ctx_len, ctx_stride,
+                                                top_k, window, n_sink, dyn_lds);
     return;
   }
   encode_few_block<DS>((int)blockIdx.x - n_sample, sweeps, keys, codebook, weights, mode, codes, B, Hkv, n_new, pos0,
@@ -338,32 +341,38 @@ hipError_t launch_decode_select_prologue(const a2ats_dims& d, const float* keys,
                                          const void* q, int q_dtype, const float* cos_b, const float* sin_b,
                                          float* q_rot, int32_t* lut, float* lut_scale, const int32_t* seq_lens,
                                          int32_t* thr, int P0, int sample_rows, int top_k, int window, int n_sink,
-                                         hipStream_t stream) {
+                                         bool shared, hipStream_t stream) {
   const int G = d.n_q_heads / d.n_kv_heads;
-  const int NG = (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
+  const int NG = shared ? 1 : (G + kHeadsPerGroup - 1) / kHeadsPerGroup;
   const int n_sample = d.batch * d.n_kv_heads * NG * P0;
   const long n_pairs = (long)d.batch * d.n_kv_heads * n_new * d.n_sub;
   const int sweeps = encode_few_sweeps(n_pairs);
   const long per_wg = (long)kFewPairsPerSweep * sweeps;
   const dim3 grid(n_sample + (unsigned)((n_pairs + per_wg - 1) / per_wg)), block(kLutThreads);
   if (grid.x == 0) return hipSuccess;
-  static LdsSlot s_lds[4][16];
+  static LdsSlot s_lds[8][16];
   hipError_t err;
-#define A2ATS_LAUNCH_SEL(DS, BF, SLOT)                                                                       \
+#define A2ATS_LAUNCH_SEL(DS, BF, SH, SLOT)                                                                   \
   do {                                                                                                       \
-    if ((err = allow_dynamic_lds(decode_select_prologue_kernel<DS, BF>, (size_t)kCoarseLdsBytes, s_lds[SLOT])) != \
-        hipSuccess)                                                                                          \
+    if ((err = allow_dynamic_lds(decode_select_prologue_kernel<DS, BF, SH>, (size_t)kCoarseLdsBytes,         \
+                                 s_lds[SLOT])) != hipSuccess)                                                \
       return err;                                                                                            \
-    hipLaunchKernelGGL((decode_select_prologue_kernel<DS, BF>), grid, block, kCoarseLdsBytes, stream, q, cos_b, \
-                       sin_b, codebook, q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG, n_sample, \
-                       keys, weights, mode, codes, n_new, pos0, d.ctx_stride, seq_lens, thr, P0, sample_rows,  \
-                       d.ctx_len, top_k, window, n_sink, sweeps);                                            \
+    hipLaunchKernelGGL((decode_select_prologue_kernel<DS, BF, SH>), grid, block, kCoarseLdsBytes, stream, q, \
+                       cos_b, sin_b, codebook, q_rot, lut, lut_scale, d.batch, d.n_q_heads, d.n_kv_heads, NG, \
+                       n_sample, keys, weights, mode, codes, n_new, pos0, d.ctx_stride, seq_lens, thr, P0,   \
+                       sample_rows, d.ctx_len, top_k, window, n_sink, sweeps);                               \
+  } while (0)
+#define A2ATS_LAUNCH_SEL2(DS, BF, SLOT)                                    \
+  do {                                                                     \
+    if (shared) A2ATS_LAUNCH_SEL(DS, BF, true, SLOT + 4);                  \
+    else A2ATS_LAUNCH_SEL(DS, BF, false, SLOT);                            \
   } while (0)
   if (d.sub_dim == 8) {
-    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_SEL(8, true, 0); else A2ATS_LAUNCH_SEL(8, false, 1);
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_SEL2(8, true, 0); else A2ATS_LAUNCH_SEL2(8, false, 1);
   } else {
-    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_SEL(4, true, 2); else A2ATS_LAUNCH_SEL(4, false, 3);
+    if (q_dtype == A2ATS_BF16) A2ATS_LAUNCH_SEL2(4, true, 2); else A2ATS_LAUNCH_SEL2(4, false, 3);
   }
+#undef A2ATS_LAUNCH_SEL2
 #undef A2ATS_LAUNCH_SEL
   return hipGetLastError();
 }

@@ -65,13 +65,15 @@ hipError_t launch_score_topk(const a2ats_dims& d, const uint8_t* codes, const Co
                              float* topk_score, float* scores_out, void* ws, bool presampled, hipStream_t stream,
                              hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 // Decode prologue (append-time encode + tables) and the threshold sampling of the streaming route in
-// one launch; launch_score_topk(..., presampled = true) then skips its sampling launch.
+// one launch; launch_score_topk(..., presampled = true) then skips its sampling launch.  shared: one table
+// and one set of thresholds per KV head (d has the real head counts; the score/top-K launches that follow
+// take dims with n_q_heads = n_kv_heads).
 hipError_t launch_decode_select_prologue(const a2ats_dims& d, const float* keys, int n_new, int pos0,
                                          const float* codebook, const float* weights, int mode, uint8_t* codes,
                                          const void* q, int q_dtype, const float* cos_b, const float* sin_b,
                                          float* q_rot, int32_t* lut, float* lut_scale, const int32_t* seq_lens,
                                          int32_t* thr, int P0, int sample_rows, int top_k, int window, int n_sink,
-                                         hipStream_t stream);
+                                         bool shared, hipStream_t stream);
 hipError_t launch_sparse_attn(const a2ats_dims& d, const void* q, const float* q_rot, const void* k_cache,
                               const void* v_cache, int kv_dtype, const int32_t* topk_idx,
                               const int32_t* topk_count, int top_k, int window, int n_sink,

@@ -173,6 +173,37 @@ def test_decode_select_checks_every_argument_before_launching(binding):
     assert call(big, ws_bytes=1024) == -3
 
 
+def test_decode_select_shared_checks_every_argument_before_launching(binding):
+    """a2ats_decode_select_shared validates the union of the arguments of the three calls it stands for before
+    anything is enqueued; the single codebook is not served."""
+    L = binding.lib()
+    null, one = ctypes.c_void_p(0), ctypes.c_void_p(16)
+
+    def call(d, top_k=2048, window=256, n_sink=0, codes=one, idx=one, cnt=one, ws=one, ws_bytes=1 << 40, n_new=1,
+             pos0=None, keys=one, mode=0):
+        pos0 = d.ctx_len - 1 if pos0 is None else pos0
+        return L.a2ats_decode_select_shared(ctypes.byref(d), keys, n_new, pos0, one, null, mode, codes, one, 0, one,
+                                            one, one, one, one, top_k, window, n_sink, null, idx, cnt, null, ws,
+                                            ws_bytes, null)
+    for d in (binding.make_dims(4, 32, 8, 128, 16, 131072), binding.make_dims(1, 4, 1, 128, 16, 4096)):
+        assert call(d, top_k=-1) == -1
+        assert call(d, window=-1) == -1
+        assert call(d, n_sink=-1) == -1
+        assert call(d, top_k=5000) == -2
+        assert call(d, codes=null) == -1
+        assert call(d, idx=null) == -1
+        assert call(d, cnt=null) == -1
+        assert call(d, n_new=33, pos0=0) == -2
+        assert call(d, keys=null) == -1
+        assert call(d, pos0=d.ctx_len) == -1
+        assert call(d, mode=binding.W_DIAG) == -1      # weights missing
+        assert call(d, mode=7) == -1
+    big = binding.make_dims(4, 32, 8, 128, 16, 131072)
+    assert call(big, ws=null, ws_bytes=0) == -3
+    assert call(big, ws_bytes=1024) == -3
+    assert call(binding.make_dims(2, 8, 2, 128, 1, 4096, n_centroids=4096)) == -2
+
+
 def test_validation_of_the_single_codebook_and_construction_calls(binding):
     """Argument checks of the entry points added for the paper's own geometry (one codebook of 4096,
     16-bit codes), the selection shared per KV head and the offline construction: all on the host,

@@ -557,6 +557,60 @@ def test_decode_select_equals_the_two_calls(name, Bn, G, M, N, K, w, n_sink, n_n
     assert int(res[1][5].max()) > 0
 
 
+@pytest.mark.parametrize("name,Bn,Hkv,G,M,N,K,w,n_sink,n_new,mode,seq_lens", [
+    ("shsel_m16_g4", 2, 2, 4, 16, 40000, 600, 128, 0, 1, "diag", None),
+    ("shsel_m32_g7_ragged", 2, 2, 7, 32, 20000, 500, 100, 4, 2, "block", [20000, 16500]),
+    ("shsel_m16_g8_batch", 4, 8, 8, 16, 33000, 2048, 256, 0, 1, "none", None),
+    ("shsel_many_problems", 40, 8, 2, 16, 20000, 256, 64, 0, 1, "diag", None),   # 320 sampling workgroups: three launches
+    ("shsel_exact_route", 2, 2, 4, 16, 3000, 64, 32, 0, 1, "diag", None),
+    ("shsel_window_0", 2, 2, 4, 16, 20000, 256, 0, 0, 1, "diag", None),          # the appended row is a candidate
+])
+def test_decode_select_shared_equals_the_three_calls(name, Bn, Hkv, G, M, N, K, w, n_sink, n_new, mode, seq_lens):
+    """a2ats_decode_select_shared (one selection per KV head: append-time encode, shared tables and threshold
+    sampling in one launch, then the streaming and final kernels) writes bit for bit what a2ats_encode_keys +
+    a2ats_build_lut_shared + a2ats_score_topk (dims with n_q_heads = n_kv_heads) write, and leaves the same
+    survivor statistics; also where it has to make the three launches one after the other."""
+    wl = synth.Workload(name, Bn, Hkv * G, Hkv, 128, M, N, K, w, n_sink=n_sink, seed=67)
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    hm = synth.make_query_second_moment(wl)
+    wmode = {"none": B.W_NONE, "diag": B.W_DIAG, "block": B.W_BLOCK}[mode]
+    weights = None if mode == "none" else hm["h_diag" if mode == "diag" else "h_block"].cuda()
+    keys = synth.make_encode_keys(wl, n_new, device="cuda", stress=True)
+    dims = H.dims_of(wl)
+    dims_kv = B.make_dims(Bn, Hkv, Hkv, 128, M, N)
+    pos0 = N - n_new
+    sl = None if seq_lens is None else torch.as_tensor(seq_lens, dtype=torch.int32, device="cuda")
+    res = []
+    for fused in (False, True):
+        st = B.DecodeState(dims, K, w, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+        sk = B.DecodeState(dims_kv, K, w, n_sink, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+        sk.lut.fill_(-1)
+        sk.ws.fill_(0x5a)
+        sk.topk_idx.fill_(-7)
+        st.q_rot.fill_(-3.0)
+        codes = xd["codes"].clone()
+        if fused:
+            B.decode_select_shared(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, xd["q"], st.cos_b,
+                                   st.sin_b, st.q_rot, sk.lut, sk.lut_scale, K, w, n_sink, sl, sk.topk_idx,
+                                   sk.topk_count, sk.topk_score, sk.ws)
+        else:
+            ws = torch.empty(max(B.workspace_bytes(dims, B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+            B.encode_keys(dims, keys, n_new, pos0, xd["codebook"], weights, wmode, codes, ws)
+            B.build_lut_shared(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, sk.lut, sk.lut_scale)
+            B.score_topk(dims_kv, codes, sk.lut, sk.lut_scale, K, w, n_sink, sl, sk.topk_idx, sk.topk_count,
+                         sk.topk_score, None, sk.ws)
+        stats = torch.empty(Bn, Hkv, dtype=torch.int32, device="cuda")
+        B.score_topk_stats(dims_kv, K, w, n_sink, sk.ws, stats)
+        torch.cuda.synchronize()
+        res.append((codes.cpu(), sk.lut.cpu(), sk.lut_scale.cpu(), st.q_rot.cpu(), sk.topk_idx.cpu(),
+                    sk.topk_count.cpu(), sk.topk_score.cpu(), stats.cpu()))
+    for i, (a, b) in enumerate(zip(*res)):
+        assert torch.equal(a, b), f"output {i} differs"
+    assert B.score_topk_plan(dims_kv, K, w, n_sink)["fast"] == (name != "shsel_exact_route")
+    assert int(res[1][5].max()) > 0
+    assert not torch.equal(res[1][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the appended rows were encoded
+
+
 @pytest.mark.parametrize("mode,n_new", [("none", 1), ("diag", 3), ("block", 8)])
 def test_single_codebook_decode_prologue_equals_the_two_calls(mode, n_new):
     """The fused prologue in the single-codebook geometry (the sweep of the few-key encoder, then the
