@@ -933,6 +933,41 @@ def _group_shared_step(wl, xd, n_sink=0, want_scores=True, seq_lens=None):
     return st, sk
 
 
+def test_shared_decode_step_in_a_hip_graph():
+    """The step with one selection per KV head as its two calls (a2ats_decode_select_shared,
+    a2ats_sparse_attn_shared), captured: every replay gives the eager result of the separate calls."""
+    wl = synth.Workload("graph_shared", 2, 8, 2, 128, 16, 30000, 900, 128, seed=9)
+    xd = H.to_dev(synth.make_decode_inputs(wl))
+    new_key = xd["k"][:, :, -1:, :].float().contiguous()
+    ws = torch.empty(max(B.workspace_bytes(H.dims_of(wl), B.OP_ENCODE), 16), dtype=torch.uint8, device="cuda")
+    B.encode_keys(H.dims_of(wl), new_key, 1, wl.ctx_len - 1, xd["codebook"], None, B.W_NONE, xd["codes"], ws)
+    st, sk = _group_shared_step(wl, xd, want_scores=False)   # eager reference (also warms the library)
+    ref = (sk.topk_idx.clone(), st.out.clone())
+
+    def step():
+        B.decode_select_shared(st.dims, new_key, 1, wl.ctx_len - 1, xd["codebook"], None, B.W_NONE, xd["codes"],
+                               xd["q"], st.cos_b, st.sin_b, st.q_rot, sk.lut, sk.lut_scale, wl.top_k, wl.window, 0,
+                               None, sk.topk_idx, sk.topk_count, None, sk.ws)
+        B.sparse_attn_shared(st.dims, xd["q"], st.q_rot, xd["k"], xd["v"], sk.topk_idx, sk.topk_count, wl.top_k,
+                             wl.window, 0, st.cos_win, st.sin_win, None, st.out, st.ws)
+    step()
+    torch.cuda.synchronize()
+    assert torch.equal(sk.topk_idx, ref[0]) and torch.equal(st.out.view(torch.int16), ref[1].view(torch.int16))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for it in range(4):
+        sk.topk_idx.fill_(-3)
+        st.out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(sk.topk_idx, ref[0]), f"replay {it}: top-K differs"
+        assert torch.equal(st.out.view(torch.int16), ref[1].view(torch.int16)), f"replay {it}: output differs"
+        junk = torch.randn(1 << 20, device="cuda").sum().item()   # eager work between replays
+        assert junk == junk
+
+
 @pytest.mark.parametrize("shape", [(2, 8, 2, 16, 9000, 300, 64), (1, 14, 2, 32, 5000, 64, 32),
                                    (2, 8, 2, 16, 40000, 512, 128), (1, 3, 3, 16, 700, 700, 16),
                                    (2, 8, 2, 1, 9000, 300, 64), (1, 7, 1, 1, 40000, 512, 128),
