@@ -143,6 +143,7 @@ __device__ __forceinline__ void sample_threshold_body(
     return;
   }
 
+  const int n_real = min(kHeadsPerGroup, G - g4 * kHeadsPerGroup);   // heads of this group that exist
   const LutLayout lay = lut_layout(B, Hq, Hkv, M);
   if (!TABLE_IN_LDS) load_coarse_table<M, NT>(lut, lay, prob, tbl);
   for (int i = tid; i < 2 * kHistBins; i += NT) (&s_hist[0][0])[i] = 0;
@@ -175,10 +176,12 @@ __device__ __forceinline__ void sample_threshold_body(
     for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(row + ((uint32_t)(qd * 16) ^ sw.row_swz));
     uint32_t a01, a23;
     score_coarse<M, false>(w, tbl, sw, a01, a23);
+    // (a head slot past the group's last head has an all-zero table: every row would land in the same
+    // bin, a thousand atomics on one address for a histogram nobody reads)
     atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);
-    atomicAdd(&s_hist[0][a01 >> 21], 1u << 16);
-    atomicAdd(&s_hist[1][(a23 & 0xffffu) >> 5], 1u);
-    atomicAdd(&s_hist[1][a23 >> 21], 1u << 16);
+    if (n_real > 1) atomicAdd(&s_hist[0][a01 >> 21], 1u << 16);
+    if (n_real > 2) atomicAdd(&s_hist[1][(a23 & 0xffffu) >> 5], 1u);
+    if (n_real > 3) atomicAdd(&s_hist[1][a23 >> 21], 1u << 16);
   }
   __syncthreads();
   // Rank search, one wave per head: lane l owns bins [32 l, 32 l + 32); a suffix scan over the
