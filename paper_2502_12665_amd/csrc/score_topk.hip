@@ -274,10 +274,24 @@ __device__ void exact_select_block(const SeqCodes& seq_codes,
 
   const int lo = sr.sink_end, hi = sr.win_start;
   uint32_t kth = 0, k_rem = (uint32_t)sr.kk;
+  // Radix digits are taken from key - key(lower bound of any score), so that the histogram bins
+  // spread over the occupied range instead of all keys sharing their leading bits.
+  const uint32_t k_lo = score_key(s_lo);
+  // Up to kKeep rows per thread (16384 candidates: every shape that takes this route for its length)
+  // are scored once and their relative keys kept in registers; the select levels and the emission
+  // then work on those instead of streaming and scoring the rows again (4 passes at 4096 tokens:
+  // 23 us).  Thread t owns rows lo + t + i NT, the order of the streaming loops below.
+  constexpr int kKeep = 16;
+  const bool resident = hi - lo <= kKeep * NT;   // (uniform)
+  uint32_t keys[kKeep];
+  if (resident) {
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+      const int j = lo + tid + i * NT;
+      keys[i] = j < hi ? score_key(score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw)) - k_lo : 0u;
+    }
+  }
   if (sr.kk < sr.ncand) {
-    // Radix digits are taken from key - key(lower bound of any score), so that the histogram bins
-    // spread over the occupied range instead of all keys sharing their leading bits.
-    const uint32_t k_lo = score_key(s_lo);
     int remaining = 32 - __clz(score_key(s_hi) - k_lo);   // significant bits of a relative key
     uint32_t prefix = 0, mask = 0;
 #pragma unroll 1
@@ -287,9 +301,15 @@ __device__ void exact_select_block(const SeqCodes& seq_codes,
       const uint32_t dmask = (1u << bits) - 1u;
       for (int i = tid; i < kHistBins; i += NT) L.hist[i] = 0;
       __syncthreads();
-      for (int j = lo + tid; j < hi; j += NT) {
-        const uint32_t key = score_key(score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw)) - k_lo;
-        if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
+      if (resident) {
+#pragma unroll
+        for (int i = 0; i < kKeep; ++i)
+          if (lo + tid + i * NT < hi && (keys[i] & mask) == prefix) atomicAdd(&L.hist[(keys[i] >> shift) & dmask], 1u);
+      } else {
+        for (int j = lo + tid; j < hi; j += NT) {
+          const uint32_t key = score_key(score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw)) - k_lo;
+          if ((key & mask) == prefix) atomicAdd(&L.hist[(key >> shift) & dmask], 1u);
+        }
       }
       __syncthreads();
       block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
@@ -306,13 +326,12 @@ __device__ void exact_select_block(const SeqCodes& seq_codes,
   // Ordered emission: keys above the K-th, plus the first k_rem positions that equal it.
   uint32_t eq_seen = 0, out_n = 0;
   const bool take_all = sr.kk >= sr.ncand;
-#pragma unroll 1
-  for (int base = lo; base < hi; base += NT) {
+  auto emit_round = [&](int base, bool have_key, uint32_t rel_key, bool& done) {
     const int j = base + tid;
     int32_t s = 0;
     uint32_t gt = 0, eq = 0;
     if (j < hi) {
-      s = score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw);
+      s = have_key ? key_score(rel_key + k_lo) : score_exact_row<M>(row_ptr<M>(seq_codes, j), tbl, sw);
       const uint32_t key = score_key(s);
       gt = take_all ? 1u : (key > kth ? 1u : 0u);
       eq = take_all ? 0u : (key == kth ? 1u : 0u);
@@ -328,7 +347,16 @@ __device__ void exact_select_block(const SeqCodes& seq_codes,
     }
     eq_seen += tot_eq;
     out_n += tot_sel;
-    if (out_n >= (uint32_t)sr.kk) break;
+    done = out_n >= (uint32_t)sr.kk;   // (uniform)
+  };
+  bool done = false;
+  if (resident) {
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i)
+      if (!done && lo + i * NT < hi) emit_round(lo + i * NT, true, keys[i], done);
+  } else {
+#pragma unroll 1
+    for (int base = lo; base < hi && !done; base += NT) emit_round(base, false, 0u, done);
   }
 }
 
