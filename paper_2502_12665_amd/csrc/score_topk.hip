@@ -55,26 +55,33 @@ TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) 
   p.cap = 8192;
   p.fast = !single_codebook(d) && ncand >= 16384 && top_k >= 1 && top_k <= 2048 && 4L * top_k <= ncand;
   if (p.fast) {
-    // Sample a sixteenth of the candidates, in units of kSampleRows, shared by at most 8
-    // workgroups: up to 8 * kSampleRows each workgroup scores kSampleRows rows, beyond that (very
-    // long contexts, where a small sample would put the 5-sigma threshold far too low and the
-    // survivor lists would outgrow the final kernel's LDS) each takes an eighth of the sample.
-    long s_tot = ncand / 16 / kSampleRows * kSampleRows;
+    // Sample an eighth of the candidates (at most 65536 rows; in units of 512 rows, at least
+    // kSampleRows), shared by at most 8 workgroups of at most 8192 rows each.  The survivors the
+    // streaming pass writes and the final kernel reads back shrink with the sample (1.95 K per head
+    // at a sixteenth, 1.6 K at an eighth), and sampled rows are cheap while few workgroups carry
+    // them: every sampling workgroup pays for a table copy (or, in the fused decode prologue, for
+    // the table build) whatever it samples.  So the number of parts is what keeps the sampling
+    // launch in one round of the 256 CUs beside the workgroups that encode a one-key append
+    // (batch * n_kv_heads * M / 16), with about 2048 rows per part where that leaves a choice; a
+    // batch whose problems alone exceed one round (the sampling is then a launch of its own) takes
+    // parts of up to 4096 rows.  Measured steps (one-key append, 1/16 in 1024-row parts before):
+    // batch 4 x 131072 tokens 82.4 -> 81.3 us, batch 16 x 32768 tokens 122.2 -> 117.6 us, batch 32 x
+    // 65536 tokens with 7 heads per KV head 390.7 -> 382.5 us.
+    long s_tot = ncand / 8 / 512 * 512;
     if (s_tot < kSampleRows) s_tot = kSampleRows;
     if (s_tot > 64 * kSampleRows) s_tot = 64 * kSampleRows;
-    p.P0 = (int)std::min<long>(8, s_tot / kSampleRows);
     const long problems = (long)d.batch * d.n_kv_heads * p.NG;
-    // Large batches (more sampling workgroups than fit one round of the CUs, so the sampling is a
-    // launch of its own anyway): an eighth of the candidates in workgroups of up to 4096 rows.  The
-    // survivors the streaming pass writes and the final kernel reads back (1.95 K per head at a
-    // sixteenth) are a quarter of the phase's HBM traffic there; the larger sample costs less than
-    // it saves only when its table copies are shared by more rows.
-    if (problems * p.P0 > 256) {
-      s_tot = ncand / 8 / kSampleRows * kSampleRows;
-      if (s_tot < kSampleRows) s_tot = kSampleRows;
-      if (s_tot > 64 * kSampleRows) s_tot = 64 * kSampleRows;
-      p.P0 = (int)std::min<long>(8, (s_tot + 4 * kSampleRows - 1) / (4 * kSampleRows));
-    }
+    const long enc = ((long)d.batch * d.n_kv_heads * d.n_sub + 15) / 16;
+    const long fit = problems > 0 ? (256 - enc) / problems : 8;   // parts per problem that fit one round
+    long parts;
+    if (fit >= 1) parts = std::min<long>(std::min<long>(8, fit), (s_tot + 2047) / 2048);
+    else parts = std::min<long>(8, (s_tot + 4095) / 4096);
+    if (parts < 1) parts = 1;
+    long rows = s_tot / parts / 512 * 512;
+    if (rows < 512) rows = 512;
+    if (rows > 8 * kSampleRows) rows = 8 * kSampleRows;
+    p.P0 = (int)parts;
+    s_tot = rows * parts;
     p.sample_rows = (int)(s_tot / p.P0);   // at most 8192: the histogram counts are 16 bits wide
     long chunks = (512 + problems - 1) / problems;
     const long max_chunks = (ncand + 2047) / 2048;
