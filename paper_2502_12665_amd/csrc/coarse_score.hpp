@@ -164,24 +164,36 @@ __device__ __forceinline__ void sample_threshold_body(
   constexpr int kRun = 128 / M;
   const uint32_t n_runs = (uint32_t)((s_all + kRun - 1) / kRun);
   const uint32_t qn = (uint32_t)sr.ncand / n_runs, rn = (uint32_t)sr.ncand - qn * n_runs;
-  for (int i = tid; i < s_p; i += NT) {
-    const uint32_t g = (uint32_t)p * (uint32_t)s_p + (uint32_t)i;
-    const uint32_t run = g / kRun;
-    int j = sr.sink_end + (int)(run * qn + (run * rn) / n_runs);
-    j = max(sr.sink_end, j & ~(kRun - 1)) + (int)(g % kRun);
-    j = min(j, sr.win_start - 1);
-    uint4 w[M / 16];
-    const uint8_t* row = row_ptr<M>(seq_codes, j);
+  // Two rows per thread and round, both requested before either is scored (the rows are cold; four at a
+  // time measured the same).
+  constexpr int kPair = 2;
+#pragma unroll 1
+  for (int i0 = tid; i0 < s_p; i0 += kPair * NT) {
+    uint4 w[kPair][M / 16];
 #pragma unroll
-    for (int qd = 0; qd < M / 16; ++qd) w[qd] = *(const uint4*)(row + ((uint32_t)(qd * 16) ^ sw.row_swz));
-    uint32_t a01, a23;
-    score_coarse<M, false>(w, tbl, sw, a01, a23);
-    // (a head slot past the group's last head has an all-zero table: every row would land in the same
-    // bin, a thousand atomics on one address for a histogram nobody reads)
-    atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);
-    if (n_real > 1) atomicAdd(&s_hist[0][a01 >> 21], 1u << 16);
-    if (n_real > 2) atomicAdd(&s_hist[1][(a23 & 0xffffu) >> 5], 1u);
-    if (n_real > 3) atomicAdd(&s_hist[1][a23 >> 21], 1u << 16);
+    for (int u = 0; u < kPair; ++u) {
+      const int i = min(i0 + u * NT, s_p - 1);   // (a slot past the end repeats the last row and is not counted)
+      const uint32_t g = (uint32_t)p * (uint32_t)s_p + (uint32_t)i;
+      const uint32_t run = g / kRun;
+      int j = sr.sink_end + (int)(run * qn + (run * rn) / n_runs);
+      j = max(sr.sink_end, j & ~(kRun - 1)) + (int)(g % kRun);
+      j = min(j, sr.win_start - 1);
+      const uint8_t* row = row_ptr<M>(seq_codes, j);
+#pragma unroll
+      for (int qd = 0; qd < M / 16; ++qd) w[u][qd] = *(const uint4*)(row + ((uint32_t)(qd * 16) ^ sw.row_swz));
+    }
+#pragma unroll
+    for (int u = 0; u < kPair; ++u) {
+      if (i0 + u * NT >= s_p) continue;
+      uint32_t a01, a23;
+      score_coarse<M, false>(w[u], tbl, sw, a01, a23);
+      // (a head slot past the group's last head has an all-zero table: every row would land in the same
+      // bin, a thousand atomics on one address for a histogram nobody reads)
+      atomicAdd(&s_hist[0][(a01 & 0xffffu) >> 5], 1u);
+      if (n_real > 1) atomicAdd(&s_hist[0][a01 >> 21], 1u << 16);
+      if (n_real > 2) atomicAdd(&s_hist[1][(a23 & 0xffffu) >> 5], 1u);
+      if (n_real > 3) atomicAdd(&s_hist[1][a23 >> 21], 1u << 16);
+    }
   }
   __syncthreads();
   // Rank search, one wave per head: lane l owns bins [32 l, 32 l + 32); a suffix scan over the
