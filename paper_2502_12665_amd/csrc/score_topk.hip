@@ -10,7 +10,7 @@
 //
 //  fast route (long contexts): the code matrix is streamed from HBM once, against a 16-bit
 //  coarse copy of the tables, and only the survivors are scored exactly.
-//    1. sample_threshold_kernel scores a sample of each sequence (about 1/16 of it, taken in
+//    1. sample_threshold_kernel scores a sample of each sequence (about 1/8 of it, taken in
 //       128-byte runs spread evenly over the candidates) with the coarse tables and derives, per
 //       head, a coarse threshold below the K-th score with a 5-sigma margin (distribution-free
 //       for independent rows: it only uses ranks of the sample).
@@ -19,7 +19,7 @@
 //       accumulates two heads).  A row whose coarse score reaches the threshold of any of the
 //       heads is written once -- a 4-byte header (position, wanting heads) and its code bytes --
 //       to the segment of its (problem, chunk, wave) in HBM, in row order.
-//    3. final_select_kernel (one workgroup per head) collects its head's survivors (about 1.7 K),
+//    3. final_select_kernel (one workgroup per head) collects its head's survivors (about 1.5 K),
 //       scores them exactly from the head's 32-bit table, radix-selects the exact K-th key among
 //       them, proves that no row outside the survivor list can reach that key (coarse and exact
 //       scores differ by less than M coarse units), and writes the winners in ascending
@@ -43,7 +43,7 @@ constexpr int kStreamThreads = 512;
 constexpr int kStreamWaves = kStreamThreads / 64;
 constexpr int kSampleThreads = 512;
 constexpr int kSegMeta = 8;          // words of a segment header: rows, 4 per-head counts, padding
-constexpr int kSampleRows = 1024;    // rows scored by one sampling workgroup
+constexpr int kSampleRows = 1024;    // smallest sample of a problem; a sampling workgroup scores up to 8 of these
 constexpr int kSmallList = 1024;     // members of the K-th key's bin ranked by brute force
 
 TopkPlan make_topk_plan(const a2ats_dims& d, int top_k, int window, int n_sink) {
