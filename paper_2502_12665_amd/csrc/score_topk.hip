@@ -253,11 +253,17 @@ __device__ __forceinline__ bool entry_wanted(uint32_t w0, int r) { return (w0 >>
 // ------------------------------------------------------------------------------------------
 // Exact route (also the fallback of the fast route)
 // ------------------------------------------------------------------------------------------
+constexpr int kKeepRows = 16;   // rows per thread the exact route keeps in registers (16384 candidates)
 struct ExactLds {
   uint32_t hist[kHistBins];
   uint32_t wave_a[kExactThreads / 64];
   uint32_t wave_b[kExactThreads / 64];
   uint32_t res[2];
+  // emission with resident keys: packed (above, equal) counts per round and wave, their exclusive
+  // prefixes over the waves of a round, and the rounds' totals
+  uint32_t round_wave[kKeepRows][kExactThreads / 64];
+  uint32_t round_pre[kKeepRows][kExactThreads / 64];
+  uint32_t round_tot[kKeepRows];
 };
 
 // Exact top-K for one head by the whole workgroup.  `head_table` is the head's [c][m] table in
@@ -288,7 +294,7 @@ __device__ void exact_select_block(const SeqCodes& seq_codes,
   // are scored once and their relative keys kept in registers; the select levels and the emission
   // then work on those instead of streaming and scoring the rows again (4 passes at 4096 tokens:
   // 23 us).  Thread t owns rows lo + t + i NT, the order of the streaming loops below.
-  constexpr int kKeep = 16;
+  constexpr int kKeep = kKeepRows;
   const bool resident = hi - lo <= kKeep * NT;   // (uniform)
   uint32_t keys[kKeep];
   if (resident) {
@@ -358,9 +364,58 @@ __device__ void exact_select_block(const SeqCodes& seq_codes,
   };
   bool done = false;
   if (resident) {
+    // All rounds at once: a wave scan of the packed (above, equal) flags per round, one scan over the
+    // waves of every round (16 lanes per round), then each thread places its winners -- two barriers
+    // instead of four per round.  A winner's slot is the number of keys above the K-th before it plus
+    // the number of equal keys before it that still fit (both counts grow with the position).
+    constexpr int NW = NT / 64;
+    static_assert(kKeep * NW <= NT && NW == 16, "one lane per (round, wave), 16 waves per round");
+    const int lane = tid & 63, wave = tid >> 6;
+    uint32_t flags = 0;        // bit 2 i: above the K-th key, bit 2 i + 1: equal to it
+    uint32_t pre[kKeep];
 #pragma unroll
-    for (int i = 0; i < kKeep; ++i)
-      if (!done && lo + i * NT < hi) emit_round(lo + i * NT, true, keys[i], done);
+    for (int i = 0; i < kKeep; ++i) {
+      uint32_t own = 0;
+      if (lo + tid + i * NT < hi) {
+        const uint32_t key = keys[i] + k_lo;
+        own = take_all ? 1u : (key > kth ? 1u : (key == kth ? 0x10000u : 0u));
+      }
+      flags |= ((own & 1u) | ((own >> 16) << 1)) << (2 * i);
+      const uint32_t v = wave_inclusive_scan(own);
+      pre[i] = v - own;
+      if (lane == 63) L.round_wave[i][wave] = v;
+    }
+    __syncthreads();
+    if (tid < kKeep * NW) {
+      const int i = tid / NW, w = tid % NW;
+      const uint32_t own = L.round_wave[i][w];
+      uint32_t v = own;
+#pragma unroll
+      for (int off = 1; off < NW; off <<= 1) {
+        const uint32_t n = __shfl_up(v, off, NW);
+        if (w >= off) v += n;
+      }
+      L.round_pre[i][w] = v - own;
+      if (w == NW - 1) L.round_tot[i] = v;
+    }
+    __syncthreads();
+    uint32_t gt_base = 0, eq_base = 0;
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+      const uint32_t f = (flags >> (2 * i)) & 3u;
+      if (f) {
+        const uint32_t p = pre[i] + L.round_pre[i][wave];
+        const uint32_t gt_before = gt_base + (p & 0xffffu), eq_before = eq_base + (p >> 16);
+        if ((f & 1u) || eq_before < k_rem) {
+          const uint32_t slot = gt_before + min(eq_before, k_rem);
+          out_idx[slot] = lo + tid + i * NT;
+          if (out_score) out_score[slot] = (float)key_score(keys[i] + k_lo) * scale;
+        }
+      }
+      const uint32_t tot = L.round_tot[i];
+      gt_base += tot & 0xffffu;
+      eq_base += tot >> 16;
+    }
   } else {
 #pragma unroll 1
     for (int base = lo; base < hi && !done; base += NT) emit_round(base, false, 0u, done);
