@@ -264,6 +264,9 @@ struct ExactLds {
   uint32_t round_wave[kKeepRows][kExactThreads / 64];
   uint32_t round_pre[kKeepRows][kExactThreads / 64];
   uint32_t round_tot[kKeepRows];
+  // the keys of the K-th key's bin after a select level, when they are few enough to rank by counting
+  uint32_t small_n;
+  uint32_t small_key[kSmallList];
 };
 
 // Exact top-K for one head by the whole workgroup.  `head_table` is the head's [c][m] table in
@@ -326,12 +329,40 @@ __device__ void exact_select_block(const SeqCodes& seq_codes,
       }
       __syncthreads();
       block_find_rank_desc<NT, kHistBins>([&](int i) { return L.hist[i]; }, k_rem, L.wave_a, L.res);
-      const uint32_t bin = L.res[0], above = L.res[1];
+      const uint32_t bin = L.res[0], above = L.res[1], m_bin = L.hist[bin];
       k_rem -= above;
       prefix |= bin << shift;
       mask |= dmask << shift;
       remaining = shift;
+      if (tid == 0) L.small_n = 0;
       __syncthreads();
+      if (resident && remaining > 0 && m_bin <= (uint32_t)kSmallList) {   // (uniform)
+        // The bin of the K-th key usually holds a handful of keys: they are listed and each member
+        // counts the members above and at its own key -- the member whose range contains k_rem is the
+        // K-th key.  (A crowded bin, heavy ties, goes on with the next radix level.)
+#pragma unroll
+        for (int i = 0; i < kKeep; ++i)
+          if (lo + tid + i * NT < hi && (keys[i] & mask) == prefix) L.small_key[atomicAdd(&L.small_n, 1u)] = keys[i];
+        __syncthreads();
+        if ((uint32_t)tid < m_bin) {
+          const uint32_t key = L.small_key[tid];
+          uint32_t gt = 0, eq = 0;
+          for (uint32_t u = 0; u < m_bin; ++u) {
+            const uint32_t ku = L.small_key[u];
+            gt += ku > key ? 1u : 0u;
+            eq += ku == key ? 1u : 0u;
+          }
+          if (gt < k_rem && k_rem <= gt + eq) {   // every member at the K-th key writes the same two words
+            L.res[0] = key;
+            L.res[1] = k_rem - gt;
+          }
+        }
+        __syncthreads();
+        prefix = L.res[0];
+        k_rem = L.res[1];
+        remaining = 0;
+        __syncthreads();   // L.res is rewritten by the caller's next use
+      }
     }
     kth = prefix + k_lo;
   }
