@@ -77,6 +77,34 @@ def test_fast_route_medium(oracle, name, G, M, N, K, w, n_sink, seq_lens, stride
     H.log(f"{name}: {res}")
 
 
+def test_random_shapes_whole_step(oracle):
+    """Twenty seeded random shapes of the whole decode step against the oracle: 1 to 8 query heads per KV
+    head, both subspace counts, contexts on either side of the exact / streaming boundary, any K up to a
+    quarter of the candidates, windows from 0 to 300, sinks, ragged lengths (empty and nearly full
+    sequences), padded strides, both cache types."""
+    import random
+    rng = random.Random(20260)
+    for it in range(20):
+        G = rng.choice([1, 2, 3, 4, 5, 7, 8])
+        M = rng.choice([16, 32])
+        Bn = rng.choice([1, 2, 3])
+        short = rng.random() < 0.35
+        N = rng.randint(300, 16000) if short else rng.randint(16500, 50000)
+        w = rng.choice([0, 1, 16, 64, 128, 300])
+        n_sink = rng.choice([0, 4, 17])
+        kmax = max(1, min(2048, N if short else (N - w - n_sink) // 4))
+        K = rng.choice([1, 7, 64, rng.randint(1, kmax), kmax])
+        lens = None
+        if rng.random() < 0.5:
+            lens = [N] + [rng.choice([0, rng.randint(1, N), N - 1]) for _ in range(Bn - 1)]
+        stride = N + rng.choice([0, 5, 64])
+        wl = synth.Workload(f"rnd{it}", Bn, 2 * G, 2, 128, M, N, K, w, n_sink=n_sink, seed=2000 + it,
+                            kv_dtype=rng.choice(["bf16", "f32"]))
+        H.log(f"case {it}: B{Bn} G{G} M{M} N{N} K{K} w{w} sinks {n_sink} lens {lens} stride {stride} {wl.kv_dtype}")
+        _, res = _run_and_check(oracle, wl, seq_lens=lens, ctx_stride=stride)
+        H.log(f"   {res}")
+
+
 def test_config2_llama8b_32k(oracle):
     wl = synth.WORKLOADS["c2_llama8b_32k"]
     H.log(wl.name)
