@@ -639,6 +639,31 @@ def test_decode_select_shared_equals_the_three_calls(name, Bn, Hkv, G, M, N, K, 
     assert not torch.equal(res[1][0][:, :, pos0:], xd["codes"][:, :, pos0:].cpu())   # the appended rows were encoded
 
 
+@pytest.mark.parametrize("shared", [False, True])
+def test_decode_select_without_an_append(shared):
+    """n_new = 0 (no key to append: keys may be NULL): the fused calls build the tables and select as the
+    separate calls do, and leave the code matrix alone."""
+    wl = synth.Workload("n0", 2, 8, 2, 128, 16, 30000, 500, 64, seed=3)
+    xd = synth.make_decode_inputs(wl, device="cuda", with_kv=False)
+    dims = H.dims_of(wl)
+    dsel = B.make_dims(2, 2, 2, 128, 16, 30000) if shared else dims
+    st = B.DecodeState(dims, 500, 64, 0, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+    got = B.DecodeState(dsel, 500, 64, 0, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+    ref = B.DecodeState(dsel, 500, 64, 0, xd["q"].dtype, xd["inv_freq"], wl.wrope_b)
+    codes = xd["codes"].clone()
+    fused = B.decode_select_shared if shared else B.decode_select
+    fused(dims, None, 0, 0, xd["codebook"], None, B.W_NONE, codes, xd["q"], st.cos_b, st.sin_b, st.q_rot, got.lut,
+          got.lut_scale, 500, 64, 0, None, got.topk_idx, got.topk_count, None, got.ws)
+    (B.build_lut_shared if shared else B.build_lut)(dims, xd["q"], st.cos_b, st.sin_b, xd["codebook"], st.q_rot, ref.lut,
+                                                    ref.lut_scale)
+    B.score_topk(dsel, codes, ref.lut, ref.lut_scale, 500, 64, 0, None, ref.topk_idx, ref.topk_count, None, None, ref.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(got.topk_idx, ref.topk_idx) and torch.equal(got.topk_count, ref.topk_count)
+    assert torch.equal(got.lut, ref.lut) and torch.equal(got.lut_scale, ref.lut_scale)
+    assert torch.equal(codes, xd["codes"])
+    assert int(got.topk_count.min()) == 500
+
+
 @pytest.mark.parametrize("mode,n_new", [("none", 1), ("diag", 3), ("block", 8)])
 def test_single_codebook_decode_prologue_equals_the_two_calls(mode, n_new):
     """The fused prologue in the single-codebook geometry (the sweep of the few-key encoder, then the
